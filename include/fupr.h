@@ -1,0 +1,277 @@
+/*
+ * fupr - inference of a filter-pruned residual network whose non-parametric
+ * operators have been folded into its convolutions, for AMD gfx950.
+ *
+ * The calls follow the paper's statement of the problem (Sec. IV-A): a
+ * pre-trained model plus user options (what to fuse, how many filters to
+ * prune) gives an optimised model, which is then run.
+ *
+ *   fupr_fold            batch norm as omega*x + lambda (Sec. IV-B-2, Eq. 3-5)
+ *                        merged into the convolution before it (Sec. VI-B-3)
+ *   fupr_select_filters  lowest-norm filters of a convolution (Sec. IV-C, Eq. 6)
+ *   fupr_prune_count     how many filters a non-fused operator loses (Alg. 1)
+ *   fupr_prune           removal of masked filters (Alg. 1, last step)
+ *   fupr_pack            weights -> device layout
+ *   fupr_conv_fused      convolution operator k x c x r x s (Sec. III, Sec. IV-B-1)
+ *                        with bias, element-wise addition and ReLU in its epilogue
+ *   fupr_maxpool, fupr_global_avgpool   the "Others" of Table II / Table VI
+ *   fupr_model_*, fupr_forward          a whole network (Table II) on one stream
+ *
+ * Conventions
+ *   - Host calls (fold, select, prune, pack, model create) take HOST pointers.
+ *     Device calls take DEVICE pointers, marked [dev] below.  The library never
+ *     allocates or frees device memory and never synchronises a stream unless
+ *     a call says so; device work is enqueued on the caller's stream
+ *     (a hipStream_t passed as void*, NULL = the default stream).
+ *   - Every call returns FUPR_OK (0) or a negative fupr_status.  On error no
+ *     output buffer has been written and nothing has been launched.
+ *   - Activations are NHWC.  A tensor of C channels has a channel stride
+ *     c_stride >= C (elements between consecutive pixels) that is a multiple of
+ *     8 for 16-bit types and of 4 for fp32; the lanes C..c_stride-1 of every
+ *     pixel hold zeros (callers provide inputs that way, kernels write outputs
+ *     that way).  Base pointers are 16-byte aligned.
+ *   - Convolutions are cross-correlations with zero padding, square stride and
+ *     padding; weights on the host are float32 in K x C x R x S order.
+ *   - Calls are re-entrant and thread-safe; they share no mutable state.
+ */
+#ifndef FUPR_H
+#define FUPR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t fupr_status;
+enum {
+  FUPR_OK = 0,
+  FUPR_ERR_NULL = -1,       /* a required pointer is NULL                              */
+  FUPR_ERR_SHAPE = -2,      /* sizes are non-positive or do not match each other       */
+  FUPR_ERR_DTYPE = -3,      /* unknown dtype, or tensors of one call differ in dtype   */
+  FUPR_ERR_MASK_EMPTY = -4, /* the mask keeps no filter                                */
+  FUPR_ERR_BN_VAR = -5,     /* var + eps is not a positive finite number               */
+  FUPR_ERR_WORKSPACE = -6,  /* workspace too small or misaligned                       */
+  FUPR_ERR_ALIGN = -7,      /* pointer or channel stride violates the alignment rules  */
+  FUPR_ERR_LAUNCH = -8,     /* the HIP runtime refused a launch, event or capture      */
+  FUPR_ERR_ARG = -9,        /* any other invalid argument (flags, norm, counts, ids)   */
+  FUPR_ERR_LIMIT = -10      /* a size exceeds what the kernels index with 32 bits      */
+};
+const char* fupr_status_str(fupr_status s); /* static string, never NULL */
+
+typedef enum { FUPR_F32 = 0, FUPR_BF16 = 1, FUPR_F16 = 2 } fupr_dtype;
+
+/* K filters, C input channels, R x S window, square stride and zero padding. */
+typedef struct {
+  int32_t K, C, R, S, stride, pad;
+} fupr_conv_shape;
+
+/* What fupr_fold merges / what the kernel epilogue applies. */
+enum { FUPR_FUSE_BN = 1, FUPR_FUSE_RELU = 2, FUPR_FUSE_ADD = 4 };
+
+/* ------------------------------------------------------------------ host -- */
+
+/*
+ * Batch norm merged into the preceding convolution (Sec. IV-B-2, Eq. 3-5;
+ * Sec. VI-B-3).  With FUPR_FUSE_BN in fuse_flags:
+ *     omega_k  = gamma_k / sqrt(var_k + eps)        lambda_k = beta_k - omega_k mean_k
+ *     W_out[k] = omega_k W[k]                        b_out[k] = lambda_k + omega_k conv_bias[k]
+ * computed in double, stored as float.  Without the flag W_out = W and
+ * b_out = conv_bias.  conv_bias may be NULL (taken as zeros).  gamma, beta,
+ * mean, var (K floats each) may be NULL only without FUPR_FUSE_BN.
+ * W_out (K*C*R*S) and b_out (K) are caller-allocated and may alias W / conv_bias.
+ * Errors: NULL, SHAPE, BN_VAR (var_k + eps <= 0 or not finite), ARG (unknown flag bits).
+ */
+fupr_status fupr_fold(const fupr_conv_shape* shape, const float* W, const float* conv_bias,
+                      const float* gamma, const float* beta, const float* mean, const float* var,
+                      float eps, uint32_t fuse_flags, float* W_out, float* b_out);
+
+/*
+ * Number of filters a non-fused operator with n filters loses at pruning rate
+ * permille/1000: floor(n * permille / 1000) in integer arithmetic, capped at
+ * n - 1 so that one filter always stays (Alg. 1).  Returns a negative status
+ * for n <= 0 or permille outside 0..1000.
+ */
+int32_t fupr_prune_count(int32_t n, int32_t permille);
+
+/*
+ * Filter importance (Sec. IV-C, Eq. 6): mask_out[k] = 0 for the n_prune filters
+ * of smallest l1 (norm = 1) or l2 (norm = 2) norm over their C*R*S weights,
+ * 1 for the others.  Norms are summed in double in (c, r, s) order; among
+ * equal norms the lower filter index is pruned first.  0 <= n_prune < K.
+ */
+fupr_status fupr_select_filters(const fupr_conv_shape* shape, const float* W, int32_t norm,
+                                int32_t n_prune, uint8_t* mask_out);
+
+/*
+ * Removal of masked filters (Alg. 1, last step).  mask has prod->K entries of
+ * 0/1.  Writes *K_keep, keep_idx[0..K_keep) (ascending filter indices kept),
+ * the producer's kept filters Wp_out (K_keep x C x R x S) and bias bp_out
+ * (K_keep; bp may be NULL, then bp_out may be NULL), and for each of the
+ * n_consumers convolutions that read the producer's output, its weights with
+ * the removed input channels dropped, Wc_out[i] (cons[i].K x K_keep x R x S).
+ * cons[i].C must equal prod->K.  All copies are exact.  Outputs are
+ * caller-allocated (sizing them for K_keep = prod->K is always enough) and must
+ * not alias inputs.
+ * Errors: NULL, SHAPE, MASK_EMPTY, ARG (mask entry not 0/1, n_consumers < 0).
+ */
+fupr_status fupr_prune(const fupr_conv_shape* prod, const float* Wp, const float* bp,
+                       const uint8_t* mask, int32_t n_consumers, const fupr_conv_shape* cons,
+                       const float* const* Wc, int32_t* K_keep, int32_t* keep_idx, float* Wp_out,
+                       float* bp_out, float* const* Wc_out);
+
+/*
+ * Device layout of one convolution's parameters: a blob of fupr_packed_bytes()
+ * bytes, to be uploaded to a 256-byte aligned device address.
+ *   16-bit types: [bias: Kp floats][weights: nchunk_pad x Kp x 8 elements]
+ *       Kp = K rounded up to 16, Cp = C rounded up to 8, chunk j = (r*S + s)*(Cp/8) + c/8
+ *       holds channels 8*(c/8)..+7 of tap (r, s); nchunk_pad = R*S*Cp/8 rounded up to 4.
+ *   fp32:         [bias: Kp floats][weights: R*S*Cp x Kp floats], Kp = K rounded up to 4,
+ *       Cp = C rounded up to 4, row (r*S + s)*Cp + c.
+ * Padding entries are zero.  16-bit values are rounded to nearest even.
+ * bias may be NULL (zeros).  Returns 0 bytes / an error for invalid shapes or dtypes.
+ */
+size_t fupr_packed_bytes(const fupr_conv_shape* shape, fupr_dtype dt);
+fupr_status fupr_pack(const fupr_conv_shape* shape, const float* W, const float* bias,
+                      fupr_dtype dt, void* blob_out);
+
+/* ---------------------------------------------------------------- device -- */
+
+/* An NHWC activation tensor in device memory. */
+typedef struct {
+  int32_t N, H, W, C, c_stride;
+  fupr_dtype dt;
+  void* ptr; /* [dev] */
+} fupr_tensor;
+
+/*
+ * The tensor added before the final ReLU (the building block's shortcut,
+ * Table II "add").  Output element (n, p, q, k) receives
+ *     t[n, p*spatial_stride, q*spatial_stride, k - c_offset]   if c_offset <= k < c_offset + t.C
+ *     0                                                         otherwise,
+ * which covers the identity shortcut (stride 1, offset 0, t.C = K), the
+ * parameter-free shortcut across a resolution change (stride 2, fewer
+ * channels), and a projection shortcut's output.  c_offset is a multiple of 4.
+ */
+typedef struct {
+  fupr_tensor t;
+  int32_t spatial_stride, c_offset;
+} fupr_residual;
+
+/*
+ * y[n,p,q,k] = act( b_k + sum_{r,s,c} x[n, p*stride+r-pad, q*stride+s-pad, c] W[k,c,r,s] (+ res) )
+ * (Sec. III; Sec. IV-B-1), accumulated in fp32; the residual is converted to
+ * fp32 and added after the bias; act is ReLU with FUPR_FUSE_RELU, else the
+ * identity; one rounding to y's type at the end.  FUPR_FUSE_ADD requires res.
+ * packed is [dev] the blob written by fupr_pack for the same shape and dtype.
+ * x, y (and res) share one dtype; y->ptr is written, including its zero
+ * padding lanes; y must not overlap x, and may overlap res only if res is the
+ * identity shortcut with y's own geometry (same pointer, stride 1, offset 0).
+ * Errors: NULL, SHAPE (y is not the conv's output shape, x->C != C, ...), DTYPE,
+ * ALIGN, ARG, LIMIT, LAUNCH.
+ */
+fupr_status fupr_conv_fused(const fupr_conv_shape* shape, const fupr_tensor* x, const void* packed,
+                            const fupr_residual* res, uint32_t epilogue_flags, const fupr_tensor* y,
+                            void* stream);
+
+/* Max over the taps of a k x k window that fall inside the image (Table II, ImageNet stem). */
+fupr_status fupr_maxpool(const fupr_tensor* x, int32_t k, int32_t stride, int32_t pad,
+                         const fupr_tensor* y, void* stream);
+
+/* y[n,0,0,c] = mean over H*W of x[n,:,:,c], fp32 accumulation (Table II, before fc). */
+fupr_status fupr_global_avgpool(const fupr_tensor* x, const fupr_tensor* y, void* stream);
+
+/* ----------------------------------------------------------------- model -- */
+
+typedef enum { FUPR_OP_CONV = 0, FUPR_OP_MAXPOOL = 1, FUPR_OP_AVGPOOL = 2 } fupr_op_kind;
+
+/*
+ * One operator of the optimised network.  Tensors are numbered: 0 is the
+ * network input, operator i (0-based) produces tensor i + 1.  A fully-connected
+ * layer is a 1x1 convolution on the 1x1 image the global mean leaves.
+ */
+typedef struct {
+  int32_t kind;          /* fupr_op_kind */
+  int32_t in;            /* tensor read */
+  int32_t res;           /* tensor added in the epilogue, -1 = none (conv only) */
+  fupr_conv_shape conv;  /* conv: its shape.  maxpool: R = S = window, stride, pad */
+  const void* packed;    /* [dev] conv only: blob from fupr_pack; must outlive the model */
+  uint32_t epilogue;     /* conv only: FUPR_FUSE_RELU | FUPR_FUSE_ADD */
+  int32_t res_spatial_stride, res_c_offset; /* see fupr_residual */
+} fupr_op_desc;
+
+typedef struct {
+  fupr_dtype dt;
+  int32_t C, H, W; /* one input image */
+  int32_t n_ops;
+  const fupr_op_desc* ops;
+} fupr_graph_desc;
+
+typedef struct fupr_model fupr_model;
+
+/*
+ * Checks the operator list (shapes chain, ids refer to earlier tensors, residual
+ * geometry fits), copies it, and plans which intermediate tensors share memory.
+ * Errors: NULL, SHAPE, DTYPE, ARG.  *out is untouched on error.
+ */
+fupr_status fupr_model_create(const fupr_graph_desc* g, fupr_model** out);
+void fupr_model_destroy(fupr_model* m);
+
+/* Bytes of [dev] workspace fupr_forward needs for a batch (0 if m is NULL or batch <= 0). */
+size_t fupr_model_workspace_bytes(const fupr_model* m, int32_t batch);
+
+/* Shape of the network output for a batch: fills N, H, W, C, c_stride (minimal), dt; ptr = NULL. */
+fupr_status fupr_model_output_shape(const fupr_model* m, int32_t batch, fupr_tensor* out);
+
+/*
+ * Runs the network on input (batch = input->N) and writes the last operator's
+ * result into output->ptr.  workspace is [dev], 256-byte aligned, at least
+ * fupr_model_workspace_bytes(m, batch) bytes, and is only used until the
+ * enqueued work completes.  Asynchronous; safe to capture in a HIP graph.
+ * Errors: NULL, SHAPE, DTYPE, ALIGN, WORKSPACE, LIMIT, LAUNCH.
+ */
+fupr_status fupr_forward(const fupr_model* m, const fupr_tensor* input, const fupr_tensor* output,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * As fupr_forward, but brackets every operator with HIP events on the stream,
+ * waits for the stream, and writes the n_ops elapsed times (milliseconds) to the
+ * HOST array op_ms.  Synchronous.  For measurement only.
+ */
+fupr_status fupr_forward_timed(const fupr_model* m, const fupr_tensor* input,
+                               const fupr_tensor* output, void* workspace, size_t workspace_bytes,
+                               void* stream, float* op_ms);
+
+/*
+ * Algorithmic work of operator i at a batch size: flops = 2*C*R*S*K per output
+ * pixel at the true (pruned) channel counts (0 for pools); bytes = input read
+ * once + output written once + residual read once + parameters read once, at
+ * the true channel counts and the model's element size.  kernel receives a
+ * static string naming the kernel variant the operator launches.
+ */
+typedef struct {
+  double flops, bytes;
+  int64_t M;         /* output pixels N*P*Q */
+  int32_t K, C, R, S, stride;
+  const char* kernel;
+} fupr_op_stats;
+fupr_status fupr_model_op_stats(const fupr_model* m, int32_t batch, int32_t op, fupr_op_stats* out);
+int32_t fupr_model_num_ops(const fupr_model* m);
+
+/*
+ * fupr_forward captured once into a HIP graph and replayed (the operators are
+ * launch-bound at CIFAR sizes).  Capture happens on `stream`, which must be a
+ * non-default stream with no other work in flight; pointers are baked in.
+ */
+typedef struct fupr_graph fupr_graph;
+fupr_status fupr_graph_create(const fupr_model* m, const fupr_tensor* input,
+                              const fupr_tensor* output, void* workspace, size_t workspace_bytes,
+                              void* stream, fupr_graph** out);
+fupr_status fupr_graph_launch(const fupr_graph* g, void* stream);
+void fupr_graph_destroy(fupr_graph* g);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FUPR_H */

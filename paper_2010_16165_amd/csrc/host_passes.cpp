@@ -1,0 +1,236 @@
+// Host-side model transformation: batch-norm merge, filter selection, filter
+// removal and packing to the device layout.  Pure functions on host memory.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <numeric>
+#include <vector>
+
+#include "fupr.h"
+#include "layout.h"
+
+extern "C" const char* fupr_status_str(fupr_status s) {
+  switch (s) {
+    case FUPR_OK: return "ok";
+    case FUPR_ERR_NULL: return "null pointer";
+    case FUPR_ERR_SHAPE: return "shape mismatch";
+    case FUPR_ERR_DTYPE: return "bad or mixed dtype";
+    case FUPR_ERR_MASK_EMPTY: return "mask keeps no filter";
+    case FUPR_ERR_BN_VAR: return "var + eps is not positive and finite";
+    case FUPR_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case FUPR_ERR_ALIGN: return "pointer or channel stride misaligned";
+    case FUPR_ERR_LAUNCH: return "HIP runtime error";
+    case FUPR_ERR_ARG: return "invalid argument";
+    case FUPR_ERR_LIMIT: return "size exceeds 32-bit indexing";
+    default: return "unknown status";
+  }
+}
+
+namespace fupr {
+
+bool shape_ok(const fupr_conv_shape* s) {
+  return s->K > 0 && s->C > 0 && s->R > 0 && s->S > 0 && s->stride > 0 && s->pad >= 0 &&
+         s->R <= 64 && s->S <= 64 && (int64_t)s->K * s->C * s->R * s->S < (int64_t(1) << 31);
+}
+
+}  // namespace fupr
+
+using fupr::shape_ok;
+
+// Sec. IV-B-2, Eq. 3-5 and the merge of Sec. VI-B-3.
+extern "C" fupr_status fupr_fold(const fupr_conv_shape* shape, const float* W,
+                                 const float* conv_bias, const float* gamma, const float* beta,
+                                 const float* mean, const float* var, float eps,
+                                 uint32_t fuse_flags, float* W_out, float* b_out) {
+  if (!shape || !W || !W_out || !b_out) return FUPR_ERR_NULL;
+  if (!shape_ok(shape)) return FUPR_ERR_SHAPE;
+  if (fuse_flags & ~uint32_t(FUPR_FUSE_BN | FUPR_FUSE_RELU | FUPR_FUSE_ADD)) return FUPR_ERR_ARG;
+  const int K = shape->K;
+  const size_t crs = (size_t)shape->C * shape->R * shape->S;
+  if (!(fuse_flags & FUPR_FUSE_BN)) {
+    if (W_out != W) std::memmove(W_out, W, sizeof(float) * K * crs);
+    for (int k = 0; k < K; ++k) b_out[k] = conv_bias ? conv_bias[k] : 0.0f;
+    return FUPR_OK;
+  }
+  if (!gamma || !beta || !mean || !var) return FUPR_ERR_NULL;
+  std::vector<double> omega(K), lambda(K);
+  for (int k = 0; k < K; ++k) {
+    const double v = (double)var[k] + (double)eps;
+    if (!(v > 0.0) || !std::isfinite(v)) return FUPR_ERR_BN_VAR;
+    omega[k] = (double)gamma[k] / std::sqrt(v);
+    lambda[k] = (double)beta[k] - omega[k] * (double)mean[k];
+  }
+  for (int k = 0; k < K; ++k) {
+    const float* src = W + (size_t)k * crs;
+    float* dst = W_out + (size_t)k * crs;
+    for (size_t i = 0; i < crs; ++i) dst[i] = (float)(omega[k] * (double)src[i]);
+    const double b = conv_bias ? (double)conv_bias[k] : 0.0;
+    b_out[k] = (float)(lambda[k] + omega[k] * b);
+  }
+  return FUPR_OK;
+}
+
+// Alg. 1: a non-fused operator loses p_phi * n filters.
+extern "C" int32_t fupr_prune_count(int32_t n, int32_t permille) {
+  if (n <= 0 || permille < 0 || permille > 1000) return FUPR_ERR_ARG;
+  const int64_t cut = ((int64_t)n * permille) / 1000;
+  return (int32_t)std::min<int64_t>(cut, n - 1);
+}
+
+// Sec. IV-C, Eq. 6.
+extern "C" fupr_status fupr_select_filters(const fupr_conv_shape* shape, const float* W,
+                                           int32_t norm, int32_t n_prune, uint8_t* mask_out) {
+  if (!shape || !W || !mask_out) return FUPR_ERR_NULL;
+  if (!shape_ok(shape)) return FUPR_ERR_SHAPE;
+  if (norm != 1 && norm != 2) return FUPR_ERR_ARG;
+  const int K = shape->K;
+  if (n_prune < 0 || n_prune >= K) return FUPR_ERR_ARG;
+  const size_t crs = (size_t)shape->C * shape->R * shape->S;
+  std::vector<double> score(K);
+  for (int k = 0; k < K; ++k) {
+    const float* f = W + (size_t)k * crs;
+    double acc = 0.0;
+    if (norm == 1) {
+      for (size_t i = 0; i < crs; ++i) acc += std::fabs((double)f[i]);
+      score[k] = acc;
+    } else {
+      for (size_t i = 0; i < crs; ++i) acc += (double)f[i] * (double)f[i];
+      score[k] = std::sqrt(acc);
+    }
+  }
+  std::vector<int> order(K);
+  std::iota(order.begin(), order.end(), 0);
+  std::stable_sort(order.begin(), order.end(),
+                   [&](int a, int b) { return score[a] < score[b]; });
+  std::vector<uint8_t> mask(K, 1);
+  for (int i = 0; i < n_prune; ++i) mask[order[i]] = 0;
+  std::memcpy(mask_out, mask.data(), K);
+  return FUPR_OK;
+}
+
+// Alg. 1, last step: masked filters are removed.
+extern "C" fupr_status fupr_prune(const fupr_conv_shape* prod, const float* Wp, const float* bp,
+                                  const uint8_t* mask, int32_t n_consumers,
+                                  const fupr_conv_shape* cons, const float* const* Wc,
+                                  int32_t* K_keep, int32_t* keep_idx, float* Wp_out, float* bp_out,
+                                  float* const* Wc_out) {
+  if (!prod || !Wp || !mask || !K_keep || !keep_idx || !Wp_out) return FUPR_ERR_NULL;
+  if (bp && !bp_out) return FUPR_ERR_NULL;
+  if (n_consumers < 0) return FUPR_ERR_ARG;
+  if (n_consumers > 0 && (!cons || !Wc || !Wc_out)) return FUPR_ERR_NULL;
+  if (!shape_ok(prod)) return FUPR_ERR_SHAPE;
+  for (int i = 0; i < n_consumers; ++i) {
+    if (!Wc[i] || !Wc_out[i]) return FUPR_ERR_NULL;
+    if (!shape_ok(&cons[i]) || cons[i].C != prod->K) return FUPR_ERR_SHAPE;
+  }
+  std::vector<int32_t> keep;
+  keep.reserve(prod->K);
+  for (int k = 0; k < prod->K; ++k) {
+    if (mask[k] > 1) return FUPR_ERR_ARG;
+    if (mask[k]) keep.push_back(k);
+  }
+  if (keep.empty()) return FUPR_ERR_MASK_EMPTY;
+
+  const int kk = (int)keep.size();
+  const size_t crs = (size_t)prod->C * prod->R * prod->S;
+  for (int j = 0; j < kk; ++j) {
+    std::memcpy(Wp_out + (size_t)j * crs, Wp + (size_t)keep[j] * crs, sizeof(float) * crs);
+    if (bp) bp_out[j] = bp[keep[j]];
+    keep_idx[j] = keep[j];
+  }
+  for (int i = 0; i < n_consumers; ++i) {
+    const size_t rs = (size_t)cons[i].R * cons[i].S;
+    const float* src = Wc[i];
+    float* dst = Wc_out[i];
+    for (int k = 0; k < cons[i].K; ++k)
+      for (int j = 0; j < kk; ++j)
+        std::memcpy(dst + ((size_t)k * kk + j) * rs,
+                    src + ((size_t)k * cons[i].C + keep[j]) * rs, sizeof(float) * rs);
+  }
+  *K_keep = kk;
+  return FUPR_OK;
+}
+
+// ---------------------------------------------------------------- packing --
+
+namespace {
+
+// float -> bfloat16 bits, round to nearest even; NaN stays NaN.
+uint16_t to_bf16(float f) {
+  uint32_t u;
+  std::memcpy(&u, &f, 4);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// float -> IEEE half bits, round to nearest even, overflow to infinity.
+uint16_t to_f16(float f) {
+  uint32_t u;
+  std::memcpy(&u, &f, 4);
+  const uint32_t sign = (u >> 16) & 0x8000u;
+  const uint32_t a = u & 0x7fffffffu;
+  if (a > 0x7f800000u) return (uint16_t)(sign | 0x7e00u);
+  if (a >= 0x477ff000u) return (uint16_t)(sign | 0x7c00u);  // >= 65520 rounds to inf
+  if (a < 0x33000001u) return (uint16_t)sign;               // <= 2^-25 rounds to zero
+  int e = (int)(a >> 23) - 127;
+  uint32_t mant = (a & 0x7fffffu) | 0x800000u;
+  int shift;
+  uint32_t base;
+  if (e < -14) {  // subnormal half
+    shift = 13 + (-14 - e);
+    base = 0;
+  } else {
+    shift = 13;
+    base = (uint32_t)(e + 15) << 10;
+    mant &= 0x7fffffu;
+  }
+  uint32_t q = mant >> shift;
+  const uint32_t rem = mant & ((1u << shift) - 1u);
+  const uint32_t half = 1u << (shift - 1);
+  if (rem > half || (rem == half && (q & 1u))) ++q;
+  return (uint16_t)(sign | (base + q));
+}
+
+}  // namespace
+
+extern "C" size_t fupr_packed_bytes(const fupr_conv_shape* shape, fupr_dtype dt) {
+  if (!shape || !shape_ok(shape)) return 0;
+  if (dt != FUPR_F32 && dt != FUPR_BF16 && dt != FUPR_F16) return 0;
+  const fupr::PackedLayout L = fupr::packed_layout(*shape, dt);
+  return L.total_bytes;
+}
+
+extern "C" fupr_status fupr_pack(const fupr_conv_shape* shape, const float* W, const float* bias,
+                                 fupr_dtype dt, void* blob_out) {
+  if (!shape || !W || !blob_out) return FUPR_ERR_NULL;
+  if (!shape_ok(shape)) return FUPR_ERR_SHAPE;
+  if (dt != FUPR_F32 && dt != FUPR_BF16 && dt != FUPR_F16) return FUPR_ERR_DTYPE;
+  const fupr::PackedLayout L = fupr::packed_layout(*shape, dt);
+  const int K = shape->K, C = shape->C, R = shape->R, S = shape->S;
+  std::memset(blob_out, 0, L.total_bytes);
+  float* b = reinterpret_cast<float*>(blob_out);
+  if (bias) std::memcpy(b, bias, sizeof(float) * K);
+  char* wbase = reinterpret_cast<char*>(blob_out) + L.weight_offset;
+  if (dt == FUPR_F32) {
+    float* w = reinterpret_cast<float*>(wbase);
+    for (int k = 0; k < K; ++k)
+      for (int c = 0; c < C; ++c)
+        for (int r = 0; r < R; ++r)
+          for (int s = 0; s < S; ++s)
+            w[((size_t)(r * S + s) * L.Cp + c) * L.Kp + k] =
+                W[(((size_t)k * C + c) * R + r) * S + s];
+    return FUPR_OK;
+  }
+  uint16_t* w = reinterpret_cast<uint16_t*>(wbase);
+  const int cpt = L.Cp / 8;
+  for (int k = 0; k < K; ++k)
+    for (int c = 0; c < C; ++c)
+      for (int r = 0; r < R; ++r)
+        for (int s = 0; s < S; ++s) {
+          const float v = W[(((size_t)k * C + c) * R + r) * S + s];
+          const size_t chunk = (size_t)(r * S + s) * cpt + c / 8;
+          w[(chunk * L.Kp + k) * 8 + (c % 8)] = dt == FUPR_BF16 ? to_bf16(v) : to_f16(v);
+        }
+  return FUPR_OK;
+}

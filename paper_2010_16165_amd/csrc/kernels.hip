@@ -1,0 +1,616 @@
+// Device kernels for gfx950 and the C-ABI calls that launch them:
+// the convolution operator with fused epilogue (Sec. III; Sec. IV-B-1 of the
+// paper), max-pool and global mean (the "Others" of Table II).
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "fupr.h"
+#include "layout.h"
+
+namespace fupr {
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+// ---- 16-bit element helpers ------------------------------------------------
+
+template <bool BF>
+__device__ __forceinline__ float to_float(uint16_t h) {
+  if constexpr (BF) {
+    return __uint_as_float((uint32_t)h << 16);
+  } else {
+    return (float)__builtin_bit_cast(_Float16, h);
+  }
+}
+
+// Round to nearest even.
+template <bool BF>
+__device__ __forceinline__ uint16_t from_float(float f) {
+  if constexpr (BF) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+  } else {
+    return __builtin_bit_cast(uint16_t, (_Float16)f);
+  }
+}
+
+template <bool BF>
+__device__ __forceinline__ f32x4 mfma_16x16x32(const uint4& a, const uint4& b, f32x4 c) {
+  if constexpr (BF) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                   __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  } else {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a),
+                                                  __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+  }
+}
+
+// ---- implicit-GEMM convolution, 16-bit inputs, fp32 accumulation -----------
+//
+// GEMM view: rows = filters (MFMA operand A, 16 per tile), columns = output
+// pixels (operand B, 16 per tile), reduction = (r, s, c) in chunks of 8
+// channels; one MFMA 16x16x32 consumes 4 chunks.  With filters on the rows,
+// every lane ends up with 4 consecutive channels of one pixel, i.e. one 8-byte
+// NHWC store.  A workgroup is 4 waves; each wave owns MT pixel tiles and NT
+// filter tiles.
+
+struct Conv16Params {
+  const uint16_t* x;
+  const uint16_t* w;     // [nchunk_pad][Kp][8]
+  const float* bias;     // [Kp]
+  const uint16_t* res;
+  uint16_t* y;
+  int H, W, xcs;
+  int P, Q, PQ, M, ycs;
+  int S, stride, pad;
+  int Kp, FT, cpt, nchunk, nsteps;
+  int rH, rW, rcs, rss, roff;
+  int relu;
+};
+
+template <bool BF, int MT, int NT>
+__global__ __launch_bounds__(256) void conv16_kernel(const Conv16Params p) {
+  extern __shared__ int2 tap_table[];  // per chunk: element offset, (r << 8 | s) or -1
+  for (int j = threadIdx.x; j < p.nsteps * 4; j += 256) {
+    int2 e;
+    if (j < p.nchunk) {
+      const int tap = j / p.cpt, c8 = j - tap * p.cpt;
+      const int r = tap / p.S, s = tap - r * p.S;
+      e.x = (r * p.W + s) * p.xcs + c8 * 8;
+      e.y = (r << 8) | s;
+    } else {
+      e.x = 0;
+      e.y = -1;
+    }
+    tap_table[j] = e;
+  }
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int li = lane & 15, g = lane >> 4;
+  const int ft0 = blockIdx.y * NT;
+
+  int ih0[MT], iw0[MT];
+  const uint16_t* xb[MT];
+  bool pv[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    const int m = ((blockIdx.x * 4 + wave) * MT + mt) * 16 + li;
+    pv[mt] = m < p.M;
+    const int mm = pv[mt] ? m : 0;
+    const int n = mm / p.PQ, rem = mm - n * p.PQ;
+    const int pp = rem / p.Q, qq = rem - pp * p.Q;
+    ih0[mt] = pp * p.stride - p.pad;
+    iw0[mt] = qq * p.stride - p.pad;
+    xb[mt] = p.x + ((int64_t)n * p.H * p.W + (int64_t)ih0[mt] * p.W + iw0[mt]) * p.xcs;
+  }
+  const uint16_t* wb[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int tt = min(ft0 + t, p.FT - 1);
+    wb[t] = p.w + ((size_t)g * p.Kp + tt * 16 + li) * 8;
+  }
+
+  f32x4 acc[MT][NT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  __syncthreads();
+
+  const size_t wstep = (size_t)4 * p.Kp * 8;
+  uint4 a_cur[NT], b_cur[MT], a_nxt[NT], b_nxt[MT];
+
+  auto load_step = [&](int step, uint4* a, uint4* b) {
+    const int2 e = tap_table[step * 4 + g];
+    const int r = e.y >> 8, s = e.y & 255;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const bool ok = pv[mt] && e.y >= 0 && (unsigned)(ih0[mt] + r) < (unsigned)p.H &&
+                      (unsigned)(iw0[mt] + s) < (unsigned)p.W;
+      b[mt] = ok ? *reinterpret_cast<const uint4*>(xb[mt] + e.x) : uint4{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+      a[t] = *reinterpret_cast<const uint4*>(wb[t] + (size_t)step * wstep);
+  };
+
+  load_step(0, a_cur, b_cur);
+  for (int step = 0; step < p.nsteps; ++step) {
+    if (step + 1 < p.nsteps) load_step(step + 1, a_nxt, b_nxt);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int t = 0; t < NT; ++t) acc[mt][t] = mfma_16x16x32<BF>(a_cur[t], b_cur[mt], acc[mt][t]);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) a_cur[t] = a_nxt[t];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) b_cur[mt] = b_nxt[mt];
+  }
+
+  // Epilogue: bias, shortcut, ReLU, one rounding, 8-byte NHWC store.
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    const int m = ((blockIdx.x * 4 + wave) * MT + mt) * 16 + li;
+    if (m >= p.M) continue;
+    const uint16_t* rp = nullptr;
+    if (p.res) {
+      const int n = m / p.PQ, rem = m - n * p.PQ;
+      const int pp = rem / p.Q, qq = rem - pp * p.Q;
+      rp = p.res + (((int64_t)n * p.rH + pp * p.rss) * p.rW + qq * p.rss) * p.rcs;
+    }
+    uint16_t* yp = p.y + (int64_t)m * p.ycs;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const int k0 = (ft0 + t) * 16 + g * 4;
+      if (ft0 + t >= p.FT || k0 >= p.ycs) continue;
+      const float4 b4 = *reinterpret_cast<const float4*>(p.bias + k0);
+      float v[4] = {acc[mt][t][0] + b4.x, acc[mt][t][1] + b4.y, acc[mt][t][2] + b4.z,
+                    acc[mt][t][3] + b4.w};
+      if (rp) {
+        const int kk = k0 - p.roff;
+        if (kk >= 0 && kk < p.rcs) {
+          const uint2 rv = *reinterpret_cast<const uint2*>(rp + kk);
+          v[0] += to_float<BF>((uint16_t)(rv.x & 0xffffu));
+          v[1] += to_float<BF>((uint16_t)(rv.x >> 16));
+          v[2] += to_float<BF>((uint16_t)(rv.y & 0xffffu));
+          v[3] += to_float<BF>((uint16_t)(rv.y >> 16));
+        }
+      }
+      if (p.relu) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i], 0.f);
+      }
+      uint2 o;
+      o.x = (uint32_t)from_float<BF>(v[0]) | ((uint32_t)from_float<BF>(v[1]) << 16);
+      o.y = (uint32_t)from_float<BF>(v[2]) | ((uint32_t)from_float<BF>(v[3]) << 16);
+      *reinterpret_cast<uint2*>(yp + k0) = o;
+    }
+  }
+}
+
+// ---- fp32 direct convolution ------------------------------------------------
+// One thread: one output pixel x 4 consecutive filters, plain FMA.
+
+struct Conv32Params {
+  const float* x;
+  const float* w;   // [R*S*Cp][Kp]
+  const float* bias;
+  const float* res;
+  float* y;
+  int H, W, xcs, Cp;
+  int P, Q, PQ, M, ycs;
+  int R, S, stride, pad;
+  int Kp, KQ;
+  int rH, rW, rcs, rss, roff;
+  int relu;
+};
+
+__global__ __launch_bounds__(256) void conv32_kernel(const Conv32Params p) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int kq = (int)(idx % p.KQ);
+  const int64_t m64 = idx / p.KQ;
+  if (m64 >= p.M) return;
+  const int m = (int)m64;
+  const int k0 = kq * 4;
+  const int n = m / p.PQ, rem = m - n * p.PQ;
+  const int pp = rem / p.Q, qq = rem - pp * p.Q;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int r = 0; r < p.R; ++r) {
+    const int ih = pp * p.stride + r - p.pad;
+    if (ih < 0 || ih >= p.H) continue;
+    for (int s = 0; s < p.S; ++s) {
+      const int iw = qq * p.stride + s - p.pad;
+      if (iw < 0 || iw >= p.W) continue;
+      const float* xp = p.x + (((int64_t)n * p.H + ih) * p.W + iw) * p.xcs;
+      const float* wp = p.w + (size_t)(r * p.S + s) * p.Cp * p.Kp + k0;
+      for (int c = 0; c < p.Cp; c += 4) {
+        const float4 xv = *reinterpret_cast<const float4*>(xp + c);
+        const float xs[4] = {xv.x, xv.y, xv.z, xv.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float4 wv = *reinterpret_cast<const float4*>(wp + (size_t)(c + i) * p.Kp);
+          acc[0] = fmaf(xs[i], wv.x, acc[0]);
+          acc[1] = fmaf(xs[i], wv.y, acc[1]);
+          acc[2] = fmaf(xs[i], wv.z, acc[2]);
+          acc[3] = fmaf(xs[i], wv.w, acc[3]);
+        }
+      }
+    }
+  }
+  if (k0 >= p.ycs) return;
+  const float4 b4 = *reinterpret_cast<const float4*>(p.bias + k0);
+  float v[4] = {acc[0] + b4.x, acc[1] + b4.y, acc[2] + b4.z, acc[3] + b4.w};
+  if (p.res) {
+    const int kk = k0 - p.roff;
+    if (kk >= 0 && kk < p.rcs) {
+      const float4 rv = *reinterpret_cast<const float4*>(
+          p.res + (((int64_t)n * p.rH + pp * p.rss) * p.rW + qq * p.rss) * p.rcs + kk);
+      v[0] += rv.x;
+      v[1] += rv.y;
+      v[2] += rv.z;
+      v[3] += rv.w;
+    }
+  }
+  if (p.relu) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i], 0.f);
+  }
+  *reinterpret_cast<float4*>(p.y + (int64_t)m * p.ycs + k0) = float4{v[0], v[1], v[2], v[3]};
+}
+
+// ---- pools -------------------------------------------------------------------
+
+struct PoolParams {
+  const void* x;
+  void* y;
+  int H, W, cs, P, Q, ycs, k, stride, pad;
+  int chunks;      // channel chunks per pixel that are processed (of the OUTPUT stride)
+  int64_t total;   // threads
+};
+
+// DT: 0 fp32 (chunk = 4 channels), 1 bf16, 2 fp16 (chunk = 8 channels).
+template <int DT>
+__global__ __launch_bounds__(256) void maxpool_kernel(const PoolParams p) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= p.total) return;
+  const int ch = (int)(idx % p.chunks);
+  int64_t pix = idx / p.chunks;
+  const int q = (int)(pix % p.Q);
+  pix /= p.Q;
+  const int pp = (int)(pix % p.P);
+  const int n = (int)(pix / p.P);
+  constexpr int V = DT == 0 ? 4 : 8;
+  float m[V];
+#pragma unroll
+  for (int i = 0; i < V; ++i) m[i] = -INFINITY;
+  for (int r = 0; r < p.k; ++r) {
+    const int ih = pp * p.stride + r - p.pad;
+    if (ih < 0 || ih >= p.H) continue;
+    for (int s = 0; s < p.k; ++s) {
+      const int iw = q * p.stride + s - p.pad;
+      if (iw < 0 || iw >= p.W) continue;
+      const int64_t off = (((int64_t)n * p.H + ih) * p.W + iw) * p.cs + ch * V;
+      if constexpr (DT == 0) {
+        const float4 v = *reinterpret_cast<const float4*>((const float*)p.x + off);
+        m[0] = fmaxf(m[0], v.x);
+        m[1] = fmaxf(m[1], v.y);
+        m[2] = fmaxf(m[2], v.z);
+        m[3] = fmaxf(m[3], v.w);
+      } else {
+        const uint4 v = *reinterpret_cast<const uint4*>((const uint16_t*)p.x + off);
+        const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          m[2 * i] = fmaxf(m[2 * i], to_float<DT == 1>((uint16_t)(u[i] & 0xffffu)));
+          m[2 * i + 1] = fmaxf(m[2 * i + 1], to_float<DT == 1>((uint16_t)(u[i] >> 16)));
+        }
+      }
+    }
+  }
+  const int64_t yoff = (((int64_t)n * p.P + pp) * p.Q + q) * p.ycs + ch * V;
+  if constexpr (DT == 0) {
+    *reinterpret_cast<float4*>((float*)p.y + yoff) = float4{m[0], m[1], m[2], m[3]};
+  } else {
+    uint4 o;
+    uint32_t u[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      u[i] = (uint32_t)from_float<DT == 1>(m[2 * i]) |
+             ((uint32_t)from_float<DT == 1>(m[2 * i + 1]) << 16);
+    o.x = u[0];
+    o.y = u[1];
+    o.z = u[2];
+    o.w = u[3];
+    *reinterpret_cast<uint4*>((uint16_t*)p.y + yoff) = o;
+  }
+}
+
+// One thread: one image x one channel chunk, sequential fp32 sum over pixels.
+template <int DT>
+__global__ __launch_bounds__(256) void avgpool_kernel(const PoolParams p) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= p.total) return;
+  const int ch = (int)(idx % p.chunks);
+  const int n = (int)(idx / p.chunks);
+  constexpr int V = DT == 0 ? 4 : 8;
+  float acc[V];
+#pragma unroll
+  for (int i = 0; i < V; ++i) acc[i] = 0.f;
+  const int hw = p.H * p.W;
+  for (int i = 0; i < hw; ++i) {
+    const int64_t off = ((int64_t)n * hw + i) * p.cs + ch * V;
+    if constexpr (DT == 0) {
+      const float4 v = *reinterpret_cast<const float4*>((const float*)p.x + off);
+      acc[0] += v.x;
+      acc[1] += v.y;
+      acc[2] += v.z;
+      acc[3] += v.w;
+    } else {
+      const uint4 v = *reinterpret_cast<const uint4*>((const uint16_t*)p.x + off);
+      const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        acc[2 * j] += to_float<DT == 1>((uint16_t)(u[j] & 0xffffu));
+        acc[2 * j + 1] += to_float<DT == 1>((uint16_t)(u[j] >> 16));
+      }
+    }
+  }
+  const float inv = (float)hw;
+#pragma unroll
+  for (int i = 0; i < V; ++i) acc[i] = acc[i] / inv;
+  const int64_t yoff = (int64_t)n * p.ycs + ch * V;
+  if constexpr (DT == 0) {
+    *reinterpret_cast<float4*>((float*)p.y + yoff) = float4{acc[0], acc[1], acc[2], acc[3]};
+  } else {
+    uint4 o;
+    uint32_t u[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      u[i] = (uint32_t)from_float<DT == 1>(acc[2 * i]) |
+             ((uint32_t)from_float<DT == 1>(acc[2 * i + 1]) << 16);
+    o.x = u[0];
+    o.y = u[1];
+    o.z = u[2];
+    o.w = u[3];
+    *reinterpret_cast<uint4*>((uint16_t*)p.y + yoff) = o;
+  }
+}
+
+// ---- tile selection -----------------------------------------------------------
+
+struct Tile {
+  int MT, NT;
+};
+
+// Filter tiles per wave: all of them when there are at most 4, otherwise the
+// group size that wastes the fewest tiles.  Pixel tiles per wave: as many as
+// keep at least ~2 workgroups per compute unit in flight.
+Tile choose_tile(int FT, int64_t M) {
+  Tile t;
+  if (FT <= 4) t.NT = FT;
+  else if (FT % 4 == 0) t.NT = 4;
+  else if (FT % 3 == 0) t.NT = 3;
+  else t.NT = 4;
+  const int64_t groups = (FT + t.NT - 1) / t.NT;
+  t.MT = 4;
+  while (t.MT > 1 && ((M + 64 * t.MT - 1) / (64 * t.MT)) * groups < 1024) t.MT >>= 1;
+  return t;
+}
+
+template <bool BF, int MT>
+fupr_status launch16_nt(const Conv16Params& p, int NT, dim3 grid, size_t shmem, hipStream_t st) {
+  switch (NT) {
+    case 1: hipLaunchKernelGGL((conv16_kernel<BF, MT, 1>), grid, dim3(256), shmem, st, p); break;
+    case 2: hipLaunchKernelGGL((conv16_kernel<BF, MT, 2>), grid, dim3(256), shmem, st, p); break;
+    case 3: hipLaunchKernelGGL((conv16_kernel<BF, MT, 3>), grid, dim3(256), shmem, st, p); break;
+    default: hipLaunchKernelGGL((conv16_kernel<BF, MT, 4>), grid, dim3(256), shmem, st, p); break;
+  }
+  return hipGetLastError() == hipSuccess ? FUPR_OK : FUPR_ERR_LAUNCH;
+}
+
+template <bool BF>
+fupr_status launch16(const Conv16Params& p, Tile t, hipStream_t st) {
+  const int64_t mblk = ((int64_t)p.M + 64 * t.MT - 1) / (64 * t.MT);
+  dim3 grid((unsigned)mblk, (unsigned)((p.FT + t.NT - 1) / t.NT));
+  const size_t shmem = (size_t)p.nsteps * 4 * sizeof(int2);
+  switch (t.MT) {
+    case 1: return launch16_nt<BF, 1>(p, t.NT, grid, shmem, st);
+    case 2: return launch16_nt<BF, 2>(p, t.NT, grid, shmem, st);
+    default: return launch16_nt<BF, 4>(p, t.NT, grid, shmem, st);
+  }
+}
+
+}  // namespace
+
+const char* conv_kernel_name(const fupr_conv_shape& s, fupr_dtype dt, int64_t M) {
+  if (dt == FUPR_F32) return "conv32_direct";
+  const PackedLayout L = packed_layout(s, dt);
+  const Tile t = choose_tile(L.Kp / 16, M);
+  static const char* names[3][4] = {
+      {"conv16_mt1_nt1", "conv16_mt1_nt2", "conv16_mt1_nt3", "conv16_mt1_nt4"},
+      {"conv16_mt2_nt1", "conv16_mt2_nt2", "conv16_mt2_nt3", "conv16_mt2_nt4"},
+      {"conv16_mt4_nt1", "conv16_mt4_nt2", "conv16_mt4_nt3", "conv16_mt4_nt4"}};
+  return names[t.MT == 1 ? 0 : t.MT == 2 ? 1 : 2][t.NT - 1];
+}
+
+fupr_status launch_conv(const ConvArgs& a, void* stream) {
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  fupr_conv_shape s{a.K, a.C, a.R, a.S, a.stride, a.pad};
+  const PackedLayout L = packed_layout(s, a.dt);
+  const int64_t M = (int64_t)a.N * a.P * a.Q;
+  const char* blob = reinterpret_cast<const char*>(a.packed);
+  if (a.dt == FUPR_F32) {
+    Conv32Params p;
+    p.x = (const float*)a.x;
+    p.w = (const float*)(blob + L.weight_offset);
+    p.bias = (const float*)blob;
+    p.res = (const float*)a.res;
+    p.y = (float*)a.y;
+    p.H = a.H; p.W = a.W; p.xcs = a.xcs; p.Cp = L.Cp;
+    p.P = a.P; p.Q = a.Q; p.PQ = a.P * a.Q; p.M = (int)M; p.ycs = a.ycs;
+    p.R = a.R; p.S = a.S; p.stride = a.stride; p.pad = a.pad;
+    p.Kp = L.Kp; p.KQ = L.Kp / 4;
+    p.rH = a.rH; p.rW = a.rW; p.rcs = a.rcs; p.rss = a.rss; p.roff = a.roff;
+    p.relu = a.relu;
+    const int64_t threads = M * p.KQ;
+    hipLaunchKernelGGL(conv32_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, p);
+    return hipGetLastError() == hipSuccess ? FUPR_OK : FUPR_ERR_LAUNCH;
+  }
+  Conv16Params p;
+  p.x = (const uint16_t*)a.x;
+  p.w = (const uint16_t*)(blob + L.weight_offset);
+  p.bias = (const float*)blob;
+  p.res = (const uint16_t*)a.res;
+  p.y = (uint16_t*)a.y;
+  p.H = a.H; p.W = a.W; p.xcs = a.xcs;
+  p.P = a.P; p.Q = a.Q; p.PQ = a.P * a.Q; p.M = (int)M; p.ycs = a.ycs;
+  p.S = a.S; p.stride = a.stride; p.pad = a.pad;
+  p.Kp = L.Kp; p.FT = L.Kp / 16; p.cpt = L.Cp / 8; p.nchunk = L.nchunk; p.nsteps = L.nchunk_pad / 4;
+  p.rH = a.rH; p.rW = a.rW; p.rcs = a.rcs; p.rss = a.rss; p.roff = a.roff;
+  p.relu = a.relu;
+  const Tile t = choose_tile(p.FT, M);
+  return a.dt == FUPR_BF16 ? launch16<true>(p, t, st) : launch16<false>(p, t, st);
+}
+
+}  // namespace fupr
+
+// ------------------------------------------------------------------ C ABI ----
+
+using namespace fupr;
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Geometry rules shared by every tensor argument.
+fupr_status check_tensor(const fupr_tensor* t) {
+  if (!t->ptr) return FUPR_ERR_NULL;
+  if (!dtype_ok((int)t->dt)) return FUPR_ERR_DTYPE;
+  if (t->N <= 0 || t->H <= 0 || t->W <= 0 || t->C <= 0) return FUPR_ERR_SHAPE;
+  if (t->c_stride < t->C || t->c_stride % c_align(t->dt) != 0) return FUPR_ERR_ALIGN;
+  if (!aligned16(t->ptr)) return FUPR_ERR_ALIGN;
+  if ((int64_t)t->N * t->H * t->W * t->c_stride >= (int64_t(1) << 31)) return FUPR_ERR_LIMIT;
+  return FUPR_OK;
+}
+
+}  // namespace
+
+extern "C" fupr_status fupr_conv_fused(const fupr_conv_shape* shape, const fupr_tensor* x,
+                                       const void* packed, const fupr_residual* res,
+                                       uint32_t epilogue_flags, const fupr_tensor* y,
+                                       void* stream) {
+  if (!shape || !x || !y || !packed) return FUPR_ERR_NULL;
+  if (!shape_ok(shape)) return FUPR_ERR_SHAPE;
+  if (epilogue_flags & ~uint32_t(FUPR_FUSE_RELU | FUPR_FUSE_ADD)) return FUPR_ERR_ARG;
+  const bool add = (epilogue_flags & FUPR_FUSE_ADD) != 0;
+  if (add && !res) return FUPR_ERR_NULL;
+  if (!add && res) return FUPR_ERR_ARG;
+  fupr_status st = check_tensor(x);
+  if (st != FUPR_OK) return st;
+  st = check_tensor(y);
+  if (st != FUPR_OK) return st;
+  if (x->dt != y->dt) return FUPR_ERR_DTYPE;
+  if ((reinterpret_cast<uintptr_t>(packed) & 255u) != 0) return FUPR_ERR_ALIGN;
+  const int P = out_extent(x->H, shape->R, shape->stride, shape->pad);
+  const int Q = out_extent(x->W, shape->S, shape->stride, shape->pad);
+  if (x->H + 2 * shape->pad < shape->R || x->W + 2 * shape->pad < shape->S) return FUPR_ERR_SHAPE;
+  if (x->C != shape->C || y->C != shape->K || y->N != x->N || y->H != P || y->W != Q)
+    return FUPR_ERR_SHAPE;
+  const PackedLayout L = packed_layout(*shape, x->dt);
+  if (y->c_stride > L.Kp) return FUPR_ERR_ALIGN;
+  if (x->ptr == y->ptr) return FUPR_ERR_ARG;
+
+  ConvArgs a{};
+  a.x = x->ptr;
+  a.packed = packed;
+  a.y = y->ptr;
+  a.N = x->N; a.H = x->H; a.W = x->W; a.C = x->C; a.xcs = x->c_stride;
+  a.P = P; a.Q = Q; a.K = shape->K; a.ycs = y->c_stride;
+  a.R = shape->R; a.S = shape->S; a.stride = shape->stride; a.pad = shape->pad;
+  a.relu = (epilogue_flags & FUPR_FUSE_RELU) ? 1 : 0;
+  a.dt = x->dt;
+  if (add) {
+    const fupr_tensor* t = &res->t;
+    st = check_tensor(t);
+    if (st != FUPR_OK) return st;
+    if (t->dt != x->dt) return FUPR_ERR_DTYPE;
+    if (res->spatial_stride < 1 || res->c_offset < 0 || res->c_offset % 4 != 0) return FUPR_ERR_ARG;
+    if (t->N != x->N || res->c_offset + t->C > shape->K) return FUPR_ERR_SHAPE;
+    if ((int64_t)(P - 1) * res->spatial_stride >= t->H ||
+        (int64_t)(Q - 1) * res->spatial_stride >= t->W)
+      return FUPR_ERR_SHAPE;
+    if (t->ptr == y->ptr && !(res->spatial_stride == 1 && res->c_offset == 0 && t->H == P &&
+                              t->W == Q && t->c_stride == y->c_stride))
+      return FUPR_ERR_ARG;
+    a.res = t->ptr;
+    a.rH = t->H; a.rW = t->W; a.rC = t->C; a.rcs = t->c_stride;
+    a.rss = res->spatial_stride; a.roff = res->c_offset;
+  }
+  return launch_conv(a, stream);
+}
+
+namespace {
+
+fupr_status pool_common(const fupr_tensor* x, const fupr_tensor* y) {
+  if (!x || !y) return FUPR_ERR_NULL;
+  fupr_status st = check_tensor(x);
+  if (st != FUPR_OK) return st;
+  st = check_tensor(y);
+  if (st != FUPR_OK) return st;
+  if (x->dt != y->dt) return FUPR_ERR_DTYPE;
+  if (x->C != y->C || x->N != y->N) return FUPR_ERR_SHAPE;
+  if (y->c_stride > x->c_stride) return FUPR_ERR_ALIGN;
+  if (x->ptr == y->ptr) return FUPR_ERR_ARG;
+  return FUPR_OK;
+}
+
+}  // namespace
+
+extern "C" fupr_status fupr_maxpool(const fupr_tensor* x, int32_t k, int32_t stride, int32_t pad,
+                                    const fupr_tensor* y, void* stream) {
+  fupr_status st = pool_common(x, y);
+  if (st != FUPR_OK) return st;
+  if (k <= 0 || stride <= 0 || pad < 0 || pad >= k) return FUPR_ERR_ARG;
+  if (x->H + 2 * pad < k || x->W + 2 * pad < k) return FUPR_ERR_SHAPE;
+  const int P = out_extent(x->H, k, stride, pad), Q = out_extent(x->W, k, stride, pad);
+  if (y->H != P || y->W != Q) return FUPR_ERR_SHAPE;
+  // every window must hold at least one tap inside the image
+  if ((int64_t)(P - 1) * stride - pad >= x->H || (int64_t)(Q - 1) * stride - pad >= x->W)
+    return FUPR_ERR_SHAPE;
+  PoolParams p;
+  p.x = x->ptr; p.y = y->ptr;
+  p.H = x->H; p.W = x->W; p.cs = x->c_stride; p.P = P; p.Q = Q; p.ycs = y->c_stride;
+  p.k = k; p.stride = stride; p.pad = pad;
+  p.chunks = y->c_stride / c_align(x->dt);
+  p.total = (int64_t)x->N * P * Q * p.chunks;
+  hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
+  dim3 grid((unsigned)((p.total + 255) / 256));
+  if (x->dt == FUPR_F32) hipLaunchKernelGGL(maxpool_kernel<0>, grid, dim3(256), 0, hs, p);
+  else if (x->dt == FUPR_BF16) hipLaunchKernelGGL(maxpool_kernel<1>, grid, dim3(256), 0, hs, p);
+  else hipLaunchKernelGGL(maxpool_kernel<2>, grid, dim3(256), 0, hs, p);
+  return hipGetLastError() == hipSuccess ? FUPR_OK : FUPR_ERR_LAUNCH;
+}
+
+extern "C" fupr_status fupr_global_avgpool(const fupr_tensor* x, const fupr_tensor* y,
+                                           void* stream) {
+  fupr_status st = pool_common(x, y);
+  if (st != FUPR_OK) return st;
+  if (y->H != 1 || y->W != 1) return FUPR_ERR_SHAPE;
+  PoolParams p{};
+  p.x = x->ptr; p.y = y->ptr;
+  p.H = x->H; p.W = x->W; p.cs = x->c_stride; p.P = 1; p.Q = 1; p.ycs = y->c_stride;
+  p.chunks = y->c_stride / c_align(x->dt);
+  p.total = (int64_t)x->N * p.chunks;
+  hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
+  dim3 grid((unsigned)((p.total + 255) / 256));
+  if (x->dt == FUPR_F32) hipLaunchKernelGGL(avgpool_kernel<0>, grid, dim3(256), 0, hs, p);
+  else if (x->dt == FUPR_BF16) hipLaunchKernelGGL(avgpool_kernel<1>, grid, dim3(256), 0, hs, p);
+  else hipLaunchKernelGGL(avgpool_kernel<2>, grid, dim3(256), 0, hs, p);
+  return hipGetLastError() == hipSuccess ? FUPR_OK : FUPR_ERR_LAUNCH;
+}

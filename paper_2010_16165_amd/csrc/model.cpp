@@ -1,0 +1,344 @@
+// Whole-network executor: validates an operator list, plans which intermediate
+// tensors share workspace memory, and enqueues one kernel per operator on the
+// caller's stream (Table II networks after fusion and filter removal).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "fupr.h"
+#include "layout.h"
+
+using namespace fupr;
+
+namespace {
+
+struct TensorInfo {
+  int C, H, W, cs;   // per image
+  int buffer;        // workspace buffer id; -1 = network input, -2 = network output
+  int last_use;      // index of the last operator reading it
+};
+
+}  // namespace
+
+struct fupr_model {
+  fupr_dtype dt;
+  std::vector<fupr_op_desc> ops;
+  std::vector<TensorInfo> tensors;        // n_ops + 1
+  std::vector<size_t> buffer_elems;       // per image, per workspace buffer
+};
+
+struct fupr_graph {
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t exec = nullptr;
+};
+
+extern "C" fupr_status fupr_model_create(const fupr_graph_desc* g, fupr_model** out) {
+  if (!g || !out || !g->ops) return FUPR_ERR_NULL;
+  if (!dtype_ok((int)g->dt)) return FUPR_ERR_DTYPE;
+  if (g->n_ops <= 0 || g->C <= 0 || g->H <= 0 || g->W <= 0) return FUPR_ERR_SHAPE;
+
+  fupr_model* m = new (std::nothrow) fupr_model;
+  if (!m) return FUPR_ERR_ARG;
+  m->dt = g->dt;
+  m->ops.assign(g->ops, g->ops + g->n_ops);
+  m->tensors.resize(g->n_ops + 1);
+  m->tensors[0] = TensorInfo{g->C, g->H, g->W, min_c_stride(g->C, g->dt), -1, -1};
+
+  fupr_status err = FUPR_OK;
+  for (int i = 0; i < g->n_ops && err == FUPR_OK; ++i) {
+    const fupr_op_desc& op = m->ops[i];
+    if (op.in < 0 || op.in > i) { err = FUPR_ERR_ARG; break; }
+    const TensorInfo& tin = m->tensors[op.in];
+    TensorInfo t{};
+    t.buffer = -3;
+    t.last_use = -1;
+    if (op.kind == FUPR_OP_CONV) {
+      const fupr_conv_shape& s = op.conv;
+      if (!shape_ok(&s)) { err = FUPR_ERR_SHAPE; break; }
+      if (!op.packed) { err = FUPR_ERR_NULL; break; }
+      if (s.C != tin.C || tin.H + 2 * s.pad < s.R || tin.W + 2 * s.pad < s.S) {
+        err = FUPR_ERR_SHAPE; break;
+      }
+      if (op.epilogue & ~uint32_t(FUPR_FUSE_RELU | FUPR_FUSE_ADD)) { err = FUPR_ERR_ARG; break; }
+      t.C = s.K;
+      t.H = out_extent(tin.H, s.R, s.stride, s.pad);
+      t.W = out_extent(tin.W, s.S, s.stride, s.pad);
+      const bool add = (op.epilogue & FUPR_FUSE_ADD) != 0;
+      if (add != (op.res >= 0)) { err = FUPR_ERR_ARG; break; }
+      if (add) {
+        if (op.res > i) { err = FUPR_ERR_ARG; break; }
+        const TensorInfo& tr = m->tensors[op.res];
+        if (op.res_spatial_stride < 1 || op.res_c_offset < 0 || op.res_c_offset % 4 != 0) {
+          err = FUPR_ERR_ARG; break;
+        }
+        if (op.res_c_offset + tr.C > s.K || (int64_t)(t.H - 1) * op.res_spatial_stride >= tr.H ||
+            (int64_t)(t.W - 1) * op.res_spatial_stride >= tr.W) {
+          err = FUPR_ERR_SHAPE; break;
+        }
+      }
+    } else if (op.kind == FUPR_OP_MAXPOOL) {
+      const int k = op.conv.R;
+      if (k <= 0 || op.conv.S != k || op.conv.stride <= 0 || op.conv.pad < 0 || op.conv.pad >= k) {
+        err = FUPR_ERR_ARG; break;
+      }
+      if (op.res >= 0) { err = FUPR_ERR_ARG; break; }
+      if (tin.H + 2 * op.conv.pad < k || tin.W + 2 * op.conv.pad < k) { err = FUPR_ERR_SHAPE; break; }
+      t.C = tin.C;
+      t.H = out_extent(tin.H, k, op.conv.stride, op.conv.pad);
+      t.W = out_extent(tin.W, k, op.conv.stride, op.conv.pad);
+    } else if (op.kind == FUPR_OP_AVGPOOL) {
+      if (op.res >= 0) { err = FUPR_ERR_ARG; break; }
+      t.C = tin.C;
+      t.H = 1;
+      t.W = 1;
+    } else {
+      err = FUPR_ERR_ARG; break;
+    }
+    t.cs = min_c_stride(t.C, g->dt);
+    m->tensors[i + 1] = t;
+  }
+  if (err != FUPR_OK) {
+    delete m;
+    return err;
+  }
+
+  // Liveness and greedy buffer sharing.
+  const int n = g->n_ops;
+  for (int i = 0; i < n; ++i) {
+    m->tensors[m->ops[i].in].last_use = i;
+    if (m->ops[i].res >= 0) m->tensors[m->ops[i].res].last_use = i;
+  }
+  std::vector<int> holder;  // buffer -> tensor id it holds, -1 = free
+  for (int i = 0; i < n; ++i) {
+    const int tid = i + 1;
+    TensorInfo& t = m->tensors[tid];
+    if (tid == n) {
+      t.buffer = -2;
+    } else {
+      const size_t need = (size_t)t.H * t.W * t.cs;
+      int pick = -1;
+      for (size_t b = 0; b < holder.size(); ++b) {
+        if (holder[b] >= 0) continue;
+        // prefer the free buffer whose size is closest to what is needed
+        if (pick < 0) pick = (int)b;
+        else {
+          const size_t cur = m->buffer_elems[pick], cand = m->buffer_elems[b];
+          const size_t dc = cur > need ? cur - need : need - cur;
+          const size_t dn = cand > need ? cand - need : need - cand;
+          if (dn < dc) pick = (int)b;
+        }
+      }
+      if (pick < 0) {
+        holder.push_back(-1);
+        m->buffer_elems.push_back(0);
+        pick = (int)holder.size() - 1;
+      }
+      holder[pick] = tid;
+      m->buffer_elems[pick] = std::max(m->buffer_elems[pick], need);
+      t.buffer = pick;
+    }
+    // tensors whose last reader is this operator become free afterwards
+    for (size_t b = 0; b < holder.size(); ++b) {
+      const int h = holder[b];
+      if (h >= 0 && h != tid && m->tensors[h].last_use <= i) holder[b] = -1;
+    }
+  }
+  *out = m;
+  return FUPR_OK;
+}
+
+extern "C" void fupr_model_destroy(fupr_model* m) { delete m; }
+
+extern "C" int32_t fupr_model_num_ops(const fupr_model* m) { return m ? (int32_t)m->ops.size() : 0; }
+
+extern "C" size_t fupr_model_workspace_bytes(const fupr_model* m, int32_t batch) {
+  if (!m || batch <= 0) return 0;
+  size_t total = 0;
+  for (size_t e : m->buffer_elems) total += round_up_sz(e * (size_t)batch * elem_size(m->dt), 256);
+  return std::max<size_t>(total, 256);
+}
+
+extern "C" fupr_status fupr_model_output_shape(const fupr_model* m, int32_t batch,
+                                               fupr_tensor* out) {
+  if (!m || !out) return FUPR_ERR_NULL;
+  if (batch <= 0) return FUPR_ERR_SHAPE;
+  const TensorInfo& t = m->tensors.back();
+  out->N = batch;
+  out->H = t.H;
+  out->W = t.W;
+  out->C = t.C;
+  out->c_stride = t.cs;
+  out->dt = m->dt;
+  out->ptr = nullptr;
+  return FUPR_OK;
+}
+
+namespace {
+
+fupr_status run(const fupr_model* m, const fupr_tensor* input, const fupr_tensor* output,
+                void* workspace, size_t workspace_bytes, void* stream, hipEvent_t* events) {
+  if (!m || !input || !output || !workspace) return FUPR_ERR_NULL;
+  if (!input->ptr || !output->ptr) return FUPR_ERR_NULL;
+  if (input->dt != m->dt || output->dt != m->dt) return FUPR_ERR_DTYPE;
+  const TensorInfo& t0 = m->tensors.front();
+  const TensorInfo& tl = m->tensors.back();
+  const int N = input->N;
+  if (N <= 0 || input->C != t0.C || input->H != t0.H || input->W != t0.W) return FUPR_ERR_SHAPE;
+  if (output->N != N || output->C != tl.C || output->H != tl.H || output->W != tl.W)
+    return FUPR_ERR_SHAPE;
+  if (input->c_stride < t0.C || input->c_stride % c_align(m->dt) != 0) return FUPR_ERR_ALIGN;
+  if (output->c_stride < tl.C || output->c_stride % c_align(m->dt) != 0) return FUPR_ERR_ALIGN;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return FUPR_ERR_WORKSPACE;
+  if (workspace_bytes < fupr_model_workspace_bytes(m, N)) return FUPR_ERR_WORKSPACE;
+  for (const TensorInfo& t : m->tensors)
+    if ((int64_t)N * t.H * t.W * t.cs >= (int64_t(1) << 31)) return FUPR_ERR_LIMIT;
+
+  std::vector<char*> base(m->buffer_elems.size());
+  size_t off = 0;
+  for (size_t b = 0; b < base.size(); ++b) {
+    base[b] = reinterpret_cast<char*>(workspace) + off;
+    off += round_up_sz(m->buffer_elems[b] * (size_t)N * elem_size(m->dt), 256);
+  }
+  auto view = [&](int tid) {
+    const TensorInfo& t = m->tensors[tid];
+    fupr_tensor v;
+    v.N = N; v.H = t.H; v.W = t.W; v.C = t.C; v.dt = m->dt;
+    if (t.buffer == -1) { v.c_stride = input->c_stride; v.ptr = input->ptr; }
+    else if (t.buffer == -2) { v.c_stride = output->c_stride; v.ptr = output->ptr; }
+    else { v.c_stride = t.cs; v.ptr = base[t.buffer]; }
+    return v;
+  };
+
+  hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
+  if (events && hipEventRecord(events[0], hs) != hipSuccess) return FUPR_ERR_LAUNCH;
+  for (size_t i = 0; i < m->ops.size(); ++i) {
+    const fupr_op_desc& op = m->ops[i];
+    const fupr_tensor x = view(op.in), y = view((int)i + 1);
+    fupr_status st;
+    if (op.kind == FUPR_OP_CONV) {
+      fupr_residual r;
+      const bool add = op.res >= 0;
+      if (add) {
+        r.t = view(op.res);
+        r.spatial_stride = op.res_spatial_stride;
+        r.c_offset = op.res_c_offset;
+      }
+      st = fupr_conv_fused(&op.conv, &x, op.packed, add ? &r : nullptr, op.epilogue, &y, stream);
+    } else if (op.kind == FUPR_OP_MAXPOOL) {
+      st = fupr_maxpool(&x, op.conv.R, op.conv.stride, op.conv.pad, &y, stream);
+    } else {
+      st = fupr_global_avgpool(&x, &y, stream);
+    }
+    if (st != FUPR_OK) return st;
+    if (events && hipEventRecord(events[i + 1], hs) != hipSuccess) return FUPR_ERR_LAUNCH;
+  }
+  return FUPR_OK;
+}
+
+}  // namespace
+
+extern "C" fupr_status fupr_forward(const fupr_model* m, const fupr_tensor* input,
+                                    const fupr_tensor* output, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+  return run(m, input, output, workspace, workspace_bytes, stream, nullptr);
+}
+
+extern "C" fupr_status fupr_forward_timed(const fupr_model* m, const fupr_tensor* input,
+                                          const fupr_tensor* output, void* workspace,
+                                          size_t workspace_bytes, void* stream, float* op_ms) {
+  if (!m || !op_ms) return FUPR_ERR_NULL;
+  const size_t n = m->ops.size();
+  std::vector<hipEvent_t> ev(n + 1, nullptr);
+  fupr_status st = FUPR_OK;
+  for (size_t i = 0; i <= n; ++i)
+    if (hipEventCreate(&ev[i]) != hipSuccess) { st = FUPR_ERR_LAUNCH; break; }
+  if (st == FUPR_OK) st = run(m, input, output, workspace, workspace_bytes, stream, ev.data());
+  if (st == FUPR_OK && hipStreamSynchronize(reinterpret_cast<hipStream_t>(stream)) != hipSuccess)
+    st = FUPR_ERR_LAUNCH;
+  if (st == FUPR_OK) {
+    std::vector<float> ms(n);
+    for (size_t i = 0; i < n; ++i)
+      if (hipEventElapsedTime(&ms[i], ev[i], ev[i + 1]) != hipSuccess) { st = FUPR_ERR_LAUNCH; break; }
+    if (st == FUPR_OK) std::copy(ms.begin(), ms.end(), op_ms);
+  }
+  for (hipEvent_t e : ev)
+    if (e) (void)hipEventDestroy(e);
+  return st;
+}
+
+extern "C" fupr_status fupr_model_op_stats(const fupr_model* m, int32_t batch, int32_t op,
+                                           fupr_op_stats* out) {
+  if (!m || !out) return FUPR_ERR_NULL;
+  if (batch <= 0 || op < 0 || op >= (int32_t)m->ops.size()) return FUPR_ERR_ARG;
+  const fupr_op_desc& d = m->ops[op];
+  const TensorInfo& ti = m->tensors[d.in];
+  const TensorInfo& to = m->tensors[op + 1];
+  const double es = (double)elem_size(m->dt);
+  fupr_op_stats s{};
+  s.M = (int64_t)batch * to.H * to.W;
+  s.K = to.C;
+  s.C = ti.C;
+  const double in_b = es * batch * (double)ti.H * ti.W * ti.C;
+  const double out_b = es * (double)s.M * to.C;
+  if (d.kind == FUPR_OP_CONV) {
+    s.R = d.conv.R; s.S = d.conv.S; s.stride = d.conv.stride;
+    const double crs = (double)d.conv.C * d.conv.R * d.conv.S;
+    s.flops = 2.0 * crs * d.conv.K * (double)s.M;
+    double res_b = 0.0;
+    if (d.res >= 0) res_b = es * (double)s.M * m->tensors[d.res].C;
+    s.bytes = in_b + out_b + res_b + es * crs * d.conv.K + 4.0 * d.conv.K;
+    s.kernel = conv_kernel_name(d.conv, m->dt, s.M);
+  } else {
+    s.R = s.S = d.kind == FUPR_OP_MAXPOOL ? d.conv.R : ti.H;
+    s.stride = d.kind == FUPR_OP_MAXPOOL ? d.conv.stride : 1;
+    s.flops = 0.0;
+    s.bytes = in_b + out_b;
+    s.kernel = d.kind == FUPR_OP_MAXPOOL ? "maxpool" : "global_avgpool";
+  }
+  *out = s;
+  return FUPR_OK;
+}
+
+extern "C" fupr_status fupr_graph_create(const fupr_model* m, const fupr_tensor* input,
+                                         const fupr_tensor* output, void* workspace,
+                                         size_t workspace_bytes, void* stream, fupr_graph** out) {
+  if (!out) return FUPR_ERR_NULL;
+  if (!stream) return FUPR_ERR_ARG;
+  hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
+  fupr_graph* g = new (std::nothrow) fupr_graph;
+  if (!g) return FUPR_ERR_ARG;
+  if (hipStreamBeginCapture(hs, hipStreamCaptureModeThreadLocal) != hipSuccess) {
+    delete g;
+    return FUPR_ERR_LAUNCH;
+  }
+  const fupr_status st = run(m, input, output, workspace, workspace_bytes, stream, nullptr);
+  const hipError_t e = hipStreamEndCapture(hs, &g->graph);
+  if (st != FUPR_OK || e != hipSuccess || !g->graph) {
+    if (g->graph) (void)hipGraphDestroy(g->graph);
+    delete g;
+    return st != FUPR_OK ? st : FUPR_ERR_LAUNCH;
+  }
+  if (hipGraphInstantiate(&g->exec, g->graph, nullptr, nullptr, 0) != hipSuccess) {
+    (void)hipGraphDestroy(g->graph);
+    delete g;
+    return FUPR_ERR_LAUNCH;
+  }
+  *out = g;
+  return FUPR_OK;
+}
+
+extern "C" fupr_status fupr_graph_launch(const fupr_graph* g, void* stream) {
+  if (!g || !g->exec) return FUPR_ERR_NULL;
+  return hipGraphLaunch(g->exec, reinterpret_cast<hipStream_t>(stream)) == hipSuccess
+             ? FUPR_OK
+             : FUPR_ERR_LAUNCH;
+}
+
+extern "C" void fupr_graph_destroy(fupr_graph* g) {
+  if (!g) return;
+  if (g->exec) (void)hipGraphExecDestroy(g->exec);
+  if (g->graph) (void)hipGraphDestroy(g->graph);
+  delete g;
+}

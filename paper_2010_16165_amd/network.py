@@ -1,0 +1,146 @@
+"""From a pre-trained model description to a runnable fupr model (Sec. IV-A:
+model + fusion options + pruning rates -> optimised model).
+
+Orchestration only: every number is produced by the library calls
+(fupr_select_filters, fupr_fold, fupr_prune, fupr_pack); this module decides
+which call sees which layer and lays the packed blobs out in one buffer.
+The model description is the plain-data format of synth.resnets.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import binding as B
+
+
+class Layer:
+    """One convolution site of the optimised network (host side)."""
+
+    def __init__(self, site, W, bias, stride, pad, relu, add=False):
+        self.site = site
+        self.W = W              # folded, compacted, float32 K x C x R x S
+        self.bias = bias        # float32 K
+        self.stride = stride
+        self.pad = pad
+        self.relu = relu
+        self.add = add
+        self.shape = B.shape_of(W, stride, pad)
+
+
+def _fold(conv, bn):
+    sh = B.shape_of(conv["W"], conv["stride"], conv["pad"])
+    return B.fupr_fold(sh, conv["W"], None, bn["gamma"], bn["beta"], bn["mean"], bn["var"],
+                       bn["eps"], B.FUSE_BN)
+
+
+def optimise(model, norm=1):
+    """Masks from the raw weights, batch norm merged, masked filters removed.
+
+    Returns {"layers": [Layer...], "masks": {(block, conv): uint8 mask},
+             "keep_idx": {(block, conv): int32 indices}, "wiring": [...]}
+    where wiring lists, per operator, what build() needs."""
+    layers, masks, keeps, wiring = [], {}, {}, []
+    stem = model["stem"]
+    if stem is not None:
+        Wf, bf = _fold(stem["conv"], stem["bn"])
+        layers.append(Layer("stem", Wf, bf, stem["conv"]["stride"], stem["conv"]["pad"], True))
+        wiring.append(("conv", len(layers) - 1, None))
+        if stem["maxpool"] is not None:
+            wiring.append(("maxpool", stem["maxpool"], None))
+    for bi, blk in enumerate(model["blocks"]):
+        convs, bns = blk["convs"], blk["bns"]
+        folded = [list(_fold(c, b)) for c, b in zip(convs, bns)]
+        for ci, pm in enumerate(blk["prune_permille"]):
+            if not pm:
+                continue
+            raw = convs[ci]["W"]
+            sh_raw = B.shape_of(raw, convs[ci]["stride"], convs[ci]["pad"])
+            n_prune = B.fupr_prune_count(sh_raw.K, pm)
+            mask = B.fupr_select_filters(sh_raw, raw, norm, n_prune)
+            Wp, bp = folded[ci]
+            Wn = folded[ci + 1][0]
+            prod = B.shape_of(Wp, convs[ci]["stride"], convs[ci]["pad"])
+            cons = B.shape_of(Wn, convs[ci + 1]["stride"], convs[ci + 1]["pad"])
+            keep, Wp_c, bp_c, (Wn_c,) = B.fupr_prune(prod, Wp, bp, mask, [cons], [Wn])
+            folded[ci] = [Wp_c, bp_c]
+            folded[ci + 1][0] = Wn_c
+            masks[(bi, ci)] = mask
+            keeps[(bi, ci)] = keep
+        sc = blk["shortcut"]
+        proj_layer = None
+        if sc["kind"] == "projection":
+            Wf, bf = _fold(sc["conv"], sc["bn"])
+            layers.append(Layer(f"b{bi}.proj", Wf, bf, sc["conv"]["stride"], sc["conv"]["pad"], False))
+            proj_layer = len(layers) - 1
+        first = len(layers)
+        for ci, (Wf, bf) in enumerate(folded):
+            last = ci == len(folded) - 1
+            layers.append(Layer(f"b{bi}.conv{ci + 1}", Wf, bf, convs[ci]["stride"], convs[ci]["pad"],
+                                True, add=last))
+        wiring.append(("block", (proj_layer, first, len(folded)), sc))
+    head = model["head"]
+    if head is not None:
+        wiring.append(("avgpool", None, None))
+        Wfc = np.ascontiguousarray(head["fc_W"][:, :, None, None], dtype=np.float32)
+        layers.append(Layer("fc", Wfc, np.asarray(head["fc_b"], dtype=np.float32), 1, 0, False))
+        wiring.append(("conv", len(layers) - 1, None))
+    return {"layers": layers, "masks": masks, "keep_idx": keeps, "wiring": wiring,
+            "dt": B.DTYPES[model["dtype"]], "in_shape": model["in_shape"]}
+
+
+def build(plan, device="cuda:0"):
+    """Pack every layer, upload one blob, create the fupr model.
+
+    Returns (Model, sites) where sites[i] is the convolution site name of
+    operator i (None for pools)."""
+    dt = plan["dt"]
+    blobs, offsets, total = [], [], 0
+    for L in plan["layers"]:
+        blob = B.fupr_pack(L.shape, L.W, L.bias, dt)
+        offsets.append(total)
+        blobs.append(blob)
+        total += (len(blob) + 255) // 256 * 256
+    host = np.zeros(total, dtype=np.uint8)
+    for off, blob in zip(offsets, blobs):
+        host[off:off + len(blob)] = blob
+    dev = B.upload_blob(host, device)
+    base = dev.data_ptr()
+
+    ops, sites = [], []
+
+    def conv_op(li, tin, res=-1, rss=1, roff=0):
+        L = plan["layers"][li]
+        epi = (B.FUSE_RELU if L.relu else 0) | (B.FUSE_ADD if res >= 0 else 0)
+        ops.append(B.OpDesc(B.OP_CONV, tin, res, L.shape, base + offsets[li], epi, rss, roff))
+        sites.append(L.site)
+        return len(ops)
+
+    cur = 0
+    for kind, a, sc in plan["wiring"]:
+        if kind == "conv":
+            cur = conv_op(a, cur)
+        elif kind == "maxpool":
+            k, st, pd = a
+            ops.append(B.OpDesc(B.OP_MAXPOOL, cur, -1, B.conv_shape(1, 1, k, k, st, pd), None, 0, 1, 0))
+            sites.append(None)
+            cur = len(ops)
+        elif kind == "avgpool":
+            ops.append(B.OpDesc(B.OP_AVGPOOL, cur, -1, B.conv_shape(1, 1, 1, 1, 1, 0), None, 0, 1, 0))
+            sites.append(None)
+            cur = len(ops)
+        else:
+            proj, first, n = a
+            x = cur
+            res, rss = x, 1
+            if sc["kind"] == "projection":
+                res = conv_op(proj, x)
+            elif sc["kind"] == "optionA":
+                rss = sc["stride"]
+            h = x
+            for i in range(n - 1):
+                h = conv_op(first + i, h)
+            cur = conv_op(first + n - 1, h, res, rss, 0)
+    model = B.Model(dt, plan["in_shape"], ops, keepalive=[dev])
+    model.sites = sites
+    model.plan = plan
+    return model, sites

@@ -1,0 +1,372 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.
+
+Tolerances (max-norm relative error, max|gpu - ref| / max|ref|, per tensor):
+2e-2 for bf16 / fp16 storage, 1e-3 for the fp32 path.  Masks and kept-filter
+indices must be identical.
+"""
+import zlib
+
+import numpy as np
+import pytest
+
+import synth
+from oracle import reference as orc
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-3, "bf16": 2e-2, "f16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def fx():
+    import torch
+    from paper_2010_16165_amd import binding as B, network
+    assert torch.cuda.is_available()
+    return B, network, torch
+
+
+def rel_err(got, ref):
+    return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+def round_to(x, dtype, torch):
+    """x rounded once to the storage dtype, as float64 (what the device holds)."""
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32))
+    td = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[dtype]
+    return t.to(td).to(torch.float64).numpy()
+
+
+# ---- single convolution sites -------------------------------------------------
+
+CONV_CASES = [
+    # name, N, C, H, W, K, R, stride, pad, residual kind, relu
+    ("3x3 C16 K12", 2, 16, 32, 32, 12, 3, 1, 1, None, True),
+    ("3x3 C12 K16 +id", 2, 12, 32, 32, 16, 3, 1, 1, "identity", True),
+    ("3x3 C10 K16 s2 +optA", 3, 10, 17, 15, 16, 3, 2, 1, "optionA", True),
+    ("3x3 C39 K64 +id", 2, 39, 8, 8, 64, 3, 1, 1, "identity", True),
+    ("3x3 C64 K45", 1, 64, 28, 28, 45, 3, 1, 1, None, True),
+    ("3x3 C45 K64 ragged M", 1, 45, 13, 11, 64, 3, 1, 1, "identity", True),
+    ("7x7 C3 K64 s2", 2, 3, 64, 64, 64, 7, 2, 3, None, True),
+    ("1x1 C64 K32", 2, 64, 14, 14, 32, 1, 1, 0, None, True),
+    ("1x1 C32 K256 +res norelu", 2, 32, 14, 14, 256, 1, 1, 0, "identity", False),
+    ("1x1 C256 K512 s2 proj", 2, 256, 14, 14, 512, 1, 2, 0, None, False),
+    ("3x3 C180 K256", 1, 180, 14, 14, 256, 3, 1, 1, None, True),
+    ("3x3 C41 K39 irregular", 2, 41, 19, 23, 39, 3, 1, 1, None, True),
+    ("3x3 C227 K193 s2", 1, 227, 15, 15, 193, 3, 2, 1, None, True),
+    ("1x1 fc C64 K10", 5, 64, 1, 1, 10, 1, 1, 0, None, False),
+    ("1x1 fc C512 K1000", 3, 512, 1, 1, 1000, 1, 1, 0, None, False),
+    ("3x3 C1 K1", 1, 1, 5, 5, 1, 3, 1, 1, None, False),
+    ("3x3 C8 K359 tiny image", 1, 8, 3, 3, 359, 3, 1, 1, None, True),
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("case", CONV_CASES, ids=[c[0] for c in CONV_CASES])
+def test_conv_site(fx, case, dtype):
+    B, network, torch = fx
+    name, n, c, h, w, k, r, stride, pad, rkind, relu = case
+    if dtype == "f32" and c * k * r * r > 200000:
+        pytest.skip("fp32 path is exercised on the small shapes")
+    rng = np.random.default_rng(zlib.crc32(name.encode()))
+    print(f"case={name} dtype={dtype}", flush=True)
+    x = rng.standard_normal((n, c, h, w)).astype(np.float32)
+    wt = (rng.standard_normal((k, c, r, r)) * np.sqrt(2.0 / (c * r * r))).astype(np.float32)
+    bn = {"gamma": rng.uniform(0.5, 1.5, k).astype(np.float32),
+          "beta": (rng.standard_normal(k) * 0.1).astype(np.float32),
+          "mean": (rng.standard_normal(k) * 0.1).astype(np.float32),
+          "var": rng.uniform(0.5, 1.5, k).astype(np.float32), "eps": 1e-5}
+    dt = B.DTYPES[dtype]
+    p = (h + 2 * pad - r) // stride + 1
+    q = (w + 2 * pad - r) // stride + 1
+
+    xr = round_to(x, dtype, torch)
+    ref = orc.batchnorm(orc.conv2d(xr, wt, stride, pad), bn)
+    res_arg, res_ref = None, None
+    if rkind == "identity":
+        rs = rng.standard_normal((n, k, p, q)).astype(np.float32)
+        res_ref = round_to(rs, dtype, torch)
+        res_arg = (B.DeviceTensor.from_nchw(rs, dt), 1, 0)
+    elif rkind == "optionA":
+        rc = max(4, (k // 2) // 4 * 4)
+        rs = rng.standard_normal((n, rc, 2 * p, 2 * q)).astype(np.float32)
+        res_ref = orc.shortcut_subsample_pad(round_to(rs, dtype, torch), k, 2)
+        res_arg = (B.DeviceTensor.from_nchw(rs, dt), 2, 0)
+    if res_ref is not None:
+        ref = orc.add(ref, res_ref)
+    if relu:
+        ref = orc.relu(ref)
+
+    sh = B.shape_of(wt, stride, pad)
+    Wf, bf = B.fupr_fold(sh, wt, None, bn["gamma"], bn["beta"], bn["mean"], bn["var"], bn["eps"],
+                         B.FUSE_BN)
+    packed = B.upload_blob(B.fupr_pack(sh, Wf, bf, dt))
+    xd = B.DeviceTensor.from_nchw(x, dt)
+    yd = B.DeviceTensor.empty(n, p, q, k, dt)
+    yd.data.fill_(7.0)   # padding lanes must be overwritten with zeros
+    flags = (B.FUSE_RELU if relu else 0) | (B.FUSE_ADD if res_arg else 0)
+    B.fupr_conv_fused(sh, xd, packed, res_arg, flags, yd)
+    torch.cuda.synchronize()
+    got = yd.to_nchw()
+    assert yd.padding_is_zero()
+    err = rel_err(got, ref)
+    print(f"  max-norm rel err {err:.3e}", flush=True)
+    assert err <= TOL[dtype], (name, dtype, err)
+
+
+def test_identity_weights_copy_input(fx):
+    """x = xconv(x, W~) (Sec. IV-B-1): bit-exact on the device, every dtype."""
+    B, network, torch = fx
+    for dtype in ("bf16", "f16", "f32"):
+        dt = B.DTYPES[dtype]
+        c = 24
+        rng = np.random.default_rng(5)
+        x = rng.standard_normal((2, c, 9, 11)).astype(np.float32)
+        wt = np.zeros((c, c, 3, 3), dtype=np.float32)
+        wt[np.arange(c), np.arange(c), 1, 1] = 1.0
+        sh = B.shape_of(wt, 1, 1)
+        packed = B.upload_blob(B.fupr_pack(sh, wt, None, dt))
+        xd = B.DeviceTensor.from_nchw(x, dt)
+        yd = B.DeviceTensor.empty(2, 9, 11, c, dt)
+        B.fupr_conv_fused(sh, xd, packed, None, 0, yd)
+        torch.cuda.synchronize()
+        assert np.array_equal(yd.to_nchw(), xd.to_nchw()), dtype
+
+
+def test_in_place_identity_residual(fx):
+    """y may be the identity shortcut's own buffer."""
+    B, network, torch = fx
+    dt = B.BF16
+    rng = np.random.default_rng(6)
+    x = rng.standard_normal((2, 16, 8, 8)).astype(np.float32)
+    rs = rng.standard_normal((2, 16, 8, 8)).astype(np.float32)
+    wt = (rng.standard_normal((16, 16, 3, 3)) * 0.1).astype(np.float32)
+    sh = B.shape_of(wt, 1, 1)
+    packed = B.upload_blob(B.fupr_pack(sh, wt, None, dt))
+    xd = B.DeviceTensor.from_nchw(x, dt)
+    y1 = B.DeviceTensor.empty(2, 8, 8, 16, dt)
+    r1 = B.DeviceTensor.from_nchw(rs, dt)
+    B.fupr_conv_fused(sh, xd, packed, (r1, 1, 0), B.FUSE_ADD | B.FUSE_RELU, y1)
+    r2 = B.DeviceTensor.from_nchw(rs, dt)
+    B.fupr_conv_fused(sh, xd, packed, (r2, 1, 0), B.FUSE_ADD | B.FUSE_RELU, r2)
+    torch.cuda.synchronize()
+    assert np.array_equal(y1.to_nchw(), r2.to_nchw())
+
+
+# ---- pools -----------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+def test_maxpool_exact(fx, dtype):
+    B, network, torch = fx
+    dt = B.DTYPES[dtype]
+    rng = np.random.default_rng(8)
+    x = -np.abs(rng.standard_normal((3, 20, 15, 18))).astype(np.float32) - 0.5
+    xd = B.DeviceTensor.from_nchw(x, dt)
+    yd = B.DeviceTensor.empty(3, 8, 9, 20, dt)
+    yd.data.fill_(3.0)
+    B.fupr_maxpool(xd, 3, 2, 1, yd)
+    torch.cuda.synchronize()
+    ref = orc.maxpool(round_to(x, dtype, torch), 3, 2, 1)
+    assert np.array_equal(yd.to_nchw(), ref)
+    assert yd.padding_is_zero()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+def test_global_avgpool(fx, dtype):
+    B, network, torch = fx
+    dt = B.DTYPES[dtype]
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((5, 44, 7, 7)).astype(np.float32) + 1.0
+    xd = B.DeviceTensor.from_nchw(x, dt)
+    yd = B.DeviceTensor.empty(5, 1, 1, 44, dt)
+    B.fupr_global_avgpool(xd, yd)
+    torch.cuda.synchronize()
+    ref = orc.global_mean(round_to(x, dtype, torch))[:, :, None, None]
+    assert rel_err(yd.to_nchw(), ref) <= (1e-5 if dtype == "f32" else 5e-3)
+    assert yd.padding_is_zero()
+
+
+# ---- whole networks ----------------------------------------------------------------
+
+def run_network(B, network, torch, model, x):
+    plan = network.optimise(model)
+    m, sites = network.build(plan)
+    dt = B.DTYPES[model["dtype"]]
+    xd = B.DeviceTensor.from_nchw(x, dt)
+    out, ws = m.alloc(x.shape[0])
+    m.fupr_forward(xd, out, ws)
+    torch.cuda.synchronize()
+    y = out.to_nchw()
+    if model["head"] is not None:
+        y = y[:, :, 0, 0]
+    return plan, m, y
+
+
+def small_models():
+    return [
+        synth.make_block_model(11, "f32", 8, 10, 250),
+        synth.make_cifar_resnet(12, "bf16", 2, 400, widths=(4, 8, 12), size=12),
+        synth.make_imagenet_basic_resnet(13, "bf16", (1, 1, 1, 1), 300, widths=(4, 8, 8, 12), size=32,
+                                         classes=7),
+        synth.make_imagenet_bottleneck_resnet(14, "bf16", (2, 1, 1, 1), 500, widths=(4, 4, 8, 8),
+                                              size=32, classes=5),
+        synth.make_imagenet_bottleneck_resnet(15, "f16", (1, 2, 1, 1), permille_range=(100, 700),
+                                              widths=(8, 8, 8, 12), size=32, classes=5),
+    ]
+
+
+@pytest.mark.parametrize("mi", range(5))
+def test_small_network(fx, mi):
+    B, network, torch = fx
+    model = small_models()[mi]
+    x = synth.make_input(77, 3, model["in_shape"])
+    masks = orc.select_masks(model)
+    ref = orc.forward(model, round_to(x, model["dtype"], torch), masks=masks)
+    plan, m, y = run_network(B, network, torch, model, x)
+    assert set(plan["masks"]) == set(masks)
+    for key in masks:
+        assert np.array_equal(plan["masks"][key], masks[key])
+        assert np.array_equal(plan["keep_idx"][key], np.flatnonzero(masks[key]))
+    err = rel_err(y, ref)
+    print(f"model {mi} {model['name']} end-to-end rel err {err:.3e}", flush=True)
+    assert err <= TOL[model["dtype"]]
+
+
+CONFIG_BATCH = {0: 1, 1: 8, 2: 2, 3: 2, 4: 2}
+
+
+@pytest.mark.parametrize("idx", range(5))
+def test_baseline_config_end_to_end(fx, idx):
+    """The five workloads at their real layer shapes (reduced batch so the
+    oracle finishes in seconds)."""
+    B, network, torch = fx
+    model, _ = synth.make_config(idx)
+    n = CONFIG_BATCH[idx]
+    x = synth.make_input(synth.BASE_SEED + idx, n, model["in_shape"])
+    masks = orc.select_masks(model)
+    print(f"config {idx}: oracle on {n} images", flush=True)
+    ref = orc.forward(model, round_to(x, model["dtype"], torch), masks=masks)
+    plan, m, y = run_network(B, network, torch, model, x)
+    for key in masks:
+        assert np.array_equal(plan["masks"][key], masks[key])
+        assert np.array_equal(plan["keep_idx"][key], np.flatnonzero(masks[key]))
+    assert np.isfinite(y).all()
+    err = rel_err(y, ref)
+    print(f"config {idx} {model['name']} end-to-end rel err {err:.3e}", flush=True)
+    assert err <= TOL[model["dtype"]]
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4])
+def test_baseline_config_teacher_forced(fx, idx):
+    """Every convolution site of the workload alone: the device site is fed
+    the oracle's input (and shortcut) rounded to the storage type and must
+    reproduce the oracle's output of that site."""
+    B, network, torch = fx
+    model, _ = synth.make_config(idx)
+    dtype = model["dtype"]
+    dt = B.DTYPES[dtype]
+    x = synth.make_input(synth.BASE_SEED + idx, 1, model["in_shape"])
+    masks = orc.select_masks(model)
+    trace = []
+    orc.forward(model, round_to(x, dtype, torch), masks=masks, trace=trace)
+    by_site = {t["site"]: t for t in trace}
+    plan = network.optimise(model)
+    # which (block, conv) feeds / is each site, to drop removed channels
+    worst = 0.0
+    for L in plan["layers"]:
+        t = by_site[L.site]
+        xin, res, yref = t["x"], t["res"], t["y"]
+        if L.site == "fc":
+            xin = xin[:, :, None, None]
+            yref = yref[:, :, None, None]
+        if L.site.startswith("b") and ".conv" in L.site:
+            bi = int(L.site[1:].split(".")[0])
+            ci = int(L.site.split("conv")[1]) - 1
+            if (bi, ci - 1) in masks:      # input produced by a pruned conv
+                xin = xin[:, np.flatnonzero(masks[(bi, ci - 1)])]
+            if (bi, ci) in masks:          # this conv lost filters
+                yref = yref[:, np.flatnonzero(masks[(bi, ci)])]
+        packed = B.upload_blob(B.fupr_pack(L.shape, L.W, L.bias, dt))
+        xd = B.DeviceTensor.from_nchw(xin, dt)
+        n, k, p, q = yref.shape
+        yd = B.DeviceTensor.empty(n, p, q, k, dt)
+        res_arg = None
+        if res is not None:
+            res_arg = (B.DeviceTensor.from_nchw(res, dt), 1, 0)
+        flags = (B.FUSE_RELU if L.relu else 0) | (B.FUSE_ADD if res_arg else 0)
+        B.fupr_conv_fused(L.shape, xd, packed, res_arg, flags, yd)
+        torch.cuda.synchronize()
+        err = rel_err(yd.to_nchw(), yref)
+        worst = max(worst, err)
+        assert err <= TOL[dtype], (L.site, err)
+    print(f"config {idx}: worst site rel err {worst:.3e} over {len(plan['layers'])} sites", flush=True)
+
+
+def test_forward_is_deterministic_and_graph_replays(fx):
+    B, network, torch = fx
+    model = synth.make_cifar_resnet(21, "bf16", 3, 400)
+    x = synth.make_input(21, 4, model["in_shape"])
+    plan = network.optimise(model)
+    m, _ = network.build(plan)
+    xd = B.DeviceTensor.from_nchw(x, B.BF16)
+    out, ws = m.alloc(4)
+    m.fupr_forward(xd, out, ws)
+    torch.cuda.synchronize()
+    first = out.data.clone()
+    m.fupr_forward(xd, out, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(first, out.data)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        out2, ws2 = m.alloc(4)
+        s.synchronize()
+        g = m.fupr_graph_create(xd, out2, ws2, B.C.c_void_p(s.cuda_stream))
+        for _ in range(3):
+            out2.data.zero_()
+            s.synchronize()
+            m.fupr_graph_launch(g, B.C.c_void_p(s.cuda_stream))
+            s.synchronize()
+            assert torch.equal(first, out2.data)
+
+
+def test_timed_forward_and_stats(fx):
+    B, network, torch = fx
+    model = synth.make_cifar_resnet(22, "bf16", 2, 400)
+    x = synth.make_input(22, 2, model["in_shape"])
+    plan = network.optimise(model)
+    m, sites = network.build(plan)
+    xd = B.DeviceTensor.from_nchw(x, B.BF16)
+    out, ws = m.alloc(2)
+    ms = m.fupr_forward_timed(xd, out, ws)
+    assert ms.shape == (m.num_ops,) and (ms > 0).all()
+    st = m.op_stats(2, 0)
+    assert st["flops"] == 2.0 * 3 * 9 * 16 * 2 * 32 * 32 and st["kernel"].startswith("conv16")
+
+
+# ---- error paths on device calls (nothing is launched) ------------------------------
+
+def test_device_call_errors(fx):
+    B, network, torch = fx
+    dt = B.BF16
+    wt = np.zeros((16, 16, 3, 3), dtype=np.float32)
+    sh = B.shape_of(wt, 1, 1)
+    packed = B.upload_blob(B.fupr_pack(sh, wt, None, dt))
+    x = B.DeviceTensor.empty(1, 8, 8, 16, dt)
+    y = B.DeviceTensor.empty(1, 8, 8, 16, dt)
+    y.data.fill_(5.0)
+
+    def expect(code, fn):
+        with pytest.raises(B.FuprError) as e:
+            fn()
+        assert e.value.status == code
+
+    bad_y = B.DeviceTensor.empty(1, 7, 8, 16, dt)
+    expect(B.ERR_SHAPE, lambda: B.fupr_conv_fused(sh, x, packed, None, 0, bad_y))
+    expect(B.ERR_NULL, lambda: B.fupr_conv_fused(sh, x, packed, None, B.FUSE_ADD, y))
+    expect(B.ERR_ARG, lambda: B.fupr_conv_fused(sh, x, packed, (x, 1, 0), 0, y))
+    expect(B.ERR_ARG, lambda: B.fupr_conv_fused(sh, x, packed, None, 64, y))
+    expect(B.ERR_DTYPE, lambda: B.fupr_conv_fused(sh, x, packed, None, 0,
+                                                  B.DeviceTensor.empty(1, 8, 8, 16, B.F16)))
+    expect(B.ERR_ARG, lambda: B.fupr_conv_fused(sh, x, packed, None, 0, x))
+    torch.cuda.synchronize()
+    assert bool((y.data == 5.0).all())
