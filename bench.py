@@ -1,0 +1,169 @@
+"""Throughput of the fused + pruned ResNet forward pass on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--batch B]
+
+A step is one forward pass of the whole optimised network (every convolution
+with its fused epilogue, pools, fc) over one batch already resident in HBM,
+replayed from a HIP graph on one stream.  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_16BIT = 2.5e15   # dense bf16 / fp16 MFMA, FLOP/s
+PEAK_FP32 = 157.3e12       # fp32 vector, FLOP/s
+PEAK_HBM = 8.0e12          # B/s
+
+
+def cpu_baseline(model, batch, budget_s=15.0):
+    """The CPU oracle (unfused, zero-masked, double precision) timed on the host
+    cores over a bounded number of images of the same workload."""
+    import synth
+    from oracle import reference as orc
+    masks = orc.select_masks(model)
+    seed = synth.BASE_SEED + model.get("config_index", 0)
+    x1 = synth.make_input(seed, 1, model["in_shape"])
+    orc.forward(model, x1, masks=masks)            # warm-up (library load, page faults)
+    t0 = time.perf_counter()
+    orc.forward(model, x1, masks=masks)
+    t1 = time.perf_counter() - t0
+    n = int(max(1, min(batch, budget_s / max(t1, 1e-6))))
+    x = synth.make_input(seed, n, model["in_shape"])
+    t0 = time.perf_counter()
+    orc.forward(model, x, masks=masks)
+    dt = time.perf_counter() - t0
+    return {"value": n / dt, "unit": "images/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"{n} of {batch} images of the workload, one pass, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=1)
+    ap.add_argument("--batch", type=int, default=0)
+    ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--per-op", action="store_true", help="print a per-operator table to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: images are independent, so N GPUs would each run "
+                 "this same forward pass on their share of the batch; run with --gpus 1")
+
+    import numpy as np
+    import torch
+    import synth
+    from paper_2010_16165_amd import binding as B, network
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    model, batch = synth.make_config(args.config)
+    if args.batch:
+        batch = args.batch
+    dt = B.DTYPES[model["dtype"]]
+    plan = network.optimise(model)
+    fm, sites = network.build(plan)
+    x = synth.make_input(synth.BASE_SEED + args.config, batch, model["in_shape"])
+    xd = B.DeviceTensor.from_nchw(x, dt)
+
+    stream = torch.cuda.Stream()
+    sp = B.C.c_void_p(stream.cuda_stream)
+    with torch.cuda.stream(stream):
+        out, ws = fm.alloc(batch)
+        stream.synchronize()
+        graph = None if args.no_graph else fm.fupr_graph_create(xd, out, ws, sp)
+
+        def step():
+            if graph is None:
+                fm.fupr_forward(xd, out, ws, sp)
+            else:
+                fm.fupr_graph_launch(graph, sp)
+
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+
+        # per-operator durations from HIP events on the same stream
+        reps = 20
+        fm.fupr_forward_timed(xd, out, ws, sp)
+        op_ms = np.zeros(fm.num_ops)
+        for _ in range(reps):
+            op_ms += fm.fupr_forward_timed(xd, out, ws, sp)
+        op_ms /= reps
+
+    ms_per_step = elapsed / args.steps * 1e3
+    stats = [fm.op_stats(batch, i) for i in range(fm.num_ops)]
+    total_flops = sum(s["flops"] for s in stats)
+    total_bytes = sum(s["bytes"] for s in stats)
+    images_per_s = batch / (ms_per_step * 1e-3)
+    tflops = total_flops / (ms_per_step * 1e-3) / 1e12
+
+    groups = {}
+    for s, ms in zip(stats, op_ms):
+        g = groups.setdefault(s["kernel"], {"ms": 0.0, "flops": 0.0, "bytes": 0.0, "launches": 0})
+        g["ms"] += ms
+        g["flops"] += s["flops"]
+        g["bytes"] += s["bytes"]
+        g["launches"] += 1
+    dom_name, dom = max(groups.items(), key=lambda kv: kv[1]["ms"])
+    peak_flops = PEAK_FP32 if dt == B.F32 else PEAK_MFMA_16BIT
+    ridge = peak_flops / PEAK_HBM
+    if dom["flops"] / dom["bytes"] >= ridge:
+        roof = {"bound": "mfma" if dt != B.F32 else "alu",
+                "achieved": dom["flops"] / (dom["ms"] * 1e-3) / 1e12,
+                "peak": peak_flops / 1e12, "unit": "TFLOP/s"}
+    else:
+        roof = {"bound": "hbm", "achieved": dom["bytes"] / (dom["ms"] * 1e-3) / 1e9,
+                "peak": PEAK_HBM / 1e9, "unit": "GB/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = dom_name
+    roof["launches_per_step"] = dom["launches"]
+    roof["avg_launch_us"] = dom["ms"] / dom["launches"] * 1e3
+    roof["algorithmic_bytes_per_launch"] = dom["bytes"] / dom["launches"]
+    roof["algorithmic_flops_per_launch"] = dom["flops"] / dom["launches"]
+
+    if args.per_op:
+        print(f"{'op':>3} {'site':<12} {'kernel':<16} {'M':>9} {'C':>5} {'K':>5} RxS/s "
+              f"{'us':>8} {'GFLOP':>8} {'MB':>8} {'TF/s':>7} {'GB/s':>7}", file=sys.stderr)
+        for i, (s, ms) in enumerate(zip(stats, op_ms)):
+            print(f"{i:>3} {str(sites[i]):<12} {s['kernel']:<16} {s['M']:>9} {s['C']:>5} {s['K']:>5} "
+                  f"{s['R']}x{s['S']}/{s['stride']} {ms * 1e3:>8.1f} {s['flops'] / 1e9:>8.3f} "
+                  f"{s['bytes'] / 1e6:>8.2f} {s['flops'] / ms / 1e9:>7.1f} {s['bytes'] / ms / 1e6:>7.0f}",
+                  file=sys.stderr)
+        print(f"sum of per-op event times {op_ms.sum() * 1e3:.1f} us; graph step {ms_per_step * 1e3:.1f} us",
+              file=sys.stderr)
+
+    line = {
+        "metric": "images_per_sec_fused_pruned_resnet_fwd",
+        "value": images_per_s, "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": model["dtype"], "data": "synthetic",
+        "config": {"workload": model["name"], "config_index": args.config, "batch": batch,
+                   "conv_launches": sum(1 for s in sites if s), "hip_graph": graph is not None},
+        "tflops": tflops, "mfma_frac": tflops * 1e12 / peak_flops,
+        "algorithmic_gflop_per_step": total_flops / 1e9,
+        "algorithmic_mb_per_step": total_bytes / 1e6,
+        "hbm_frac_network": total_bytes / (ms_per_step * 1e-3) / PEAK_HBM,
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(model, batch)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,389 @@
+"""CPU tests of the library's host side: the C-ABI surface, batch-norm merge,
+filter selection, filter removal, packing, model planning and error paths.
+No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import synth
+from oracle import reference as orc
+from paper_2010_16165_amd import binding as B, network
+
+RNG = np.random.default_rng(3)
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def rand_bn(k):
+    f = lambda a: np.asarray(a, dtype=np.float32)
+    return {"gamma": f(RNG.uniform(0.5, 1.5, k)), "beta": f(RNG.standard_normal(k) * 0.1),
+            "mean": f(RNG.standard_normal(k) * 0.1), "var": f(RNG.uniform(0.5, 1.5, k)), "eps": 1e-5}
+
+
+# ---- C ABI surface ------------------------------------------------------------
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "fupr.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(fupr_[a-z_0-9]+)\s*\(", header))
+    assert len(declared) >= 20
+    lib = C.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert declared == set(B.SIGNATURES), declared ^ set(B.SIGNATURES)
+
+
+def test_status_strings():
+    for code in range(0, -11, -1):
+        assert B.status_str(code) not in ("", "unknown status")
+    assert B.status_str(-99) == "unknown status"
+
+
+# ---- fold (Eq. 3-5 and the merge) -------------------------------------------------
+
+def test_fold_matches_closed_form():
+    w = RNG.standard_normal((6, 5, 3, 3)).astype(np.float32)
+    bn = rand_bn(6)
+    sh = B.shape_of(w, 1, 1)
+    wf, bf = B.fupr_fold(sh, w, None, bn["gamma"], bn["beta"], bn["mean"], bn["var"], bn["eps"],
+                         B.FUSE_BN)
+    wo, bo = orc.fold(w, bn)
+    assert wf.dtype == np.float32 and bf.dtype == np.float32
+    np.testing.assert_allclose(wf, wo, rtol=2 ** -23)
+    np.testing.assert_allclose(bf, bo, rtol=2 ** -22, atol=1e-9)
+
+
+def test_fold_then_conv_equals_conv_then_bn():
+    x = RNG.standard_normal((2, 5, 7, 7))
+    w = RNG.standard_normal((6, 5, 3, 3)).astype(np.float32)
+    bn = rand_bn(6)
+    cb = RNG.standard_normal(6).astype(np.float32)
+    sh = B.shape_of(w, 1, 1)
+    wf, bf = B.fupr_fold(sh, w, cb, bn["gamma"], bn["beta"], bn["mean"], bn["var"], bn["eps"],
+                         B.FUSE_BN)
+    ref = orc.batchnorm(orc.conv2d(x, w, 1, 1) + cb[None, :, None, None].astype(np.float64), bn)
+    got = orc.conv2d(x, wf, 1, 1) + bf[None, :, None, None].astype(np.float64)
+    assert np.abs(got - ref).max() / np.abs(ref).max() <= 1e-5
+
+
+def test_fold_identity_special_case_is_exact():
+    k = 4
+    var = RNG.uniform(0.5, 1.5, k).astype(np.float32)
+    mean = RNG.standard_normal(k).astype(np.float32)
+    # gamma = sqrt(var + eps) in double, eps = 0 so that omega is exactly 1 for perfect squares
+    var = (np.arange(1, k + 1, dtype=np.float32)) ** 2
+    gamma = np.arange(1, k + 1, dtype=np.float32)
+    w = RNG.standard_normal((k, 3, 3, 3)).astype(np.float32)
+    sh = B.shape_of(w, 1, 1)
+    wf, bf = B.fupr_fold(sh, w, None, gamma, mean, mean, var, 0.0, B.FUSE_BN)
+    assert np.array_equal(wf, w) and np.all(bf == 0)
+
+
+def test_fold_without_bn_flag_copies():
+    w = RNG.standard_normal((3, 2, 1, 1)).astype(np.float32)
+    b = RNG.standard_normal(3).astype(np.float32)
+    sh = B.shape_of(w, 1, 0)
+    wf, bf = B.fupr_fold(sh, w, b, None, None, None, None, 1e-5, 0)
+    assert np.array_equal(wf, w) and np.array_equal(bf, b)
+    wf, bf = B.fupr_fold(sh, w, None, None, None, None, None, 1e-5, B.FUSE_RELU)
+    assert np.all(bf == 0)
+
+
+def expect(code, fn):
+    with pytest.raises(B.FuprError) as e:
+        fn()
+    assert e.value.status == code, (e.value.status, code)
+
+
+def test_fold_errors_leave_outputs_untouched():
+    w = np.ones((2, 2, 1, 1), dtype=np.float32)
+    bn = rand_bn(2)
+    sh = B.shape_of(w, 1, 0)
+    bad_var = np.array([1.0, -1.0], dtype=np.float32)
+    expect(B.ERR_BN_VAR, lambda: B.fupr_fold(sh, w, None, bn["gamma"], bn["beta"], bn["mean"],
+                                             bad_var, 1e-5, B.FUSE_BN))
+    expect(B.ERR_BN_VAR, lambda: B.fupr_fold(sh, w, None, bn["gamma"], bn["beta"], bn["mean"],
+                                             np.array([1.0, np.inf], dtype=np.float32), 1e-5,
+                                             B.FUSE_BN))
+    expect(B.ERR_NULL, lambda: B.fupr_fold(sh, w, None, None, bn["beta"], bn["mean"], bn["var"],
+                                           1e-5, B.FUSE_BN))
+    expect(B.ERR_ARG, lambda: B.fupr_fold(sh, w, None, bn["gamma"], bn["beta"], bn["mean"],
+                                          bn["var"], 1e-5, 128))
+    expect(B.ERR_SHAPE, lambda: B.fupr_fold(B.conv_shape(0, 2, 1, 1, 1, 0), w, None, bn["gamma"],
+                                            bn["beta"], bn["mean"], bn["var"], 1e-5, B.FUSE_BN))
+    # raw call: outputs keep their sentinel on error
+    wout = np.full(4, 9.0, dtype=np.float32)
+    bout = np.full(2, 9.0, dtype=np.float32)
+    F = B._F
+    st = B._lib.fupr_fold(C.byref(sh), w.ctypes.data_as(F), None, bn["gamma"].ctypes.data_as(F),
+                          bn["beta"].ctypes.data_as(F), bn["mean"].ctypes.data_as(F),
+                          bad_var.ctypes.data_as(F), C.c_float(1e-5), B.FUSE_BN,
+                          wout.ctypes.data_as(F), bout.ctypes.data_as(F))
+    assert st == B.ERR_BN_VAR and np.all(wout == 9.0) and np.all(bout == 9.0)
+
+
+# ---- filter selection ------------------------------------------------------------------
+
+@pytest.mark.parametrize("n,permille", [(16, 250), (16, 400), (32, 400), (64, 400), (64, 300),
+                                        (128, 300), (256, 300), (512, 300), (64, 500), (4, 1000),
+                                        (7, 0), (1, 999), (2048, 137)])
+def test_prune_count_matches_oracle(n, permille):
+    assert B.fupr_prune_count(n, permille) == orc.prune_count(n, permille)
+
+
+def test_prune_count_errors():
+    expect(B.ERR_ARG, lambda: B.fupr_prune_count(0, 100))
+    expect(B.ERR_ARG, lambda: B.fupr_prune_count(8, 1001))
+    expect(B.ERR_ARG, lambda: B.fupr_prune_count(8, -1))
+
+
+@pytest.mark.parametrize("norm", [1, 2])
+def test_select_filters_bit_exact_vs_oracle(norm):
+    for k, c, r in [(16, 16, 3), (64, 3, 7), (39, 64, 3), (256, 64, 1), (5, 1, 1)]:
+        w = RNG.standard_normal((k, c, r, r)).astype(np.float32)
+        for n_prune in (0, 1, k // 3, k - 1):
+            got = B.fupr_select_filters(B.shape_of(w, 1, 0), w, norm, n_prune)
+            assert np.array_equal(got, orc.select_mask(w, n_prune, norm))
+            assert int(got.sum()) == k - n_prune
+
+
+def test_select_filters_tie_rule_and_norm_choice():
+    w = np.ones((6, 2, 3, 3), dtype=np.float32)
+    assert list(B.fupr_select_filters(B.shape_of(w, 1, 1), w, 1, 2)) == [0, 0, 1, 1, 1, 1]
+    w = np.zeros((2, 4, 1, 1), dtype=np.float32)
+    w[0, :, 0, 0] = 1
+    w[1, 0, 0, 0] = 3
+    sh = B.shape_of(w, 1, 0)
+    assert list(B.fupr_select_filters(sh, w, 1, 1)) == [1, 0]
+    assert list(B.fupr_select_filters(sh, w, 2, 1)) == [0, 1]
+    expect(B.ERR_ARG, lambda: B.fupr_select_filters(sh, w, 3, 1))
+    expect(B.ERR_ARG, lambda: B.fupr_select_filters(sh, w, 1, 2))
+    expect(B.ERR_ARG, lambda: B.fupr_select_filters(sh, w, 1, -1))
+
+
+@pytest.mark.parametrize("idx", [0, 1, 2, 3, 4])
+def test_masks_of_baseline_configs_match_oracle(idx):
+    model, _ = synth.make_config(idx)
+    plan = network.optimise(model)
+    masks = orc.select_masks(model)
+    assert set(plan["masks"]) == set(masks) and masks
+    for key, m in masks.items():
+        assert np.array_equal(plan["masks"][key], m)
+        assert np.array_equal(plan["keep_idx"][key], np.flatnonzero(m))
+        assert plan["keep_idx"][key].dtype == np.int32
+
+
+# ---- filter removal -----------------------------------------------------------------------
+
+def test_prune_is_an_exact_gather():
+    wp = RNG.standard_normal((9, 4, 3, 3)).astype(np.float32)
+    bp = RNG.standard_normal(9).astype(np.float32)
+    wc1 = RNG.standard_normal((7, 9, 3, 3)).astype(np.float32)
+    wc2 = RNG.standard_normal((5, 9, 1, 1)).astype(np.float32)
+    mask = np.array([1, 0, 1, 1, 0, 0, 1, 0, 1], dtype=np.uint8)
+    keep, wpo, bpo, (w1o, w2o) = B.fupr_prune(B.shape_of(wp, 1, 1), wp, bp, mask,
+                                              [B.shape_of(wc1, 1, 1), B.shape_of(wc2, 2, 0)],
+                                              [wc1, wc2])
+    idx = [0, 2, 3, 6, 8]
+    assert list(keep) == idx
+    # gather written out by hand
+    for j, k in enumerate(idx):
+        assert wpo[j].tobytes() == wp[k].tobytes() and bpo[j] == bp[k]
+        for f in range(7):
+            assert w1o[f, j].tobytes() == wc1[f, k].tobytes()
+        for f in range(5):
+            assert w2o[f, j].tobytes() == wc2[f, k].tobytes()
+    assert wpo.shape == (5, 4, 3, 3) and w1o.shape == (7, 5, 3, 3) and w2o.shape == (5, 5, 1, 1)
+
+
+def test_prune_without_bias_or_consumers():
+    wp = RNG.standard_normal((4, 2, 1, 1)).astype(np.float32)
+    keep, wpo, bpo, rest = B.fupr_prune(B.shape_of(wp, 1, 0), wp, None, [0, 1, 1, 0], [], [])
+    assert list(keep) == [1, 2] and bpo is None and rest == [] and np.array_equal(wpo, wp[1:3])
+
+
+def test_prune_and_fold_commute():
+    """Per-filter scaling commutes with the gather: bit-exact either way round."""
+    w1 = RNG.standard_normal((8, 3, 3, 3)).astype(np.float32)
+    w2 = RNG.standard_normal((6, 8, 3, 3)).astype(np.float32)
+    bn1, bn2 = rand_bn(8), rand_bn(6)
+    s1, s2 = B.shape_of(w1, 1, 1), B.shape_of(w2, 1, 1)
+    mask = B.fupr_select_filters(s1, w1, 1, 3)
+    fold = lambda sh, w, bn: B.fupr_fold(sh, w, None, bn["gamma"], bn["beta"], bn["mean"],
+                                         bn["var"], bn["eps"], B.FUSE_BN)
+    # fold, then prune
+    w1f, b1f = fold(s1, w1, bn1)
+    w2f, b2f = fold(s2, w2, bn2)
+    _, a1, ab1, (a2,) = B.fupr_prune(s1, w1f, b1f, mask, [s2], [w2f])
+    # prune, then fold
+    keep, p1, _, (p2,) = B.fupr_prune(s1, w1, None, mask, [s2], [w2])
+    bn1k = {k: (v[keep] if k != "eps" else v) for k, v in bn1.items()}
+    c1, cb1 = fold(B.shape_of(p1, 1, 1), p1, bn1k)
+    c2, _ = fold(B.shape_of(p2, 1, 1), p2, bn2)
+    assert np.array_equal(a1, c1) and np.array_equal(ab1, cb1) and np.array_equal(a2, c2)
+
+
+def test_prune_errors():
+    wp = np.ones((4, 2, 1, 1), dtype=np.float32)
+    sh = B.shape_of(wp, 1, 0)
+    wc = np.ones((3, 4, 1, 1), dtype=np.float32)
+    expect(B.ERR_MASK_EMPTY, lambda: B.fupr_prune(sh, wp, None, [0, 0, 0, 0], [], []))
+    expect(B.ERR_ARG, lambda: B.fupr_prune(sh, wp, None, [1, 2, 0, 0], [], []))
+    bad = B.conv_shape(3, 5, 1, 1, 1, 0)     # consumer C != producer K
+    expect(B.ERR_SHAPE, lambda: B.fupr_prune(sh, wp, None, [1, 1, 0, 0], [bad], [wc]))
+
+
+def test_library_compaction_equals_oracle_extraction():
+    """The thinner model the library builds is the oracle's `extract` of the
+    merged weights, filter for filter."""
+    model = synth.make_imagenet_bottleneck_resnet(14, "bf16", (2, 1, 1, 1), 500, widths=(4, 4, 8, 8),
+                                                  size=32, classes=5)
+    plan = network.optimise(model)
+    thin = orc.extract(model, orc.select_masks(model))
+    by_site = {L.site: L for L in plan["layers"]}
+    for bi, blk in enumerate(thin["blocks"]):
+        for ci, (conv, bn) in enumerate(zip(blk["convs"], blk["bns"])):
+            L = by_site[f"b{bi}.conv{ci + 1}"]
+            wo, bo = orc.fold(conv["W"], bn)
+            assert L.W.shape == wo.shape
+            np.testing.assert_allclose(L.W, wo, rtol=2 ** -23)
+            np.testing.assert_allclose(L.bias, bo, rtol=2 ** -22, atol=1e-9)
+
+
+# ---- packing ---------------------------------------------------------------------------------
+
+def bf16_bits_rne(a):
+    u = np.asarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = u + 0x7FFF + ((u >> 16) & 1)
+    return (u >> 16).astype(np.uint16)
+
+
+@pytest.mark.parametrize("k,c,r", [(10, 16, 3), (16, 10, 3), (64, 3, 7), (39, 64, 3), (1000, 20, 1),
+                                   (1, 1, 1)])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_pack_16bit_layout(k, c, r, dtype):
+    w = RNG.standard_normal((k, c, r, r)).astype(np.float32)
+    b = RNG.standard_normal(k).astype(np.float32)
+    sh = B.shape_of(w, 1, r // 2)
+    blob = B.fupr_pack(sh, w, b, B.DTYPES[dtype])
+    kp, cp = (k + 15) // 16 * 16, (c + 7) // 8 * 8
+    nchunk = r * r * cp // 8
+    nchunk_pad = (nchunk + 3) // 4 * 4
+    woff = (kp * 4 + 255) // 256 * 256
+    assert len(blob) == (woff + nchunk_pad * kp * 16 + 255) // 256 * 256 == B.fupr_packed_bytes(
+        sh, B.DTYPES[dtype])
+    bias = blob[:kp * 4].view(np.float32)
+    assert np.array_equal(bias[:k], b) and np.all(bias[k:] == 0)
+    wt = blob[woff:woff + nchunk_pad * kp * 16].view(np.uint16).reshape(nchunk_pad, kp, 8)
+    expect_bits = np.zeros((nchunk_pad, kp, 8), dtype=np.uint16)
+    bits = bf16_bits_rne(w) if dtype == "bf16" else w.astype(np.float16).view(np.uint16)
+    for rr in range(r):
+        for ss in range(r):
+            for cc in range(c):
+                expect_bits[(rr * r + ss) * (cp // 8) + cc // 8, :k, cc % 8] = bits[:, cc, rr, ss]
+    assert np.array_equal(wt, expect_bits)
+
+
+def test_pack_16bit_rounding_edge_cases():
+    vals = np.array([1.0, 1.00390625, 1.01171875, 65519.9, 65520.0, 1e-8, 5.96e-8, 6.1e-5, -0.0,
+                     3.0e-5, np.inf, 70000.0], dtype=np.float32)
+    w = np.zeros((1, 16, 1, 1), dtype=np.float32)
+    w[0, :len(vals), 0, 0] = vals
+    sh = B.shape_of(w, 1, 0)
+    for dtype in ("bf16", "f16"):
+        blob = B.fupr_pack(sh, w, None, B.DTYPES[dtype])
+        wt = blob[256:256 + 4 * 16 * 16].view(np.uint16).reshape(4, 16, 8)
+        got = np.concatenate([wt[0, 0], wt[1, 0]])
+        with np.errstate(over="ignore"):
+            want = bf16_bits_rne(w[0, :, 0, 0]) if dtype == "bf16" else \
+                w[0, :, 0, 0].astype(np.float16).view(np.uint16)
+        assert np.array_equal(got, want), dtype
+
+
+def test_pack_f32_layout():
+    k, c, r = 10, 6, 3
+    w = RNG.standard_normal((k, c, r, r)).astype(np.float32)
+    sh = B.shape_of(w, 1, 1)
+    blob = B.fupr_pack(sh, w, None, B.F32)
+    kp, cp = 12, 8
+    assert len(blob) == 256 + (r * r * cp * kp * 4 + 255) // 256 * 256
+    assert np.all(blob[:kp * 4].view(np.float32) == 0)
+    wt = blob[256:256 + r * r * cp * kp * 4].view(np.float32).reshape(r * r, cp, kp)
+    want = np.zeros((r * r, cp, kp), dtype=np.float32)
+    want[:, :c, :k] = w.transpose(2, 3, 1, 0).reshape(r * r, c, k)
+    assert np.array_equal(wt, want)
+
+
+def test_pack_errors():
+    assert B.fupr_packed_bytes(B.conv_shape(0, 1, 1, 1, 1, 0), B.BF16) == 0
+    assert B.fupr_packed_bytes(B.conv_shape(1, 1, 1, 1, 1, 0), 7) == 0
+    w = np.zeros((1, 1, 1, 1), dtype=np.float32)
+    st = B._lib.fupr_pack(C.byref(B.conv_shape(1, 1, 1, 1, 1, 0)), w.ctypes.data_as(B._F), None, 7,
+                          C.c_void_p(w.ctypes.data))
+    assert st == B.ERR_DTYPE
+    st = B._lib.fupr_pack(C.byref(B.conv_shape(1, 1, 1, 1, 1, 0)), None, None, B.BF16,
+                          C.c_void_p(w.ctypes.data))
+    assert st == B.ERR_NULL
+
+
+# ---- model planning (host only; device pointers are never dereferenced) -----------------------
+
+def fake_ops(specs):
+    """specs: (kind, in, res, K, C, R, stride, pad, epilogue, rss)"""
+    ops = []
+    for kind, tin, res, k, c, r, st, pd, epi, rss in specs:
+        ops.append(B.OpDesc(kind, tin, res, B.conv_shape(k, c, r, r, st, pd), 0x1000, epi, rss, 0))
+    return ops
+
+
+def test_model_plan_shares_buffers_and_reports_shapes():
+    ops = fake_ops([
+        (B.OP_CONV, 0, -1, 16, 3, 3, 1, 1, B.FUSE_RELU, 1),                  # t1 16x32x32
+        (B.OP_CONV, 1, -1, 10, 16, 3, 1, 1, B.FUSE_RELU, 1),                 # t2
+        (B.OP_CONV, 2, 1, 16, 10, 3, 1, 1, B.FUSE_RELU | B.FUSE_ADD, 1),     # t3 (+t1)
+        (B.OP_CONV, 3, -1, 20, 16, 3, 2, 1, B.FUSE_RELU, 1),                 # t4 20x16x16
+        (B.OP_CONV, 4, 3, 32, 20, 3, 1, 1, B.FUSE_RELU | B.FUSE_ADD, 2),     # t5 32x16x16 (+t3 ::2)
+        (B.OP_AVGPOOL, 5, -1, 1, 1, 1, 1, 0, 0, 1),
+        (B.OP_CONV, 6, -1, 10, 32, 1, 1, 0, 0, 1),
+    ])
+    m = B.Model(B.BF16, (3, 32, 32), ops, None)
+    assert m.num_ops == 7
+    t = m.output_shape(5)
+    assert (t.N, t.H, t.W, t.C, t.c_stride) == (5, 1, 1, 10, 16)
+    # three live 16-channel 32x32 tensors at most -> three buffers of 32 KB per image
+    assert m.workspace_bytes(1) == 3 * 32 * 32 * 16 * 2
+    assert m.workspace_bytes(4) == 4 * m.workspace_bytes(1)
+    s = m.op_stats(2, 2)
+    assert s["flops"] == 2.0 * 10 * 9 * 16 * 2 * 1024
+    assert s["bytes"] == 2 * (2 * 1024 * 10 + 2 * 1024 * 16 + 2 * 1024 * 16 + 16 * 10 * 9) + 4 * 16
+    assert s["kernel"].startswith("conv16")
+
+
+def test_model_create_errors():
+    ok = (B.OP_CONV, 0, -1, 16, 3, 3, 1, 1, B.FUSE_RELU, 1)
+    cases = [
+        ([(B.OP_CONV, 0, -1, 16, 4, 3, 1, 1, 0, 1)], B.ERR_SHAPE),             # C mismatch
+        ([ok, (B.OP_CONV, 2, -1, 16, 16, 3, 1, 1, 0, 1)], B.ERR_ARG),          # reads a later tensor
+        ([ok, (B.OP_CONV, 1, 0, 16, 16, 3, 1, 1, 0, 1)], B.ERR_ARG),           # res without ADD
+        ([ok, (B.OP_CONV, 1, -1, 16, 16, 3, 1, 1, B.FUSE_ADD, 1)], B.ERR_ARG),  # ADD without res
+        ([ok, (B.OP_CONV, 1, 0, 16, 16, 3, 2, 1, B.FUSE_ADD, 3)], B.ERR_SHAPE),  # residual too small
+        ([ok, (7, 1, -1, 1, 1, 1, 1, 0, 0, 1)], B.ERR_ARG),                    # unknown kind
+        ([ok, (B.OP_MAXPOOL, 1, -1, 1, 1, 3, 2, 3, 0, 1)], B.ERR_ARG),         # pad >= window
+        ([(B.OP_CONV, 0, -1, 16, 3, 40, 1, 1, 0, 1)], B.ERR_SHAPE),            # window larger than image
+    ]
+    for specs, code in cases:
+        expect(code, lambda: B.Model(B.BF16, (3, 32, 32), fake_ops(specs), None))
+    expect(B.ERR_DTYPE, lambda: B.Model(5, (3, 32, 32), fake_ops([ok]), None))
+    bad = fake_ops([ok])
+    bad[0].packed = None
+    expect(B.ERR_NULL, lambda: B.Model(B.BF16, (3, 32, 32), bad, None))
+
+
+def test_baseline_config_graphs_have_expected_launch_counts():
+    want = {0: 2, 1: 56, 2: 21, 3: 54, 4: 54}
+    for idx, n in want.items():
+        model, _ = synth.make_config(idx)
+        plan = network.optimise(model)
+        assert len(plan["layers"]) == n
