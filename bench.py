@@ -50,6 +50,7 @@ def main():
     ap.add_argument("--config", type=int, default=1)
     ap.add_argument("--batch", type=int, default=0)
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--schedule", choices=["auto", "per-layer"], default="auto")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-op", action="store_true", help="print a per-operator table to stderr")
     args = ap.parse_args()
@@ -70,6 +71,8 @@ def main():
     dt = B.DTYPES[model["dtype"]]
     plan = network.optimise(model)
     fm, sites = network.build(plan)
+    if args.schedule == "per-layer":
+        fm.set_schedule(B.SCHEDULE_PER_LAYER)
     x = synth.make_input(synth.BASE_SEED + args.config, batch, model["in_shape"])
     xd = B.DeviceTensor.from_nchw(x, dt)
 
@@ -104,7 +107,11 @@ def main():
         op_ms /= reps
 
     ms_per_step = elapsed / args.steps * 1e3
-    stats = [fm.op_stats(batch, i) for i in range(fm.num_ops)]
+    n_launch = fm.num_launches
+    stats = [fm.launch_stats(batch, i) for i in range(n_launch)]
+    op_ms = op_ms[:n_launch]
+    if n_launch != fm.num_ops:
+        sites = ["network"] * n_launch
     total_flops = sum(s["flops"] for s in stats)
     total_bytes = sum(s["bytes"] for s in stats)
     images_per_s = batch / (ms_per_step * 1e-3)
@@ -153,7 +160,8 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": model["dtype"], "data": "synthetic",
         "config": {"workload": model["name"], "config_index": args.config, "batch": batch,
-                   "conv_launches": sum(1 for s in sites if s), "hip_graph": graph is not None},
+                   "kernel_launches": n_launch, "schedule": args.schedule,
+                   "hip_graph": graph is not None},
         "tflops": tflops, "mfma_frac": tflops * 1e12 / peak_flops,
         "algorithmic_gflop_per_step": total_flops / 1e9,
         "algorithmic_mb_per_step": total_bytes / 1e6,

@@ -218,6 +218,17 @@ typedef struct fupr_model fupr_model;
 fupr_status fupr_model_create(const fupr_graph_desc* g, fupr_model** out);
 void fupr_model_destroy(fupr_model* m);
 
+/*
+ * How fupr_forward schedules the network.  AUTO (default): if every activation
+ * tensor of one image fits in the compute unit's LDS (CIFAR-size networks of
+ * Table II), the whole network runs as ONE kernel, one workgroup per image,
+ * activations never leaving LDS; otherwise one kernel per operator.
+ * PER_LAYER: always one kernel per operator.  Both schedules compute the same
+ * arithmetic in the same order and give bit-identical results.
+ */
+enum { FUPR_SCHEDULE_AUTO = 0, FUPR_SCHEDULE_PER_LAYER = 1 };
+fupr_status fupr_model_set_schedule(fupr_model* m, int32_t schedule);
+
 /* Bytes of [dev] workspace fupr_forward needs for a batch (0 if m is NULL or batch <= 0). */
 size_t fupr_model_workspace_bytes(const fupr_model* m, int32_t batch);
 
@@ -235,9 +246,10 @@ fupr_status fupr_forward(const fupr_model* m, const fupr_tensor* input, const fu
                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * As fupr_forward, but brackets every operator with HIP events on the stream,
- * waits for the stream, and writes the n_ops elapsed times (milliseconds) to the
- * HOST array op_ms.  Synchronous.  For measurement only.
+ * As fupr_forward, but brackets every kernel launch with HIP events on the
+ * stream, waits for the stream, and writes elapsed times (milliseconds) to the
+ * HOST array op_ms, which has fupr_model_num_ops entries: entry i is launch i;
+ * entries past the number of launches are 0.  Synchronous.  For measurement only.
  */
 fupr_status fupr_forward_timed(const fupr_model* m, const fupr_tensor* input,
                                const fupr_tensor* output, void* workspace, size_t workspace_bytes,
@@ -258,6 +270,16 @@ typedef struct {
 } fupr_op_stats;
 fupr_status fupr_model_op_stats(const fupr_model* m, int32_t batch, int32_t op, fupr_op_stats* out);
 int32_t fupr_model_num_ops(const fupr_model* m);
+
+/*
+ * Kernel launches of one forward pass under the current schedule (1 for the
+ * one-kernel schedule, else one per operator) and the algorithmic work of
+ * launch i.  For the one-kernel schedule: all the network's flops; bytes = the
+ * images read once + the result written once + every parameter read once.
+ */
+int32_t fupr_model_num_launches(const fupr_model* m);
+fupr_status fupr_model_launch_stats(const fupr_model* m, int32_t batch, int32_t launch,
+                                    fupr_op_stats* out);
 
 /*
  * fupr_forward captured once into a HIP graph and replayed (the operators are

@@ -10,6 +10,10 @@ import ctypes as C
 import os
 
 import numpy as np
+# torch first: libfupr.so and torch must share ONE HIP runtime in the process, and
+# the one torch ships is the one its allocator and streams belong to.  Loading
+# libfupr.so before torch would bind it to another copy that sees no device.
+import torch  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfupr.so")
@@ -27,6 +31,7 @@ ERR_WORKSPACE, ERR_ALIGN, ERR_LAUNCH, ERR_ARG, ERR_LIMIT = -6, -7, -8, -9, -10
 F32, BF16, F16 = 0, 1, 2
 FUSE_BN, FUSE_RELU, FUSE_ADD = 1, 2, 4
 OP_CONV, OP_MAXPOOL, OP_AVGPOOL = 0, 1, 2
+SCHEDULE_AUTO, SCHEDULE_PER_LAYER = 0, 1
 DTYPES = {"f32": F32, "bf16": BF16, "f16": F16}
 
 
@@ -96,6 +101,9 @@ SIGNATURES = {
     "fupr_forward_timed": (C.c_int32, [C.c_void_p, _T, _T, C.c_void_p, C.c_size_t, C.c_void_p, _F]),
     "fupr_model_op_stats": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(OpStats)]),
     "fupr_model_num_ops": (C.c_int32, [C.c_void_p]),
+    "fupr_model_num_launches": (C.c_int32, [C.c_void_p]),
+    "fupr_model_launch_stats": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(OpStats)]),
+    "fupr_model_set_schedule": (C.c_int32, [C.c_void_p, C.c_int32]),
     "fupr_graph_create": (C.c_int32, [C.c_void_p, _T, _T, C.c_void_p, C.c_size_t, C.c_void_p,
                                       C.POINTER(C.c_void_p)]),
     "fupr_graph_launch": (C.c_int32, [C.c_void_p, C.c_void_p]),
@@ -345,12 +353,29 @@ class Model:
                "fupr_model_output_shape")
         return t
 
+    @property
+    def num_launches(self):
+        return int(_lib.fupr_model_num_launches(self._h))
+
+    def set_schedule(self, schedule):
+        _check(_lib.fupr_model_set_schedule(self._h, int(schedule)), "fupr_model_set_schedule")
+
+    @staticmethod
+    def _stats(s):
+        return {"flops": s.flops, "bytes": s.bytes, "M": s.M, "K": s.K, "C": s.C, "R": s.R,
+                "S": s.S, "stride": s.stride, "kernel": s.kernel.decode()}
+
     def op_stats(self, batch, op):
         s = OpStats()
         _check(_lib.fupr_model_op_stats(self._h, int(batch), int(op), C.byref(s)),
                "fupr_model_op_stats")
-        return {"flops": s.flops, "bytes": s.bytes, "M": s.M, "K": s.K, "C": s.C, "R": s.R,
-                "S": s.S, "stride": s.stride, "kernel": s.kernel.decode()}
+        return self._stats(s)
+
+    def launch_stats(self, batch, launch):
+        s = OpStats()
+        _check(_lib.fupr_model_launch_stats(self._h, int(batch), int(launch), C.byref(s)),
+               "fupr_model_launch_stats")
+        return self._stats(s)
 
     def alloc(self, batch, device="cuda:0"):
         """(output DeviceTensor, workspace torch tensor) for a batch size."""

@@ -4,51 +4,15 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <cstdio>
+#include <cstdlib>
 
 #include "fupr.h"
 #include "layout.h"
+#include "device_utils.h"
 
 namespace fupr {
 namespace {
-
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
-
-// ---- 16-bit element helpers ------------------------------------------------
-
-template <bool BF>
-__device__ __forceinline__ float to_float(uint16_t h) {
-  if constexpr (BF) {
-    return __uint_as_float((uint32_t)h << 16);
-  } else {
-    return (float)__builtin_bit_cast(_Float16, h);
-  }
-}
-
-// Round to nearest even.
-template <bool BF>
-__device__ __forceinline__ uint16_t from_float(float f) {
-  if constexpr (BF) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-  } else {
-    return __builtin_bit_cast(uint16_t, (_Float16)f);
-  }
-}
-
-template <bool BF>
-__device__ __forceinline__ f32x4 mfma_16x16x32(const uint4& a, const uint4& b, f32x4 c) {
-  if constexpr (BF) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
-                                                   __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-  } else {
-    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a),
-                                                  __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-  }
-}
 
 // ---- implicit-GEMM convolution, 16-bit inputs, fp32 accumulation -----------
 //
@@ -411,7 +375,7 @@ fupr_status launch16_nt(const Conv16Params& p, int NT, dim3 grid, size_t shmem, 
     case 3: hipLaunchKernelGGL((conv16_kernel<BF, MT, 3>), grid, dim3(256), shmem, st, p); break;
     default: hipLaunchKernelGGL((conv16_kernel<BF, MT, 4>), grid, dim3(256), shmem, st, p); break;
   }
-  return hipGetLastError() == hipSuccess ? FUPR_OK : FUPR_ERR_LAUNCH;
+  return launch_status(__func__);
 }
 
 template <bool BF>
@@ -427,6 +391,13 @@ fupr_status launch16(const Conv16Params& p, Tile t, hipStream_t st) {
 }
 
 }  // namespace
+
+fupr_status launch_status(const char* what) {
+  const hipError_t e = hipGetLastError();
+  if (e == hipSuccess) return FUPR_OK;
+  if (getenv("FUPR_DEBUG")) fprintf(stderr, "fupr: %s: %s\n", what, hipGetErrorString(e));
+  return FUPR_ERR_LAUNCH;
+}
 
 const char* conv_kernel_name(const fupr_conv_shape& s, fupr_dtype dt, int64_t M) {
   if (dt == FUPR_F32) return "conv32_direct";
@@ -460,7 +431,7 @@ fupr_status launch_conv(const ConvArgs& a, void* stream) {
     p.relu = a.relu;
     const int64_t threads = M * p.KQ;
     hipLaunchKernelGGL(conv32_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, p);
-    return hipGetLastError() == hipSuccess ? FUPR_OK : FUPR_ERR_LAUNCH;
+    return launch_status(__func__);
   }
   Conv16Params p;
   p.x = (const uint16_t*)a.x;
@@ -594,7 +565,7 @@ extern "C" fupr_status fupr_maxpool(const fupr_tensor* x, int32_t k, int32_t str
   if (x->dt == FUPR_F32) hipLaunchKernelGGL(maxpool_kernel<0>, grid, dim3(256), 0, hs, p);
   else if (x->dt == FUPR_BF16) hipLaunchKernelGGL(maxpool_kernel<1>, grid, dim3(256), 0, hs, p);
   else hipLaunchKernelGGL(maxpool_kernel<2>, grid, dim3(256), 0, hs, p);
-  return hipGetLastError() == hipSuccess ? FUPR_OK : FUPR_ERR_LAUNCH;
+  return launch_status(__func__);
 }
 
 extern "C" fupr_status fupr_global_avgpool(const fupr_tensor* x, const fupr_tensor* y,
@@ -612,5 +583,5 @@ extern "C" fupr_status fupr_global_avgpool(const fupr_tensor* x, const fupr_tens
   if (x->dt == FUPR_F32) hipLaunchKernelGGL(avgpool_kernel<0>, grid, dim3(256), 0, hs, p);
   else if (x->dt == FUPR_BF16) hipLaunchKernelGGL(avgpool_kernel<1>, grid, dim3(256), 0, hs, p);
   else hipLaunchKernelGGL(avgpool_kernel<2>, grid, dim3(256), 0, hs, p);
-  return hipGetLastError() == hipSuccess ? FUPR_OK : FUPR_ERR_LAUNCH;
+  return launch_status(__func__);
 }

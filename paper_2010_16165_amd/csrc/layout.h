@@ -46,6 +46,10 @@ inline PackedLayout packed_layout(const fupr_conv_shape& s, fupr_dtype dt) {
   return L;
 }
 
+// FUPR_OK if the HIP runtime has no pending error, else FUPR_ERR_LAUNCH (the
+// runtime's message goes to stderr when the environment has FUPR_DEBUG set).
+fupr_status launch_status(const char* what);
+
 // Launchers (kernels.hip); all arguments already validated.
 struct ConvArgs {
   const void* x;
@@ -61,5 +65,43 @@ struct ConvArgs {
 };
 fupr_status launch_conv(const ConvArgs& a, void* stream);
 const char* conv_kernel_name(const fupr_conv_shape& s, fupr_dtype dt, int64_t M);
+
+// ---- whole network in one kernel, activations resident in LDS ----------------
+// One workgroup per image walks a table of layers; see resident.hip.
+
+constexpr int kResMaxLayers = 72;
+constexpr int kResTableEntries = 256;             // chunks per layer the tap table can hold
+constexpr int kResThreads = 1024;
+constexpr size_t kResLdsLimit = 160 * 1024;
+
+struct ResLayer {             // 48 bytes
+  const void* packed;         // conv: blob (bias + weights)
+  uint16_t in_off, out_off, res_off;  // LDS offsets in 16-byte units; res_off 0xffff = none
+  uint16_t nchunk;
+  uint16_t cs_in, cs_out, res_cs;     // elements per pixel
+  uint16_t Kp;
+  uint8_t kind;               // 0 conv, 1 global mean
+  uint8_t H, W, P, Q;
+  uint8_t S, stride, pad;
+  uint8_t cpt, nsteps, FT, NT;
+  uint8_t res_W, res_ss;
+  uint8_t relu, last;
+  uint8_t reserved[4];
+};
+static_assert(sizeof(ResLayer) == 48, "ResLayer must stay 48 bytes");
+
+struct ResParams {
+  const void* x;    // N images, NHWC, in_elems elements each
+  void* y;          // N x out_pixels x y_cs
+  int in_elems;     // per image
+  int in_off;       // LDS offset (16-byte units) the image is staged to
+  int y_cs, out_pixels;
+  int n_layers;
+  int lds_bytes;
+  ResLayer layers[kResMaxLayers];
+};
+static_assert(sizeof(ResParams) <= 3800, "kernel arguments must stay under 4 KB");
+
+fupr_status launch_resident(const ResParams& p, int N, fupr_dtype dt, void* stream);
 
 }  // namespace fupr

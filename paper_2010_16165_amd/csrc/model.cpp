@@ -27,12 +27,133 @@ struct fupr_model {
   std::vector<fupr_op_desc> ops;
   std::vector<TensorInfo> tensors;        // n_ops + 1
   std::vector<size_t> buffer_elems;       // per image, per workspace buffer
+  int schedule = FUPR_SCHEDULE_AUTO;
+  bool resident_ok = false;               // the whole network fits one LDS-resident kernel
+  ResParams resident{};                   // x, y, y_cs filled per call
 };
 
 struct fupr_graph {
   hipGraph_t graph = nullptr;
   hipGraphExec_t exec = nullptr;
 };
+
+namespace {
+
+// Filter tiles a wave keeps per work item of the LDS-resident kernel: as many as
+// possible (the pixel operand is then read from LDS once for all of them) while
+// the layer still has at least one item per wave.
+int resident_nt(int n_ptiles, int FT) {
+  int nt = std::min(FT, 4);
+  while (nt > 1 && n_ptiles * ((FT + nt - 1) / nt) < kResThreads / 64) nt = (nt + 1) / 2;
+  return nt;
+}
+
+// Tries to lay the whole network out for resident_kernel: every per-image
+// tensor (input included, final output excluded) in LDS.
+void plan_resident(fupr_model* m) {
+  m->resident_ok = false;
+  const int n = (int)m->ops.size();
+  if (m->dt == FUPR_F32 || n > kResMaxLayers) return;
+  for (const TensorInfo& t : m->tensors)
+    if (t.H > 255 || t.W > 255 || t.cs > 65535) return;
+
+  // LDS buffers in 16-byte units, same greedy sharing as the workspace plan
+  std::vector<int> holder, units, where(n + 1, -1);
+  auto tensor_units = [&](const TensorInfo& t) { return (size_t)t.H * t.W * t.cs * 2 / 16; };
+  auto place = [&](int tid) {
+    const size_t need = tensor_units(m->tensors[tid]);
+    int pick = -1;
+    for (size_t b = 0; b < holder.size(); ++b) {
+      if (holder[b] >= 0) continue;
+      if (pick < 0) { pick = (int)b; continue; }
+      const size_t cur = units[pick], cand = units[b];
+      const size_t dc = cur > need ? cur - need : need - cur;
+      const size_t dn = cand > need ? cand - need : need - cand;
+      if (dn < dc) pick = (int)b;
+    }
+    if (pick < 0) {
+      holder.push_back(-1);
+      units.push_back(0);
+      pick = (int)holder.size() - 1;
+    }
+    holder[pick] = tid;
+    units[pick] = (int)std::max<size_t>(units[pick], need);
+    where[tid] = pick;
+  };
+  place(0);
+  for (int i = 0; i < n; ++i) {
+    const int tid = i + 1;
+    if (tid != n) place(tid);
+    for (size_t b = 0; b < holder.size(); ++b) {
+      const int h = holder[b];
+      if (h >= 0 && h != tid && m->tensors[h].last_use <= i) holder[b] = -1;
+    }
+  }
+  std::vector<size_t> offset(units.size());
+  size_t total_units = 0;
+  for (size_t b = 0; b < units.size(); ++b) {
+    offset[b] = total_units;
+    total_units += units[b];
+  }
+  const size_t table_bytes = 2 * kResTableEntries * sizeof(int32_t) * 2;
+  const size_t lds_bytes = table_bytes + total_units * 16;
+  if (lds_bytes > kResLdsLimit || total_units >= 0xffff) return;
+
+  ResParams& R = m->resident;
+  R = ResParams{};
+  const TensorInfo& t0 = m->tensors[0];
+  R.in_elems = t0.H * t0.W * t0.cs;
+  R.in_off = (int)offset[where[0]];
+  R.n_layers = n;
+  R.lds_bytes = (int)lds_bytes;
+  R.out_pixels = m->tensors[n].H * m->tensors[n].W;
+  for (int i = 0; i < n; ++i) {
+    const fupr_op_desc& op = m->ops[i];
+    const TensorInfo& ti = m->tensors[op.in];
+    const TensorInfo& to = m->tensors[i + 1];
+    ResLayer L{};
+    L.in_off = (uint16_t)offset[where[op.in]];
+    L.out_off = i + 1 == n ? 0 : (uint16_t)offset[where[i + 1]];
+    L.res_off = 0xffff;
+    L.cs_in = (uint16_t)ti.cs;
+    L.cs_out = (uint16_t)to.cs;
+    L.H = (uint8_t)ti.H; L.W = (uint8_t)ti.W; L.P = (uint8_t)to.H; L.Q = (uint8_t)to.W;
+    L.last = i + 1 == n;
+    if (op.kind == FUPR_OP_AVGPOOL) {
+      L.kind = 1;
+    } else if (op.kind == FUPR_OP_CONV) {
+      const fupr_conv_shape& s = op.conv;
+      const PackedLayout PL = packed_layout(s, m->dt);
+      if (PL.nchunk_pad > kResTableEntries || s.S > 255 || s.stride > 255 || s.pad > 255 ||
+          PL.Cp / 8 > 255 || PL.Kp / 16 > 255 || PL.Kp > 65535)
+        return;
+      L.kind = 0;
+      L.packed = op.packed;
+      L.nchunk = (uint16_t)PL.nchunk;
+      L.Kp = (uint16_t)PL.Kp;
+      L.S = (uint8_t)s.S; L.stride = (uint8_t)s.stride; L.pad = (uint8_t)s.pad;
+      L.cpt = (uint8_t)(PL.Cp / 8);
+      L.nsteps = (uint8_t)(PL.nchunk_pad / 4);
+      L.FT = (uint8_t)(PL.Kp / 16);
+      L.NT = (uint8_t)resident_nt((to.H * to.W + 15) / 16, L.FT);
+      L.relu = (op.epilogue & FUPR_FUSE_RELU) ? 1 : 0;
+      if (op.res >= 0) {
+        if (op.res_c_offset != 0 || op.res_spatial_stride > 255) return;
+        const TensorInfo& tr = m->tensors[op.res];
+        L.res_off = (uint16_t)offset[where[op.res]];
+        L.res_cs = (uint16_t)tr.cs;
+        L.res_W = (uint8_t)tr.W;
+        L.res_ss = (uint8_t)op.res_spatial_stride;
+      }
+    } else {
+      return;   // max-pool networks have images too large for LDS anyway
+    }
+    R.layers[i] = L;
+  }
+  m->resident_ok = true;
+}
+
+}  // namespace
 
 extern "C" fupr_status fupr_model_create(const fupr_graph_desc* g, fupr_model** out) {
   if (!g || !out || !g->ops) return FUPR_ERR_NULL;
@@ -145,7 +266,15 @@ extern "C" fupr_status fupr_model_create(const fupr_graph_desc* g, fupr_model** 
       if (h >= 0 && h != tid && m->tensors[h].last_use <= i) holder[b] = -1;
     }
   }
+  plan_resident(m);
   *out = m;
+  return FUPR_OK;
+}
+
+extern "C" fupr_status fupr_model_set_schedule(fupr_model* m, int32_t schedule) {
+  if (!m) return FUPR_ERR_NULL;
+  if (schedule != FUPR_SCHEDULE_AUTO && schedule != FUPR_SCHEDULE_PER_LAYER) return FUPR_ERR_ARG;
+  m->schedule = schedule;
   return FUPR_OK;
 }
 
@@ -176,6 +305,17 @@ extern "C" fupr_status fupr_model_output_shape(const fupr_model* m, int32_t batc
 }
 
 namespace {
+
+// The one-kernel schedule applies when the plan exists, the caller has not
+// asked for per-layer kernels, and the caller's tensors have the strides the
+// plan assumed.
+bool use_resident(const fupr_model* m, const fupr_tensor* input, const fupr_tensor* output) {
+  if (!m->resident_ok || m->schedule != FUPR_SCHEDULE_AUTO) return false;
+  if (input->c_stride != m->tensors.front().cs) return false;
+  const fupr_op_desc& last = m->ops.back();
+  const int limit = last.kind == FUPR_OP_CONV ? round_up(last.conv.K, 16) : m->tensors[last.in].cs;
+  return output->c_stride <= limit;
+}
 
 fupr_status run(const fupr_model* m, const fupr_tensor* input, const fupr_tensor* output,
                 void* workspace, size_t workspace_bytes, void* stream, hipEvent_t* events) {
@@ -213,6 +353,16 @@ fupr_status run(const fupr_model* m, const fupr_tensor* input, const fupr_tensor
 
   hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
   if (events && hipEventRecord(events[0], hs) != hipSuccess) return FUPR_ERR_LAUNCH;
+  if (use_resident(m, input, output)) {
+    ResParams R = m->resident;
+    R.x = input->ptr;
+    R.y = output->ptr;
+    R.y_cs = output->c_stride;
+    const fupr_status st = launch_resident(R, N, m->dt, stream);
+    if (st != FUPR_OK) return st;
+    if (events && hipEventRecord(events[1], hs) != hipSuccess) return FUPR_ERR_LAUNCH;
+    return FUPR_OK;
+  }
   for (size_t i = 0; i < m->ops.size(); ++i) {
     const fupr_op_desc& op = m->ops[i];
     const fupr_tensor x = view(op.in), y = view((int)i + 1);
@@ -258,8 +408,9 @@ extern "C" fupr_status fupr_forward_timed(const fupr_model* m, const fupr_tensor
   if (st == FUPR_OK && hipStreamSynchronize(reinterpret_cast<hipStream_t>(stream)) != hipSuccess)
     st = FUPR_ERR_LAUNCH;
   if (st == FUPR_OK) {
-    std::vector<float> ms(n);
-    for (size_t i = 0; i < n; ++i)
+    std::vector<float> ms(n, 0.0f);
+    const size_t launches = use_resident(m, input, output) ? 1 : n;
+    for (size_t i = 0; i < launches; ++i)
       if (hipEventElapsedTime(&ms[i], ev[i], ev[i + 1]) != hipSuccess) { st = FUPR_ERR_LAUNCH; break; }
     if (st == FUPR_OK) std::copy(ms.begin(), ms.end(), op_ms);
   }
@@ -297,6 +448,43 @@ extern "C" fupr_status fupr_model_op_stats(const fupr_model* m, int32_t batch, i
     s.bytes = in_b + out_b;
     s.kernel = d.kind == FUPR_OP_MAXPOOL ? "maxpool" : "global_avgpool";
   }
+  *out = s;
+  return FUPR_OK;
+}
+
+extern "C" int32_t fupr_model_num_launches(const fupr_model* m) {
+  if (!m) return 0;
+  return m->resident_ok && m->schedule == FUPR_SCHEDULE_AUTO ? 1 : (int32_t)m->ops.size();
+}
+
+extern "C" fupr_status fupr_model_launch_stats(const fupr_model* m, int32_t batch, int32_t launch,
+                                               fupr_op_stats* out) {
+  if (!m || !out) return FUPR_ERR_NULL;
+  if (batch <= 0 || launch < 0 || launch >= fupr_model_num_launches(m)) return FUPR_ERR_ARG;
+  if (!(m->resident_ok && m->schedule == FUPR_SCHEDULE_AUTO))
+    return fupr_model_op_stats(m, batch, launch, out);
+  // one kernel: all flops; the image in, the result out, every parameter once
+  const double es = (double)elem_size(m->dt);
+  const TensorInfo& t0 = m->tensors.front();
+  const TensorInfo& tl = m->tensors.back();
+  fupr_op_stats s{};
+  s.M = batch;
+  s.C = t0.C;
+  s.K = tl.C;
+  s.R = t0.H;
+  s.S = t0.W;
+  s.stride = 1;
+  s.bytes = es * batch * ((double)t0.C * t0.H * t0.W + (double)tl.C * tl.H * tl.W);
+  for (size_t i = 0; i < m->ops.size(); ++i) {
+    fupr_op_stats o;
+    const fupr_status st = fupr_model_op_stats(m, batch, (int32_t)i, &o);
+    if (st != FUPR_OK) return st;
+    s.flops += o.flops;
+    const fupr_op_desc& d = m->ops[i];
+    if (d.kind == FUPR_OP_CONV)
+      s.bytes += es * (double)d.conv.C * d.conv.R * d.conv.S * d.conv.K + 4.0 * d.conv.K;
+  }
+  s.kernel = "resident_network";
   *out = s;
   return FUPR_OK;
 }

@@ -302,6 +302,58 @@ def test_baseline_config_teacher_forced(fx, idx):
     print(f"config {idx}: worst site rel err {worst:.3e} over {len(plan['layers'])} sites", flush=True)
 
 
+def resident_models():
+    return [
+        synth.make_cifar_resnet(31, "bf16", 3, 400),
+        synth.make_cifar_resnet(32, "f16", 2, 250, widths=(8, 24, 40), size=24, classes=13),
+        synth.make_block_model(33, "bf16", 16, 32, 250),
+        synth.make_cifar_resnet(34, "bf16", 1, 0, widths=(16, 32, 64), size=32),
+    ]
+
+
+@pytest.mark.parametrize("mi", range(4))
+def test_one_kernel_schedule_equals_per_layer_schedule(fx, mi):
+    """The LDS-resident one-kernel schedule and the per-layer schedule do the
+    same arithmetic in the same order: outputs are bit-identical, and both
+    match the oracle."""
+    B, network, torch = fx
+    model = resident_models()[mi]
+    n = 5
+    x = synth.make_input(41 + mi, n, model["in_shape"])
+    dt = B.DTYPES[model["dtype"]]
+    plan = network.optimise(model)
+    m, _ = network.build(plan)
+    assert m.num_launches == 1, "model should be eligible for the one-kernel schedule"
+    xd = B.DeviceTensor.from_nchw(x, dt)
+    out_a, ws = m.alloc(n)
+    out_a.data.fill_(9.0)
+    m.fupr_forward(xd, out_a, ws)
+    torch.cuda.synchronize()
+    m.set_schedule(B.SCHEDULE_PER_LAYER)
+    assert m.num_launches == m.num_ops
+    out_b, ws_b = m.alloc(n)
+    m.fupr_forward(xd, out_b, ws_b)
+    torch.cuda.synchronize()
+    assert torch.equal(out_a.data, out_b.data)
+    assert out_a.padding_is_zero()
+    masks = orc.select_masks(model)
+    ref = orc.forward(model, round_to(x, model["dtype"], torch), masks=masks)
+    y = out_a.to_nchw()
+    if model["head"] is not None:
+        y = y[:, :, 0, 0]
+    err = rel_err(y, ref)
+    print(f"resident model {mi}: rel err {err:.3e}", flush=True)
+    assert err <= TOL[model["dtype"]]
+
+
+def test_imagenet_models_use_per_layer_schedule(fx):
+    B, network, torch = fx
+    model = synth.make_imagenet_basic_resnet(13, "bf16", (1, 1, 1, 1), 300, widths=(4, 8, 8, 12),
+                                             size=32, classes=7)
+    m, _ = network.build(network.optimise(model))
+    assert m.num_launches == m.num_ops     # has a max-pool
+
+
 def test_forward_is_deterministic_and_graph_replays(fx):
     B, network, torch = fx
     model = synth.make_cifar_resnet(21, "bf16", 3, 400)
@@ -338,7 +390,12 @@ def test_timed_forward_and_stats(fx):
     xd = B.DeviceTensor.from_nchw(x, B.BF16)
     out, ws = m.alloc(2)
     ms = m.fupr_forward_timed(xd, out, ws)
-    assert ms.shape == (m.num_ops,) and (ms > 0).all()
+    assert ms.shape == (m.num_ops,) and ms[0] > 0 and (ms[m.num_launches:] == 0).all()
+    total = sum(m.op_stats(2, i)["flops"] for i in range(m.num_ops))
+    assert m.launch_stats(2, 0)["flops"] == total and m.launch_stats(2, 0)["kernel"] == "resident_network"
+    m.set_schedule(B.SCHEDULE_PER_LAYER)
+    ms = m.fupr_forward_timed(xd, out, ws)
+    assert (ms > 0).all()
     st = m.op_stats(2, 0)
     assert st["flops"] == 2.0 * 3 * 9 * 16 * 2 * 32 * 32 and st["kernel"].startswith("conv16")
 
