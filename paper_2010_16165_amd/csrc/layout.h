@@ -74,26 +74,30 @@ constexpr int kResTableEntries = 256;             // chunks per layer the tap ta
 constexpr int kResThreads = 1024;
 constexpr size_t kResLdsLimit = 160 * 1024;
 
+// One layer of the table, packed into aligned 32-bit words so that the kernel
+// reads it with scalar loads only (a byte or unaligned 16-bit field would be
+// fetched with a vector load, whose wait would also drain the parameter
+// prefetch in flight).
 struct ResLayer {             // 48 bytes
-  const void* packed;         // conv: blob (bias + weights)
-  uint16_t in_off, out_off, res_off;  // LDS offsets in 16-byte units; res_off 0xffff = none
-  uint16_t nchunk;
-  uint16_t cs_in, cs_out, res_cs;     // elements per pixel
-  uint16_t Kp;
-  uint8_t kind;               // 0 conv, 1 global mean
-  uint8_t H, W, P, Q;
-  uint8_t S, stride, pad;
-  uint8_t cpt, nsteps, FT, NT;
-  uint8_t res_W, res_ss;
-  uint8_t relu, last;
-  uint8_t reserved[4];
+  const void* packed;         // conv: blob (bias + weights) in global memory
+  uint32_t off0;              // in_off | out_off << 16        LDS offsets, 16-byte units
+  uint32_t off1;              // res_off | w_off << 16         res_off 0xffff = none
+  uint32_t sz;                // blob_units | nchunk << 16     blob_units: 16-byte units staged to w_off
+  uint32_t ps0;               // ps_in | ps_out << 16          LDS pixel strides, elements
+  uint32_t ps1;               // ps_res | cs_out << 16         cs_out: lanes written per output pixel
+  uint32_t ch;                // res_cs | Kp << 16             res_cs: lanes held per residual pixel
+  uint32_t g0;                // H | W << 8 | P << 16 | Q << 24
+  uint32_t g1;                // S | stride << 8 | pad << 16 | cpt << 24
+  uint32_t g2;                // nsteps | FT << 8 | MT << 16 | NT << 24   work item: MT x NT tiles
+  uint32_t g3;                // res_W | res_ss << 8 | flags << 16
 };
 static_assert(sizeof(ResLayer) == 48, "ResLayer must stay 48 bytes");
+constexpr int kResMean = 1, kResRelu = 2, kResLast = 4;
 
 struct ResParams {
-  const void* x;    // N images, NHWC, in_elems elements each
+  const void* x;    // N images, NHWC
   void* y;          // N x out_pixels x y_cs
-  int in_elems;     // per image
+  int in_pixels, in_cs, in_ps;   // image: pixels, global channel stride, LDS pixel stride
   int in_off;       // LDS offset (16-byte units) the image is staged to
   int y_cs, out_pixels;
   int n_layers;
@@ -101,6 +105,11 @@ struct ResParams {
   ResLayer layers[kResMaxLayers];
 };
 static_assert(sizeof(ResParams) <= 3800, "kernel arguments must stay under 4 KB");
+
+// Each thread carries the next layer's parameters through the current layer
+// in kResPrefetch 16-byte registers, so a blob may not exceed this.
+constexpr int kResPrefetch = 5;
+constexpr size_t kResMaxBlob = (size_t)kResPrefetch * 16 * kResThreads;
 
 fupr_status launch_resident(const ResParams& p, int N, fupr_dtype dt, void* stream);
 

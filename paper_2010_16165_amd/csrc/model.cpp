@@ -39,118 +39,182 @@ struct fupr_graph {
 
 namespace {
 
-// Filter tiles a wave keeps per work item of the LDS-resident kernel: as many as
-// possible (the pixel operand is then read from LDS once for all of them) while
-// the layer still has at least one item per wave.
-int resident_nt(int n_ptiles, int FT) {
-  int nt = std::min(FT, 4);
-  while (nt > 1 && n_ptiles * ((FT + nt - 1) / nt) < kResThreads / 64) nt = (nt + 1) / 2;
-  return nt;
+// Shape of one work item of the LDS-resident kernel for a conv layer: MT pixel
+// tiles x NT filter tiles (MT*NT <= 4 accumulator tiles per wave).  Picks the
+// shape with the smallest estimated layer time: LDS operand traffic (each
+// 16 x 32 fragment is 1 KB = 8 clocks of the compute unit's LDS port) against
+// MFMA issue on the busiest of the four SIMDs (16 clocks per 16x16x32).
+void resident_item_shape(int n_ptiles, int FT, int nsteps, int* MT_out, int* NT_out) {
+  static const int shapes[8][2] = {{4, 1}, {2, 2}, {1, 4}, {3, 1}, {1, 3}, {2, 1}, {1, 2}, {1, 1}};
+  const int waves = kResThreads / 64;
+  double best = 1e30;
+  for (const auto& sh : shapes) {
+    const int mt = sh[0], nt = sh[1];
+    const int items = ((n_ptiles + mt - 1) / mt) * ((FT + nt - 1) / nt);
+    const int rounds = (items + waves - 1) / waves;
+    const double lds = (double)items * nsteps * (mt + nt) * 8.0;
+    const int per_simd = (std::min(items, waves) + 3) / 4 * rounds;
+    const double mfma = (double)per_simd * nsteps * mt * nt * 16.0;
+    const double latency = (double)rounds * nsteps * 40.0;   // exposed per-step latency
+    const double t = std::max(lds, mfma) + latency;
+    if (t < best) {
+      best = t;
+      *MT_out = mt;
+      *NT_out = nt;
+    }
+  }
+}
+
+// A block of LDS with a lifetime in layers; blocks whose lifetimes intersect
+// must not overlap.
+struct LdsBlock {
+  size_t units;       // 16-byte units
+  int first, last;    // layers during which it is live (inclusive)
+  size_t offset;
+};
+
+// Greedy offset assignment: largest first, lowest offset that fits.
+size_t assign_offsets(std::vector<LdsBlock>& blocks) {
+  std::vector<int> order(blocks.size());
+  for (size_t i = 0; i < order.size(); ++i) order[i] = (int)i;
+  std::stable_sort(order.begin(), order.end(),
+                   [&](int a, int b) { return blocks[a].units > blocks[b].units; });
+  std::vector<int> placed;
+  size_t extent = 0;
+  for (int id : order) {
+    LdsBlock& b = blocks[id];
+    if (b.units == 0) { b.offset = 0; continue; }
+    std::vector<std::pair<size_t, size_t>> busy;
+    for (int other : placed) {
+      const LdsBlock& o = blocks[other];
+      if (o.first <= b.last && b.first <= o.last) busy.emplace_back(o.offset, o.offset + o.units);
+    }
+    std::sort(busy.begin(), busy.end());
+    size_t at = 0;
+    for (const auto& iv : busy) {
+      if (at + b.units <= iv.first) break;
+      at = std::max(at, iv.second);
+    }
+    b.offset = at;
+    extent = std::max(extent, at + b.units);
+    placed.push_back(id);
+  }
+  return extent;
 }
 
 // Tries to lay the whole network out for resident_kernel: every per-image
-// tensor (input included, final output excluded) in LDS.
+// tensor (input included, final output excluded) and, for the current and the
+// next layer, the parameter blob, in LDS.
 void plan_resident(fupr_model* m) {
   m->resident_ok = false;
   const int n = (int)m->ops.size();
   if (m->dt == FUPR_F32 || n > kResMaxLayers) return;
   for (const TensorInfo& t : m->tensors)
-    if (t.H > 255 || t.W > 255 || t.cs > 65535) return;
+    if (t.H > 255 || t.W > 255 || t.cs > 4096) return;
 
-  // LDS buffers in 16-byte units, same greedy sharing as the workspace plan
-  std::vector<int> holder, units, where(n + 1, -1);
-  auto tensor_units = [&](const TensorInfo& t) { return (size_t)t.H * t.W * t.cs * 2 / 16; };
-  auto place = [&](int tid) {
-    const size_t need = tensor_units(m->tensors[tid]);
-    int pick = -1;
-    for (size_t b = 0; b < holder.size(); ++b) {
-      if (holder[b] >= 0) continue;
-      if (pick < 0) { pick = (int)b; continue; }
-      const size_t cur = units[pick], cand = units[b];
-      const size_t dc = cur > need ? cur - need : need - cur;
-      const size_t dn = cand > need ? cand - need : need - cand;
-      if (dn < dc) pick = (int)b;
-    }
-    if (pick < 0) {
-      holder.push_back(-1);
-      units.push_back(0);
-      pick = (int)holder.size() - 1;
-    }
-    holder[pick] = tid;
-    units[pick] = (int)std::max<size_t>(units[pick], need);
-    where[tid] = pick;
-  };
-  place(0);
-  for (int i = 0; i < n; ++i) {
-    const int tid = i + 1;
-    if (tid != n) place(tid);
-    for (size_t b = 0; b < holder.size(); ++b) {
-      const int h = holder[b];
-      if (h >= 0 && h != tid && m->tensors[h].last_use <= i) holder[b] = -1;
-    }
-  }
-  std::vector<size_t> offset(units.size());
-  size_t total_units = 0;
-  for (size_t b = 0; b < units.size(); ++b) {
-    offset[b] = total_units;
-    total_units += units[b];
-  }
   const size_t table_bytes = 2 * kResTableEntries * sizeof(int32_t) * 2;
-  const size_t lds_bytes = table_bytes + total_units * 16;
-  if (lds_bytes > kResLdsLimit || total_units >= 0xffff) return;
+  const size_t budget_units = (kResLdsLimit - table_bytes) / 16;
 
-  ResParams& R = m->resident;
-  R = ResParams{};
-  const TensorInfo& t0 = m->tensors[0];
-  R.in_elems = t0.H * t0.W * t0.cs;
-  R.in_off = (int)offset[where[0]];
-  R.n_layers = n;
-  R.lds_bytes = (int)lds_bytes;
-  R.out_pixels = m->tensors[n].H * m->tensors[n].W;
-  for (int i = 0; i < n; ++i) {
-    const fupr_op_desc& op = m->ops[i];
-    const TensorInfo& ti = m->tensors[op.in];
-    const TensorInfo& to = m->tensors[i + 1];
-    ResLayer L{};
-    L.in_off = (uint16_t)offset[where[op.in]];
-    L.out_off = i + 1 == n ? 0 : (uint16_t)offset[where[i + 1]];
-    L.res_off = 0xffff;
-    L.cs_in = (uint16_t)ti.cs;
-    L.cs_out = (uint16_t)to.cs;
-    L.H = (uint8_t)ti.H; L.W = (uint8_t)ti.W; L.P = (uint8_t)to.H; L.Q = (uint8_t)to.W;
-    L.last = i + 1 == n;
-    if (op.kind == FUPR_OP_AVGPOOL) {
-      L.kind = 1;
-    } else if (op.kind == FUPR_OP_CONV) {
-      const fupr_conv_shape& s = op.conv;
-      const PackedLayout PL = packed_layout(s, m->dt);
-      if (PL.nchunk_pad > kResTableEntries || s.S > 255 || s.stride > 255 || s.pad > 255 ||
-          PL.Cp / 8 > 255 || PL.Kp / 16 > 255 || PL.Kp > 65535)
-        return;
-      L.kind = 0;
-      L.packed = op.packed;
-      L.nchunk = (uint16_t)PL.nchunk;
-      L.Kp = (uint16_t)PL.Kp;
-      L.S = (uint8_t)s.S; L.stride = (uint8_t)s.stride; L.pad = (uint8_t)s.pad;
-      L.cpt = (uint8_t)(PL.Cp / 8);
-      L.nsteps = (uint8_t)(PL.nchunk_pad / 4);
-      L.FT = (uint8_t)(PL.Kp / 16);
-      L.NT = (uint8_t)resident_nt((to.H * to.W + 15) / 16, L.FT);
-      L.relu = (op.epilogue & FUPR_FUSE_RELU) ? 1 : 0;
-      if (op.res >= 0) {
-        if (op.res_c_offset != 0 || op.res_spatial_stride > 255) return;
-        const TensorInfo& tr = m->tensors[op.res];
-        L.res_off = (uint16_t)offset[where[op.res]];
-        L.res_cs = (uint16_t)tr.cs;
-        L.res_W = (uint8_t)tr.W;
-        L.res_ss = (uint8_t)op.res_spatial_stride;
-      }
-    } else {
-      return;   // max-pool networks have images too large for LDS anyway
+  // pad = 1: LDS pixel stride = channel stride + 8 elements, which spreads the
+  // 16 pixels of a fragment over all banks; fall back to the dense stride when
+  // the padded layout does not fit.
+  for (int pad = 1; pad >= 0; --pad) {
+    std::vector<LdsBlock> blocks(2 * (size_t)n + 1);
+    auto stride_of = [&](const TensorInfo& t) { return t.cs + (pad && t.H * t.W > 1 ? 8 : 0); };
+    for (int tid = 0; tid <= n; ++tid) {
+      const TensorInfo& t = m->tensors[tid];
+      LdsBlock& b = blocks[tid];
+      b.first = tid - 1;                       // produced by layer tid-1 (image: before layer 0)
+      b.last = std::max(t.last_use, b.first);
+      b.units = tid == n ? 0 : (size_t)t.H * t.W * stride_of(t) * 2 / 16;
     }
-    R.layers[i] = L;
+    bool ok = true;
+    for (int i = 0; i < n && ok; ++i) {
+      LdsBlock& b = blocks[n + 1 + i];
+      b.first = i - 1;                         // written while layer i-1 is still running
+      b.last = i;
+      b.units = 0;
+      if (m->ops[i].kind == FUPR_OP_CONV) {
+        const PackedLayout PL = packed_layout(m->ops[i].conv, m->dt);
+        if (PL.total_bytes > kResMaxBlob) ok = false;
+        b.units = PL.total_bytes / 16;
+      }
+    }
+    if (!ok) return;
+    const size_t extent = assign_offsets(blocks);
+    if (extent > budget_units || extent >= 0xffff) continue;
+
+    ResParams& R = m->resident;
+    R = ResParams{};
+    const TensorInfo& t0 = m->tensors[0];
+    R.in_pixels = t0.H * t0.W;
+    R.in_cs = t0.cs;
+    R.in_ps = stride_of(t0);
+    R.in_off = (int)blocks[0].offset;
+    R.n_layers = n;
+    R.lds_bytes = (int)(table_bytes + extent * 16);
+    R.out_pixels = m->tensors[n].H * m->tensors[n].W;
+    for (int i = 0; i < n; ++i) {
+      const fupr_op_desc& op = m->ops[i];
+      const TensorInfo& ti = m->tensors[op.in];
+      const TensorInfo& to = m->tensors[i + 1];
+      uint32_t in_off = (uint32_t)blocks[op.in].offset, out_off = (uint32_t)blocks[i + 1].offset;
+      uint32_t res_off = 0xffff, w_off = (uint32_t)blocks[n + 1 + i].offset;
+      uint32_t blob_units = (uint32_t)blocks[n + 1 + i].units, nchunk = 0;
+      uint32_t ps_in = (uint32_t)stride_of(ti), ps_out = (uint32_t)stride_of(to), ps_res = 0;
+      uint32_t cs_out = (uint32_t)to.cs, res_cs = 0, Kp = 0;
+      uint32_t S = 0, stride = 0, padding = 0, cpt = 0, nsteps = 0, FT = 0, MT = 1, NT = 1;
+      uint32_t res_W = 0, res_ss = 0, flags = i + 1 == n ? kResLast : 0;
+      const void* packed = nullptr;
+      if (op.kind == FUPR_OP_AVGPOOL) {
+        flags |= kResMean;
+      } else if (op.kind == FUPR_OP_CONV) {
+        const fupr_conv_shape& s = op.conv;
+        const PackedLayout PL = packed_layout(s, m->dt);
+        if (PL.nchunk_pad > kResTableEntries || s.S > 255 || s.stride > 255 || s.pad > 255 ||
+            PL.Cp / 8 > 255 || PL.Kp / 16 > 255 || PL.Kp > 4096)
+          return;
+        packed = op.packed;
+        nchunk = (uint32_t)PL.nchunk;
+        Kp = (uint32_t)PL.Kp;
+        S = (uint32_t)s.S; stride = (uint32_t)s.stride; padding = (uint32_t)s.pad;
+        cpt = (uint32_t)(PL.Cp / 8);
+        nsteps = (uint32_t)(PL.nchunk_pad / 4);
+        FT = (uint32_t)(PL.Kp / 16);
+        int mt = 1, nt = 1;
+        resident_item_shape((to.H * to.W + 15) / 16, (int)FT, (int)nsteps, &mt, &nt);
+        MT = (uint32_t)mt;
+        NT = (uint32_t)nt;
+        if (op.epilogue & FUPR_FUSE_RELU) flags |= kResRelu;
+        if (op.res >= 0) {
+          if (op.res_c_offset != 0 || op.res_spatial_stride > 255) return;
+          const TensorInfo& tr = m->tensors[op.res];
+          res_off = (uint32_t)blocks[op.res].offset;
+          res_cs = (uint32_t)tr.cs;
+          ps_res = (uint32_t)stride_of(tr);
+          res_W = (uint32_t)tr.W;
+          res_ss = (uint32_t)op.res_spatial_stride;
+        }
+      } else {
+        return;   // max-pool networks have images too large for LDS anyway
+      }
+      ResLayer L{};
+      L.packed = packed;
+      L.off0 = in_off | out_off << 16;
+      L.off1 = res_off | w_off << 16;
+      L.sz = blob_units | nchunk << 16;
+      L.ps0 = ps_in | ps_out << 16;
+      L.ps1 = ps_res | cs_out << 16;
+      L.ch = res_cs | Kp << 16;
+      L.g0 = (uint32_t)ti.H | (uint32_t)ti.W << 8 | (uint32_t)to.H << 16 | (uint32_t)to.W << 24;
+      L.g1 = S | stride << 8 | padding << 16 | cpt << 24;
+      L.g2 = nsteps | FT << 8 | MT << 16 | NT << 24;
+      L.g3 = res_W | res_ss << 8 | flags << 16;
+      R.layers[i] = L;
+    }
+    m->resident_ok = true;
+    return;
   }
-  m->resident_ok = true;
 }
 
 }  // namespace

@@ -1,5 +1,6 @@
 // A whole small-image network in ONE kernel: one workgroup per image, every
-// activation tensor of that image resident in LDS, layers walked from a table.
+// activation tensor of that image AND the current layer's parameters resident
+// in LDS, layers walked from a table.
 //
 // At CIFAR sizes (Table II, 32x32 inputs) each per-layer kernel runs for a few
 // microseconds and the forward pass is bound by launches and by activations
@@ -8,6 +9,13 @@
 // folding non-parametric operators into convolutions ("Sys.", "BN", "Add"
 // columns of Table VI) is removed here one level further: the operator
 // boundaries themselves.
+//
+// Per layer: the next layer's parameter blob is fetched from global memory into
+// registers BEFORE the current layer is computed and written to LDS after it,
+// so no global-memory latency sits on the layer chain; both MFMA operands of
+// the current layer (filters = A, pixels = B) come from LDS.  A work item is
+// MT pixel tiles x NT filter tiles of 16 x 16, so every LDS fragment feeds
+// several MFMAs.
 //
 // Arithmetic is the same as conv16_kernel's, step for step: the same chunk
 // order along (r, s, c), the same MFMA 16x16x32 accumulation, the same
@@ -38,7 +46,215 @@ __device__ __forceinline__ int opaque(int v) {
   return r;
 }
 
-// Work item of a conv layer: one tile of 16 output pixels x NT filter tiles.
+// A layer descriptor unpacked into scalar registers.
+struct LayerRegs {
+  const void* packed;
+  int in_off, out_off, res_off, w_off, blob_units, nchunk;
+  int ps_in, ps_out, ps_res, cs_out, res_cs, Kp;
+  int H, W, P, Q, S, stride, pad, cpt, nsteps, FT, MT, NT, res_W, res_ss, flags;
+};
+
+__device__ __forceinline__ LayerRegs unpack(const ResLayer& L) {
+  LayerRegs r;
+  r.packed = L.packed;
+  const uint32_t off0 = L.off0, off1 = L.off1, sz = L.sz, ps0 = L.ps0, ps1 = L.ps1, ch = L.ch;
+  const uint32_t g0 = L.g0, g1 = L.g1, g2 = L.g2, g3 = L.g3;
+  r.in_off = opaque(off0 & 0xffff);   r.out_off = opaque(off0 >> 16);
+  r.res_off = opaque(off1 & 0xffff);  r.w_off = opaque(off1 >> 16);
+  r.blob_units = opaque(sz & 0xffff); r.nchunk = opaque(sz >> 16);
+  r.ps_in = opaque(ps0 & 0xffff);     r.ps_out = opaque(ps0 >> 16);
+  r.ps_res = opaque(ps1 & 0xffff);    r.cs_out = opaque(ps1 >> 16);
+  r.res_cs = opaque(ch & 0xffff);     r.Kp = opaque(ch >> 16);
+  r.H = opaque(g0 & 255);  r.W = opaque((g0 >> 8) & 255);
+  r.P = opaque((g0 >> 16) & 255);  r.Q = opaque(g0 >> 24);
+  r.S = opaque(g1 & 255);  r.stride = opaque((g1 >> 8) & 255);
+  r.pad = opaque((g1 >> 16) & 255);  r.cpt = opaque(g1 >> 24);
+  r.nsteps = opaque(g2 & 255);  r.FT = opaque((g2 >> 8) & 255);
+  r.MT = opaque((g2 >> 16) & 255);  r.NT = opaque(g2 >> 24);
+  r.res_W = opaque(g3 & 255);  r.res_ss = opaque((g3 >> 8) & 255);
+  r.flags = opaque(g3 >> 16);
+  return r;
+}
+
+// All work items of one conv layer that fall to this wave.  LAST: the layer
+// writes the network output to global memory instead of LDS.
+//
+// The K loop keeps D steps of operands in flight (ring of register buffers,
+// loop unrolled by D) and reads the tap-table entry of a step one issue ahead
+// of that step's operand reads, so that a step costs one LDS round trip spread
+// over D steps rather than two in series.
+template <bool BF, int MT, int NT, bool LAST>
+__device__ __forceinline__ void conv_items(const LayerRegs& L, const ResParams& p, char* act,
+                                           const int2* tab, int n, int lane, int wave) {
+  constexpr int D = (MT + NT <= 2) ? 4 : (MT + NT <= 4 ? 3 : 2);
+  const int li = lane & 15, g = lane >> 4;
+  const int H = L.H, W = L.W, Q = L.Q;
+  const int ps_in = L.ps_in, ps_out = L.ps_out;
+  const int stride = L.stride, pad = L.pad, nsteps = L.nsteps;
+  const int FT = L.FT, Kp = L.Kp;
+  const bool relu = (L.flags & kResRelu) != 0, has_res = L.res_off != 0xffff;
+  const int M = L.P * Q;
+  const int n_ptiles = (M + 15) >> 4;
+  const int n_pgroups = (n_ptiles + MT - 1) / MT;
+  const int n_fgroups = (FT + NT - 1) / NT;
+  const int n_items = n_pgroups * n_fgroups;
+  const int ycs = LAST ? p.y_cs : L.cs_out;
+
+  const char* in = act + L.in_off * 16;
+  const char* wblob = act + L.w_off * 16;
+  const float* bias = reinterpret_cast<const float*>(wblob);
+  const char* wts = wblob + (Kp * 4 + 255) / 256 * 256;
+  const int wstep = 4 * Kp * 16;   // bytes per MFMA step
+  const char* res = act + L.res_off * 16;
+  const int2* tabg = tab + g;
+
+  for (int item = wave; item < n_items; item += kWaves) {
+    const int pg = item / n_fgroups;
+    const int ft0 = (item - pg * n_fgroups) * NT;
+    int m[MT], ih0[MT], iw0[MT], base[MT], roff[MT];
+    bool pv[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      m[mt] = (pg * MT + mt) * 16 + li;
+      pv[mt] = m[mt] < M;
+      const int mm = pv[mt] ? m[mt] : 0;
+      const int pp = mm / Q, qq = mm - pp * Q;
+      ih0[mt] = pp * stride - pad;
+      iw0[mt] = qq * stride - pad;
+      base[mt] = (ih0[mt] * W + iw0[mt]) * ps_in * 2;
+      roff[mt] = ((pp * L.res_ss) * L.res_W + qq * L.res_ss) * L.ps_res * 2;
+    }
+    int woff[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) woff[t] = (g * Kp + min(ft0 + t, FT - 1) * 16 + li) * 16;
+
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int t = 0; t < NT; ++t) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    uint4 a[D][NT], b[D][MT];
+    const char* wp = wts;   // weights of the next step to be issued
+    int ls = 0;             // next step to be issued
+    int2 e_pre;             // its tap-table entry
+    auto operands = [&](const int2 e, uint4* av, uint4* bv) {
+      const int r = e.y >> 8, s = e.y & 255;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const bool ok = pv[mt] && e.y >= 0 && (unsigned)(ih0[mt] + r) < (unsigned)H &&
+                        (unsigned)(iw0[mt] + s) < (unsigned)W;
+        bv[mt] = ok ? *reinterpret_cast<const uint4*>(in + base[mt] + e.x) : uint4{0u, 0u, 0u, 0u};
+      }
+#pragma unroll
+      for (int t = 0; t < NT; ++t) av[t] = *reinterpret_cast<const uint4*>(wp + woff[t]);
+      wp += wstep;
+      ++ls;
+    };
+
+    {
+      int2 e0[D];
+#pragma unroll
+      for (int d = 0; d < D; ++d) e0[d] = tabg[min(d, nsteps - 1) * 4];
+      e_pre = tabg[min(D, nsteps - 1) * 4];
+#pragma unroll
+      for (int d = 0; d < D; ++d)
+        if (d < nsteps) operands(e0[d], a[d], b[d]);
+    }
+    for (int step0 = 0; step0 < nsteps; step0 += D) {
+#pragma unroll
+      for (int d = 0; d < D; ++d) {
+        if (step0 + d < nsteps) {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+              acc[mt][t] = mfma_16x16x32<BF>(a[d][t], b[d][mt], acc[mt][t]);
+          if (ls < nsteps) {
+            const int2 e = e_pre;
+            e_pre = tabg[min(ls + 1, nsteps - 1) * 4];
+            operands(e, a[d], b[d]);
+          }
+        }
+      }
+    }
+
+    // epilogue: bias, shortcut, ReLU, one rounding.  All LDS reads first.
+    float4 b4[NT];
+    uint2 rv[MT][NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const int k0 = (min(ft0 + t, FT - 1)) * 16 + g * 4;
+      b4[t] = *reinterpret_cast<const float4*>(bias + k0);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const bool rd = has_res && pv[mt] && k0 < L.res_cs;
+        rv[mt][t] = rd ? *reinterpret_cast<const uint2*>(res + roff[mt] + k0 * 2) : uint2{0u, 0u};
+      }
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        const int k0 = (ft0 + t) * 16 + g * 4;
+        if (!pv[mt] || ft0 + t >= FT || k0 >= ycs) continue;
+        float v[4] = {acc[mt][t][0] + b4[t].x, acc[mt][t][1] + b4[t].y, acc[mt][t][2] + b4[t].z,
+                      acc[mt][t][3] + b4[t].w};
+        if (has_res) {
+          v[0] += to_float<BF>((uint16_t)(rv[mt][t].x & 0xffffu));
+          v[1] += to_float<BF>((uint16_t)(rv[mt][t].x >> 16));
+          v[2] += to_float<BF>((uint16_t)(rv[mt][t].y & 0xffffu));
+          v[3] += to_float<BF>((uint16_t)(rv[mt][t].y >> 16));
+        }
+        if (relu) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i], 0.f);
+        }
+        uint2 o;
+        o.x = (uint32_t)from_float<BF>(v[0]) | ((uint32_t)from_float<BF>(v[1]) << 16);
+        o.y = (uint32_t)from_float<BF>(v[2]) | ((uint32_t)from_float<BF>(v[3]) << 16);
+        if constexpr (LAST) {
+          uint16_t* yp = reinterpret_cast<uint16_t*>(p.y) +
+                         ((size_t)n * p.out_pixels + m[mt]) * p.y_cs;
+          *reinterpret_cast<uint2*>(yp + k0) = o;
+        } else {
+          char* yp = act + L.out_off * 16 + (m[mt] * ps_out + k0) * 2;
+          *reinterpret_cast<uint2*>(yp) = o;
+        }
+      }
+    }
+  }
+}
+
+template <bool BF, int MT, int NT>
+__device__ __forceinline__ void conv_layer(const LayerRegs& L, const ResParams& p, char* act,
+                                           const int2* tab, int n, int lane, int wave) {
+  if (L.flags & kResLast) conv_items<BF, MT, NT, true>(L, p, act, tab, n, lane, wave);
+  else conv_items<BF, MT, NT, false>(L, p, act, tab, n, lane, wave);
+}
+
+// A layer's parameter blob: global memory -> registers (issued early) ...
+__device__ __forceinline__ void fetch_blob(const void* packed, int units, int tid,
+                                           uint4 (&wreg)[kResPrefetch]) {
+  const uint4* src = reinterpret_cast<const uint4*>(packed);
+#pragma unroll
+  for (int k = 0; k < kResPrefetch; ++k) {
+    const int idx = tid + k * kResThreads;
+    wreg[k] = idx < units ? src[idx] : uint4{0u, 0u, 0u, 0u};
+  }
+}
+
+// ... and registers -> LDS (after the current layer's compute).
+__device__ __forceinline__ void commit_blob(int w_off, int units, int tid, char* act,
+                                            const uint4 (&wreg)[kResPrefetch]) {
+  uint4* dst = reinterpret_cast<uint4*>(act + w_off * 16);
+#pragma unroll
+  for (int k = 0; k < kResPrefetch; ++k) {
+    const int idx = tid + k * kResThreads;
+    if (idx < units) dst[idx] = wreg[k];
+  }
+}
+
 template <bool BF>
 __global__ __launch_bounds__(kResThreads) void resident_kernel(const ResParams p) {
   extern __shared__ uint4 lds4[];
@@ -48,29 +264,45 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(const ResParams p
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int li = lane & 15, g = lane >> 4;
   const int n = blockIdx.x;
 
-  // stage the image into LDS
+  // parameters of the layer after the current one travel through these registers
+  uint4 wreg[kResPrefetch];
+  LayerRegs L = unpack(p.layers[0]);
+  fetch_blob(L.packed, L.blob_units, tid, wreg);
   {
+    // stage the image into LDS at the LDS pixel stride
+    const int cpp = p.in_cs >> 3, lpp = p.in_ps >> 3;
     const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(p.x) +
-                                                      (size_t)n * p.in_elems);
-    uint4* dst = reinterpret_cast<uint4*>(act + (size_t)p.in_off * 16);
-    for (int i = tid; i < p.in_elems / 8; i += kResThreads) dst[i] = src[i];
+                                                      (size_t)n * p.in_pixels * p.in_cs);
+    uint4* dst = reinterpret_cast<uint4*>(act + p.in_off * 16);
+    const int total = p.in_pixels * cpp;
+    for (int i = tid; i < total; i += kResThreads) {
+      const int pix = i / cpp, ch = i - pix * cpp;
+      dst[pix * lpp + ch] = src[i];
+    }
   }
+  commit_blob(L.w_off, L.blob_units, tid, act, wreg);
 
-  for (int l = 0; l < p.n_layers; ++l) {
-    const ResLayer& L = p.layers[l];
+  const int n_layers = __builtin_amdgcn_readfirstlane(p.n_layers);
+  for (int l = 0; l < n_layers; ++l) {
+    const bool has_next = l + 1 < n_layers;
+    LayerRegs Ln = L;
+    if (has_next) {
+      Ln = unpack(p.layers[l + 1]);
+      fetch_blob(Ln.packed, Ln.blob_units, tid, wreg);
+    }
+
     int2* tab = tables + (l & 1) * kResTableEntries;
-    if (L.kind == 0) {
-      const int W = opaque(L.W), cs = opaque(L.cs_in), cpt = opaque(L.cpt), S = opaque(L.S);
-      const int nentries = opaque(L.nsteps) * 4;
+    if (!(L.flags & kResMean)) {
+      const int W = L.W, ps = L.ps_in, cpt = L.cpt, S = L.S;
+      const int nentries = L.nsteps * 4, nchunk = L.nchunk;
       for (int j = tid; j < nentries; j += kResThreads) {
         int2 e;
-        if (j < L.nchunk) {
+        if (j < nchunk) {
           const int tap = j / cpt, c8 = j - tap * cpt;
           const int r = tap / S, s = tap - r * S;
-          e.x = ((r * W + s) * cs + c8 * 8) * 2;   // byte offset
+          e.x = ((r * W + s) * ps + c8 * 8) * 2;   // byte offset
           e.y = (r << 8) | s;
         } else {
           e.x = 0;
@@ -79,145 +311,33 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(const ResParams p
         tab[j] = e;
       }
     }
-    __syncthreads();   // previous layer's output and this layer's table are visible
+    __syncthreads();   // previous layer's output, this layer's parameters and table are visible
 
-    if (L.kind == 1) {
+    if (L.flags & kResMean) {
       // global mean over H*W, sequential fp32 sum per channel
-      const int hw = opaque(L.H) * opaque(L.W), cs = opaque(L.cs_in);
-      const uint16_t* in = reinterpret_cast<const uint16_t*>(act + (size_t)L.in_off * 16);
+      const int hw = L.H * L.W, ps = L.ps_in;
+      const uint16_t* in = reinterpret_cast<const uint16_t*>(act + L.in_off * 16);
       for (int c = tid; c < L.cs_out; c += kResThreads) {
         float acc = 0.f;
-        for (int i = 0; i < hw; ++i) acc += to_float<BF>(in[i * cs + c]);
+        for (int i = 0; i < hw; ++i) acc += to_float<BF>(in[i * ps + c]);
         const uint16_t o = from_float<BF>(acc / (float)hw);
-        if (L.last) reinterpret_cast<uint16_t*>(p.y)[(size_t)n * p.y_cs + c] = o;
-        else reinterpret_cast<uint16_t*>(act + (size_t)L.out_off * 16)[c] = o;
+        if (L.flags & kResLast) reinterpret_cast<uint16_t*>(p.y)[(size_t)n * p.y_cs + c] = o;
+        else reinterpret_cast<uint16_t*>(act + L.out_off * 16)[c] = o;
       }
-      continue;
-    }
-
-    // ---- convolution ---------------------------------------------------------
-    const int H = opaque(L.H), W = opaque(L.W), P = opaque(L.P), Q = opaque(L.Q);
-    const int cs_in = opaque(L.cs_in), cs_out = opaque(L.cs_out);
-    const int stride = opaque(L.stride), pad = opaque(L.pad), nsteps = opaque(L.nsteps);
-    const int FT = opaque(L.FT), NT = opaque(L.NT), Kp = opaque(L.Kp);
-    const int res_W = opaque(L.res_W), res_ss = opaque(L.res_ss), res_cs = opaque(L.res_cs);
-    const int M = P * Q;
-    const int n_ptiles = (M + 15) >> 4;
-    const int n_fgroups = (FT + NT - 1) / NT;
-    const int n_items = n_ptiles * n_fgroups;
-    const char* blob = reinterpret_cast<const char*>(L.packed);
-    const float* bias = reinterpret_cast<const float*>(blob);
-    const uint16_t* wts = reinterpret_cast<const uint16_t*>(
-        blob + ((size_t)Kp * 4 + 255) / 256 * 256);
-    const char* in = act + (size_t)L.in_off * 16;
-    const size_t wstep = (size_t)4 * Kp * 8;
-
-    // per-item lane state
-    int ih0 = 0, iw0 = 0, base = 0, m = 0, ft0 = 0;
-    bool pv = false;
-    auto decode = [&](int item) {
-      const int pt = item / n_fgroups;
-      ft0 = (item - pt * n_fgroups) * NT;
-      m = pt * 16 + li;
-      pv = m < M;
-      const int mm = pv ? m : 0;
-      const int pp = mm / Q, qq = mm - pp * Q;
-      ih0 = pp * stride - pad;
-      iw0 = qq * stride - pad;
-      base = ((ih0 * W + iw0) * cs_in) * 2;
-    };
-    auto load = [&](int step, uint4* a, uint4& b) {
-      const int2 e = tab[step * 4 + g];
-      const int r = e.y >> 8, s = e.y & 255;
-      const bool ok = pv && e.y >= 0 && (unsigned)(ih0 + r) < (unsigned)H &&
-                      (unsigned)(iw0 + s) < (unsigned)W;
-      b = ok ? *reinterpret_cast<const uint4*>(in + base + e.x) : uint4{0u, 0u, 0u, 0u};
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        if (t < NT) {
-          const int tt = min(ft0 + t, FT - 1);
-          a[t] = *reinterpret_cast<const uint4*>(wts + (size_t)step * wstep +
-                                                 ((size_t)g * Kp + tt * 16 + li) * 8);
-        }
-      }
-    };
-
-    int item = wave;
-    if (item < n_items) {
-      f32x4 acc[4];
-#pragma unroll
-      for (int t = 0; t < 4; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-      uint4 a_cur[4], a_nxt[4], b_cur, b_nxt;
-      decode(item);
-      load(0, a_cur, b_cur);
-      int step = 0;
-      while (true) {
-        // state of the item being computed, kept for its epilogue
-        const int c_m = m, c_ft0 = ft0;
-        const bool c_pv = pv;
-        int nstep = step + 1, nitem = item;
-        if (nstep == nsteps) {
-          nstep = 0;
-          nitem = item + kWaves;
-        }
-        const bool more = nitem < n_items;
-        if (more) {
-          if (nstep == 0) decode(nitem);
-          load(nstep, a_nxt, b_nxt);
-        }
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-          if (t < NT) acc[t] = mfma_16x16x32<BF>(a_cur[t], b_cur, acc[t]);
-
-        if (step == nsteps - 1) {
-          // epilogue of the finished item
-          if (c_pv) {
-            const int pp = c_m / Q, qq = c_m - pp * Q;
-            const uint16_t* rp = nullptr;
-            if (L.res_off != 0xffff)
-              rp = reinterpret_cast<const uint16_t*>(act + (size_t)L.res_off * 16) +
-                   ((pp * res_ss) * res_W + qq * res_ss) * res_cs;
-            uint16_t* yp = L.last
-                               ? reinterpret_cast<uint16_t*>(p.y) +
-                                     ((size_t)n * p.out_pixels + c_m) * p.y_cs
-                               : reinterpret_cast<uint16_t*>(act + (size_t)L.out_off * 16) +
-                                     c_m * cs_out;
-            const int ycs = L.last ? p.y_cs : cs_out;
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-              const int k0 = (c_ft0 + t) * 16 + g * 4;
-              if (t >= NT || c_ft0 + t >= FT || k0 >= ycs) continue;
-              const float4 b4 = *reinterpret_cast<const float4*>(bias + k0);
-              float v[4] = {acc[t][0] + b4.x, acc[t][1] + b4.y, acc[t][2] + b4.z,
-                            acc[t][3] + b4.w};
-              if (rp && k0 < res_cs) {
-                const uint2 rv = *reinterpret_cast<const uint2*>(rp + k0);
-                v[0] += to_float<BF>((uint16_t)(rv.x & 0xffffu));
-                v[1] += to_float<BF>((uint16_t)(rv.x >> 16));
-                v[2] += to_float<BF>((uint16_t)(rv.y & 0xffffu));
-                v[3] += to_float<BF>((uint16_t)(rv.y >> 16));
-              }
-              if (L.relu) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i], 0.f);
-              }
-              uint2 o;
-              o.x = (uint32_t)from_float<BF>(v[0]) | ((uint32_t)from_float<BF>(v[1]) << 16);
-              o.y = (uint32_t)from_float<BF>(v[2]) | ((uint32_t)from_float<BF>(v[3]) << 16);
-              *reinterpret_cast<uint2*>(yp + k0) = o;
-            }
-          }
-#pragma unroll
-          for (int t = 0; t < 4; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
-        if (!more) break;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) a_cur[t] = a_nxt[t];
-        b_cur = b_nxt;
-        item = nitem;
-        step = nstep;
+    } else {
+      switch (L.MT * 8 + L.NT) {
+        case 1 * 8 + 1: conv_layer<BF, 1, 1>(L, p, act, tab, n, lane, wave); break;
+        case 1 * 8 + 2: conv_layer<BF, 1, 2>(L, p, act, tab, n, lane, wave); break;
+        case 1 * 8 + 3: conv_layer<BF, 1, 3>(L, p, act, tab, n, lane, wave); break;
+        case 1 * 8 + 4: conv_layer<BF, 1, 4>(L, p, act, tab, n, lane, wave); break;
+        case 2 * 8 + 1: conv_layer<BF, 2, 1>(L, p, act, tab, n, lane, wave); break;
+        case 2 * 8 + 2: conv_layer<BF, 2, 2>(L, p, act, tab, n, lane, wave); break;
+        case 3 * 8 + 1: conv_layer<BF, 3, 1>(L, p, act, tab, n, lane, wave); break;
+        default: conv_layer<BF, 4, 1>(L, p, act, tab, n, lane, wave); break;
       }
     }
+    if (has_next) commit_blob(Ln.w_off, Ln.blob_units, tid, act, wreg);
+    L = Ln;
   }
 }
 

@@ -307,7 +307,7 @@ def resident_models():
         synth.make_cifar_resnet(31, "bf16", 3, 400),
         synth.make_cifar_resnet(32, "f16", 2, 250, widths=(8, 24, 40), size=24, classes=13),
         synth.make_block_model(33, "bf16", 16, 32, 250),
-        synth.make_cifar_resnet(34, "bf16", 1, 0, widths=(16, 32, 64), size=32),
+        synth.make_cifar_resnet(34, "bf16", 1, 250, widths=(16, 32, 64), size=32),
     ]
 
 
