@@ -23,13 +23,16 @@ __device__ __forceinline__ float to_float(uint16_t h) {
 template <bool BF>
 __device__ __forceinline__ uint16_t from_float(float f) {
   if constexpr (BF) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    return __builtin_bit_cast(uint16_t, (__bf16)f);   // v_cvt_pk_bf16_f32 on gfx950
   } else {
     return __builtin_bit_cast(uint16_t, (_Float16)f);
   }
+}
+
+// Two floats rounded to nearest even and packed, a in the low half.
+template <bool BF>
+__device__ __forceinline__ uint32_t pack2(float a, float b) {
+  return (uint32_t)from_float<BF>(a) | ((uint32_t)from_float<BF>(b) << 16);
 }
 
 template <bool BF>

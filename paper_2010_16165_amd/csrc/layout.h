@@ -80,25 +80,31 @@ constexpr size_t kResLdsLimit = 160 * 1024;
 // prefetch in flight).
 struct ResLayer {             // 48 bytes
   const void* packed;         // conv: blob (bias + weights) in global memory
-  uint32_t off0;              // in_off | out_off << 16        LDS offsets, 16-byte units
-  uint32_t off1;              // res_off | w_off << 16         res_off 0xffff = none
-  uint32_t sz;                // blob_units | nchunk << 16     blob_units: 16-byte units staged to w_off
-  uint32_t ps0;               // ps_in | ps_out << 16          LDS pixel strides, elements
-  uint32_t ps1;               // ps_res | cs_out << 16         cs_out: lanes written per output pixel
-  uint32_t ch;                // res_cs | Kp << 16             res_cs: lanes held per residual pixel
-  uint32_t g0;                // H | W << 8 | P << 16 | Q << 24
-  uint32_t g1;                // S | stride << 8 | pad << 16 | cpt << 24
-  uint32_t g2;                // nsteps | FT << 8 | MT << 16 | NT << 24   work item: MT x NT tiles
-  uint32_t g3;                // res_W | res_ss << 8 | flags << 16
+  uint32_t off0;              // in_org | out_org << 16     LDS offsets, 16-byte units (see below)
+  uint32_t off1;              // res_org | w_off << 16      res_org 0xffff = none
+  uint32_t sz;                // blob_units | nchunk << 16  blob_units: 16-byte units staged to w_off
+  uint32_t ps0;               // ps_in | ps_out << 16       LDS pixel strides, elements
+  uint32_t ps1;               // ps_res | cs_out << 16      cs_out: lanes written per output pixel
+  uint32_t ch;                // res_cs | Kp << 16          res_cs: lanes held per residual pixel
+  uint32_t g0;                // Wh_in | Wh_out << 8 | P << 16 | Q << 24   Wh: pixels per LDS row
+  uint32_t g1;                // S | stride << 8 | cpt << 16 | nsteps << 24
+  uint32_t g2;                // FT | MT << 8 | NT << 16 | res_Wh << 24    work item: MT x NT tiles
+  uint32_t g3;                // res_ss | flags << 8 | out_halo << 16
 };
+// Tensors in LDS carry a halo of zero pixels.  in_org is the LDS offset of the
+// pixel that tap (0, 0) of output pixel (0, 0) reads; out_org and res_org are
+// the offsets of interior pixel (0, 0).  For the global-mean layer P x Q is the
+// INPUT extent and in_org its interior origin.
 static_assert(sizeof(ResLayer) == 48, "ResLayer must stay 48 bytes");
 constexpr int kResMean = 1, kResRelu = 2, kResLast = 4;
 
 struct ResParams {
   const void* x;    // N images, NHWC
   void* y;          // N x out_pixels x y_cs
-  int in_pixels, in_cs, in_ps;   // image: pixels, global channel stride, LDS pixel stride
-  int in_off;       // LDS offset (16-byte units) the image is staged to
+  int in_H, in_W, in_Wh;         // image extent and pixels per LDS row (in_W + 2 * hp)
+  int in_cs, in_ps;              // global channel stride, LDS pixel stride (elements)
+  int in_org;                    // LDS offset (16-byte units) of the image's interior pixel (0, 0)
+  int hp;                        // halo width of every LDS tensor larger than 1 x 1
   int y_cs, out_pixels;
   int n_layers;
   int lds_bytes;

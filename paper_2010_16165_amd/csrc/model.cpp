@@ -112,7 +112,15 @@ void plan_resident(fupr_model* m) {
   for (const TensorInfo& t : m->tensors)
     if (t.H > 255 || t.W > 255 || t.cs > 4096) return;
 
-  const size_t table_bytes = 2 * kResTableEntries * sizeof(int32_t) * 2;
+  // every LDS tensor larger than 1 x 1 gets a ring of hp zero pixels
+  int hp = 0;
+  for (const fupr_op_desc& op : m->ops)
+    if (op.kind == FUPR_OP_CONV) hp = std::max(hp, op.conv.pad);
+  for (const TensorInfo& t : m->tensors)
+    if (t.W + 2 * hp > 255 || t.H + 2 * hp > 255) return;
+  auto halo_of = [&](const TensorInfo& t) { return t.H * t.W > 1 ? hp : 0; };
+
+  const size_t table_bytes = 2 * kResTableEntries * sizeof(int32_t);
   const size_t budget_units = (kResLdsLimit - table_bytes) / 16;
 
   // pad = 1: LDS pixel stride = channel stride + 8 elements, which spreads the
@@ -121,12 +129,14 @@ void plan_resident(fupr_model* m) {
   for (int pad = 1; pad >= 0; --pad) {
     std::vector<LdsBlock> blocks(2 * (size_t)n + 1);
     auto stride_of = [&](const TensorInfo& t) { return t.cs + (pad && t.H * t.W > 1 ? 8 : 0); };
+    auto row_of = [&](const TensorInfo& t) { return t.W + 2 * halo_of(t); };
     for (int tid = 0; tid <= n; ++tid) {
       const TensorInfo& t = m->tensors[tid];
       LdsBlock& b = blocks[tid];
       b.first = tid - 1;                       // produced by layer tid-1 (image: before layer 0)
       b.last = std::max(t.last_use, b.first);
-      b.units = tid == n ? 0 : (size_t)t.H * t.W * stride_of(t) * 2 / 16;
+      b.units = tid == n ? 0
+                         : (size_t)(t.H + 2 * halo_of(t)) * row_of(t) * stride_of(t) * 2 / 16;
     }
     bool ok = true;
     for (int i = 0; i < n && ok; ++i) {
@@ -144,13 +154,22 @@ void plan_resident(fupr_model* m) {
     const size_t extent = assign_offsets(blocks);
     if (extent > budget_units || extent >= 0xffff) continue;
 
+    // LDS offset (16-byte units) of pixel (row, col) counted from the halo's corner
+    auto pixel_at = [&](int tid, int row, int col) {
+      const TensorInfo& t = m->tensors[tid];
+      return (uint32_t)(blocks[tid].offset + (size_t)(row * row_of(t) + col) * stride_of(t) / 8);
+    };
+
     ResParams& R = m->resident;
     R = ResParams{};
     const TensorInfo& t0 = m->tensors[0];
-    R.in_pixels = t0.H * t0.W;
+    R.in_H = t0.H;
+    R.in_W = t0.W;
+    R.in_Wh = row_of(t0);
     R.in_cs = t0.cs;
     R.in_ps = stride_of(t0);
-    R.in_off = (int)blocks[0].offset;
+    R.in_org = (int)pixel_at(0, halo_of(t0), halo_of(t0));
+    R.hp = hp;
     R.n_layers = n;
     R.lds_bytes = (int)(table_bytes + extent * 16);
     R.out_pixels = m->tensors[n].H * m->tensors[n].W;
@@ -158,26 +177,33 @@ void plan_resident(fupr_model* m) {
       const fupr_op_desc& op = m->ops[i];
       const TensorInfo& ti = m->tensors[op.in];
       const TensorInfo& to = m->tensors[i + 1];
-      uint32_t in_off = (uint32_t)blocks[op.in].offset, out_off = (uint32_t)blocks[i + 1].offset;
-      uint32_t res_off = 0xffff, w_off = (uint32_t)blocks[n + 1 + i].offset;
+      const bool last = i + 1 == n;
+      uint32_t in_org = 0, out_org = last ? 0 : pixel_at(i + 1, halo_of(to), halo_of(to));
+      uint32_t res_org = 0xffff, w_off = (uint32_t)blocks[n + 1 + i].offset;
       uint32_t blob_units = (uint32_t)blocks[n + 1 + i].units, nchunk = 0;
       uint32_t ps_in = (uint32_t)stride_of(ti), ps_out = (uint32_t)stride_of(to), ps_res = 0;
       uint32_t cs_out = (uint32_t)to.cs, res_cs = 0, Kp = 0;
-      uint32_t S = 0, stride = 0, padding = 0, cpt = 0, nsteps = 0, FT = 0, MT = 1, NT = 1;
-      uint32_t res_W = 0, res_ss = 0, flags = i + 1 == n ? kResLast : 0;
+      uint32_t S = 0, stride = 0, cpt = 0, nsteps = 0, FT = 0, MT = 1, NT = 1;
+      uint32_t res_Wh = 0, res_ss = 0, flags = last ? kResLast : 0;
+      uint32_t P = (uint32_t)to.H, Q = (uint32_t)to.W;
       const void* packed = nullptr;
       if (op.kind == FUPR_OP_AVGPOOL) {
         flags |= kResMean;
+        in_org = pixel_at(op.in, halo_of(ti), halo_of(ti));
+        P = (uint32_t)ti.H;      // the mean layer iterates over its INPUT extent
+        Q = (uint32_t)ti.W;
       } else if (op.kind == FUPR_OP_CONV) {
         const fupr_conv_shape& s = op.conv;
         const PackedLayout PL = packed_layout(s, m->dt);
-        if (PL.nchunk_pad > kResTableEntries || s.S > 255 || s.stride > 255 || s.pad > 255 ||
+        if (PL.nchunk_pad > kResTableEntries || s.S > 255 || s.stride > 255 ||
             PL.Cp / 8 > 255 || PL.Kp / 16 > 255 || PL.Kp > 4096)
           return;
+        if (halo_of(ti) < s.pad) return;   // a padded conv on a 1 x 1 image: not laid out here
         packed = op.packed;
+        in_org = pixel_at(op.in, halo_of(ti) - s.pad, halo_of(ti) - s.pad);
         nchunk = (uint32_t)PL.nchunk;
         Kp = (uint32_t)PL.Kp;
-        S = (uint32_t)s.S; stride = (uint32_t)s.stride; padding = (uint32_t)s.pad;
+        S = (uint32_t)s.S; stride = (uint32_t)s.stride;
         cpt = (uint32_t)(PL.Cp / 8);
         nsteps = (uint32_t)(PL.nchunk_pad / 4);
         FT = (uint32_t)(PL.Kp / 16);
@@ -189,27 +215,28 @@ void plan_resident(fupr_model* m) {
         if (op.res >= 0) {
           if (op.res_c_offset != 0 || op.res_spatial_stride > 255) return;
           const TensorInfo& tr = m->tensors[op.res];
-          res_off = (uint32_t)blocks[op.res].offset;
+          res_org = pixel_at(op.res, halo_of(tr), halo_of(tr));
           res_cs = (uint32_t)tr.cs;
           ps_res = (uint32_t)stride_of(tr);
-          res_W = (uint32_t)tr.W;
+          res_Wh = (uint32_t)row_of(tr);
           res_ss = (uint32_t)op.res_spatial_stride;
         }
       } else {
         return;   // max-pool networks have images too large for LDS anyway
       }
+      if (in_org >= 0xffff || out_org >= 0xffff || (res_org != 0xffff && res_org >= 0xffff)) return;
       ResLayer L{};
       L.packed = packed;
-      L.off0 = in_off | out_off << 16;
-      L.off1 = res_off | w_off << 16;
+      L.off0 = in_org | out_org << 16;
+      L.off1 = res_org | w_off << 16;
       L.sz = blob_units | nchunk << 16;
       L.ps0 = ps_in | ps_out << 16;
       L.ps1 = ps_res | cs_out << 16;
       L.ch = res_cs | Kp << 16;
-      L.g0 = (uint32_t)ti.H | (uint32_t)ti.W << 8 | (uint32_t)to.H << 16 | (uint32_t)to.W << 24;
-      L.g1 = S | stride << 8 | padding << 16 | cpt << 24;
-      L.g2 = nsteps | FT << 8 | MT << 16 | NT << 24;
-      L.g3 = res_W | res_ss << 8 | flags << 16;
+      L.g0 = (uint32_t)row_of(ti) | (uint32_t)row_of(to) << 8 | P << 16 | Q << 24;
+      L.g1 = S | stride << 8 | cpt << 16 | nsteps << 24;
+      L.g2 = FT | MT << 8 | NT << 16 | res_Wh << 24;
+      L.g3 = res_ss | flags << 8 | (uint32_t)halo_of(to) << 16;
       R.layers[i] = L;
     }
     m->resident_ok = true;

@@ -49,9 +49,9 @@ __device__ __forceinline__ int opaque(int v) {
 // A layer descriptor unpacked into scalar registers.
 struct LayerRegs {
   const void* packed;
-  int in_off, out_off, res_off, w_off, blob_units, nchunk;
+  int in_org, out_org, res_org, w_off, blob_units, nchunk;
   int ps_in, ps_out, ps_res, cs_out, res_cs, Kp;
-  int H, W, P, Q, S, stride, pad, cpt, nsteps, FT, MT, NT, res_W, res_ss, flags;
+  int Wh_in, Wh_out, P, Q, S, stride, cpt, nsteps, FT, MT, NT, res_Wh, res_ss, flags, out_halo;
 };
 
 __device__ __forceinline__ LayerRegs unpack(const ResLayer& L) {
@@ -59,74 +59,100 @@ __device__ __forceinline__ LayerRegs unpack(const ResLayer& L) {
   r.packed = L.packed;
   const uint32_t off0 = L.off0, off1 = L.off1, sz = L.sz, ps0 = L.ps0, ps1 = L.ps1, ch = L.ch;
   const uint32_t g0 = L.g0, g1 = L.g1, g2 = L.g2, g3 = L.g3;
-  r.in_off = opaque(off0 & 0xffff);   r.out_off = opaque(off0 >> 16);
-  r.res_off = opaque(off1 & 0xffff);  r.w_off = opaque(off1 >> 16);
+  r.in_org = opaque(off0 & 0xffff);   r.out_org = opaque(off0 >> 16);
+  r.res_org = opaque(off1 & 0xffff);  r.w_off = opaque(off1 >> 16);
   r.blob_units = opaque(sz & 0xffff); r.nchunk = opaque(sz >> 16);
   r.ps_in = opaque(ps0 & 0xffff);     r.ps_out = opaque(ps0 >> 16);
   r.ps_res = opaque(ps1 & 0xffff);    r.cs_out = opaque(ps1 >> 16);
   r.res_cs = opaque(ch & 0xffff);     r.Kp = opaque(ch >> 16);
-  r.H = opaque(g0 & 255);  r.W = opaque((g0 >> 8) & 255);
+  r.Wh_in = opaque(g0 & 255);  r.Wh_out = opaque((g0 >> 8) & 255);
   r.P = opaque((g0 >> 16) & 255);  r.Q = opaque(g0 >> 24);
   r.S = opaque(g1 & 255);  r.stride = opaque((g1 >> 8) & 255);
-  r.pad = opaque((g1 >> 16) & 255);  r.cpt = opaque(g1 >> 24);
-  r.nsteps = opaque(g2 & 255);  r.FT = opaque((g2 >> 8) & 255);
-  r.MT = opaque((g2 >> 16) & 255);  r.NT = opaque(g2 >> 24);
-  r.res_W = opaque(g3 & 255);  r.res_ss = opaque((g3 >> 8) & 255);
-  r.flags = opaque(g3 >> 16);
+  r.cpt = opaque((g1 >> 16) & 255);  r.nsteps = opaque(g1 >> 24);
+  r.FT = opaque(g2 & 255);  r.MT = opaque((g2 >> 8) & 255);
+  r.NT = opaque((g2 >> 16) & 255);  r.res_Wh = opaque(g2 >> 24);
+  r.res_ss = opaque(g3 & 255);  r.flags = opaque((g3 >> 8) & 255);
+  r.out_halo = opaque((g3 >> 16) & 255);
   return r;
+}
+
+// Zeroes the halo ring (hp pixels wide) around a P x Q tensor whose interior
+// starts at byte offset org; Wh = Q + 2*hp pixels per row, ps2 bytes per pixel,
+// chunks 16-byte units per pixel that hold channels.
+__device__ __forceinline__ void zero_halo(char* act, int org, int P, int Q, int Wh, int ps2,
+                                          int chunks, int hp, int tid) {
+  const int raw = org - hp * (Wh + 1) * ps2;
+  const int top_bottom = 2 * hp * Wh;
+  const int total = (top_bottom + 2 * hp * P) * chunks;
+  for (int i = tid; i < total; i += kResThreads) {
+    const int px = i / chunks, ch = i - px * chunks;
+    int row, col;
+    if (px < top_bottom) {
+      const int rr = px / Wh;
+      col = px - rr * Wh;
+      row = rr < hp ? rr : P + rr;
+    } else {
+      const int q = px - top_bottom;
+      const int rr = q / (2 * hp), cc = q - rr * 2 * hp;
+      row = hp + rr;
+      col = cc < hp ? cc : Q + cc;
+    }
+    *reinterpret_cast<uint4*>(act + raw + (row * Wh + col) * ps2 + ch * 16) = uint4{0u, 0u, 0u, 0u};
+  }
 }
 
 // All work items of one conv layer that fall to this wave.  LAST: the layer
 // writes the network output to global memory instead of LDS.
 //
-// The K loop keeps D steps of operands in flight (ring of register buffers,
-// loop unrolled by D) and reads the tap-table entry of a step one issue ahead
-// of that step's operand reads, so that a step costs one LDS round trip spread
-// over D steps rather than two in series.
+// Every activation tensor in LDS carries a ring of zero pixels as wide as the
+// largest padding of any convolution, so a tap never needs a bounds check: the
+// K loop is one table read, MT + NT address additions, MT + NT LDS reads and
+// MT * NT MFMAs per step.  D steps of operands are kept in flight (ring of
+// register buffers, loop unrolled by D), and the table entry of a step is read
+// one issue ahead of that step's operand reads.
 template <bool BF, int MT, int NT, bool LAST>
 __device__ __forceinline__ void conv_items(const LayerRegs& L, const ResParams& p, char* act,
-                                           const int2* tab, int n, int lane, int wave) {
+                                           const int* tab, int n, int lane, int wave) {
   constexpr int D = (MT + NT <= 2) ? 4 : (MT + NT <= 4 ? 3 : 2);
   const int li = lane & 15, g = lane >> 4;
-  const int H = L.H, W = L.W, Q = L.Q;
-  const int ps_in = L.ps_in, ps_out = L.ps_out;
-  const int stride = L.stride, pad = L.pad, nsteps = L.nsteps;
-  const int FT = L.FT, Kp = L.Kp;
-  const bool relu = (L.flags & kResRelu) != 0, has_res = L.res_off != 0xffff;
+  const int Q = L.Q, nsteps = L.nsteps, FT = L.FT, Kp = L.Kp;
+  const bool relu = (L.flags & kResRelu) != 0, has_res = L.res_org != 0xffff;
   const int M = L.P * Q;
+  const uint32_t magicQ = 0xffffffffu / (uint32_t)Q + 1u;   // floor(m / Q) = mulhi(m, magicQ), m < 2^16
   const int n_ptiles = (M + 15) >> 4;
   const int n_pgroups = (n_ptiles + MT - 1) / MT;
   const int n_fgroups = (FT + NT - 1) / NT;
   const int n_items = n_pgroups * n_fgroups;
   const int ycs = LAST ? p.y_cs : L.cs_out;
 
-  const char* in = act + L.in_off * 16;
-  const char* wblob = act + L.w_off * 16;
-  const float* bias = reinterpret_cast<const float*>(wblob);
-  const char* wts = wblob + (Kp * 4 + 255) / 256 * 256;
+  const int in_org = L.in_org * 16, out_org = L.out_org * 16, res_org = L.res_org * 16;
+  const int in_row = L.stride * L.Wh_in * L.ps_in * 2, in_col = L.stride * L.ps_in * 2;
+  const int out_row = L.Wh_out * L.ps_out * 2, out_col = L.ps_out * 2;
+  const int res_row = L.res_ss * L.res_Wh * L.ps_res * 2, res_col = L.res_ss * L.ps_res * 2;
+  const int wblob = L.w_off * 16;
+  const float* bias = reinterpret_cast<const float*>(act + wblob);
+  const int wts = wblob + (Kp * 4 + 255) / 256 * 256;
   const int wstep = 4 * Kp * 16;   // bytes per MFMA step
-  const char* res = act + L.res_off * 16;
-  const int2* tabg = tab + g;
+  const int* tabg = tab + g;
 
   for (int item = wave; item < n_items; item += kWaves) {
     const int pg = item / n_fgroups;
     const int ft0 = (item - pg * n_fgroups) * NT;
-    int m[MT], ih0[MT], iw0[MT], base[MT], roff[MT];
+    int m[MT], bptr[MT], ooff[MT], roff[MT];
     bool pv[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       m[mt] = (pg * MT + mt) * 16 + li;
       pv[mt] = m[mt] < M;
-      const int mm = pv[mt] ? m[mt] : 0;
-      const int pp = mm / Q, qq = mm - pp * Q;
-      ih0[mt] = pp * stride - pad;
-      iw0[mt] = qq * stride - pad;
-      base[mt] = (ih0[mt] * W + iw0[mt]) * ps_in * 2;
-      roff[mt] = ((pp * L.res_ss) * L.res_W + qq * L.res_ss) * L.ps_res * 2;
+      const int mc = min(m[mt], M - 1);
+      const int pp = (int)__umulhi((uint32_t)mc, magicQ), qq = mc - pp * Q;
+      bptr[mt] = in_org + pp * in_row + qq * in_col;
+      ooff[mt] = out_org + pp * out_row + qq * out_col;
+      roff[mt] = res_org + pp * res_row + qq * res_col;
     }
-    int woff[NT];
+    int aptr[NT];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) woff[t] = (g * Kp + min(ft0 + t, FT - 1) * 16 + li) * 16;
+    for (int t = 0; t < NT; ++t) aptr[t] = wts + (g * Kp + min(ft0 + t, FT - 1) * 16 + li) * 16;
 
     f32x4 acc[MT][NT];
 #pragma unroll
@@ -135,25 +161,21 @@ __device__ __forceinline__ void conv_items(const LayerRegs& L, const ResParams& 
       for (int t = 0; t < NT; ++t) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     uint4 a[D][NT], b[D][MT];
-    const char* wp = wts;   // weights of the next step to be issued
-    int ls = 0;             // next step to be issued
-    int2 e_pre;             // its tap-table entry
-    auto operands = [&](const int2 e, uint4* av, uint4* bv) {
-      const int r = e.y >> 8, s = e.y & 255;
+    int ls = 0;   // next step to be issued
+    int e_pre;    // its tap-table entry
+    auto operands = [&](const int e, uint4* av, uint4* bv) {
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const bool ok = pv[mt] && e.y >= 0 && (unsigned)(ih0[mt] + r) < (unsigned)H &&
-                        (unsigned)(iw0[mt] + s) < (unsigned)W;
-        bv[mt] = ok ? *reinterpret_cast<const uint4*>(in + base[mt] + e.x) : uint4{0u, 0u, 0u, 0u};
+      for (int mt = 0; mt < MT; ++mt) bv[mt] = *reinterpret_cast<const uint4*>(act + bptr[mt] + e);
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        av[t] = *reinterpret_cast<const uint4*>(act + aptr[t]);
+        aptr[t] += wstep;
       }
-#pragma unroll
-      for (int t = 0; t < NT; ++t) av[t] = *reinterpret_cast<const uint4*>(wp + woff[t]);
-      wp += wstep;
       ++ls;
     };
 
     {
-      int2 e0[D];
+      int e0[D];
 #pragma unroll
       for (int d = 0; d < D; ++d) e0[d] = tabg[min(d, nsteps - 1) * 4];
       e_pre = tabg[min(D, nsteps - 1) * 4];
@@ -171,7 +193,7 @@ __device__ __forceinline__ void conv_items(const LayerRegs& L, const ResParams& 
             for (int t = 0; t < NT; ++t)
               acc[mt][t] = mfma_16x16x32<BF>(a[d][t], b[d][mt], acc[mt][t]);
           if (ls < nsteps) {
-            const int2 e = e_pre;
+            const int e = e_pre;
             e_pre = tabg[min(ls + 1, nsteps - 1) * 4];
             operands(e, a[d], b[d]);
           }
@@ -188,8 +210,8 @@ __device__ __forceinline__ void conv_items(const LayerRegs& L, const ResParams& 
       b4[t] = *reinterpret_cast<const float4*>(bias + k0);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        const bool rd = has_res && pv[mt] && k0 < L.res_cs;
-        rv[mt][t] = rd ? *reinterpret_cast<const uint2*>(res + roff[mt] + k0 * 2) : uint2{0u, 0u};
+        const bool rd = has_res && k0 < L.res_cs;
+        rv[mt][t] = rd ? *reinterpret_cast<const uint2*>(act + roff[mt] + k0 * 2) : uint2{0u, 0u};
       }
     }
 #pragma unroll
@@ -211,15 +233,14 @@ __device__ __forceinline__ void conv_items(const LayerRegs& L, const ResParams& 
           for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i], 0.f);
         }
         uint2 o;
-        o.x = (uint32_t)from_float<BF>(v[0]) | ((uint32_t)from_float<BF>(v[1]) << 16);
-        o.y = (uint32_t)from_float<BF>(v[2]) | ((uint32_t)from_float<BF>(v[3]) << 16);
+        o.x = pack2<BF>(v[0], v[1]);
+        o.y = pack2<BF>(v[2], v[3]);
         if constexpr (LAST) {
           uint16_t* yp = reinterpret_cast<uint16_t*>(p.y) +
                          ((size_t)n * p.out_pixels + m[mt]) * p.y_cs;
           *reinterpret_cast<uint2*>(yp + k0) = o;
         } else {
-          char* yp = act + L.out_off * 16 + (m[mt] * ps_out + k0) * 2;
-          *reinterpret_cast<uint2*>(yp) = o;
+          *reinterpret_cast<uint2*>(act + ooff[mt] + k0 * 2) = o;
         }
       }
     }
@@ -228,7 +249,7 @@ __device__ __forceinline__ void conv_items(const LayerRegs& L, const ResParams& 
 
 template <bool BF, int MT, int NT>
 __device__ __forceinline__ void conv_layer(const LayerRegs& L, const ResParams& p, char* act,
-                                           const int2* tab, int n, int lane, int wave) {
+                                           const int* tab, int n, int lane, int wave) {
   if (L.flags & kResLast) conv_items<BF, MT, NT, true>(L, p, act, tab, n, lane, wave);
   else conv_items<BF, MT, NT, false>(L, p, act, tab, n, lane, wave);
 }
@@ -259,28 +280,31 @@ template <bool BF>
 __global__ __launch_bounds__(kResThreads) void resident_kernel(const ResParams p) {
   extern __shared__ uint4 lds4[];
   char* lds = reinterpret_cast<char*>(lds4);
-  int2* tables = reinterpret_cast<int2*>(lds);   // two tap tables of kResTableEntries
-  char* act = lds + 2 * kResTableEntries * sizeof(int2);
+  int* tables = reinterpret_cast<int*>(lds);   // two tap tables of kResTableEntries
+  char* act = lds + 2 * kResTableEntries * sizeof(int);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int n = blockIdx.x;
+  const int hp = __builtin_amdgcn_readfirstlane(p.hp);
 
   // parameters of the layer after the current one travel through these registers
   uint4 wreg[kResPrefetch];
   LayerRegs L = unpack(p.layers[0]);
   fetch_blob(L.packed, L.blob_units, tid, wreg);
   {
-    // stage the image into LDS at the LDS pixel stride
-    const int cpp = p.in_cs >> 3, lpp = p.in_ps >> 3;
+    // stage the image into the interior of its LDS tensor, zero its halo
+    const int cpp = p.in_cs >> 3;
     const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(p.x) +
-                                                      (size_t)n * p.in_pixels * p.in_cs);
-    uint4* dst = reinterpret_cast<uint4*>(act + p.in_off * 16);
-    const int total = p.in_pixels * cpp;
+                                                      (size_t)n * p.in_H * p.in_W * p.in_cs);
+    const int org = p.in_org * 16, ps2 = p.in_ps * 2;
+    const int total = p.in_H * p.in_W * cpp;
     for (int i = tid; i < total; i += kResThreads) {
       const int pix = i / cpp, ch = i - pix * cpp;
-      dst[pix * lpp + ch] = src[i];
+      const int row = pix / p.in_W, col = pix - row * p.in_W;
+      *reinterpret_cast<uint4*>(act + org + (row * p.in_Wh + col) * ps2 + ch * 16) = src[i];
     }
+    if (hp > 0 && p.in_H * p.in_W > 1) zero_halo(act, org, p.in_H, p.in_W, p.in_Wh, ps2, cpp, hp, tid);
   }
   commit_blob(L.w_off, L.blob_units, tid, act, wreg);
 
@@ -293,20 +317,16 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(const ResParams p
       fetch_blob(Ln.packed, Ln.blob_units, tid, wreg);
     }
 
-    int2* tab = tables + (l & 1) * kResTableEntries;
+    int* tab = tables + (l & 1) * kResTableEntries;
     if (!(L.flags & kResMean)) {
-      const int W = L.W, ps = L.ps_in, cpt = L.cpt, S = L.S;
+      const int Wh = L.Wh_in, ps = L.ps_in, cpt = L.cpt, S = L.S;
       const int nentries = L.nsteps * 4, nchunk = L.nchunk;
       for (int j = tid; j < nentries; j += kResThreads) {
-        int2 e;
+        int e = 0;   // padding chunks (zero weights) re-read the first chunk: finite data
         if (j < nchunk) {
           const int tap = j / cpt, c8 = j - tap * cpt;
           const int r = tap / S, s = tap - r * S;
-          e.x = ((r * W + s) * ps + c8 * 8) * 2;   // byte offset
-          e.y = (r << 8) | s;
-        } else {
-          e.x = 0;
-          e.y = -1;
+          e = ((r * Wh + s) * ps + c8 * 8) * 2;   // byte offset from the window's first pixel
         }
         tab[j] = e;
       }
@@ -314,17 +334,21 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(const ResParams p
     __syncthreads();   // previous layer's output, this layer's parameters and table are visible
 
     if (L.flags & kResMean) {
-      // global mean over H*W, sequential fp32 sum per channel
-      const int hw = L.H * L.W, ps = L.ps_in;
-      const uint16_t* in = reinterpret_cast<const uint16_t*>(act + L.in_off * 16);
+      // global mean over the P x Q interior, sequential fp32 sum per channel
+      const int Pm = L.P, Qm = L.Q, ps = L.ps_in, Wh = L.Wh_in;
+      const uint16_t* in = reinterpret_cast<const uint16_t*>(act + L.in_org * 16);
       for (int c = tid; c < L.cs_out; c += kResThreads) {
         float acc = 0.f;
-        for (int i = 0; i < hw; ++i) acc += to_float<BF>(in[i * ps + c]);
-        const uint16_t o = from_float<BF>(acc / (float)hw);
+        for (int i = 0; i < Pm; ++i)
+          for (int j = 0; j < Qm; ++j) acc += to_float<BF>(in[(i * Wh + j) * ps + c]);
+        const uint16_t o = from_float<BF>(acc / (float)(Pm * Qm));
         if (L.flags & kResLast) reinterpret_cast<uint16_t*>(p.y)[(size_t)n * p.y_cs + c] = o;
-        else reinterpret_cast<uint16_t*>(act + L.out_off * 16)[c] = o;
+        else reinterpret_cast<uint16_t*>(act + L.out_org * 16)[c] = o;
       }
     } else {
+      if (L.out_halo > 0 && !(L.flags & kResLast))
+        zero_halo(act, L.out_org * 16, L.P, L.Q, L.Wh_out, L.ps_out * 2, L.cs_out >> 3, L.out_halo,
+                  tid);
       switch (L.MT * 8 + L.NT) {
         case 1 * 8 + 1: conv_layer<BF, 1, 1>(L, p, act, tab, n, lane, wave); break;
         case 1 * 8 + 2: conv_layer<BF, 1, 2>(L, p, act, tab, n, lane, wave); break;
