@@ -32,7 +32,15 @@ __device__ __forceinline__ uint16_t from_float(float f) {
 // Two floats rounded to nearest even and packed, a in the low half.
 template <bool BF>
 __device__ __forceinline__ uint32_t pack2(float a, float b) {
-  return (uint32_t)from_float<BF>(a) | ((uint32_t)from_float<BF>(b) << 16);
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  const f32x2 v = {a, b};
+  if constexpr (BF) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+  } else {
+    typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+  }
 }
 
 template <bool BF>

@@ -151,8 +151,8 @@ __global__ __launch_bounds__(256) void conv16_kernel(const Conv16Params p) {
         for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i], 0.f);
       }
       uint2 o;
-      o.x = (uint32_t)from_float<BF>(v[0]) | ((uint32_t)from_float<BF>(v[1]) << 16);
-      o.y = (uint32_t)from_float<BF>(v[2]) | ((uint32_t)from_float<BF>(v[3]) << 16);
+      o.x = pack2<BF>(v[0], v[1]);
+      o.y = pack2<BF>(v[2], v[3]);
       *reinterpret_cast<uint2*>(yp + k0) = o;
     }
   }
