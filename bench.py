@@ -21,9 +21,10 @@ PEAK_FP32 = 157.3e12       # fp32 vector, FLOP/s
 PEAK_HBM = 8.0e12          # B/s
 
 
-def cpu_baseline(model, batch, budget_s=15.0):
+def cpu_baseline(model, batch, budget_s=12.0):
     """The CPU oracle (unfused, zero-masked, double precision) timed on the host
-    cores over a bounded number of images of the same workload."""
+    cores over a bounded sample of the same workload: as many images of the
+    batch as fit the time budget, and whole passes over them until it is spent."""
     import synth
     from oracle import reference as orc
     masks = orc.select_masks(model)
@@ -35,11 +36,15 @@ def cpu_baseline(model, batch, budget_s=15.0):
     t1 = time.perf_counter() - t0
     n = int(max(1, min(batch, budget_s / max(t1, 1e-6))))
     x = synth.make_input(seed, n, model["in_shape"])
-    t0 = time.perf_counter()
-    orc.forward(model, x, masks=masks)
-    dt = time.perf_counter() - t0
-    return {"value": n / dt, "unit": "images/s", "cores": orc.num_threads(), "kind": "oracle",
-            "sample": f"{n} of {batch} images of the workload, one pass, {dt:.1f} s"}
+    passes, spent = 0, 0.0
+    while spent < budget_s and passes < 1000:
+        t0 = time.perf_counter()
+        orc.forward(model, x, masks=masks)
+        spent += time.perf_counter() - t0
+        passes += 1
+    return {"value": n * passes / spent, "unit": "images/s", "cores": orc.num_threads(),
+            "kind": "oracle",
+            "sample": f"{n} of {batch} images of the workload, {passes} passes, {spent:.1f} s"}
 
 
 def main():
