@@ -58,6 +58,9 @@ def main():
     ap.add_argument("--schedule", choices=["auto", "per-layer"], default="auto")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-op", action="store_true", help="print a per-operator table to stderr")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="also run a plain device-to-device copy of MIB mebibytes (a kernel of "
+                         "known traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE by)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: images are independent, so N GPUs would each run "
@@ -110,6 +113,13 @@ def main():
         for _ in range(reps):
             op_ms += fm.fupr_forward_timed(xd, out, ws, sp)
         op_ms /= reps
+
+    if args.copy_calibration:
+        src = torch.empty(args.copy_calibration << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     ms_per_step = elapsed / args.steps * 1e3
     n_launch = fm.num_launches

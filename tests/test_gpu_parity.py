@@ -354,6 +354,43 @@ def test_imagenet_models_use_per_layer_schedule(fx):
     assert m.num_launches == m.num_ops     # has a max-pool
 
 
+@pytest.mark.parametrize("idx", range(5))
+def test_baseline_config_full_batch_sampled(fx, idx):
+    """The workload at its full batch size, launched the way bench.py launches it
+    (HIP-graph replay on a side stream); the oracle computes a sample of the
+    images (first, second, middle, last) one by one."""
+    B, network, torch = fx
+    model, batch = synth.make_config(idx)
+    dtype = model["dtype"]
+    seed = synth.BASE_SEED + idx
+    plan = network.optimise(model)
+    m, _ = network.build(plan)
+    x = synth.make_input(seed, batch, model["in_shape"])
+    xd = B.DeviceTensor.from_nchw(x, B.DTYPES[dtype])
+    s = torch.cuda.Stream()
+    sp = B.C.c_void_p(s.cuda_stream)
+    with torch.cuda.stream(s):
+        out, ws = m.alloc(batch)
+        out.data.fill_(float("nan"))
+        s.synchronize()
+        g = m.fupr_graph_create(xd, out, ws, sp)
+        m.fupr_graph_launch(g, sp)
+        s.synchronize()
+    y = out.to_nchw()
+    if model["head"] is not None:
+        y = y[:, :, 0, 0]
+    assert np.isfinite(y).all()
+    masks = orc.select_masks(model)
+    sample = sorted({0, min(1, batch - 1), batch // 2, batch - 1})
+    print(f"config {idx}: batch {batch}, oracle on images {sample}", flush=True)
+    worst = 0.0
+    for i in sample:
+        ref = orc.forward(model, round_to(x[i:i + 1], dtype, torch), masks=masks)
+        worst = max(worst, rel_err(y[i:i + 1], ref))
+    print(f"config {idx}: worst sampled rel err {worst:.3e}", flush=True)
+    assert worst <= TOL[dtype]
+
+
 def test_forward_is_deterministic_and_graph_replays(fx):
     B, network, torch = fx
     model = synth.make_cifar_resnet(21, "bf16", 3, 400)
