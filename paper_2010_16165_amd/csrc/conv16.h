@@ -1,0 +1,28 @@
+// Internal: arguments of the 16-bit implicit-GEMM convolution kernels.
+#pragma once
+#include <cstdint>
+
+#include "fupr.h"
+
+namespace fupr {
+
+struct Conv16Params {
+  const uint16_t* x;
+  const uint16_t* w;     // [nchunk_pad][Kp][8]
+  const float* bias;     // [Kp]
+  const uint16_t* res;
+  uint16_t* y;
+  int H, W, xcs;
+  int P, Q, PQ, M, ycs;
+  int S, stride, pad;
+  int Kp, FT, cpt, nchunk, nsteps;
+  int rH, rW, rcs, rss, roff;
+  int relu;
+  uint32_t x_bytes, w_bytes;   // extents of x and w, for range-checked buffer loads
+};
+
+// conv_tiled.hip: LDS-staged filters, register-blocked tiles.  M = N*P*Q.
+fupr_status launch_conv16_tiled(const Conv16Params& p, bool bf16, void* stream);
+const char* conv16_tiled_name(int FT, int nsteps, int64_t M);
+
+}  // namespace fupr

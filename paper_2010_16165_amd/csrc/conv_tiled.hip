@@ -1,0 +1,355 @@
+// 16-bit implicit-GEMM convolution with LDS-staged filters and register-blocked
+// tiles: the per-layer kernel for the convolution operator k x c x r x s
+// (Sec. III; Sec. IV-B-1 of the paper) at the channel counts filter removal
+// leaves (Alg. 1).
+//
+// GEMM view as in conv16_kernel: rows = filters (MFMA operand A), columns =
+// output pixels (operand B), reduction over (r, s, c) in chunks of 8 channels,
+// 4 chunks per MFMA 16x16x32 step; the chunk order, and therefore the order of
+// every fp32 accumulation, is the same in all conv kernels of this library.
+//
+// A workgroup of 4 waves (WM x WN) computes WM*MT*16 pixels x WN*NT*16 filters.
+//   - Filters: KS steps at a time are copied global -> registers -> LDS, double
+//     buffered, one barrier per KS steps; the copy of stage s+1 is in flight
+//     while stage s is multiplied.  Every wave reads its NT fragments per step
+//     from LDS.
+//   - Pixels: each lane loads its own 16 bytes (8 channels of one tap of one
+//     pixel) straight from global memory KS steps ahead of use; a tap outside
+//     the image contributes zeros.  The 3x3 re-reads hit L1/L2.
+//   - Workgroups are numbered so that each XCD (its own L2) works on a
+//     contiguous range of pixel blocks and all filter groups of those blocks.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstdlib>
+#include <cstring>
+
+#include "conv16.h"
+#include "device_utils.h"
+#include "layout.h"
+
+namespace fupr {
+namespace {
+
+template <bool BF, int MT, int NT, int WM, int WN, int KS>
+__global__ __launch_bounds__(256) void conv16_tiled_kernel(const Conv16Params p, int fgroups,
+                                                           int units, int per_xcd) {
+  constexpr int BNF = WN * NT * 16;        // filters per workgroup
+  constexpr int BMPX = WM * MT * 16;       // pixels per workgroup
+  constexpr int STAGE = KS * 4 * BNF;      // uint4 per filter stage
+  constexpr int CP = (STAGE + 255) / 256;  // uint4 per thread per stage
+
+  extern __shared__ uint4 smem[];
+  uint4* wlds = smem;                                         // [2][STAGE]
+  int2* tap_table = reinterpret_cast<int2*>(smem + 2 * STAGE);  // [nsteps * 4]
+
+  // XCD-aware numbering: hardware deals consecutive workgroups round-robin to 8 XCDs
+  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+  const int unit = xcd * per_xcd + local;
+  if (local >= per_xcd || unit >= units) return;
+  const int pb = unit / fgroups, fgi = unit - pb * fgroups;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 15, g = lane >> 4;
+  const int wm = wave % WM, wn = wave / WM;
+  const int f0 = fgi * BNF;                // first filter of the workgroup
+  const int nchunk_pad = p.nsteps * 4;
+  // Buffer descriptors: a load whose offset lies outside the tensor returns
+  // zeros, so neither the pixel loads nor the filter loads need a branch (a load
+  // under a branch would force every wait to drain all loads in flight).
+  const __amdgpu_buffer_rsrc_t xrsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.x), 0, p.x_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t wrsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.w), 0, p.w_bytes, 0x00020000);
+  constexpr uint32_t kOutside = 0xfffffff0u;
+
+  uint4 wreg[CP];
+  auto stage_fetch = [&](int stage) {
+#pragma unroll
+    for (int k = 0; k < CP; ++k) {
+      const int i = tid + k * 256;
+      const int cl = i / BNF, f = i - cl * BNF;
+      const int chunk = stage * (KS * 4) + cl, gf = f0 + f;
+      const bool ok = i < STAGE && gf < p.Kp;   // chunks past the end are outside the buffer
+      const uint32_t off = ok ? (uint32_t)(chunk * p.Kp + gf) * 16u : kOutside;
+      wreg[k] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, off, 0, 0));
+    }
+  };
+  auto stage_commit = [&](int buf) {
+#pragma unroll
+    for (int k = 0; k < CP; ++k) {
+      const int i = tid + k * 256;
+      if (i < STAGE) wlds[buf * STAGE + i] = wreg[k];
+    }
+  };
+
+  stage_fetch(0);
+  for (int j = tid; j < nchunk_pad; j += 256) {
+    int2 e;
+    if (j < p.nchunk) {
+      const int tap = j / p.cpt, c8 = j - tap * p.cpt;
+      const int r = tap / p.S, s = tap - r * p.S;
+      e.x = ((r * p.W + s) * p.xcs + c8 * 8) * 2;   // bytes
+      e.y = (r << 8) | s;
+    } else {
+      e.x = 0;
+      e.y = -1;
+    }
+    tap_table[j] = e;
+  }
+
+  int ih0[MT], iw0[MT];
+  uint32_t xoff[MT];   // byte offset of the window's first pixel, modulo 2^32
+  bool pv[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    const int m = pb * BMPX + (wm * MT + mt) * 16 + li;
+    pv[mt] = m < p.M;
+    const int mm = pv[mt] ? m : 0;
+    const int n = mm / p.PQ, rem = mm - n * p.PQ;
+    const int pp = rem / p.Q, qq = rem - pp * p.Q;
+    ih0[mt] = pp * p.stride - p.pad;
+    iw0[mt] = qq * p.stride - p.pad;
+    xoff[mt] = (uint32_t)((n * p.H + ih0[mt]) * p.W + iw0[mt]) * (uint32_t)(p.xcs * 2);
+  }
+
+  f32x4 acc[MT][NT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  stage_commit(0);
+  __syncthreads();   // tap table and filter stage 0 are visible
+
+  // Pixel operands of one stage, in registers: bc is multiplied while bn is in flight.
+  uint4 bc[KS][MT], bn[KS][MT];
+  auto fetch_pixels = [&](int stage) {
+#pragma unroll
+    for (int d = 0; d < KS; ++d) {
+      const int step = min(stage * KS + d, p.nsteps - 1);
+      const int2 e = tap_table[step * 4 + g];
+      const int r = e.y >> 8, s = e.y & 255;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const bool ok = pv[mt] && e.y >= 0 && (unsigned)(ih0[mt] + r) < (unsigned)p.H &&
+                        (unsigned)(iw0[mt] + s) < (unsigned)p.W;
+        const uint32_t off = ok ? xoff[mt] + (uint32_t)e.x : kOutside;
+        bn[d][mt] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, off, 0, 0));
+      }
+    }
+  };
+  auto rotate_pixels = [&]() {
+#pragma unroll
+    for (int d = 0; d < KS; ++d)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) bc[d][mt] = bn[d][mt];
+  };
+  fetch_pixels(0);
+  rotate_pixels();
+
+  // All global loads of stage st+1 are issued before stage st is multiplied and
+  // are first touched after it, so the only wait for memory sits at the stage end.
+  const int nstages = (p.nsteps + KS - 1) / KS;
+  for (int st = 0; st < nstages; ++st) {
+    const bool more = st + 1 < nstages;
+    if (more) {
+      stage_fetch(st + 1);
+      fetch_pixels(st + 1);
+    }
+    const uint4* wl = wlds + (st & 1) * STAGE + g * BNF + wn * NT * 16 + li;
+#pragma unroll
+    for (int d = 0; d < KS; ++d) {
+      if (st * KS + d < p.nsteps) {
+        uint4 a[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) a[t] = wl[d * 4 * BNF + t * 16];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int t = 0; t < NT; ++t) acc[mt][t] = mfma_16x16x32<BF>(a[t], bc[d][mt], acc[mt][t]);
+      }
+    }
+    if (more) {
+      stage_commit((st + 1) & 1);
+      rotate_pixels();
+    }
+    __syncthreads();
+  }
+
+  // Epilogue: bias, shortcut, ReLU, one rounding, 8-byte NHWC store.
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    const int m = pb * BMPX + (wm * MT + mt) * 16 + li;
+    if (m >= p.M) continue;
+    const uint16_t* rp = nullptr;
+    if (p.res) {
+      const int n = m / p.PQ, rem = m - n * p.PQ;
+      const int pp = rem / p.Q, qq = rem - pp * p.Q;
+      rp = p.res + (((int64_t)n * p.rH + pp * p.rss) * p.rW + qq * p.rss) * p.rcs;
+    }
+    uint16_t* yp = p.y + (int64_t)m * p.ycs;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const int ftile = fgi * (WN * NT) + wn * NT + t;
+      const int k0 = ftile * 16 + g * 4;
+      if (ftile >= p.FT || k0 >= p.ycs) continue;
+      const float4 b4 = *reinterpret_cast<const float4*>(p.bias + k0);
+      float v[4] = {acc[mt][t][0] + b4.x, acc[mt][t][1] + b4.y, acc[mt][t][2] + b4.z,
+                    acc[mt][t][3] + b4.w};
+      if (rp) {
+        const int kk = k0 - p.roff;
+        if (kk >= 0 && kk < p.rcs) {
+          const uint2 rv = *reinterpret_cast<const uint2*>(rp + kk);
+          v[0] += to_float<BF>((uint16_t)(rv.x & 0xffffu));
+          v[1] += to_float<BF>((uint16_t)(rv.x >> 16));
+          v[2] += to_float<BF>((uint16_t)(rv.y & 0xffffu));
+          v[3] += to_float<BF>((uint16_t)(rv.y >> 16));
+        }
+      }
+      if (p.relu) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i], 0.f);
+      }
+      uint2 o;
+      o.x = pack2<BF>(v[0], v[1]);
+      o.y = pack2<BF>(v[2], v[3]);
+      *reinterpret_cast<uint2*>(yp + k0) = o;
+    }
+  }
+}
+
+// ---- tile table -----------------------------------------------------------------
+
+struct TileCfg {
+  int MT, NT, WM, WN;
+  const char* name;
+};
+
+// Every instantiated tile.  WM x WN = 4 waves.
+constexpr TileCfg kTiles[] = {
+    {1, 1, 4, 1, "conv16t_64x16"},   {2, 1, 4, 1, "conv16t_128x16"},  {4, 1, 4, 1, "conv16t_256x16"},
+    {1, 2, 4, 1, "conv16t_64x32"},   {2, 2, 4, 1, "conv16t_128x32"},  {4, 2, 4, 1, "conv16t_256x32"},
+    {1, 3, 4, 1, "conv16t_64x48"},   {2, 3, 4, 1, "conv16t_128x48"},  {4, 3, 4, 1, "conv16t_256x48"},
+    {1, 4, 4, 1, "conv16t_64x64"},   {2, 4, 4, 1, "conv16t_128x64"},  {4, 4, 4, 1, "conv16t_256x64"},
+    {1, 6, 4, 1, "conv16t_64x96"},   {2, 6, 4, 1, "conv16t_128x96"},  {4, 6, 4, 1, "conv16t_256x96"},
+    {1, 8, 4, 1, "conv16t_64x128"},  {2, 8, 4, 1, "conv16t_128x128"}, {4, 8, 4, 1, "conv16t_256x128"},
+    {1, 3, 2, 2, "conv16t_32x96"},   {2, 3, 2, 2, "conv16t_64x96w"},
+    {1, 4, 2, 2, "conv16t_32x128"},  {2, 4, 2, 2, "conv16t_64x128w"},
+    {4, 4, 2, 2, "conv16t_128x128w"},
+};
+constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
+
+constexpr int stage_steps(int MT, int NT) { return MT * NT <= 16 ? 4 : 2; }
+
+// Estimated time of a layer under a tile, in clocks of one compute unit
+// (relative numbers only): the workgroups run in waves over 256 CUs; within a
+// workgroup a step costs the slowest of MFMA issue (16 clocks per 16x16x32 on
+// each of the 4 SIMDs), LDS traffic (128 B/clock) and vector-memory traffic
+// (64 B/clock), plus a fixed cost per workgroup.
+double tile_cost(const TileCfg& t, int FT, int nsteps, int64_t M) {
+  const int bnf = t.WN * t.NT, bm = t.WM * t.MT * 16;
+  const int64_t mblocks = (M + bm - 1) / bm;
+  const int fgroups = (FT + bnf - 1) / bnf;
+  const double blocks = (double)mblocks * fgroups;
+  const double mfma = t.MT * t.NT * 16.0;                              // per wave, per step
+  const double lds = (4.0 * t.NT * 1024 + bnf * 1024.0) / 128.0;       // fragment reads + stage write
+  const double vmem = (4.0 * t.MT * 1024 + bnf * 1024.0) / 64.0;       // pixel loads + stage fetch
+  const double step = std::max(mfma, std::max(lds, vmem));
+  const double per_block = nsteps * step + 1500.0 + 40.0 * t.MT * t.NT;  // prologue + epilogue
+  const int resident = t.MT * t.NT >= 24 ? 1 : 2;                      // workgroups per CU
+  const double rounds = std::ceil(blocks / (256.0 * resident));
+  return rounds * per_block * (resident == 2 ? 1.6 : 1.0);
+}
+
+// FUPR_CONV_TILE=<tile name> in the environment forces one tile for every layer
+// (read at each launch; a tuning aid for sweeps, not needed in normal use).
+int forced_tile() {
+  const char* e = getenv("FUPR_CONV_TILE");
+  if (!e) return -1;
+  for (int i = 0; i < kNumTiles; ++i)
+    if (strcmp(e, kTiles[i].name) == 0) return i;
+  return -1;
+}
+
+int choose_tile(int FT, int nsteps, int64_t M) {
+  const int f = forced_tile();
+  if (f >= 0) return f;
+  int best = 0;
+  double best_cost = 1e300;
+  for (int i = 0; i < kNumTiles; ++i) {
+    const double c = tile_cost(kTiles[i], FT, nsteps, M);
+    if (c < best_cost) {
+      best_cost = c;
+      best = i;
+    }
+  }
+  return best;
+}
+
+template <bool BF, int MT, int NT, int WM, int WN>
+fupr_status launch_tile(const Conv16Params& p, hipStream_t st) {
+  constexpr int KS = stage_steps(MT, NT);
+  constexpr int BNF = WN * NT * 16, BMPX = WM * MT * 16;
+  const int64_t mblocks = ((int64_t)p.M + BMPX - 1) / BMPX;
+  const int fgroups = (p.Kp + BNF - 1) / BNF;
+  const int64_t units = mblocks * fgroups;
+  if (units >= (int64_t(1) << 30)) return FUPR_ERR_LIMIT;
+  const int per_xcd = (int)((units + 7) / 8);
+  const size_t shmem = (size_t)2 * KS * 4 * BNF * 16 + (size_t)p.nsteps * 4 * sizeof(int2);
+  auto kernel = conv16_tiled_kernel<BF, MT, NT, WM, WN, KS>;
+  if (shmem > 64 * 1024) {
+    static const hipError_t attr = hipFuncSetAttribute(
+        reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (attr != hipSuccess) return FUPR_ERR_LAUNCH;
+  }
+  hipLaunchKernelGGL(kernel, dim3((unsigned)(per_xcd * 8)), dim3(256), shmem, st, p, fgroups,
+                     (int)units, per_xcd);
+  return launch_status("conv16_tiled_kernel");
+}
+
+template <bool BF>
+fupr_status dispatch(const Conv16Params& p, int tile, hipStream_t st) {
+  switch (tile) {
+    case 0: return launch_tile<BF, 1, 1, 4, 1>(p, st);
+    case 1: return launch_tile<BF, 2, 1, 4, 1>(p, st);
+    case 2: return launch_tile<BF, 4, 1, 4, 1>(p, st);
+    case 3: return launch_tile<BF, 1, 2, 4, 1>(p, st);
+    case 4: return launch_tile<BF, 2, 2, 4, 1>(p, st);
+    case 5: return launch_tile<BF, 4, 2, 4, 1>(p, st);
+    case 6: return launch_tile<BF, 1, 3, 4, 1>(p, st);
+    case 7: return launch_tile<BF, 2, 3, 4, 1>(p, st);
+    case 8: return launch_tile<BF, 4, 3, 4, 1>(p, st);
+    case 9: return launch_tile<BF, 1, 4, 4, 1>(p, st);
+    case 10: return launch_tile<BF, 2, 4, 4, 1>(p, st);
+    case 11: return launch_tile<BF, 4, 4, 4, 1>(p, st);
+    case 12: return launch_tile<BF, 1, 6, 4, 1>(p, st);
+    case 13: return launch_tile<BF, 2, 6, 4, 1>(p, st);
+    case 14: return launch_tile<BF, 4, 6, 4, 1>(p, st);
+    case 15: return launch_tile<BF, 1, 8, 4, 1>(p, st);
+    case 16: return launch_tile<BF, 2, 8, 4, 1>(p, st);
+    case 17: return launch_tile<BF, 4, 8, 4, 1>(p, st);
+    case 18: return launch_tile<BF, 1, 3, 2, 2>(p, st);
+    case 19: return launch_tile<BF, 2, 3, 2, 2>(p, st);
+    case 20: return launch_tile<BF, 1, 4, 2, 2>(p, st);
+    case 21: return launch_tile<BF, 2, 4, 2, 2>(p, st);
+    default: return launch_tile<BF, 4, 4, 2, 2>(p, st);
+  }
+}
+
+}  // namespace
+
+const char* conv16_tiled_name(int FT, int nsteps, int64_t M) {
+  return kTiles[choose_tile(FT, nsteps, M)].name;
+}
+
+fupr_status launch_conv16_tiled(const Conv16Params& p, bool bf16, void* stream) {
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const int tile = choose_tile(p.FT, p.nsteps, p.M);
+  return bf16 ? dispatch<true>(p, tile, st) : dispatch<false>(p, tile, st);
+}
+
+}  // namespace fupr

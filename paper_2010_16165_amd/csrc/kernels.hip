@@ -10,6 +10,7 @@
 #include "fupr.h"
 #include "layout.h"
 #include "device_utils.h"
+#include "conv16.h"
 
 namespace fupr {
 namespace {
@@ -22,20 +23,6 @@ namespace {
 // every lane ends up with 4 consecutive channels of one pixel, i.e. one 8-byte
 // NHWC store.  A workgroup is 4 waves; each wave owns MT pixel tiles and NT
 // filter tiles.
-
-struct Conv16Params {
-  const uint16_t* x;
-  const uint16_t* w;     // [nchunk_pad][Kp][8]
-  const float* bias;     // [Kp]
-  const uint16_t* res;
-  uint16_t* y;
-  int H, W, xcs;
-  int P, Q, PQ, M, ycs;
-  int S, stride, pad;
-  int Kp, FT, cpt, nchunk, nsteps;
-  int rH, rW, rcs, rss, roff;
-  int relu;
-};
 
 template <bool BF, int MT, int NT>
 __global__ __launch_bounds__(256) void conv16_kernel(const Conv16Params p) {
@@ -402,6 +389,7 @@ fupr_status launch_status(const char* what) {
 const char* conv_kernel_name(const fupr_conv_shape& s, fupr_dtype dt, int64_t M) {
   if (dt == FUPR_F32) return "conv32_direct";
   const PackedLayout L = packed_layout(s, dt);
+  if (!getenv("FUPR_CONV_V1")) return conv16_tiled_name(L.Kp / 16, L.nchunk_pad / 4, M);
   const Tile t = choose_tile(L.Kp / 16, M);
   static const char* names[3][4] = {
       {"conv16_mt1_nt1", "conv16_mt1_nt2", "conv16_mt1_nt3", "conv16_mt1_nt4"},
@@ -445,8 +433,13 @@ fupr_status launch_conv(const ConvArgs& a, void* stream) {
   p.Kp = L.Kp; p.FT = L.Kp / 16; p.cpt = L.Cp / 8; p.nchunk = L.nchunk; p.nsteps = L.nchunk_pad / 4;
   p.rH = a.rH; p.rW = a.rW; p.rcs = a.rcs; p.rss = a.rss; p.roff = a.roff;
   p.relu = a.relu;
-  const Tile t = choose_tile(p.FT, M);
-  return a.dt == FUPR_BF16 ? launch16<true>(p, t, st) : launch16<false>(p, t, st);
+  p.x_bytes = (uint32_t)((int64_t)a.N * a.H * a.W * a.xcs * 2);
+  p.w_bytes = (uint32_t)((size_t)L.nchunk_pad * L.Kp * 16);
+  if (getenv("FUPR_CONV_V1")) {
+    const Tile t = choose_tile(p.FT, M);
+    return a.dt == FUPR_BF16 ? launch16<true>(p, t, st) : launch16<false>(p, t, st);
+  }
+  return launch_conv16_tiled(p, a.dt == FUPR_BF16, stream);
 }
 
 }  // namespace fupr
