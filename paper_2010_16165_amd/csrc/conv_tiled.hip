@@ -3,7 +3,7 @@
 // (Sec. III; Sec. IV-B-1 of the paper) at the channel counts filter removal
 // leaves (Alg. 1).
 //
-// GEMM view as in conv16_kernel: rows = filters (MFMA operand A), columns =
+// GEMM view: rows = filters (MFMA operand A), columns =
 // output pixels (operand B), reduction over (r, s, c) in chunks of 8 channels,
 // 4 chunks per MFMA 16x16x32 step; the chunk order, and therefore the order of
 // every fp32 accumulation, is the same in all conv kernels of this library.
@@ -225,45 +225,19 @@ __global__ __launch_bounds__(256) void conv16_tiled_kernel(const Conv16Params p,
 // ---- tile table -----------------------------------------------------------------
 
 struct TileCfg {
-  int MT, NT, WM, WN;
+  int MT, NT;
   const char* name;
 };
 
-// Every instantiated tile.  WM x WN = 4 waves.
+// Every instantiated tile: 4 waves side by side along the pixels, MT pixel
+// tiles x NT filter tiles of 16 each per wave.
 constexpr TileCfg kTiles[] = {
-    {1, 1, 4, 1, "conv16t_64x16"},   {2, 1, 4, 1, "conv16t_128x16"},  {4, 1, 4, 1, "conv16t_256x16"},
-    {1, 2, 4, 1, "conv16t_64x32"},   {2, 2, 4, 1, "conv16t_128x32"},  {4, 2, 4, 1, "conv16t_256x32"},
-    {1, 3, 4, 1, "conv16t_64x48"},   {2, 3, 4, 1, "conv16t_128x48"},  {4, 3, 4, 1, "conv16t_256x48"},
-    {1, 4, 4, 1, "conv16t_64x64"},   {2, 4, 4, 1, "conv16t_128x64"},  {4, 4, 4, 1, "conv16t_256x64"},
-    {1, 6, 4, 1, "conv16t_64x96"},   {2, 6, 4, 1, "conv16t_128x96"},  {4, 6, 4, 1, "conv16t_256x96"},
-    {1, 8, 4, 1, "conv16t_64x128"},  {2, 8, 4, 1, "conv16t_128x128"}, {4, 8, 4, 1, "conv16t_256x128"},
-    {1, 3, 2, 2, "conv16t_32x96"},   {2, 3, 2, 2, "conv16t_64x96w"},
-    {1, 4, 2, 2, "conv16t_32x128"},  {2, 4, 2, 2, "conv16t_64x128w"},
-    {4, 4, 2, 2, "conv16t_128x128w"},
+    {1, 1, "conv16t_64x16"}, {2, 1, "conv16t_128x16"}, {1, 2, "conv16t_64x32"}, {2, 2, "conv16t_128x32"},
+    {1, 3, "conv16t_64x48"}, {2, 3, "conv16t_128x48"}, {1, 4, "conv16t_64x64"}, {2, 4, "conv16t_128x64"},
+    {1, 6, "conv16t_64x96"}, {2, 6, "conv16t_128x96"}, {1, 8, "conv16t_64x128"}, {2, 8, "conv16t_128x128"},
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
-
-constexpr int stage_steps(int MT, int NT) { return MT * NT <= 16 ? 4 : 2; }
-
-// Estimated time of a layer under a tile, in clocks of one compute unit
-// (relative numbers only): the workgroups run in waves over 256 CUs; within a
-// workgroup a step costs the slowest of MFMA issue (16 clocks per 16x16x32 on
-// each of the 4 SIMDs), LDS traffic (128 B/clock) and vector-memory traffic
-// (64 B/clock), plus a fixed cost per workgroup.
-double tile_cost(const TileCfg& t, int FT, int nsteps, int64_t M) {
-  const int bnf = t.WN * t.NT, bm = t.WM * t.MT * 16;
-  const int64_t mblocks = (M + bm - 1) / bm;
-  const int fgroups = (FT + bnf - 1) / bnf;
-  const double blocks = (double)mblocks * fgroups;
-  const double mfma = t.MT * t.NT * 16.0;                              // per wave, per step
-  const double lds = (4.0 * t.NT * 1024 + bnf * 1024.0) / 128.0;       // fragment reads + stage write
-  const double vmem = (4.0 * t.MT * 1024 + bnf * 1024.0) / 64.0;       // pixel loads + stage fetch
-  const double step = std::max(mfma, std::max(lds, vmem));
-  const double per_block = nsteps * step + 1500.0 + 40.0 * t.MT * t.NT;  // prologue + epilogue
-  const int resident = t.MT * t.NT >= 24 ? 1 : 2;                      // workgroups per CU
-  const double rounds = std::ceil(blocks / (256.0 * resident));
-  return rounds * per_block * (resident == 2 ? 1.6 : 1.0);
-}
+constexpr int kStageSteps = 4;
 
 // FUPR_CONV_TILE=<tile name> in the environment forces one tile for every layer
 // (read at each launch; a tuning aid for sweeps, not needed in normal use).
@@ -275,24 +249,37 @@ int forced_tile() {
   return -1;
 }
 
+// Tile of a layer with FT filter tiles and M output pixels.  The rule is the
+// one that lost least against the per-layer best in a sweep of all tiles over
+// every layer shape of the ResNet-18 and ResNet-50 workloads (the layers are
+// bound by memory latency, not MFMA issue, so mid-size tiles with several
+// workgroups per compute unit win over the largest ones):
+//   filters per workgroup: 16 * nt, nt from {1, 2, 3, 4, 6} with the fewest
+//       padded filter tiles over all filter groups, the larger nt on a tie;
+//   pixels per workgroup: 128, or 64 when 128 would leave fewer than 128 workgroups.
 int choose_tile(int FT, int nsteps, int64_t M) {
+  (void)nsteps;
   const int f = forced_tile();
   if (f >= 0) return f;
-  int best = 0;
-  double best_cost = 1e300;
-  for (int i = 0; i < kNumTiles; ++i) {
-    const double c = tile_cost(kTiles[i], FT, nsteps, M);
-    if (c < best_cost) {
-      best_cost = c;
-      best = i;
+  static const int nts[] = {1, 2, 3, 4, 6};
+  int nt = 1, best_waste = 1 << 30;
+  for (int c : nts) {
+    const int groups = (FT + c - 1) / c, waste = groups * c - FT;
+    if (waste < best_waste || (waste == best_waste && c > nt)) {
+      best_waste = waste;
+      nt = c;
     }
   }
-  return best;
+  const int64_t groups = (FT + nt - 1) / nt;
+  const int mt = ((M + 127) / 128) * groups >= 128 ? 2 : 1;
+  for (int i = 0; i < kNumTiles; ++i)
+    if (kTiles[i].MT == mt && kTiles[i].NT == nt) return i;
+  return 0;
 }
 
-template <bool BF, int MT, int NT, int WM, int WN>
+template <bool BF, int MT, int NT>
 fupr_status launch_tile(const Conv16Params& p, hipStream_t st) {
-  constexpr int KS = stage_steps(MT, NT);
+  constexpr int KS = kStageSteps, WM = 4, WN = 1;
   constexpr int BNF = WN * NT * 16, BMPX = WM * MT * 16;
   const int64_t mblocks = ((int64_t)p.M + BMPX - 1) / BMPX;
   const int fgroups = (p.Kp + BNF - 1) / BNF;
@@ -314,29 +301,18 @@ fupr_status launch_tile(const Conv16Params& p, hipStream_t st) {
 template <bool BF>
 fupr_status dispatch(const Conv16Params& p, int tile, hipStream_t st) {
   switch (tile) {
-    case 0: return launch_tile<BF, 1, 1, 4, 1>(p, st);
-    case 1: return launch_tile<BF, 2, 1, 4, 1>(p, st);
-    case 2: return launch_tile<BF, 4, 1, 4, 1>(p, st);
-    case 3: return launch_tile<BF, 1, 2, 4, 1>(p, st);
-    case 4: return launch_tile<BF, 2, 2, 4, 1>(p, st);
-    case 5: return launch_tile<BF, 4, 2, 4, 1>(p, st);
-    case 6: return launch_tile<BF, 1, 3, 4, 1>(p, st);
-    case 7: return launch_tile<BF, 2, 3, 4, 1>(p, st);
-    case 8: return launch_tile<BF, 4, 3, 4, 1>(p, st);
-    case 9: return launch_tile<BF, 1, 4, 4, 1>(p, st);
-    case 10: return launch_tile<BF, 2, 4, 4, 1>(p, st);
-    case 11: return launch_tile<BF, 4, 4, 4, 1>(p, st);
-    case 12: return launch_tile<BF, 1, 6, 4, 1>(p, st);
-    case 13: return launch_tile<BF, 2, 6, 4, 1>(p, st);
-    case 14: return launch_tile<BF, 4, 6, 4, 1>(p, st);
-    case 15: return launch_tile<BF, 1, 8, 4, 1>(p, st);
-    case 16: return launch_tile<BF, 2, 8, 4, 1>(p, st);
-    case 17: return launch_tile<BF, 4, 8, 4, 1>(p, st);
-    case 18: return launch_tile<BF, 1, 3, 2, 2>(p, st);
-    case 19: return launch_tile<BF, 2, 3, 2, 2>(p, st);
-    case 20: return launch_tile<BF, 1, 4, 2, 2>(p, st);
-    case 21: return launch_tile<BF, 2, 4, 2, 2>(p, st);
-    default: return launch_tile<BF, 4, 4, 2, 2>(p, st);
+    case 0: return launch_tile<BF, 1, 1>(p, st);
+    case 1: return launch_tile<BF, 2, 1>(p, st);
+    case 2: return launch_tile<BF, 1, 2>(p, st);
+    case 3: return launch_tile<BF, 2, 2>(p, st);
+    case 4: return launch_tile<BF, 1, 3>(p, st);
+    case 5: return launch_tile<BF, 2, 3>(p, st);
+    case 6: return launch_tile<BF, 1, 4>(p, st);
+    case 7: return launch_tile<BF, 2, 4>(p, st);
+    case 8: return launch_tile<BF, 1, 6>(p, st);
+    case 9: return launch_tile<BF, 2, 6>(p, st);
+    case 10: return launch_tile<BF, 1, 8>(p, st);
+    default: return launch_tile<BF, 2, 8>(p, st);
   }
 }
 

@@ -15,136 +15,6 @@
 namespace fupr {
 namespace {
 
-// ---- implicit-GEMM convolution, 16-bit inputs, fp32 accumulation -----------
-//
-// GEMM view: rows = filters (MFMA operand A, 16 per tile), columns = output
-// pixels (operand B, 16 per tile), reduction = (r, s, c) in chunks of 8
-// channels; one MFMA 16x16x32 consumes 4 chunks.  With filters on the rows,
-// every lane ends up with 4 consecutive channels of one pixel, i.e. one 8-byte
-// NHWC store.  A workgroup is 4 waves; each wave owns MT pixel tiles and NT
-// filter tiles.
-
-template <bool BF, int MT, int NT>
-__global__ __launch_bounds__(256) void conv16_kernel(const Conv16Params p) {
-  extern __shared__ int2 tap_table[];  // per chunk: element offset, (r << 8 | s) or -1
-  for (int j = threadIdx.x; j < p.nsteps * 4; j += 256) {
-    int2 e;
-    if (j < p.nchunk) {
-      const int tap = j / p.cpt, c8 = j - tap * p.cpt;
-      const int r = tap / p.S, s = tap - r * p.S;
-      e.x = (r * p.W + s) * p.xcs + c8 * 8;
-      e.y = (r << 8) | s;
-    } else {
-      e.x = 0;
-      e.y = -1;
-    }
-    tap_table[j] = e;
-  }
-
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int li = lane & 15, g = lane >> 4;
-  const int ft0 = blockIdx.y * NT;
-
-  int ih0[MT], iw0[MT];
-  const uint16_t* xb[MT];
-  bool pv[MT];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    const int m = ((blockIdx.x * 4 + wave) * MT + mt) * 16 + li;
-    pv[mt] = m < p.M;
-    const int mm = pv[mt] ? m : 0;
-    const int n = mm / p.PQ, rem = mm - n * p.PQ;
-    const int pp = rem / p.Q, qq = rem - pp * p.Q;
-    ih0[mt] = pp * p.stride - p.pad;
-    iw0[mt] = qq * p.stride - p.pad;
-    xb[mt] = p.x + ((int64_t)n * p.H * p.W + (int64_t)ih0[mt] * p.W + iw0[mt]) * p.xcs;
-  }
-  const uint16_t* wb[NT];
-#pragma unroll
-  for (int t = 0; t < NT; ++t) {
-    const int tt = min(ft0 + t, p.FT - 1);
-    wb[t] = p.w + ((size_t)g * p.Kp + tt * 16 + li) * 8;
-  }
-
-  f32x4 acc[MT][NT];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-    for (int t = 0; t < NT; ++t) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  __syncthreads();
-
-  const size_t wstep = (size_t)4 * p.Kp * 8;
-  uint4 a_cur[NT], b_cur[MT], a_nxt[NT], b_nxt[MT];
-
-  auto load_step = [&](int step, uint4* a, uint4* b) {
-    const int2 e = tap_table[step * 4 + g];
-    const int r = e.y >> 8, s = e.y & 255;
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const bool ok = pv[mt] && e.y >= 0 && (unsigned)(ih0[mt] + r) < (unsigned)p.H &&
-                      (unsigned)(iw0[mt] + s) < (unsigned)p.W;
-      b[mt] = ok ? *reinterpret_cast<const uint4*>(xb[mt] + e.x) : uint4{0u, 0u, 0u, 0u};
-    }
-#pragma unroll
-    for (int t = 0; t < NT; ++t)
-      a[t] = *reinterpret_cast<const uint4*>(wb[t] + (size_t)step * wstep);
-  };
-
-  load_step(0, a_cur, b_cur);
-  for (int step = 0; step < p.nsteps; ++step) {
-    if (step + 1 < p.nsteps) load_step(step + 1, a_nxt, b_nxt);
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-      for (int t = 0; t < NT; ++t) acc[mt][t] = mfma_16x16x32<BF>(a_cur[t], b_cur[mt], acc[mt][t]);
-#pragma unroll
-    for (int t = 0; t < NT; ++t) a_cur[t] = a_nxt[t];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) b_cur[mt] = b_nxt[mt];
-  }
-
-  // Epilogue: bias, shortcut, ReLU, one rounding, 8-byte NHWC store.
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    const int m = ((blockIdx.x * 4 + wave) * MT + mt) * 16 + li;
-    if (m >= p.M) continue;
-    const uint16_t* rp = nullptr;
-    if (p.res) {
-      const int n = m / p.PQ, rem = m - n * p.PQ;
-      const int pp = rem / p.Q, qq = rem - pp * p.Q;
-      rp = p.res + (((int64_t)n * p.rH + pp * p.rss) * p.rW + qq * p.rss) * p.rcs;
-    }
-    uint16_t* yp = p.y + (int64_t)m * p.ycs;
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      const int k0 = (ft0 + t) * 16 + g * 4;
-      if (ft0 + t >= p.FT || k0 >= p.ycs) continue;
-      const float4 b4 = *reinterpret_cast<const float4*>(p.bias + k0);
-      float v[4] = {acc[mt][t][0] + b4.x, acc[mt][t][1] + b4.y, acc[mt][t][2] + b4.z,
-                    acc[mt][t][3] + b4.w};
-      if (rp) {
-        const int kk = k0 - p.roff;
-        if (kk >= 0 && kk < p.rcs) {
-          const uint2 rv = *reinterpret_cast<const uint2*>(rp + kk);
-          v[0] += to_float<BF>((uint16_t)(rv.x & 0xffffu));
-          v[1] += to_float<BF>((uint16_t)(rv.x >> 16));
-          v[2] += to_float<BF>((uint16_t)(rv.y & 0xffffu));
-          v[3] += to_float<BF>((uint16_t)(rv.y >> 16));
-        }
-      }
-      if (p.relu) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i], 0.f);
-      }
-      uint2 o;
-      o.x = pack2<BF>(v[0], v[1]);
-      o.y = pack2<BF>(v[2], v[3]);
-      *reinterpret_cast<uint2*>(yp + k0) = o;
-    }
-  }
-}
-
 // ---- fp32 direct convolution ------------------------------------------------
 // One thread: one output pixel x 4 consecutive filters, plain FMA.
 
@@ -333,50 +203,6 @@ __global__ __launch_bounds__(256) void avgpool_kernel(const PoolParams p) {
   }
 }
 
-// ---- tile selection -----------------------------------------------------------
-
-struct Tile {
-  int MT, NT;
-};
-
-// Filter tiles per wave: all of them when there are at most 4, otherwise the
-// group size that wastes the fewest tiles.  Pixel tiles per wave: as many as
-// keep at least ~2 workgroups per compute unit in flight.
-Tile choose_tile(int FT, int64_t M) {
-  Tile t;
-  if (FT <= 4) t.NT = FT;
-  else if (FT % 4 == 0) t.NT = 4;
-  else if (FT % 3 == 0) t.NT = 3;
-  else t.NT = 4;
-  const int64_t groups = (FT + t.NT - 1) / t.NT;
-  t.MT = 4;
-  while (t.MT > 1 && ((M + 64 * t.MT - 1) / (64 * t.MT)) * groups < 1024) t.MT >>= 1;
-  return t;
-}
-
-template <bool BF, int MT>
-fupr_status launch16_nt(const Conv16Params& p, int NT, dim3 grid, size_t shmem, hipStream_t st) {
-  switch (NT) {
-    case 1: hipLaunchKernelGGL((conv16_kernel<BF, MT, 1>), grid, dim3(256), shmem, st, p); break;
-    case 2: hipLaunchKernelGGL((conv16_kernel<BF, MT, 2>), grid, dim3(256), shmem, st, p); break;
-    case 3: hipLaunchKernelGGL((conv16_kernel<BF, MT, 3>), grid, dim3(256), shmem, st, p); break;
-    default: hipLaunchKernelGGL((conv16_kernel<BF, MT, 4>), grid, dim3(256), shmem, st, p); break;
-  }
-  return launch_status(__func__);
-}
-
-template <bool BF>
-fupr_status launch16(const Conv16Params& p, Tile t, hipStream_t st) {
-  const int64_t mblk = ((int64_t)p.M + 64 * t.MT - 1) / (64 * t.MT);
-  dim3 grid((unsigned)mblk, (unsigned)((p.FT + t.NT - 1) / t.NT));
-  const size_t shmem = (size_t)p.nsteps * 4 * sizeof(int2);
-  switch (t.MT) {
-    case 1: return launch16_nt<BF, 1>(p, t.NT, grid, shmem, st);
-    case 2: return launch16_nt<BF, 2>(p, t.NT, grid, shmem, st);
-    default: return launch16_nt<BF, 4>(p, t.NT, grid, shmem, st);
-  }
-}
-
 }  // namespace
 
 fupr_status launch_status(const char* what) {
@@ -389,13 +215,7 @@ fupr_status launch_status(const char* what) {
 const char* conv_kernel_name(const fupr_conv_shape& s, fupr_dtype dt, int64_t M) {
   if (dt == FUPR_F32) return "conv32_direct";
   const PackedLayout L = packed_layout(s, dt);
-  if (!getenv("FUPR_CONV_V1")) return conv16_tiled_name(L.Kp / 16, L.nchunk_pad / 4, M);
-  const Tile t = choose_tile(L.Kp / 16, M);
-  static const char* names[3][4] = {
-      {"conv16_mt1_nt1", "conv16_mt1_nt2", "conv16_mt1_nt3", "conv16_mt1_nt4"},
-      {"conv16_mt2_nt1", "conv16_mt2_nt2", "conv16_mt2_nt3", "conv16_mt2_nt4"},
-      {"conv16_mt4_nt1", "conv16_mt4_nt2", "conv16_mt4_nt3", "conv16_mt4_nt4"}};
-  return names[t.MT == 1 ? 0 : t.MT == 2 ? 1 : 2][t.NT - 1];
+  return conv16_tiled_name(L.Kp / 16, L.nchunk_pad / 4, M);
 }
 
 fupr_status launch_conv(const ConvArgs& a, void* stream) {
@@ -435,10 +255,6 @@ fupr_status launch_conv(const ConvArgs& a, void* stream) {
   p.relu = a.relu;
   p.x_bytes = (uint32_t)((int64_t)a.N * a.H * a.W * a.xcs * 2);
   p.w_bytes = (uint32_t)((size_t)L.nchunk_pad * L.Kp * 16);
-  if (getenv("FUPR_CONV_V1")) {
-    const Tile t = choose_tile(p.FT, M);
-    return a.dt == FUPR_BF16 ? launch16<true>(p, t, st) : launch16<false>(p, t, st);
-  }
   return launch_conv16_tiled(p, a.dt == FUPR_BF16, stream);
 }
 

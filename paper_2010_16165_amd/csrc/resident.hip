@@ -17,7 +17,7 @@
 // MT pixel tiles x NT filter tiles of 16 x 16, so every LDS fragment feeds
 // several MFMAs.
 //
-// Arithmetic is the same as conv16_kernel's, step for step: the same chunk
+// Arithmetic is the same as the per-layer kernel's, step for step: the same chunk
 // order along (r, s, c), the same MFMA 16x16x32 accumulation, the same
 // epilogue (bias, shortcut, ReLU, one rounding), so results are bit-identical
 // to the per-layer path.
