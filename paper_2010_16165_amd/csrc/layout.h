@@ -69,53 +69,59 @@ const char* conv_kernel_name(const fupr_conv_shape& s, fupr_dtype dt, int64_t M)
 // ---- whole network in one kernel, activations resident in LDS ----------------
 // One workgroup per image walks a table of layers; see resident.hip.
 
-constexpr int kResMaxLayers = 72;
+constexpr int kResMaxLayers = 256;
 constexpr int kResTableEntries = 256;             // chunks per layer the tap table can hold
 constexpr int kResThreads = 1024;
 constexpr size_t kResLdsLimit = 160 * 1024;
+constexpr int kResScratchBytes = 2048;            // start of LDS: partial sums of the mean layer
 
-// One layer of the table, packed into aligned 32-bit words so that the kernel
-// reads it with scalar loads only (a byte or unaligned 16-bit field would be
-// fetched with a vector load, whose wait would also drain the parameter
-// prefetch in flight).
-struct ResLayer {             // 48 bytes
-  const void* packed;         // conv: blob (bias + weights) in global memory
-  uint32_t off0;              // in_org | out_org << 16     LDS offsets, 16-byte units (see below)
-  uint32_t off1;              // res_org | w_off << 16      res_org 0xffff = none
-  uint32_t sz;                // blob_units | nchunk << 16  blob_units: 16-byte units staged to w_off
-  uint32_t ps0;               // ps_in | ps_out << 16       LDS pixel strides, elements
-  uint32_t ps1;               // ps_res | cs_out << 16      cs_out: lanes written per output pixel
-  uint32_t ch;                // res_cs | Kp << 16          res_cs: lanes held per residual pixel
-  uint32_t g0;                // Wh_in | Wh_out << 8 | P << 16 | Q << 24   Wh: pixels per LDS row
-  uint32_t g1;                // S | stride << 8 | cpt << 16 | nsteps << 24
-  uint32_t g2;                // FT | MT << 8 | NT << 16 | res_Wh << 24    work item: MT x NT tiles
-  uint32_t g3;                // res_ss | flags << 8 | out_halo << 16
+// One layer of the table the kernel walks (device memory, read with scalar
+// loads).  Everything the kernel would otherwise derive per layer is worked out
+// once on the host: LDS byte offsets, byte strides per output row / column,
+// reciprocal multipliers for the two divisions, the work-item count.
+//
+// Tensors in LDS carry a halo of zero pixels.  in_org is the LDS byte offset of
+// the pixel that tap (0, 0) of output pixel (0, 0) reads; out_org and res_org
+// are the offsets of interior pixel (0, 0).  For the global-mean layer M is the
+// INPUT pixel count, Q its width, in_org its interior origin, in_row / in_col
+// its byte strides.
+struct ResLayer {
+  const void* packed;        // conv: blob (bias + weights) in global memory
+  const void* table;         // conv: tap table in global memory, nsteps * 4 byte offsets
+  int32_t blob_units;        // 16-byte units staged to w_off
+  int32_t tab_units;         // 16-byte units staged to tab_off
+  int32_t w_off, tab_off;    // LDS byte offsets of the blob and of the table
+  int32_t wts_off, wstep;    // LDS byte offset of the weights; bytes per MFMA step (4 chunks)
+  int32_t in_org, out_org, res_org;   // res_org < 0: no shortcut
+  int32_t in_row, in_col;    // bytes from an output pixel's window to the next row's / column's
+  int32_t out_row, out_col, res_row, res_col;
+  int32_t M, Q;              // output pixels, output width
+  uint32_t magicQ;           // floor(m / Q) = mulhi(m, magicQ) for m < 2^16; 0 when Q = 1
+  uint32_t magicF;           // floor(item / n_fgroups), likewise
+  int32_t nsteps, FT;        // MFMA steps along (r, s, c); filter tiles of 16
+  int32_t MT, NT;            // work item: MT pixel tiles x NT filter tiles
+  int32_t n_fgroups, n_items;
+  int32_t cs_out, res_cs;    // lanes written per output pixel, lanes held per shortcut pixel
+  int32_t flags;
+  // halo of the output tensor, zeroed by this layer when kResZeroHalo is set
+  int32_t hz_org, hz_P, hz_Q, hz_Wh, hz_ps2, hz_chunks, hz_hp;
+  int32_t pad_[1];
 };
-// Tensors in LDS carry a halo of zero pixels.  in_org is the LDS offset of the
-// pixel that tap (0, 0) of output pixel (0, 0) reads; out_org and res_org are
-// the offsets of interior pixel (0, 0).  For the global-mean layer P x Q is the
-// INPUT extent and in_org its interior origin.
-static_assert(sizeof(ResLayer) == 48, "ResLayer must stay 48 bytes");
-constexpr int kResMean = 1, kResRelu = 2, kResLast = 4;
+static_assert(sizeof(ResLayer) == 160, "ResLayer is read as 40 dwords");
+constexpr int kResMean = 1, kResRelu = 2, kResLast = 4, kResZeroHalo = 8;
 
 struct ResParams {
-  const void* x;    // N images, NHWC
-  void* y;          // N x out_pixels x y_cs
-  int in_H, in_W, in_Wh;         // image extent and pixels per LDS row (in_W + 2 * hp)
-  int in_cs, in_ps;              // global channel stride, LDS pixel stride (elements)
-  int in_org;                    // LDS offset (16-byte units) of the image's interior pixel (0, 0)
-  int hp;                        // halo width of every LDS tensor larger than 1 x 1
+  const void* x;             // N images, NHWC
+  void* y;                   // N x out_pixels x y_cs
+  const ResLayer* layers;    // device memory
+  int in_H, in_W, in_Wh;     // image extent and pixels per LDS row (in_W + 2 * hp)
+  int in_cs, in_ps2;         // global channel stride (elements), LDS pixel stride (bytes)
+  int in_org;                // LDS byte offset of the image's interior pixel (0, 0)
+  int hp;                    // halo width of every LDS tensor larger than 1 x 1
   int y_cs, out_pixels;
   int n_layers;
   int lds_bytes;
-  ResLayer layers[kResMaxLayers];
 };
-static_assert(sizeof(ResParams) <= 3800, "kernel arguments must stay under 4 KB");
-
-// Each thread carries the next layer's parameters through the current layer
-// in kResPrefetch 16-byte registers, so a blob may not exceed this.
-constexpr int kResPrefetch = 5;
-constexpr size_t kResMaxBlob = (size_t)kResPrefetch * 16 * kResThreads;
 
 fupr_status launch_resident(const ResParams& p, int N, fupr_dtype dt, void* stream);
 

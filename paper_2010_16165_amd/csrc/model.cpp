@@ -4,6 +4,9 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdio>
+#include <cstdlib>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -30,6 +33,11 @@ struct fupr_model {
   int schedule = FUPR_SCHEDULE_AUTO;
   bool resident_ok = false;               // the whole network fits one LDS-resident kernel
   ResParams resident{};                   // x, y, y_cs filled per call
+  std::vector<ResLayer> res_layers;       // host copy of the layer table
+  std::vector<int32_t> res_tables;        // tap tables of all layers, back to back
+  std::vector<size_t> res_table_at;       // first entry of each layer's table
+  void* res_dev = nullptr;                // device copy: layer table, then tap tables
+  std::mutex res_mutex;
 };
 
 struct fupr_graph {
@@ -40,23 +48,45 @@ struct fupr_graph {
 namespace {
 
 // Shape of one work item of the LDS-resident kernel for a conv layer: MT pixel
-// tiles x NT filter tiles (MT*NT <= 4 accumulator tiles per wave).  Picks the
-// shape with the smallest estimated layer time: LDS operand traffic (each
-// 16 x 32 fragment is 1 KB = 8 clocks of the compute unit's LDS port) against
-// MFMA issue on the busiest of the four SIMDs (16 clocks per 16x16x32).
-void resident_item_shape(int n_ptiles, int FT, int nsteps, int* MT_out, int* NT_out) {
+// tiles x NT filter tiles.  Picks the shape with the smallest estimated layer
+// time from three measured rates: the compute unit's LDS port (about 5.6 clocks
+// per 1 KB fragment read, 16 per 8-byte-per-lane store), MFMA 16x16x32 issue on
+// the busiest of the four SIMDs (16 clocks, 24 when a wave has a single
+// accumulator and every MFMA waits for the one before), and vector
+// instructions beside them (about 2.7 clocks each).  Items go round robin
+// over 16 waves, hence over the 4 SIMDs.
+// FUPR_RES_ITEM="M/FT/nsteps:MTxNT,..." overrides the choice per layer class
+// (a tuning aid).
+void resident_item_shape(int M, int FT, int nsteps, bool has_res, int* MT_out, int* NT_out) {
   static const int shapes[8][2] = {{4, 1}, {2, 2}, {1, 4}, {3, 1}, {1, 3}, {2, 1}, {1, 2}, {1, 1}};
+  if (const char* env = std::getenv("FUPR_RES_ITEM")) {
+    const char* c = env;
+    while (*c) {
+      int em = 0, ef = 0, es = 0, mt = 0, nt = 0, used = 0;
+      if (std::sscanf(c, "%d/%d/%d:%dx%d%n", &em, &ef, &es, &mt, &nt, &used) == 5) {
+        if (em == M && ef == FT && es == nsteps)
+          for (const auto& sh : shapes)
+            if (sh[0] == mt && sh[1] == nt) { *MT_out = mt; *NT_out = nt; return; }
+        c += used;
+      }
+      while (*c && *c != ',') ++c;
+      if (*c == ',') ++c;
+    }
+  }
   const int waves = kResThreads / 64;
+  const int n_ptiles = (M + 15) / 16;
+  const int steps = nsteps + (has_res ? 1 : 0);
   double best = 1e30;
   for (const auto& sh : shapes) {
     const int mt = sh[0], nt = sh[1];
     const int items = ((n_ptiles + mt - 1) / mt) * ((FT + nt - 1) / nt);
     const int rounds = (items + waves - 1) / waves;
-    const double lds = (double)items * nsteps * (mt + nt) * 8.0;
-    const int per_simd = (std::min(items, waves) + 3) / 4 * rounds;
-    const double mfma = (double)per_simd * nsteps * mt * nt * 16.0;
-    const double latency = (double)rounds * nsteps * 40.0;   // exposed per-step latency
-    const double t = std::max(lds, mfma) + latency;
+    const int simd_items = (items + 3) / 4;
+    const double lds = (double)items * (nsteps * (mt * 5.6 + nt * 5.0 + 2.0) +
+                                        (has_res ? mt * nt * 5.6 : 0.0) + mt * nt * 16.0 + nt * 5.0);
+    const double mfma = (double)simd_items * steps * mt * nt * (mt * nt == 1 ? 24.0 : 16.0);
+    const double valu = (double)simd_items * (20.0 + 9.0 * mt + nsteps * (mt + 1.0) + 8.0 * mt * nt) * 2.7;
+    const double t = std::max(lds, mfma + 0.6 * valu) + rounds * 600.0;
     if (t < best) {
       best = t;
       *MT_out = mt;
@@ -102,9 +132,29 @@ size_t assign_offsets(std::vector<LdsBlock>& blocks) {
   return extent;
 }
 
+// LDS pixel stride in bytes for a tensor of cs 16-bit lanes.  The 16 pixels x 4
+// chunks of one MFMA pixel fragment are read with one 16-byte access per lane;
+// measured on gfx950 that access runs at full rate when the pixel stride is an
+// odd multiple of 32 bytes (an odd multiple of 16 when the reading convolution
+// has stride 2, which doubles the lane-to-lane distance), and at half rate or
+// worse otherwise.  mode 0: the nearest such stride; 1: channel stride + 16
+// bytes; 2: dense.
+int lds_pixel_stride(int cs, bool strided_reader, int mode) {
+  const int dense = cs * 2;
+  if (mode == 2) return dense;
+  if (mode == 1) return dense + 16;
+  if (strided_reader) return dense % 32 == 16 ? dense : dense + 16;
+  int ps2 = dense;
+  while (ps2 % 64 != 32) ps2 += 16;
+  return ps2;
+}
+
+// floor(v / d) = mulhi(v, reciprocal) for v < 2^16; 0 stands for d = 1
+uint32_t reciprocal_u16(int d) { return d == 1 ? 0u : 0xffffffffu / (uint32_t)d + 1u; }
+
 // Tries to lay the whole network out for resident_kernel: every per-image
 // tensor (input included, final output excluded) and, for the current and the
-// next layer, the parameter blob, in LDS.
+// next layer, the tap table and the parameter blob, in LDS.
 void plan_resident(fupr_model* m) {
   m->resident_ok = false;
   const int n = (int)m->ops.size();
@@ -114,29 +164,40 @@ void plan_resident(fupr_model* m) {
 
   // every LDS tensor larger than 1 x 1 gets a ring of hp zero pixels
   int hp = 0;
-  for (const fupr_op_desc& op : m->ops)
+  for (const fupr_op_desc& op : m->ops) {
     if (op.kind == FUPR_OP_CONV) hp = std::max(hp, op.conv.pad);
+    else if (op.kind != FUPR_OP_AVGPOOL) return;   // max-pool networks: images too large for LDS
+  }
   for (const TensorInfo& t : m->tensors)
-    if (t.W + 2 * hp > 255 || t.H + 2 * hp > 255) return;
+    if ((int64_t)(t.W + 2 * hp) * (t.H + 2 * hp) >= 65536) return;
   auto halo_of = [&](const TensorInfo& t) { return t.H * t.W > 1 ? hp : 0; };
+  auto row_of = [&](const TensorInfo& t) { return t.W + 2 * halo_of(t); };
 
-  const size_t table_bytes = 2 * kResTableEntries * sizeof(int32_t);
-  const size_t budget_units = (kResLdsLimit - table_bytes) / 16;
+  // which tensors are only ever the main input of stride-2 convolutions
+  std::vector<int> readers(n + 1, 0), strided(n + 1, 0);
+  for (const fupr_op_desc& op : m->ops)
+    if (op.kind == FUPR_OP_CONV) {
+      ++readers[op.in];
+      if (op.conv.stride == 2) ++strided[op.in];
+    }
 
-  // pad = 1: LDS pixel stride = channel stride + 8 elements, which spreads the
-  // 16 pixels of a fragment over all banks; fall back to the dense stride when
-  // the padded layout does not fit.
-  for (int pad = 1; pad >= 0; --pad) {
+  const size_t budget_units = (kResLdsLimit - kResScratchBytes) / 16;
+
+  for (int mode = 0; mode <= 2; ++mode) {
+    std::vector<int> ps2(n + 1);
+    for (int tid = 0; tid <= n; ++tid) {
+      const TensorInfo& t = m->tensors[tid];
+      ps2[tid] = t.H * t.W > 1
+                     ? lds_pixel_stride(t.cs, readers[tid] > 0 && strided[tid] == readers[tid], mode)
+                     : t.cs * 2;
+    }
     std::vector<LdsBlock> blocks(2 * (size_t)n + 1);
-    auto stride_of = [&](const TensorInfo& t) { return t.cs + (pad && t.H * t.W > 1 ? 8 : 0); };
-    auto row_of = [&](const TensorInfo& t) { return t.W + 2 * halo_of(t); };
     for (int tid = 0; tid <= n; ++tid) {
       const TensorInfo& t = m->tensors[tid];
       LdsBlock& b = blocks[tid];
       b.first = tid - 1;                       // produced by layer tid-1 (image: before layer 0)
       b.last = std::max(t.last_use, b.first);
-      b.units = tid == n ? 0
-                         : (size_t)(t.H + 2 * halo_of(t)) * row_of(t) * stride_of(t) * 2 / 16;
+      b.units = tid == n ? 0 : (size_t)(t.H + 2 * halo_of(t)) * row_of(t) * ps2[tid] / 16;
     }
     bool ok = true;
     for (int i = 0; i < n && ok; ++i) {
@@ -146,18 +207,40 @@ void plan_resident(fupr_model* m) {
       b.units = 0;
       if (m->ops[i].kind == FUPR_OP_CONV) {
         const PackedLayout PL = packed_layout(m->ops[i].conv, m->dt);
-        if (PL.total_bytes > kResMaxBlob) ok = false;
-        b.units = PL.total_bytes / 16;
+        if (PL.nchunk_pad > kResTableEntries) ok = false;
+        b.units = PL.nchunk_pad / 4 + PL.total_bytes / 16;   // table (16 bytes per step), blob
       }
     }
     if (!ok) return;
     const size_t extent = assign_offsets(blocks);
-    if (extent > budget_units || extent >= 0xffff) continue;
+    if (extent > budget_units) continue;
 
-    // LDS offset (16-byte units) of pixel (row, col) counted from the halo's corner
+    // LDS byte offset of pixel (row, col) counted from the halo's corner
     auto pixel_at = [&](int tid, int row, int col) {
       const TensorInfo& t = m->tensors[tid];
-      return (uint32_t)(blocks[tid].offset + (size_t)(row * row_of(t) + col) * stride_of(t) / 8);
+      return (int32_t)(blocks[tid].offset * 16 + (size_t)(row * row_of(t) + col) * ps2[tid]);
+    };
+
+    // known-zero 16-byte units, to skip re-zeroing halos that are still clean
+    std::vector<uint8_t> clean(extent, 0);
+    auto mark = [&](size_t first, size_t count, uint8_t v) {
+      std::fill(clean.begin() + first, clean.begin() + first + count, v);
+    };
+    auto halo_units = [&](int tid, auto&& fn) {   // fn(unit) for every channel chunk of the halo
+      const TensorInfo& t = m->tensors[tid];
+      const int h = halo_of(t), Wh = row_of(t);
+      for (int row = 0; row < t.H + 2 * h; ++row)
+        for (int col = 0; col < Wh; ++col) {
+          if (row >= h && row < t.H + h && col >= h && col < t.W + h) continue;
+          const size_t u = (size_t)pixel_at(tid, row, col) / 16;
+          for (int c = 0; c < t.cs / 8; ++c) fn(u + c);
+        }
+    };
+    auto write_interior = [&](int tid) {
+      const TensorInfo& t = m->tensors[tid];
+      const int h = halo_of(t);
+      for (int row = 0; row < t.H; ++row)
+        mark((size_t)pixel_at(tid, row + h, h) / 16, (size_t)t.W * ps2[tid] / 16, 0);
     };
 
     ResParams& R = m->resident;
@@ -167,81 +250,158 @@ void plan_resident(fupr_model* m) {
     R.in_W = t0.W;
     R.in_Wh = row_of(t0);
     R.in_cs = t0.cs;
-    R.in_ps = stride_of(t0);
-    R.in_org = (int)pixel_at(0, halo_of(t0), halo_of(t0));
+    R.in_ps2 = ps2[0];
+    R.in_org = pixel_at(0, halo_of(t0), halo_of(t0));
     R.hp = hp;
     R.n_layers = n;
-    R.lds_bytes = (int)(table_bytes + extent * 16);
+    R.lds_bytes = (int)(kResScratchBytes + extent * 16);
     R.out_pixels = m->tensors[n].H * m->tensors[n].W;
+    write_interior(0);
+    halo_units(0, [&](size_t u) { clean[u] = 1; });
+    if (blocks[n + 1].units) mark(blocks[n + 1].offset, blocks[n + 1].units, 0);
+
+    m->res_layers.assign(n, ResLayer{});
+    m->res_tables.clear();
+    m->res_table_at.assign(n, 0);
     for (int i = 0; i < n; ++i) {
       const fupr_op_desc& op = m->ops[i];
       const TensorInfo& ti = m->tensors[op.in];
       const TensorInfo& to = m->tensors[i + 1];
       const bool last = i + 1 == n;
-      uint32_t in_org = 0, out_org = last ? 0 : pixel_at(i + 1, halo_of(to), halo_of(to));
-      uint32_t res_org = 0xffff, w_off = (uint32_t)blocks[n + 1 + i].offset;
-      uint32_t blob_units = (uint32_t)blocks[n + 1 + i].units, nchunk = 0;
-      uint32_t ps_in = (uint32_t)stride_of(ti), ps_out = (uint32_t)stride_of(to), ps_res = 0;
-      uint32_t cs_out = (uint32_t)to.cs, res_cs = 0, Kp = 0;
-      uint32_t S = 0, stride = 0, cpt = 0, nsteps = 0, FT = 0, MT = 1, NT = 1;
-      uint32_t res_Wh = 0, res_ss = 0, flags = last ? kResLast : 0;
-      uint32_t P = (uint32_t)to.H, Q = (uint32_t)to.W;
-      const void* packed = nullptr;
+      ResLayer L{};
+      L.flags = last ? kResLast : 0;
+      L.res_org = -1;
+      L.out_org = last ? 0 : pixel_at(i + 1, halo_of(to), halo_of(to));
+      L.cs_out = to.cs;
+      L.M = to.H * to.W;
+      L.Q = to.W;
+      L.MT = L.NT = L.n_fgroups = 1;
       if (op.kind == FUPR_OP_AVGPOOL) {
-        flags |= kResMean;
-        in_org = pixel_at(op.in, halo_of(ti), halo_of(ti));
-        P = (uint32_t)ti.H;      // the mean layer iterates over its INPUT extent
-        Q = (uint32_t)ti.W;
-      } else if (op.kind == FUPR_OP_CONV) {
+        L.flags |= kResMean;
+        L.in_org = pixel_at(op.in, halo_of(ti), halo_of(ti));
+        L.in_row = row_of(ti) * ps2[op.in];
+        L.in_col = ps2[op.in];
+        L.M = ti.H * ti.W;       // the mean layer iterates over its INPUT extent
+        L.Q = ti.W;
+        // partial sums held in the scratch area: MT parts x cs_out floats
+        L.MT = std::min(8, kResScratchBytes / 4 / to.cs);
+        if (L.MT < 1 || L.MT * to.cs > kResThreads) return;
+      } else {
         const fupr_conv_shape& s = op.conv;
         const PackedLayout PL = packed_layout(s, m->dt);
-        if (PL.nchunk_pad > kResTableEntries || s.S > 255 || s.stride > 255 ||
-            PL.Cp / 8 > 255 || PL.Kp / 16 > 255 || PL.Kp > 4096)
-          return;
         if (halo_of(ti) < s.pad) return;   // a padded conv on a 1 x 1 image: not laid out here
-        packed = op.packed;
-        in_org = pixel_at(op.in, halo_of(ti) - s.pad, halo_of(ti) - s.pad);
-        nchunk = (uint32_t)PL.nchunk;
-        Kp = (uint32_t)PL.Kp;
-        S = (uint32_t)s.S; stride = (uint32_t)s.stride;
-        cpt = (uint32_t)(PL.Cp / 8);
-        nsteps = (uint32_t)(PL.nchunk_pad / 4);
-        FT = (uint32_t)(PL.Kp / 16);
-        int mt = 1, nt = 1;
-        resident_item_shape((to.H * to.W + 15) / 16, (int)FT, (int)nsteps, &mt, &nt);
-        MT = (uint32_t)mt;
-        NT = (uint32_t)nt;
-        if (op.epilogue & FUPR_FUSE_RELU) flags |= kResRelu;
+        const int nsteps = PL.nchunk_pad / 4, cpt = PL.Cp / 8;
+        L.packed = op.packed;
+        L.blob_units = (int32_t)(PL.total_bytes / 16);
+        L.tab_units = nsteps;
+        L.tab_off = (int32_t)(blocks[n + 1 + i].offset * 16);
+        L.w_off = L.tab_off + nsteps * 16;
+        L.wts_off = L.w_off + (int32_t)PL.weight_offset;
+        L.wstep = 4 * PL.Kp * 16;
+        L.in_org = pixel_at(op.in, halo_of(ti) - s.pad, halo_of(ti) - s.pad);
+        L.in_row = s.stride * row_of(ti) * ps2[op.in];
+        L.in_col = s.stride * ps2[op.in];
+        L.out_row = row_of(to) * ps2[i + 1];
+        L.out_col = ps2[i + 1];
+        L.nsteps = nsteps;
+        L.FT = PL.Kp / 16;
+        if (op.epilogue & FUPR_FUSE_RELU) L.flags |= kResRelu;
         if (op.res >= 0) {
-          if (op.res_c_offset != 0 || op.res_spatial_stride > 255) return;
+          if (op.res_c_offset != 0) return;
           const TensorInfo& tr = m->tensors[op.res];
-          res_org = pixel_at(op.res, halo_of(tr), halo_of(tr));
-          res_cs = (uint32_t)tr.cs;
-          ps_res = (uint32_t)stride_of(tr);
-          res_Wh = (uint32_t)row_of(tr);
-          res_ss = (uint32_t)op.res_spatial_stride;
+          L.res_org = pixel_at(op.res, halo_of(tr), halo_of(tr));
+          L.res_cs = tr.cs;
+          L.res_row = op.res_spatial_stride * row_of(tr) * ps2[op.res];
+          L.res_col = op.res_spatial_stride * ps2[op.res];
         }
-      } else {
-        return;   // max-pool networks have images too large for LDS anyway
+        int mt = 1, nt = 1;
+        resident_item_shape(L.M, L.FT, nsteps, op.res >= 0, &mt, &nt);
+        L.MT = mt;
+        L.NT = nt;
+        L.n_fgroups = (L.FT + nt - 1) / nt;
+        L.n_items = ((L.M + 15) / 16 + mt - 1) / mt * L.n_fgroups;
+        if (L.n_items >= 65536) return;
+        // tap table: byte offset of every chunk from the window's first pixel;
+        // padding chunks (zero weights) re-read the first chunk: finite data
+        m->res_table_at[i] = m->res_tables.size();
+        for (int j = 0; j < nsteps * 4; ++j) {
+          int32_t e = 0;
+          if (j < PL.nchunk) {
+            const int tap = j / cpt, c8 = j - tap * cpt;
+            const int r = tap / s.S, sx = tap - r * s.S;
+            e = (r * row_of(ti) + sx) * ps2[op.in] + c8 * 16;
+          }
+          m->res_tables.push_back(e);
+        }
       }
-      if (in_org >= 0xffff || out_org >= 0xffff || (res_org != 0xffff && res_org >= 0xffff)) return;
-      ResLayer L{};
-      L.packed = packed;
-      L.off0 = in_org | out_org << 16;
-      L.off1 = res_org | w_off << 16;
-      L.sz = blob_units | nchunk << 16;
-      L.ps0 = ps_in | ps_out << 16;
-      L.ps1 = ps_res | cs_out << 16;
-      L.ch = res_cs | Kp << 16;
-      L.g0 = (uint32_t)row_of(ti) | (uint32_t)row_of(to) << 8 | P << 16 | Q << 24;
-      L.g1 = S | stride << 8 | cpt << 16 | nsteps << 24;
-      L.g2 = FT | MT << 8 | NT << 16 | res_Wh << 24;
-      L.g3 = res_ss | flags << 8 | (uint32_t)halo_of(to) << 16;
-      R.layers[i] = L;
+      L.magicQ = reciprocal_u16(L.Q);
+      L.magicF = reciprocal_u16(L.n_fgroups);
+      if (!last) {
+        bool dirty = false;
+        halo_units(i + 1, [&](size_t u) { dirty = dirty || !clean[u]; });
+        if (dirty) {
+          L.flags |= kResZeroHalo;
+          L.hz_org = L.out_org;
+          L.hz_P = to.H;
+          L.hz_Q = to.W;
+          L.hz_Wh = row_of(to);
+          L.hz_ps2 = ps2[i + 1];
+          L.hz_chunks = to.cs / 8;
+          L.hz_hp = halo_of(to);
+          halo_units(i + 1, [&](size_t u) { clean[u] = 1; });
+        }
+        if (halo_of(to) > 0) write_interior(i + 1);
+        else mark(blocks[i + 1].offset, blocks[i + 1].units, 0);
+      }
+      if (i + 1 < n && blocks[n + 2 + i].units) mark(blocks[n + 2 + i].offset, blocks[n + 2 + i].units, 0);
+      m->res_layers[i] = L;
+      if (std::getenv("FUPR_DEBUG"))
+        std::fprintf(stderr, "resident layer %d: M %d FT %d steps %d item %dx%d items %d ps2 in %d out %d "
+                     "zero_halo %d res %d\n", i, L.M, L.FT, L.nsteps, L.MT, L.NT, L.n_items, ps2[op.in],
+                     ps2[i + 1], (L.flags & kResZeroHalo) != 0, L.res_org >= 0);
     }
+    if (std::getenv("FUPR_DEBUG"))
+      std::fprintf(stderr, "resident plan: stride mode %d, %d bytes of LDS\n", mode, R.lds_bytes);
     m->resident_ok = true;
     return;
   }
+}
+
+void release_resident(fupr_model* m) {
+  if (m->res_dev) (void)hipFree(m->res_dev);
+  m->res_dev = nullptr;
+}
+
+// Copies the layer table and the tap tables to the device (once).  Returns
+// false when there is no device to copy to.
+bool upload_resident(const fupr_model* cm) {
+  fupr_model* m = const_cast<fupr_model*>(cm);
+  std::lock_guard<std::mutex> lock(m->res_mutex);
+  if (m->res_dev) return true;
+  const size_t n = m->res_layers.size();
+  const size_t layer_bytes = round_up_sz(n * sizeof(ResLayer), 256);
+  const size_t table_bytes = round_up_sz(m->res_tables.size() * sizeof(int32_t), 256) + 256;
+  void* dev = nullptr;
+  if (hipMalloc(&dev, layer_bytes + table_bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  char* base = reinterpret_cast<char*>(dev);
+  std::vector<ResLayer> layers = m->res_layers;
+  for (size_t i = 0; i < n; ++i)
+    layers[i].table = base + layer_bytes + m->res_table_at[i] * sizeof(int32_t);
+  bool ok = hipMemcpy(base, layers.data(), n * sizeof(ResLayer), hipMemcpyHostToDevice) == hipSuccess;
+  if (ok && !m->res_tables.empty())
+    ok = hipMemcpy(base + layer_bytes, m->res_tables.data(), m->res_tables.size() * sizeof(int32_t),
+                   hipMemcpyHostToDevice) == hipSuccess;
+  if (!ok) {
+    (void)hipGetLastError();
+    (void)hipFree(dev);
+    return false;
+  }
+  m->res_dev = dev;
+  m->resident.layers = reinterpret_cast<const ResLayer*>(dev);
+  return true;
 }
 
 }  // namespace
@@ -358,6 +518,7 @@ extern "C" fupr_status fupr_model_create(const fupr_graph_desc* g, fupr_model** 
     }
   }
   plan_resident(m);
+  if (m->resident_ok) (void)upload_resident(m);   // retried at the first forward pass if no device yet
   *out = m;
   return FUPR_OK;
 }
@@ -369,7 +530,11 @@ extern "C" fupr_status fupr_model_set_schedule(fupr_model* m, int32_t schedule) 
   return FUPR_OK;
 }
 
-extern "C" void fupr_model_destroy(fupr_model* m) { delete m; }
+extern "C" void fupr_model_destroy(fupr_model* m) {
+  if (!m) return;
+  release_resident(m);
+  delete m;
+}
 
 extern "C" int32_t fupr_model_num_ops(const fupr_model* m) { return m ? (int32_t)m->ops.size() : 0; }
 
@@ -445,6 +610,7 @@ fupr_status run(const fupr_model* m, const fupr_tensor* input, const fupr_tensor
   hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
   if (events && hipEventRecord(events[0], hs) != hipSuccess) return FUPR_ERR_LAUNCH;
   if (use_resident(m, input, output)) {
+    if (!upload_resident(m)) return FUPR_ERR_LAUNCH;
     ResParams R = m->resident;
     R.x = input->ptr;
     R.y = output->ptr;
@@ -585,6 +751,7 @@ extern "C" fupr_status fupr_graph_create(const fupr_model* m, const fupr_tensor*
                                          size_t workspace_bytes, void* stream, fupr_graph** out) {
   if (!out) return FUPR_ERR_NULL;
   if (!stream) return FUPR_ERR_ARG;
+  if (m && m->resident_ok) (void)upload_resident(m);   // no allocation inside the capture
   hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
   fupr_graph* g = new (std::nothrow) fupr_graph;
   if (!g) return FUPR_ERR_ARG;

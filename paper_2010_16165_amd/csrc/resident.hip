@@ -10,17 +10,18 @@
 // columns of Table VI) is removed here one level further: the operator
 // boundaries themselves.
 //
-// Per layer: the next layer's parameter blob is fetched from global memory into
-// registers BEFORE the current layer is computed and written to LDS after it,
-// so no global-memory latency sits on the layer chain; both MFMA operands of
-// the current layer (filters = A, pixels = B) come from LDS.  A work item is
-// MT pixel tiles x NT filter tiles of 16 x 16, so every LDS fragment feeds
-// several MFMAs.
+// Per layer: the next layer's parameter blob and tap table are on their way from
+// global memory into LDS WHILE the current layer is computed, so no
+// global-memory latency sits on the layer chain; both MFMA operands of the
+// current layer (filters = A, pixels = B) come from LDS.
+// A work item is MT pixel tiles x NT filter tiles of 16 x 16, so every LDS
+// fragment feeds several MFMAs.
 //
-// Arithmetic is the same as the per-layer kernel's, step for step: the same chunk
-// order along (r, s, c), the same MFMA 16x16x32 accumulation, the same
-// epilogue (bias, shortcut, ReLU, one rounding), so results are bit-identical
-// to the per-layer path.
+// The instruction stream around the MFMAs is what bounds a network this small,
+// so it is kept short: the bias enters as the accumulator input of the first
+// MFMA, and the shortcut is added by one more MFMA step whose filter operand
+// is a one-hot (identity) fragment built in registers — the epilogue is ReLU,
+// one rounding and one LDS store.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -35,45 +36,9 @@ namespace {
 
 constexpr int kWaves = kResThreads / 64;
 
-// A wave-uniform value the optimiser knows nothing about.  The layer table
-// stores geometry in bytes; arithmetic on values KNOWN to be bytes was turned
-// into packed byte dot products that dropped the sign of a subtracted term
-// (tap - r*S came out as tap + r*S), so every field is laundered through a
-// scalar move before it enters index arithmetic.
-__device__ __forceinline__ int opaque(int v) {
-  int r;
-  asm volatile("s_mov_b32 %0, %1" : "=s"(r) : "s"(v));
-  return r;
-}
-
-// A layer descriptor unpacked into scalar registers.
-struct LayerRegs {
-  const void* packed;
-  int in_org, out_org, res_org, w_off, blob_units, nchunk;
-  int ps_in, ps_out, ps_res, cs_out, res_cs, Kp;
-  int Wh_in, Wh_out, P, Q, S, stride, cpt, nsteps, FT, MT, NT, res_Wh, res_ss, flags, out_halo;
-};
-
-__device__ __forceinline__ LayerRegs unpack(const ResLayer& L) {
-  LayerRegs r;
-  r.packed = L.packed;
-  const uint32_t off0 = L.off0, off1 = L.off1, sz = L.sz, ps0 = L.ps0, ps1 = L.ps1, ch = L.ch;
-  const uint32_t g0 = L.g0, g1 = L.g1, g2 = L.g2, g3 = L.g3;
-  r.in_org = opaque(off0 & 0xffff);   r.out_org = opaque(off0 >> 16);
-  r.res_org = opaque(off1 & 0xffff);  r.w_off = opaque(off1 >> 16);
-  r.blob_units = opaque(sz & 0xffff); r.nchunk = opaque(sz >> 16);
-  r.ps_in = opaque(ps0 & 0xffff);     r.ps_out = opaque(ps0 >> 16);
-  r.ps_res = opaque(ps1 & 0xffff);    r.cs_out = opaque(ps1 >> 16);
-  r.res_cs = opaque(ch & 0xffff);     r.Kp = opaque(ch >> 16);
-  r.Wh_in = opaque(g0 & 255);  r.Wh_out = opaque((g0 >> 8) & 255);
-  r.P = opaque((g0 >> 16) & 255);  r.Q = opaque(g0 >> 24);
-  r.S = opaque(g1 & 255);  r.stride = opaque((g1 >> 8) & 255);
-  r.cpt = opaque((g1 >> 16) & 255);  r.nsteps = opaque(g1 >> 24);
-  r.FT = opaque(g2 & 255);  r.MT = opaque((g2 >> 8) & 255);
-  r.NT = opaque((g2 >> 16) & 255);  r.res_Wh = opaque(g2 >> 24);
-  r.res_ss = opaque(g3 & 255);  r.flags = opaque((g3 >> 8) & 255);
-  r.out_halo = opaque((g3 >> 16) & 255);
-  return r;
+// floor(v / d) for v < 2^16 from the host's reciprocal of d (0 stands for d = 1).
+__device__ __forceinline__ int div_magic(int v, uint32_t magic) {
+  return magic ? (int)__umulhi((uint32_t)v, magic) : v;
 }
 
 // Zeroes the halo ring (hp pixels wide) around a P x Q tensor whose interior
@@ -101,133 +66,142 @@ __device__ __forceinline__ void zero_halo(char* act, int org, int P, int Q, int 
   }
 }
 
+// The filter fragment of the shortcut step for filter tile ft: row i (= filter
+// ft*16 + i) has a single 1.0 at reduction index i, so the MFMA adds shortcut
+// channel ft*16 + i to that filter's accumulator; rows beyond the shortcut's
+// channel count stay zero (a shortcut with fewer channels than the block
+// output is the zero-padded kind).
+template <bool BF>
+__device__ __forceinline__ uint4 identity_fragment(int ft, int res_cs, int li, int g) {
+  const uint32_t one = BF ? 0x3f80u : 0x3c00u;
+  const bool on = g == (li >> 3) && ft * 16 + li < res_cs;
+  const uint32_t v = on ? one << ((li & 1) * 16) : 0u;
+  const int j = (li & 7) >> 1;
+  return uint4{j == 0 ? v : 0u, j == 1 ? v : 0u, j == 2 ? v : 0u, j == 3 ? v : 0u};
+}
+
 // All work items of one conv layer that fall to this wave.  LAST: the layer
 // writes the network output to global memory instead of LDS.
 //
 // Every activation tensor in LDS carries a ring of zero pixels as wide as the
 // largest padding of any convolution, so a tap never needs a bounds check: the
-// K loop is one table read, MT + NT address additions, MT + NT LDS reads and
+// K loop is one table read, MT + 1 address additions, MT + NT LDS reads and
 // MT * NT MFMAs per step.  D steps of operands are kept in flight (ring of
-// register buffers, loop unrolled by D), and the table entry of a step is read
-// one issue ahead of that step's operand reads.
+// register buffers, loop unrolled by D).
 template <bool BF, int MT, int NT, bool LAST>
-__device__ __forceinline__ void conv_items(const LayerRegs& L, const ResParams& p, char* act,
-                                           const int* tab, int n, int lane, int wave) {
-  constexpr int D = (MT + NT <= 2) ? 4 : (MT + NT <= 4 ? 3 : 2);
+__device__ __forceinline__ void conv_items(const ResLayer& L, const ResParams& p, char* act,
+                                           int n, int lane, int wave) {
+  constexpr int D = (MT + NT <= 3) ? 4 : (MT + NT == 4 ? 3 : 2);
   const int li = lane & 15, g = lane >> 4;
-  const int Q = L.Q, nsteps = L.nsteps, FT = L.FT, Kp = L.Kp;
-  const bool relu = (L.flags & kResRelu) != 0, has_res = L.res_org != 0xffff;
-  const int M = L.P * Q;
-  const uint32_t magicQ = 0xffffffffu / (uint32_t)Q + 1u;   // floor(m / Q) = mulhi(m, magicQ), m < 2^16
-  const int n_ptiles = (M + 15) >> 4;
-  const int n_pgroups = (n_ptiles + MT - 1) / MT;
-  const int n_fgroups = (FT + NT - 1) / NT;
-  const int n_items = n_pgroups * n_fgroups;
+  const int nsteps = L.nsteps, FT = L.FT, M = L.M, Q = L.Q;
+  const bool relu = (L.flags & kResRelu) != 0, has_res = L.res_org >= 0;
   const int ycs = LAST ? p.y_cs : L.cs_out;
-
-  const int in_org = L.in_org * 16, out_org = L.out_org * 16, res_org = L.res_org * 16;
-  const int in_row = L.stride * L.Wh_in * L.ps_in * 2, in_col = L.stride * L.ps_in * 2;
-  const int out_row = L.Wh_out * L.ps_out * 2, out_col = L.ps_out * 2;
-  const int res_row = L.res_ss * L.res_Wh * L.ps_res * 2, res_col = L.res_ss * L.ps_res * 2;
-  const int wblob = L.w_off * 16;
-  const float* bias = reinterpret_cast<const float*>(act + wblob);
-  const int wts = wblob + (Kp * 4 + 255) / 256 * 256;
-  const int wstep = 4 * Kp * 16;   // bytes per MFMA step
-  const int* tabg = tab + g;
+  const int wstep = L.wstep;
+  const int a_lane = L.wts_off + g * (wstep >> 2) + li * 16;
+  const float* bias = reinterpret_cast<const float*>(act + L.w_off);
+  const int* tabg = reinterpret_cast<const int*>(act + L.tab_off) + g;
+  const int n_items = L.n_items, n_fgroups = L.n_fgroups;
 
   for (int item = wave; item < n_items; item += kWaves) {
-    const int pg = item / n_fgroups;
+    const int pg = div_magic(item, L.magicF);
     const int ft0 = (item - pg * n_fgroups) * NT;
     int m[MT], bptr[MT], ooff[MT], roff[MT];
-    bool pv[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       m[mt] = (pg * MT + mt) * 16 + li;
-      pv[mt] = m[mt] < M;
       const int mc = min(m[mt], M - 1);
-      const int pp = (int)__umulhi((uint32_t)mc, magicQ), qq = mc - pp * Q;
-      bptr[mt] = in_org + pp * in_row + qq * in_col;
-      ooff[mt] = out_org + pp * out_row + qq * out_col;
-      roff[mt] = res_org + pp * res_row + qq * res_col;
+      const int pp = div_magic(mc, L.magicQ), qq = mc - pp * Q;
+      bptr[mt] = L.in_org + pp * L.in_row + qq * L.in_col;
+      ooff[mt] = L.out_org + pp * L.out_row + qq * L.out_col;
+      roff[mt] = L.res_org + pp * L.res_row + qq * L.res_col;
     }
-    int aptr[NT];
+    // filter tiles past the last one repeat it (computed, not stored)
+    int ft[NT];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) aptr[t] = wts + (g * Kp + min(ft0 + t, FT - 1) * 16 + li) * 16;
-
-    f32x4 acc[MT][NT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-      for (int t = 0; t < NT; ++t) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < NT; ++t) ft[t] = min(ft0 + t, FT - 1);
+    int aptr = a_lane;
 
     uint4 a[D][NT], b[D][MT];
-    int ls = 0;   // next step to be issued
-    int e_pre;    // its tap-table entry
     auto operands = [&](const int e, uint4* av, uint4* bv) {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) bv[mt] = *reinterpret_cast<const uint4*>(act + bptr[mt] + e);
 #pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        av[t] = *reinterpret_cast<const uint4*>(act + aptr[t]);
-        aptr[t] += wstep;
-      }
-      ++ls;
+      for (int t = 0; t < NT; ++t) av[t] = *reinterpret_cast<const uint4*>(act + aptr + ft[t] * 256);
+      aptr += wstep;
     };
 
-    {
-      int e0[D];
+    int e0[D];
 #pragma unroll
-      for (int d = 0; d < D; ++d) e0[d] = tabg[min(d, nsteps - 1) * 4];
-      e_pre = tabg[min(D, nsteps - 1) * 4];
+    for (int d = 0; d < D; ++d) e0[d] = tabg[min(d, nsteps - 1) * 4];
+    int e_pre = tabg[min(D, nsteps - 1) * 4];
+    int ls = D;   // next step whose table entry is e_pre
 #pragma unroll
-      for (int d = 0; d < D; ++d)
-        if (d < nsteps) operands(e0[d], a[d], b[d]);
+    for (int d = 0; d < D; ++d)
+      if (d < nsteps) operands(e0[d], a[d], b[d]);
+
+    // the bias is the accumulator input of the first step
+    f32x4 b4[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+      b4[t] = *reinterpret_cast<const f32x4*>(bias + ft[t] * 16 + g * 4);
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int t = 0; t < NT; ++t) acc[mt][t] = mfma_16x16x32<BF>(a[0][t], b[0][mt], b4[t]);
+    if (D < nsteps) {
+      const int e = e_pre;
+      e_pre = tabg[min(D + 1, nsteps - 1) * 4];
+      ls = D + 1;
+      operands(e, a[0], b[0]);
     }
     for (int step0 = 0; step0 < nsteps; step0 += D) {
 #pragma unroll
       for (int d = 0; d < D; ++d) {
+        if (step0 + d == 0) continue;   // peeled above
         if (step0 + d < nsteps) {
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int t = 0; t < NT; ++t)
               acc[mt][t] = mfma_16x16x32<BF>(a[d][t], b[d][mt], acc[mt][t]);
-          if (ls < nsteps) {
+          if (step0 + d + D < nsteps) {
             const int e = e_pre;
-            e_pre = tabg[min(ls + 1, nsteps - 1) * 4];
+            ++ls;
+            e_pre = tabg[min(ls, nsteps - 1) * 4];
             operands(e, a[d], b[d]);
           }
         }
       }
     }
-
-    // epilogue: bias, shortcut, ReLU, one rounding.  All LDS reads first.
-    float4 b4[NT];
-    uint2 rv[MT][NT];
+    if (has_res) {
+      // the shortcut: one more step whose filter fragment is one-hot
+      uint4 rb[MT][NT];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      const int k0 = (min(ft0 + t, FT - 1)) * 16 + g * 4;
-      b4[t] = *reinterpret_cast<const float4*>(bias + k0);
+      for (int t = 0; t < NT; ++t) {
+        const int chunk = min(ft[t] * 2 + (g & 1), (L.res_cs >> 3) - 1);
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const bool rd = has_res && k0 < L.res_cs;
-        rv[mt][t] = rd ? *reinterpret_cast<const uint2*>(act + roff[mt] + k0 * 2) : uint2{0u, 0u};
+        for (int mt = 0; mt < MT; ++mt)
+          rb[mt][t] = *reinterpret_cast<const uint4*>(act + roff[mt] + chunk * 16);
+      }
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        if (ft[t] * 16 < L.res_cs) {
+          const uint4 ia = identity_fragment<BF>(ft[t], L.res_cs, li, g);
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) acc[mt][t] = mfma_16x16x32<BF>(ia, rb[mt][t], acc[mt][t]);
+        }
       }
     }
+
+    // epilogue: ReLU, one rounding, store
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
         const int k0 = (ft0 + t) * 16 + g * 4;
-        if (!pv[mt] || ft0 + t >= FT || k0 >= ycs) continue;
-        float v[4] = {acc[mt][t][0] + b4[t].x, acc[mt][t][1] + b4[t].y, acc[mt][t][2] + b4[t].z,
-                      acc[mt][t][3] + b4[t].w};
-        if (has_res) {
-          v[0] += to_float<BF>((uint16_t)(rv[mt][t].x & 0xffffu));
-          v[1] += to_float<BF>((uint16_t)(rv[mt][t].x >> 16));
-          v[2] += to_float<BF>((uint16_t)(rv[mt][t].y & 0xffffu));
-          v[3] += to_float<BF>((uint16_t)(rv[mt][t].y >> 16));
-        }
+        if (m[mt] >= M || ft0 + t >= FT || k0 >= ycs) continue;
+        float v[4] = {acc[mt][t][0], acc[mt][t][1], acc[mt][t][2], acc[mt][t][3]};
         if (relu) {
 #pragma unroll
           for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i], 0.f);
@@ -248,120 +222,145 @@ __device__ __forceinline__ void conv_items(const LayerRegs& L, const ResParams& 
 }
 
 template <bool BF, int MT, int NT>
-__device__ __forceinline__ void conv_layer(const LayerRegs& L, const ResParams& p, char* act,
-                                           const int* tab, int n, int lane, int wave) {
-  if (L.flags & kResLast) conv_items<BF, MT, NT, true>(L, p, act, tab, n, lane, wave);
-  else conv_items<BF, MT, NT, false>(L, p, act, tab, n, lane, wave);
+__device__ __forceinline__ void conv_layer(const ResLayer& L, const ResParams& p, char* act,
+                                           int n, int lane, int wave) {
+  if (L.flags & kResLast) conv_items<BF, MT, NT, true>(L, p, act, n, lane, wave);
+  else conv_items<BF, MT, NT, false>(L, p, act, n, lane, wave);
 }
 
-// A layer's parameter blob: global memory -> registers (issued early) ...
-__device__ __forceinline__ void fetch_blob(const void* packed, int units, int tid,
-                                           uint4 (&wreg)[kResPrefetch]) {
-  const uint4* src = reinterpret_cast<const uint4*>(packed);
-#pragma unroll
-  for (int k = 0; k < kResPrefetch; ++k) {
-    const int idx = tid + k * kResThreads;
-    wreg[k] = idx < units ? src[idx] : uint4{0u, 0u, 0u, 0u};
+// Global mean over the M interior pixels of the input, per channel, in fp32:
+// L.MT partial sums over interleaved pixels, then their sum in order.
+template <bool BF>
+__device__ __forceinline__ void mean_layer(const ResLayer& L, const ResParams& p, char* lds,
+                                           char* act, int n, int tid) {
+  float* part = reinterpret_cast<float*>(lds);   // parts x cs_out floats of scratch
+  const int cs = L.cs_out, M = L.M, Q = L.Q, parts = L.MT;
+  if (tid < parts * cs) {
+    const int c = tid % cs, k = tid / cs;
+    float acc = 0.f;
+    for (int i = k; i < M; i += parts) {
+      const int pp = div_magic(i, L.magicQ), qq = i - pp * Q;
+      acc += to_float<BF>(*reinterpret_cast<const uint16_t*>(act + L.in_org + pp * L.in_row +
+                                                             qq * L.in_col + c * 2));
+    }
+    part[k * cs + c] = acc;
+  }
+  __syncthreads();
+  if (tid < cs) {
+    float acc = 0.f;
+    for (int k = 0; k < parts; ++k) acc += part[k * cs + tid];
+    const uint16_t o = from_float<BF>(acc / (float)M);
+    if (L.flags & kResLast) reinterpret_cast<uint16_t*>(p.y)[(size_t)n * p.y_cs + tid] = o;
+    else *reinterpret_cast<uint16_t*>(act + L.out_org + tid * 2) = o;
   }
 }
 
-// ... and registers -> LDS (after the current layer's compute).
-__device__ __forceinline__ void commit_blob(int w_off, int units, int tid, char* act,
-                                            const uint4 (&wreg)[kResPrefetch]) {
-  uint4* dst = reinterpret_cast<uint4*>(act + w_off * 16);
+// The layer table is read through the constant address space so that every
+// descriptor load is a scalar load (a uniform load from plain global memory
+// after the kernel's first store becomes a vector load whose wait would also
+// drain the parameter staging in flight).
+typedef const uint32_t __attribute__((address_space(4)))* ConstWords;
+typedef const void __attribute__((address_space(1)))* GlobalPtr;
+typedef void __attribute__((address_space(3)))* LdsPtr;
+
+// The first eight dwords of a ResLayer: all that staging needs.
+struct StageHead {
+  const void* packed;
+  const void* table;
+  int32_t blob_units, tab_units, w_off, tab_off;
+};
+static_assert(sizeof(StageHead) == 32, "StageHead mirrors the head of ResLayer");
+
+template <class T>
+__device__ __forceinline__ T load_words(ConstWords w) {
+  constexpr int kWords = sizeof(T) / 4;
+  struct Raw { uint32_t u[kWords]; } raw;
 #pragma unroll
-  for (int k = 0; k < kResPrefetch; ++k) {
-    const int idx = tid + k * kResThreads;
-    if (idx < units) dst[idx] = wreg[k];
-  }
+  for (int i = 0; i < kWords; ++i) raw.u[i] = w[i];
+  return __builtin_bit_cast(T, raw);
 }
+
+// A layer's parameter blob and tap table go from global memory straight into
+// LDS (16 bytes per lane, lane i of a wave to the i-th 16-byte slot after the
+// wave's base), issued before the current layer is computed and awaited after
+// it: no register is held and no global-memory latency sits on the layer chain.
+__device__ __forceinline__ void stage_params(const StageHead& H, char* act, int lane, int wave) {
+  const char* src = reinterpret_cast<const char*>(H.packed);
+  for (int u = wave * 64; u < H.blob_units; u += kResThreads) {
+    if (u + lane < H.blob_units)
+      __builtin_amdgcn_global_load_lds((GlobalPtr)(src + (size_t)(u + lane) * 16),
+                                       (LdsPtr)(act + H.w_off + u * 16), 16, 0, 0);
+  }
+  // the table (at most 64 slots) goes through the last wave, which has the
+  // smallest share of the blob
+  if (wave == kWaves - 1 && lane < H.tab_units)
+    __builtin_amdgcn_global_load_lds(
+        (GlobalPtr)(reinterpret_cast<const char*>(H.table) + lane * 16), (LdsPtr)(act + H.tab_off),
+        16, 0, 0);
+}
+
+__device__ __forceinline__ void staging_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 template <bool BF>
 __global__ __launch_bounds__(kResThreads) void resident_kernel(const ResParams p) {
   extern __shared__ uint4 lds4[];
   char* lds = reinterpret_cast<char*>(lds4);
-  int* tables = reinterpret_cast<int*>(lds);   // two tap tables of kResTableEntries
-  char* act = lds + 2 * kResTableEntries * sizeof(int);
+  char* act = lds + kResScratchBytes;
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = blockIdx.x;
-  const int hp = __builtin_amdgcn_readfirstlane(p.hp);
+  ConstWords table = (ConstWords)(uintptr_t)p.layers;
+  constexpr int kLayerWords = sizeof(ResLayer) / 4;
 
-  // parameters of the layer after the current one travel through these registers
-  uint4 wreg[kResPrefetch];
-  LayerRegs L = unpack(p.layers[0]);
-  fetch_blob(L.packed, L.blob_units, tid, wreg);
   {
+    const StageHead H = load_words<StageHead>(table);
+    stage_params(H, act, lane, wave);
     // stage the image into the interior of its LDS tensor, zero its halo
     const int cpp = p.in_cs >> 3;
     const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(p.x) +
                                                       (size_t)n * p.in_H * p.in_W * p.in_cs);
-    const int org = p.in_org * 16, ps2 = p.in_ps * 2;
     const int total = p.in_H * p.in_W * cpp;
     for (int i = tid; i < total; i += kResThreads) {
       const int pix = i / cpp, ch = i - pix * cpp;
       const int row = pix / p.in_W, col = pix - row * p.in_W;
-      *reinterpret_cast<uint4*>(act + org + (row * p.in_Wh + col) * ps2 + ch * 16) = src[i];
+      *reinterpret_cast<uint4*>(act + p.in_org + (row * p.in_Wh + col) * p.in_ps2 + ch * 16) = src[i];
     }
-    if (hp > 0 && p.in_H * p.in_W > 1) zero_halo(act, org, p.in_H, p.in_W, p.in_Wh, ps2, cpp, hp, tid);
+    if (p.hp > 0 && p.in_H * p.in_W > 1)
+      zero_halo(act, p.in_org, p.in_H, p.in_W, p.in_Wh, p.in_ps2, cpp, p.hp, tid);
   }
-  commit_blob(L.w_off, L.blob_units, tid, act, wreg);
+  ResLayer L = load_words<ResLayer>(table);
+  staging_done();
+  __syncthreads();
 
-  const int n_layers = __builtin_amdgcn_readfirstlane(p.n_layers);
+  const int n_layers = p.n_layers;
   for (int l = 0; l < n_layers; ++l) {
     const bool has_next = l + 1 < n_layers;
-    LayerRegs Ln = L;
     if (has_next) {
-      Ln = unpack(p.layers[l + 1]);
-      fetch_blob(Ln.packed, Ln.blob_units, tid, wreg);
+      const StageHead Hn = load_words<StageHead>(table + (l + 1) * kLayerWords);
+      stage_params(Hn, act, lane, wave);
     }
 
-    int* tab = tables + (l & 1) * kResTableEntries;
-    if (!(L.flags & kResMean)) {
-      const int Wh = L.Wh_in, ps = L.ps_in, cpt = L.cpt, S = L.S;
-      const int nentries = L.nsteps * 4, nchunk = L.nchunk;
-      for (int j = tid; j < nentries; j += kResThreads) {
-        int e = 0;   // padding chunks (zero weights) re-read the first chunk: finite data
-        if (j < nchunk) {
-          const int tap = j / cpt, c8 = j - tap * cpt;
-          const int r = tap / S, s = tap - r * S;
-          e = ((r * Wh + s) * ps + c8 * 8) * 2;   // byte offset from the window's first pixel
-        }
-        tab[j] = e;
-      }
-    }
-    __syncthreads();   // previous layer's output, this layer's parameters and table are visible
-
+    if (L.flags & kResZeroHalo)
+      zero_halo(act, L.hz_org, L.hz_P, L.hz_Q, L.hz_Wh, L.hz_ps2, L.hz_chunks, L.hz_hp, tid);
     if (L.flags & kResMean) {
-      // global mean over the P x Q interior, sequential fp32 sum per channel
-      const int Pm = L.P, Qm = L.Q, ps = L.ps_in, Wh = L.Wh_in;
-      const uint16_t* in = reinterpret_cast<const uint16_t*>(act + L.in_org * 16);
-      for (int c = tid; c < L.cs_out; c += kResThreads) {
-        float acc = 0.f;
-        for (int i = 0; i < Pm; ++i)
-          for (int j = 0; j < Qm; ++j) acc += to_float<BF>(in[(i * Wh + j) * ps + c]);
-        const uint16_t o = from_float<BF>(acc / (float)(Pm * Qm));
-        if (L.flags & kResLast) reinterpret_cast<uint16_t*>(p.y)[(size_t)n * p.y_cs + c] = o;
-        else reinterpret_cast<uint16_t*>(act + L.out_org * 16)[c] = o;
-      }
+      mean_layer<BF>(L, p, lds, act, n, tid);
     } else {
-      if (L.out_halo > 0 && !(L.flags & kResLast))
-        zero_halo(act, L.out_org * 16, L.P, L.Q, L.Wh_out, L.ps_out * 2, L.cs_out >> 3, L.out_halo,
-                  tid);
       switch (L.MT * 8 + L.NT) {
-        case 1 * 8 + 1: conv_layer<BF, 1, 1>(L, p, act, tab, n, lane, wave); break;
-        case 1 * 8 + 2: conv_layer<BF, 1, 2>(L, p, act, tab, n, lane, wave); break;
-        case 1 * 8 + 3: conv_layer<BF, 1, 3>(L, p, act, tab, n, lane, wave); break;
-        case 1 * 8 + 4: conv_layer<BF, 1, 4>(L, p, act, tab, n, lane, wave); break;
-        case 2 * 8 + 1: conv_layer<BF, 2, 1>(L, p, act, tab, n, lane, wave); break;
-        case 2 * 8 + 2: conv_layer<BF, 2, 2>(L, p, act, tab, n, lane, wave); break;
-        case 3 * 8 + 1: conv_layer<BF, 3, 1>(L, p, act, tab, n, lane, wave); break;
-        default: conv_layer<BF, 4, 1>(L, p, act, tab, n, lane, wave); break;
+        case 1 * 8 + 1: conv_layer<BF, 1, 1>(L, p, act, n, lane, wave); break;
+        case 1 * 8 + 2: conv_layer<BF, 1, 2>(L, p, act, n, lane, wave); break;
+        case 1 * 8 + 3: conv_layer<BF, 1, 3>(L, p, act, n, lane, wave); break;
+        case 1 * 8 + 4: conv_layer<BF, 1, 4>(L, p, act, n, lane, wave); break;
+        case 2 * 8 + 1: conv_layer<BF, 2, 1>(L, p, act, n, lane, wave); break;
+        case 2 * 8 + 2: conv_layer<BF, 2, 2>(L, p, act, n, lane, wave); break;
+        case 3 * 8 + 1: conv_layer<BF, 3, 1>(L, p, act, n, lane, wave); break;
+        default: conv_layer<BF, 4, 1>(L, p, act, n, lane, wave); break;
       }
     }
-    if (has_next) commit_blob(Ln.w_off, Ln.blob_units, tid, act, wreg);
-    L = Ln;
+    if (has_next) L = load_words<ResLayer>(table + (l + 1) * kLayerWords);   // in flight across the barrier
+    staging_done();
+    __syncthreads();   // this layer's output and the next layer's parameters are visible
   }
 }
 

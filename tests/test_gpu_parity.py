@@ -313,9 +313,10 @@ def resident_models():
 
 @pytest.mark.parametrize("mi", range(4))
 def test_one_kernel_schedule_equals_per_layer_schedule(fx, mi):
-    """The LDS-resident one-kernel schedule and the per-layer schedule do the
-    same arithmetic in the same order: outputs are bit-identical, and both
-    match the oracle."""
+    """The LDS-resident one-kernel schedule and the per-layer schedule compute
+    the same network (the one-kernel schedule adds bias and shortcut inside the
+    MFMA accumulation, so roundings differ): the two agree within half the
+    tolerance, and both match the oracle."""
     B, network, torch = fx
     model = resident_models()[mi]
     n = 5
@@ -334,7 +335,8 @@ def test_one_kernel_schedule_equals_per_layer_schedule(fx, mi):
     out_b, ws_b = m.alloc(n)
     m.fupr_forward(xd, out_b, ws_b)
     torch.cuda.synchronize()
-    assert torch.equal(out_a.data, out_b.data)
+    between = rel_err(out_a.to_nchw(), out_b.to_nchw())
+    assert between <= TOL[model["dtype"]] / 2, between
     assert out_a.padding_is_zero()
     masks = orc.select_masks(model)
     ref = orc.forward(model, round_to(x, model["dtype"], torch), masks=masks)
