@@ -132,21 +132,27 @@ size_t assign_offsets(std::vector<LdsBlock>& blocks) {
   return extent;
 }
 
-// LDS pixel stride in bytes for a tensor of cs 16-bit lanes.  The 16 pixels x 4
+// LDS pixel stride in bytes for tensors of cs 16-bit lanes.  The 16 pixels x 4
 // chunks of one MFMA pixel fragment are read with one 16-byte access per lane;
-// measured on gfx950 that access runs at full rate when the pixel stride is an
-// odd multiple of 32 bytes (an odd multiple of 16 when the reading convolution
-// has stride 2, which doubles the lane-to-lane distance), and at half rate or
-// worse otherwise.  mode 0: the nearest such stride; 1: channel stride + 16
-// bytes; 2: dense.
-int lds_pixel_stride(int cs, bool strided_reader, int mode) {
+// measured on gfx950 that access takes about 5 clocks of the LDS port when the
+// pixel stride is an odd multiple of 32 bytes, 8.6 at other multiples of 16
+// that are not multiples of 64, 8.7 at odd multiples of 64 and 16.7 at
+// multiples of 128.  mode 0: the nearest odd multiple of 32; 1: the nearest
+// stride that is not a multiple of 64; 2: dense.
+int lds_pixel_stride(int cs, int mode) {
   const int dense = cs * 2;
   if (mode == 2) return dense;
-  if (mode == 1) return dense + 16;
-  if (strided_reader) return dense % 32 == 16 ? dense : dense + 16;
+  if (mode == 1) return dense % 64 == 0 ? dense + 16 : dense;
   int ps2 = dense;
   while (ps2 % 64 != 32) ps2 += 16;
   return ps2;
+}
+
+double lds_read_clocks(int ps2) {
+  if (ps2 % 64 == 32) return 5.1;
+  if (ps2 % 128 == 0) return 16.7;
+  if (ps2 % 64 == 0) return 8.7;
+  return 8.6;
 }
 
 // floor(v / d) = mulhi(v, reciprocal) for v < 2^16; 0 stands for d = 1
@@ -173,23 +179,52 @@ void plan_resident(fupr_model* m) {
   auto halo_of = [&](const TensorInfo& t) { return t.H * t.W > 1 ? hp : 0; };
   auto row_of = [&](const TensorInfo& t) { return t.W + 2 * halo_of(t); };
 
-  // which tensors are only ever the main input of stride-2 convolutions
-  std::vector<int> readers(n + 1, 0), strided(n + 1, 0);
-  for (const fupr_op_desc& op : m->ops)
-    if (op.kind == FUPR_OP_CONV) {
-      ++readers[op.in];
-      if (op.conv.stride == 2) ++strided[op.in];
-    }
-
   const size_t budget_units = (kResLdsLimit - kResScratchBytes) / 16;
 
-  for (int mode = 0; mode <= 2; ++mode) {
+  // Tensors of one resolution share one pixel stride (that of the widest), so
+  // that a tensor lands on the bytes of a dead tensor of the same geometry and
+  // finds its halo still zero.  Per resolution the stride is the cheapest to
+  // read that still lets the whole plan fit.
+  struct Res { int H, W, cs, readers; };
+  std::vector<Res> classes;
+  std::vector<int> class_of(n + 1, -1);
+  for (int tid = 0; tid <= n; ++tid) {
+    const TensorInfo& t = m->tensors[tid];
+    if (t.H * t.W <= 1 || tid == n) continue;
+    size_t c = 0;
+    while (c < classes.size() && !(classes[c].H == t.H && classes[c].W == t.W)) ++c;
+    if (c == classes.size()) classes.push_back(Res{t.H, t.W, 0, 0});
+    classes[c].cs = std::max(classes[c].cs, t.cs);
+    class_of[tid] = (int)c;
+  }
+  for (const fupr_op_desc& op : m->ops)
+    if (op.kind == FUPR_OP_CONV && class_of[op.in] >= 0) ++classes[class_of[op.in]].readers;
+  const int k = (int)classes.size();
+  std::vector<std::pair<double, std::vector<int>>> candidates;
+  if (k <= 5) {
+    int combos = 1;
+    for (int c = 0; c < k; ++c) combos *= 3;
+    for (int code = 0; code < combos; ++code) {
+      std::vector<int> modes(k);
+      double cost = 0.0;
+      for (int c = 0, rest = code; c < k; ++c, rest /= 3) {
+        modes[c] = rest % 3;
+        const int ps2 = lds_pixel_stride(classes[c].cs, modes[c]);
+        cost += classes[c].readers * lds_read_clocks(ps2) + 1e-6 * ps2;   // ties: the smaller stride
+      }
+      candidates.emplace_back(cost, modes);
+    }
+  } else {
+    for (int mode = 0; mode < 3; ++mode) candidates.emplace_back((double)mode, std::vector<int>(k, mode));
+  }
+  std::stable_sort(candidates.begin(), candidates.end(),
+                   [](const auto& a, const auto& b) { return a.first < b.first; });
+
+  for (const auto& cand : candidates) {
     std::vector<int> ps2(n + 1);
     for (int tid = 0; tid <= n; ++tid) {
-      const TensorInfo& t = m->tensors[tid];
-      ps2[tid] = t.H * t.W > 1
-                     ? lds_pixel_stride(t.cs, readers[tid] > 0 && strided[tid] == readers[tid], mode)
-                     : t.cs * 2;
+      const int c = class_of[tid];
+      ps2[tid] = c >= 0 ? lds_pixel_stride(classes[c].cs, cand.second[c]) : m->tensors[tid].cs * 2;
     }
     std::vector<LdsBlock> blocks(2 * (size_t)n + 1);
     for (int tid = 0; tid <= n; ++tid) {
@@ -202,7 +237,7 @@ void plan_resident(fupr_model* m) {
     bool ok = true;
     for (int i = 0; i < n && ok; ++i) {
       LdsBlock& b = blocks[n + 1 + i];
-      b.first = i - 1;                         // written while layer i-1 is still running
+      b.first = i - 1;                         // lands while layer i-1 is running
       b.last = i;
       b.units = 0;
       if (m->ops[i].kind == FUPR_OP_CONV) {
@@ -361,7 +396,7 @@ void plan_resident(fupr_model* m) {
                      ps2[i + 1], (L.flags & kResZeroHalo) != 0, L.res_org >= 0);
     }
     if (std::getenv("FUPR_DEBUG"))
-      std::fprintf(stderr, "resident plan: stride mode %d, %d bytes of LDS\n", mode, R.lds_bytes);
+      std::fprintf(stderr, "resident plan: %d bytes of LDS\n", R.lds_bytes);
     m->resident_ok = true;
     return;
   }

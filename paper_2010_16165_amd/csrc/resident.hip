@@ -18,10 +18,10 @@
 // fragment feeds several MFMAs.
 //
 // The instruction stream around the MFMAs is what bounds a network this small,
-// so it is kept short: the bias enters as the accumulator input of the first
-// MFMA, and the shortcut is added by one more MFMA step whose filter operand
-// is a one-hot (identity) fragment built in registers — the epilogue is ReLU,
-// one rounding and one LDS store.
+// so it is kept short: the accumulator starts from the bias, and the shortcut is
+// added by one more MFMA step whose filter operand is a one-hot (identity)
+// fragment built in registers — the epilogue is ReLU, one rounding and one LDS
+// store.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -105,7 +105,25 @@ __device__ __forceinline__ void conv_items(const ResLayer& L, const ResParams& p
   for (int item = wave; item < n_items; item += kWaves) {
     const int pg = div_magic(item, L.magicF);
     const int ft0 = (item - pg * n_fgroups) * NT;
-    int m[MT], bptr[MT], ooff[MT], roff[MT];
+    // filter tiles past the last one repeat it (computed, not stored)
+    int ft[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) ft[t] = min(ft0 + t, FT - 1);
+
+    // table entries of the first steps and the bias are requested first: their
+    // latency passes while the pixel addresses are worked out
+    int e0[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) e0[d] = tabg[min(d, nsteps - 1) * 4];
+    int e_pre = tabg[min(D, nsteps - 1) * 4];
+    int ls = D;   // the step whose table entry is e_pre
+    f32x4 b4[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+      b4[t] = *reinterpret_cast<const f32x4*>(bias + ft[t] * 16 + g * 4);
+
+    int m[MT], bptr[MT], ooff[MT];
+    uint4 rb[MT][NT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       m[mt] = (pg * MT + mt) * 16 + li;
@@ -113,12 +131,15 @@ __device__ __forceinline__ void conv_items(const ResLayer& L, const ResParams& p
       const int pp = div_magic(mc, L.magicQ), qq = mc - pp * Q;
       bptr[mt] = L.in_org + pp * L.in_row + qq * L.in_col;
       ooff[mt] = L.out_org + pp * L.out_row + qq * L.out_col;
-      roff[mt] = L.res_org + pp * L.res_row + qq * L.res_col;
-    }
-    // filter tiles past the last one repeat it (computed, not stored)
-    int ft[NT];
+      if (has_res) {
+        const int roff = L.res_org + pp * L.res_row + qq * L.res_col;
 #pragma unroll
-    for (int t = 0; t < NT; ++t) ft[t] = min(ft0 + t, FT - 1);
+        for (int t = 0; t < NT; ++t) {
+          const int chunk = min(ft[t] * 2 + (g & 1), (L.res_cs >> 3) - 1);
+          rb[mt][t] = *reinterpret_cast<const uint4*>(act + roff + chunk * 16);
+        }
+      }
+    }
     int aptr = a_lane;
 
     uint4 a[D][NT], b[D][MT];
@@ -129,36 +150,28 @@ __device__ __forceinline__ void conv_items(const ResLayer& L, const ResParams& p
       for (int t = 0; t < NT; ++t) av[t] = *reinterpret_cast<const uint4*>(act + aptr + ft[t] * 256);
       aptr += wstep;
     };
-
-    int e0[D];
-#pragma unroll
-    for (int d = 0; d < D; ++d) e0[d] = tabg[min(d, nsteps - 1) * 4];
-    int e_pre = tabg[min(D, nsteps - 1) * 4];
-    int ls = D;   // next step whose table entry is e_pre
 #pragma unroll
     for (int d = 0; d < D; ++d)
       if (d < nsteps) operands(e0[d], a[d], b[d]);
 
-    // the bias is the accumulator input of the first step
-    f32x4 b4[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t)
-      b4[t] = *reinterpret_cast<const f32x4*>(bias + ft[t] * 16 + g * 4);
+    // The accumulator starts from the bias.  The shortcut goes in first: one
+    // MFMA step whose filter fragment is one-hot.
     f32x4 acc[MT][NT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int t = 0; t < NT; ++t) {
+      if (has_res && ft[t] * 16 < L.res_cs) {
+        const uint4 ia = identity_fragment<BF>(ft[t], L.res_cs, li, g);
 #pragma unroll
-      for (int t = 0; t < NT; ++t) acc[mt][t] = mfma_16x16x32<BF>(a[0][t], b[0][mt], b4[t]);
-    if (D < nsteps) {
-      const int e = e_pre;
-      e_pre = tabg[min(D + 1, nsteps - 1) * 4];
-      ls = D + 1;
-      operands(e, a[0], b[0]);
+        for (int mt = 0; mt < MT; ++mt) acc[mt][t] = mfma_16x16x32<BF>(ia, rb[mt][t], b4[t]);
+      } else {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[mt][t] = b4[t];
+      }
     }
+
     for (int step0 = 0; step0 < nsteps; step0 += D) {
 #pragma unroll
       for (int d = 0; d < D; ++d) {
-        if (step0 + d == 0) continue;   // peeled above
         if (step0 + d < nsteps) {
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt)
@@ -174,25 +187,6 @@ __device__ __forceinline__ void conv_items(const ResLayer& L, const ResParams& p
         }
       }
     }
-    if (has_res) {
-      // the shortcut: one more step whose filter fragment is one-hot
-      uint4 rb[MT][NT];
-#pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        const int chunk = min(ft[t] * 2 + (g & 1), (L.res_cs >> 3) - 1);
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          rb[mt][t] = *reinterpret_cast<const uint4*>(act + roff[mt] + chunk * 16);
-      }
-#pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        if (ft[t] * 16 < L.res_cs) {
-          const uint4 ia = identity_fragment<BF>(ft[t], L.res_cs, li, g);
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt) acc[mt][t] = mfma_16x16x32<BF>(ia, rb[mt][t], acc[mt][t]);
-        }
-      }
-    }
 
     // epilogue: ReLU, one rounding, store
 #pragma unroll
@@ -203,8 +197,9 @@ __device__ __forceinline__ void conv_items(const ResLayer& L, const ResParams& p
         if (m[mt] >= M || ft0 + t >= FT || k0 >= ycs) continue;
         float v[4] = {acc[mt][t][0], acc[mt][t][1], acc[mt][t][2], acc[mt][t][3]};
         if (relu) {
+          // max(x, 0) on the bit pattern: negative floats are negative integers
 #pragma unroll
-          for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i], 0.f);
+          for (int i = 0; i < 4; ++i) v[i] = __int_as_float(max(__float_as_int(v[i]), 0));
         }
         uint2 o;
         o.x = pack2<BF>(v[0], v[1]);
