@@ -70,7 +70,6 @@ const char* conv_kernel_name(const fupr_conv_shape& s, fupr_dtype dt, int64_t M)
 // One workgroup per image walks a table of layers; see resident.hip.
 
 constexpr int kResMaxLayers = 256;
-constexpr int kResTableEntries = 256;             // chunks per layer the tap table can hold
 constexpr int kResThreads = 1024;
 constexpr size_t kResLdsLimit = 160 * 1024;
 constexpr int kResScratchBytes = 2048;            // start of LDS: partial sums of the mean layer
@@ -81,13 +80,14 @@ constexpr int kResScratchBytes = 2048;            // start of LDS: partial sums 
 // reciprocal multipliers for the two divisions, the work-item count.
 //
 // Tensors in LDS carry a halo of zero pixels.  in_org is the LDS byte offset of
-// the pixel that tap (0, 0) of output pixel (0, 0) reads; out_org and res_org
+// the pixel that tap (0, 0) of output pixel (0, 0) reads (the tap table's entries
+// include it); out_org and res_org
 // are the offsets of interior pixel (0, 0).  For the global-mean layer M is the
 // INPUT pixel count, Q its width, in_org its interior origin, in_row / in_col
 // its byte strides.
 struct ResLayer {
   const void* packed;        // conv: blob (bias + weights) in global memory
-  const void* table;         // conv: tap table in global memory, nsteps * 4 byte offsets
+  const void* table;         // conv: tap table in global memory, (nsteps + kResTablePad) * 4 LDS byte offsets
   int32_t blob_units;        // 16-byte units staged to w_off
   int32_t tab_units;         // 16-byte units staged to tab_off
   int32_t w_off, tab_off;    // LDS byte offsets of the blob and of the table
@@ -109,6 +109,13 @@ struct ResLayer {
 };
 static_assert(sizeof(ResLayer) == 160, "ResLayer is read as 40 dwords");
 constexpr int kResMean = 1, kResRelu = 2, kResLast = 4, kResZeroHalo = 8;
+// kResFull: every tile of every work item is whole (no clamped pixel, no partial
+// filter group, all 16 lanes of every filter tile stored).  kResReuse: a wave's
+// first work item covers the same pixels at the same strides as in the previous
+// conv layer, every tile is whole, and the output's strides are the input's.
+// kResLikeOut: the shortcut tensor has the output's strides.
+constexpr int kResFull = 16, kResReuse = 32, kResLikeOut = 64;
+constexpr int kResTablePad = 8;   // steps of padding after a tap table (2 * deepest prefetch)
 
 struct ResParams {
   const void* x;             // N images, NHWC

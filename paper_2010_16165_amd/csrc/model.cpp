@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <array>
 #include <cstdio>
 #include <cstdlib>
 #include <mutex>
@@ -58,7 +59,7 @@ namespace {
 // FUPR_RES_ITEM="M/FT/nsteps:MTxNT,..." overrides the choice per layer class
 // (a tuning aid).
 void resident_item_shape(int M, int FT, int nsteps, bool has_res, int* MT_out, int* NT_out) {
-  static const int shapes[8][2] = {{4, 1}, {2, 2}, {1, 4}, {3, 1}, {1, 3}, {2, 1}, {1, 2}, {1, 1}};
+  static const int shapes[5][2] = {{4, 1}, {2, 2}, {2, 1}, {1, 2}, {1, 1}};
   if (const char* env = std::getenv("FUPR_RES_ITEM")) {
     const char* c = env;
     while (*c) {
@@ -242,8 +243,8 @@ void plan_resident(fupr_model* m) {
       b.units = 0;
       if (m->ops[i].kind == FUPR_OP_CONV) {
         const PackedLayout PL = packed_layout(m->ops[i].conv, m->dt);
-        if (PL.nchunk_pad > kResTableEntries) ok = false;
-        b.units = PL.nchunk_pad / 4 + PL.total_bytes / 16;   // table (16 bytes per step), blob
+        if (PL.nchunk_pad / 4 + kResTablePad > 64) ok = false;   // one wave stages the table
+        b.units = PL.nchunk_pad / 4 + kResTablePad + PL.total_bytes / 16;   // table (16 bytes per step), blob
       }
     }
     if (!ok) return;
@@ -295,6 +296,8 @@ void plan_resident(fupr_model* m) {
     halo_units(0, [&](size_t u) { clean[u] = 1; });
     if (blocks[n + 1].units) mark(blocks[n + 1].offset, blocks[n + 1].units, 0);
 
+    std::array<int, 8> prev_geometry;
+    prev_geometry.fill(-1);
     m->res_layers.assign(n, ResLayer{});
     m->res_tables.clear();
     m->res_table_at.assign(n, 0);
@@ -328,9 +331,9 @@ void plan_resident(fupr_model* m) {
         const int nsteps = PL.nchunk_pad / 4, cpt = PL.Cp / 8;
         L.packed = op.packed;
         L.blob_units = (int32_t)(PL.total_bytes / 16);
-        L.tab_units = nsteps;
+        L.tab_units = nsteps + kResTablePad;
         L.tab_off = (int32_t)(blocks[n + 1 + i].offset * 16);
-        L.w_off = L.tab_off + nsteps * 16;
+        L.w_off = L.tab_off + L.tab_units * 16;
         L.wts_off = L.w_off + (int32_t)PL.weight_offset;
         L.wstep = 4 * PL.Kp * 16;
         L.in_org = pixel_at(op.in, halo_of(ti) - s.pad, halo_of(ti) - s.pad);
@@ -356,17 +359,29 @@ void plan_resident(fupr_model* m) {
         L.n_fgroups = (L.FT + nt - 1) / nt;
         L.n_items = ((L.M + 15) / 16 + mt - 1) / mt * L.n_fgroups;
         if (L.n_items >= 65536) return;
-        // tap table: byte offset of every chunk from the window's first pixel;
-        // padding chunks (zero weights) re-read the first chunk: finite data
+        if (L.M % (16 * mt) == 0 && L.FT % nt == 0 && to.cs == PL.Kp && !last) L.flags |= kResFull;
+        if (op.res >= 0 && L.res_row == L.out_row && L.res_col == L.out_col) L.flags |= kResLikeOut;
+        const std::array<int, 8> geometry = {L.M, L.Q, mt, L.n_fgroups, L.in_row, L.in_col, L.out_row, L.out_col};
+        if (L.n_items <= kResThreads / 64) {
+          if (geometry == prev_geometry && (L.flags & kResFull) && L.in_row == L.out_row &&
+              L.in_col == L.out_col)
+            L.flags |= kResReuse;
+          prev_geometry = geometry;
+        } else {
+          prev_geometry.fill(-1);   // later work items overwrite what the first one left
+        }
+        // tap table: LDS byte offset of every chunk of output pixel (0, 0)'s
+        // window; padding chunks (zero weights) and the padding steps after the
+        // last one re-read the first chunk: finite data
         m->res_table_at[i] = m->res_tables.size();
-        for (int j = 0; j < nsteps * 4; ++j) {
+        for (int j = 0; j < L.tab_units * 4; ++j) {
           int32_t e = 0;
           if (j < PL.nchunk) {
             const int tap = j / cpt, c8 = j - tap * cpt;
             const int r = tap / s.S, sx = tap - r * s.S;
             e = (r * row_of(ti) + sx) * ps2[op.in] + c8 * 16;
           }
-          m->res_tables.push_back(e);
+          m->res_tables.push_back(L.in_org + e);
         }
       }
       L.magicQ = reciprocal_u16(L.Q);

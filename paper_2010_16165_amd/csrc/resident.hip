@@ -80,26 +80,48 @@ __device__ __forceinline__ uint4 identity_fragment(int ft, int res_cs, int li, i
   return uint4{j == 0 ? v : 0u, j == 1 ? v : 0u, j == 2 ? v : 0u, j == 3 ? v : 0u};
 }
 
+// Pixel addressing of a wave's first work item, kept from one layer to the next:
+// consecutive layers of one resolution give a wave the same pixels at the same
+// strides, so the divisions and multiplications behind these offsets are done
+// once per resolution rather than once per layer.
+struct PixelCache {
+  int rin[4];    // byte offset of the pixel's window from the window of pixel 0, per pixel tile
+};
+
+typedef short short2_t __attribute__((ext_vector_type(2)));
+
+// max(x, floor) on two packed 16-bit floats, as signed 16-bit integers: with
+// floor = 0 this is ReLU (negative floats are negative integers), with floor =
+// the most negative integer it is the identity.
+__device__ __forceinline__ uint32_t clamp_below(uint32_t v, uint32_t floor2) {
+  const short2_t a = __builtin_bit_cast(short2_t, v), f = __builtin_bit_cast(short2_t, floor2);
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(a, f));
+}
+
 // All work items of one conv layer that fall to this wave.  LAST: the layer
 // writes the network output to global memory instead of LDS.
 //
 // Every activation tensor in LDS carries a ring of zero pixels as wide as the
 // largest padding of any convolution, so a tap never needs a bounds check: the
-// K loop is one table read, MT + 1 address additions, MT + NT LDS reads and
-// MT * NT MFMAs per step.  D steps of operands are kept in flight (ring of
-// register buffers, loop unrolled by D).
+// K loop is MT + 1 address additions, MT + NT LDS reads and MT * NT MFMAs per
+// step, plus one table read per step issued a whole group of steps ahead.  D
+// steps of operands are kept in flight (ring of register buffers, loop
+// unrolled by D).
 template <bool BF, int MT, int NT, bool LAST>
 __device__ __forceinline__ void conv_items(const ResLayer& L, const ResParams& p, char* act,
-                                           int n, int lane, int wave) {
+                                           int n, int lane, int wave, PixelCache& pc) {
   constexpr int D = (MT + NT <= 3) ? 4 : (MT + NT == 4 ? 3 : 2);
   const int li = lane & 15, g = lane >> 4;
   const int nsteps = L.nsteps, FT = L.FT, M = L.M, Q = L.Q;
-  const bool relu = (L.flags & kResRelu) != 0, has_res = L.res_org >= 0;
+  const bool has_res = L.res_org >= 0;
+  const bool full = (L.flags & kResFull) != 0;       // every tile of every item is whole
+  const bool reuse = (L.flags & kResReuse) != 0;     // pc holds this layer's first item
+  const uint32_t floor2 = (L.flags & kResRelu) ? 0u : 0x80008000u;
   const int ycs = LAST ? p.y_cs : L.cs_out;
   const int wstep = L.wstep;
   const int a_lane = L.wts_off + g * (wstep >> 2) + li * 16;
   const float* bias = reinterpret_cast<const float*>(act + L.w_off);
-  const int* tabg = reinterpret_cast<const int*>(act + L.tab_off) + g;
+  const int tab_lane = L.tab_off + g * 4;
   const int n_items = L.n_items, n_fgroups = L.n_fgroups;
 
   for (int item = wave; item < n_items; item += kWaves) {
@@ -110,44 +132,74 @@ __device__ __forceinline__ void conv_items(const ResLayer& L, const ResParams& p
 #pragma unroll
     for (int t = 0; t < NT; ++t) ft[t] = min(ft0 + t, FT - 1);
 
-    // table entries of the first steps and the bias are requested first: their
-    // latency passes while the pixel addresses are worked out
-    int e0[D];
+    // Table entries of the first two groups of steps and the bias are requested
+    // first: their latency passes while the addresses are worked out.  (The
+    // table is padded by 2 * D steps, so no index needs clamping.)
+    int e0[D], e_cur[D];   // entries of steps 0 .. D-1 and D .. 2D-1
 #pragma unroll
-    for (int d = 0; d < D; ++d) e0[d] = tabg[min(d, nsteps - 1) * 4];
-    int e_pre = tabg[min(D, nsteps - 1) * 4];
-    int ls = D;   // the step whose table entry is e_pre
+    for (int d = 0; d < D; ++d) e0[d] = *reinterpret_cast<const int*>(act + tab_lane + d * 16);
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+      e_cur[d] = *reinterpret_cast<const int*>(act + tab_lane + (D + d) * 16);
+    int tptr = tab_lane + 2 * D * 16;
     f32x4 b4[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t)
       b4[t] = *reinterpret_cast<const f32x4*>(bias + ft[t] * 16 + g * 4);
 
-    int m[MT], bptr[MT], ooff[MT];
-    uint4 rb[MT][NT];
+    int m[MT], rin[MT], rout[MT];
+    if (reuse && item == wave) {
+      // same pixels, same strides as in the previous layer; output strides = input strides
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      m[mt] = (pg * MT + mt) * 16 + li;
-      const int mc = min(m[mt], M - 1);
-      const int pp = div_magic(mc, L.magicQ), qq = mc - pp * Q;
-      bptr[mt] = L.in_org + pp * L.in_row + qq * L.in_col;
-      ooff[mt] = L.out_org + pp * L.out_row + qq * L.out_col;
-      if (has_res) {
-        const int roff = L.res_org + pp * L.res_row + qq * L.res_col;
+      for (int mt = 0; mt < MT; ++mt) {
+        m[mt] = 0;   // not looked at: every tile is whole
+        rin[mt] = pc.rin[mt];
+        rout[mt] = rin[mt] + g * 8;
+      }
+    } else {
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-          const int chunk = min(ft[t] * 2 + (g & 1), (L.res_cs >> 3) - 1);
-          rb[mt][t] = *reinterpret_cast<const uint4*>(act + roff + chunk * 16);
-        }
+      for (int mt = 0; mt < MT; ++mt) {
+        m[mt] = (pg * MT + mt) * 16 + li;
+        const int mc = min(m[mt], M - 1);
+        const int pp = div_magic(mc, L.magicQ), qq = mc - pp * Q;
+        rin[mt] = pp * L.in_row + qq * L.in_col;
+        rout[mt] = pp * L.out_row + qq * L.out_col + g * 8;
+        pc.rin[mt] = rin[mt];
       }
     }
-    int aptr = a_lane;
 
+    // shortcut operands: 16 bytes of the shortcut pixel per lane
+    uint4 rb[MT][NT];
+    if (has_res) {
+      int cres[NT];
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+        cres[t] = L.res_org + min(ft[t] * 2 + (g & 1), (L.res_cs >> 3) - 1) * 16;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        int rres;
+        if (L.flags & kResLikeOut) {
+          rres = rout[mt] - g * 8;
+        } else {
+          const int mc = min(m[mt], M - 1);
+          const int pp = div_magic(mc, L.magicQ), qq = mc - pp * Q;
+          rres = pp * L.res_row + qq * L.res_col;
+        }
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+          rb[mt][t] = *reinterpret_cast<const uint4*>(act + rres + cres[t]);
+      }
+    }
+
+    int aptr = a_lane + ft0 * 256;
     uint4 a[D][NT], b[D][MT];
     auto operands = [&](const int e, uint4* av, uint4* bv) {
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) bv[mt] = *reinterpret_cast<const uint4*>(act + bptr[mt] + e);
+      for (int mt = 0; mt < MT; ++mt)
+        bv[mt] = *reinterpret_cast<const uint4*>(act + rin[mt] + e);   // e includes the origin
 #pragma unroll
-      for (int t = 0; t < NT; ++t) av[t] = *reinterpret_cast<const uint4*>(act + aptr + ft[t] * 256);
+      for (int t = 0; t < NT; ++t)
+        av[t] = *reinterpret_cast<const uint4*>(act + aptr + (ft[t] - ft0) * 256);
       aptr += wstep;
     };
 #pragma unroll
@@ -170,6 +222,11 @@ __device__ __forceinline__ void conv_items(const ResLayer& L, const ResParams& p
     }
 
     for (int step0 = 0; step0 < nsteps; step0 += D) {
+      // the table entries a step needs are read a whole group ahead of it
+      int e_nxt[D];
+#pragma unroll
+      for (int d = 0; d < D; ++d) e_nxt[d] = *reinterpret_cast<const int*>(act + tptr + d * 16);
+      tptr += D * 16;
 #pragma unroll
       for (int d = 0; d < D; ++d) {
         if (step0 + d < nsteps) {
@@ -178,38 +235,29 @@ __device__ __forceinline__ void conv_items(const ResLayer& L, const ResParams& p
 #pragma unroll
             for (int t = 0; t < NT; ++t)
               acc[mt][t] = mfma_16x16x32<BF>(a[d][t], b[d][mt], acc[mt][t]);
-          if (step0 + d + D < nsteps) {
-            const int e = e_pre;
-            ++ls;
-            e_pre = tabg[min(ls, nsteps - 1) * 4];
-            operands(e, a[d], b[d]);
-          }
+          if (step0 + d + D < nsteps) operands(e_cur[d], a[d], b[d]);
         }
       }
+#pragma unroll
+      for (int d = 0; d < D; ++d) e_cur[d] = e_nxt[d];
     }
 
-    // epilogue: ReLU, one rounding, store
+    // epilogue: one rounding, ReLU on the rounded pair, store
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
-        const int k0 = (ft0 + t) * 16 + g * 4;
-        if (m[mt] >= M || ft0 + t >= FT || k0 >= ycs) continue;
-        float v[4] = {acc[mt][t][0], acc[mt][t][1], acc[mt][t][2], acc[mt][t][3]};
-        if (relu) {
-          // max(x, 0) on the bit pattern: negative floats are negative integers
-#pragma unroll
-          for (int i = 0; i < 4; ++i) v[i] = __int_as_float(max(__float_as_int(v[i]), 0));
-        }
         uint2 o;
-        o.x = pack2<BF>(v[0], v[1]);
-        o.y = pack2<BF>(v[2], v[3]);
+        o.x = clamp_below(pack2<BF>(acc[mt][t][0], acc[mt][t][1]), floor2);
+        o.y = clamp_below(pack2<BF>(acc[mt][t][2], acc[mt][t][3]), floor2);
+        const int k0 = (ft0 + t) * 16 + g * 4;
+        if (!full && (m[mt] >= M || ft0 + t >= FT || k0 >= ycs)) continue;
         if constexpr (LAST) {
           uint16_t* yp = reinterpret_cast<uint16_t*>(p.y) +
                          ((size_t)n * p.out_pixels + m[mt]) * p.y_cs;
           *reinterpret_cast<uint2*>(yp + k0) = o;
         } else {
-          *reinterpret_cast<uint2*>(act + ooff[mt] + k0 * 2) = o;
+          *reinterpret_cast<uint2*>(act + rout[mt] + (L.out_org + (ft0 + t) * 32)) = o;
         }
       }
     }
@@ -218,9 +266,9 @@ __device__ __forceinline__ void conv_items(const ResLayer& L, const ResParams& p
 
 template <bool BF, int MT, int NT>
 __device__ __forceinline__ void conv_layer(const ResLayer& L, const ResParams& p, char* act,
-                                           int n, int lane, int wave) {
-  if (L.flags & kResLast) conv_items<BF, MT, NT, true>(L, p, act, n, lane, wave);
-  else conv_items<BF, MT, NT, false>(L, p, act, n, lane, wave);
+                                           int n, int lane, int wave, PixelCache& pc) {
+  if (L.flags & kResLast) conv_items<BF, MT, NT, true>(L, p, act, n, lane, wave, pc);
+  else conv_items<BF, MT, NT, false>(L, p, act, n, lane, wave, pc);
 }
 
 // Global mean over the M interior pixels of the input, per channel, in fp32:
@@ -255,7 +303,6 @@ __device__ __forceinline__ void mean_layer(const ResLayer& L, const ResParams& p
 // after the kernel's first store becomes a vector load whose wait would also
 // drain the parameter staging in flight).
 typedef const uint32_t __attribute__((address_space(4)))* ConstWords;
-typedef const void __attribute__((address_space(1)))* GlobalPtr;
 typedef void __attribute__((address_space(3)))* LdsPtr;
 
 // The first eight dwords of a ResLayer: all that staging needs.
@@ -275,23 +322,40 @@ __device__ __forceinline__ T load_words(ConstWords w) {
   return __builtin_bit_cast(T, raw);
 }
 
+// One wave-wide global -> LDS load: lane i moves 16 bytes from its own global
+// address to the i-th 16-byte slot after lds_base (M0 holds the base).  Written
+// as inline assembly so that the compiler does not take it for an LDS store
+// that later LDS reads might alias (it would wait for the whole transfer before
+// the current layer's first LDS access); the kernel orders it by hand: issued
+// after the barrier that retires the destination's previous contents, awaited
+// (vmcnt) before the barrier that publishes it.
+__device__ __forceinline__ void load_to_lds(const void* src, uint32_t lds_base) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %1, off"
+      :
+      : "s"(lds_base), "v"(src)
+      : "memory", "m0");
+}
+
+__device__ __forceinline__ uint32_t lds_address(const char* p) {
+  return (uint32_t)(uintptr_t)(LdsPtr)p;
+}
+
 // A layer's parameter blob and tap table go from global memory straight into
-// LDS (16 bytes per lane, lane i of a wave to the i-th 16-byte slot after the
-// wave's base), issued before the current layer is computed and awaited after
-// it: no register is held and no global-memory latency sits on the layer chain.
+// LDS, issued before the current layer is computed and awaited after it: no
+// register is held and no global-memory latency sits on the layer chain.
 __device__ __forceinline__ void stage_params(const StageHead& H, char* act, int lane, int wave) {
   const char* src = reinterpret_cast<const char*>(H.packed);
+  const uint32_t dst = lds_address(act + H.w_off);
   for (int u = wave * 64; u < H.blob_units; u += kResThreads) {
-    if (u + lane < H.blob_units)
-      __builtin_amdgcn_global_load_lds((GlobalPtr)(src + (size_t)(u + lane) * 16),
-                                       (LdsPtr)(act + H.w_off + u * 16), 16, 0, 0);
+    if (u + lane < H.blob_units) load_to_lds(src + (size_t)(u + lane) * 16, dst + u * 16);
   }
   // the table (at most 64 slots) goes through the last wave, which has the
   // smallest share of the blob
   if (wave == kWaves - 1 && lane < H.tab_units)
-    __builtin_amdgcn_global_load_lds(
-        (GlobalPtr)(reinterpret_cast<const char*>(H.table) + lane * 16), (LdsPtr)(act + H.tab_off),
-        16, 0, 0);
+    load_to_lds(reinterpret_cast<const char*>(H.table) + lane * 16, lds_address(act + H.tab_off));
 }
 
 __device__ __forceinline__ void staging_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
@@ -330,6 +394,7 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(const ResParams p
   __syncthreads();
 
   const int n_layers = p.n_layers;
+  PixelCache pc;
   for (int l = 0; l < n_layers; ++l) {
     const bool has_next = l + 1 < n_layers;
     if (has_next) {
@@ -343,14 +408,11 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(const ResParams p
       mean_layer<BF>(L, p, lds, act, n, tid);
     } else {
       switch (L.MT * 8 + L.NT) {
-        case 1 * 8 + 1: conv_layer<BF, 1, 1>(L, p, act, n, lane, wave); break;
-        case 1 * 8 + 2: conv_layer<BF, 1, 2>(L, p, act, n, lane, wave); break;
-        case 1 * 8 + 3: conv_layer<BF, 1, 3>(L, p, act, n, lane, wave); break;
-        case 1 * 8 + 4: conv_layer<BF, 1, 4>(L, p, act, n, lane, wave); break;
-        case 2 * 8 + 1: conv_layer<BF, 2, 1>(L, p, act, n, lane, wave); break;
-        case 2 * 8 + 2: conv_layer<BF, 2, 2>(L, p, act, n, lane, wave); break;
-        case 3 * 8 + 1: conv_layer<BF, 3, 1>(L, p, act, n, lane, wave); break;
-        default: conv_layer<BF, 4, 1>(L, p, act, n, lane, wave); break;
+        case 1 * 8 + 1: conv_layer<BF, 1, 1>(L, p, act, n, lane, wave, pc); break;
+        case 1 * 8 + 2: conv_layer<BF, 1, 2>(L, p, act, n, lane, wave, pc); break;
+        case 2 * 8 + 1: conv_layer<BF, 2, 1>(L, p, act, n, lane, wave, pc); break;
+        case 2 * 8 + 2: conv_layer<BF, 2, 2>(L, p, act, n, lane, wave, pc); break;
+        default: conv_layer<BF, 4, 1>(L, p, act, n, lane, wave, pc); break;
       }
     }
     if (has_next) L = load_words<ResLayer>(table + (l + 1) * kLayerWords);   // in flight across the barrier
