@@ -109,12 +109,13 @@ struct ResLayer {
 };
 static_assert(sizeof(ResLayer) == 160, "ResLayer is read as 40 dwords");
 constexpr int kResMean = 1, kResRelu = 2, kResLast = 4, kResZeroHalo = 8;
-// kResFull: every tile of every work item is whole (no clamped pixel, no partial
-// filter group, all 16 lanes of every filter tile stored).  kResReuse: a wave's
-// first work item covers the same pixels at the same strides as in the previous
-// conv layer, every tile is whole, and the output's strides are the input's.
+// kResFullPixels: the pixel count is a multiple of a work item's pixels (no
+// clamped pixel).  kResFullFilters: no work item has a missing filter tile and
+// all 16 lanes of every filter tile are stored.  kResReuse: a wave's first work
+// item covers the same pixels at the same strides as in the previous conv
+// layer, no pixel tile is ragged, and the output's strides are the input's.
 // kResLikeOut: the shortcut tensor has the output's strides.
-constexpr int kResFull = 16, kResReuse = 32, kResLikeOut = 64;
+constexpr int kResFullPixels = 16, kResReuse = 32, kResLikeOut = 64, kResFullFilters = 128;
 constexpr int kResTablePad = 8;   // steps of padding after a tap table (2 * deepest prefetch)
 
 struct ResParams {

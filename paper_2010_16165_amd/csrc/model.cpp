@@ -104,12 +104,11 @@ struct LdsBlock {
   size_t offset;
 };
 
-// Greedy offset assignment: largest first, lowest offset that fits.
-size_t assign_offsets(std::vector<LdsBlock>& blocks) {
-  std::vector<int> order(blocks.size());
-  for (size_t i = 0; i < order.size(); ++i) order[i] = (int)i;
-  std::stable_sort(order.begin(), order.end(),
-                   [&](int a, int b) { return blocks[a].units > blocks[b].units; });
+// Offset assignment: blocks are placed one by one at the lowest offset free
+// over their whole lifetime.  The order matters; three orders are tried
+// (largest first, earliest first, longest-lived first) and the tightest result
+// is kept.
+size_t place_in_order(std::vector<LdsBlock>& blocks, const std::vector<int>& order) {
   std::vector<int> placed;
   size_t extent = 0;
   for (int id : order) {
@@ -131,6 +130,31 @@ size_t assign_offsets(std::vector<LdsBlock>& blocks) {
     placed.push_back(id);
   }
   return extent;
+}
+
+size_t assign_offsets(std::vector<LdsBlock>& blocks) {
+  std::vector<int> order(blocks.size());
+  for (size_t i = 0; i < order.size(); ++i) order[i] = (int)i;
+  std::vector<LdsBlock> best;
+  size_t best_extent = ~size_t(0);
+  for (int rule = 0; rule < 3; ++rule) {
+    std::vector<int> o = order;
+    std::stable_sort(o.begin(), o.end(), [&](int a, int b) {
+      const LdsBlock &x = blocks[a], &y = blocks[b];
+      if (rule == 0) return x.units > y.units;
+      if (rule == 1) return x.first != y.first ? x.first < y.first : x.units > y.units;
+      const int lx = x.last - x.first, ly = y.last - y.first;
+      return lx != ly ? lx > ly : x.units > y.units;
+    });
+    std::vector<LdsBlock> trial = blocks;
+    const size_t extent = place_in_order(trial, o);
+    if (extent < best_extent) {
+      best_extent = extent;
+      best = trial;
+    }
+  }
+  blocks = best;
+  return best_extent;
 }
 
 // LDS pixel stride in bytes for tensors of cs 16-bit lanes.  The 16 pixels x 4
@@ -200,6 +224,20 @@ void plan_resident(fupr_model* m) {
   }
   for (const fupr_op_desc& op : m->ops)
     if (op.kind == FUPR_OP_CONV && class_of[op.in] >= 0) ++classes[class_of[op.in]].readers;
+  // A block's output may be written over its shortcut tensor: the shortcut is
+  // read by the lane that writes the same pixel and channels, before it writes,
+  // and by nobody else; no convolution reads it in that layer.  home[t] is the
+  // tensor whose LDS block t lives in.
+  std::vector<int> home(n + 1);
+  for (int tid = 0; tid <= n; ++tid) home[tid] = tid;
+  for (int i = 0; i + 1 < n; ++i) {
+    const fupr_op_desc& op = m->ops[i];
+    if (op.kind != FUPR_OP_CONV || op.res < 0 || op.res == op.in) continue;
+    const TensorInfo& tr = m->tensors[op.res];
+    if (tr.last_use != i || op.res_spatial_stride != 1 || op.res_c_offset != 0) continue;
+    if (class_of[op.res] < 0 || class_of[op.res] != class_of[i + 1]) continue;
+    home[i + 1] = home[op.res];
+  }
   const int k = (int)classes.size();
   std::vector<std::pair<double, std::vector<int>>> candidates;
   if (k <= 5) {
@@ -234,6 +272,10 @@ void plan_resident(fupr_model* m) {
       b.first = tid - 1;                       // produced by layer tid-1 (image: before layer 0)
       b.last = std::max(t.last_use, b.first);
       b.units = tid == n ? 0 : (size_t)(t.H + 2 * halo_of(t)) * row_of(t) * ps2[tid] / 16;
+      if (home[tid] != tid) {                  // written over its shortcut: that block lives on
+        blocks[home[tid]].last = std::max(blocks[home[tid]].last, b.last);
+        b.units = 0;
+      }
     }
     bool ok = true;
     for (int i = 0; i < n && ok; ++i) {
@@ -249,12 +291,19 @@ void plan_resident(fupr_model* m) {
     }
     if (!ok) return;
     const size_t extent = assign_offsets(blocks);
+    if (std::getenv("FUPR_DEBUG")) {
+      std::fprintf(stderr, "resident candidate: strides");
+      for (int c = 0; c < k; ++c)
+        std::fprintf(stderr, " %dx%d:%d", classes[c].H, classes[c].W,
+                     lds_pixel_stride(classes[c].cs, cand.second[c]));
+      std::fprintf(stderr, " -> %zu bytes (limit %zu)\n", extent * 16, budget_units * 16);
+    }
     if (extent > budget_units) continue;
 
     // LDS byte offset of pixel (row, col) counted from the halo's corner
     auto pixel_at = [&](int tid, int row, int col) {
       const TensorInfo& t = m->tensors[tid];
-      return (int32_t)(blocks[tid].offset * 16 + (size_t)(row * row_of(t) + col) * ps2[tid]);
+      return (int32_t)(blocks[home[tid]].offset * 16 + (size_t)(row * row_of(t) + col) * ps2[tid]);
     };
 
     // known-zero 16-byte units, to skip re-zeroing halos that are still clean
@@ -359,11 +408,12 @@ void plan_resident(fupr_model* m) {
         L.n_fgroups = (L.FT + nt - 1) / nt;
         L.n_items = ((L.M + 15) / 16 + mt - 1) / mt * L.n_fgroups;
         if (L.n_items >= 65536) return;
-        if (L.M % (16 * mt) == 0 && L.FT % nt == 0 && to.cs == PL.Kp && !last) L.flags |= kResFull;
+        if (L.M % (16 * mt) == 0) L.flags |= kResFullPixels;
+        if (L.FT % nt == 0 && to.cs == PL.Kp && !last) L.flags |= kResFullFilters;
         if (op.res >= 0 && L.res_row == L.out_row && L.res_col == L.out_col) L.flags |= kResLikeOut;
         const std::array<int, 8> geometry = {L.M, L.Q, mt, L.n_fgroups, L.in_row, L.in_col, L.out_row, L.out_col};
         if (L.n_items <= kResThreads / 64) {
-          if (geometry == prev_geometry && (L.flags & kResFull) && L.in_row == L.out_row &&
+          if (geometry == prev_geometry && (L.flags & kResFullPixels) && !last && L.in_row == L.out_row &&
               L.in_col == L.out_col)
             L.flags |= kResReuse;
           prev_geometry = geometry;
@@ -401,7 +451,7 @@ void plan_resident(fupr_model* m) {
           halo_units(i + 1, [&](size_t u) { clean[u] = 1; });
         }
         if (halo_of(to) > 0) write_interior(i + 1);
-        else mark(blocks[i + 1].offset, blocks[i + 1].units, 0);
+        else mark(blocks[home[i + 1]].offset, blocks[home[i + 1]].units, 0);
       }
       if (i + 1 < n && blocks[n + 2 + i].units) mark(blocks[n + 2 + i].offset, blocks[n + 2 + i].units, 0);
       m->res_layers[i] = L;

@@ -114,8 +114,9 @@ __device__ __forceinline__ void conv_items(const ResLayer& L, const ResParams& p
   const int li = lane & 15, g = lane >> 4;
   const int nsteps = L.nsteps, FT = L.FT, M = L.M, Q = L.Q;
   const bool has_res = L.res_org >= 0;
-  const bool full = (L.flags & kResFull) != 0;       // every tile of every item is whole
-  const bool reuse = (L.flags & kResReuse) != 0;     // pc holds this layer's first item
+  const bool full_pixels = (L.flags & kResFullPixels) != 0;     // no pixel tile is ragged
+  const bool full_filters = (L.flags & kResFullFilters) != 0;   // no filter tile is missing or partly stored
+  const bool reuse = (L.flags & kResReuse) != 0;                // pc holds this layer's first item
   const uint32_t floor2 = (L.flags & kResRelu) ? 0u : 0x80008000u;
   const int ycs = LAST ? p.y_cs : L.cs_out;
   const int wstep = L.wstep;
@@ -152,7 +153,7 @@ __device__ __forceinline__ void conv_items(const ResLayer& L, const ResParams& p
       // same pixels, same strides as in the previous layer; output strides = input strides
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        m[mt] = 0;   // not looked at: every tile is whole
+        m[mt] = 0;   // not looked at: no pixel tile is ragged
         rin[mt] = pc.rin[mt];
         rout[mt] = rin[mt] + g * 8;
       }
@@ -221,25 +222,37 @@ __device__ __forceinline__ void conv_items(const ResLayer& L, const ResParams& p
       }
     }
 
-    for (int step0 = 0; step0 < nsteps; step0 += D) {
-      // the table entries a step needs are read a whole group ahead of it
+    auto mfmas = [&](const uint4* av, const uint4* bv) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[mt][t] = mfma_16x16x32<BF>(av[t], bv[mt], acc[mt][t]);
+    };
+    // The table entries a step needs are read a whole group of D steps ahead
+    // of it.  Main part: groups whose D steps and D refills all exist, no
+    // condition inside; then at most 2D - 1 steps with conditions.
+    int step0 = 0;
+    for (; step0 + 2 * D <= nsteps; step0 += D) {
       int e_nxt[D];
 #pragma unroll
       for (int d = 0; d < D; ++d) e_nxt[d] = *reinterpret_cast<const int*>(act + tptr + d * 16);
       tptr += D * 16;
 #pragma unroll
       for (int d = 0; d < D; ++d) {
-        if (step0 + d < nsteps) {
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int t = 0; t < NT; ++t)
-              acc[mt][t] = mfma_16x16x32<BF>(a[d][t], b[d][mt], acc[mt][t]);
-          if (step0 + d + D < nsteps) operands(e_cur[d], a[d], b[d]);
-        }
+        mfmas(a[d], b[d]);
+        operands(e_cur[d], a[d], b[d]);
       }
 #pragma unroll
       for (int d = 0; d < D; ++d) e_cur[d] = e_nxt[d];
+    }
+    for (; step0 < nsteps; step0 += D) {
+#pragma unroll
+      for (int d = 0; d < D; ++d) {
+        if (step0 + d < nsteps) {
+          mfmas(a[d], b[d]);
+          if (step0 + d + D < nsteps) operands(e_cur[d], a[d], b[d]);
+        }
+      }
     }
 
     // epilogue: one rounding, ReLU on the rounded pair, store
@@ -251,7 +264,8 @@ __device__ __forceinline__ void conv_items(const ResLayer& L, const ResParams& p
         o.x = clamp_below(pack2<BF>(acc[mt][t][0], acc[mt][t][1]), floor2);
         o.y = clamp_below(pack2<BF>(acc[mt][t][2], acc[mt][t][3]), floor2);
         const int k0 = (ft0 + t) * 16 + g * 4;
-        if (!full && (m[mt] >= M || ft0 + t >= FT || k0 >= ycs)) continue;
+        if (!full_pixels && m[mt] >= M) continue;
+        if (!full_filters && (ft0 + t >= FT || k0 >= ycs)) continue;
         if constexpr (LAST) {
           uint16_t* yp = reinterpret_cast<uint16_t*>(p.y) +
                          ((size_t)n * p.out_pixels + m[mt]) * p.y_cs;
@@ -329,13 +343,14 @@ __device__ __forceinline__ T load_words(ConstWords w) {
 // the current layer's first LDS access); the kernel orders it by hand: issued
 // after the barrier that retires the destination's previous contents, awaited
 // (vmcnt) before the barrier that publishes it.
-__device__ __forceinline__ void load_to_lds(const void* src, uint32_t lds_base) {
+__device__ __forceinline__ void load_to_lds(const void* src_base, uint32_t lane_offset,
+                                            uint32_t lds_base) {
   asm volatile(
       "s_mov_b32 m0, %0\n\t"
       "s_nop 0\n\t"
-      "global_load_lds_dwordx4 %1, off"
+      "global_load_lds_dwordx4 %1, %2"
       :
-      : "s"(lds_base), "v"(src)
+      : "s"(lds_base), "v"(lane_offset), "s"(src_base)
       : "memory", "m0");
 }
 
@@ -345,17 +360,25 @@ __device__ __forceinline__ uint32_t lds_address(const char* p) {
 
 // A layer's parameter blob and tap table go from global memory straight into
 // LDS, issued before the current layer is computed and awaited after it: no
-// register is held and no global-memory latency sits on the layer chain.
-__device__ __forceinline__ void stage_params(const StageHead& H, char* act, int lane, int wave) {
+// register is held and no global-memory latency sits on the layer chain.  The
+// waves that have no work item in the current layer (busy = number that do) do
+// the staging; when every wave is busy all share it.
+__device__ __forceinline__ void stage_params(ConstWords next, int busy, char* act, int lane,
+                                             int wave) {
+  const int stagers = busy < kWaves ? kWaves - busy : kWaves;
+  const int me = busy < kWaves ? wave - busy : wave;
+  if (me < 0) return;
+  const StageHead H = load_words<StageHead>(next);
   const char* src = reinterpret_cast<const char*>(H.packed);
   const uint32_t dst = lds_address(act + H.w_off);
-  for (int u = wave * 64; u < H.blob_units; u += kResThreads) {
-    if (u + lane < H.blob_units) load_to_lds(src + (size_t)(u + lane) * 16, dst + u * 16);
+  const uint32_t lane_offset = lane * 16;
+  for (int u = me * 64; u < H.blob_units; u += stagers * 64) {
+    if (u + lane < H.blob_units) load_to_lds(src + (size_t)u * 16, lane_offset, dst + u * 16);
   }
   // the table (at most 64 slots) goes through the last wave, which has the
   // smallest share of the blob
   if (wave == kWaves - 1 && lane < H.tab_units)
-    load_to_lds(reinterpret_cast<const char*>(H.table) + lane * 16, lds_address(act + H.tab_off));
+    load_to_lds(H.table, lane_offset, lds_address(act + H.tab_off));
 }
 
 __device__ __forceinline__ void staging_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
@@ -374,8 +397,7 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(const ResParams p
   constexpr int kLayerWords = sizeof(ResLayer) / 4;
 
   {
-    const StageHead H = load_words<StageHead>(table);
-    stage_params(H, act, lane, wave);
+    stage_params(table, kWaves, act, lane, wave);
     // stage the image into the interior of its LDS tensor, zero its halo
     const int cpp = p.in_cs >> 3;
     const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(p.x) +
@@ -397,10 +419,9 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(const ResParams p
   PixelCache pc;
   for (int l = 0; l < n_layers; ++l) {
     const bool has_next = l + 1 < n_layers;
-    if (has_next) {
-      const StageHead Hn = load_words<StageHead>(table + (l + 1) * kLayerWords);
-      stage_params(Hn, act, lane, wave);
-    }
+    if (has_next)
+      stage_params(table + (l + 1) * kLayerWords, (L.flags & kResMean) ? kWaves : L.n_items, act, lane,
+                   wave);
 
     if (L.flags & kResZeroHalo)
       zero_halo(act, L.hz_org, L.hz_P, L.hz_Q, L.hz_Wh, L.hz_ps2, L.hz_chunks, L.hz_hp, tid);
