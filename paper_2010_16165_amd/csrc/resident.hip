@@ -256,6 +256,30 @@ __device__ __forceinline__ void conv_items(const ResLayer& L, const ResParams& p
     }
 
     // epilogue: one rounding, ReLU on the rounded pair, store
+    if (!LAST && MT % 2 == 0 && full_pixels && full_filters) {
+      // Two pixel tiles at a time.  A lane holds 4 channels (8 bytes) of one
+      // pixel of each tile; lanes 16 apart hold the next 4 channels of the same
+      // pixel.  Swapping odd 16-lane rows of the first tile's registers with
+      // even rows of the second's gives every lane 8 consecutive channels of
+      // ONE pixel (even rows: first tile, odd rows: second tile): half as many
+      // LDS stores, each 16 bytes.
+#pragma unroll
+      for (int mt = 0; mt < MT; mt += 2) {
+        const int wsel = ((g & 1) ? rout[mt + 1] : rout[mt]) - g * 8 + (g >> 1) * 16;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          const uint32_t p0 = clamp_below(pack2<BF>(acc[mt][t][0], acc[mt][t][1]), floor2);
+          const uint32_t p1 = clamp_below(pack2<BF>(acc[mt][t][2], acc[mt][t][3]), floor2);
+          const uint32_t q0 = clamp_below(pack2<BF>(acc[mt + 1][t][0], acc[mt + 1][t][1]), floor2);
+          const uint32_t q1 = clamp_below(pack2<BF>(acc[mt + 1][t][2], acc[mt + 1][t][3]), floor2);
+          const auto r0 = __builtin_amdgcn_permlane16_swap(p0, q0, false, false);
+          const auto r1 = __builtin_amdgcn_permlane16_swap(p1, q1, false, false);
+          *reinterpret_cast<uint4*>(act + wsel + (L.out_org + (ft0 + t) * 32)) =
+              uint4{r0[0], r1[0], r0[1], r1[1]};
+        }
+      }
+      continue;
+    }
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
