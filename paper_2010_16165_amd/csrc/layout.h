@@ -106,8 +106,13 @@ struct ResLayer {
   // halo of the output tensor, zeroed by this layer when kResZeroHalo is set
   int32_t hz_org, hz_P, hz_Q, hz_Wh, hz_ps2, hz_chunks, hz_hp;
   int32_t pad_[1];
+  // what staging the NEXT layer's parameters needs (a copy of that layer's first
+  // eight dwords), so that no load stands between a layer's start and the staging
+  const void* next_packed;
+  const void* next_table;
+  int32_t next_blob_units, next_tab_units, next_w_off, next_tab_off;
 };
-static_assert(sizeof(ResLayer) == 160, "ResLayer is read as 40 dwords");
+static_assert(sizeof(ResLayer) == 192, "ResLayer is read as 48 dwords");
 constexpr int kResMean = 1, kResRelu = 2, kResLast = 4, kResZeroHalo = 8;
 // kResFullPixels: the pixel count is a multiple of a work item's pixels (no
 // clamped pixel).  kResFullFilters: no work item has a missing filter tile and

@@ -490,6 +490,14 @@ bool upload_resident(const fupr_model* cm) {
   std::vector<ResLayer> layers = m->res_layers;
   for (size_t i = 0; i < n; ++i)
     layers[i].table = base + layer_bytes + m->res_table_at[i] * sizeof(int32_t);
+  for (size_t i = 0; i + 1 < n; ++i) {
+    layers[i].next_packed = layers[i + 1].packed;
+    layers[i].next_table = layers[i + 1].table;
+    layers[i].next_blob_units = layers[i + 1].blob_units;
+    layers[i].next_tab_units = layers[i + 1].tab_units;
+    layers[i].next_w_off = layers[i + 1].w_off;
+    layers[i].next_tab_off = layers[i + 1].tab_off;
+  }
   bool ok = hipMemcpy(base, layers.data(), n * sizeof(ResLayer), hipMemcpyHostToDevice) == hipSuccess;
   if (ok && !m->res_tables.empty())
     ok = hipMemcpy(base + layer_bytes, m->res_tables.data(), m->res_tables.size() * sizeof(int32_t),

@@ -387,12 +387,11 @@ __device__ __forceinline__ uint32_t lds_address(const char* p) {
 // register is held and no global-memory latency sits on the layer chain.  The
 // waves that have no work item in the current layer (busy = number that do) do
 // the staging; when every wave is busy all share it.
-__device__ __forceinline__ void stage_params(ConstWords next, int busy, char* act, int lane,
+__device__ __forceinline__ void stage_params(const StageHead& H, int busy, char* act, int lane,
                                              int wave) {
   const int stagers = busy < kWaves ? kWaves - busy : kWaves;
   const int me = busy < kWaves ? wave - busy : wave;
   if (me < 0) return;
-  const StageHead H = load_words<StageHead>(next);
   const char* src = reinterpret_cast<const char*>(H.packed);
   const uint32_t dst = lds_address(act + H.w_off);
   const uint32_t lane_offset = lane * 16;
@@ -421,7 +420,7 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(const ResParams p
   constexpr int kLayerWords = sizeof(ResLayer) / 4;
 
   {
-    stage_params(table, kWaves, act, lane, wave);
+    stage_params(load_words<StageHead>(table), kWaves, act, lane, wave);
     // stage the image into the interior of its LDS tensor, zero its halo
     const int cpp = p.in_cs >> 3;
     const uint4* src = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(p.x) +
@@ -443,9 +442,11 @@ __global__ __launch_bounds__(kResThreads) void resident_kernel(const ResParams p
   PixelCache pc;
   for (int l = 0; l < n_layers; ++l) {
     const bool has_next = l + 1 < n_layers;
-    if (has_next)
-      stage_params(table + (l + 1) * kLayerWords, (L.flags & kResMean) ? kWaves : L.n_items, act, lane,
-                   wave);
+    if (has_next) {
+      const StageHead Hn = {L.next_packed, L.next_table, L.next_blob_units,
+                            L.next_tab_units, L.next_w_off, L.next_tab_off};
+      stage_params(Hn, (L.flags & kResMean) ? kWaves : L.n_items, act, lane, wave);
+    }
 
     if (L.flags & kResZeroHalo)
       zero_halo(act, L.hz_org, L.hz_P, L.hz_Q, L.hz_Wh, L.hz_ps2, L.hz_chunks, L.hz_hp, tid);
