@@ -222,6 +222,17 @@ __device__ __forceinline__ void conv_items(const ResLayer& L, const ResParams& p
       }
     }
 
+    // scheduling hint: one LDS read and one address addition in the shadow of
+    // each of the next n MFMAs (a wave alone on its SIMD otherwise issues the
+    // MFMAs back to back and only then the reads)
+    auto interleave = [](int n) {
+#pragma unroll
+      for (int i = 0; i < n; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
+        __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);   // vector ALU
+      }
+    };
     auto mfmas = [&](const uint4* av, const uint4* bv) {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
@@ -242,6 +253,7 @@ __device__ __forceinline__ void conv_items(const ResLayer& L, const ResParams& p
         mfmas(a[d], b[d]);
         operands(e_cur[d], a[d], b[d]);
       }
+      interleave(D * MT * NT);
 #pragma unroll
       for (int d = 0; d < D; ++d) e_cur[d] = e_nxt[d];
     }
