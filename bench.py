@@ -47,6 +47,22 @@ def cpu_baseline(model, batch, budget_s=12.0):
             "sample": f"{n} of {batch} images of the workload, {passes} passes, {spent:.1f} s"}
 
 
+def measured_traffic(kernel, args):
+    """HBM bytes per launch of the dominant kernel from the stored rocprofv3 counter
+    runs (FETCH_SIZE and WRITE_SIZE, each scaled by a copy of known size); None when
+    there is no record for this kernel and workload, or when the kernel sources have
+    changed since the counters were taken."""
+    from paper_2010_16165_amd import record_traffic as rt
+    if args.config != 1 or args.batch or args.schedule != "auto" or not os.path.exists(rt.STORE):
+        return None
+    with open(rt.STORE) as f:
+        rec = json.load(f)
+    if rec.get("sources_sha256") != rt.sources_hash():
+        return None
+    entry = rec.get("kernels", {}).get(kernel)
+    return entry["bytes_per_launch"] if entry else None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -150,7 +166,7 @@ def main():
         roof = {"bound": "hbm", "achieved": dom["bytes"] / (dom["ms"] * 1e-3) / 1e9,
                 "peak": PEAK_HBM / 1e9, "unit": "GB/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = measured_traffic(dom_name, args)
     roof["kernel"] = dom_name
     roof["launches_per_step"] = dom["launches"]
     roof["avg_launch_us"] = dom["ms"] / dom["launches"] * 1e3
