@@ -21,13 +21,15 @@ PEAK_FP32 = 157.3e12       # fp32 vector, FLOP/s
 PEAK_HBM = 8.0e12          # B/s
 
 
-def cpu_baseline(model, batch, budget_s=12.0):
+def cpu_baseline(model, batch, aggressive="off", budget_s=12.0):
     """The CPU oracle (unfused, zero-masked, double precision) timed on the host
     cores over a bounded sample of the same workload: as many images of the
     batch as fit the time budget, and whole passes over them until it is spent."""
     import synth
     from oracle import reference as orc
-    masks = orc.select_masks(model)
+    if aggressive != "off":
+        model = orc.aggressive_fuse(model)
+    masks = orc.select_masks(model) if aggressive != "fused" else {}
     seed = synth.BASE_SEED + model.get("config_index", 0)
     x1 = synth.make_input(seed, 1, model["in_shape"])
     orc.forward(model, x1, masks=masks)            # warm-up (library load, page faults)
@@ -53,7 +55,8 @@ def measured_traffic(kernel, args):
     there is no record for this kernel and workload, or when the kernel sources have
     changed since the counters were taken."""
     from paper_2010_16165_amd import record_traffic as rt
-    if args.config != 1 or args.batch or args.schedule != "auto" or not os.path.exists(rt.STORE):
+    if (args.config != 1 or args.batch or args.schedule != "auto" or args.aggressive != "off"
+            or not os.path.exists(rt.STORE)):
         return None
     with open(rt.STORE) as f:
         rec = json.load(f)
@@ -72,6 +75,9 @@ def main():
     ap.add_argument("--batch", type=int, default=0)
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--schedule", choices=["auto", "per-layer"], default="auto")
+    ap.add_argument("--aggressive", choices=["off", "fused", "fused-pruned"], default="off",
+                    help="aggressive fusion of the basic blocks (Sec. IV-B): fused = dilated "
+                         "convolutions, no additions; fused-pruned = then the n - m prune-back of Alg. 1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-op", action="store_true", help="print a per-operator table to stderr")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -93,7 +99,8 @@ def main():
     if args.batch:
         batch = args.batch
     dt = B.DTYPES[model["dtype"]]
-    plan = network.optimise(model)
+    plan = network.optimise(model, aggressive=args.aggressive != "off",
+                            prune_fused=args.aggressive == "fused-pruned")
     fm, sites = network.build(plan)
     if args.schedule == "per-layer":
         fm.set_schedule(B.SCHEDULE_PER_LAYER)
@@ -192,6 +199,7 @@ def main():
         "vs_baseline": None, "dtype": model["dtype"], "data": "synthetic",
         "config": {"workload": model["name"], "config_index": args.config, "batch": batch,
                    "kernel_launches": n_launch, "schedule": args.schedule,
+                   "aggressive_fusion": args.aggressive,
                    "hip_graph": graph is not None},
         "tflops": tflops, "mfma_frac": tflops * 1e12 / peak_flops,
         "algorithmic_gflop_per_step": total_flops / 1e9,
@@ -200,7 +208,7 @@ def main():
         "roofline": roof,
     }
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(model, batch)
+        line["cpu_baseline"] = cpu_baseline(model, batch, args.aggressive)
     print(json.dumps(line))
 
 

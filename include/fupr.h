@@ -8,6 +8,9 @@
  *
  *   fupr_fold            batch norm as omega*x + lambda (Sec. IV-B-2, Eq. 3-5)
  *                        merged into the convolution before it (Sec. VI-B-3)
+ *   fupr_xconv_fuse      aggressive fusion of a basic residual block: auxiliary and
+ *                        padded convolutions concatenated to its two convolutions,
+ *                        batch norms adjusted, the addition gone (Sec. IV-B-1, IV-B-2)
  *   fupr_select_filters  lowest-norm filters of a convolution (Sec. IV-C, Eq. 6)
  *   fupr_prune_count     how many filters a non-fused operator loses (Alg. 1)
  *   fupr_prune           removal of masked filters (Alg. 1, last step)
@@ -56,7 +59,8 @@ enum {
   FUPR_ERR_ALIGN = -7,      /* pointer or channel stride violates the alignment rules  */
   FUPR_ERR_LAUNCH = -8,     /* the HIP runtime refused a launch, event or capture      */
   FUPR_ERR_ARG = -9,        /* any other invalid argument (flags, norm, counts, ids)   */
-  FUPR_ERR_LIMIT = -10      /* a size exceeds what the kernels index with 32 bits      */
+  FUPR_ERR_LIMIT = -10,     /* a size exceeds what the kernels index with 32 bits      */
+  FUPR_ERR_BN_SCALE = -11   /* a batch-norm scale that must be inverted is zero        */
 };
 const char* fupr_status_str(fupr_status s); /* static string, never NULL */
 
@@ -87,11 +91,70 @@ fupr_status fupr_fold(const fupr_conv_shape* shape, const float* W, const float*
                       const float* gamma, const float* beta, const float* mean, const float* var,
                       float eps, uint32_t fuse_flags, float* W_out, float* b_out);
 
+/* Batch-norm parameters of one operator (Sec. IV-B-2, Eq. 3-5): K floats each, host. */
+typedef struct {
+  const float* gamma;
+  const float* beta;
+  const float* mean;
+  const float* var;
+  float eps;
+} fupr_bn;
+
+/* The shortcut of a basic residual block (Table II). */
+enum {
+  FUPR_SHORTCUT_IDENTITY = 0,      /* y = F(x) + x                                            */
+  FUPR_SHORTCUT_SUBSAMPLE_PAD = 1, /* x[:, ::stride, ::stride], zero channels up to conv2's K */
+  FUPR_SHORTCUT_PROJECTION = 2     /* 1 x 1 convolution (stride of conv1) and its batch norm  */
+};
+
+/*
+ * Aggressive operator fusion of a basic residual block (Sec. IV-B-1: the
+ * basic-block recipe and the projection-shortcut recipe; batch norms per
+ * Sec. IV-B-2).  The block
+ *     h = relu(bn1(conv1(x)));  y = relu(bn2(conv2(h)) + shortcut(x))
+ * with conv1 = k1 x c x r x s, conv2 = k2 x k1 x r x s (r, s odd, pad = r/2 = s/2,
+ * conv2 of stride 1) becomes two dilated convolutions and no addition:
+ *     [h ; x'] = relu(bn1'(conv1'(x)));  y = relu(bn2'(conv2'([h ; x'])))
+ *   W1_out  (k1 + c) x c x r x s: conv1's filters, then the auxiliary convolution for
+ *           channel-wise fusion: filter k1 + j has a single 1 at (channel j, centre tap),
+ *           so its output is x at conv1's stride.
+ *   bn1_out (k1 + c each): bn1, then the auxiliary batch norm omega = 1, lambda = 0
+ *           (gamma = sqrt(1 + eps) rounded to float, beta = mean = 0, var = 1).
+ *   W2_out  k2 x (k1 + c) x r x s: conv2's channels, then the auxiliary convolution for
+ *           filter-wise fusion at the centre tap of channels k1 + j.  bn2 stays after the
+ *           fused operator and would scale what these weights add, so they hold its
+ *           inverse: 1 / omega2_k at j = k for FUPR_SHORTCUT_IDENTITY (needs c = k2,
+ *           conv1 stride 1) and FUPR_SHORTCUT_SUBSAMPLE_PAD (c <= k2; rows k >= c stay
+ *           zero); omega_p,k / omega2_k * Wp[k][j] for FUPR_SHORTCUT_PROJECTION (the
+ *           1 x 1 convolution padded to r x s).
+ *   beta2_out (k2): beta2, plus the projection's shift lambda_p,k for
+ *           FUPR_SHORTCUT_PROJECTION; gamma, mean, var of bn2 are unchanged.
+ * The copy of x passes through the block's first ReLU: the rewrite is exact for
+ * block inputs that are themselves outputs of a ReLU.  All values are computed
+ * in double and stored as float.  proj, Wp, bnp are read only for
+ * FUPR_SHORTCUT_PROJECTION (proj = k2 x c x 1 x 1, pad 0, conv1's stride).
+ * Outputs are caller-allocated and must not alias inputs.
+ * Errors: NULL, SHAPE (sizes that do not fit the recipe), ARG (unknown shortcut),
+ * BN_VAR, BN_SCALE (omega2_k = 0: the batch norm after conv2 cannot be inverted).
+ */
+typedef struct {
+  float* gamma;
+  float* beta;
+  float* mean;
+  float* var;
+} fupr_bn_out;
+fupr_status fupr_xconv_fuse(const fupr_conv_shape* conv1, const float* W1, const fupr_bn* bn1,
+                            const fupr_conv_shape* conv2, const float* W2, const fupr_bn* bn2,
+                            int32_t shortcut, const fupr_conv_shape* proj, const float* Wp,
+                            const fupr_bn* bnp, float* W1_out, const fupr_bn_out* bn1_out,
+                            float* W2_out, float* beta2_out);
+
 /*
  * Number of filters a non-fused operator with n filters loses at pruning rate
  * permille/1000: floor(n * permille / 1000) in integer arithmetic, capped at
  * n - 1 so that one filter always stays (Alg. 1).  Returns a negative status
- * for n <= 0 or permille outside 0..1000.
+ * for n <= 0 or permille outside 0..1000.  (A FUSED operator with n filters, m
+ * of them original, loses n - m instead: pass that count to fupr_select_filters.)
  */
 int32_t fupr_prune_count(int32_t n, int32_t permille);
 

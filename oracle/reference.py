@@ -16,6 +16,10 @@ paper's equivalence claims:
     (Eq. 3-5) and merged into the preceding convolution (Sec. VI-B-3);
   * extract(): the thinner model obtained when masked filters are removed
     (last step of Alg. 1).
+
+aggressive_fuse() builds the "dilated" model of Sec. IV-B (auxiliary and padded
+convolutions concatenated to a basic block's two convolutions, batch norms
+adjusted, the element-wise addition gone); the same walker evaluates it.
 """
 from __future__ import annotations
 
@@ -165,14 +169,21 @@ def select_mask(w, n_prune, norm=1):
 
 
 def select_masks(model, norm=1):
-    """{(block, conv): mask} for every conv with a nonzero pruning rate; norms
-    are taken on the raw (unfolded) weights."""
+    """{(block, conv): mask} for every conv that loses filters; norms are taken
+    on the raw (unfolded) weights.  A fused operator with n filters, m of them
+    original, loses the n - m of lowest norm; any other operator with a nonzero
+    rate loses floor(p_phi n) (Alg. 1)."""
     masks = {}
     for bi, blk in enumerate(model["blocks"]):
+        original = blk.get("original_filters")
         for ci, pm in enumerate(blk["prune_permille"]):
-            if pm:
-                w = blk["convs"][ci]["W"]
-                masks[(bi, ci)] = select_mask(w, prune_count(w.shape[0], pm), norm)
+            w = blk["convs"][ci]["W"]
+            if original is not None:
+                n_prune = w.shape[0] - original[ci]
+            else:
+                n_prune = prune_count(w.shape[0], pm) if pm else 0
+            if n_prune:
+                masks[(bi, ci)] = select_mask(w, n_prune, norm)
     return masks
 
 
@@ -249,6 +260,101 @@ def _conv_bn(x, conv, bn, merged):
 
 
 # --------------------------------------------------------------------------
+# aggressive operator fusion (Sec. IV-B)
+# --------------------------------------------------------------------------
+
+def _omega_lambda(bn):
+    omega = _f64(bn["gamma"]) / np.sqrt(_f64(bn["var"]) + float(bn["eps"]))
+    return omega, _f64(bn["beta"]) - omega * _f64(bn["mean"])
+
+
+def aggressive_fuse_block(blk):
+    """A basic residual block (two r x s convolutions, a shortcut, an addition)
+    rewritten as two dilated convolutions and no addition (Sec. IV-B-1, the
+    basic-block and projection-shortcut recipes; batch norms per Sec. IV-B-2).
+
+    With conv1 = k1 x c x r x s, conv2 = k2 x k1 x r x s:
+      * an auxiliary convolution for channel-wise fusion, identity weights (a 1
+        at the centre tap of filter j, channel j), is concatenated to conv1
+        along the filters: (k1 + c) x c x r x s; its c outputs are the block
+        input (at conv1's stride).  An auxiliary batch norm with omega = 1,
+        lambda = 0 goes with them.
+      * an auxiliary convolution for filter-wise fusion is concatenated to conv2
+        along the channels: k2 x (k1 + c) x r x s, reading the copied input.
+        The batch norm after conv2 stays and would scale what the auxiliary
+        weights add, so they hold its inverse: 1 / omega2_k at (k, k, centre)
+        for an identity (or subsample-and-zero-pad) shortcut.  A 1 x 1
+        projection on the shortcut becomes a padded r x s convolution whose
+        centre tap is omega_p,k / omega2_k * Wp[k, :]; its shift lambda_p goes
+        into the shift of the batch norm after conv2.
+
+    The copy of the input passes through the block's first ReLU, so the rewrite
+    is exact for block inputs that are outputs of a ReLU (every block of the
+    Table II networks).  Returns the fused block; "original_filters" records m
+    of Alg. 1 for both operators.
+    """
+    if blk["kind"] != "basic":
+        raise ValueError("only basic blocks are fused")
+    c1, c2 = blk["convs"]
+    b1, b2 = blk["bns"]
+    w1, w2 = _f64(c1["W"]), _f64(c2["W"])
+    k1, c, r, s_ = w1.shape
+    k2 = w2.shape[0]
+    assert w2.shape[1:] == (k1, r, s_) and r % 2 == 1 and s_ % 2 == 1
+    assert c1["pad"] == r // 2 and c2["pad"] == r // 2 and c2["stride"] == 1
+    cr, cs = r // 2, s_ // 2
+    sc = blk["shortcut"]
+
+    aux_c = np.zeros((c, c, r, s_))
+    aux_c[np.arange(c), np.arange(c), cr, cs] = 1.0
+    w1f = np.concatenate([w1, aux_c], axis=0)
+    eps1 = float(b1["eps"])
+    bn1f = {"gamma": np.concatenate([_f64(b1["gamma"]), np.full(c, np.sqrt(1.0 + eps1))]),
+            "beta": np.concatenate([_f64(b1["beta"]), np.zeros(c)]),
+            "mean": np.concatenate([_f64(b1["mean"]), np.zeros(c)]),
+            "var": np.concatenate([_f64(b1["var"]), np.ones(c)]),
+            "eps": eps1}
+
+    omega2, _ = _omega_lambda(b2)
+    if np.any(omega2 == 0.0):
+        raise ZeroDivisionError("the batch norm after conv2 has a zero scale")
+    aux_f = np.zeros((k2, c, r, s_))
+    beta2 = _f64(b2["beta"]).copy()
+    if sc["kind"] in ("identity", "optionA"):
+        assert c <= k2 and (sc["kind"] == "optionA" or c == k2)
+        assert c1["stride"] == (sc["stride"] if sc["kind"] == "optionA" else 1)
+        aux_f[np.arange(c), np.arange(c), cr, cs] = 1.0 / omega2[:c]
+    elif sc["kind"] == "projection":
+        wp = _f64(sc["conv"]["W"])
+        assert wp.shape == (k2, c, 1, 1) and sc["conv"]["pad"] == 0
+        assert sc["conv"]["stride"] == c1["stride"]
+        omega_p, lambda_p = _omega_lambda(sc["bn"])
+        aux_f[:, :, cr, cs] = (omega_p / omega2)[:, None] * wp[:, :, 0, 0]
+        beta2 += lambda_p
+    else:
+        raise ValueError(sc["kind"])
+    w2f = np.concatenate([w2, aux_f], axis=1)
+    bn2f = dict(b2)
+    bn2f["beta"] = beta2
+
+    return {"kind": "basic",
+            "convs": [{"W": w1f, "stride": c1["stride"], "pad": c1["pad"]},
+                      {"W": w2f, "stride": 1, "pad": c2["pad"]}],
+            "bns": [bn1f, bn2f],
+            "prune_permille": [0, 0],
+            "original_filters": [k1, k2],
+            "shortcut": {"kind": "none"}}
+
+
+def aggressive_fuse(model):
+    """The model with every basic block rewritten by aggressive_fuse_block."""
+    out = dict(model)
+    out["blocks"] = [aggressive_fuse_block(b) if b["kind"] == "basic" else b
+                     for b in model["blocks"]]
+    return out
+
+
+# --------------------------------------------------------------------------
 # network
 # --------------------------------------------------------------------------
 
@@ -284,7 +390,9 @@ def forward(model, x, masks=None, merged=False, trace=None):
         convs, bns = blk["convs"], blk["bns"]
         sc = blk["shortcut"]
         k_out = convs[-1]["W"].shape[0]
-        if sc["kind"] == "identity":
+        if sc["kind"] == "none":
+            short = None
+        elif sc["kind"] == "identity":
             short = x
         elif sc["kind"] == "optionA":
             short = shortcut_subsample_pad(x, k_out, sc["stride"])
@@ -296,7 +404,8 @@ def forward(model, x, masks=None, merged=False, trace=None):
             y = relu(_conv_bn(h, convs[ci], bns[ci], merged))
             rec(f"b{bi}.conv{ci + 1}", h, None, y)
             h = y
-        y = relu(add(_conv_bn(h, convs[-1], bns[-1], merged), short))
+        y = _conv_bn(h, convs[-1], bns[-1], merged)
+        y = relu(y if short is None else add(y, short))
         rec(f"b{bi}.conv{len(convs)}", h, short, y)
         x = y
     head = model["head"]

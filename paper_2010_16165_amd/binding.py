@@ -27,10 +27,11 @@ _lib = C.CDLL(LIB_PATH)
 # ---- enums ------------------------------------------------------------------
 FUPR_OK = 0
 ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_MASK_EMPTY, ERR_BN_VAR = -1, -2, -3, -4, -5
-ERR_WORKSPACE, ERR_ALIGN, ERR_LAUNCH, ERR_ARG, ERR_LIMIT = -6, -7, -8, -9, -10
+ERR_WORKSPACE, ERR_ALIGN, ERR_LAUNCH, ERR_ARG, ERR_LIMIT, ERR_BN_SCALE = -6, -7, -8, -9, -10, -11
 F32, BF16, F16 = 0, 1, 2
 FUSE_BN, FUSE_RELU, FUSE_ADD = 1, 2, 4
 OP_CONV, OP_MAXPOOL, OP_AVGPOOL = 0, 1, 2
+SHORTCUT_IDENTITY, SHORTCUT_SUBSAMPLE_PAD, SHORTCUT_PROJECTION = 0, 1, 2
 SCHEDULE_AUTO, SCHEDULE_PER_LAYER = 0, 1
 DTYPES = {"f32": F32, "bf16": BF16, "f16": F16}
 
@@ -67,6 +68,16 @@ class GraphDesc(C.Structure):
                 ("n_ops", C.c_int32), ("ops", C.POINTER(OpDesc))]
 
 
+class Bn(C.Structure):
+    _fields_ = [("gamma", C.POINTER(C.c_float)), ("beta", C.POINTER(C.c_float)),
+                ("mean", C.POINTER(C.c_float)), ("var", C.POINTER(C.c_float)), ("eps", C.c_float)]
+
+
+class BnOut(C.Structure):
+    _fields_ = [("gamma", C.POINTER(C.c_float)), ("beta", C.POINTER(C.c_float)),
+                ("mean", C.POINTER(C.c_float)), ("var", C.POINTER(C.c_float))]
+
+
 class OpStats(C.Structure):
     _fields_ = [("flops", C.c_double), ("bytes", C.c_double), ("M", C.c_int64),
                 ("K", C.c_int32), ("C", C.c_int32), ("R", C.c_int32), ("S", C.c_int32),
@@ -83,6 +94,8 @@ _T = C.POINTER(Tensor)
 SIGNATURES = {
     "fupr_status_str": (C.c_char_p, [C.c_int32]),
     "fupr_fold": (C.c_int32, [_SH, _F, _F, _F, _F, _F, _F, C.c_float, C.c_uint32, _F, _F]),
+    "fupr_xconv_fuse": (C.c_int32, [_SH, _F, C.POINTER(Bn), _SH, _F, C.POINTER(Bn), C.c_int32, _SH, _F,
+                                    C.POINTER(Bn), _F, C.POINTER(BnOut), _F, _F]),
     "fupr_prune_count": (C.c_int32, [C.c_int32, C.c_int32]),
     "fupr_select_filters": (C.c_int32, [_SH, _F, C.c_int32, C.c_int32, _U8]),
     "fupr_prune": (C.c_int32, [_SH, _F, _F, _U8, C.c_int32, _SH, C.POINTER(_F), _I32, _I32, _F, _F,
@@ -152,6 +165,44 @@ def fupr_fold(shape, W, conv_bias, gamma, beta, mean, var, eps, fuse_flags):
                         int(fuse_flags), _fp(W_out), _fp(b_out))
     _check(st, "fupr_fold")
     return W_out, b_out
+
+
+def _bn_struct(bn):
+    """(struct, arrays kept alive) for a batch-norm dict of synth.resnets."""
+    arrs = [_f32(bn[k]) for k in ("gamma", "beta", "mean", "var")]
+    return Bn(*[_fp(a) for a in arrs], C.c_float(bn["eps"])), arrs
+
+
+def fupr_xconv_fuse(conv1, bn1, conv2, bn2, shortcut, proj=None, bnp=None):
+    """conv1, conv2, proj: conv dicts {"W", "stride", "pad"}; bn*: batch-norm dicts.
+    Returns (conv1', bn1', conv2', bn2') in the same formats."""
+    W1, W2 = _f32(conv1["W"]), _f32(conv2["W"])
+    s1 = shape_of(W1, conv1["stride"], conv1["pad"])
+    s2 = shape_of(W2, conv2["stride"], conv2["pad"])
+    k1, c, r, s = W1.shape
+    k2 = W2.shape[0]
+    b1, keep1 = _bn_struct(bn1)
+    b2, keep2 = _bn_struct(bn2)
+    sp, Wp, bp, keep_p = None, None, None, None
+    if proj is not None:
+        Wp = _f32(proj["W"])
+        sp = shape_of(Wp, proj["stride"], proj["pad"])
+        bp, keep_p = _bn_struct(bnp)
+    W1_out = np.empty((k1 + c, c, r, s), dtype=np.float32)
+    W2_out = np.empty((k2, k1 + c, r, s), dtype=np.float32)
+    outs = [np.empty(k1 + c, dtype=np.float32) for _ in range(4)]
+    beta2 = np.empty(k2, dtype=np.float32)
+    bo = BnOut(*[_fp(a) for a in outs])
+    st = _lib.fupr_xconv_fuse(C.byref(s1), _fp(W1), C.byref(b1), C.byref(s2), _fp(W2), C.byref(b2),
+                              int(shortcut), None if sp is None else C.byref(sp), _fp(Wp),
+                              None if bp is None else C.byref(bp), _fp(W1_out), C.byref(bo),
+                              _fp(W2_out), _fp(beta2))
+    _check(st, "fupr_xconv_fuse")
+    bn1f = {"gamma": outs[0], "beta": outs[1], "mean": outs[2], "var": outs[3], "eps": bn1["eps"]}
+    bn2f = dict(bn2)
+    bn2f["beta"] = beta2
+    return ({"W": W1_out, "stride": conv1["stride"], "pad": conv1["pad"]}, bn1f,
+            {"W": W2_out, "stride": conv2["stride"], "pad": conv2["pad"]}, bn2f)
 
 
 def fupr_prune_count(n, permille):

@@ -22,6 +22,7 @@ extern "C" const char* fupr_status_str(fupr_status s) {
     case FUPR_ERR_LAUNCH: return "HIP runtime error";
     case FUPR_ERR_ARG: return "invalid argument";
     case FUPR_ERR_LIMIT: return "size exceeds 32-bit indexing";
+    case FUPR_ERR_BN_SCALE: return "batch-norm scale to invert is zero";
     default: return "unknown status";
   }
 }
@@ -66,6 +67,104 @@ extern "C" fupr_status fupr_fold(const fupr_conv_shape* shape, const float* W,
     for (size_t i = 0; i < crs; ++i) dst[i] = (float)(omega[k] * (double)src[i]);
     const double b = conv_bias ? (double)conv_bias[k] : 0.0;
     b_out[k] = (float)(lambda[k] + omega[k] * b);
+  }
+  return FUPR_OK;
+}
+
+namespace {
+
+// omega and lambda of Eq. 3-5 in double; false if var + eps is unusable.
+bool affine_of(const fupr_bn& bn, int K, std::vector<double>* omega, std::vector<double>* lambda) {
+  omega->resize(K);
+  lambda->resize(K);
+  for (int k = 0; k < K; ++k) {
+    const double v = (double)bn.var[k] + (double)bn.eps;
+    if (!(v > 0.0) || !std::isfinite(v)) return false;
+    (*omega)[k] = (double)bn.gamma[k] / std::sqrt(v);
+    (*lambda)[k] = (double)bn.beta[k] - (*omega)[k] * (double)bn.mean[k];
+  }
+  return true;
+}
+
+bool bn_present(const fupr_bn* bn) { return bn && bn->gamma && bn->beta && bn->mean && bn->var; }
+
+}  // namespace
+
+// Sec. IV-B-1 (auxiliary and padded convolutions) and IV-B-2 (batch norms).
+extern "C" fupr_status fupr_xconv_fuse(const fupr_conv_shape* conv1, const float* W1,
+                                       const fupr_bn* bn1, const fupr_conv_shape* conv2,
+                                       const float* W2, const fupr_bn* bn2, int32_t shortcut,
+                                       const fupr_conv_shape* proj, const float* Wp,
+                                       const fupr_bn* bnp, float* W1_out,
+                                       const fupr_bn_out* bn1_out, float* W2_out,
+                                       float* beta2_out) {
+  if (!conv1 || !W1 || !conv2 || !W2 || !W1_out || !W2_out || !beta2_out) return FUPR_ERR_NULL;
+  if (!bn_present(bn1) || !bn_present(bn2)) return FUPR_ERR_NULL;
+  if (!bn1_out || !bn1_out->gamma || !bn1_out->beta || !bn1_out->mean || !bn1_out->var)
+    return FUPR_ERR_NULL;
+  if (shortcut != FUPR_SHORTCUT_IDENTITY && shortcut != FUPR_SHORTCUT_SUBSAMPLE_PAD &&
+      shortcut != FUPR_SHORTCUT_PROJECTION)
+    return FUPR_ERR_ARG;
+  if (!shape_ok(conv1) || !shape_ok(conv2)) return FUPR_ERR_SHAPE;
+  const int k1 = conv1->K, c = conv1->C, R = conv1->R, S = conv1->S, k2 = conv2->K;
+  if (conv2->C != k1 || conv2->R != R || conv2->S != S || R % 2 == 0 || S % 2 == 0 ||
+      conv1->pad != R / 2 || conv1->pad != S / 2 || conv2->pad != conv1->pad || conv2->stride != 1)
+    return FUPR_ERR_SHAPE;
+  if (shortcut == FUPR_SHORTCUT_IDENTITY && (c != k2 || conv1->stride != 1)) return FUPR_ERR_SHAPE;
+  if (shortcut == FUPR_SHORTCUT_SUBSAMPLE_PAD && c > k2) return FUPR_ERR_SHAPE;
+  if (shortcut == FUPR_SHORTCUT_PROJECTION) {
+    if (!proj || !Wp || !bn_present(bnp)) return FUPR_ERR_NULL;
+    if (!shape_ok(proj) || proj->K != k2 || proj->C != c || proj->R != 1 || proj->S != 1 ||
+        proj->pad != 0 || proj->stride != conv1->stride)
+      return FUPR_ERR_SHAPE;
+  }
+  if ((int64_t)(k1 + c) * c * R * S >= (int64_t(1) << 31) ||
+      (int64_t)k2 * (k1 + c) * R * S >= (int64_t(1) << 31))
+    return FUPR_ERR_LIMIT;
+
+  std::vector<double> omega2, lambda2, omega_p, lambda_p;
+  if (!affine_of(*bn2, k2, &omega2, &lambda2)) return FUPR_ERR_BN_VAR;
+  for (int k = 0; k < k2; ++k)
+    if (omega2[k] == 0.0) return FUPR_ERR_BN_SCALE;
+  if (shortcut == FUPR_SHORTCUT_PROJECTION && !affine_of(*bnp, k2, &omega_p, &lambda_p))
+    return FUPR_ERR_BN_VAR;
+  {
+    const double v1 = 1.0 + (double)bn1->eps;
+    if (!(v1 > 0.0) || !std::isfinite(v1)) return FUPR_ERR_BN_VAR;
+  }
+
+  const size_t rs = (size_t)R * S, centre = (size_t)(R / 2) * S + S / 2;
+  // conv1': conv1's filters, then one identity filter per input channel
+  const size_t crs1 = (size_t)c * rs;
+  std::memcpy(W1_out, W1, sizeof(float) * k1 * crs1);
+  std::memset(W1_out + (size_t)k1 * crs1, 0, sizeof(float) * c * crs1);
+  for (int j = 0; j < c; ++j) W1_out[(size_t)(k1 + j) * crs1 + (size_t)j * rs + centre] = 1.0f;
+  // bn1': bn1, then omega = 1, lambda = 0
+  std::memcpy(bn1_out->gamma, bn1->gamma, sizeof(float) * k1);
+  std::memcpy(bn1_out->beta, bn1->beta, sizeof(float) * k1);
+  std::memcpy(bn1_out->mean, bn1->mean, sizeof(float) * k1);
+  std::memcpy(bn1_out->var, bn1->var, sizeof(float) * k1);
+  for (int j = 0; j < c; ++j) {
+    bn1_out->gamma[k1 + j] = (float)std::sqrt(1.0 + (double)bn1->eps);
+    bn1_out->beta[k1 + j] = 0.0f;
+    bn1_out->mean[k1 + j] = 0.0f;
+    bn1_out->var[k1 + j] = 1.0f;
+  }
+  // conv2': conv2's channels, then the auxiliary / padded weights at the centre tap
+  const size_t crs2_in = (size_t)k1 * rs, crs2_out = (size_t)(k1 + c) * rs;
+  for (int k = 0; k < k2; ++k) {
+    float* dst = W2_out + (size_t)k * crs2_out;
+    std::memcpy(dst, W2 + (size_t)k * crs2_in, sizeof(float) * crs2_in);
+    std::memset(dst + crs2_in, 0, sizeof(float) * c * rs);
+    if (shortcut == FUPR_SHORTCUT_PROJECTION) {
+      for (int j = 0; j < c; ++j)
+        dst[crs2_in + (size_t)j * rs + centre] =
+            (float)(omega_p[k] / omega2[k] * (double)Wp[(size_t)k * c + j]);
+      beta2_out[k] = (float)((double)bn2->beta[k] + lambda_p[k]);
+    } else {
+      if (k < c) dst[crs2_in + (size_t)k * rs + centre] = (float)(1.0 / omega2[k]);
+      beta2_out[k] = bn2->beta[k];
+    }
   }
   return FUPR_OK;
 }

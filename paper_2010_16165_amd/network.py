@@ -33,8 +33,28 @@ def _fold(conv, bn):
                        bn["eps"], B.FUSE_BN)
 
 
-def optimise(model, norm=1):
+_SHORTCUTS = {"identity": B.SHORTCUT_IDENTITY, "optionA": B.SHORTCUT_SUBSAMPLE_PAD,
+              "projection": B.SHORTCUT_PROJECTION}
+
+
+def _aggressive(blk):
+    """A basic block after aggressive fusion (Sec. IV-B): two dilated convolutions,
+    no addition.  A fused operator loses n - m filters (Alg. 1), m = its original
+    filter count; that is recorded as an explicit count."""
+    sc = blk["shortcut"]
+    c1, b1, c2, b2 = B.fupr_xconv_fuse(blk["convs"][0], blk["bns"][0], blk["convs"][1], blk["bns"][1],
+                                       _SHORTCUTS[sc["kind"]], sc.get("conv"), sc.get("bn"))
+    k1 = blk["convs"][0]["W"].shape[0]
+    return {"kind": "basic", "convs": [c1, c2], "bns": [b1, b2], "prune_permille": [0, 0],
+            "prune_counts": [c1["W"].shape[0] - k1, 0], "shortcut": {"kind": "none"}}
+
+
+def optimise(model, norm=1, aggressive=False, prune_fused=True):
     """Masks from the raw weights, batch norm merged, masked filters removed.
+
+    aggressive: basic blocks are first rewritten by aggressive fusion; with
+    prune_fused their dilated first operator then loses its n - m lowest-norm
+    filters (Alg. 1), without it the fused model is run as it is.
 
     Returns {"layers": [Layer...], "masks": {(block, conv): uint8 mask},
              "keep_idx": {(block, conv): int32 indices}, "wiring": [...]}
@@ -48,14 +68,19 @@ def optimise(model, norm=1):
         if stem["maxpool"] is not None:
             wiring.append(("maxpool", stem["maxpool"], None))
     for bi, blk in enumerate(model["blocks"]):
+        if aggressive and blk["kind"] == "basic":
+            blk = _aggressive(blk)
+            if not prune_fused:
+                blk["prune_counts"] = [0, 0]
         convs, bns = blk["convs"], blk["bns"]
         folded = [list(_fold(c, b)) for c, b in zip(convs, bns)]
+        counts = blk.get("prune_counts")
         for ci, pm in enumerate(blk["prune_permille"]):
-            if not pm:
+            if not pm and not (counts and counts[ci]):
                 continue
             raw = convs[ci]["W"]
             sh_raw = B.shape_of(raw, convs[ci]["stride"], convs[ci]["pad"])
-            n_prune = B.fupr_prune_count(sh_raw.K, pm)
+            n_prune = counts[ci] if counts else B.fupr_prune_count(sh_raw.K, pm)
             mask = B.fupr_select_filters(sh_raw, raw, norm, n_prune)
             Wp, bp = folded[ci]
             Wn = folded[ci + 1][0]
@@ -76,7 +101,7 @@ def optimise(model, norm=1):
         for ci, (Wf, bf) in enumerate(folded):
             last = ci == len(folded) - 1
             layers.append(Layer(f"b{bi}.conv{ci + 1}", Wf, bf, convs[ci]["stride"], convs[ci]["pad"],
-                                True, add=last))
+                                True, add=last and sc["kind"] != "none"))
         wiring.append(("block", (proj_layer, first, len(folded)), sc))
     head = model["head"]
     if head is not None:
@@ -132,7 +157,9 @@ def build(plan, device="cuda:0"):
             proj, first, n = a
             x = cur
             res, rss = x, 1
-            if sc["kind"] == "projection":
+            if sc["kind"] == "none":
+                res = -1
+            elif sc["kind"] == "projection":
                 res = conv_op(proj, x)
             elif sc["kind"] == "optionA":
                 rss = sc["stride"]

@@ -188,8 +188,8 @@ def test_global_avgpool(fx, dtype):
 
 # ---- whole networks ----------------------------------------------------------------
 
-def run_network(B, network, torch, model, x):
-    plan = network.optimise(model)
+def run_network(B, network, torch, model, x, **options):
+    plan = network.optimise(model, **options)
     m, sites = network.build(plan)
     dt = B.DTYPES[model["dtype"]]
     xd = B.DeviceTensor.from_nchw(x, dt)
@@ -229,6 +229,45 @@ def test_small_network(fx, mi):
         assert np.array_equal(plan["keep_idx"][key], np.flatnonzero(masks[key]))
     err = rel_err(y, ref)
     print(f"model {mi} {model['name']} end-to-end rel err {err:.3e}", flush=True)
+    assert err <= TOL[model["dtype"]]
+
+
+def fusible_models():
+    return [
+        synth.make_cifar_resnet(21, "bf16", 2, 400, widths=(8, 16, 24), size=16, classes=5),
+        synth.make_imagenet_basic_resnet(22, "f16", (1, 2, 1, 1), 300, widths=(8, 16, 16, 24), size=32,
+                                         classes=7),
+    ]
+
+
+@pytest.mark.parametrize("mi", range(2))
+def test_aggressively_fused_network(fx, mi):
+    """Aggressive fusion (Sec. IV-B) through the same kernels: the dilated
+    convolutions without an addition give the oracle's fused model, and (the
+    rewrite being an equivalence) the oracle's original model; with the n - m
+    prune-back of Alg. 1 they give the oracle's fused model with those filters
+    zeroed."""
+    B, network, torch = fx
+    model = fusible_models()[mi]
+    x = synth.make_input(78, 3, model["in_shape"])
+    xr = round_to(x, model["dtype"], torch)
+    fused = orc.aggressive_fuse(model)
+    ref_fused = orc.forward(fused, xr)
+    ref_original = orc.forward(model, xr)
+    plan, m, y = run_network(B, network, torch, model, x, aggressive=True, prune_fused=False)
+    assert not plan["masks"] and not any(L.add for L in plan["layers"])
+    err = rel_err(y, ref_fused)
+    print(f"fused model {mi}: rel err {err:.3e} (vs original {rel_err(y, ref_original):.3e})", flush=True)
+    assert err <= TOL[model["dtype"]]
+    assert rel_err(y, ref_original) <= TOL[model["dtype"]]
+    masks = orc.select_masks(fused)
+    ref_pruned = orc.forward(fused, xr, masks=masks)
+    plan, m, y = run_network(B, network, torch, model, x, aggressive=True)
+    assert set(plan["masks"]) == set(masks)
+    for key in masks:
+        assert np.array_equal(plan["masks"][key], masks[key])
+    err = rel_err(y, ref_pruned)
+    print(f"fused + pruned-back model {mi}: rel err {err:.3e}", flush=True)
     assert err <= TOL[model["dtype"]]
 
 

@@ -36,7 +36,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_status_strings():
-    for code in range(0, -11, -1):
+    for code in range(0, -12, -1):
         assert B.status_str(code) not in ("", "unknown status")
     assert B.status_str(-99) == "unknown status"
 
@@ -387,3 +387,82 @@ def test_baseline_config_graphs_have_expected_launch_counts():
         model, _ = synth.make_config(idx)
         plan = network.optimise(model)
         assert len(plan["layers"]) == n
+
+
+# ---- aggressive fusion (Sec. IV-B) -------------------------------------------------
+
+def fusible_blocks():
+    a = synth.make_cifar_resnet(21, "bf16", 2, 400, widths=(4, 8, 12), size=12, classes=5)
+    b = synth.make_imagenet_basic_resnet(22, "bf16", (1, 2, 1, 1), 300, widths=(4, 8, 8, 12), size=32,
+                                         classes=7)
+    return a["blocks"] + b["blocks"]
+
+
+def test_xconv_fuse_matches_oracle_construction():
+    kinds = set()
+    for blk in fusible_blocks():
+        kinds.add(blk["shortcut"]["kind"])
+        got = network._aggressive(blk)
+        ref = orc.aggressive_fuse_block(blk)
+        for ci in range(2):
+            a, b = got["convs"][ci]["W"], ref["convs"][ci]["W"]
+            assert a.dtype == np.float32 and a.shape == b.shape
+            np.testing.assert_allclose(a, b, rtol=2e-7, atol=0)
+            assert np.array_equal(a == 0, b == 0)
+            for key in ("gamma", "beta", "mean", "var"):
+                np.testing.assert_allclose(got["bns"][ci][key], ref["bns"][ci][key], rtol=2e-7, atol=1e-9)
+        n, m = got["convs"][0]["W"].shape[0], ref["original_filters"][0]
+        assert got["prune_counts"] == [n - m, 0]
+    assert kinds == {"identity", "optionA", "projection"}
+
+
+def test_aggressive_plan_selects_the_oracles_filters():
+    model = synth.make_imagenet_basic_resnet(22, "bf16", (1, 2, 1, 1), 300, widths=(4, 8, 8, 12),
+                                             size=32, classes=7)
+    plan = network.optimise(model, aggressive=True)
+    masks = orc.select_masks(orc.aggressive_fuse(model))
+    assert set(plan["masks"]) == set(masks)
+    for key in masks:
+        assert np.array_equal(plan["masks"][key], masks[key])
+    assert not any(L.add for L in plan["layers"])
+    unpruned = network.optimise(model, aggressive=True, prune_fused=False)
+    assert not unpruned["masks"]
+    k, c = model["blocks"][0]["convs"][0]["W"].shape[:2]
+    by_site = {L.site: L for L in unpruned["layers"]}
+    assert by_site["b0.conv1"].W.shape == (k + c, c, 3, 3)
+    assert by_site["b0.conv2"].W.shape == (k, k + c, 3, 3)
+
+
+def test_xconv_fuse_errors():
+    blk = fusible_blocks()[0]
+    c1, c2 = blk["convs"]
+    b1, b2 = blk["bns"]
+    # a zero scale after conv2 cannot be inverted
+    bad = dict(b2)
+    g = b2["gamma"].copy()
+    g[1] = 0.0
+    bad["gamma"] = g
+    with pytest.raises(B.FuprError) as e:
+        B.fupr_xconv_fuse(c1, b1, c2, bad, B.SHORTCUT_IDENTITY)
+    assert e.value.status == B.ERR_BN_SCALE
+    # var + eps must be positive
+    bad = dict(b2)
+    bad["var"] = -np.ones_like(b2["var"])
+    with pytest.raises(B.FuprError) as e:
+        B.fupr_xconv_fuse(c1, b1, c2, bad, B.SHORTCUT_IDENTITY)
+    assert e.value.status == B.ERR_BN_VAR
+    # unknown shortcut kind, projection without its convolution, mismatched conv2
+    with pytest.raises(B.FuprError) as e:
+        B.fupr_xconv_fuse(c1, b1, c2, b2, 7)
+    assert e.value.status == B.ERR_ARG
+    with pytest.raises(B.FuprError) as e:
+        B.fupr_xconv_fuse(c1, b1, c2, b2, B.SHORTCUT_PROJECTION)
+    assert e.value.status == B.ERR_NULL
+    wrong = {"W": np.zeros((4, 5, 3, 3), np.float32), "stride": 1, "pad": 1}
+    with pytest.raises(B.FuprError) as e:
+        B.fupr_xconv_fuse(c1, b1, wrong, b2, B.SHORTCUT_IDENTITY)
+    assert e.value.status == B.ERR_SHAPE
+    even = {"W": np.zeros((4, 4, 2, 2), np.float32), "stride": 1, "pad": 1}
+    with pytest.raises(B.FuprError) as e:
+        B.fupr_xconv_fuse(even, b1, even, b2, B.SHORTCUT_IDENTITY)
+    assert e.value.status == B.ERR_SHAPE

@@ -401,3 +401,87 @@ def test_baseline_config_channel_counts():
         for bi, ci, pm in synth.prunable_convs(model):
             n = model["blocks"][bi]["convs"][ci]["W"].shape[0]
             assert n - orc.prune_count(n, pm) == table[n]
+
+
+# ---- aggressive operator fusion (Sec. IV-B) -------------------------------------------
+
+def fusible_models():
+    """Basic blocks with each kind of shortcut: identity, subsample + zero-pad,
+    1 x 1 projection."""
+    return [
+        synth.make_cifar_resnet(21, "bf16", 2, 400, widths=(4, 8, 12), size=12, classes=5),
+        synth.make_imagenet_basic_resnet(22, "bf16", (1, 2, 1, 1), 300, widths=(4, 8, 8, 12), size=32,
+                                         classes=7),
+    ]
+
+
+@pytest.mark.parametrize("mi", range(2))
+def test_aggressive_fusion_is_an_equivalence(mi):
+    """The fused model - auxiliary and padded convolutions concatenated, batch
+    norms adjusted, no addition - computes what the original computes
+    (Sec. IV-B: "the output of the neural network remains unchanged").  The
+    original is evaluated by the walker pinned above; a wrong inverse of the
+    batch norm on the filter-wise auxiliary weights, a misplaced identity tap or
+    a lost projection shift all break this."""
+    model = fusible_models()[mi]
+    x = synth.make_input(97, 2, model["in_shape"])
+    fused = orc.aggressive_fuse(model)
+    a = orc.forward(model, x)
+    b = orc.forward(fused, x)
+    np.testing.assert_allclose(a, b, rtol=1e-10, atol=1e-10 * np.abs(a).max())
+    for blk in fused["blocks"]:
+        assert blk["shortcut"]["kind"] == "none"
+
+
+def test_aggressive_fusion_shapes_and_auxiliary_values():
+    """conv1' is (k + c) x c x 3 x 3 and conv2' is k x (k + c) x 3 x 3
+    (Sec. IV-B-1); the channel-wise auxiliary filters are identities with an
+    auxiliary batch norm omega = 1, lambda = 0; the filter-wise auxiliary weights
+    are the inverse of the batch norm after conv2 (Sec. IV-B-2)."""
+    model = fusible_models()[0]
+    blk = model["blocks"][0]                      # identity shortcut
+    k, c = blk["convs"][0]["W"].shape[:2]
+    f = orc.aggressive_fuse_block(blk)
+    w1, w2 = f["convs"][0]["W"], f["convs"][1]["W"]
+    assert w1.shape == (k + c, c, 3, 3) and w2.shape == (k, k + c, 3, 3)
+    assert np.array_equal(w1[:k], blk["convs"][0]["W"]) and np.array_equal(w2[:, :k], blk["convs"][1]["W"])
+    assert np.array_equal(w1[k:], identity_weights(c))
+    bn1 = f["bns"][0]
+    omega_aux = bn1["gamma"][k:] / np.sqrt(bn1["var"][k:] + bn1["eps"])
+    assert np.array_equal(omega_aux, np.ones(c))
+    assert not bn1["beta"][k:].any() and not bn1["mean"][k:].any()
+    b2 = blk["bns"][1]
+    omega2 = b2["gamma"].astype(np.float64) / np.sqrt(b2["var"].astype(np.float64) + b2["eps"])
+    aux = w2[:, k:]
+    assert np.allclose(aux[np.arange(k), np.arange(k), 1, 1] * omega2, 1.0, rtol=1e-15)
+    assert np.count_nonzero(aux) == k
+    assert f["original_filters"] == [k, k]
+
+
+def test_fused_operator_loses_n_minus_m_filters():
+    """Alg. 1: a fused operator with n filters, m of them original, loses its
+    n - m lowest-norm filters; conv2' (n = m) loses none."""
+    model = fusible_models()[1]
+    fused = orc.aggressive_fuse(model)
+    masks = orc.select_masks(fused)
+    for bi, blk in enumerate(fused["blocks"]):
+        n, c = blk["convs"][0]["W"].shape[:2]
+        m = blk["original_filters"][0]
+        assert n - m == c
+        assert int((masks[(bi, 0)] == 0).sum()) == n - m
+        assert (bi, 1) not in masks
+    # the thinner model equals the fused model with those filters zeroed
+    x = synth.make_input(96, 2, model["in_shape"])
+    a = orc.forward(fused, x, masks=masks)
+    b = orc.forward(orc.extract(fused, masks), x)
+    assert np.array_equal(a, b)
+
+
+def test_fusion_needs_an_invertible_batch_norm():
+    blk = dict(fusible_models()[0]["blocks"][0])
+    blk["bns"] = [dict(b) for b in blk["bns"]]
+    g = blk["bns"][1]["gamma"].copy()
+    g[2] = 0.0
+    blk["bns"][1]["gamma"] = g
+    with pytest.raises(ZeroDivisionError):
+        orc.aggressive_fuse_block(blk)
