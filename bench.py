@@ -73,6 +73,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1)
     ap.add_argument("--batch", type=int, default=0)
+    ap.add_argument("--workload", choices=["resnet20", "resnet32", "resnet18", "resnet34"],
+                    help="one of the paper's own networks (Table II) instead of --config; "
+                         "batch 1 unless --batch is given (Tables V-VI are batch-1 latencies)")
+    ap.add_argument("--permille", type=int, default=300, help="pruning rate of --workload")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--schedule", choices=["auto", "per-layer"], default="auto")
     ap.add_argument("--aggressive", choices=["off", "fused", "fused-pruned"], default="off",
@@ -95,7 +99,11 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
-    model, batch = synth.make_config(args.config)
+    if args.workload:
+        model, batch = synth.make_paper_workload(args.workload, args.permille), 1
+        args.config = -1
+    else:
+        model, batch = synth.make_config(args.config)
     if args.batch:
         batch = args.batch
     dt = B.DTYPES[model["dtype"]]
@@ -104,7 +112,7 @@ def main():
     fm, sites = network.build(plan)
     if args.schedule == "per-layer":
         fm.set_schedule(B.SCHEDULE_PER_LAYER)
-    x = synth.make_input(synth.BASE_SEED + args.config, batch, model["in_shape"])
+    x = synth.make_input(synth.BASE_SEED + max(args.config, 0), batch, model["in_shape"])
     xd = B.DeviceTensor.from_nchw(x, dt)
 
     stream = torch.cuda.Stream()

@@ -121,6 +121,10 @@ constexpr int kResMean = 1, kResRelu = 2, kResLast = 4, kResZeroHalo = 8;
 // layer, no pixel tile is ragged, and the output's strides are the input's.
 // kResLikeOut: the shortcut tensor has the output's strides.
 constexpr int kResFullPixels = 16, kResReuse = 32, kResLikeOut = 64, kResFullFilters = 128;
+// An entry with n_items = 0 and no flag is not a layer of the network: it only
+// stages the parameters of the entry after it (no wave has a work item, so all
+// stage).  The planner puts one in front of a layer whose parameters find no
+// room in LDS during the layer before it.
 constexpr int kResTablePad = 8;   // steps of padding after a tap table (2 * deepest prefetch)
 
 struct ResParams {

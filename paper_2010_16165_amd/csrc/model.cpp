@@ -259,6 +259,20 @@ void plan_resident(fupr_model* m) {
   std::stable_sort(candidates.begin(), candidates.end(),
                    [](const auto& a, const auto& b) { return a.first < b.first; });
 
+  // Parameter blocks by size, largest first: when nothing fits with every
+  // layer's parameters staged one layer ahead, the largest ones are staged at
+  // the start of their own layer instead (their global-memory latency is then
+  // exposed, but they need LDS for one layer only).
+  std::vector<int> by_size;
+  for (int i = 1; i < n; ++i)
+    if (m->ops[i].kind == FUPR_OP_CONV) by_size.push_back(i);
+  std::stable_sort(by_size.begin(), by_size.end(), [&](int a, int b) {
+    return packed_layout(m->ops[a].conv, m->dt).total_bytes >
+           packed_layout(m->ops[b].conv, m->dt).total_bytes;
+  });
+  for (size_t n_late = 0; n_late <= by_size.size(); ++n_late) {
+  std::vector<char> late(n, 0);
+  for (size_t j = 0; j < n_late; ++j) late[by_size[j]] = 1;
   for (const auto& cand : candidates) {
     std::vector<int> ps2(n + 1);
     for (int tid = 0; tid <= n; ++tid) {
@@ -280,7 +294,7 @@ void plan_resident(fupr_model* m) {
     bool ok = true;
     for (int i = 0; i < n && ok; ++i) {
       LdsBlock& b = blocks[n + 1 + i];
-      b.first = i - 1;                         // lands while layer i-1 is running
+      b.first = late[i] ? i : i - 1;           // lands while layer i-1 is running, unless late
       b.last = i;
       b.units = 0;
       if (m->ops[i].kind == FUPR_OP_CONV) {
@@ -296,7 +310,8 @@ void plan_resident(fupr_model* m) {
       for (int c = 0; c < k; ++c)
         std::fprintf(stderr, " %dx%d:%d", classes[c].H, classes[c].W,
                      lds_pixel_stride(classes[c].cs, cand.second[c]));
-      std::fprintf(stderr, " -> %zu bytes (limit %zu)\n", extent * 16, budget_units * 16);
+      std::fprintf(stderr, " late %zu -> %zu bytes (limit %zu)\n", n_late, extent * 16,
+                   budget_units * 16);
     }
     if (extent > budget_units) continue;
 
@@ -338,7 +353,6 @@ void plan_resident(fupr_model* m) {
     R.in_ps2 = ps2[0];
     R.in_org = pixel_at(0, halo_of(t0), halo_of(t0));
     R.hp = hp;
-    R.n_layers = n;
     R.lds_bytes = (int)(kResScratchBytes + extent * 16);
     R.out_pixels = m->tensors[n].H * m->tensors[n].W;
     write_interior(0);
@@ -347,16 +361,26 @@ void plan_resident(fupr_model* m) {
 
     std::array<int, 8> prev_geometry;
     prev_geometry.fill(-1);
-    m->res_layers.assign(n, ResLayer{});
+    m->res_layers.clear();
     m->res_tables.clear();
-    m->res_table_at.assign(n, 0);
+    m->res_table_at.clear();
     for (int i = 0; i < n; ++i) {
       const fupr_op_desc& op = m->ops[i];
       const TensorInfo& ti = m->tensors[op.in];
       const TensorInfo& to = m->tensors[i + 1];
       const bool last = i + 1 == n;
       ResLayer L{};
+      size_t table_at = 0;
       L.flags = last ? kResLast : 0;
+      if (late[i]) {
+        // an entry that does nothing but stage this layer's parameters
+        ResLayer stage{};
+        stage.res_org = -1;
+        stage.MT = stage.NT = stage.n_fgroups = stage.Q = stage.M = 1;   // a conv entry without work items
+        m->res_layers.push_back(stage);
+        m->res_table_at.push_back(0);
+        if (blocks[n + 1 + i].units) mark(blocks[n + 1 + i].offset, blocks[n + 1 + i].units, 0);
+      }
       L.res_org = -1;
       L.out_org = last ? 0 : pixel_at(i + 1, halo_of(to), halo_of(to));
       L.cs_out = to.cs;
@@ -423,7 +447,7 @@ void plan_resident(fupr_model* m) {
         // tap table: LDS byte offset of every chunk of output pixel (0, 0)'s
         // window; padding chunks (zero weights) and the padding steps after the
         // last one re-read the first chunk: finite data
-        m->res_table_at[i] = m->res_tables.size();
+        table_at = m->res_tables.size();
         for (int j = 0; j < L.tab_units * 4; ++j) {
           int32_t e = 0;
           if (j < PL.nchunk) {
@@ -453,17 +477,23 @@ void plan_resident(fupr_model* m) {
         if (halo_of(to) > 0) write_interior(i + 1);
         else mark(blocks[home[i + 1]].offset, blocks[home[i + 1]].units, 0);
       }
-      if (i + 1 < n && blocks[n + 2 + i].units) mark(blocks[n + 2 + i].offset, blocks[n + 2 + i].units, 0);
-      m->res_layers[i] = L;
+      if (i + 1 < n && !late[i + 1] && blocks[n + 2 + i].units)
+        mark(blocks[n + 2 + i].offset, blocks[n + 2 + i].units, 0);
+      m->res_layers.push_back(L);
+      m->res_table_at.push_back(table_at);
       if (std::getenv("FUPR_DEBUG"))
         std::fprintf(stderr, "resident layer %d: M %d FT %d steps %d item %dx%d items %d ps2 in %d out %d "
                      "zero_halo %d res %d\n", i, L.M, L.FT, L.nsteps, L.MT, L.NT, L.n_items, ps2[op.in],
                      ps2[i + 1], (L.flags & kResZeroHalo) != 0, L.res_org >= 0);
     }
+    if (m->res_layers.size() > (size_t)kResMaxLayers) return;
+    R.n_layers = (int)m->res_layers.size();
     if (std::getenv("FUPR_DEBUG"))
-      std::fprintf(stderr, "resident plan: %d bytes of LDS\n", R.lds_bytes);
+      std::fprintf(stderr, "resident plan: %d bytes of LDS, %d table entries for %d layers\n",
+                   R.lds_bytes, R.n_layers, n);
     m->resident_ok = true;
     return;
+  }
   }
 }
 

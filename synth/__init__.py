@@ -14,5 +14,7 @@ from .resnets import (  # noqa: F401
     make_imagenet_basic_resnet,
     make_imagenet_bottleneck_resnet,
     make_input,
+    make_paper_workload,
+    PAPER_WORKLOADS,
     prunable_convs,
 )

@@ -205,6 +205,28 @@ def make_config(index):
     return m, _DEFAULT_BATCH[index]
 
 
+# The networks the paper itself measures (Table II; Tables V-VI are latencies at
+# batch 1): seeds BASE_SEED + 10 + position in this list.
+PAPER_WORKLOADS = ["resnet20", "resnet32", "resnet18", "resnet34"]
+
+
+def make_paper_workload(name, permille=300, dtype="bf16"):
+    """ResNet-20 / 32 on 32 x 32 images, ResNet-18 / 34 on 224 x 224 images, every
+    block's first convolution pruned at `permille` (the paper's rates are 0, 100,
+    200, 300)."""
+    seed = BASE_SEED + 10 + PAPER_WORKLOADS.index(name)
+    if name == "resnet20":
+        m = make_cifar_resnet(seed, dtype, 3, permille)
+    elif name == "resnet32":
+        m = make_cifar_resnet(seed, dtype, 5, permille)
+    elif name == "resnet18":
+        m = make_imagenet_basic_resnet(seed, dtype, (2, 2, 2, 2), permille)
+    else:
+        m = make_imagenet_basic_resnet(seed, dtype, (3, 4, 6, 3), permille)
+    m["name"] = f"{name}-{dtype}-p{permille}"
+    return m
+
+
 def make_input(seed, batch, in_shape, first=0):
     """Images first..first+batch-1 of the stream, NCHW float32, x ~ N(0, 1).
 

@@ -271,6 +271,37 @@ def test_aggressively_fused_network(fx, mi):
     assert err <= TOL[model["dtype"]]
 
 
+@pytest.mark.parametrize("name", synth.PAPER_WORKLOADS)
+def test_paper_workload_at_batch_one(fx, name):
+    """The networks the paper measures (Table II) in the setting it measures them
+    in (one image, Tables V-VI), against the oracle."""
+    B, network, torch = fx
+    model = synth.make_paper_workload(name)
+    x = synth.make_input(79, 1, model["in_shape"])
+    masks = orc.select_masks(model)
+    ref = orc.forward(model, round_to(x, model["dtype"], torch), masks=masks)
+    plan, m, y = run_network(B, network, torch, model, x)
+    assert m.num_launches == (1 if name in ("resnet20", "resnet32") else m.num_ops)
+    err = rel_err(y, ref)
+    print(f"{model['name']}: rel err {err:.3e}", flush=True)
+    assert err <= TOL[model["dtype"]]
+
+
+def test_unpruned_cifar_network_stays_in_one_kernel(fx):
+    """Unpruned ResNet-20: the 64 x 64 x 3 x 3 parameter blocks of the last stage do
+    not fit LDS twice, so those layers stage their parameters at their own start;
+    the network still runs as one kernel and matches the oracle."""
+    B, network, torch = fx
+    model = synth.make_paper_workload("resnet20", permille=0)
+    x = synth.make_input(80, 3, model["in_shape"])
+    ref = orc.forward(model, round_to(x, model["dtype"], torch))
+    plan, m, y = run_network(B, network, torch, model, x)
+    assert m.num_launches == 1
+    err = rel_err(y, ref)
+    print(f"{model['name']}: rel err {err:.3e}", flush=True)
+    assert err <= TOL[model["dtype"]]
+
+
 CONFIG_BATCH = {0: 1, 1: 8, 2: 2, 3: 2, 4: 2}
 
 
