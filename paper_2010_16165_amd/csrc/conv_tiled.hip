@@ -254,19 +254,25 @@ int forced_tile() {
 // every layer shape of the ResNet-18 and ResNet-50 workloads (the layers are
 // bound by memory latency, not MFMA issue, so mid-size tiles with several
 // workgroups per compute unit win over the largest ones):
-//   filters per workgroup: 16 * nt, nt from {1, 2, 3, 4, 6} with the fewest
-//       padded filter tiles over all filter groups, the larger nt on a tie;
+//   filters per workgroup: 16 * nt, nt from {1, 2, 3, 4, 6} with the least padded
+//       work, narrow workgroups weighted up (see below), the larger nt on a tie;
 //   pixels per workgroup: 128, or 64 when 128 would leave fewer than 128 workgroups.
 int choose_tile(int FT, int nsteps, int64_t M) {
   (void)nsteps;
   const int f = forced_tile();
   if (f >= 0) return f;
+  // filter tiles per workgroup: least padded work, where a workgroup of 1 (2)
+  // filter tiles costs about 1.5 (1.2) times as much per tile as a wider one
+  // (each pixel fragment it loads feeds that many fewer MFMAs)
   static const int nts[] = {1, 2, 3, 4, 6};
-  int nt = 1, best_waste = 1 << 30;
-  for (int c : nts) {
-    const int groups = (FT + c - 1) / c, waste = groups * c - FT;
-    if (waste < best_waste || (waste == best_waste && c > nt)) {
-      best_waste = waste;
+  static const double cost[] = {1.5, 1.2, 1.0, 1.0, 1.0};
+  int nt = 1;
+  double best = 1e30;
+  for (int i = 0; i < 5; ++i) {
+    const int c = nts[i], groups = (FT + c - 1) / c;
+    const double score = groups * c * cost[i];
+    if (score < best - 1e-9 || (score < best + 1e-9 && c > nt)) {
+      best = score;
       nt = c;
     }
   }
