@@ -152,19 +152,23 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const PoolParams p) {
   }
 }
 
-// One thread: one image x one channel chunk, sequential fp32 sum over pixels.
+// Global mean.  A workgroup is 32 (image, channel chunk) pairs x 8 parts: part k
+// sums pixels k, k + 8, ... in fp32, the 8 partial sums are then added in order.
+constexpr int kPoolParts = 8;
 template <int DT>
 __global__ __launch_bounds__(256) void avgpool_kernel(const PoolParams p) {
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= p.total) return;
-  const int ch = (int)(idx % p.chunks);
-  const int n = (int)(idx / p.chunks);
   constexpr int V = DT == 0 ? 4 : 8;
+  __shared__ float partial[kPoolParts][32][V];
+  const int slot = threadIdx.x & 31, part = threadIdx.x >> 5;
+  const int64_t idx = (int64_t)blockIdx.x * 32 + slot;
+  const bool live = idx < p.total;
+  const int ch = live ? (int)(idx % p.chunks) : 0;
+  const int n = live ? (int)(idx / p.chunks) : 0;
   float acc[V];
 #pragma unroll
   for (int i = 0; i < V; ++i) acc[i] = 0.f;
   const int hw = p.H * p.W;
-  for (int i = 0; i < hw; ++i) {
+  for (int i = part; live && i < hw; i += kPoolParts) {
     const int64_t off = ((int64_t)n * hw + i) * p.cs + ch * V;
     if constexpr (DT == 0) {
       const float4 v = *reinterpret_cast<const float4*>((const float*)p.x + off);
@@ -181,6 +185,17 @@ __global__ __launch_bounds__(256) void avgpool_kernel(const PoolParams p) {
         acc[2 * j + 1] += to_float<DT == 1>((uint16_t)(u[j] >> 16));
       }
     }
+  }
+#pragma unroll
+  for (int i = 0; i < V; ++i) partial[part][slot][i] = acc[i];
+  __syncthreads();
+  if (part != 0 || !live) return;
+#pragma unroll
+  for (int i = 0; i < V; ++i) {
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < kPoolParts; ++k) s += partial[k][slot][i];
+    acc[i] = s;
   }
   const float inv = (float)hw;
 #pragma unroll
@@ -388,7 +403,7 @@ extern "C" fupr_status fupr_global_avgpool(const fupr_tensor* x, const fupr_tens
   p.chunks = y->c_stride / c_align(x->dt);
   p.total = (int64_t)x->N * p.chunks;
   hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
-  dim3 grid((unsigned)((p.total + 255) / 256));
+  dim3 grid((unsigned)((p.total + 31) / 32));
   if (x->dt == FUPR_F32) hipLaunchKernelGGL(avgpool_kernel<0>, grid, dim3(256), 0, hs, p);
   else if (x->dt == FUPR_BF16) hipLaunchKernelGGL(avgpool_kernel<1>, grid, dim3(256), 0, hs, p);
   else hipLaunchKernelGGL(avgpool_kernel<2>, grid, dim3(256), 0, hs, p);
