@@ -227,10 +227,29 @@ fupr_status launch_status(const char* what) {
   return FUPR_ERR_LAUNCH;
 }
 
-const char* conv_kernel_name(const fupr_conv_shape& s, fupr_dtype dt, int64_t M) {
-  if (dt == FUPR_F32) return "conv32_direct";
+namespace {
+
+// Geometry of a 16-bit convolution as the kernels take it.
+Conv16Params geometry16(const fupr_conv_shape& s, fupr_dtype dt, int N, int H, int W) {
   const PackedLayout L = packed_layout(s, dt);
-  return conv16_tiled_name(L.Kp / 16, L.nchunk_pad / 4, M);
+  Conv16Params p{};
+  p.H = H; p.W = W;
+  p.P = out_extent(H, s.R, s.stride, s.pad);
+  p.Q = out_extent(W, s.S, s.stride, s.pad);
+  p.PQ = p.P * p.Q;
+  p.M = (int)((int64_t)N * p.PQ);
+  p.S = s.S; p.stride = s.stride; p.pad = s.pad;
+  p.Kp = L.Kp; p.FT = L.Kp / 16; p.cpt = L.Cp / 8; p.nchunk = L.nchunk; p.nsteps = L.nchunk_pad / 4;
+  return p;
+}
+
+}  // namespace
+
+const char* conv_kernel_name(const fupr_conv_shape& s, fupr_dtype dt, int N, int H, int W) {
+  if (dt == FUPR_F32) return "conv32_direct";
+  const Conv16Params g = geometry16(s, dt, N, H, W);
+  if (s.R == 3 && conv_patch_applies(g)) return conv_patch_name(g);
+  return conv16_tiled_name(g.FT, g.nsteps, g.M);
 }
 
 fupr_status launch_conv(const ConvArgs& a, void* stream) {
@@ -270,6 +289,7 @@ fupr_status launch_conv(const ConvArgs& a, void* stream) {
   p.relu = a.relu;
   p.x_bytes = (uint32_t)((int64_t)a.N * a.H * a.W * a.xcs * 2);
   p.w_bytes = (uint32_t)((size_t)L.nchunk_pad * L.Kp * 16);
+  if (a.R == 3 && conv_patch_applies(p)) return launch_conv_patch(p, a.N, a.dt == FUPR_BF16, stream);
   return launch_conv16_tiled(p, a.dt == FUPR_BF16, stream);
 }
 

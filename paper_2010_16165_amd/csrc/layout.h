@@ -64,7 +64,7 @@ struct ConvArgs {
   fupr_dtype dt;
 };
 fupr_status launch_conv(const ConvArgs& a, void* stream);
-const char* conv_kernel_name(const fupr_conv_shape& s, fupr_dtype dt, int64_t M);
+const char* conv_kernel_name(const fupr_conv_shape& s, fupr_dtype dt, int N, int H, int W);
 
 // ---- whole network in one kernel, activations resident in LDS ----------------
 // One workgroup per image walks a table of layers; see resident.hip.

@@ -835,7 +835,7 @@ extern "C" fupr_status fupr_model_op_stats(const fupr_model* m, int32_t batch, i
     double res_b = 0.0;
     if (d.res >= 0) res_b = es * (double)s.M * m->tensors[d.res].C;
     s.bytes = in_b + out_b + res_b + es * crs * d.conv.K + 4.0 * d.conv.K;
-    s.kernel = conv_kernel_name(d.conv, m->dt, s.M);
+    s.kernel = conv_kernel_name(d.conv, m->dt, batch, ti.H, ti.W);
   } else {
     s.R = s.S = d.kind == FUPR_OP_MAXPOOL ? d.conv.R : ti.H;
     s.stride = d.kind == FUPR_OP_MAXPOOL ? d.conv.stride : 1;

@@ -358,7 +358,7 @@ def test_model_plan_shares_buffers_and_reports_shapes():
     s = m.op_stats(2, 2)
     assert s["flops"] == 2.0 * 10 * 9 * 16 * 2 * 1024
     assert s["bytes"] == 2 * (2 * 1024 * 10 + 2 * 1024 * 16 + 2 * 1024 * 16 + 16 * 10 * 9) + 4 * 16
-    assert s["kernel"].startswith("conv16")
+    assert s["kernel"].startswith("conv")
 
 
 def test_model_create_errors():
