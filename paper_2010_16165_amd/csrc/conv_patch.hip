@@ -182,26 +182,32 @@ __global__ __launch_bounds__(kPatchThreads) void conv_patch_kernel(const PatchPa
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
-    // 9 taps = 9 MFMA steps over these 32 channels
+    // 9 taps = 9 MFMA steps over these 32 channels; the operands of a step are
+    // read while the step before it is multiplied
+    int brow[3][MT];
 #pragma unroll
-    for (int r = 0; r < 3; ++r) {
-      int brow[MT];
+    for (int r = 0; r < 3; ++r)
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) brow[mt] = rin[mt] + r * row_bytes;
+      for (int mt = 0; mt < MT; ++mt) brow[r][mt] = rin[mt] + r * row_bytes;
+    uint4 a[2][NT], b[2][MT];
+    auto operands = [&](int tap, uint4* av, uint4* bv) {
+      const int r = tap / 3, sx = tap - r * 3;
 #pragma unroll
-      for (int s = 0; s < 3; ++s) {
-        uint4 a[NT], b[MT];
+      for (int mt = 0; mt < MT; ++mt)
+        bv[mt] = *reinterpret_cast<const uint4*>(patch + brow[r][mt] + sx * 32);
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          b[mt] = *reinterpret_cast<const uint4*>(patch + brow[mt] + s * 32);
+      for (int t = 0; t < NT; ++t)
+        av[t] = *reinterpret_cast<const uint4*>(wts + a_lane + tap * kWStep + t * 256);
+    };
+    operands(0, a[0], b[0]);
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) {
+      if (tap + 1 < 9) operands(tap + 1, a[(tap + 1) & 1], b[(tap + 1) & 1]);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int t = 0; t < NT; ++t)
-          a[t] = *reinterpret_cast<const uint4*>(wts + a_lane + (r * 3 + s) * kWStep + t * 256);
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-          for (int t = 0; t < NT; ++t) acc[mt][t] = mfma_16x16x32<BF>(a[t], b[mt], acc[mt][t]);
-      }
+          acc[mt][t] = mfma_16x16x32<BF>(a[tap & 1][t], b[tap & 1][mt], acc[mt][t]);
     }
   }
 
