@@ -27,9 +27,10 @@ const char* conv16_tiled_name(int FT, int nsteps, int64_t M);
 
 // conv_patch.hip: 3 x 3 convolutions with the workgroup's input patch in LDS.
 // Geometry fields of the argument only (H, W, P, Q, PQ, S, stride, pad, cpt,
-// nchunk, FT, Kp) decide whether it applies and which tile it runs.
-bool conv_patch_applies(const Conv16Params& geometry);
-const char* conv_patch_name(const Conv16Params& geometry);
+// nchunk, FT, Kp) and the batch size decide whether it applies and which tile
+// it runs.
+bool conv_patch_applies(const Conv16Params& geometry, int N);
+const char* conv_patch_name(const Conv16Params& geometry, int N);
 fupr_status launch_conv_patch(const Conv16Params& p, int N, bool bf16, void* stream);
 
 }  // namespace fupr

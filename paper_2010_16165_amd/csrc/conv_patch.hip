@@ -2,20 +2,38 @@
 // a workgroup staged in LDS (Sec. III, Sec. IV-B-1: operator k x c x 3 x 3; the
 // epilogue applies what Sec. VI-B-3 merges and the block's addition and ReLU).
 //
-// The tiled kernel loads every pixel fragment from global memory once per tap
-// with its own range check; its instruction stream (7.6 vector + 3.3 scalar
-// instructions per MFMA on the ResNet-18 layers) bounds it, not the MFMAs.
-// Here a workgroup owns a strip of consecutive output pixels of one image
-// and a group of filters, and walks the input channels 32 at a time:
-//   * the strip's input rows, full width plus a column of zeros on each side,
-//     go global -> LDS for those 32 channels (two planes of 16 channels, pixel
-//     stride 32 bytes: the stride at which 16-byte-per-lane reads run at full
-//     rate), rows outside the image are zeros written once;
-//   * the 9 x 4 weight chunks of the filter group go global -> LDS;
-//   * every tap is then one MFMA 16x16x32 step whose pixel fragment is an LDS
-//     read at (pixel base + row offset) + immediate column offset: 3 address
-//     additions per pixel tile per 9 steps, no range checks.
-// Two workgroups share a compute unit, so one computes while the other stages.
+// GEMM view as in the other kernels: rows = filters (MFMA operand A), columns =
+// output pixels (operand B), reduction over (32-channel stage, tap).
+//
+//   * The batch is one tall image: image n occupies rows n*Hv + 1 .. n*Hv + H of
+//     a virtual input with Hv = H + stride rows per image; the rows between
+//     images are zero and serve as the padding of both neighbours.  Output
+//     rows are numbered the same way (Pv = P + 1 per image; the extra row is
+//     computed and not stored), so a tile is a run of BM consecutive virtual
+//     output pixels wherever image boundaries fall, and small images fill
+//     their tiles.
+//   * A tile's input rows, full width plus a zero column on each side, go
+//     global -> LDS 32 channels at a time (two planes of 16 channels, pixel
+//     stride 32 bytes: the stride at which 16-byte-per-lane LDS reads run at
+//     full rate; for stride 2 even and odd columns are stored apart so that
+//     consecutive output pixels still read consecutive slots).  The loads are
+//     range-checked buffer loads that write LDS directly: everything outside
+//     the image or the tensor arrives as zeros, all lanes always load.
+//   * The 9 x 4 weight chunks of the stage for the tile's filters travel the
+//     same way; when one filter group covers the layer and all stages' weights
+//     fit beside the patch buffers they are loaded once and stay.
+//   * Waves are specialised: four loading waves issue the global -> LDS loads
+//     of the next unit while the computing waves multiply the current one, so
+//     that a computing wave never waits for room in the vector memory queue
+//     with its MFMAs behind it.  Units (tile, stage) are double buffered; one
+//     barrier per unit joins the two kinds of waves.
+//   * A workgroup is persistent: it walks a contiguous range of tiles, and the
+//     sequence (tile, stage) is one pipeline, so that the first loads of the
+//     next tile fly during the last stage and the epilogue of the current one.
+//   * Every tap is one MFMA 16x16x32 step whose pixel fragment is an LDS read at
+//     (pixel base + row offset + column offset); no range checks in the loop.
+//     The accumulators start at zero and the bias joins in the epilogue, so the
+//     computing waves touch global memory only there.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -31,9 +49,9 @@
 namespace fupr {
 namespace {
 
-constexpr int kPatchThreads = 256;
-constexpr int kPatchWaves = 4;
-constexpr int kMaxPatchLoads = 12;   // 16-byte slots of the patch per thread and stage
+constexpr int kMaxPatchLoads = 12;          // 16-byte slots of the patch per thread and stage
+constexpr uint32_t kOutside = 0x80000000u;  // beyond every tensor this kernel accepts
+constexpr size_t kPatchLdsLimit = 160 * 1024;
 
 struct PatchParams {
   const uint16_t* x;
@@ -41,163 +59,266 @@ struct PatchParams {
   const float* bias;
   const uint16_t* res;
   uint16_t* y;
-  int H, W, xcs;
-  int P, Q, PQ, ycs;
+  uint32_t x_bytes, w_bytes, y_bytes, res_bytes;
+  int N, H, W, xcs;
+  int P, Q, ycs;
+  int Hv, Pv, Mv;        // virtual rows per image (input, output); virtual output pixels
   int stride;
   int Kp, cpt, n_stages;
   int rH, rW, rcs, rss, roff;
   int relu;
-  int strips;            // per image
-  int PR, Wh;            // patch rows; patch columns = W + 2
+  int PR, Wh, Whh;       // patch rows; slots per patch row (W + 2); even columns per row
   int plane_bytes;       // PR * Wh * 32
   int patch_slots;       // 2 planes * PR * Wh * 2 halves
-  int n_loads;           // ceil(patch_slots / 256)
-  uint32_t magicQ, magicWh, magicPR;
+  int n_loads;           // patch loads per thread and stage
+  int tap1, tap2;        // byte offsets of the second and third tap of a row
+  int w_resident;        // all stages' weights stay in LDS (one filter group only)
+  int patch_base;        // LDS byte offset of patch buffer 0
+  int buf_stride;        // bytes from buffer 0 to buffer 1
+  int fgroups, tiles;
+  uint32_t magicQ, magicWh, magicPR, magicHv, magicPv;
 };
 
 __device__ __forceinline__ int div_by(int v, uint32_t magic) {
   return magic ? (int)__umulhi((uint32_t)v, magic) : v;
 }
 
-// lane i moves 16 bytes from src_base + lane_offset to the i-th slot after lds_base
-__device__ __forceinline__ void load_to_lds(const void* src_base, uint32_t lane_offset,
-                                            uint32_t lds_base) {
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+// lane i moves the 16 bytes at offset off of the buffer to the i-th slot after
+// lds_base; an offset outside the buffer writes zeros
+__device__ __forceinline__ void load_to_lds(const i32x4& rsrc, uint32_t off, uint32_t lds_base) {
   asm volatile(
       "s_mov_b32 m0, %0\n\t"
       "s_nop 0\n\t"
-      "global_load_lds_dwordx4 %1, %2"
+      "buffer_load_dwordx4 %1, %2, 0 offen lds"
       :
-      : "s"(lds_base), "v"(lane_offset), "s"(src_base)
+      : "s"(lds_base), "v"(off), "s"(rsrc)
       : "memory", "m0");
+}
+
+__device__ __forceinline__ i32x4 make_rsrc(const void* base, uint32_t bytes) {
+  const uint64_t a = reinterpret_cast<uint64_t>(base);
+  i32x4 r;
+  r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+  r[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32));
+  r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+  r[3] = 0x00020000;
+  return r;
 }
 
 typedef void __attribute__((address_space(3)))* LdsPtr;
 typedef short short2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ uint32_t clamp_below(uint32_t v, uint32_t floor2) {
   const short2_t a = __builtin_bit_cast(short2_t, v), f = __builtin_bit_cast(short2_t, floor2);
   return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(a, f));
 }
 
-// MT pixel tiles x NT filter tiles of 16 x 16 per wave; the 4 waves of a
-// workgroup sit side by side along the pixels: 64 * MT pixels x 16 * NT filters.
-template <bool BF, int MT, int NT>
-__global__ __launch_bounds__(kPatchThreads) void conv_patch_kernel(const PatchParams p) {
-  constexpr int NF = NT * 16;
-  constexpr int BM = kPatchWaves * MT * 16;
-  constexpr int kWeightSlots = 36 * NF;                              // 9 taps x 4 chunks x NF filters
-  constexpr int kWeightLoads = (kWeightSlots + kPatchThreads - 1) / kPatchThreads;
-  constexpr int kWStep = 4 * NF * 16;                                // bytes of weights per tap
+constexpr int kLoaderWaves = 4;
+
+// WM x WN computing waves, each owning MT pixel tiles x NT filter tiles of
+// 16 x 16, and kLoaderWaves loading waves.  The computing waves issue only LDS
+// reads and MFMAs in the main loop (a wave that waits for room in the vector
+// memory queue cannot issue its MFMAs); the loading waves move the next unit's
+// weights and patch global -> LDS meanwhile.  One barrier per unit joins them.
+template <bool BF, int WM, int WN, int MT, int NT>
+__global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kernel(
+    const PatchParams p) {
+  constexpr int NWC = WM * WN;
+  constexpr int NL = kLoaderWaves * 64;                        // loading threads
+  constexpr int NF = WN * NT * 16;
+  constexpr int BM = WM * MT * 16;
+  constexpr int kWeightSlots = 36 * NF;                        // 9 taps x 4 chunks x NF filters
+  constexpr int kWeightLoads = (kWeightSlots + NL - 1) / NL;
+  constexpr int kWeightBytes = kWeightLoads * NL * 16;
+  constexpr int kWStep = 4 * NF * 16;                          // bytes of weights per tap
   extern __shared__ uint4 lds4[];
   char* lds = reinterpret_cast<char*>(lds4);
-  char* wts = lds;                                                   // [36][NF][16 bytes]
-  char* patch = lds + kWeightSlots * 16;                             // [2][PR][Wh][32 bytes]
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(LdsPtr)lds;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int li = lane & 15, g = lane >> 4;
-  const int n = blockIdx.x / p.strips, strip = blockIdx.x - n * p.strips;
-  const int f0 = blockIdx.y * NF;
-  const int m0 = strip * BM;                          // first output pixel of the strip
-  const int p_lo = div_by(m0, p.magicQ);              // its output row
-  const int in_row0 = p_lo * p.stride - 1;            // image row of patch row 0
 
-  // ---- what this thread stages of the patch: fixed for all channel stages ----
-  int goff[kMaxPatchLoads];      // element offset in x of the slot's 8 channels at c0 = 0; -1: none
-  int chunk_of[kMaxPatchLoads];  // which of the stage's four 8-channel chunks
-#pragma unroll
-  for (int i = 0; i < kMaxPatchLoads; ++i) {
-    goff[i] = -1;
-    chunk_of[i] = 0;
-    if (i < p.n_loads) {
-      const int s = (i * kPatchWaves + wave) * 64 + lane;
-      const int half = s & 1, t = s >> 1;
-      const int t2 = div_by(t, p.magicWh), col = t - t2 * p.Wh;
-      const int plane = div_by(t2, p.magicPR), row = t2 - plane * p.PR;
-      const int ih = in_row0 + row, iw = col - 1;
-      chunk_of[i] = plane * 2 + half;
-      if (s < p.patch_slots) {
-        if (ih >= 0 && ih < p.H && iw >= 0 && iw < p.W)
-          goff[i] = ((n * p.H + ih) * p.W + iw) * p.xcs + plane * 16 + half * 8;
-        else   // outside the image: zeros, written once
-          *reinterpret_cast<uint4*>(patch + s * 16) = uint4{0u, 0u, 0u, 0u};
-      }
-    }
-  }
+  const int t_begin = (int)((int64_t)blockIdx.x * p.tiles / gridDim.x);
+  const int t_end = (int)((int64_t)(blockIdx.x + 1) * p.tiles / gridDim.x);
+  const int n_units = (t_end - t_begin) * p.n_stages;
+  if (n_units <= 0) return;
 
-  // ---- this lane's pixels ------------------------------------------------------
-  const int row_bytes = p.Wh * 32;
-  int m[MT], rin[MT];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    m[mt] = m0 + (wave * MT + mt) * 16 + li;
-    const int mc = min(m[mt], p.PQ - 1);
-    const int pp = div_by(mc, p.magicQ), qq = mc - pp * p.Q;
-    rin[mt] = ((pp - p_lo) * p.stride * p.Wh + qq * p.stride) * 32 + (g >> 1) * p.plane_bytes +
-              (g & 1) * 16;
-  }
-  const int a_lane = g * (NF * 16) + li * 16;
-
-  f32x4 acc[MT][NT];
-#pragma unroll
-  for (int t = 0; t < NT; ++t) {
-    const int k0 = min(f0 + t * 16, p.Kp - 16) + g * 4;
-    const f32x4 b4 = *reinterpret_cast<const f32x4*>(p.bias + k0);
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt][t] = b4;
-  }
-
-  const uint32_t lane_off16 = lane * 16;
-  const uint32_t patch_lds = (uint32_t)(uintptr_t)(LdsPtr)patch;
-  const uint32_t wts_lds = (uint32_t)(uintptr_t)(LdsPtr)wts;
-  const int xchunks = p.xcs >> 3;
-
-  for (int stage = 0; stage < p.n_stages; ++stage) {
-    const int c0 = stage * 32;
-    if (stage > 0) __syncthreads();   // everybody has read the previous stage
-    // weights: row = tap * 4 + chunk of the stage, NF filters of 16 bytes each
-#pragma unroll
-    for (int i = 0; i < kWeightLoads; ++i) {
-      const int sbase = (i * kPatchWaves + wave) * 64, s = sbase + lane;
-      if (s < kWeightSlots) {
-        const int row = s / NF, f = s - row * NF;
-        const int tap = row >> 2, cc = (c0 >> 3) + (row & 3);
-        // a chunk past the last one repeats the tap's first (finite; the patch is zero there)
-        const int chunk = tap * p.cpt + (cc < p.cpt ? cc : 0);
-        const int filt = min(f0 + f, p.Kp - 1);
-        load_to_lds(p.w, (uint32_t)(chunk * p.Kp + filt) * 16u, wts_lds + sbase * 16);
-      }
-    }
-    // patch
+  if (wave >= NWC) {
+    // ================================ loading waves ================================
+    const int lw = wave - NWC;
+    const i32x4 xrsrc = make_rsrc(p.x, p.x_bytes), wrsrc = make_rsrc(p.w, p.w_bytes);
+    // What a slot of the patch holds does not depend on the tile except for the
+    // image row: slot_row = patch row, bit 15 = column inside the image;
+    // slot_off = byte offset in x as if patch row 0 were row 0 of image 0.
+    uint32_t slot_off[kMaxPatchLoads], goff[kMaxPatchLoads];
+    int slot_row[kMaxPatchLoads];
 #pragma unroll
     for (int i = 0; i < kMaxPatchLoads; ++i) {
-      if (i < p.n_loads && goff[i] >= 0) {
-        const int sbase = (i * kPatchWaves + wave) * 64, s = sbase + lane;
-        if ((c0 >> 3) + chunk_of[i] < xchunks)
-          load_to_lds(p.x, (uint32_t)(goff[i] + c0) * 2u, patch_lds + sbase * 16);
-        else   // past the last channel: zeros
-          *reinterpret_cast<uint4*>(patch + s * 16) = uint4{0u, 0u, 0u, 0u};
+      slot_off[i] = 0;
+      slot_row[i] = 0;
+      goff[i] = kOutside;
+      if (i < p.n_loads) {
+        const int s = (i * kLoaderWaves + lw) * 64 + lane;
+        const int half = s & 1, t = s >> 1;
+        const int t2 = div_by(t, p.magicWh), colpos = t - t2 * p.Wh;
+        const int plane = div_by(t2, p.magicPR), row = t2 - plane * p.PR;
+        int col = colpos;
+        if (p.stride == 2) {
+          const int odd = colpos >= p.Whh ? 1 : 0;
+          col = 2 * (colpos - odd * p.Whh) + odd;
+        }
+        const int iw = col - 1;
+        const bool ok = s < p.patch_slots && iw >= 0 && iw < p.W;
+        slot_row[i] = row | (ok ? 0x8000 : 0);
+        slot_off[i] = (uint32_t)((row * p.W + iw) * p.xcs + plane * 16 + half * 8) * 2u;
       }
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    int l_f0 = 0;
+    const uint32_t image_row_bytes = (uint32_t)(p.W * p.xcs * 2);
+    auto setup_load = [&](int tile) {
+      const int strip = tile / p.fgroups;
+      l_f0 = (tile - strip * p.fgroups) * NF;
+      const int gv_lo = (strip * BM) / p.Q;
+      const int v0 = gv_lo * p.stride;             // first virtual input row of the patch
+      const int n0 = v0 / p.Hv, vrem0 = v0 - n0 * p.Hv;
+#pragma unroll
+      for (int i = 0; i < kMaxPatchLoads; ++i) {
+        if (i < p.n_loads) {
+          const int row = slot_row[i] & 0x7fff;
+          const int dn = div_by(vrem0 + row, p.magicHv);
+          const int ihm = vrem0 - dn * p.Hv - 1;   // image row = ihm + row
+          const int ih = ihm + row, n = n0 + dn;
+          const bool ok = (slot_row[i] & 0x8000) && n < p.N && ih >= 0 && ih < p.H;
+          goff[i] = ok ? slot_off[i] + (uint32_t)(n * p.H + ihm) * image_row_bytes : kOutside;
+        }
+      }
+    };
+    auto load_weights = [&](int stage, uint32_t wdst) {
+#pragma unroll
+      for (int i = 0; i < kWeightLoads; ++i) {
+        const int sbase = (i * kLoaderWaves + lw) * 64, s = sbase + lane;
+        const int row = s / NF, f = s - row * NF;
+        const int tap = row >> 2, cc = stage * 4 + (row & 3);
+        const bool ok = s < kWeightSlots && cc < p.cpt && l_f0 + f < p.Kp;
+        const uint32_t off =
+            ok ? (uint32_t)((tap * p.cpt + cc) * p.Kp + l_f0 + f) * 16u : kOutside;
+        load_to_lds(wrsrc, off, wdst + sbase * 16);
+      }
+    };
+    auto load_patch = [&](int stage, uint32_t pdst) {
+#pragma unroll
+      for (int i = 0; i < kMaxPatchLoads; ++i)
+        if (i < p.n_loads)
+          load_to_lds(xrsrc, goff[i] + (uint32_t)stage * 64u,
+                      pdst + ((i * kLoaderWaves + lw) * 64) * 16);
+    };
 
+    int l_tile = t_begin, l_stage = 0;
+    setup_load(l_tile);
+    if (p.w_resident) {
+      for (int st = 0; st < p.n_stages; ++st) load_weights(st, lds_base + st * kWeightBytes);
+    } else {
+      load_weights(0, lds_base);
+    }
+    load_patch(0, lds_base + p.patch_base);
+    if (++l_stage == p.n_stages) { l_stage = 0; ++l_tile; }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    for (int u = 0; u < n_units; ++u) {
+      __syncthreads();   // unit u is in LDS; the computing waves have finished unit u - 1
+      if (u + 1 < n_units) {
+        if (l_stage == 0) setup_load(l_tile);
+        const uint32_t nb = (uint32_t)((u + 1) & 1) * (uint32_t)p.buf_stride;
+        if (!p.w_resident) load_weights(l_stage, lds_base + nb);
+        load_patch(l_stage, lds_base + p.patch_base + nb);
+        if (++l_stage == p.n_stages) { l_stage = 0; ++l_tile; }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      }
+    }
+    return;
+  }
+
+  // ================================ computing waves ================================
+  const int li = lane & 15, g = lane >> 4;
+  const int wm = wave % WM, wn = wave / WM;
+  const __amdgpu_buffer_rsrc_t yrsrc =
+      __builtin_amdgcn_make_buffer_rsrc(p.y, 0, p.y_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rrsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.res), 0, p.res_bytes, 0x00020000);
+  const int row_bytes = p.Wh * 32;
+  int rin[MT];
+  uint32_t yoff[MT], roff[MT];   // byte offsets of the pixel in y and in the shortcut tensor
+  int c_f0 = 0;
+  f32x4 acc[MT][NT], bias4[NT];
+  u32x2 rv[MT][NT];              // shortcut values, fetched during the last stage
+  auto setup_compute = [&](int tile) {
+    const int strip = tile / p.fgroups;
+    c_f0 = (tile - strip * p.fgroups) * NF;
+    const int m0 = strip * BM;
+    const int gv_lo = m0 / p.Q;
+    const int q_lo = m0 - gv_lo * p.Q;
+    const int n_lo = gv_lo / p.Pv, p_lo = gv_lo - n_lo * p.Pv;
+    const int last = p.Mv - 1 - m0;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int ml = (wm * MT + mt) * 16 + li;
+      const int t = q_lo + min(ml, last);
+      const int dg = div_by(t, p.magicQ), qq = t - dg * p.Q;
+      rin[mt] = (dg * p.stride * p.Wh + qq) * 32 + (g >> 1) * p.plane_bytes + (g & 1) * 16;
+      const int t2 = p_lo + dg, dn = div_by(t2, p.magicPv);
+      const int pp = t2 - dn * p.Pv, n = n_lo + dn;
+      const bool ok = ml <= last && pp < p.P && n < p.N;   // pp = P: the row between two images
+      yoff[mt] = ok ? (uint32_t)(((n * p.P + pp) * p.Q + qq) * p.ycs) * 2u : kOutside;
+      roff[mt] = ok ? (uint32_t)(((n * p.rH + pp * p.rss) * p.rW + qq * p.rss) * p.rcs) * 2u
+                    : kOutside;
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const int k0 = min(c_f0 + (wn * NT + t) * 16, p.Kp - 16) + g * 4;
+      bias4[t] = *reinterpret_cast<const f32x4*>(p.bias + k0);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+  };
+  const int a_lane = g * (NF * 16) + (wn * NT * 16 + li) * 16;
+  const int k_lane = (wn * NT * 16 + g * 4);
+  const uint32_t floor2 = p.relu ? 0u : 0x80008000u;
+
+  int c_tile = t_begin, c_stage = 0;
+  for (int u = 0; u < n_units; ++u) {
+    __syncthreads();   // unit u is in LDS
+    const int buf = u & 1;
+    if (c_stage == 0) setup_compute(c_tile);
+    const bool last = c_stage == p.n_stages - 1;
+    if (last && p.res) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          const int rc = c_f0 + k_lane + t * 16 - p.roff;
+          const uint32_t off = (rc >= 0 && rc < p.rcs) ? roff[mt] + (uint32_t)rc * 2u : kOutside;
+          rv[mt][t] = __builtin_amdgcn_raw_buffer_load_b64(rrsrc, off, 0, 0);
+        }
+    }
+    const char* wts = lds + (p.w_resident ? c_stage * kWeightBytes : buf * p.buf_stride);
+    const char* patch = lds + p.patch_base + buf * p.buf_stride;
     // 9 taps = 9 MFMA steps over these 32 channels; the operands of a step are
     // read while the step before it is multiplied
-    int brow[3][MT];
-#pragma unroll
-    for (int r = 0; r < 3; ++r)
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) brow[r][mt] = rin[mt] + r * row_bytes;
     uint4 a[2][NT], b[2][MT];
     auto operands = [&](int tap, uint4* av, uint4* bv) {
       const int r = tap / 3, sx = tap - r * 3;
+      const int off = r * row_bytes + (sx == 0 ? 0 : (sx == 1 ? p.tap1 : p.tap2));
+      // in the order the MFMAs below want them
+      av[0] = *reinterpret_cast<const uint4*>(wts + a_lane + tap * kWStep);
+      bv[0] = *reinterpret_cast<const uint4*>(patch + rin[0] + off);
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-        bv[mt] = *reinterpret_cast<const uint4*>(patch + brow[r][mt] + sx * 32);
-#pragma unroll
-      for (int t = 0; t < NT; ++t)
+      for (int t = 1; t < NT; ++t)
         av[t] = *reinterpret_cast<const uint4*>(wts + a_lane + tap * kWStep + t * 256);
+#pragma unroll
+      for (int mt = 1; mt < MT; ++mt)
+        bv[mt] = *reinterpret_cast<const uint4*>(patch + rin[mt] + off);
     };
     operands(0, a[0], b[0]);
 #pragma unroll
@@ -209,37 +330,32 @@ __global__ __launch_bounds__(kPatchThreads) void conv_patch_kernel(const PatchPa
         for (int t = 0; t < NT; ++t)
           acc[mt][t] = mfma_16x16x32<BF>(a[tap & 1][t], b[tap & 1][mt], acc[mt][t]);
     }
-  }
-
-  // ---- epilogue: shortcut, ReLU, one rounding ------------------------------------
-  const uint32_t floor2 = p.relu ? 0u : 0x80008000u;
-  const int m_end = min(m0 + BM, p.PQ);
+    if (last) {
+      // bias, shortcut, ReLU, one rounding
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    if (m[mt] >= m_end) continue;
-    const int pp = div_by(m[mt], p.magicQ), qq = m[mt] - pp * p.Q;
-    const size_t ypix = ((size_t)n * p.PQ + m[mt]) * p.ycs;
-    const size_t rpix =
-        p.res ? (((size_t)n * p.rH + (size_t)pp * p.rss) * p.rW + (size_t)qq * p.rss) * p.rcs : 0;
+      for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      const int k0 = f0 + t * 16 + g * 4;
-      if (k0 >= p.ycs) continue;
-      float v[4] = {acc[mt][t][0], acc[mt][t][1], acc[mt][t][2], acc[mt][t][3]};
-      if (p.res) {
-        const int rc = k0 - p.roff;
-        if (rc >= 0 && rc < p.rcs) {
-          const uint2 rv = *reinterpret_cast<const uint2*>(p.res + rpix + rc);
-          v[0] += to_float<BF>((uint16_t)(rv.x & 0xffffu));
-          v[1] += to_float<BF>((uint16_t)(rv.x >> 16));
-          v[2] += to_float<BF>((uint16_t)(rv.y & 0xffffu));
-          v[3] += to_float<BF>((uint16_t)(rv.y >> 16));
+        for (int t = 0; t < NT; ++t) {
+          float v[4] = {acc[mt][t][0] + bias4[t][0], acc[mt][t][1] + bias4[t][1],
+                        acc[mt][t][2] + bias4[t][2], acc[mt][t][3] + bias4[t][3]};
+          if (p.res) {
+            v[0] += to_float<BF>((uint16_t)(rv[mt][t][0] & 0xffffu));
+            v[1] += to_float<BF>((uint16_t)(rv[mt][t][0] >> 16));
+            v[2] += to_float<BF>((uint16_t)(rv[mt][t][1] & 0xffffu));
+            v[3] += to_float<BF>((uint16_t)(rv[mt][t][1] >> 16));
+          }
+          u32x2 o;
+          o[0] = clamp_below(pack2<BF>(v[0], v[1]), floor2);
+          o[1] = clamp_below(pack2<BF>(v[2], v[3]), floor2);
+          const int k0 = c_f0 + k_lane + t * 16;
+          const uint32_t off = k0 < p.ycs ? yoff[mt] + (uint32_t)k0 * 2u : kOutside;
+          __builtin_amdgcn_raw_buffer_store_b64(o, yrsrc, off, 0, 0);
         }
       }
-      uint2 o;
-      o.x = clamp_below(pack2<BF>(v[0], v[1]), floor2);
-      o.y = clamp_below(pack2<BF>(v[2], v[3]), floor2);
-      *reinterpret_cast<uint2*>(p.y + ypix + k0) = o;
+      c_stage = 0;
+      ++c_tile;
+    } else {
+      ++c_stage;
     }
   }
 }
@@ -247,74 +363,157 @@ __global__ __launch_bounds__(kPatchThreads) void conv_patch_kernel(const PatchPa
 uint32_t reciprocal(int d) { return d == 1 ? 0u : 0xffffffffu / (uint32_t)d + 1u; }
 
 struct PatchTile {
-  int MT, NT;
+  int WM, WN, MT, NT;
+  const char* name;
 };
+// pixels x filters per workgroup
+constexpr PatchTile kTiles[] = {
+    {4, 1, 4, 4, "conv3x3p_256x64"}, {4, 1, 4, 3, "conv3x3p_256x48"},
+    {4, 1, 4, 2, "conv3x3p_256x32"}, {2, 2, 4, 2, "conv3x3p_128x64"},
+    {2, 2, 4, 1, "conv3x3p_128x32"}, {2, 2, 2, 2, "conv3x3p_64x64"},
+    {2, 2, 7, 2, "conv3x3p_224x64"}, {2, 2, 7, 1, "conv3x3p_224x32"},
+    {4, 1, 7, 4, "conv3x3p_448x64"}, {4, 1, 2, 4, "conv3x3p_128x64w"},
+    {4, 1, 7, 2, "conv3x3p_448x32"}, {4, 1, 7, 3, "conv3x3p_448x48"},
+};
+constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
-// Filters per workgroup: 64, or 48 / 32 when that pads less.
-int choose_patch_nt(int FT) {
-  const int waste4 = (FT + 3) / 4 * 4 - FT, waste3 = (FT + 2) / 3 * 3 - FT;
-  return FT <= 2 ? 2 : (waste3 < waste4 ? 3 : 4);
+int num_compute_units() {
+  static int cus = [] {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        n <= 0) {
+      (void)hipGetLastError();
+      return 256;
+    }
+    return n;
+  }();
+  return cus;
 }
 
+struct PatchPlan {
+  PatchParams p;
+  size_t lds_bytes;
+  int grid;
+  double cost;
+};
+
 // Fills the parameters that depend on the tile; false if the layer does not fit.
-bool plan_patch(const Conv16Params& c, int N, const PatchTile& tile, PatchParams* out,
-                size_t* lds_bytes, dim3* grid) {
+bool plan_patch(const Conv16Params& c, int N, const PatchTile& tile, PatchPlan* out) {
   PatchParams p{};
-  const int BM = kPatchWaves * tile.MT * 16, NF = tile.NT * 16;
+  const int NTH = kLoaderWaves * 64;   // loading threads
+  const int NW = tile.WM * tile.WN;
+  const int BM = tile.WM * tile.MT * 16, NF = tile.WN * tile.NT * 16;
+  if (c.P * c.stride != c.H) return false;
   p.x = c.x; p.w = c.w; p.bias = c.bias; p.res = c.res; p.y = c.y;
-  p.H = c.H; p.W = c.W; p.xcs = c.xcs;
-  p.P = c.P; p.Q = c.Q; p.PQ = c.PQ; p.ycs = c.ycs;
+  p.x_bytes = c.x_bytes; p.w_bytes = c.w_bytes;
+  p.N = N; p.H = c.H; p.W = c.W; p.xcs = c.xcs;
+  p.P = c.P; p.Q = c.Q; p.ycs = c.ycs;
   p.stride = c.stride;
+  p.Hv = c.H + c.stride;
+  p.Pv = c.P + 1;
+  const int64_t Mv = (int64_t)N * p.Pv * c.Q;
+  if (Mv >= (int64_t(1) << 30) || (int64_t)N * p.Hv >= (int64_t(1) << 30)) return false;
+  const uint64_t y_bytes = (uint64_t)N * c.P * c.Q * c.ycs * 2;
+  const uint64_t res_bytes = c.res ? (uint64_t)N * c.rH * c.rW * c.rcs * 2 : 0;
+  if ((uint64_t)N * c.H * c.W * c.xcs * 2 >= kOutside || y_bytes >= kOutside ||
+      res_bytes >= kOutside)
+    return false;
+  p.y_bytes = (uint32_t)y_bytes;
+  p.res_bytes = (uint32_t)res_bytes;
+  p.Mv = (int)Mv;
   p.Kp = c.Kp; p.cpt = c.cpt; p.n_stages = (c.cpt + 3) / 4;
   p.rH = c.rH; p.rW = c.rW; p.rcs = c.rcs; p.rss = c.rss; p.roff = c.roff;
   p.relu = c.relu;
-  p.strips = (c.PQ + BM - 1) / BM;
-  const int rows_out = std::min(c.P, (BM - 1 + c.Q - 1) / c.Q + 1);   // rows a strip can touch
+  // virtual output rows a tile can touch
+  const int rows_out = BM % c.Q == 0 ? BM / c.Q : (BM - 1 + c.Q - 1) / c.Q + 1;
   p.PR = (rows_out - 1) * c.stride + 3;
   p.Wh = c.W + 2;
+  p.Whh = (p.Wh + 1) / 2;
   p.plane_bytes = p.PR * p.Wh * 32;
   p.patch_slots = 2 * p.PR * p.Wh * 2;
-  p.n_loads = (p.patch_slots + kPatchThreads - 1) / kPatchThreads;
+  p.n_loads = (p.patch_slots + NTH - 1) / NTH;
   if (p.n_loads > kMaxPatchLoads) return false;
+  p.tap1 = c.stride == 1 ? 32 : p.Whh * 32;
+  p.tap2 = c.stride == 1 ? 64 : 32;
+  const int weight_bytes = (36 * NF + NTH - 1) / NTH * NTH * 16;   // one stage, as loaded
+  const int patch_bytes = p.n_loads * NTH * 16;
+  p.fgroups = (c.Kp + NF - 1) / NF;
+  // weights of all stages resident when one filter group covers the layer and
+  // they fit beside the two patch buffers
+  p.w_resident = p.fgroups == 1 &&
+                 (size_t)p.n_stages * weight_bytes + 2 * (size_t)patch_bytes <= kPatchLdsLimit;
+  if (p.w_resident) {
+    p.patch_base = p.n_stages * weight_bytes;
+    p.buf_stride = patch_bytes;
+    out->lds_bytes = (size_t)p.patch_base + 2 * (size_t)patch_bytes;
+  } else {
+    p.patch_base = weight_bytes;
+    p.buf_stride = weight_bytes + patch_bytes;
+    out->lds_bytes = 2 * (size_t)p.buf_stride;
+  }
   p.magicQ = reciprocal(c.Q);
   p.magicWh = reciprocal(p.Wh);
   p.magicPR = reciprocal(p.PR);
-  if ((int64_t)p.patch_slots >= 65536 || c.PQ >= 65536) return false;   // reciprocal range
-  *lds_bytes = (size_t)36 * NF * 16 + (size_t)2 * p.plane_bytes;
-  if (*lds_bytes > 80 * 1024) return false;   // two workgroups per compute unit
-  const int64_t gx = (int64_t)N * p.strips;
-  if (gx >= (int64_t(1) << 31)) return false;
-  *grid = dim3((unsigned)gx, (unsigned)((c.Kp + NF - 1) / NF));
-  *out = p;
+  p.magicHv = reciprocal(p.Hv);
+  p.magicPv = reciprocal(p.Pv);
+  // range in which the reciprocal multiplications are exact
+  if (p.n_loads * NTH >= 65536 || BM + c.Q >= 65536 || p.Hv + p.PR >= 65536 ||
+      p.Pv + rows_out >= 65536)
+    return false;
+  if (out->lds_bytes > kPatchLdsLimit) return false;
+  const int64_t strips = (Mv + BM - 1) / BM;
+  const int64_t tiles = strips * p.fgroups;
+  if (tiles >= (int64_t(1) << 30)) return false;
+  p.tiles = (int)tiles;
+  const int cus = num_compute_units();
+  out->grid = (int)std::min<int64_t>(tiles, cus);
+  // Estimated clocks.  Measured on gfx950: within a unit the MFMAs and the LDS
+  // reads of a computing wave add up rather than overlap (reads issued between
+  // MFMAs slow both), a 16-byte-per-lane LDS read costs about 5.4 clocks of the
+  // LDS port, the loading waves move about 40 bytes per clock, and the
+  // epilogue's 8-byte accesses about 16.
+  const double mfma = 9.0 * tile.MT * tile.NT * 16.0 * NW / 4.0;
+  const double ldsr = 9.0 * (tile.MT + tile.NT) * NW * 5.4;
+  const double load = (patch_bytes + (p.w_resident ? 0 : weight_bytes)) / 40.0;
+  const double unit = std::max(mfma + ldsr, load) + 150.0;
+  const double epi = 500.0 + (double)BM * NF * (c.res ? 4.0 : 2.0) / 16.0;
+  const double per_tile = p.n_stages * unit + epi;
+  out->cost = 6000.0 + (double)((tiles + out->grid - 1) / out->grid) * per_tile;
+  out->p = p;
   return true;
 }
 
-template <bool BF, int MT, int NT>
-fupr_status launch_patch(const PatchParams& p, size_t lds_bytes, dim3 grid, hipStream_t st) {
+template <bool BF, int WM, int WN, int MT, int NT>
+fupr_status launch_patch(const PatchPlan& plan, hipStream_t st) {
   static std::once_flag once;
   static hipError_t status = hipSuccess;
   std::call_once(once, [] {
-    status = hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_patch_kernel<BF, MT, NT>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
+    status =
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_patch_kernel<BF, WM, WN, MT, NT>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPatchLdsLimit);
   });
   if (status != hipSuccess) return FUPR_ERR_LAUNCH;
-  hipLaunchKernelGGL((conv_patch_kernel<BF, MT, NT>), grid, dim3(kPatchThreads), lds_bytes, st, p);
+  hipLaunchKernelGGL((conv_patch_kernel<BF, WM, WN, MT, NT>), dim3((unsigned)plan.grid),
+                     dim3((WM * WN + kLoaderWaves) * 64), plan.lds_bytes, st, plan.p);
   return launch_status("conv_patch_kernel");
 }
 
 template <bool BF>
-fupr_status dispatch_patch(const PatchTile& t, const PatchParams& p, size_t lds, dim3 grid,
-                           hipStream_t st) {
-  switch (t.MT * 8 + t.NT) {
-    case 4 * 8 + 4: return launch_patch<BF, 4, 4>(p, lds, grid, st);
-    case 4 * 8 + 3: return launch_patch<BF, 4, 3>(p, lds, grid, st);
-    case 4 * 8 + 2: return launch_patch<BF, 4, 2>(p, lds, grid, st);
-    case 2 * 8 + 4: return launch_patch<BF, 2, 4>(p, lds, grid, st);
-    case 2 * 8 + 3: return launch_patch<BF, 2, 3>(p, lds, grid, st);
-    case 2 * 8 + 2: return launch_patch<BF, 2, 2>(p, lds, grid, st);
-    case 1 * 8 + 4: return launch_patch<BF, 1, 4>(p, lds, grid, st);
-    case 1 * 8 + 3: return launch_patch<BF, 1, 3>(p, lds, grid, st);
-    default: return launch_patch<BF, 1, 2>(p, lds, grid, st);
+fupr_status dispatch_patch(int tile, const PatchPlan& plan, hipStream_t st) {
+  switch (tile) {
+    case 0: return launch_patch<BF, 4, 1, 4, 4>(plan, st);
+    case 1: return launch_patch<BF, 4, 1, 4, 3>(plan, st);
+    case 2: return launch_patch<BF, 4, 1, 4, 2>(plan, st);
+    case 3: return launch_patch<BF, 2, 2, 4, 2>(plan, st);
+    case 4: return launch_patch<BF, 2, 2, 4, 1>(plan, st);
+    case 5: return launch_patch<BF, 2, 2, 2, 2>(plan, st);
+    case 6: return launch_patch<BF, 2, 2, 7, 2>(plan, st);
+    case 7: return launch_patch<BF, 2, 2, 7, 1>(plan, st);
+    case 8: return launch_patch<BF, 4, 1, 7, 4>(plan, st);
+    case 9: return launch_patch<BF, 4, 1, 2, 4>(plan, st);
+    case 10: return launch_patch<BF, 4, 1, 7, 2>(plan, st);
+    default: return launch_patch<BF, 4, 1, 7, 3>(plan, st);
   }
 }
 
@@ -323,53 +522,50 @@ bool patch_disabled() {
   return e && e[0] == '0';
 }
 
-// Pixels per workgroup: 256 / 128 / 64, the largest that the image's pixel
-// count (a strip never spans two images) and LDS allow.
-bool pick_patch(const Conv16Params& c, int N, PatchTile* tile, PatchParams* p, size_t* lds,
-                dim3* grid) {
-  tile->NT = choose_patch_nt(c.FT);
-  for (int mt = c.PQ > 128 ? 4 : (c.PQ > 64 ? 2 : 1); mt >= 1; mt /= 2) {
-    tile->MT = mt;
-    if (plan_patch(c, N, *tile, p, lds, grid)) return true;
+// The tile with the least estimated time; FUPR_PATCH_TILE=<index> forces one
+// (tuning aid).  -1: none fits.
+int pick_patch(const Conv16Params& c, int N, PatchPlan* best) {
+  int forced = -1;
+  if (const char* e = std::getenv("FUPR_PATCH_TILE")) forced = std::atoi(e);
+  int which = -1;
+  for (int i = 0; i < kNumTiles; ++i) {
+    PatchPlan plan;
+    if (!plan_patch(c, N, kTiles[i], &plan)) continue;
+    if (i == forced) {
+      *best = plan;
+      return i;
+    }
+    if (which < 0 || plan.cost < best->cost) {
+      *best = plan;
+      which = i;
+    }
   }
-  return false;
+  return which;
 }
 
 }  // namespace
 
-bool conv_patch_applies(const Conv16Params& c) {
+bool conv_patch_applies(const Conv16Params& c, int N) {
   if (patch_disabled()) return false;
   if (c.S != 3 || c.nchunk != 9 * c.cpt || c.pad != 1 || (c.stride != 1 && c.stride != 2))
     return false;
   if (c.cpt < 2) return false;   // fewer than 16 channels: nothing to reuse
-  PatchTile tile;
-  PatchParams p;
-  size_t lds;
-  dim3 grid;
-  return pick_patch(c, 1, &tile, &p, &lds, &grid);
+  PatchPlan plan;
+  return pick_patch(c, N, &plan) >= 0;
 }
 
-const char* conv_patch_name(const Conv16Params& c) {
-  static const char* names[3][3] = {{"conv3x3p_64x32", "conv3x3p_64x48", "conv3x3p_64x64"},
-                                    {"conv3x3p_128x32", "conv3x3p_128x48", "conv3x3p_128x64"},
-                                    {"conv3x3p_256x32", "conv3x3p_256x48", "conv3x3p_256x64"}};
-  PatchTile t;
-  PatchParams p;
-  size_t lds;
-  dim3 grid;
-  if (!pick_patch(c, 1, &t, &p, &lds, &grid)) return "conv3x3p";
-  return names[t.MT == 4 ? 2 : t.MT == 2 ? 1 : 0][t.NT - 2];
+const char* conv_patch_name(const Conv16Params& c, int N) {
+  PatchPlan plan;
+  const int t = pick_patch(c, N, &plan);
+  return t < 0 ? "conv3x3p" : kTiles[t].name;
 }
 
 fupr_status launch_conv_patch(const Conv16Params& c, int N, bool bf16, void* stream) {
-  PatchTile tile;
-  PatchParams p;
-  size_t lds;
-  dim3 grid;
-  if (!pick_patch(c, N, &tile, &p, &lds, &grid)) return FUPR_ERR_LIMIT;
+  PatchPlan plan;
+  const int t = pick_patch(c, N, &plan);
+  if (t < 0) return FUPR_ERR_LIMIT;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-  return bf16 ? dispatch_patch<true>(tile, p, lds, grid, st)
-              : dispatch_patch<false>(tile, p, lds, grid, st);
+  return bf16 ? dispatch_patch<true>(t, plan, st) : dispatch_patch<false>(t, plan, st);
 }
 
 }  // namespace fupr

@@ -248,7 +248,7 @@ Conv16Params geometry16(const fupr_conv_shape& s, fupr_dtype dt, int N, int H, i
 const char* conv_kernel_name(const fupr_conv_shape& s, fupr_dtype dt, int N, int H, int W) {
   if (dt == FUPR_F32) return "conv32_direct";
   const Conv16Params g = geometry16(s, dt, N, H, W);
-  if (s.R == 3 && conv_patch_applies(g)) return conv_patch_name(g);
+  if (s.R == 3 && conv_patch_applies(g, N)) return conv_patch_name(g, N);
   return conv16_tiled_name(g.FT, g.nsteps, g.M);
 }
 
@@ -289,7 +289,7 @@ fupr_status launch_conv(const ConvArgs& a, void* stream) {
   p.relu = a.relu;
   p.x_bytes = (uint32_t)((int64_t)a.N * a.H * a.W * a.xcs * 2);
   p.w_bytes = (uint32_t)((size_t)L.nchunk_pad * L.Kp * 16);
-  if (a.R == 3 && conv_patch_applies(p)) return launch_conv_patch(p, a.N, a.dt == FUPR_BF16, stream);
+  if (a.R == 3 && conv_patch_applies(p, a.N)) return launch_conv_patch(p, a.N, a.dt == FUPR_BF16, stream);
   return launch_conv16_tiled(p, a.dt == FUPR_BF16, stream);
 }
 
