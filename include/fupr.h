@@ -18,6 +18,8 @@
  *   fupr_conv_fused      convolution operator k x c x r x s (Sec. III, Sec. IV-B-1)
  *                        with bias, element-wise addition and ReLU in its epilogue
  *   fupr_maxpool, fupr_global_avgpool   the "Others" of Table II / Table VI
+ *   fupr_conv_maxpool_fused             Table II's ImageNet stem (7 x 7 convolution, stride 2, then
+ *                        3 x 3 max pool, stride 2) in one kernel
  *   fupr_model_*, fupr_forward          a whole network (Table II) on one stream
  *
  * Conventions
@@ -244,6 +246,21 @@ fupr_status fupr_maxpool(const fupr_tensor* x, int32_t k, int32_t stride, int32_
 
 /* y[n,0,0,c] = mean over H*W of x[n,:,:,c], fp32 accumulation (Table II, before fc). */
 fupr_status fupr_global_avgpool(const fupr_tensor* x, const fupr_tensor* y, void* stream);
+
+/*
+ * The ImageNet stem of Table II as one operator: y = maxpool_{3x3, stride 2, pad 1}(
+ * relu(conv(x) + bias)) without writing the convolution's output to memory
+ * (the operator-fusion idea of Sec. IV-B applied to the one "Others" operator
+ * that follows a convolution directly).  shape must be 7 x 7, stride 2, pad 3,
+ * C <= 4, K = 64; x, y [dev] 16-bit NHWC, y->c_stride = 64, y->H/W the pool's
+ * output extent; packed [dev] from fupr_pack.  The result equals fupr_conv_fused
+ * (ReLU) followed by fupr_maxpool bit for bit: rounding is monotonic, so the
+ * maximum of rounded values is the rounded maximum.
+ * Errors: NULL, SHAPE, DTYPE, ALIGN; LIMIT when the shape is not the one above.
+ */
+fupr_status fupr_conv_maxpool_fused(const fupr_conv_shape* shape, const fupr_tensor* x,
+                                    const void* packed, int32_t pool_k, int32_t pool_stride,
+                                    int32_t pool_pad, const fupr_tensor* y, void* stream);
 
 /* ----------------------------------------------------------------- model -- */
 

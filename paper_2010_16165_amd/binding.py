@@ -106,6 +106,8 @@ SIGNATURES = {
                                     C.c_void_p]),
     "fupr_maxpool": (C.c_int32, [_T, C.c_int32, C.c_int32, C.c_int32, _T, C.c_void_p]),
     "fupr_global_avgpool": (C.c_int32, [_T, _T, C.c_void_p]),
+    "fupr_conv_maxpool_fused": (C.c_int32, [C.POINTER(ConvShape), _T, C.c_void_p, C.c_int32,
+                                            C.c_int32, C.c_int32, _T, C.c_void_p]),
     "fupr_model_create": (C.c_int32, [C.POINTER(GraphDesc), C.POINTER(C.c_void_p)]),
     "fupr_model_destroy": (None, [C.c_void_p]),
     "fupr_model_workspace_bytes": (C.c_size_t, [C.c_void_p, C.c_int32]),
@@ -356,6 +358,14 @@ def fupr_maxpool(x, k, stride, pad, y, stream=None):
     st = _lib.fupr_maxpool(C.byref(xs), int(k), int(stride), int(pad), C.byref(ys),
                            stream if stream is not None else current_stream())
     _check(st, "fupr_maxpool")
+
+
+def fupr_conv_maxpool_fused(shape, x, packed, pool_k, pool_stride, pool_pad, y, stream=None):
+    xs, ys = x.struct, y.struct
+    st = _lib.fupr_conv_maxpool_fused(C.byref(shape), C.byref(xs), C.c_void_p(packed.data_ptr()),
+                                      int(pool_k), int(pool_stride), int(pool_pad), C.byref(ys),
+                                      stream if stream is not None else current_stream())
+    _check(st, "fupr_conv_maxpool_fused")
 
 
 def fupr_global_avgpool(x, y, stream=None):

@@ -9,6 +9,7 @@
 
 #include "fupr.h"
 #include "layout.h"
+#include "stem_pool.h"
 #include "device_utils.h"
 #include "conv16.h"
 
@@ -368,6 +369,35 @@ extern "C" fupr_status fupr_conv_fused(const fupr_conv_shape* shape, const fupr_
     a.rss = res->spatial_stride; a.roff = res->c_offset;
   }
   return launch_conv(a, stream);
+}
+
+extern "C" fupr_status fupr_conv_maxpool_fused(const fupr_conv_shape* shape, const fupr_tensor* x,
+                                               const void* packed, int32_t pool_k,
+                                               int32_t pool_stride, int32_t pool_pad,
+                                               const fupr_tensor* y, void* stream) {
+  if (!shape || !x || !y || !packed) return FUPR_ERR_NULL;
+  if (!shape_ok(shape)) return FUPR_ERR_SHAPE;
+  fupr_status st = check_tensor(x);
+  if (st != FUPR_OK) return st;
+  st = check_tensor(y);
+  if (st != FUPR_OK) return st;
+  if (x->dt != y->dt) return FUPR_ERR_DTYPE;
+  if ((reinterpret_cast<uintptr_t>(packed) & 255u) != 0) return FUPR_ERR_ALIGN;
+  if (pool_k <= 0 || pool_stride <= 0 || pool_pad < 0 || pool_pad >= pool_k) return FUPR_ERR_ARG;
+  if (x->H + 2 * shape->pad < shape->R || x->W + 2 * shape->pad < shape->S) return FUPR_ERR_SHAPE;
+  const int SH = out_extent(x->H, shape->R, shape->stride, shape->pad);
+  const int SW = out_extent(x->W, shape->S, shape->stride, shape->pad);
+  if (SH + 2 * pool_pad < pool_k || SW + 2 * pool_pad < pool_k) return FUPR_ERR_SHAPE;
+  const int P = out_extent(SH, pool_k, pool_stride, pool_pad);
+  const int Q = out_extent(SW, pool_k, pool_stride, pool_pad);
+  if (x->C != shape->C || y->C != shape->K || y->N != x->N || y->H != P || y->W != Q)
+    return FUPR_ERR_SHAPE;
+  if (x->ptr == y->ptr) return FUPR_ERR_ARG;
+  if (!stem_pool_applies(*shape, x->dt, x->N, x->H, x->W, x->c_stride, y->c_stride, pool_k,
+                         pool_stride, pool_pad))
+    return FUPR_ERR_LIMIT;
+  return launch_stem_pool(*shape, x->dt, x->N, x->H, x->W, x->c_stride, y->c_stride, x->ptr, packed,
+                          y->ptr, stream);
 }
 
 namespace {

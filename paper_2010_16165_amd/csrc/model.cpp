@@ -13,6 +13,7 @@
 
 #include "fupr.h"
 #include "layout.h"
+#include "stem_pool.h"
 
 using namespace fupr;
 
@@ -711,6 +712,35 @@ bool use_resident(const fupr_model* m, const fupr_tensor* input, const fupr_tens
   return output->c_stride <= limit;
 }
 
+// One kernel launch of the per-operator schedule: `count` consecutive operators.
+struct Launch {
+  int first, count;
+};
+
+// Operator i is a 16-bit 7 x 7 stem convolution with ReLU whose only reader is
+// the 3 x 3 max-pool right behind it: the two run as one kernel.
+bool stem_pool_pair(const fupr_model* m, size_t i) {
+  if (m->schedule != FUPR_SCHEDULE_AUTO || i + 1 >= m->ops.size()) return false;
+  const fupr_op_desc& c = m->ops[i];
+  const fupr_op_desc& q = m->ops[i + 1];
+  if (c.kind != FUPR_OP_CONV || c.res >= 0 || c.epilogue != FUPR_FUSE_RELU) return false;
+  if (q.kind != FUPR_OP_MAXPOOL || q.in != (int)i + 1) return false;
+  if (m->tensors[i + 1].last_use != (int)i + 1) return false;
+  const TensorInfo& tin = m->tensors[c.in];
+  return stem_pool_applies(c.conv, m->dt, 1, tin.H, tin.W, tin.cs, m->tensors[i + 2].cs, q.conv.R,
+                           q.conv.stride, q.conv.pad);
+}
+
+std::vector<Launch> launches_of(const fupr_model* m) {
+  std::vector<Launch> v;
+  for (size_t i = 0; i < m->ops.size();) {
+    const int count = stem_pool_pair(m, i) ? 2 : 1;
+    v.push_back(Launch{(int)i, count});
+    i += count;
+  }
+  return v;
+}
+
 fupr_status run(const fupr_model* m, const fupr_tensor* input, const fupr_tensor* output,
                 void* workspace, size_t workspace_bytes, void* stream, hipEvent_t* events) {
   if (!m || !input || !output || !workspace) return FUPR_ERR_NULL;
@@ -758,11 +788,17 @@ fupr_status run(const fupr_model* m, const fupr_tensor* input, const fupr_tensor
     if (events && hipEventRecord(events[1], hs) != hipSuccess) return FUPR_ERR_LAUNCH;
     return FUPR_OK;
   }
-  for (size_t i = 0; i < m->ops.size(); ++i) {
+  const std::vector<Launch> launches = launches_of(m);
+  for (size_t l = 0; l < launches.size(); ++l) {
+    const size_t i = (size_t)launches[l].first;
     const fupr_op_desc& op = m->ops[i];
-    const fupr_tensor x = view(op.in), y = view((int)i + 1);
+    const fupr_tensor x = view(op.in), y = view((int)i + launches[l].count);
     fupr_status st;
-    if (op.kind == FUPR_OP_CONV) {
+    if (launches[l].count == 2) {
+      const fupr_op_desc& pool = m->ops[i + 1];
+      st = fupr_conv_maxpool_fused(&op.conv, &x, op.packed, pool.conv.R, pool.conv.stride,
+                                   pool.conv.pad, &y, stream);
+    } else if (op.kind == FUPR_OP_CONV) {
       fupr_residual r;
       const bool add = op.res >= 0;
       if (add) {
@@ -777,7 +813,7 @@ fupr_status run(const fupr_model* m, const fupr_tensor* input, const fupr_tensor
       st = fupr_global_avgpool(&x, &y, stream);
     }
     if (st != FUPR_OK) return st;
-    if (events && hipEventRecord(events[i + 1], hs) != hipSuccess) return FUPR_ERR_LAUNCH;
+    if (events && hipEventRecord(events[l + 1], hs) != hipSuccess) return FUPR_ERR_LAUNCH;
   }
   return FUPR_OK;
 }
@@ -804,7 +840,7 @@ extern "C" fupr_status fupr_forward_timed(const fupr_model* m, const fupr_tensor
     st = FUPR_ERR_LAUNCH;
   if (st == FUPR_OK) {
     std::vector<float> ms(n, 0.0f);
-    const size_t launches = use_resident(m, input, output) ? 1 : n;
+    const size_t launches = use_resident(m, input, output) ? 1 : launches_of(m).size();
     for (size_t i = 0; i < launches; ++i)
       if (hipEventElapsedTime(&ms[i], ev[i], ev[i + 1]) != hipSuccess) { st = FUPR_ERR_LAUNCH; break; }
     if (st == FUPR_OK) std::copy(ms.begin(), ms.end(), op_ms);
@@ -849,15 +885,29 @@ extern "C" fupr_status fupr_model_op_stats(const fupr_model* m, int32_t batch, i
 
 extern "C" int32_t fupr_model_num_launches(const fupr_model* m) {
   if (!m) return 0;
-  return m->resident_ok && m->schedule == FUPR_SCHEDULE_AUTO ? 1 : (int32_t)m->ops.size();
+  return m->resident_ok && m->schedule == FUPR_SCHEDULE_AUTO ? 1 : (int32_t)launches_of(m).size();
 }
 
 extern "C" fupr_status fupr_model_launch_stats(const fupr_model* m, int32_t batch, int32_t launch,
                                                fupr_op_stats* out) {
   if (!m || !out) return FUPR_ERR_NULL;
   if (batch <= 0 || launch < 0 || launch >= fupr_model_num_launches(m)) return FUPR_ERR_ARG;
-  if (!(m->resident_ok && m->schedule == FUPR_SCHEDULE_AUTO))
-    return fupr_model_op_stats(m, batch, launch, out);
+  if (!(m->resident_ok && m->schedule == FUPR_SCHEDULE_AUTO)) {
+    const Launch l = launches_of(m)[launch];
+    fupr_status st = fupr_model_op_stats(m, batch, l.first, out);
+    if (st != FUPR_OK || l.count == 1) return st;
+    // convolution + pool in one kernel: the convolution's flops; its input and
+    // parameters read, the pool's output written
+    fupr_op_stats pool;
+    st = fupr_model_op_stats(m, batch, l.first + 1, &pool);
+    if (st != FUPR_OK) return st;
+    const double es = (double)elem_size(m->dt);
+    const TensorInfo& mid = m->tensors[l.first + 1];
+    const double mid_b = es * batch * (double)mid.H * mid.W * mid.C;
+    out->bytes += pool.bytes - 2.0 * mid_b;
+    out->kernel = "stem7x7_maxpool";
+    return FUPR_OK;
+  }
   // one kernel: all flops; the image in, the result out, every parameter once
   const double es = (double)elem_size(m->dt);
   const TensorInfo& t0 = m->tensors.front();

@@ -188,6 +188,87 @@ def test_global_avgpool(fx, dtype):
 
 # ---- whole networks ----------------------------------------------------------------
 
+# ---- stem convolution + max-pool in one kernel -------------------------------------
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("size", [(64, 64), (70, 58), (30, 26)], ids=["64x64", "70x58", "30x26"])
+def test_stem_maxpool_fused(fx, size, dtype):
+    """Table II's ImageNet stem as one operator: against the oracle's conv, BN,
+    ReLU, max-pool, and bit for bit against the two separate kernels."""
+    B, network, torch = fx
+    h, w = size
+    n, c, k = 3, 3, 64
+    rng = np.random.default_rng(1000 + h)
+    print(f"stem {h}x{w} {dtype}", flush=True)
+    x = rng.standard_normal((n, c, h, w)).astype(np.float32)
+    wt = (rng.standard_normal((k, c, 7, 7)) * np.sqrt(2.0 / (c * 49))).astype(np.float32)
+    bn = {"gamma": rng.uniform(0.5, 1.5, k).astype(np.float32),
+          "beta": (rng.standard_normal(k) * 0.1).astype(np.float32),
+          "mean": (rng.standard_normal(k) * 0.1).astype(np.float32),
+          "var": rng.uniform(0.5, 1.5, k).astype(np.float32), "eps": 1e-5}
+    dt = B.DTYPES[dtype]
+    sh_, sw_ = (h + 6 - 7) // 2 + 1, (w + 6 - 7) // 2 + 1
+    p, q = (sh_ + 2 - 3) // 2 + 1, (sw_ + 2 - 3) // 2 + 1
+    xr = round_to(x, dtype, torch)
+    ref = orc.maxpool(orc.relu(orc.batchnorm(orc.conv2d(xr, wt, 2, 3), bn)), 3, 2, 1)
+
+    sh = B.shape_of(wt, 2, 3)
+    Wf, bf = B.fupr_fold(sh, wt, None, bn["gamma"], bn["beta"], bn["mean"], bn["var"], bn["eps"],
+                         B.FUSE_BN)
+    packed = B.upload_blob(B.fupr_pack(sh, Wf, bf, dt))
+    xd = B.DeviceTensor.from_nchw(x, dt)
+    yd = B.DeviceTensor.empty(n, p, q, k, dt)
+    yd.data.fill_(7.0)
+    B.fupr_conv_maxpool_fused(sh, xd, packed, 3, 2, 1, yd)
+    torch.cuda.synchronize()
+    got = yd.to_nchw()
+    err = rel_err(got, ref)
+    print(f"  max-norm rel err {err:.3e}", flush=True)
+    assert err <= TOL[dtype], (size, dtype, err)
+    # the two-kernel path: same accumulation order, one rounding each, max of rounded values
+    mid = B.DeviceTensor.empty(n, sh_, sw_, k, dt)
+    y2 = B.DeviceTensor.empty(n, p, q, k, dt)
+    B.fupr_conv_fused(sh, xd, packed, None, B.FUSE_RELU, mid)
+    B.fupr_maxpool(mid, 3, 2, 1, y2)
+    torch.cuda.synchronize()
+    err2 = rel_err(got, y2.to_nchw())
+    print(f"  against conv + pool kernels {err2:.3e}", flush=True)
+    assert err2 <= TOL[dtype] / 4
+
+
+def test_stem_maxpool_fused_rejects_other_shapes(fx):
+    B, network, torch = fx
+    wt = np.zeros((32, 3, 7, 7), np.float32)
+    sh = B.shape_of(wt, 2, 3)
+    packed = B.upload_blob(B.fupr_pack(sh, wt, np.zeros(32, np.float32), B.BF16))
+    xd = B.DeviceTensor.from_nchw(np.zeros((1, 3, 32, 32), np.float32), B.BF16)
+    yd = B.DeviceTensor.empty(1, 8, 8, 32, B.BF16)
+    with pytest.raises(B.FuprError) as e:
+        B.fupr_conv_maxpool_fused(sh, xd, packed, 3, 2, 1, yd)
+    assert e.value.status == B.ERR_LIMIT
+
+
+def test_imagenet_stem_and_pool_run_as_one_launch(fx):
+    B, network, torch = fx
+    model = synth.make_imagenet_basic_resnet(14, "bf16", (1, 1, 1, 1), 300, widths=(64, 8, 8, 12),
+                                             size=64, classes=7)
+    m, _ = network.build(network.optimise(model))
+    assert m.num_launches == m.num_ops - 1
+    assert m.launch_stats(2, 0)["kernel"] == "stem7x7_maxpool"
+    x = synth.make_input(14, 2, model["in_shape"])
+    xd = B.DeviceTensor.from_nchw(x, B.BF16)
+    out, ws = m.alloc(2)
+    m.fupr_forward(xd, out, ws)
+    torch.cuda.synchronize()
+    fused = out.data.clone()
+    m.set_schedule(B.SCHEDULE_PER_LAYER)
+    assert m.num_launches == m.num_ops
+    m.fupr_forward(xd, out, ws)
+    torch.cuda.synchronize()
+    ref = out.data.float()
+    assert float((fused.float() - ref).abs().max() / ref.abs().max()) <= TOL["bf16"] / 4
+
+
 def run_network(B, network, torch, model, x, **options):
     plan = network.optimise(model, **options)
     m, sites = network.build(plan)
@@ -281,7 +362,8 @@ def test_paper_workload_at_batch_one(fx, name):
     masks = orc.select_masks(model)
     ref = orc.forward(model, round_to(x, model["dtype"], torch), masks=masks)
     plan, m, y = run_network(B, network, torch, model, x)
-    assert m.num_launches == (1 if name in ("resnet20", "resnet32") else m.num_ops)
+    # CIFAR networks: one kernel; ImageNet networks: one per operator, stem + pool as one
+    assert m.num_launches == (1 if name in ("resnet20", "resnet32") else m.num_ops - 1)
     err = rel_err(y, ref)
     print(f"{model['name']}: rel err {err:.3e}", flush=True)
     assert err <= TOL[model["dtype"]]
