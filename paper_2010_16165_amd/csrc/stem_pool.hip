@@ -31,6 +31,7 @@ namespace fupr {
 namespace {
 
 constexpr uint32_t kOutside = 0x80000000u;
+constexpr int kMaxStemPatchLoads = 8;  // 8-byte pixels of the input patch per thread
 constexpr int kStemPixelBytes = 144;   // 64 channels + 16 bytes: spreads LDS banks
 
 struct StemParams {
@@ -44,6 +45,7 @@ struct StemParams {
   int P, Q, ycs;         // pool output
   int TP, TQ;            // pool outputs per workgroup
   int tiles_p, tiles_q;  // per image
+  int total_tiles;
   int th, tw;            // convolution outputs per workgroup: 2 TP + 1, 2 TQ + 1
   int PH, PW;            // input patch: 2 th + 5 rows, 2 tw + 5 columns rounded up to even
   int n_ctiles;          // 16-pixel tiles of th * tw
@@ -66,21 +68,13 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemParams p) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int li = lane & 15, g = lane >> 4;
 
-  int tile = blockIdx.x;
   const int per_image = p.tiles_p * p.tiles_q;
-  const int n = tile / per_image;
-  tile -= n * per_image;
-  const int tp = tile / p.tiles_q, tq = tile - tp * p.tiles_q;
-  const int p0 = tp * p.TP, q0 = tq * p.TQ;      // first pool output
-  const int a0 = 2 * p0 - 1, b0 = 2 * q0 - 1;    // first convolution output
-  const int h0 = 2 * a0 - 3, w0 = 2 * b0 - 3;    // first input pixel
-
   const __amdgpu_buffer_rsrc_t xrsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.x), 0, p.x_bytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t wrsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.w), 0, p.w_bytes, 0x00020000);
 
-  // ---- filters: [r * 4 + j][filter][2 taps x 4 channels] in LDS --------------------
+  // ---- filters: [r * 4 + j][filter][2 taps x 4 channels] in LDS, then registers -----
   for (int e = tid; e < 28 * 64; e += 256) {
     const int ch = e >> 6, f = e & 63;
     const int r = ch >> 2, j = ch & 3;
@@ -89,15 +83,6 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemParams p) {
     const u32x2 hi = __builtin_amdgcn_raw_buffer_load_b64(
         wrsrc, 2 * j + 1 < 7 ? (uint32_t)((tap + 1) * 64 + f) * 16u : kOutside, 0, 0);
     *reinterpret_cast<uint4*>(lds + e * 16) = uint4{lo[0], lo[1], hi[0], hi[1]};
-  }
-  // ---- input patch: [PH][PW][4 channels] ------------------------------------------
-  char* patch = lds + p.patch_off;
-  for (int e = tid; e < p.PH * p.PW; e += 256) {
-    const int pr = div_by(e, p.magic_PW), pc = e - pr * p.PW;
-    const int ih = h0 + pr, iw = w0 + pc;
-    const bool ok = ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
-    const uint32_t off = ok ? (uint32_t)(((n * p.H + ih) * p.W + iw) * p.xcs) * 2u : kOutside;
-    *reinterpret_cast<u32x2*>(patch + e * 8) = __builtin_amdgcn_raw_buffer_load_b64(xrsrc, off, 0, 0);
   }
   f32x4 bias4[4];
 #pragma unroll
@@ -109,61 +94,111 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemParams p) {
 #pragma unroll
     for (int t = 0; t < 4; ++t)
       a[k][t] = *reinterpret_cast<const uint4*>(lds + (((k * 4 + g) * 64) + t * 16 + li) * 16);
-  __syncthreads();   // the staging area is free: the convolution tile may overwrite it
+  // (the first barrier of the tile loop frees the staging area for the convolution tile)
 
-  // ---- convolution tile -> LDS -----------------------------------------------------
+  char* patch = lds + p.patch_off;
   char* stem = lds + p.stem_off;
   const int n_cpix = p.th * p.tw;
   const int prow_bytes = p.PW * 8;
-  for (int ct = wave; ct < p.n_ctiles; ct += 4) {
-    const int cp = ct * 16 + li;
-    const int cpc = min(cp, n_cpix - 1);
-    const int sr = div_by(cpc, p.magic_tw), sc = cpc - sr * p.tw;
-    const char* bp = patch + (2 * sr * p.PW + 2 * sc) * 8 + g * 16;
-    uint4 b[7];
+  const int ychunks = p.ycs >> 3;
+  const int n_patch = p.PH * p.PW;
+
+  // the input patch of a tile: [PH][PW][4 channels], fetched one tile ahead
+  u32x2 pre[kMaxStemPatchLoads];
+  auto fetch = [&](int tile) {
+    const int n = tile / per_image, rem = tile - n * per_image;
+    const int tp = rem / p.tiles_q, tq = rem - tp * p.tiles_q;
+    const int h0 = 4 * tp * p.TP - 5, w0 = 4 * tq * p.TQ - 5;   // first input pixel
 #pragma unroll
-    for (int k = 0; k < 7; ++k) b[k] = *reinterpret_cast<const uint4*>(bp + k * prow_bytes);
-    f32x4 acc[4];
+    for (int i = 0; i < kMaxStemPatchLoads; ++i) {
+      const int e = tid + i * 256;
+      const int pr = div_by(e, p.magic_PW), pc = e - pr * p.PW;
+      const int ih = h0 + pr, iw = w0 + pc;
+      const bool ok = e < n_patch && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+      const uint32_t off = ok ? (uint32_t)(((n * p.H + ih) * p.W + iw) * p.xcs) * 2u : kOutside;
+      pre[i] = __builtin_amdgcn_raw_buffer_load_b64(xrsrc, off, 0, 0);
+    }
+  };
+
+  int tile = blockIdx.x;
+  if (tile < p.total_tiles) fetch(tile);
+  for (; tile < p.total_tiles; tile += gridDim.x) {
+    const int n = tile / per_image, rem = tile - n * per_image;
+    const int tp = rem / p.tiles_q, tq = rem - tp * p.tiles_q;
+    const int p0 = tp * p.TP, q0 = tq * p.TQ;      // first pool output
+    const int a0 = 2 * p0 - 1, b0 = 2 * q0 - 1;    // first convolution output
 #pragma unroll
-    for (int t = 0; t < 4; ++t) acc[t] = bias4[t];
+    for (int i = 0; i < kMaxStemPatchLoads; ++i) {
+      const int e = tid + i * 256;
+      if (e < n_patch) *reinterpret_cast<u32x2*>(patch + e * 8) = pre[i];
+    }
+    __syncthreads();   // patch complete; the previous tile's maxima have been taken
+    if (tile + (int)gridDim.x < p.total_tiles) fetch(tile + gridDim.x);
+
+    // ---- convolution tile -> LDS ---------------------------------------------------
+    for (int ct = wave; ct < p.n_ctiles; ct += 4) {
+      const int cp = ct * 16 + li;
+      const int cpc = min(cp, n_cpix - 1);
+      const int sr = div_by(cpc, p.magic_tw), sc = cpc - sr * p.tw;
+      const char* bp = patch + (2 * sr * p.PW + 2 * sc) * 8 + g * 16;
+      uint4 b[7];
 #pragma unroll
-    for (int k = 0; k < 7; ++k)
+      for (int k = 0; k < 7; ++k) b[k] = *reinterpret_cast<const uint4*>(bp + k * prow_bytes);
+      f32x4 acc[4];
 #pragma unroll
-      for (int t = 0; t < 4; ++t) acc[t] = mfma_16x16x32<BF>(a[k][t], b[k], acc[t]);
-    const int sh = a0 + sr, sw = b0 + sc;
-    const bool inside = sh >= 0 && sh < p.SH && sw >= 0 && sw < p.SW;
-    if (cp < n_cpix) {
+      for (int t = 0; t < 4; ++t) acc[t] = bias4[t];
 #pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        u32x2 o;
-        o[0] = inside ? pack2<BF>(fmaxf(acc[t][0], 0.f), fmaxf(acc[t][1], 0.f)) : 0u;
-        o[1] = inside ? pack2<BF>(fmaxf(acc[t][2], 0.f), fmaxf(acc[t][3], 0.f)) : 0u;
-        *reinterpret_cast<u32x2*>(stem + cp * kStemPixelBytes + t * 32 + g * 8) = o;
+      for (int k = 0; k < 7; ++k)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc[t] = mfma_16x16x32<BF>(a[k][t], b[k], acc[t]);
+      const int sh = a0 + sr, sw = b0 + sc;
+      const bool inside = sh >= 0 && sh < p.SH && sw >= 0 && sw < p.SW;
+      if (cp < n_cpix) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          u32x2 o;
+          o[0] = inside ? pack2<BF>(fmaxf(acc[t][0], 0.f), fmaxf(acc[t][1], 0.f)) : 0u;
+          o[1] = inside ? pack2<BF>(fmaxf(acc[t][2], 0.f), fmaxf(acc[t][3], 0.f)) : 0u;
+          *reinterpret_cast<u32x2*>(stem + cp * kStemPixelBytes + t * 32 + g * 8) = o;
+        }
       }
     }
-  }
-  __syncthreads();
+    __syncthreads();   // tile complete; the patch may be overwritten
 
-  // ---- 3 x 3 stride-2 maxima: one thread per (pool pixel, 8 channels) ---------------
-  // non-negative values of either 16-bit format order like their bit patterns
-  const int ychunks = p.ycs >> 3;
-  for (int e = tid; e < p.TP * p.TQ * 8; e += 256) {
-    const int c8 = e & 7, pix = e >> 3;
-    const int pp = div_by(pix, p.magic_TQ), qq = pix - pp * p.TQ;
-    const int gp = p0 + pp, gq = q0 + qq;
-    if (gp >= p.P || gq >= p.Q || c8 >= ychunks) continue;
-    short8_t m = {0, 0, 0, 0, 0, 0, 0, 0};
+    // ---- 3 x 3 stride-2 maxima: one thread per (pool pixel, 8 channels) -------------
+    // non-negative values of either 16-bit format order like their bit patterns
+    for (int e = tid; e < p.TP * p.TQ * 8; e += 256) {
+      const int c8 = e & 7, pix = e >> 3;
+      const int pp = div_by(pix, p.magic_TQ), qq = pix - pp * p.TQ;
+      const int gp = p0 + pp, gq = q0 + qq;
+      if (gp >= p.P || gq >= p.Q || c8 >= ychunks) continue;
+      short8_t m = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-    for (int r = 0; r < 3; ++r)
+      for (int r = 0; r < 3; ++r)
 #pragma unroll
-      for (int s = 0; s < 3; ++s) {
-        const uint4 v = *reinterpret_cast<const uint4*>(
-            stem + ((2 * pp + r) * p.tw + 2 * qq + s) * kStemPixelBytes + c8 * 16);
-        m = __builtin_elementwise_max(m, __builtin_bit_cast(short8_t, v));
-      }
-    *reinterpret_cast<uint4*>(p.y + (((size_t)n * p.P + gp) * p.Q + gq) * p.ycs + c8 * 8) =
-        __builtin_bit_cast(uint4, m);
+        for (int s = 0; s < 3; ++s) {
+          const uint4 v = *reinterpret_cast<const uint4*>(
+              stem + ((2 * pp + r) * p.tw + 2 * qq + s) * kStemPixelBytes + c8 * 16);
+          m = __builtin_elementwise_max(m, __builtin_bit_cast(short8_t, v));
+        }
+      *reinterpret_cast<uint4*>(p.y + (((size_t)n * p.P + gp) * p.Q + gq) * p.ycs + c8 * 8) =
+          __builtin_bit_cast(uint4, m);
+    }
   }
+}
+
+int stem_compute_units() {
+  static int cus = [] {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        n <= 0) {
+      (void)hipGetLastError();
+      return 256;
+    }
+    return n;
+  }();
+  return cus;
 }
 
 uint32_t reciprocal(int d) { return d == 1 ? 0u : 0xffffffffu / (uint32_t)d + 1u; }
@@ -201,10 +236,12 @@ bool plan_stem(const fupr_conv_shape& s, fupr_dtype dt, int N, int H, int W, int
   p.magic_tw = reciprocal(p.tw);
   p.magic_PW = reciprocal(p.PW);
   p.magic_TQ = reciprocal(p.TQ);
-  if (p.PH * p.PW >= 65536 || p.th * p.tw + 16 >= 65536) return false;
+  if (p.PH * p.PW > kMaxStemPatchLoads * 256 || p.th * p.tw + 16 >= 65536) return false;
   if ((int64_t)N * H * W * xcs * 2 >= (int64_t)kOutside) return false;
-  *grid = (int64_t)N * p.tiles_p * p.tiles_q;
-  if (*grid >= (int64_t(1) << 31)) return false;
+  const int64_t total = (int64_t)N * p.tiles_p * p.tiles_q;
+  if (total >= (int64_t(1) << 30)) return false;
+  p.total_tiles = (int)total;
+  *grid = std::min<int64_t>(total, 2 * (int64_t)stem_compute_units());   // two workgroups fit a compute unit
   *out = p;
   return true;
 }
