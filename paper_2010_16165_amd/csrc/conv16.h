@@ -33,4 +33,10 @@ bool conv_patch_applies(const Conv16Params& geometry, int N);
 const char* conv_patch_name(const Conv16Params& geometry, int N);
 fupr_status launch_conv_patch(const Conv16Params& p, int N, bool bf16, void* stream);
 
+// conv1x1.hip: 1 x 1 convolutions whose filters fit in LDS, streamed.  Geometry
+// fields decide whether it applies.
+bool conv1x1_stream_applies(const Conv16Params& geometry);
+const char* conv1x1_stream_name(const Conv16Params& geometry);
+fupr_status launch_conv1x1_stream(const Conv16Params& p, int N, bool bf16, void* stream);
+
 }  // namespace fupr

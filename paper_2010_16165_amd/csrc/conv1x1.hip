@@ -1,0 +1,300 @@
+// 1 x 1 convolution (Sec. III: operator k x c x 1 x 1; the bottleneck blocks'
+// first and last convolutions and projection shortcuts) as a streaming kernel
+// for layers whose filters fit in LDS: these layers move far more bytes than
+// they multiply, so the kernel is built around keeping many loads in flight.
+//
+//   * A workgroup copies its filter group (all channels) and bias into LDS once
+//     and then streams pixels; it is persistent and sized so that two fit a
+//     compute unit (eight waves).
+//   * Each wave works alone on 16-pixel tiles, with no barrier after the copy:
+//     lane (pixel, channel group) loads its 16 bytes per 32-channel step straight
+//     from global memory in MFMA layout, the filter fragments come from LDS,
+//     the epilogue adds the shortcut, applies ReLU, rounds once and stores
+//     8 bytes per lane.
+//   * The pixel fragments and shortcut values of the wave's next tile are
+//     loaded before the current tile is multiplied, so every wave always has a
+//     whole tile of loads outstanding.
+//   * All global accesses are range-checked buffer accesses: channels past the
+//     tensor's stride and pixels past the end read zeros, stores there vanish.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <cstdlib>
+#include <mutex>
+
+#include "conv16.h"
+#include "device_utils.h"
+#include "fupr.h"
+#include "layout.h"
+
+namespace fupr {
+namespace {
+
+constexpr uint32_t kOutside = 0x80000000u;
+constexpr int kStreamLdsLimit = 72 * 1024;   // two workgroups per compute unit
+
+struct StreamParams {
+  const uint16_t* x;
+  const uint16_t* w;     // [nchunk_pad][Kp][8]
+  const float* bias;
+  const uint16_t* res;
+  uint16_t* y;
+  uint32_t x_bytes, w_bytes, y_bytes, res_bytes;
+  int H, W, xcs;
+  int P, Q, PQ, M, ycs;
+  int stride;
+  int Kp, cpt, ksteps;
+  int rH, rW, rcs, rss, roff;
+  int relu;
+  int plain;             // pixel m of the output is pixel m of the input and of the shortcut
+  int n_tiles;           // 16-pixel tiles
+};
+
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef short short2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t clamp_below2(uint32_t v, uint32_t floor2) {
+  const short2_t a = __builtin_bit_cast(short2_t, v), f = __builtin_bit_cast(short2_t, floor2);
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(a, f));
+}
+
+// NT filter tiles of 16 per workgroup (every wave computes all of them for its
+// pixels); at most KMAX steps of 32 channels.
+template <bool BF, int NT, int KMAX>
+__global__ __launch_bounds__(256) void conv1x1_stream_kernel(const StreamParams p) {
+  constexpr int NF = NT * 16;
+  extern __shared__ uint4 lds4[];
+  char* lds = reinterpret_cast<char*>(lds4);
+  float* bias_lds = reinterpret_cast<float*>(lds);                 // [NF]
+  char* wts = lds + NF * 4;                                        // [ksteps * 4][NF][16 bytes]
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int li = lane & 15, g = lane >> 4;
+  const int f0 = blockIdx.y * NF;
+
+  const __amdgpu_buffer_rsrc_t xrsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.x), 0, p.x_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t wrsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.w), 0, p.w_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t yrsrc =
+      __builtin_amdgcn_make_buffer_rsrc(p.y, 0, p.y_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rrsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.res), 0, p.res_bytes, 0x00020000);
+
+  // ---- filters and bias of this group -> LDS -----------------------------------------
+  for (int e = tid; e < p.ksteps * 4 * NF; e += 256) {
+    const int chunk = e / NF, f = e - chunk * NF;
+    const bool ok = chunk < p.cpt && f0 + f < p.Kp;
+    const uint32_t off = ok ? (uint32_t)(chunk * p.Kp + f0 + f) * 16u : kOutside;
+    *reinterpret_cast<uint4*>(wts + e * 16) =
+        __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, off, 0, 0));
+  }
+  for (int e = tid; e < NF; e += 256) bias_lds[e] = f0 + e < p.Kp ? p.bias[f0 + e] : 0.f;
+  __syncthreads();
+
+  // ---- this wave's tiles -------------------------------------------------------------
+  const int n_waves = gridDim.x * 4;
+  int tile = blockIdx.x * 4 + wave;
+  uint4 bn[KMAX] = {};
+  u32x2 rvn[NT] = {};
+  uint32_t yoff_n = kOutside;
+  auto fetch = [&](int t) {
+    const int m = t * 16 + li;
+    uint32_t xo = kOutside, ro = kOutside;
+    yoff_n = kOutside;
+    if (m < p.M) {
+      yoff_n = (uint32_t)m * (uint32_t)(p.ycs * 2);
+      if (p.plain) {
+        xo = (uint32_t)m * (uint32_t)(p.xcs * 2);
+        ro = (uint32_t)m * (uint32_t)(p.rcs * 2);
+      } else {
+        const int n = m / p.PQ, rem = m - n * p.PQ;
+        const int pp = rem / p.Q, qq = rem - pp * p.Q;
+        xo = (uint32_t)(((n * p.H + pp * p.stride) * p.W + qq * p.stride) * p.xcs) * 2u;
+        ro = (uint32_t)(((n * p.rH + pp * p.rss) * p.rW + qq * p.rss) * p.rcs) * 2u;
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k) {
+      if (k < p.ksteps) {
+        const int chunk = k * 4 + g;
+        const uint32_t off = chunk * 8 < p.xcs ? xo + (uint32_t)chunk * 16u : kOutside;
+        bn[k] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, off, 0, 0));
+      }
+    }
+    if (p.res) {
+#pragma unroll
+      for (int t2 = 0; t2 < NT; ++t2) {
+        const int rc = f0 + t2 * 16 + g * 4 - p.roff;
+        const uint32_t off = (rc >= 0 && rc < p.rcs) ? ro + (uint32_t)rc * 2u : kOutside;
+        rvn[t2] = __builtin_amdgcn_raw_buffer_load_b64(rrsrc, off, 0, 0);
+      }
+    }
+  };
+  if (tile < p.n_tiles) fetch(tile);
+  const uint32_t floor2 = p.relu ? 0u : 0x80008000u;
+  const char* a_lane = wts + (g * NF + li) * 16;
+  for (; tile < p.n_tiles; tile += n_waves) {
+    uint4 b[KMAX];
+    u32x2 rv[NT];
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k) b[k] = bn[k];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) rv[t] = rvn[t];
+    const uint32_t yoff = yoff_n;
+    if (tile + n_waves < p.n_tiles) fetch(tile + n_waves);
+
+    f32x4 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = *reinterpret_cast<const f32x4*>(bias_lds + t * 16 + g * 4);
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k) {
+      if (k < p.ksteps) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          const uint4 a = *reinterpret_cast<const uint4*>(a_lane + (k * 4 * NF + t * 16) * 16);
+          acc[t] = mfma_16x16x32<BF>(a, b[k], acc[t]);
+        }
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      float v[4] = {acc[t][0], acc[t][1], acc[t][2], acc[t][3]};
+      if (p.res) {
+        v[0] += to_float<BF>((uint16_t)(rv[t][0] & 0xffffu));
+        v[1] += to_float<BF>((uint16_t)(rv[t][0] >> 16));
+        v[2] += to_float<BF>((uint16_t)(rv[t][1] & 0xffffu));
+        v[3] += to_float<BF>((uint16_t)(rv[t][1] >> 16));
+      }
+      u32x2 o;
+      o[0] = clamp_below2(pack2<BF>(v[0], v[1]), floor2);
+      o[1] = clamp_below2(pack2<BF>(v[2], v[3]), floor2);
+      const int k0 = f0 + t * 16 + g * 4;
+      const uint32_t off = k0 < p.ycs ? yoff + (uint32_t)k0 * 2u : kOutside;
+      __builtin_amdgcn_raw_buffer_store_b64(o, yrsrc, off, 0, 0);
+    }
+  }
+}
+
+struct StreamTile {
+  int NT, KMAX;
+  const char* name;
+};
+constexpr StreamTile kStreamTiles[] = {
+    {16, 2, "conv1x1s_256f"}, {16, 4, "conv1x1s_256f_c128"}, {8, 8, "conv1x1s_128f"},
+    {4, 8, "conv1x1s_64f"},   {4, 16, "conv1x1s_64f_c512"},  {2, 8, "conv1x1s_32f"},
+};
+constexpr int kNumStreamTiles = sizeof(kStreamTiles) / sizeof(kStreamTiles[0]);
+
+int stream_compute_units() {
+  static int cus = [] {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        n <= 0) {
+      (void)hipGetLastError();
+      return 256;
+    }
+    return n;
+  }();
+  return cus;
+}
+
+size_t stream_lds_bytes(const StreamTile& t, int ksteps) {
+  return (size_t)t.NT * 16 * 4 + (size_t)ksteps * 4 * t.NT * 16 * 16;
+}
+
+// The widest filter group whose filters fit; -1: the layer is not for this kernel.
+int pick_stream(const Conv16Params& c) {
+  if (const char* e = std::getenv("FUPR_CONV1X1_STREAM"))
+    if (e[0] == '0') return -1;
+  if (c.S != 1 || c.nchunk != c.cpt || c.pad != 0 || (c.stride != 1 && c.stride != 2)) return -1;
+  if (c.roff % 4 != 0) return -1;
+  const int ksteps = (c.cpt + 3) / 4;
+  int best = -1;
+  double best_cost = 1e30;
+  for (int i = 0; i < kNumStreamTiles; ++i) {
+    const StreamTile& t = kStreamTiles[i];
+    if (ksteps > t.KMAX || stream_lds_bytes(t, ksteps) > (size_t)kStreamLdsLimit) continue;
+    // padded filter tiles, and the input is read once per group
+    const int groups = (c.FT + t.NT - 1) / t.NT;
+    const double cost = (double)groups * t.NT * 32.0 + (double)groups * c.cpt * 16.0 +
+                        (t.KMAX - ksteps) * 0.01;
+    if (cost < best_cost) {
+      best_cost = cost;
+      best = i;
+    }
+  }
+  return best;
+}
+
+template <bool BF, int NT, int KMAX>
+fupr_status launch_stream(const StreamParams& p, dim3 grid, size_t lds, hipStream_t st) {
+  static std::once_flag once;
+  static hipError_t status = hipSuccess;
+  std::call_once(once, [] {
+    status = hipFuncSetAttribute(
+        reinterpret_cast<const void*>(&conv1x1_stream_kernel<BF, NT, KMAX>),
+        hipFuncAttributeMaxDynamicSharedMemorySize, kStreamLdsLimit);
+  });
+  if (status != hipSuccess) return FUPR_ERR_LAUNCH;
+  hipLaunchKernelGGL((conv1x1_stream_kernel<BF, NT, KMAX>), grid, dim3(256), lds, st, p);
+  return launch_status("conv1x1_stream_kernel");
+}
+
+template <bool BF>
+fupr_status dispatch_stream(int tile, const StreamParams& p, dim3 grid, size_t lds,
+                            hipStream_t st) {
+  switch (tile) {
+    case 0: return launch_stream<BF, 16, 2>(p, grid, lds, st);
+    case 1: return launch_stream<BF, 16, 4>(p, grid, lds, st);
+    case 2: return launch_stream<BF, 8, 8>(p, grid, lds, st);
+    case 3: return launch_stream<BF, 4, 8>(p, grid, lds, st);
+    case 4: return launch_stream<BF, 4, 16>(p, grid, lds, st);
+    default: return launch_stream<BF, 2, 8>(p, grid, lds, st);
+  }
+}
+
+}  // namespace
+
+bool conv1x1_stream_applies(const Conv16Params& c) { return pick_stream(c) >= 0; }
+
+const char* conv1x1_stream_name(const Conv16Params& c) {
+  const int t = pick_stream(c);
+  return t < 0 ? "conv1x1s" : kStreamTiles[t].name;
+}
+
+fupr_status launch_conv1x1_stream(const Conv16Params& c, int N, bool bf16, void* stream) {
+  const int t = pick_stream(c);
+  if (t < 0) return FUPR_ERR_LIMIT;
+  const StreamTile& tile = kStreamTiles[t];
+  StreamParams p{};
+  p.x = c.x; p.w = c.w; p.bias = c.bias; p.res = c.res; p.y = c.y;
+  const uint64_t y_bytes = (uint64_t)c.M * c.ycs * 2;
+  const uint64_t res_bytes = c.res ? (uint64_t)N * c.rH * c.rW * c.rcs * 2 : 0;
+  if ((uint64_t)c.x_bytes >= kOutside || y_bytes >= kOutside || res_bytes >= kOutside)
+    return FUPR_ERR_LIMIT;
+  p.x_bytes = c.x_bytes; p.w_bytes = c.w_bytes;
+  p.y_bytes = (uint32_t)y_bytes; p.res_bytes = (uint32_t)res_bytes;
+  p.H = c.H; p.W = c.W; p.xcs = c.xcs;
+  p.P = c.P; p.Q = c.Q; p.PQ = c.PQ; p.M = c.M; p.ycs = c.ycs;
+  p.stride = c.stride;
+  p.Kp = c.Kp; p.cpt = c.cpt; p.ksteps = (c.cpt + 3) / 4;
+  p.rH = c.rH; p.rW = c.rW; p.rcs = c.rcs; p.rss = c.rss; p.roff = c.roff;
+  p.relu = c.relu;
+  p.plain = c.stride == 1 && (!c.res || (c.rss == 1 && c.rH == c.P && c.rW == c.Q));
+  p.n_tiles = (c.M + 15) / 16;
+  const int groups = (c.FT + tile.NT - 1) / tile.NT;
+  // persistent workgroups, two per compute unit over all filter groups
+  const int per_group = std::max(1, 2 * stream_compute_units() / groups);
+  const int gx = std::min((p.n_tiles + 3) / 4, per_group);
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const dim3 grid((unsigned)gx, (unsigned)groups);
+  const size_t lds = stream_lds_bytes(tile, p.ksteps);
+  return bf16 ? dispatch_stream<true>(t, p, grid, lds, st)
+              : dispatch_stream<false>(t, p, grid, lds, st);
+}
+
+}  // namespace fupr
