@@ -52,6 +52,8 @@ struct StreamParams {
 };
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef void __attribute__((address_space(3)))* LdsPtr;
 typedef short short2_t __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ uint32_t clamp_below2(uint32_t v, uint32_t floor2) {
@@ -84,14 +86,33 @@ __global__ __launch_bounds__(256) void conv1x1_stream_kernel(const StreamParams 
       __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.res), 0, p.res_bytes, 0x00020000);
 
   // ---- filters and bias of this group -> LDS -----------------------------------------
-  for (int e = tid; e < p.ksteps * 4 * NF; e += 256) {
-    const int chunk = e / NF, f = e - chunk * NF;
-    const bool ok = chunk < p.cpt && f0 + f < p.Kp;
-    const uint32_t off = ok ? (uint32_t)(chunk * p.Kp + f0 + f) * 16u : kOutside;
-    *reinterpret_cast<uint4*>(wts + e * 16) =
-        __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, off, 0, 0));
+  // straight into LDS, all loads in flight at once; slots past the group's
+  // filters or the layer's channels receive zeros
+  {
+    const uint64_t wa = reinterpret_cast<uint64_t>(p.w);
+    i32x4 wr;
+    wr[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)wa);
+    wr[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)(wa >> 32));
+    wr[2] = __builtin_amdgcn_readfirstlane((int)p.w_bytes);
+    wr[3] = 0x00020000;
+    const uint32_t wts_lds = (uint32_t)(uintptr_t)(LdsPtr)wts;
+    const int n_slots = p.ksteps * 4 * NF;
+    for (int base = wave * 64; base < n_slots; base += 256) {
+      const int e = base + lane;
+      const int chunk = e / NF, f = e - chunk * NF;
+      const bool ok = e < n_slots && chunk < p.cpt && f0 + f < p.Kp;
+      const uint32_t off = ok ? (uint32_t)(chunk * p.Kp + f0 + f) * 16u : kOutside;
+      asm volatile(
+          "s_mov_b32 m0, %0\n\t"
+          "s_nop 0\n\t"
+          "buffer_load_dwordx4 %1, %2, 0 offen lds"
+          :
+          : "s"(wts_lds + base * 16), "v"(off), "s"(wr)
+          : "memory", "m0");
+    }
   }
   for (int e = tid; e < NF; e += 256) bias_lds[e] = f0 + e < p.Kp ? p.bias[f0 + e] : 0.f;
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
   // ---- this wave's tiles -------------------------------------------------------------
@@ -203,7 +224,8 @@ int stream_compute_units() {
 }
 
 size_t stream_lds_bytes(const StreamTile& t, int ksteps) {
-  return (size_t)t.NT * 16 * 4 + (size_t)ksteps * 4 * t.NT * 16 * 16;
+  // the filter area is written by whole waves of 1 KB
+  return (size_t)t.NT * 16 * 4 + round_up_sz((size_t)ksteps * 4 * t.NT * 16 * 16, 1024);
 }
 
 // The widest filter group whose filters fit; -1: the layer is not for this kernel.
