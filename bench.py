@@ -49,6 +49,39 @@ def cpu_baseline(model, batch, aggressive="off", budget_s=12.0):
             "sample": f"{n} of {batch} images of the workload, {passes} passes, {spent:.1f} s"}
 
 
+def quick_measure(config, steps=40, warmup=5):
+    """Graph-replay time of another configuration of the same path (context beside
+    the headline workload): images/s, TFLOP/s at algorithmic flops."""
+    import torch
+    import synth
+    from paper_2010_16165_amd import binding as B, network
+    model, batch = synth.make_config(config)
+    dt = B.DTYPES[model["dtype"]]
+    fm, _ = network.build(network.optimise(model))
+    x = synth.make_input(synth.BASE_SEED + config, batch, model["in_shape"])
+    xd = B.DeviceTensor.from_nchw(x, dt)
+    stream = torch.cuda.Stream()
+    sp = B.C.c_void_p(stream.cuda_stream)
+    with torch.cuda.stream(stream):
+        out, ws = fm.alloc(batch)
+        stream.synchronize()
+        graph = fm.fupr_graph_create(xd, out, ws, sp)
+        for _ in range(warmup):
+            fm.fupr_graph_launch(graph, sp)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fm.fupr_graph_launch(graph, sp)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / steps * 1e3
+    flops = sum(fm.launch_stats(batch, i)["flops"] for i in range(fm.num_launches))
+    peak = PEAK_FP32 if dt == B.F32 else PEAK_MFMA_16BIT
+    return {"workload": model["name"], "config_index": config, "batch": batch,
+            "dtype": model["dtype"], "kernel_launches": fm.num_launches, "ms_per_step": ms,
+            "images_per_s": batch / (ms * 1e-3), "tflops": flops / (ms * 1e-3) / 1e12,
+            "mfma_frac": flops / (ms * 1e-3) / peak}
+
+
 def measured_traffic(kernel, args):
     """HBM bytes per launch of the dominant kernel from the stored rocprofv3 counter
     runs (FETCH_SIZE and WRITE_SIZE, each scaled by a copy of known size); None when
@@ -84,6 +117,8 @@ def main():
                          "convolutions, no additions; fused-pruned = then the n - m prune-back of Alg. 1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-op", action="store_true", help="print a per-operator table to stderr")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short runs of the ImageNet-size configurations")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="also run a plain device-to-device copy of MIB mebibytes (a kernel of "
                          "known traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE by)")
@@ -156,8 +191,10 @@ def main():
     n_launch = fm.num_launches
     stats = [fm.launch_stats(batch, i) for i in range(n_launch)]
     op_ms = op_ms[:n_launch]
-    if n_launch != fm.num_ops:
-        sites = ["network"] * n_launch
+    if n_launch == 1 and fm.num_ops > 1:
+        sites = ["network"]
+    elif n_launch == fm.num_ops - 1 and stats[0]["kernel"] == "stem7x7_maxpool":
+        sites = [sites[0]] + list(sites[2:])    # stem convolution and max-pool are one launch
     total_flops = sum(s["flops"] for s in stats)
     total_bytes = sum(s["bytes"] for s in stats)
     images_per_s = batch / (ms_per_step * 1e-3)
@@ -215,6 +252,13 @@ def main():
         "hbm_frac_network": total_bytes / (ms_per_step * 1e-3) / PEAK_HBM,
         "roofline": roof,
     }
+    default_run = (args.config == 1 and not args.batch and args.schedule == "auto"
+                   and args.aggressive == "off" and not args.workload)
+    if default_run and not args.no_other_workloads:
+        # the larger configurations of the same path, a few replays each
+        del xd, out, ws
+        torch.cuda.empty_cache()
+        line["other_workloads"] = [quick_measure(c) for c in (2, 3, 4)]
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(model, batch, args.aggressive)
     print(json.dumps(line))

@@ -52,6 +52,7 @@ struct StreamParams {
 };
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef void __attribute__((address_space(3)))* LdsPtr;
 typedef short short2_t __attribute__((ext_vector_type(2)));
@@ -119,7 +120,10 @@ __global__ __launch_bounds__(256) void conv1x1_stream_kernel(const StreamParams 
   const int n_waves = gridDim.x * 4;
   int tile = blockIdx.x * 4 + wave;
   uint4 bn[KMAX] = {};
-  u32x2 rvn[NT] = {};
+  static_assert(NT % 2 == 0, "filter tiles are handled in pairs");
+  constexpr int NP = NT / 2;
+  u32x4 rvn[NP] = {};
+  const int k_pair = (g & 1) * 16 + (g >> 1) * 8;   // channel of this lane's 16 bytes in a tile pair
   uint32_t yoff_n = kOutside;
   auto fetch = [&](int t) {
     const int m = t * 16 + li;
@@ -147,10 +151,10 @@ __global__ __launch_bounds__(256) void conv1x1_stream_kernel(const StreamParams 
     }
     if (p.res) {
 #pragma unroll
-      for (int t2 = 0; t2 < NT; ++t2) {
-        const int rc = f0 + t2 * 16 + g * 4 - p.roff;
+      for (int pr = 0; pr < NP; ++pr) {
+        const int rc = f0 + pr * 32 + k_pair - p.roff;
         const uint32_t off = (rc >= 0 && rc < p.rcs) ? ro + (uint32_t)rc * 2u : kOutside;
-        rvn[t2] = __builtin_amdgcn_raw_buffer_load_b64(rrsrc, off, 0, 0);
+        rvn[pr] = __builtin_amdgcn_raw_buffer_load_b128(rrsrc, off, 0, 0);
       }
     }
   };
@@ -159,11 +163,11 @@ __global__ __launch_bounds__(256) void conv1x1_stream_kernel(const StreamParams 
   const char* a_lane = wts + (g * NF + li) * 16;
   for (; tile < p.n_tiles; tile += n_waves) {
     uint4 b[KMAX];
-    u32x2 rv[NT];
+    u32x4 rv[NP];
 #pragma unroll
     for (int k = 0; k < KMAX; ++k) b[k] = bn[k];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) rv[t] = rvn[t];
+    for (int pr = 0; pr < NP; ++pr) rv[pr] = rvn[pr];
     const uint32_t yoff = yoff_n;
     if (tile + n_waves < p.n_tiles) fetch(tile + n_waves);
 
@@ -180,21 +184,39 @@ __global__ __launch_bounds__(256) void conv1x1_stream_kernel(const StreamParams 
         }
       }
     }
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      float v[4] = {acc[t][0], acc[t][1], acc[t][2], acc[t][3]};
+    // Epilogue in pairs of filter tiles exchanged between 16-lane rows: lane
+    // (pixel, g) then holds channels (g >> 1) * 8 .. + 7 of tile t + (g & 1), so
+    // every access is 16 bytes and a pixel's 64 bytes come from four lanes.
+    auto finish = [&](const f32x4& av, uint32_t r0, uint32_t r1) {
+      float v[4] = {av[0], av[1], av[2], av[3]};
       if (p.res) {
-        v[0] += to_float<BF>((uint16_t)(rv[t][0] & 0xffffu));
-        v[1] += to_float<BF>((uint16_t)(rv[t][0] >> 16));
-        v[2] += to_float<BF>((uint16_t)(rv[t][1] & 0xffffu));
-        v[3] += to_float<BF>((uint16_t)(rv[t][1] >> 16));
+        v[0] += to_float<BF>((uint16_t)(r0 & 0xffffu));
+        v[1] += to_float<BF>((uint16_t)(r0 >> 16));
+        v[2] += to_float<BF>((uint16_t)(r1 & 0xffffu));
+        v[3] += to_float<BF>((uint16_t)(r1 >> 16));
       }
       u32x2 o;
       o[0] = clamp_below2(pack2<BF>(v[0], v[1]), floor2);
       o[1] = clamp_below2(pack2<BF>(v[2], v[3]), floor2);
-      const int k0 = f0 + t * 16 + g * 4;
+      return o;
+    };
+#pragma unroll
+    for (int pr = 0; pr < NP; ++pr) {
+      const int t = 2 * pr;
+      uint32_t ra0 = 0, ra1 = 0, rb0 = 0, rb1 = 0;
+      if (p.res) {
+        const auto s0 = __builtin_amdgcn_permlane16_swap(rv[pr][0], rv[pr][2], false, false);
+        const auto s1 = __builtin_amdgcn_permlane16_swap(rv[pr][1], rv[pr][3], false, false);
+        ra0 = s0[0]; ra1 = s1[0];
+        rb0 = s0[1]; rb1 = s1[1];
+      }
+      const u32x2 oa = finish(acc[t], ra0, ra1), ob = finish(acc[t + 1], rb0, rb1);
+      const auto w0 = __builtin_amdgcn_permlane16_swap(oa[0], ob[0], false, false);
+      const auto w1 = __builtin_amdgcn_permlane16_swap(oa[1], ob[1], false, false);
+      const u32x4 o4 = {w0[0], w1[0], w0[1], w1[1]};
+      const int k0 = f0 + pr * 32 + k_pair;
       const uint32_t off = k0 < p.ycs ? yoff + (uint32_t)k0 * 2u : kOutside;
-      __builtin_amdgcn_raw_buffer_store_b64(o, yrsrc, off, 0, 0);
+      __builtin_amdgcn_raw_buffer_store_b128(o4, yrsrc, off, 0, 0);
     }
   }
 }
@@ -233,7 +255,7 @@ int pick_stream(const Conv16Params& c) {
   if (const char* e = std::getenv("FUPR_CONV1X1_STREAM"))
     if (e[0] == '0') return -1;
   if (c.S != 1 || c.nchunk != c.cpt || c.pad != 0 || (c.stride != 1 && c.stride != 2)) return -1;
-  if (c.roff % 4 != 0) return -1;
+  if (c.roff % 8 != 0) return -1;   // 16-byte shortcut loads
   const int ksteps = (c.cpt + 3) / 4;
   int best = -1;
   double best_cost = 1e30;

@@ -110,6 +110,7 @@ __device__ __forceinline__ i32x4 make_rsrc(const void* base, uint32_t bytes) {
 typedef void __attribute__((address_space(3)))* LdsPtr;
 typedef short short2_t __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ uint32_t clamp_below(uint32_t v, uint32_t floor2) {
   const short2_t a = __builtin_bit_cast(short2_t, v), f = __builtin_bit_cast(short2_t, floor2);
@@ -252,7 +253,13 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
   uint32_t yoff[MT], roff[MT];   // byte offsets of the pixel in y and in the shortcut tensor
   int c_f0 = 0;
   f32x4 acc[MT][NT], bias4[NT];
-  u32x2 rv[MT][NT];              // shortcut values, fetched during the last stage
+  // Epilogue accesses are 16 bytes per lane: a pair of filter tiles (t, t + 1)
+  // is exchanged between 16-lane rows, after which lane (pixel, g) holds channels
+  // (g >> 1) * 8 .. + 7 of tile t + (g & 1), i.e. a pixel's 64 bytes of the pair
+  // come from four lanes of one instruction.  An odd last tile keeps 8 bytes.
+  constexpr int NP = NT / 2;
+  u32x4 rvw[MT][NP > 0 ? NP : 1];   // shortcut values, fetched during the last stage
+  u32x2 rvo[MT];
   auto setup_compute = [&](int tile) {
     const int strip = tile / p.fgroups;
     c_f0 = (tile - strip * p.fgroups) * NF;
@@ -284,6 +291,7 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
   };
   const int a_lane = g * (NF * 16) + (wn * NT * 16 + li) * 16;
   const int k_lane = (wn * NT * 16 + g * 4);
+  const int k_pair = wn * NT * 16 + (g & 1) * 16 + (g >> 1) * 8;
   const uint32_t floor2 = p.relu ? 0u : 0x80008000u;
 
   int c_tile = t_begin, c_stage = 0;
@@ -296,11 +304,19 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-          const int rc = c_f0 + k_lane + t * 16 - p.roff;
+        for (int pr = 0; pr < NP; ++pr) {
+          const int rc = c_f0 + k_pair + pr * 32 - p.roff;
           const uint32_t off = (rc >= 0 && rc < p.rcs) ? roff[mt] + (uint32_t)rc * 2u : kOutside;
-          rv[mt][t] = __builtin_amdgcn_raw_buffer_load_b64(rrsrc, off, 0, 0);
+          rvw[mt][pr] = __builtin_amdgcn_raw_buffer_load_b128(rrsrc, off, 0, 0);
         }
+      if constexpr (NT & 1) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const int rc = c_f0 + k_lane + (NT - 1) * 16 - p.roff;
+          const uint32_t off = (rc >= 0 && rc < p.rcs) ? roff[mt] + (uint32_t)rc * 2u : kOutside;
+          rvo[mt] = __builtin_amdgcn_raw_buffer_load_b64(rrsrc, off, 0, 0);
+        }
+      }
     }
     const char* wts = lds + (p.w_resident ? c_stage * kWeightBytes : buf * p.buf_stride);
     const char* patch = lds + p.patch_base + buf * p.buf_stride;
@@ -332,21 +348,44 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
     }
     if (last) {
       // bias, shortcut, ReLU, one rounding
+      auto finish = [&](const f32x4& av, const f32x4& bv, uint32_t r0, uint32_t r1) {
+        float v[4] = {av[0] + bv[0], av[1] + bv[1], av[2] + bv[2], av[3] + bv[3]};
+        if (p.res) {
+          v[0] += to_float<BF>((uint16_t)(r0 & 0xffffu));
+          v[1] += to_float<BF>((uint16_t)(r0 >> 16));
+          v[2] += to_float<BF>((uint16_t)(r1 & 0xffffu));
+          v[3] += to_float<BF>((uint16_t)(r1 >> 16));
+        }
+        u32x2 o;
+        o[0] = clamp_below(pack2<BF>(v[0], v[1]), floor2);
+        o[1] = clamp_below(pack2<BF>(v[2], v[3]), floor2);
+        return o;
+      };
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-          float v[4] = {acc[mt][t][0] + bias4[t][0], acc[mt][t][1] + bias4[t][1],
-                        acc[mt][t][2] + bias4[t][2], acc[mt][t][3] + bias4[t][3]};
+        for (int pr = 0; pr < NP; ++pr) {
+          const int t = 2 * pr;
+          uint32_t ra0 = 0, ra1 = 0, rb0 = 0, rb1 = 0;
           if (p.res) {
-            v[0] += to_float<BF>((uint16_t)(rv[mt][t][0] & 0xffffu));
-            v[1] += to_float<BF>((uint16_t)(rv[mt][t][0] >> 16));
-            v[2] += to_float<BF>((uint16_t)(rv[mt][t][1] & 0xffffu));
-            v[3] += to_float<BF>((uint16_t)(rv[mt][t][1] >> 16));
+            const u32x4 x4 = rvw[mt][pr];
+            const auto s0 = __builtin_amdgcn_permlane16_swap(x4[0], x4[2], false, false);
+            const auto s1 = __builtin_amdgcn_permlane16_swap(x4[1], x4[3], false, false);
+            ra0 = s0[0]; ra1 = s1[0];   // tile t
+            rb0 = s0[1]; rb1 = s1[1];   // tile t + 1
           }
-          u32x2 o;
-          o[0] = clamp_below(pack2<BF>(v[0], v[1]), floor2);
-          o[1] = clamp_below(pack2<BF>(v[2], v[3]), floor2);
+          const u32x2 oa = finish(acc[mt][t], bias4[t], ra0, ra1);
+          const u32x2 ob = finish(acc[mt][t + 1], bias4[t + 1], rb0, rb1);
+          const auto w0 = __builtin_amdgcn_permlane16_swap(oa[0], ob[0], false, false);
+          const auto w1 = __builtin_amdgcn_permlane16_swap(oa[1], ob[1], false, false);
+          const u32x4 o4 = {w0[0], w1[0], w0[1], w1[1]};
+          const int k0 = c_f0 + k_pair + pr * 32;
+          const uint32_t off = k0 < p.ycs ? yoff[mt] + (uint32_t)k0 * 2u : kOutside;
+          __builtin_amdgcn_raw_buffer_store_b128(o4, yrsrc, off, 0, 0);
+        }
+        if constexpr (NT & 1) {
+          const int t = NT - 1;
+          const u32x2 o = finish(acc[mt][t], bias4[t], rvo[mt][0], rvo[mt][1]);
           const int k0 = c_f0 + k_lane + t * 16;
           const uint32_t off = k0 < p.ycs ? yoff[mt] + (uint32_t)k0 * 2u : kOutside;
           __builtin_amdgcn_raw_buffer_store_b64(o, yrsrc, off, 0, 0);
@@ -405,6 +444,7 @@ bool plan_patch(const Conv16Params& c, int N, const PatchTile& tile, PatchPlan* 
   const int NW = tile.WM * tile.WN;
   const int BM = tile.WM * tile.MT * 16, NF = tile.WN * tile.NT * 16;
   if (c.P * c.stride != c.H) return false;
+  if (c.res && c.roff % 8 != 0) return false;   // 16-byte shortcut loads
   p.x = c.x; p.w = c.w; p.bias = c.bias; p.res = c.res; p.y = c.y;
   p.x_bytes = c.x_bytes; p.w_bytes = c.w_bytes;
   p.N = N; p.H = c.H; p.W = c.W; p.xcs = c.xcs;

@@ -24,8 +24,8 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 STORE = os.path.join(HERE, "traffic.json")
-SOURCES = ["csrc/resident.hip", "csrc/conv_tiled.hip", "csrc/kernels.hip", "csrc/model.cpp",
-           "csrc/layout.h", "csrc/device_utils.h", "csrc/conv16.h"]
+# what the recorded kernel is compiled from
+SOURCES = ["csrc/resident.hip", "csrc/layout.h", "csrc/device_utils.h"]
 KERNELS = {"resident_network": "resident_kernel"}
 COPY_MIB = 1024
 
