@@ -39,4 +39,10 @@ bool conv1x1_stream_applies(const Conv16Params& geometry);
 const char* conv1x1_stream_name(const Conv16Params& geometry);
 fupr_status launch_conv1x1_stream(const Conv16Params& p, int N, bool bf16, void* stream);
 
+// conv1x1_pipe.hip: 1 x 1 convolutions with 128 channels or more whose filters do
+// not fit in LDS, as a pipelined GEMM.
+bool conv1x1_pipe_applies(const Conv16Params& geometry);
+const char* conv1x1_pipe_name(const Conv16Params& geometry);
+fupr_status launch_conv1x1_pipe(const Conv16Params& p, int N, bool bf16, void* stream);
+
 }  // namespace fupr

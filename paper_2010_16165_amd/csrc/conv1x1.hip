@@ -113,8 +113,6 @@ __global__ __launch_bounds__(256) void conv1x1_stream_kernel(const StreamParams 
     }
   }
   for (int e = tid; e < NF; e += 256) bias_lds[e] = f0 + e < p.Kp ? p.bias[f0 + e] : 0.f;
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
 
   // ---- this wave's tiles -------------------------------------------------------------
   const int n_waves = gridDim.x * 4;
@@ -158,7 +156,9 @@ __global__ __launch_bounds__(256) void conv1x1_stream_kernel(const StreamParams 
       }
     }
   };
-  if (tile < p.n_tiles) fetch(tile);
+  if (tile < p.n_tiles) fetch(tile);   // in flight while the filters arrive
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();   // filters and bias are in LDS
   const uint32_t floor2 = p.relu ? 0u : 0x80008000u;
   const char* a_lane = wts + (g * NF + li) * 16;
   for (; tile < p.n_tiles; tile += n_waves) {
