@@ -244,12 +244,20 @@ Conv16Params geometry16(const fupr_conv_shape& s, fupr_dtype dt, int N, int H, i
   return p;
 }
 
+// Between the two 1 x 1 kernels (measured per layer on the ResNet-50 workloads):
+// the pipelined GEMM wins from 512 input channels on and on the small images of
+// the last stages; the streaming kernel wins where pixels are many and filters few.
+bool prefer_pipe(const Conv16Params& g) {
+  return conv1x1_pipe_applies(g) && (g.cpt >= 64 || g.M <= 16384);
+}
+
 }  // namespace
 
 const char* conv_kernel_name(const fupr_conv_shape& s, fupr_dtype dt, int N, int H, int W) {
   if (dt == FUPR_F32) return "conv32_direct";
   const Conv16Params g = geometry16(s, dt, N, H, W);
   if (s.R == 3 && conv_patch_applies(g, N)) return conv_patch_name(g, N);
+  if (s.R == 1 && prefer_pipe(g)) return conv1x1_pipe_name(g);
   if (s.R == 1 && conv1x1_stream_applies(g)) return conv1x1_stream_name(g);
   if (s.R == 1 && conv1x1_pipe_applies(g)) return conv1x1_pipe_name(g);
   return conv16_tiled_name(g.FT, g.nsteps, g.M);
@@ -293,6 +301,7 @@ fupr_status launch_conv(const ConvArgs& a, void* stream) {
   p.x_bytes = (uint32_t)((int64_t)a.N * a.H * a.W * a.xcs * 2);
   p.w_bytes = (uint32_t)((size_t)L.nchunk_pad * L.Kp * 16);
   if (a.R == 3 && conv_patch_applies(p, a.N)) return launch_conv_patch(p, a.N, a.dt == FUPR_BF16, stream);
+  if (a.R == 1 && prefer_pipe(p)) return launch_conv1x1_pipe(p, a.N, a.dt == FUPR_BF16, stream);
   if (a.R == 1 && conv1x1_stream_applies(p)) return launch_conv1x1_stream(p, a.N, a.dt == FUPR_BF16, stream);
   if (a.R == 1 && conv1x1_pipe_applies(p)) return launch_conv1x1_pipe(p, a.N, a.dt == FUPR_BF16, stream);
   return launch_conv16_tiled(p, a.dt == FUPR_BF16, stream);
