@@ -591,7 +591,14 @@ bool conv_patch_applies(const Conv16Params& c, int N) {
     return false;
   if (c.cpt < 2) return false;   // fewer than 16 channels: nothing to reuse
   PatchPlan plan;
-  return pick_patch(c, N, &plan) >= 0;
+  const int t = pick_patch(c, N, &plan);
+  if (t < 0) return false;
+  // Stride 2 needs four input pixels per output pixel in LDS; where that leaves
+  // only tiles under 128 x 64 (56 x 56 inputs), the general kernel, which reads
+  // pixel fragments straight from global memory, was measured faster.
+  const int area = kTiles[t].WM * kTiles[t].MT * 16 * kTiles[t].WN * kTiles[t].NT * 16;
+  if (c.stride == 2 && area < 128 * 64) return false;
+  return true;
 }
 
 const char* conv_patch_name(const Conv16Params& c, int N) {
