@@ -361,6 +361,37 @@ def test_model_plan_shares_buffers_and_reports_shapes():
     assert s["kernel"].startswith("conv")
 
 
+def test_kernel_selection_per_layer_class():
+    """Which kernel an operator launches is decided on the host from its shape
+    alone: every layer class of the ImageNet workloads must get its own kernel."""
+    ops = fake_ops([
+        (B.OP_CONV, 0, -1, 64, 3, 7, 2, 3, B.FUSE_RELU, 1),                   # t1 64 x 112 x 112
+        (B.OP_MAXPOOL, 1, -1, 1, 1, 3, 2, 1, 0, 1),                           # t2 64 x 56 x 56
+        (B.OP_CONV, 2, -1, 45, 64, 3, 1, 1, B.FUSE_RELU, 1),                  # t3
+        (B.OP_CONV, 3, 2, 64, 45, 3, 1, 1, B.FUSE_RELU | B.FUSE_ADD, 1),      # t4
+        (B.OP_CONV, 4, -1, 256, 64, 1, 1, 0, 0, 1),                           # t5 256 x 56 x 56
+        (B.OP_CONV, 5, -1, 32, 256, 1, 1, 0, B.FUSE_RELU, 1),                 # t6
+        (B.OP_CONV, 6, -1, 90, 32, 3, 2, 1, B.FUSE_RELU, 1),                  # t7 90 x 28 x 28
+        (B.OP_CONV, 7, -1, 1024, 90, 1, 2, 0, 0, 1),                          # t8 1024 x 14 x 14
+        (B.OP_CONV, 8, -1, 128, 1024, 1, 1, 0, B.FUSE_RELU, 1),               # t9
+    ])
+    m = B.Model(B.BF16, (3, 224, 224), ops, None)
+    names = [m.op_stats(64, i)["kernel"] for i in range(m.num_ops)]
+    assert names[2].startswith("conv3x3p_") and names[3].startswith("conv3x3p_")
+    assert names[4].startswith("conv1x1s_") and names[5].startswith("conv1x1s_")
+    assert names[6].startswith("conv16t_")        # stride 2 at 56 x 56: the general kernel
+    assert names[8].startswith("conv1x1p_")       # 1024 channels: filters do not fit in LDS
+    # the stem convolution and the max-pool behind it are one launch
+    assert m.num_launches == m.num_ops - 1
+    first = m.launch_stats(64, 0)
+    assert first["kernel"] == "stem7x7_maxpool"
+    conv, pool = m.op_stats(64, 0), m.op_stats(64, 1)
+    mid = 2 * 64 * 112 * 112 * 64
+    assert first["flops"] == conv["flops"] and first["bytes"] == conv["bytes"] + pool["bytes"] - 2 * mid
+    m.set_schedule(B.SCHEDULE_PER_LAYER)
+    assert m.num_launches == m.num_ops and m.launch_stats(64, 0)["kernel"].startswith("conv16t_")
+
+
 def test_model_create_errors():
     ok = (B.OP_CONV, 0, -1, 16, 3, 3, 1, 1, B.FUSE_RELU, 1)
     cases = [
