@@ -27,6 +27,8 @@ struct TensorInfo {
 
 }  // namespace
 
+constexpr int kMaxSplit = 4;
+
 struct fupr_model {
   fupr_dtype dt;
   std::vector<fupr_op_desc> ops;
@@ -40,6 +42,13 @@ struct fupr_model {
   std::vector<size_t> res_table_at;       // first entry of each layer's table
   void* res_dev = nullptr;                // device copy: layer table, then tap tables
   std::mutex res_mutex;
+  // Per-operator schedule: the batch runs as kSplit sub-batches on streams of
+  // their own that fork from and join the caller's stream, so that one
+  // sub-batch's launch gaps, prologues and tails are filled by the other's work.
+  bool side_ready = false;
+  hipStream_t side_stream[kMaxSplit - 1] = {};
+  hipEvent_t fork_event = nullptr, join_event[kMaxSplit - 1] = {};
+  std::mutex side_mutex;                  // one forked enqueue at a time
 };
 
 struct fupr_graph {
@@ -498,6 +507,8 @@ void plan_resident(fupr_model* m) {
   }
 }
 
+void release_side(fupr_model* m);   // below, with the forked schedule
+
 void release_resident(fupr_model* m) {
   if (m->res_dev) (void)hipFree(m->res_dev);
   m->res_dev = nullptr;
@@ -672,6 +683,7 @@ extern "C" fupr_status fupr_model_set_schedule(fupr_model* m, int32_t schedule) 
 extern "C" void fupr_model_destroy(fupr_model* m) {
   if (!m) return;
   release_resident(m);
+  release_side(m);
   delete m;
 }
 
@@ -741,6 +753,43 @@ std::vector<Launch> launches_of(const fupr_model* m) {
   return v;
 }
 
+// Sub-batches of the per-operator schedule.  Measured on the ImageNet-size
+// workloads: two sub-batches of 128 images gain 6 %, sub-batches of 32 lose 11 %
+// (their kernels no longer fill the compute units), more than two never pay;
+// so two from 192 images on, else one.  FUPR_SPLIT=<1..4> forces a count.
+int split_count(int N) {
+  const char* e = getenv("FUPR_SPLIT");   // read at every call: a tuning and testing aid
+  const int forced = e ? std::min(std::max(atoi(e), 1), kMaxSplit) : 0;
+  if (forced) return std::min(forced, std::max(N / 8, 1));
+  return N >= 192 ? 2 : 1;
+}
+
+// Streams and events of the forked schedule; created outside any stream capture.
+bool ensure_side(const fupr_model* cm) {
+  fupr_model* m = const_cast<fupr_model*>(cm);
+  std::lock_guard<std::mutex> lock(m->res_mutex);
+  if (m->side_ready) return true;
+  bool ok = hipEventCreateWithFlags(&m->fork_event, hipEventDisableTiming) == hipSuccess;
+  for (int k = 0; ok && k < kMaxSplit - 1; ++k) {
+    ok = hipStreamCreateWithFlags(&m->side_stream[k], hipStreamNonBlocking) == hipSuccess &&
+         hipEventCreateWithFlags(&m->join_event[k], hipEventDisableTiming) == hipSuccess;
+  }
+  if (!ok) {
+    (void)hipGetLastError();
+    return false;
+  }
+  m->side_ready = true;
+  return true;
+}
+
+void release_side(fupr_model* m) {
+  if (m->fork_event) (void)hipEventDestroy(m->fork_event);
+  for (int k = 0; k < kMaxSplit - 1; ++k) {
+    if (m->join_event[k]) (void)hipEventDestroy(m->join_event[k]);
+    if (m->side_stream[k]) (void)hipStreamDestroy(m->side_stream[k]);
+  }
+}
+
 fupr_status run(const fupr_model* m, const fupr_tensor* input, const fupr_tensor* output,
                 void* workspace, size_t workspace_bytes, void* stream, hipEvent_t* events) {
   if (!m || !input || !output || !workspace) return FUPR_ERR_NULL;
@@ -765,13 +814,25 @@ fupr_status run(const fupr_model* m, const fupr_tensor* input, const fupr_tensor
     base[b] = reinterpret_cast<char*>(workspace) + off;
     off += round_up_sz(m->buffer_elems[b] * (size_t)N * elem_size(m->dt), 256);
   }
-  auto view = [&](int tid) {
+  // images n0 .. n0 + count - 1 of a tensor; inside a workspace buffer every
+  // sub-batch owns the slice its images would need at the buffer's largest tensor
+  const size_t es = elem_size(m->dt);
+  auto view = [&](int tid, int n0, int count) {
     const TensorInfo& t = m->tensors[tid];
     fupr_tensor v;
-    v.N = N; v.H = t.H; v.W = t.W; v.C = t.C; v.dt = m->dt;
-    if (t.buffer == -1) { v.c_stride = input->c_stride; v.ptr = input->ptr; }
-    else if (t.buffer == -2) { v.c_stride = output->c_stride; v.ptr = output->ptr; }
-    else { v.c_stride = t.cs; v.ptr = base[t.buffer]; }
+    v.N = count; v.H = t.H; v.W = t.W; v.C = t.C; v.dt = m->dt;
+    char* ptr;
+    if (t.buffer == -1) {
+      v.c_stride = input->c_stride;
+      ptr = (char*)input->ptr + (size_t)n0 * t.H * t.W * input->c_stride * es;
+    } else if (t.buffer == -2) {
+      v.c_stride = output->c_stride;
+      ptr = (char*)output->ptr + (size_t)n0 * t.H * t.W * output->c_stride * es;
+    } else {
+      v.c_stride = t.cs;
+      ptr = base[t.buffer] + (size_t)n0 * m->buffer_elems[t.buffer] * es;
+    }
+    v.ptr = ptr;
     return v;
   };
 
@@ -789,33 +850,59 @@ fupr_status run(const fupr_model* m, const fupr_tensor* input, const fupr_tensor
     return FUPR_OK;
   }
   const std::vector<Launch> launches = launches_of(m);
-  for (size_t l = 0; l < launches.size(); ++l) {
-    const size_t i = (size_t)launches[l].first;
-    const fupr_op_desc& op = m->ops[i];
-    const fupr_tensor x = view(op.in), y = view((int)i + launches[l].count);
-    fupr_status st;
-    if (launches[l].count == 2) {
-      const fupr_op_desc& pool = m->ops[i + 1];
-      st = fupr_conv_maxpool_fused(&op.conv, &x, op.packed, pool.conv.R, pool.conv.stride,
-                                   pool.conv.pad, &y, stream);
-    } else if (op.kind == FUPR_OP_CONV) {
-      fupr_residual r;
-      const bool add = op.res >= 0;
-      if (add) {
-        r.t = view(op.res);
-        r.spatial_stride = op.res_spatial_stride;
-        r.c_offset = op.res_c_offset;
+  auto enqueue = [&](int n0, int count, void* on, bool record) -> fupr_status {
+    for (size_t l = 0; l < launches.size(); ++l) {
+      const size_t i = (size_t)launches[l].first;
+      const fupr_op_desc& op = m->ops[i];
+      const fupr_tensor x = view(op.in, n0, count);
+      const fupr_tensor y = view((int)i + launches[l].count, n0, count);
+      fupr_status st;
+      if (launches[l].count == 2) {
+        const fupr_op_desc& pool = m->ops[i + 1];
+        st = fupr_conv_maxpool_fused(&op.conv, &x, op.packed, pool.conv.R, pool.conv.stride,
+                                     pool.conv.pad, &y, on);
+      } else if (op.kind == FUPR_OP_CONV) {
+        fupr_residual r;
+        const bool add = op.res >= 0;
+        if (add) {
+          r.t = view(op.res, n0, count);
+          r.spatial_stride = op.res_spatial_stride;
+          r.c_offset = op.res_c_offset;
+        }
+        st = fupr_conv_fused(&op.conv, &x, op.packed, add ? &r : nullptr, op.epilogue, &y, on);
+      } else if (op.kind == FUPR_OP_MAXPOOL) {
+        st = fupr_maxpool(&x, op.conv.R, op.conv.stride, op.conv.pad, &y, on);
+      } else {
+        st = fupr_global_avgpool(&x, &y, on);
       }
-      st = fupr_conv_fused(&op.conv, &x, op.packed, add ? &r : nullptr, op.epilogue, &y, stream);
-    } else if (op.kind == FUPR_OP_MAXPOOL) {
-      st = fupr_maxpool(&x, op.conv.R, op.conv.stride, op.conv.pad, &y, stream);
-    } else {
-      st = fupr_global_avgpool(&x, &y, stream);
+      if (st != FUPR_OK) return st;
+      if (record && hipEventRecord(events[l + 1], hs) != hipSuccess) return FUPR_ERR_LAUNCH;
     }
-    if (st != FUPR_OK) return st;
-    if (events && hipEventRecord(events[l + 1], hs) != hipSuccess) return FUPR_ERR_LAUNCH;
+    return FUPR_OK;
+  };
+  // Timed runs and small batches stay on the caller's stream; otherwise the
+  // batch is cut into sub-batches that run side by side (images are independent).
+  const int split = events ? 1 : split_count(N);
+  if (split <= 1 || m->schedule != FUPR_SCHEDULE_AUTO || !ensure_side(m))
+    return enqueue(0, N, stream, events != nullptr);
+  std::lock_guard<std::mutex> lock(const_cast<fupr_model*>(m)->side_mutex);
+  if (hipEventRecord(m->fork_event, hs) != hipSuccess) return FUPR_ERR_LAUNCH;
+  for (int k = 1; k < split; ++k)
+    if (hipStreamWaitEvent(m->side_stream[k - 1], m->fork_event, 0) != hipSuccess)
+      return FUPR_ERR_LAUNCH;
+  fupr_status result = FUPR_OK;
+  for (int k = 0; k < split; ++k) {
+    const int n0 = (int)((int64_t)N * k / split), n1 = (int)((int64_t)N * (k + 1) / split);
+    const fupr_status st = enqueue(n0, n1 - n0, k == 0 ? stream : (void*)m->side_stream[k - 1], false);
+    if (st != FUPR_OK && result == FUPR_OK) result = st;
   }
-  return FUPR_OK;
+  // always join, so that the caller's stream (or capture) is whole again
+  for (int k = 1; k < split; ++k) {
+    if (hipEventRecord(m->join_event[k - 1], m->side_stream[k - 1]) != hipSuccess ||
+        hipStreamWaitEvent(hs, m->join_event[k - 1], 0) != hipSuccess)
+      return FUPR_ERR_LAUNCH;
+  }
+  return result;
 }
 
 }  // namespace
@@ -940,6 +1027,7 @@ extern "C" fupr_status fupr_graph_create(const fupr_model* m, const fupr_tensor*
   if (!out) return FUPR_ERR_NULL;
   if (!stream) return FUPR_ERR_ARG;
   if (m && m->resident_ok) (void)upload_resident(m);   // no allocation inside the capture
+  if (m) (void)ensure_side(m);                          // nor stream / event creation
   hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
   fupr_graph* g = new (std::nothrow) fupr_graph;
   if (!g) return FUPR_ERR_ARG;

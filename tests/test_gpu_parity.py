@@ -572,6 +572,50 @@ def test_forward_is_deterministic_and_graph_replays(fx):
             assert torch.equal(first, out2.data)
 
 
+def test_sub_batches_on_forked_streams_give_identical_results(fx):
+    """Large batches run as sub-batches on streams that fork from and join the
+    caller's stream; images are independent, so the result must not change by a
+    bit, eagerly and from a replayed graph."""
+    import os
+    B, network, torch = fx
+    model = synth.make_imagenet_basic_resnet(31, "bf16", (1, 1, 1, 1), 300, widths=(64, 16, 24, 40),
+                                             size=64, classes=9)
+    n = 26
+    x = synth.make_input(31, n, model["in_shape"])
+    m, _ = network.build(network.optimise(model))
+    xd = B.DeviceTensor.from_nchw(x, B.BF16)
+    out, ws = m.alloc(n)
+    old = os.environ.get("FUPR_SPLIT")
+    try:
+        os.environ["FUPR_SPLIT"] = "1"
+        m.fupr_forward(xd, out, ws)
+        torch.cuda.synchronize()
+        whole = out.data.clone()
+        for parts in (2, 3):
+            os.environ["FUPR_SPLIT"] = str(parts)
+            print(f"sub-batches: {parts}", flush=True)
+            out.data.zero_()
+            m.fupr_forward(xd, out, ws)
+            torch.cuda.synchronize()
+            assert torch.equal(whole, out.data)
+            s = torch.cuda.Stream()
+            with torch.cuda.stream(s):
+                out2, ws2 = m.alloc(n)
+                s.synchronize()
+                g = m.fupr_graph_create(xd, out2, ws2, B.C.c_void_p(s.cuda_stream))
+                for _ in range(3):
+                    out2.data.zero_()
+                    s.synchronize()
+                    m.fupr_graph_launch(g, B.C.c_void_p(s.cuda_stream))
+                    s.synchronize()
+                    assert torch.equal(whole, out2.data)
+    finally:
+        if old is None:
+            os.environ.pop("FUPR_SPLIT", None)
+        else:
+            os.environ["FUPR_SPLIT"] = old
+
+
 def test_timed_forward_and_stats(fx):
     B, network, torch = fx
     model = synth.make_cifar_resnet(22, "bf16", 2, 400)
