@@ -53,6 +53,14 @@ constexpr int kMaxPatchLoads = 12;          // 16-byte slots of the patch per th
 constexpr uint32_t kOutside = 0x80000000u;  // beyond every tensor this kernel accepts
 constexpr size_t kPatchLdsLimit = 160 * 1024;
 
+// floor(v / d) for 0 <= v < 2^31 as mulhi(v, mul) >> shift with shift =
+// ceil(log2 d) - 1, mul = ceil(2^(32 + shift) / d) < 2^32 (the error mul * d -
+// 2^(32 + shift) is below d <= 2^(shift + 1), hence exact while v < 2^31);
+// mul = 0 stands for d = 1.
+struct FastDiv {
+  uint32_t mul, shift;
+};
+
 struct PatchParams {
   const uint16_t* x;
   const uint16_t* w;     // [nchunk_pad][Kp][8]
@@ -76,11 +84,13 @@ struct PatchParams {
   int patch_base;        // LDS byte offset of patch buffer 0
   int buf_stride;        // bytes from buffer 0 to buffer 1
   int fgroups, tiles;
-  uint32_t magicQ, magicWh, magicPR, magicHv, magicPv;
+  int tiles_q, tiles_r;  // tiles / grid, tiles % grid
+  FastDiv divQ, divWh, divPR, divHv, divPv, divF;   // by Q, Wh, PR, Hv, Pv, fgroups
 };
 
-__device__ __forceinline__ int div_by(int v, uint32_t magic) {
-  return magic ? (int)__umulhi((uint32_t)v, magic) : v;
+__device__ __forceinline__ int div_by(int v, const FastDiv& d) {
+  const uint32_t q = __umulhi((uint32_t)v, d.mul) >> d.shift;
+  return d.mul ? (int)q : v;
 }
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
@@ -142,8 +152,10 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-  const int t_begin = (int)((int64_t)blockIdx.x * p.tiles / gridDim.x);
-  const int t_end = (int)((int64_t)(blockIdx.x + 1) * p.tiles / gridDim.x);
+  // tiles are dealt in contiguous ranges: tiles_q each, one more for the first tiles_r
+  const int wg = blockIdx.x;
+  const int t_begin = wg * p.tiles_q + min(wg, p.tiles_r);
+  const int t_end = t_begin + p.tiles_q + (wg < p.tiles_r ? 1 : 0);
   const int n_units = (t_end - t_begin) * p.n_stages;
   if (n_units <= 0) return;
 
@@ -151,45 +163,21 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
     // ================================ loading waves ================================
     const int lw = wave - NWC;
     const i32x4 xrsrc = make_rsrc(p.x, p.x_bytes), wrsrc = make_rsrc(p.w, p.w_bytes);
-    // What a slot of the patch holds does not depend on the tile except for the
-    // image row: slot_row = patch row, bit 15 = column inside the image;
-    // slot_off = byte offset in x as if patch row 0 were row 0 of image 0.
     uint32_t slot_off[kMaxPatchLoads], goff[kMaxPatchLoads];
     int slot_row[kMaxPatchLoads];
-#pragma unroll
-    for (int i = 0; i < kMaxPatchLoads; ++i) {
-      slot_off[i] = 0;
-      slot_row[i] = 0;
-      goff[i] = kOutside;
-      if (i < p.n_loads) {
-        const int s = (i * kLoaderWaves + lw) * 64 + lane;
-        const int half = s & 1, t = s >> 1;
-        const int t2 = div_by(t, p.magicWh), colpos = t - t2 * p.Wh;
-        const int plane = div_by(t2, p.magicPR), row = t2 - plane * p.PR;
-        int col = colpos;
-        if (p.stride == 2) {
-          const int odd = colpos >= p.Whh ? 1 : 0;
-          col = 2 * (colpos - odd * p.Whh) + odd;
-        }
-        const int iw = col - 1;
-        const bool ok = s < p.patch_slots && iw >= 0 && iw < p.W;
-        slot_row[i] = row | (ok ? 0x8000 : 0);
-        slot_off[i] = (uint32_t)((row * p.W + iw) * p.xcs + plane * 16 + half * 8) * 2u;
-      }
-    }
     int l_f0 = 0;
     const uint32_t image_row_bytes = (uint32_t)(p.W * p.xcs * 2);
     auto setup_load = [&](int tile) {
-      const int strip = tile / p.fgroups;
+      const int strip = div_by(tile, p.divF);
       l_f0 = (tile - strip * p.fgroups) * NF;
-      const int gv_lo = (strip * BM) / p.Q;
+      const int gv_lo = div_by(strip * BM, p.divQ);
       const int v0 = gv_lo * p.stride;             // first virtual input row of the patch
-      const int n0 = v0 / p.Hv, vrem0 = v0 - n0 * p.Hv;
+      const int n0 = div_by(v0, p.divHv), vrem0 = v0 - n0 * p.Hv;
 #pragma unroll
       for (int i = 0; i < kMaxPatchLoads; ++i) {
         if (i < p.n_loads) {
           const int row = slot_row[i] & 0x7fff;
-          const int dn = div_by(vrem0 + row, p.magicHv);
+          const int dn = div_by(vrem0 + row, p.divHv);
           const int ihm = vrem0 - dn * p.Hv - 1;   // image row = ihm + row
           const int ih = ihm + row, n = n0 + dn;
           const bool ok = (slot_row[i] & 0x8000) && n < p.N && ih >= 0 && ih < p.H;
@@ -217,13 +205,39 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
                       pdst + ((i * kLoaderWaves + lw) * 64) * 16);
     };
 
+    // the first weights are on their way while the patch slots are worked out
     int l_tile = t_begin, l_stage = 0;
-    setup_load(l_tile);
+    l_f0 = (l_tile - div_by(l_tile, p.divF) * p.fgroups) * NF;
     if (p.w_resident) {
       for (int st = 0; st < p.n_stages; ++st) load_weights(st, lds_base + st * kWeightBytes);
     } else {
       load_weights(0, lds_base);
     }
+    // What a slot of the patch holds does not depend on the tile except for the
+    // image row: slot_row = patch row, bit 15 = column inside the image;
+    // slot_off = byte offset in x as if patch row 0 were row 0 of image 0.
+#pragma unroll
+    for (int i = 0; i < kMaxPatchLoads; ++i) {
+      slot_off[i] = 0;
+      slot_row[i] = 0;
+      goff[i] = kOutside;
+      if (i < p.n_loads) {
+        const int s = (i * kLoaderWaves + lw) * 64 + lane;
+        const int half = s & 1, t = s >> 1;
+        const int t2 = div_by(t, p.divWh), colpos = t - t2 * p.Wh;
+        const int plane = div_by(t2, p.divPR), row = t2 - plane * p.PR;
+        int col = colpos;
+        if (p.stride == 2) {
+          const int odd = colpos >= p.Whh ? 1 : 0;
+          col = 2 * (colpos - odd * p.Whh) + odd;
+        }
+        const int iw = col - 1;
+        const bool ok = s < p.patch_slots && iw >= 0 && iw < p.W;
+        slot_row[i] = row | (ok ? 0x8000 : 0);
+        slot_off[i] = (uint32_t)((row * p.W + iw) * p.xcs + plane * 16 + half * 8) * 2u;
+      }
+    }
+    setup_load(l_tile);
     load_patch(0, lds_base + p.patch_base);
     if (++l_stage == p.n_stages) { l_stage = 0; ++l_tile; }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -261,20 +275,20 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
   u32x4 rvw[MT][NP > 0 ? NP : 1];   // shortcut values, fetched during the last stage
   u32x2 rvo[MT];
   auto setup_compute = [&](int tile) {
-    const int strip = tile / p.fgroups;
+    const int strip = div_by(tile, p.divF);
     c_f0 = (tile - strip * p.fgroups) * NF;
     const int m0 = strip * BM;
-    const int gv_lo = m0 / p.Q;
+    const int gv_lo = div_by(m0, p.divQ);
     const int q_lo = m0 - gv_lo * p.Q;
-    const int n_lo = gv_lo / p.Pv, p_lo = gv_lo - n_lo * p.Pv;
+    const int n_lo = div_by(gv_lo, p.divPv), p_lo = gv_lo - n_lo * p.Pv;
     const int last = p.Mv - 1 - m0;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       const int ml = (wm * MT + mt) * 16 + li;
       const int t = q_lo + min(ml, last);
-      const int dg = div_by(t, p.magicQ), qq = t - dg * p.Q;
+      const int dg = div_by(t, p.divQ), qq = t - dg * p.Q;
       rin[mt] = (dg * p.stride * p.Wh + qq) * 32 + (g >> 1) * p.plane_bytes + (g & 1) * 16;
-      const int t2 = p_lo + dg, dn = div_by(t2, p.magicPv);
+      const int t2 = p_lo + dg, dn = div_by(t2, p.divPv);
       const int pp = t2 - dn * p.Pv, n = n_lo + dn;
       const bool ok = ml <= last && pp < p.P && n < p.N;   // pp = P: the row between two images
       yoff[mt] = ok ? (uint32_t)(((n * p.P + pp) * p.Q + qq) * p.ycs) * 2u : kOutside;
@@ -399,7 +413,13 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
   }
 }
 
-uint32_t reciprocal(int d) { return d == 1 ? 0u : 0xffffffffu / (uint32_t)d + 1u; }
+FastDiv fast_div(int d) {
+  if (d <= 1) return FastDiv{0u, 0u};
+  uint32_t shift = 0;
+  while ((1u << (shift + 1)) < (uint32_t)d) ++shift;   // ceil(log2 d) - 1
+  const uint64_t two = uint64_t(1) << (32 + shift);
+  return FastDiv{(uint32_t)((two + (uint64_t)d - 1) / (uint64_t)d), shift};
+}
 
 struct PatchTile {
   int WM, WN, MT, NT;
@@ -479,6 +499,7 @@ bool plan_patch(const Conv16Params& c, int N, const PatchTile& tile, PatchPlan* 
   const int weight_bytes = (36 * NF + NTH - 1) / NTH * NTH * 16;   // one stage, as loaded
   const int patch_bytes = p.n_loads * NTH * 16;
   p.fgroups = (c.Kp + NF - 1) / NF;
+  p.divF = fast_div(p.fgroups);
   // weights of all stages resident when one filter group covers the layer and
   // they fit beside the two patch buffers
   p.w_resident = p.fgroups == 1 &&
@@ -492,15 +513,11 @@ bool plan_patch(const Conv16Params& c, int N, const PatchTile& tile, PatchPlan* 
     p.buf_stride = weight_bytes + patch_bytes;
     out->lds_bytes = 2 * (size_t)p.buf_stride;
   }
-  p.magicQ = reciprocal(c.Q);
-  p.magicWh = reciprocal(p.Wh);
-  p.magicPR = reciprocal(p.PR);
-  p.magicHv = reciprocal(p.Hv);
-  p.magicPv = reciprocal(p.Pv);
-  // range in which the reciprocal multiplications are exact
-  if (p.n_loads * NTH >= 65536 || BM + c.Q >= 65536 || p.Hv + p.PR >= 65536 ||
-      p.Pv + rows_out >= 65536)
-    return false;
+  p.divQ = fast_div(c.Q);
+  p.divWh = fast_div(p.Wh);
+  p.divPR = fast_div(p.PR);
+  p.divHv = fast_div(p.Hv);
+  p.divPv = fast_div(p.Pv);
   if (out->lds_bytes > kPatchLdsLimit) return false;
   const int64_t strips = (Mv + BM - 1) / BM;
   const int64_t tiles = strips * p.fgroups;
@@ -508,6 +525,8 @@ bool plan_patch(const Conv16Params& c, int N, const PatchTile& tile, PatchPlan* 
   p.tiles = (int)tiles;
   const int cus = num_compute_units();
   out->grid = (int)std::min<int64_t>(tiles, cus);
+  p.tiles_q = p.tiles / out->grid;
+  p.tiles_r = p.tiles % out->grid;
   // Estimated clocks.  Measured on gfx950: within a unit the MFMAs and the LDS
   // reads of a computing wave add up rather than overlap (reads issued between
   // MFMAs slow both), a 16-byte-per-lane LDS read costs about 5.4 clocks of the
