@@ -48,6 +48,8 @@ struct PipeParams {
   int relu;
   int plain;             // output pixel m is input pixel m and shortcut pixel m
   int fgroups, tiles;
+  int tiles_q, tiles_r;  // tiles / grid, tiles % grid
+  FastDiv divPQ, divQ, divF;
 };
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
@@ -119,8 +121,9 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv1x1_pipe_ke
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-  const int t_begin = (int)((int64_t)blockIdx.x * p.tiles / gridDim.x);
-  const int t_end = (int)((int64_t)(blockIdx.x + 1) * p.tiles / gridDim.x);
+  const int wg = blockIdx.x;
+  const int t_begin = wg * p.tiles_q + min(wg, p.tiles_r);
+  const int t_end = t_begin + p.tiles_q + (wg < p.tiles_r ? 1 : 0);
   const int n_units = (t_end - t_begin) * p.n_units;
   if (n_units <= 0) return;
 
@@ -132,7 +135,7 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv1x1_pipe_ke
     uint32_t poff[kPixelLoads];    // byte offset in x of the slot's pixel; kOutside: none
     int l_f0 = 0;
     auto setup_load = [&](int tile) {
-      const int strip = tile / p.fgroups;
+      const int strip = div_by(tile, p.divF);
       l_f0 = (tile - strip * p.fgroups) * NF;
       const int m0 = strip * BM;
 #pragma unroll
@@ -144,8 +147,8 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv1x1_pipe_ke
           if (p.plain) {
             off = (uint32_t)m * (uint32_t)(p.xcs * 2);
           } else {
-            const int n = m / p.PQ, rem = m - n * p.PQ;
-            const int pp = rem / p.Q, qq = rem - pp * p.Q;
+            const int n = div_by(m, p.divPQ), rem = m - n * p.PQ;
+            const int pp = div_by(rem, p.divQ), qq = rem - pp * p.Q;
             off = (uint32_t)(((n * p.H + pp * p.stride) * p.W + qq * p.stride) * p.xcs) * 2u;
           }
         }
@@ -216,7 +219,7 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv1x1_pipe_ke
   for (int mt = 0; mt < MT; ++mt)
     rin[mt] = ((wm * MT + mt) * 16 + li) * 32 + (g >> 1) * (BM * 32) + (g & 1) * 16;
   auto setup_compute = [&](int tile) {
-    const int strip = tile / p.fgroups;
+    const int strip = div_by(tile, p.divF);
     c_f0 = (tile - strip * p.fgroups) * NF;
     const int m0 = strip * BM;
 #pragma unroll
@@ -229,8 +232,8 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv1x1_pipe_ke
         if (p.plain) {
           roff[mt] = (uint32_t)m * (uint32_t)(p.rcs * 2);
         } else if (p.res) {
-          const int n = m / p.PQ, rem = m - n * p.PQ;
-          const int pp = rem / p.Q, qq = rem - pp * p.Q;
+          const int n = div_by(m, p.divPQ), rem = m - n * p.PQ;
+          const int pp = div_by(rem, p.divQ), qq = rem - pp * p.Q;
           roff[mt] = (uint32_t)(((n * p.rH + pp * p.rss) * p.rW + qq * p.rss) * p.rcs) * 2u;
         }
       }
@@ -463,6 +466,11 @@ fupr_status launch_conv1x1_pipe(const Conv16Params& c, int N, bool bf16, void* s
   p.plain = c.stride == 1 && (!c.res || (c.rss == 1 && c.rH == c.P && c.rW == c.Q));
   p.fgroups = plan.fgroups;
   p.tiles = (int)plan.tiles;
+  p.tiles_q = p.tiles / plan.grid;
+  p.tiles_r = p.tiles % plan.grid;
+  p.divPQ = fast_div(c.PQ);
+  p.divQ = fast_div(c.Q);
+  p.divF = fast_div(plan.fgroups);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   return bf16 ? dispatch_pipe<true>(p, plan, st) : dispatch_pipe<false>(p, plan, st);
 }

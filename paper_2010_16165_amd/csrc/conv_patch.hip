@@ -53,14 +53,6 @@ constexpr int kMaxPatchLoads = 12;          // 16-byte slots of the patch per th
 constexpr uint32_t kOutside = 0x80000000u;  // beyond every tensor this kernel accepts
 constexpr size_t kPatchLdsLimit = 160 * 1024;
 
-// floor(v / d) for 0 <= v < 2^31 as mulhi(v, mul) >> shift with shift =
-// ceil(log2 d) - 1, mul = ceil(2^(32 + shift) / d) < 2^32 (the error mul * d -
-// 2^(32 + shift) is below d <= 2^(shift + 1), hence exact while v < 2^31);
-// mul = 0 stands for d = 1.
-struct FastDiv {
-  uint32_t mul, shift;
-};
-
 struct PatchParams {
   const uint16_t* x;
   const uint16_t* w;     // [nchunk_pad][Kp][8]
@@ -87,11 +79,6 @@ struct PatchParams {
   int tiles_q, tiles_r;  // tiles / grid, tiles % grid
   FastDiv divQ, divWh, divPR, divHv, divPv, divF;   // by Q, Wh, PR, Hv, Pv, fgroups
 };
-
-__device__ __forceinline__ int div_by(int v, const FastDiv& d) {
-  const uint32_t q = __umulhi((uint32_t)v, d.mul) >> d.shift;
-  return d.mul ? (int)q : v;
-}
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
@@ -411,14 +398,6 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
       ++c_stage;
     }
   }
-}
-
-FastDiv fast_div(int d) {
-  if (d <= 1) return FastDiv{0u, 0u};
-  uint32_t shift = 0;
-  while ((1u << (shift + 1)) < (uint32_t)d) ++shift;   // ceil(log2 d) - 1
-  const uint64_t two = uint64_t(1) << (32 + shift);
-  return FastDiv{(uint32_t)((two + (uint64_t)d - 1) / (uint64_t)d), shift};
 }
 
 struct PatchTile {

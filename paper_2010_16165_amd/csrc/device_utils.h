@@ -54,4 +54,25 @@ __device__ __forceinline__ f32x4 mfma_16x16x32(const uint4& a, const uint4& b, f
   }
 }
 
+// floor(v / d) for 0 <= v < 2^31 as mulhi(v, mul) >> shift with shift =
+// ceil(log2 d) - 1, mul = ceil(2^(32 + shift) / d) < 2^32 (the error mul * d -
+// 2^(32 + shift) is below d <= 2^(shift + 1), hence exact while v < 2^31);
+// mul = 0 stands for d = 1.
+struct FastDiv {
+  uint32_t mul, shift;
+};
+
+__device__ __forceinline__ int div_by(int v, const FastDiv& d) {
+  const uint32_t q = __umulhi((uint32_t)v, d.mul) >> d.shift;
+  return d.mul ? (int)q : v;
+}
+
+inline FastDiv fast_div(int d) {
+  if (d <= 1) return FastDiv{0u, 0u};
+  uint32_t shift = 0;
+  while ((1u << (shift + 1)) < (uint32_t)d) ++shift;   // ceil(log2 d) - 1
+  const uint64_t two = uint64_t(1) << (32 + shift);
+  return FastDiv{(uint32_t)((two + (uint64_t)d - 1) / (uint64_t)d), shift};
+}
+
 }  // namespace fupr
