@@ -50,12 +50,8 @@ struct StemParams {
   int PH, PW;            // input patch: 2 th + 5 rows, 2 tw + 5 columns rounded up to even
   int n_ctiles;          // 16-pixel tiles of th * tw
   int patch_off, stem_off;   // LDS byte offsets (the filter staging area starts at 0)
-  uint32_t magic_tw, magic_PW, magic_TQ;
+  FastDiv div_tw, div_PW, div_TQ, div_image, div_tq;   // by tw, PW, TQ, tiles per image, tiles_q
 };
-
-__device__ __forceinline__ int div_by(int v, uint32_t magic) {
-  return magic ? (int)__umulhi((uint32_t)v, magic) : v;
-}
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef short short8_t __attribute__((ext_vector_type(8)));
@@ -105,16 +101,21 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemParams p) {
 
   // the input patch of a tile: [PH][PW][4 channels], fetched one tile ahead
   u32x2 pre[kMaxStemPatchLoads];
+  int slot_rc[kMaxStemPatchLoads];   // patch row << 16 | patch column of this thread's pixels
+#pragma unroll
+  for (int i = 0; i < kMaxStemPatchLoads; ++i) {
+    const int e = tid + i * 256;
+    const int pr = div_by(e, p.div_PW), pc = e - pr * p.PW;
+    slot_rc[i] = e < n_patch ? (pr << 16 | pc) : -1;
+  }
   auto fetch = [&](int tile) {
-    const int n = tile / per_image, rem = tile - n * per_image;
-    const int tp = rem / p.tiles_q, tq = rem - tp * p.tiles_q;
+    const int n = div_by(tile, p.div_image), rem = tile - n * per_image;
+    const int tp = div_by(rem, p.div_tq), tq = rem - tp * p.tiles_q;
     const int h0 = 4 * tp * p.TP - 5, w0 = 4 * tq * p.TQ - 5;   // first input pixel
 #pragma unroll
     for (int i = 0; i < kMaxStemPatchLoads; ++i) {
-      const int e = tid + i * 256;
-      const int pr = div_by(e, p.magic_PW), pc = e - pr * p.PW;
-      const int ih = h0 + pr, iw = w0 + pc;
-      const bool ok = e < n_patch && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+      const int ih = h0 + (slot_rc[i] >> 16), iw = w0 + (slot_rc[i] & 0xffff);
+      const bool ok = slot_rc[i] >= 0 && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
       const uint32_t off = ok ? (uint32_t)(((n * p.H + ih) * p.W + iw) * p.xcs) * 2u : kOutside;
       pre[i] = __builtin_amdgcn_raw_buffer_load_b64(xrsrc, off, 0, 0);
     }
@@ -123,14 +124,14 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemParams p) {
   int tile = blockIdx.x;
   if (tile < p.total_tiles) fetch(tile);
   for (; tile < p.total_tiles; tile += gridDim.x) {
-    const int n = tile / per_image, rem = tile - n * per_image;
-    const int tp = rem / p.tiles_q, tq = rem - tp * p.tiles_q;
+    const int n = div_by(tile, p.div_image), rem = tile - n * per_image;
+    const int tp = div_by(rem, p.div_tq), tq = rem - tp * p.tiles_q;
     const int p0 = tp * p.TP, q0 = tq * p.TQ;      // first pool output
     const int a0 = 2 * p0 - 1, b0 = 2 * q0 - 1;    // first convolution output
 #pragma unroll
     for (int i = 0; i < kMaxStemPatchLoads; ++i) {
       const int e = tid + i * 256;
-      if (e < n_patch) *reinterpret_cast<u32x2*>(patch + e * 8) = pre[i];
+      if (slot_rc[i] >= 0) *reinterpret_cast<u32x2*>(patch + e * 8) = pre[i];
     }
     __syncthreads();   // patch complete; the previous tile's maxima have been taken
     if (tile + (int)gridDim.x < p.total_tiles) fetch(tile + gridDim.x);
@@ -139,7 +140,7 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemParams p) {
     for (int ct = wave; ct < p.n_ctiles; ct += 4) {
       const int cp = ct * 16 + li;
       const int cpc = min(cp, n_cpix - 1);
-      const int sr = div_by(cpc, p.magic_tw), sc = cpc - sr * p.tw;
+      const int sr = div_by(cpc, p.div_tw), sc = cpc - sr * p.tw;
       const char* bp = patch + (2 * sr * p.PW + 2 * sc) * 8 + g * 16;
       uint4 b[7];
 #pragma unroll
@@ -169,7 +170,7 @@ __global__ __launch_bounds__(256) void stem_pool_kernel(const StemParams p) {
     // non-negative values of either 16-bit format order like their bit patterns
     for (int e = tid; e < p.TP * p.TQ * 8; e += 256) {
       const int c8 = e & 7, pix = e >> 3;
-      const int pp = div_by(pix, p.magic_TQ), qq = pix - pp * p.TQ;
+      const int pp = div_by(pix, p.div_TQ), qq = pix - pp * p.TQ;
       const int gp = p0 + pp, gq = q0 + qq;
       if (gp >= p.P || gq >= p.Q || c8 >= ychunks) continue;
       short8_t m = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -201,8 +202,6 @@ int stem_compute_units() {
   return cus;
 }
 
-uint32_t reciprocal(int d) { return d == 1 ? 0u : 0xffffffffu / (uint32_t)d + 1u; }
-
 bool plan_stem(const fupr_conv_shape& s, fupr_dtype dt, int N, int H, int W, int xcs, int ycs,
                int pool_k, int pool_stride, int pool_pad, StemParams* out, size_t* lds_bytes,
                int64_t* grid) {
@@ -233,9 +232,11 @@ bool plan_stem(const fupr_conv_shape& s, fupr_dtype dt, int N, int H, int W, int
   p.patch_off = round_up(std::max(stage_bytes, stem_bytes), 16);
   *lds_bytes = (size_t)p.patch_off + (size_t)p.PH * p.PW * 8;
   if (*lds_bytes > 64 * 1024) return false;
-  p.magic_tw = reciprocal(p.tw);
-  p.magic_PW = reciprocal(p.PW);
-  p.magic_TQ = reciprocal(p.TQ);
+  p.div_tw = fast_div(p.tw);
+  p.div_PW = fast_div(p.PW);
+  p.div_TQ = fast_div(p.TQ);
+  p.div_image = fast_div(p.tiles_p * p.tiles_q);
+  p.div_tq = fast_div(p.tiles_q);
   if (p.PH * p.PW > kMaxStemPatchLoads * 256 || p.th * p.tw + 16 >= 65536) return false;
   if ((int64_t)N * H * W * xcs * 2 >= (int64_t)kOutside) return false;
   const int64_t total = (int64_t)N * p.tiles_p * p.tiles_q;
