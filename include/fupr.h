@@ -18,6 +18,8 @@
  *   fupr_conv_fused      convolution operator k x c x r x s (Sec. III, Sec. IV-B-1)
  *                        with bias, element-wise addition and ReLU in its epilogue
  *   fupr_maxpool, fupr_global_avgpool   the "Others" of Table II / Table VI
+ *   fupr_conv_conv1x1_fused             two consecutive 1 x 1 convolutions (a bottleneck block's last,
+ *                        the next block's first), the second from the first one's registers
  *   fupr_conv_maxpool_fused             Table II's ImageNet stem (7 x 7 convolution, stride 2, then
  *                        3 x 3 max pool, stride 2) in one kernel
  *   fupr_model_*, fupr_forward          a whole network (Table II) on one stream
@@ -261,6 +263,25 @@ fupr_status fupr_global_avgpool(const fupr_tensor* x, const fupr_tensor* y, void
 fupr_status fupr_conv_maxpool_fused(const fupr_conv_shape* shape, const fupr_tensor* x,
                                     const void* packed, int32_t pool_k, int32_t pool_stride,
                                     int32_t pool_pad, const fupr_tensor* y, void* stream);
+
+/*
+ * Two 1 x 1 convolutions in one kernel: y = act1(conv1(x) + bias1 (+ res)) as
+ * fupr_conv_fused computes it, and h = act2(conv2(y) + bias2) computed from the
+ * rounded y while it is still in registers, so that the second convolution never
+ * reads y from memory (a bottleneck block's last convolution and the next
+ * block's first one, Table II; operator fusion in the sense of Sec. IV-B applied
+ * across a block boundary).  Both y and h are written.  shape1, shape2: 1 x 1,
+ * stride 1, pad 0, shape2.C = shape1.K <= 256, shape2.K <= 64, 16-bit types;
+ * y->c_stride = shape1.K rounded up to 8.  Arguments as in fupr_conv_fused; the
+ * second convolution has no shortcut.  h differs from fupr_conv_fused applied to
+ * y only by the order of the fp32 summation inside a 32-channel step.
+ * Errors: as fupr_conv_fused; LIMIT when the pair is not of the shape above.
+ */
+fupr_status fupr_conv_conv1x1_fused(const fupr_conv_shape* shape1, const fupr_tensor* x,
+                                    const void* packed1, const fupr_residual* res, uint32_t flags1,
+                                    const fupr_tensor* y, const fupr_conv_shape* shape2,
+                                    const void* packed2, uint32_t flags2, const fupr_tensor* h,
+                                    void* stream);
 
 /* ----------------------------------------------------------------- model -- */
 

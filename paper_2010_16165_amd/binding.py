@@ -106,6 +106,8 @@ SIGNATURES = {
                                     C.c_void_p]),
     "fupr_maxpool": (C.c_int32, [_T, C.c_int32, C.c_int32, C.c_int32, _T, C.c_void_p]),
     "fupr_global_avgpool": (C.c_int32, [_T, _T, C.c_void_p]),
+    "fupr_conv_conv1x1_fused": (C.c_int32, [_SH, _T, C.c_void_p, C.POINTER(Residual), C.c_uint32, _T,
+                                            _SH, C.c_void_p, C.c_uint32, _T, C.c_void_p]),
     "fupr_conv_maxpool_fused": (C.c_int32, [C.POINTER(ConvShape), _T, C.c_void_p, C.c_int32,
                                             C.c_int32, C.c_int32, _T, C.c_void_p]),
     "fupr_model_create": (C.c_int32, [C.POINTER(GraphDesc), C.POINTER(C.c_void_p)]),
@@ -358,6 +360,19 @@ def fupr_maxpool(x, k, stride, pad, y, stream=None):
     st = _lib.fupr_maxpool(C.byref(xs), int(k), int(stride), int(pad), C.byref(ys),
                            stream if stream is not None else current_stream())
     _check(st, "fupr_maxpool")
+
+
+def fupr_conv_conv1x1_fused(shape1, x, packed1, res, flags1, y, shape2, packed2, flags2, h, stream=None):
+    """res: None or (DeviceTensor, spatial_stride, c_offset), as in fupr_conv_fused."""
+    xs, ys, hs = x.struct, y.struct, h.struct
+    r = None
+    if res is not None:
+        r = Residual(res[0].struct, int(res[1]), int(res[2]))
+    st = _lib.fupr_conv_conv1x1_fused(C.byref(shape1), C.byref(xs), C.c_void_p(packed1.data_ptr()),
+                                      None if r is None else C.byref(r), int(flags1), C.byref(ys),
+                                      C.byref(shape2), C.c_void_p(packed2.data_ptr()), int(flags2),
+                                      C.byref(hs), stream if stream is not None else current_stream())
+    _check(st, "fupr_conv_conv1x1_fused")
 
 
 def fupr_conv_maxpool_fused(shape, x, packed, pool_k, pool_stride, pool_pad, y, stream=None):

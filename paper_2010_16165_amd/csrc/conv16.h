@@ -39,6 +39,12 @@ bool conv1x1_stream_applies(const Conv16Params& geometry);
 const char* conv1x1_stream_name(const Conv16Params& geometry);
 fupr_status launch_conv1x1_stream(const Conv16Params& p, int N, bool bf16, void* stream);
 
+// conv1x1.hip: a 1 x 1 convolution followed by another 1 x 1 convolution that reads
+// all of its output channels, in one launch.
+bool conv1x1_fused_pair_applies(const Conv16Params& first, const Conv16Params& second);
+fupr_status launch_conv1x1_fused_pair(const Conv16Params& first, const Conv16Params& second, int N,
+                                      bool bf16, void* stream);
+
 // conv1x1_pipe.hip: 1 x 1 convolutions with 128 channels or more whose filters do
 // not fit in LDS, as a pipelined GEMM.
 bool conv1x1_pipe_applies(const Conv16Params& geometry);

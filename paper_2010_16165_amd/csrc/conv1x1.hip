@@ -33,6 +33,7 @@ namespace {
 
 constexpr uint32_t kOutside = 0x80000000u;
 constexpr int kStreamLdsLimit = 72 * 1024;   // two workgroups per compute unit
+constexpr int kStreamFusedLdsLimit = 80 * 1024;   // likewise, with a second layer's filters
 
 struct StreamParams {
   const uint16_t* x;
@@ -48,6 +49,13 @@ struct StreamParams {
   int rH, rW, rcs, rss, roff;
   int relu;
   int plain;             // pixel m of the output is pixel m of the input and of the shortcut
+  // a second 1 x 1 convolution applied to the output tile while it is in registers
+  const uint16_t* w2;    // [nchunk_pad2][Kp2][8]; its channels are this layer's filters
+  const float* bias2;
+  uint16_t* h;           // its output, M pixels x hcs
+  uint32_t w2_bytes, h_bytes;
+  int Kp2, cpt2, hcs, relu2;
+  int w_lds_bytes;       // LDS bytes of the first convolution's filters
   int n_tiles;           // 16-pixel tiles
 };
 
@@ -64,13 +72,22 @@ __device__ __forceinline__ uint32_t clamp_below2(uint32_t v, uint32_t floor2) {
 
 // NT filter tiles of 16 per workgroup (every wave computes all of them for its
 // pixels); at most KMAX steps of 32 channels.
-template <bool BF, int NT, int KMAX>
+// NT2 > 0: the layer is followed by another 1 x 1 convolution with NT2 filter
+// tiles that reads all of this layer's output channels (one filter group): a
+// wave's finished 16-pixel tile, rounded as it is stored, is at once the pixel
+// operand of the second convolution, whose output is stored as well; the
+// second layer never reads the first one's output from memory.
+template <bool BF, int NT, int KMAX, int NT2>
 __global__ __launch_bounds__(256) void conv1x1_stream_kernel(const StreamParams p) {
   constexpr int NF = NT * 16;
+  constexpr int NF2 = NT2 * 16;
   extern __shared__ uint4 lds4[];
   char* lds = reinterpret_cast<char*>(lds4);
   float* bias_lds = reinterpret_cast<float*>(lds);                 // [NF]
   char* wts = lds + NF * 4;                                        // [ksteps * 4][NF][16 bytes]
+  // second convolution: [NF2] bias, then [NT / 2 steps * 4][NF2][16 bytes]
+  float* bias2_lds = reinterpret_cast<float*>(wts + p.w_lds_bytes);
+  char* wts2 = reinterpret_cast<char*>(bias2_lds) + NF2 * 4;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -85,6 +102,8 @@ __global__ __launch_bounds__(256) void conv1x1_stream_kernel(const StreamParams 
       __builtin_amdgcn_make_buffer_rsrc(p.y, 0, p.y_bytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t rrsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.res), 0, p.res_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t hrsrc =
+      __builtin_amdgcn_make_buffer_rsrc(p.h, 0, p.h_bytes, 0x00020000);
 
   // ---- filters and bias of this group -> LDS -----------------------------------------
   // straight into LDS, all loads in flight at once; slots past the group's
@@ -113,6 +132,30 @@ __global__ __launch_bounds__(256) void conv1x1_stream_kernel(const StreamParams 
     }
   }
   for (int e = tid; e < NF; e += 256) bias_lds[e] = f0 + e < p.Kp ? p.bias[f0 + e] : 0.f;
+  if constexpr (NT2 > 0) {
+    const uint64_t wa = reinterpret_cast<uint64_t>(p.w2);
+    i32x4 wr;
+    wr[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)wa);
+    wr[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)(wa >> 32));
+    wr[2] = __builtin_amdgcn_readfirstlane((int)p.w2_bytes);
+    wr[3] = 0x00020000;
+    const uint32_t wts2_lds = (uint32_t)(uintptr_t)(LdsPtr)wts2;
+    constexpr int n_slots2 = (NT / 2) * 4 * NF2;
+    for (int base = wave * 64; base < n_slots2; base += 256) {
+      const int e = base + lane;
+      const int chunk = e / NF2, f = e - chunk * NF2;
+      const bool ok = e < n_slots2 && chunk < p.cpt2 && f < p.Kp2;
+      const uint32_t off = ok ? (uint32_t)(chunk * p.Kp2 + f) * 16u : kOutside;
+      asm volatile(
+          "s_mov_b32 m0, %0\n\t"
+          "s_nop 0\n\t"
+          "buffer_load_dwordx4 %1, %2, 0 offen lds"
+          :
+          : "s"(wts2_lds + base * 16), "v"(off), "s"(wr)
+          : "memory", "m0");
+    }
+    for (int e = tid; e < NF2; e += 256) bias2_lds[e] = e < p.Kp2 ? p.bias2[e] : 0.f;
+  }
 
   // ---- this wave's tiles -------------------------------------------------------------
   const int n_waves = gridDim.x * 4;
@@ -122,13 +165,15 @@ __global__ __launch_bounds__(256) void conv1x1_stream_kernel(const StreamParams 
   constexpr int NP = NT / 2;
   u32x4 rvn[NP] = {};
   const int k_pair = (g & 1) * 16 + (g >> 1) * 8;   // channel of this lane's 16 bytes in a tile pair
-  uint32_t yoff_n = kOutside;
+  uint32_t yoff_n = kOutside, hoff_n = kOutside;
   auto fetch = [&](int t) {
     const int m = t * 16 + li;
     uint32_t xo = kOutside, ro = kOutside;
     yoff_n = kOutside;
+    hoff_n = kOutside;
     if (m < p.M) {
       yoff_n = (uint32_t)m * (uint32_t)(p.ycs * 2);
+      hoff_n = (uint32_t)m * (uint32_t)(p.hcs * 2);
       if (p.plain) {
         xo = (uint32_t)m * (uint32_t)(p.xcs * 2);
         ro = (uint32_t)m * (uint32_t)(p.rcs * 2);
@@ -168,9 +213,10 @@ __global__ __launch_bounds__(256) void conv1x1_stream_kernel(const StreamParams 
     for (int k = 0; k < KMAX; ++k) b[k] = bn[k];
 #pragma unroll
     for (int pr = 0; pr < NP; ++pr) rv[pr] = rvn[pr];
-    const uint32_t yoff = yoff_n;
+    const uint32_t yoff = yoff_n, hoff = hoff_n;
     if (tile + n_waves < p.n_tiles) fetch(tile + n_waves);
 
+    uint4 yb[NT2 > 0 ? NP : 1];   // the finished tile as pixel fragments of the second convolution
     f32x4 acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = *reinterpret_cast<const f32x4*>(bias_lds + t * 16 + g * 4);
@@ -217,6 +263,42 @@ __global__ __launch_bounds__(256) void conv1x1_stream_kernel(const StreamParams 
       const int k0 = f0 + pr * 32 + k_pair;
       const uint32_t off = k0 < p.ycs ? yoff + (uint32_t)k0 * 2u : kOutside;
       __builtin_amdgcn_raw_buffer_store_b128(o4, yrsrc, off, 0, 0);
+      if constexpr (NT2 > 0) yb[pr] = __builtin_bit_cast(uint4, o4);
+    }
+    if constexpr (NT2 > 0) {
+      // Pair pr of the output is step pr of the second reduction: lane (pixel, g)
+      // holds channels pr * 32 + (g & 1) * 16 + (g >> 1) * 8 .. + 7, i.e. chunk
+      // (g & 1) * 2 + (g >> 1) of the step, and reads the matching filter chunk.
+      const char* a2_lane = wts2 + ((((g & 1) * 2 + (g >> 1)) * NF2) + li) * 16;
+      f32x4 acc2[NT2];
+#pragma unroll
+      for (int t = 0; t < NT2; ++t)
+        acc2[t] = *reinterpret_cast<const f32x4*>(bias2_lds + t * 16 + g * 4);
+#pragma unroll
+      for (int s2 = 0; s2 < NP; ++s2) {
+        if (s2 * 4 < p.cpt2) {
+#pragma unroll
+          for (int t = 0; t < NT2; ++t) {
+            const uint4 a2 = *reinterpret_cast<const uint4*>(a2_lane + (s2 * 4 * NF2 + t * 16) * 16);
+            acc2[t] = mfma_16x16x32<BF>(a2, yb[s2], acc2[t]);
+          }
+        }
+      }
+      const uint32_t floor2b = p.relu2 ? 0u : 0x80008000u;
+#pragma unroll
+      for (int pr = 0; pr < NT2 / 2; ++pr) {
+        u32x2 oa, ob;
+        oa[0] = clamp_below2(pack2<BF>(acc2[2 * pr][0], acc2[2 * pr][1]), floor2b);
+        oa[1] = clamp_below2(pack2<BF>(acc2[2 * pr][2], acc2[2 * pr][3]), floor2b);
+        ob[0] = clamp_below2(pack2<BF>(acc2[2 * pr + 1][0], acc2[2 * pr + 1][1]), floor2b);
+        ob[1] = clamp_below2(pack2<BF>(acc2[2 * pr + 1][2], acc2[2 * pr + 1][3]), floor2b);
+        const auto w0 = __builtin_amdgcn_permlane16_swap(oa[0], ob[0], false, false);
+        const auto w1 = __builtin_amdgcn_permlane16_swap(oa[1], ob[1], false, false);
+        const u32x4 o4 = {w0[0], w1[0], w0[1], w1[1]};
+        const int k0 = pr * 32 + k_pair;
+        const uint32_t off = k0 < p.hcs ? hoff + (uint32_t)k0 * 2u : kOutside;
+        __builtin_amdgcn_raw_buffer_store_b128(o4, hrsrc, off, 0, 0);
+      }
     }
   }
 }
@@ -274,17 +356,17 @@ int pick_stream(const Conv16Params& c) {
   return best;
 }
 
-template <bool BF, int NT, int KMAX>
+template <bool BF, int NT, int KMAX, int NT2 = 0>
 fupr_status launch_stream(const StreamParams& p, dim3 grid, size_t lds, hipStream_t st) {
   static std::once_flag once;
   static hipError_t status = hipSuccess;
   std::call_once(once, [] {
     status = hipFuncSetAttribute(
-        reinterpret_cast<const void*>(&conv1x1_stream_kernel<BF, NT, KMAX>),
-        hipFuncAttributeMaxDynamicSharedMemorySize, kStreamLdsLimit);
+        reinterpret_cast<const void*>(&conv1x1_stream_kernel<BF, NT, KMAX, NT2>),
+        hipFuncAttributeMaxDynamicSharedMemorySize, kStreamFusedLdsLimit);
   });
   if (status != hipSuccess) return FUPR_ERR_LAUNCH;
-  hipLaunchKernelGGL((conv1x1_stream_kernel<BF, NT, KMAX>), grid, dim3(256), lds, st, p);
+  hipLaunchKernelGGL((conv1x1_stream_kernel<BF, NT, KMAX, NT2>), grid, dim3(256), lds, st, p);
   return launch_status("conv1x1_stream_kernel");
 }
 
@@ -310,16 +392,15 @@ const char* conv1x1_stream_name(const Conv16Params& c) {
   return t < 0 ? "conv1x1s" : kStreamTiles[t].name;
 }
 
-fupr_status launch_conv1x1_stream(const Conv16Params& c, int N, bool bf16, void* stream) {
-  const int t = pick_stream(c);
-  if (t < 0) return FUPR_ERR_LIMIT;
-  const StreamTile& tile = kStreamTiles[t];
+namespace {
+
+// Everything but the second convolution's fields; false if a tensor is too large.
+bool fill_stream_params(const Conv16Params& c, int N, StreamParams* out) {
   StreamParams p{};
   p.x = c.x; p.w = c.w; p.bias = c.bias; p.res = c.res; p.y = c.y;
   const uint64_t y_bytes = (uint64_t)c.M * c.ycs * 2;
   const uint64_t res_bytes = c.res ? (uint64_t)N * c.rH * c.rW * c.rcs * 2 : 0;
-  if ((uint64_t)c.x_bytes >= kOutside || y_bytes >= kOutside || res_bytes >= kOutside)
-    return FUPR_ERR_LIMIT;
+  if ((uint64_t)c.x_bytes >= kOutside || y_bytes >= kOutside || res_bytes >= kOutside) return false;
   p.x_bytes = c.x_bytes; p.w_bytes = c.w_bytes;
   p.y_bytes = (uint32_t)y_bytes; p.res_bytes = (uint32_t)res_bytes;
   p.H = c.H; p.W = c.W; p.xcs = c.xcs;
@@ -330,6 +411,36 @@ fupr_status launch_conv1x1_stream(const Conv16Params& c, int N, bool bf16, void*
   p.relu = c.relu;
   p.plain = c.stride == 1 && (!c.res || (c.rss == 1 && c.rH == c.P && c.rW == c.Q));
   p.n_tiles = (c.M + 15) / 16;
+  *out = p;
+  return true;
+}
+
+// Which 16-tile variant (2 or 4 steps) and how many second-layer filter tiles a
+// fused pair needs; false if the pair is not for the fused kernel.
+bool plan_fused(const Conv16Params& c1, const Conv16Params& c2, int* kmax, int* nt2, size_t* lds) {
+  if (const char* e = std::getenv("FUPR_CONV1X1_FUSE"))
+    if (e[0] == '0') return false;
+  const int t = pick_stream(c1);
+  if (t < 0 || kStreamTiles[t].NT != 16 || c1.FT > 16 || c1.stride != 1) return false;
+  if (c2.S != 1 || c2.nchunk != c2.cpt || c2.pad != 0 || c2.stride != 1 || c2.res) return false;
+  if (c2.cpt * 8 != c1.ycs || c2.cpt > 32 || c2.FT > 4) return false;   // reads all of y's channels
+  if (c2.H != c1.P || c2.W != c1.Q) return false;
+  *kmax = kStreamTiles[t].KMAX;
+  *nt2 = c2.FT <= 2 ? 2 : 4;
+  const int ksteps = (c1.cpt + 3) / 4;
+  *lds = stream_lds_bytes(kStreamTiles[t], ksteps) + (size_t)*nt2 * 16 * 4 +
+         (size_t)8 * 4 * *nt2 * 16 * 16;
+  return *lds <= (size_t)kStreamFusedLdsLimit;
+}
+
+}  // namespace
+
+fupr_status launch_conv1x1_stream(const Conv16Params& c, int N, bool bf16, void* stream) {
+  const int t = pick_stream(c);
+  if (t < 0) return FUPR_ERR_LIMIT;
+  const StreamTile& tile = kStreamTiles[t];
+  StreamParams p;
+  if (!fill_stream_params(c, N, &p)) return FUPR_ERR_LIMIT;
   const int groups = (c.FT + tile.NT - 1) / tile.NT;
   // persistent workgroups, two per compute unit over all filter groups
   const int per_group = std::max(1, 2 * stream_compute_units() / groups);
@@ -339,6 +450,41 @@ fupr_status launch_conv1x1_stream(const Conv16Params& c, int N, bool bf16, void*
   const size_t lds = stream_lds_bytes(tile, p.ksteps);
   return bf16 ? dispatch_stream<true>(t, p, grid, lds, st)
               : dispatch_stream<false>(t, p, grid, lds, st);
+}
+
+bool conv1x1_fused_pair_applies(const Conv16Params& c1, const Conv16Params& c2) {
+  int kmax, nt2;
+  size_t lds;
+  return plan_fused(c1, c2, &kmax, &nt2, &lds);
+}
+
+fupr_status launch_conv1x1_fused_pair(const Conv16Params& c1, const Conv16Params& c2, int N,
+                                      bool bf16, void* stream) {
+  int kmax, nt2;
+  size_t lds;
+  if (!plan_fused(c1, c2, &kmax, &nt2, &lds)) return FUPR_ERR_LIMIT;
+  StreamParams p;
+  if (!fill_stream_params(c1, N, &p)) return FUPR_ERR_LIMIT;
+  const uint64_t h_bytes = (uint64_t)c2.M * c2.ycs * 2;
+  if (h_bytes >= kOutside) return FUPR_ERR_LIMIT;
+  p.w2 = c2.w; p.bias2 = c2.bias; p.h = c2.y;
+  p.w2_bytes = c2.w_bytes; p.h_bytes = (uint32_t)h_bytes;
+  p.Kp2 = c2.Kp; p.cpt2 = c2.cpt; p.hcs = c2.ycs; p.relu2 = c2.relu;
+  p.w_lds_bytes = (int)round_up_sz((size_t)p.ksteps * 4 * 16 * 16 * 16, 1024);
+  const int gx = std::min((p.n_tiles + 3) / 4, 2 * stream_compute_units());
+  const dim3 grid((unsigned)gx, 1u);
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const int key = (bf16 ? 100 : 0) + kmax * 10 + nt2;
+  switch (key) {
+    case 122: return launch_stream<true, 16, 2, 2>(p, grid, lds, st);
+    case 124: return launch_stream<true, 16, 2, 4>(p, grid, lds, st);
+    case 142: return launch_stream<true, 16, 4, 2>(p, grid, lds, st);
+    case 144: return launch_stream<true, 16, 4, 4>(p, grid, lds, st);
+    case 22: return launch_stream<false, 16, 2, 2>(p, grid, lds, st);
+    case 24: return launch_stream<false, 16, 2, 4>(p, grid, lds, st);
+    case 42: return launch_stream<false, 16, 4, 2>(p, grid, lds, st);
+    default: return launch_stream<false, 16, 4, 4>(p, grid, lds, st);
+  }
 }
 
 }  // namespace fupr

@@ -244,6 +244,29 @@ Conv16Params geometry16(const fupr_conv_shape& s, fupr_dtype dt, int N, int H, i
   return p;
 }
 
+// A 16-bit convolution's arguments as the kernels take them.
+Conv16Params params16(const ConvArgs& a) {
+  fupr_conv_shape s{a.K, a.C, a.R, a.S, a.stride, a.pad};
+  const PackedLayout L = packed_layout(s, a.dt);
+  const char* blob = reinterpret_cast<const char*>(a.packed);
+  const int64_t M = (int64_t)a.N * a.P * a.Q;
+  Conv16Params p{};
+  p.x = (const uint16_t*)a.x;
+  p.w = (const uint16_t*)(blob + L.weight_offset);
+  p.bias = (const float*)blob;
+  p.res = (const uint16_t*)a.res;
+  p.y = (uint16_t*)a.y;
+  p.H = a.H; p.W = a.W; p.xcs = a.xcs;
+  p.P = a.P; p.Q = a.Q; p.PQ = a.P * a.Q; p.M = (int)M; p.ycs = a.ycs;
+  p.S = a.S; p.stride = a.stride; p.pad = a.pad;
+  p.Kp = L.Kp; p.FT = L.Kp / 16; p.cpt = L.Cp / 8; p.nchunk = L.nchunk; p.nsteps = L.nchunk_pad / 4;
+  p.rH = a.rH; p.rW = a.rW; p.rcs = a.rcs; p.rss = a.rss; p.roff = a.roff;
+  p.relu = a.relu;
+  p.x_bytes = (uint32_t)((int64_t)a.N * a.H * a.W * a.xcs * 2);
+  p.w_bytes = (uint32_t)((size_t)L.nchunk_pad * L.Kp * 16);
+  return p;
+}
+
 // Between the two 1 x 1 kernels (measured per layer on the ResNet-50 workloads):
 // the pipelined GEMM wins from 512 input channels on and on the small images of
 // the last stages; the streaming kernel wins where pixels are many and filters few.
@@ -286,20 +309,7 @@ fupr_status launch_conv(const ConvArgs& a, void* stream) {
     hipLaunchKernelGGL(conv32_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, p);
     return launch_status(__func__);
   }
-  Conv16Params p;
-  p.x = (const uint16_t*)a.x;
-  p.w = (const uint16_t*)(blob + L.weight_offset);
-  p.bias = (const float*)blob;
-  p.res = (const uint16_t*)a.res;
-  p.y = (uint16_t*)a.y;
-  p.H = a.H; p.W = a.W; p.xcs = a.xcs;
-  p.P = a.P; p.Q = a.Q; p.PQ = a.P * a.Q; p.M = (int)M; p.ycs = a.ycs;
-  p.S = a.S; p.stride = a.stride; p.pad = a.pad;
-  p.Kp = L.Kp; p.FT = L.Kp / 16; p.cpt = L.Cp / 8; p.nchunk = L.nchunk; p.nsteps = L.nchunk_pad / 4;
-  p.rH = a.rH; p.rW = a.rW; p.rcs = a.rcs; p.rss = a.rss; p.roff = a.roff;
-  p.relu = a.relu;
-  p.x_bytes = (uint32_t)((int64_t)a.N * a.H * a.W * a.xcs * 2);
-  p.w_bytes = (uint32_t)((size_t)L.nchunk_pad * L.Kp * 16);
+  const Conv16Params p = params16(a);
   if (a.R == 3 && conv_patch_applies(p, a.N)) return launch_conv_patch(p, a.N, a.dt == FUPR_BF16, stream);
   if (a.R == 1 && prefer_pipe(p)) return launch_conv1x1_pipe(p, a.N, a.dt == FUPR_BF16, stream);
   if (a.R == 1 && conv1x1_stream_applies(p)) return launch_conv1x1_stream(p, a.N, a.dt == FUPR_BF16, stream);
@@ -330,10 +340,12 @@ fupr_status check_tensor(const fupr_tensor* t) {
 
 }  // namespace
 
-extern "C" fupr_status fupr_conv_fused(const fupr_conv_shape* shape, const fupr_tensor* x,
-                                       const void* packed, const fupr_residual* res,
-                                       uint32_t epilogue_flags, const fupr_tensor* y,
-                                       void* stream) {
+namespace {
+
+// Validates one fused convolution call and fills the launcher's arguments.
+fupr_status check_conv(const fupr_conv_shape* shape, const fupr_tensor* x, const void* packed,
+                       const fupr_residual* res, uint32_t epilogue_flags, const fupr_tensor* y,
+                       ConvArgs* out) {
   if (!shape || !x || !y || !packed) return FUPR_ERR_NULL;
   if (!shape_ok(shape)) return FUPR_ERR_SHAPE;
   if (epilogue_flags & ~uint32_t(FUPR_FUSE_RELU | FUPR_FUSE_ADD)) return FUPR_ERR_ARG;
@@ -381,7 +393,46 @@ extern "C" fupr_status fupr_conv_fused(const fupr_conv_shape* shape, const fupr_
     a.rH = t->H; a.rW = t->W; a.rC = t->C; a.rcs = t->c_stride;
     a.rss = res->spatial_stride; a.roff = res->c_offset;
   }
-  return launch_conv(a, stream);
+  *out = a;
+  return FUPR_OK;
+}
+
+}  // namespace
+
+extern "C" fupr_status fupr_conv_fused(const fupr_conv_shape* shape, const fupr_tensor* x,
+                                       const void* packed, const fupr_residual* res,
+                                       uint32_t epilogue_flags, const fupr_tensor* y,
+                                       void* stream) {
+  ConvArgs a;
+  const fupr_status st = check_conv(shape, x, packed, res, epilogue_flags, y, &a);
+  return st != FUPR_OK ? st : launch_conv(a, stream);
+}
+
+extern "C" fupr_status fupr_conv_conv1x1_fused(const fupr_conv_shape* shape1, const fupr_tensor* x,
+                                               const void* packed1, const fupr_residual* res,
+                                               uint32_t flags1, const fupr_tensor* y,
+                                               const fupr_conv_shape* shape2, const void* packed2,
+                                               uint32_t flags2, const fupr_tensor* h,
+                                               void* stream) {
+  ConvArgs a, b;
+  fupr_status st = check_conv(shape1, x, packed1, res, flags1, y, &a);
+  if (st != FUPR_OK) return st;
+  st = check_conv(shape2, y, packed2, nullptr, flags2, h, &b);
+  if (st != FUPR_OK) return st;
+  if (h->ptr == x->ptr || (res && h->ptr == res->t.ptr)) return FUPR_ERR_ARG;
+  if (a.dt == FUPR_F32) return FUPR_ERR_LIMIT;
+  const Conv16Params p1 = params16(a), p2 = params16(b);
+  if (!conv1x1_fused_pair_applies(p1, p2)) return FUPR_ERR_LIMIT;
+  return launch_conv1x1_fused_pair(p1, p2, a.N, a.dt == FUPR_BF16, stream);
+}
+
+bool fupr::conv_pair_fusable(const fupr_conv_shape& s1, const fupr_conv_shape& s2, fupr_dtype dt,
+                             int N, int H, int W) {
+  if (dt == FUPR_F32) return false;
+  Conv16Params g1 = geometry16(s1, dt, N, H, W);
+  g1.ycs = min_c_stride(s1.K, dt);
+  const Conv16Params g2 = geometry16(s2, dt, N, g1.P, g1.Q);
+  return s1.R == 1 && s2.R == 1 && conv1x1_fused_pair_applies(g1, g2);
 }
 
 extern "C" fupr_status fupr_conv_maxpool_fused(const fupr_conv_shape* shape, const fupr_tensor* x,

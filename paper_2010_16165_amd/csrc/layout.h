@@ -65,6 +65,10 @@ struct ConvArgs {
 };
 fupr_status launch_conv(const ConvArgs& a, void* stream);
 const char* conv_kernel_name(const fupr_conv_shape& s, fupr_dtype dt, int N, int H, int W);
+// Shapes only: can convolution s1 on an N x H x W input and convolution s2 on its
+// output run as one launch (fupr_conv_conv1x1_fused)?
+bool conv_pair_fusable(const fupr_conv_shape& s1, const fupr_conv_shape& s2, fupr_dtype dt, int N,
+                       int H, int W);
 
 // ---- whole network in one kernel, activations resident in LDS ----------------
 // One workgroup per image walks a table of layers; see resident.hip.

@@ -508,6 +508,7 @@ void plan_resident(fupr_model* m) {
 }
 
 void release_side(fupr_model* m);   // below, with the forked schedule
+bool conv_conv_pair(const fupr_model* m, size_t i);   // below, with the launch list
 
 void release_resident(fupr_model* m) {
   if (m->res_dev) (void)hipFree(m->res_dev);
@@ -632,6 +633,17 @@ extern "C" fupr_status fupr_model_create(const fupr_graph_desc* g, fupr_model** 
     m->tensors[m->ops[i].in].last_use = i;
     if (m->ops[i].res >= 0) m->tensors[m->ops[i].res].last_use = i;
   }
+  // two convolutions that may run as one kernel: what the first reads must
+  // outlive the second, whose output is written while the first still reads
+  for (int i = 0; i + 1 < n; ++i) {
+    if (!conv_conv_pair(m, (size_t)i)) continue;
+    TensorInfo& tin = m->tensors[m->ops[i].in];
+    tin.last_use = std::max(tin.last_use, i + 1);
+    if (m->ops[i].res >= 0) {
+      TensorInfo& tr = m->tensors[m->ops[i].res];
+      tr.last_use = std::max(tr.last_use, i + 1);
+    }
+  }
   std::vector<int> holder;  // buffer -> tensor id it holds, -1 = free
   for (int i = 0; i < n; ++i) {
     const int tid = i + 1;
@@ -743,10 +755,24 @@ bool stem_pool_pair(const fupr_model* m, size_t i) {
                            q.conv.stride, q.conv.pad);
 }
 
+// Operator i is a 1 x 1 convolution whose whole output tile a wave holds, and
+// operator i + 1 a 1 x 1 convolution of exactly that tensor (a bottleneck
+// block's last convolution and the next block's first): one kernel computes
+// both, the second from the first one's registers.
+bool conv_conv_pair(const fupr_model* m, size_t i) {
+  if (m->schedule != FUPR_SCHEDULE_AUTO || i + 1 >= m->ops.size()) return false;
+  const fupr_op_desc& a = m->ops[i];
+  const fupr_op_desc& b = m->ops[i + 1];
+  if (a.kind != FUPR_OP_CONV || b.kind != FUPR_OP_CONV) return false;
+  if (b.in != (int)i + 1 || b.res >= 0) return false;
+  const TensorInfo& tin = m->tensors[a.in];
+  return conv_pair_fusable(a.conv, b.conv, m->dt, 1, tin.H, tin.W);
+}
+
 std::vector<Launch> launches_of(const fupr_model* m) {
   std::vector<Launch> v;
   for (size_t i = 0; i < m->ops.size();) {
-    const int count = stem_pool_pair(m, i) ? 2 : 1;
+    const int count = (stem_pool_pair(m, i) || conv_conv_pair(m, i)) ? 2 : 1;
     v.push_back(Launch{(int)i, count});
     i += count;
   }
@@ -857,7 +883,19 @@ fupr_status run(const fupr_model* m, const fupr_tensor* input, const fupr_tensor
       const fupr_tensor x = view(op.in, n0, count);
       const fupr_tensor y = view((int)i + launches[l].count, n0, count);
       fupr_status st;
-      if (launches[l].count == 2) {
+      if (launches[l].count == 2 && m->ops[i + 1].kind == FUPR_OP_CONV) {
+        const fupr_op_desc& second = m->ops[i + 1];
+        const fupr_tensor mid = view((int)i + 1, n0, count);
+        fupr_residual r;
+        const bool add = op.res >= 0;
+        if (add) {
+          r.t = view(op.res, n0, count);
+          r.spatial_stride = op.res_spatial_stride;
+          r.c_offset = op.res_c_offset;
+        }
+        st = fupr_conv_conv1x1_fused(&op.conv, &x, op.packed, add ? &r : nullptr, op.epilogue, &mid,
+                                     &second.conv, second.packed, second.epilogue, &y, on);
+      } else if (launches[l].count == 2) {
         const fupr_op_desc& pool = m->ops[i + 1];
         st = fupr_conv_maxpool_fused(&op.conv, &x, op.packed, pool.conv.R, pool.conv.stride,
                                      pool.conv.pad, &y, on);
@@ -983,6 +1021,18 @@ extern "C" fupr_status fupr_model_launch_stats(const fupr_model* m, int32_t batc
     const Launch l = launches_of(m)[launch];
     fupr_status st = fupr_model_op_stats(m, batch, l.first, out);
     if (st != FUPR_OK || l.count == 1) return st;
+    if (m->ops[l.first + 1].kind == FUPR_OP_CONV) {
+      // two convolutions in one kernel: both outputs are written, the first one's
+      // is not read back
+      fupr_op_stats second;
+      st = fupr_model_op_stats(m, batch, l.first + 1, &second);
+      if (st != FUPR_OK) return st;
+      const TensorInfo& mid = m->tensors[l.first + 1];
+      out->flops += second.flops;
+      out->bytes += second.bytes - (double)elem_size(m->dt) * batch * (double)mid.H * mid.W * mid.C;
+      out->kernel = "conv1x1s_256f+conv1x1";
+      return FUPR_OK;
+    }
     // convolution + pool in one kernel: the convolution's flops; its input and
     // parameters read, the pool's output written
     fupr_op_stats pool;

@@ -236,6 +236,75 @@ def test_stem_maxpool_fused(fx, size, dtype):
     assert err2 <= TOL[dtype] / 4
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("case", [(32, 256, 32, True), (64, 200, 64, True), (58, 256, 45, False)],
+                         ids=["32-256-32+res", "64-200-64+res", "58-256-45"])
+def test_two_1x1_convolutions_in_one_kernel(fx, case, dtype):
+    """A block's last 1 x 1 convolution and the next block's first one as one
+    launch: both outputs against the oracle (the second from the first one's
+    value rounded to the storage type), and against the two separate kernels."""
+    B, network, torch = fx
+    c, k1, k2, with_res = case
+    n, hh, ww = 3, 9, 7
+    rng = np.random.default_rng(500 + c + k2)
+    print(f"pair {c}->{k1}->{k2} res={with_res} {dtype}", flush=True)
+    dt = B.DTYPES[dtype]
+    x = rng.standard_normal((n, c, hh, ww)).astype(np.float32)
+    w1 = (rng.standard_normal((k1, c, 1, 1)) * np.sqrt(2.0 / c)).astype(np.float32)
+    b1 = (rng.standard_normal(k1) * 0.1).astype(np.float32)
+    w2 = (rng.standard_normal((k2, k1, 1, 1)) * np.sqrt(2.0 / k1)).astype(np.float32)
+    b2 = (rng.standard_normal(k2) * 0.1).astype(np.float32)
+    rs = rng.standard_normal((n, k1, hh, ww)).astype(np.float32)
+    y_ref = orc.conv2d(round_to(x, dtype, torch), w1, 1, 0) + b1.astype(np.float64)[None, :, None, None]
+    if with_res:
+        y_ref = orc.add(y_ref, round_to(rs, dtype, torch))
+    y_ref = orc.relu(y_ref)
+    sh1, sh2 = B.shape_of(w1, 1, 0), B.shape_of(w2, 1, 0)
+    p1 = B.upload_blob(B.fupr_pack(sh1, w1, b1, dt))
+    p2 = B.upload_blob(B.fupr_pack(sh2, w2, b2, dt))
+    xd = B.DeviceTensor.from_nchw(x, dt)
+    rd = B.DeviceTensor.from_nchw(rs, dt)
+    yd = B.DeviceTensor.empty(n, hh, ww, k1, dt)
+    hd = B.DeviceTensor.empty(n, hh, ww, k2, dt)
+    yd.data.fill_(7.0)
+    hd.data.fill_(7.0)
+    res = (rd, 1, 0) if with_res else None
+    f1 = B.FUSE_RELU | (B.FUSE_ADD if with_res else 0)
+    B.fupr_conv_conv1x1_fused(sh1, xd, p1, res, f1, yd, sh2, p2, B.FUSE_RELU, hd)
+    torch.cuda.synchronize()
+    y = yd.to_nchw()
+    assert yd.padding_is_zero() and hd.padding_is_zero()
+    err_y = rel_err(y, y_ref)
+    # the second convolution reads what the device holds of y
+    h_ref = orc.relu(orc.conv2d(y, w2, 1, 0) + b2.astype(np.float64)[None, :, None, None])
+    err_h = rel_err(hd.to_nchw(), h_ref)
+    print(f"  max-norm rel err y {err_y:.3e}, h {err_h:.3e}", flush=True)
+    assert err_y <= TOL[dtype] and err_h <= TOL[dtype]
+    # the two separate kernels
+    y2 = B.DeviceTensor.empty(n, hh, ww, k1, dt)
+    h2 = B.DeviceTensor.empty(n, hh, ww, k2, dt)
+    B.fupr_conv_fused(sh1, xd, p1, res, f1, y2)
+    B.fupr_conv_fused(sh2, y2, p2, None, B.FUSE_RELU, h2)
+    torch.cuda.synchronize()
+    assert torch.equal(yd.data, y2.data)
+    assert rel_err(hd.to_nchw(), h2.to_nchw()) <= TOL[dtype] / 4
+
+
+def test_two_1x1_convolutions_rejected_when_not_a_pair(fx):
+    B, network, torch = fx
+    w1 = np.zeros((512, 64, 1, 1), np.float32)   # 512 filters: two filter groups
+    w2 = np.zeros((32, 512, 1, 1), np.float32)
+    sh1, sh2 = B.shape_of(w1, 1, 0), B.shape_of(w2, 1, 0)
+    p1 = B.upload_blob(B.fupr_pack(sh1, w1, np.zeros(512, np.float32), B.BF16))
+    p2 = B.upload_blob(B.fupr_pack(sh2, w2, np.zeros(32, np.float32), B.BF16))
+    xd = B.DeviceTensor.from_nchw(np.zeros((1, 64, 4, 4), np.float32), B.BF16)
+    yd = B.DeviceTensor.empty(1, 4, 4, 512, B.BF16)
+    hd = B.DeviceTensor.empty(1, 4, 4, 32, B.BF16)
+    with pytest.raises(B.FuprError) as e:
+        B.fupr_conv_conv1x1_fused(sh1, xd, p1, None, B.FUSE_RELU, yd, sh2, p2, B.FUSE_RELU, hd)
+    assert e.value.status == B.ERR_LIMIT
+
+
 def test_stem_maxpool_fused_rejects_other_shapes(fx):
     B, network, torch = fx
     wt = np.zeros((32, 3, 7, 7), np.float32)

@@ -381,8 +381,13 @@ def test_kernel_selection_per_layer_class():
     assert names[4].startswith("conv1x1s_") and names[5].startswith("conv1x1s_")
     assert names[6].startswith("conv16t_")        # stride 2 at 56 x 56: the general kernel
     assert names[8].startswith("conv1x1p_")       # 1024 channels: filters do not fit in LDS
-    # the stem convolution and the max-pool behind it are one launch
-    assert m.num_launches == m.num_ops - 1
+    # the stem convolution and the max-pool behind it are one launch, and so are
+    # the 64 -> 256 and 256 -> 32 1 x 1 convolutions (the second from the first's registers)
+    assert m.num_launches == m.num_ops - 2
+    pair = m.launch_stats(64, 3)
+    a, b = m.op_stats(64, 4), m.op_stats(64, 5)
+    assert pair["kernel"] == "conv1x1s_256f+conv1x1" and pair["flops"] == a["flops"] + b["flops"]
+    assert pair["bytes"] == a["bytes"] + b["bytes"] - 2 * 64 * 56 * 56 * 256
     first = m.launch_stats(64, 0)
     assert first["kernel"] == "stem7x7_maxpool"
     conv, pool = m.op_stats(64, 0), m.op_stats(64, 1)
