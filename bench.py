@@ -191,10 +191,14 @@ def main():
     n_launch = fm.num_launches
     stats = [fm.launch_stats(batch, i) for i in range(n_launch)]
     op_ms = op_ms[:n_launch]
-    if n_launch == 1 and fm.num_ops > 1:
-        sites = ["network"]
-    elif n_launch == fm.num_ops - 1 and stats[0]["kernel"] == "stem7x7_maxpool":
-        sites = [sites[0]] + list(sites[2:])    # stem convolution and max-pool are one launch
+    # a launch may cover several operators: name it after them
+    def launch_site(st):
+        if st["n_ops"] == fm.num_ops and fm.num_ops > 2:
+            return "network"
+        names = [str(sites[i]) for i in range(st["first_op"], st["first_op"] + st["n_ops"])
+                 if sites[i] is not None]
+        return "+".join(names) if names else "None"
+    sites = [launch_site(st) for st in stats]
     total_flops = sum(s["flops"] for s in stats)
     total_bytes = sum(s["bytes"] for s in stats)
     images_per_s = batch / (ms_per_step * 1e-3)
@@ -226,10 +230,10 @@ def main():
     roof["algorithmic_flops_per_launch"] = dom["flops"] / dom["launches"]
 
     if args.per_op:
-        print(f"{'op':>3} {'site':<12} {'kernel':<16} {'M':>9} {'C':>5} {'K':>5} RxS/s "
+        print(f"{'op':>3} {'site':<18} {'kernel':<21} {'M':>9} {'C':>5} {'K':>5} RxS/s "
               f"{'us':>8} {'GFLOP':>8} {'MB':>8} {'TF/s':>7} {'GB/s':>7}", file=sys.stderr)
         for i, (s, ms) in enumerate(zip(stats, op_ms)):
-            print(f"{i:>3} {str(sites[i]):<12} {s['kernel']:<16} {s['M']:>9} {s['C']:>5} {s['K']:>5} "
+            print(f"{i:>3} {str(sites[i]):<18} {s['kernel']:<21} {s['M']:>9} {s['C']:>5} {s['K']:>5} "
                   f"{s['R']}x{s['S']}/{s['stride']} {ms * 1e3:>8.1f} {s['flops'] / 1e9:>8.3f} "
                   f"{s['bytes'] / 1e6:>8.2f} {s['flops'] / ms / 1e9:>7.1f} {s['bytes'] / ms / 1e6:>7.0f}",
                   file=sys.stderr)

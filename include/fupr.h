@@ -367,6 +367,8 @@ typedef struct {
   double flops, bytes;
   int64_t M;         /* output pixels N*P*Q */
   int32_t K, C, R, S, stride;
+  int32_t first_op, n_ops; /* the operators covered: op itself for fupr_model_op_stats; a launch
+                              may cover two (stem convolution + max-pool, two 1 x 1 convolutions) */
   const char* kernel;
 } fupr_op_stats;
 fupr_status fupr_model_op_stats(const fupr_model* m, int32_t batch, int32_t op, fupr_op_stats* out);

@@ -81,7 +81,8 @@ class BnOut(C.Structure):
 class OpStats(C.Structure):
     _fields_ = [("flops", C.c_double), ("bytes", C.c_double), ("M", C.c_int64),
                 ("K", C.c_int32), ("C", C.c_int32), ("R", C.c_int32), ("S", C.c_int32),
-                ("stride", C.c_int32), ("kernel", C.c_char_p)]
+                ("stride", C.c_int32), ("first_op", C.c_int32), ("n_ops", C.c_int32),
+                ("kernel", C.c_char_p)]
 
 
 _F = C.POINTER(C.c_float)
@@ -439,7 +440,8 @@ class Model:
     @staticmethod
     def _stats(s):
         return {"flops": s.flops, "bytes": s.bytes, "M": s.M, "K": s.K, "C": s.C, "R": s.R,
-                "S": s.S, "stride": s.stride, "kernel": s.kernel.decode()}
+                "S": s.S, "stride": s.stride, "first_op": s.first_op, "n_ops": s.n_ops,
+                "kernel": s.kernel.decode()}
 
     def op_stats(self, batch, op):
         s = OpStats()

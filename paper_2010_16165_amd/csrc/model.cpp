@@ -984,6 +984,8 @@ extern "C" fupr_status fupr_model_op_stats(const fupr_model* m, int32_t batch, i
   const TensorInfo& to = m->tensors[op + 1];
   const double es = (double)elem_size(m->dt);
   fupr_op_stats s{};
+  s.first_op = op;
+  s.n_ops = 1;
   s.M = (int64_t)batch * to.H * to.W;
   s.K = to.C;
   s.C = ti.C;
@@ -1021,6 +1023,7 @@ extern "C" fupr_status fupr_model_launch_stats(const fupr_model* m, int32_t batc
     const Launch l = launches_of(m)[launch];
     fupr_status st = fupr_model_op_stats(m, batch, l.first, out);
     if (st != FUPR_OK || l.count == 1) return st;
+    out->n_ops = l.count;
     if (m->ops[l.first + 1].kind == FUPR_OP_CONV) {
       // two convolutions in one kernel: both outputs are written, the first one's
       // is not read back
@@ -1050,6 +1053,8 @@ extern "C" fupr_status fupr_model_launch_stats(const fupr_model* m, int32_t batc
   const TensorInfo& t0 = m->tensors.front();
   const TensorInfo& tl = m->tensors.back();
   fupr_op_stats s{};
+  s.first_op = 0;
+  s.n_ops = (int32_t)m->ops.size();
   s.M = batch;
   s.C = t0.C;
   s.K = tl.C;

@@ -159,13 +159,17 @@ def build(plan, device="cuda:0"):
             res, rss = x, 1
             if sc["kind"] == "none":
                 res = -1
-            elif sc["kind"] == "projection":
-                res = conv_op(proj, x)
             elif sc["kind"] == "optionA":
                 rss = sc["stride"]
             h = x
             for i in range(n - 1):
                 h = conv_op(first + i, h)
+                if i == 0 and sc["kind"] == "projection":
+                    # after the block's first convolution, so that it directly follows the
+                    # previous block's last one (the library runs such a pair as one kernel)
+                    res = conv_op(proj, x)
+            if n == 1 and sc["kind"] == "projection":
+                res = conv_op(proj, x)
             cur = conv_op(first + n - 1, h, res, rss, 0)
     model = B.Model(dt, plan["in_shape"], ops, keepalive=[dev])
     model.sites = sites
