@@ -58,6 +58,19 @@ CONV_CASES = [
     ("1x1 fc C512 K1000", 3, 512, 1, 1, 1000, 1, 1, 0, None, False),
     ("3x3 C1 K1", 1, 1, 5, 5, 1, 3, 1, 1, None, False),
     ("3x3 C8 K359 tiny image", 1, 8, 3, 3, 359, 3, 1, 1, None, True),
+    # tiles that run across image boundaries, several filter groups, every shortcut kind
+    ("3x3 C64 K128 7x7 x5 images +id", 5, 64, 7, 7, 128, 3, 1, 1, "identity", True),
+    ("3x3 C96 K200 s2 14x12 +optA", 3, 96, 14, 12, 200, 3, 2, 1, "optionA", True),
+    ("3x3 C40 K72 s2 odd width", 2, 40, 10, 13, 72, 3, 2, 1, None, False),
+    ("3x3 C32 K32 56x56", 2, 32, 56, 56, 32, 3, 1, 1, None, True),
+    ("3x3 C45 K64 56x56 +id", 1, 45, 56, 56, 64, 3, 1, 1, "identity", True),
+    # 1 x 1: filters in LDS / pipelined, ragged channel and filter counts, shortcuts
+    ("1x1 C200 K24", 3, 200, 9, 11, 24, 1, 1, 0, None, True),
+    ("1x1 C512 K64 +id norelu", 2, 512, 10, 10, 64, 1, 1, 0, "identity", False),
+    ("1x1 C520 K100 ragged", 3, 520, 7, 9, 100, 1, 1, 0, None, True),
+    ("1x1 C1024 K128", 1, 1024, 14, 14, 128, 1, 1, 0, None, True),
+    ("1x1 C136 K300 s2 +optA-shaped", 2, 136, 12, 12, 300, 1, 2, 0, None, False),
+    ("1x1 fc C2048 K1000", 4, 2048, 1, 1, 1000, 1, 1, 0, None, False),
 ]
 
 
