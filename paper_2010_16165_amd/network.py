@@ -161,15 +161,18 @@ def build(plan, device="cuda:0"):
                 res = -1
             elif sc["kind"] == "optionA":
                 rss = sc["stride"]
+            # Where the projection shortcut goes in the operator list: the library runs a
+            # block's last 1 x 1 convolution and the next block's first one as one kernel
+            # when they are adjacent, so a bottleneck block's projection follows its first
+            # convolution; a basic block's comes first.
+            late = sc["kind"] == "projection" and n >= 3
+            if sc["kind"] == "projection" and not late:
+                res = conv_op(proj, x)
             h = x
             for i in range(n - 1):
                 h = conv_op(first + i, h)
-                if i == 0 and sc["kind"] == "projection":
-                    # after the block's first convolution, so that it directly follows the
-                    # previous block's last one (the library runs such a pair as one kernel)
+                if i == 0 and late:
                     res = conv_op(proj, x)
-            if n == 1 and sc["kind"] == "projection":
-                res = conv_op(proj, x)
             cur = conv_op(first + n - 1, h, res, rss, 0)
     model = B.Model(dt, plan["in_shape"], ops, keepalive=[dev])
     model.sites = sites
