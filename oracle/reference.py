@@ -215,7 +215,10 @@ def zero_masked(model, masks):
 def extract(model, masks):
     """The thinner network left when masked filters are removed: the producer
     loses those filters (and batch-norm channels), the next conv of the block
-    loses the matching input channels."""
+    loses the matching input channels.  A block's LAST conv has no next conv:
+    its kept filters are recorded as the block's "stream_keep", the channels of
+    the block's full-width output they add to (identity shortcut only; the other
+    channels of the output are the shortcut's alone)."""
     out = dict(model)
     out["blocks"] = []
     for bi, blk in enumerate(model["blocks"]):
@@ -231,8 +234,13 @@ def extract(model, masks):
             nb["convs"][ci]["W"] = np.ascontiguousarray(nb["convs"][ci]["W"][keep])
             for key in ("gamma", "beta", "mean", "var"):
                 nb["bns"][ci][key] = np.ascontiguousarray(nb["bns"][ci][key][keep])
-            nxt = nb["convs"][ci + 1]
-            nxt["W"] = np.ascontiguousarray(nxt["W"][:, keep])
+            if ci + 1 < len(blk["convs"]):
+                nxt = nb["convs"][ci + 1]
+                nxt["W"] = np.ascontiguousarray(nxt["W"][:, keep])
+            else:
+                if blk["shortcut"]["kind"] != "identity":
+                    raise ValueError("output filters are removed only beside an identity shortcut")
+                nb["stream_keep"] = keep
         out["blocks"].append(nb)
     return out
 
@@ -405,6 +413,13 @@ def forward(model, x, masks=None, merged=False, trace=None):
             rec(f"b{bi}.conv{ci + 1}", h, None, y)
             h = y
         y = _conv_bn(h, convs[-1], bns[-1], merged)
+        keep = blk.get("stream_keep")
+        if keep is not None:
+            # removed output filters contribute nothing: the kept ones go to their
+            # own channels of a full-width tensor of zeros
+            wide = np.zeros_like(short)
+            wide[:, keep] = y
+            y = wide
         y = relu(y if short is None else add(y, short))
         rec(f"b{bi}.conv{len(convs)}", h, short, y)
         x = y

@@ -20,7 +20,9 @@ Layout of a model (all arrays numpy float32, C-contiguous):
     bn    = {"gamma", "beta", "mean", "var": (K,), "eps": float}
     block = {"kind": "basic" | "bottleneck",
              "convs": [conv, ...], "bns": [bn, ...],
-             "prune_permille": [int, ...],   # one per conv, 0 = not pruned
+             "prune_permille": [int, ...],   # one per conv, 0 = not pruned; a nonzero
+                                             # rate on the LAST conv prunes the block's
+                                             # output filters (identity shortcut only)
              "shortcut": {"kind": "identity"}
                        | {"kind": "optionA", "stride": 2}
                        | {"kind": "projection", "conv": conv, "bn": bn}}
@@ -72,11 +74,11 @@ def _conv_bn(rng, k, c, r, s, stride, pad):
     return cv, _bn(rng, k)
 
 
-def _basic_block(rng, c_in, k, stride, shortcut, permille):
+def _basic_block(rng, c_in, k, stride, shortcut, permille, out_permille=0):
     c1, b1 = _conv_bn(rng, k, c_in, 3, 3, stride, 1)
     c2, b2 = _conv_bn(rng, k, k, 3, 3, 1, 1)
     blk = {"kind": "basic", "convs": [c1, c2], "bns": [b1, b2],
-           "prune_permille": [int(permille), 0]}
+           "prune_permille": [int(permille), int(out_permille) if shortcut == "identity" else 0]}
     if shortcut == "projection":
         sc, sb = _conv_bn(rng, k, c_in, 1, 1, stride, 0)
         blk["shortcut"] = {"kind": "projection", "conv": sc, "bn": sb}
@@ -87,13 +89,14 @@ def _basic_block(rng, c_in, k, stride, shortcut, permille):
     return blk
 
 
-def _bottleneck_block(rng, c_in, width, stride, projection, permilles):
+def _bottleneck_block(rng, c_in, width, stride, projection, permilles, out_permille=0):
     k_out = 4 * width
     c1, b1 = _conv_bn(rng, width, c_in, 1, 1, 1, 0)
     c2, b2 = _conv_bn(rng, width, width, 3, 3, stride, 1)
     c3, b3 = _conv_bn(rng, k_out, width, 1, 1, 1, 0)
     blk = {"kind": "bottleneck", "convs": [c1, c2, c3], "bns": [b1, b2, b3],
-           "prune_permille": [int(permilles[0]), int(permilles[1]), 0]}
+           "prune_permille": [int(permilles[0]), int(permilles[1]),
+                              0 if projection else int(out_permille)]}
     if projection:
         sc, sb = _conv_bn(rng, k_out, c_in, 1, 1, stride, 0)
         blk["shortcut"] = {"kind": "projection", "conv": sc, "bn": sb}
@@ -108,16 +111,16 @@ def _head(rng, n_in, n_out):
             "fc_b": np.zeros(n_out, dtype=np.float32)}
 
 
-def make_block_model(seed, dtype="f32", channels=16, size=32, permille=250):
+def make_block_model(seed, dtype="f32", channels=16, size=32, permille=250, out_permille=0):
     """One CIFAR-style basic block with identity shortcut (config 0)."""
     rng = np.random.default_rng([seed, 1])
-    blk = _basic_block(rng, channels, channels, 1, "identity", permille)
+    blk = _basic_block(rng, channels, channels, 1, "identity", permille, out_permille)
     return {"name": "basic-block", "dtype": dtype, "in_shape": (channels, size, size),
             "stem": None, "blocks": [blk], "head": None}
 
 
 def make_cifar_resnet(seed, dtype="bf16", blocks_per_stage=9, permille=400,
-                      widths=(16, 32, 64), size=32, classes=10):
+                      widths=(16, 32, 64), size=32, classes=10, out_permille=0):
     """CIFAR residual network of Table II (3x3/16 stem, three stages, fc 10)
     with option-A shortcuts where the resolution halves."""
     rng = np.random.default_rng([seed, 1])
@@ -128,7 +131,8 @@ def make_cifar_resnet(seed, dtype="bf16", blocks_per_stage=9, permille=400,
         for bi in range(blocks_per_stage):
             down = si > 0 and bi == 0
             blocks.append(_basic_block(rng, c_in, k, 2 if down else 1,
-                                       "optionA" if down else "identity", permille))
+                                       "optionA" if down else "identity", permille,
+                                       out_permille))
             c_in = k
     return {"name": f"cifar-resnet{6 * blocks_per_stage + 2}", "dtype": dtype,
             "in_shape": (3, size, size),
@@ -137,7 +141,8 @@ def make_cifar_resnet(seed, dtype="bf16", blocks_per_stage=9, permille=400,
 
 
 def make_imagenet_basic_resnet(seed, dtype="bf16", stage_blocks=(2, 2, 2, 2), permille=300,
-                               widths=(64, 128, 256, 512), size=224, classes=1000):
+                               widths=(64, 128, 256, 512), size=224, classes=1000,
+                               out_permille=0):
     """ImageNet residual network of Table II (7x7/64 stem, max-pool, four
     stages of basic blocks, fc 1000) with projection shortcuts."""
     rng = np.random.default_rng([seed, 1])
@@ -148,7 +153,8 @@ def make_imagenet_basic_resnet(seed, dtype="bf16", stage_blocks=(2, 2, 2, 2), pe
         for bi in range(stage_blocks[si]):
             down = si > 0 and bi == 0
             blocks.append(_basic_block(rng, c_in, k, 2 if down else 1,
-                                       "projection" if down else "identity", permille))
+                                       "projection" if down else "identity", permille,
+                                       out_permille))
             c_in = k
     return {"name": f"imagenet-resnet{2 * sum(stage_blocks) + 2}", "dtype": dtype,
             "in_shape": (3, size, size),
@@ -158,7 +164,8 @@ def make_imagenet_basic_resnet(seed, dtype="bf16", stage_blocks=(2, 2, 2, 2), pe
 
 def make_imagenet_bottleneck_resnet(seed, dtype="bf16", stage_blocks=(3, 4, 6, 3),
                                     permille=500, permille_range=None,
-                                    widths=(64, 128, 256, 512), size=224, classes=1000):
+                                    widths=(64, 128, 256, 512), size=224, classes=1000,
+                                    out_permille=0):
     """Bottleneck residual network (1x1, 3x3, 1x1 with 4x expansion; stride on
     the 3x3).  permille_range=(lo, hi) draws one rate per prunable conv."""
     rng = np.random.default_rng([seed, 1])
@@ -174,7 +181,7 @@ def make_imagenet_bottleneck_resnet(seed, dtype="bf16", stage_blocks=(3, 4, 6, 3
             else:
                 lo, hi = permille_range
                 pm = tuple(int(np.floor(prng.uniform(lo, hi))) for _ in range(2))
-            blocks.append(_bottleneck_block(rng, c_in, w, stride, bi == 0, pm))
+            blocks.append(_bottleneck_block(rng, c_in, w, stride, bi == 0, pm, out_permille))
             c_in = 4 * w
     return {"name": f"imagenet-resnet{3 * sum(stage_blocks) + 2}", "dtype": dtype,
             "in_shape": (3, size, size),
@@ -210,20 +217,24 @@ def make_config(index):
 PAPER_WORKLOADS = ["resnet20", "resnet32", "resnet18", "resnet34"]
 
 
-def make_paper_workload(name, permille=300, dtype="bf16"):
+def make_paper_workload(name, permille=300, dtype="bf16", out_permille=0):
     """ResNet-20 / 32 on 32 x 32 images, ResNet-18 / 34 on 224 x 224 images, every
     block's first convolution pruned at `permille` (the paper's rates are 0, 100,
-    200, 300)."""
+    200, 300).  out_permille: the rate of the last convolution of every block with
+    an identity shortcut (the paper prunes all non-fused convolutions at one rate,
+    Sec. V-A; the blocks whose shortcut changes shape keep their output filters)."""
     seed = BASE_SEED + 10 + PAPER_WORKLOADS.index(name)
     if name == "resnet20":
-        m = make_cifar_resnet(seed, dtype, 3, permille)
+        m = make_cifar_resnet(seed, dtype, 3, permille, out_permille=out_permille)
     elif name == "resnet32":
-        m = make_cifar_resnet(seed, dtype, 5, permille)
+        m = make_cifar_resnet(seed, dtype, 5, permille, out_permille=out_permille)
     elif name == "resnet18":
-        m = make_imagenet_basic_resnet(seed, dtype, (2, 2, 2, 2), permille)
+        m = make_imagenet_basic_resnet(seed, dtype, (2, 2, 2, 2), permille,
+                                       out_permille=out_permille)
     else:
-        m = make_imagenet_basic_resnet(seed, dtype, (3, 4, 6, 3), permille)
-    m["name"] = f"{name}-{dtype}-p{permille}"
+        m = make_imagenet_basic_resnet(seed, dtype, (3, 4, 6, 3), permille,
+                                       out_permille=out_permille)
+    m["name"] = f"{name}-{dtype}-p{permille}" + (f"-out{out_permille}" if out_permille else "")
     return m
 
 

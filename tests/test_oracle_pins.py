@@ -356,6 +356,89 @@ def test_pruned_network_matches_library_with_zeroed_filters():
     np.testing.assert_allclose(y, ref, rtol=1e-10, atol=1e-10 * np.abs(ref).max())
 
 
+# ---- output filters of a block (Sec. V-A: all non-fused convolutions are pruned) -----
+
+def stream_models():
+    return [
+        synth.make_block_model(21, "bf16", 8, 10, 250, out_permille=400),
+        synth.make_cifar_resnet(22, "bf16", 2, 400, widths=(4, 8, 12), size=12, out_permille=300),
+        synth.make_imagenet_basic_resnet(23, "bf16", (2, 1, 2, 1), 300, widths=(4, 8, 8, 12), size=32,
+                                         classes=7, out_permille=500),
+        synth.make_imagenet_bottleneck_resnet(24, "bf16", (2, 2, 1, 1), 500, widths=(4, 4, 8, 8),
+                                              size=32, classes=5, out_permille=300),
+    ]
+
+
+@pytest.mark.parametrize("mi", range(4))
+def test_only_identity_blocks_lose_output_filters(mi):
+    model = stream_models()[mi]
+    masks = orc.select_masks(model)
+    seen = 0
+    for bi, blk in enumerate(model["blocks"]):
+        last = len(blk["convs"]) - 1
+        if blk["shortcut"]["kind"] == "identity":
+            m = masks[(bi, last)]
+            k = blk["convs"][last]["W"].shape[0]
+            assert int(m.sum()) == k - orc.prune_count(k, blk["prune_permille"][last]) < k
+            seen += 1
+        else:
+            assert (bi, last) not in masks
+    assert seen
+
+
+def test_block_output_with_removed_filters_by_hand():
+    """One block: the output channels whose filter went are relu(x) alone, the
+    others are those of the block with all its output filters (their filters and
+    what they read are untouched)."""
+    model = synth.make_block_model(25, "bf16", 8, 9, 0, out_permille=500)
+    x = np.abs(synth.make_input(95, 2, model["in_shape"]))
+    masks = orc.select_masks(model)
+    assert list(masks) == [(0, 1)]
+    keep = masks[(0, 1)].astype(bool)
+    assert keep.sum() == 4
+    full = orc.forward(model, x)
+    pruned = orc.forward(model, x, masks=masks)
+    assert np.array_equal(pruned[:, keep], full[:, keep])
+    assert np.array_equal(pruned[:, ~keep], np.maximum(x[:, ~keep].astype(np.float64), 0.0))
+    assert not np.array_equal(pruned[:, ~keep], full[:, ~keep])
+    ref = torch_forward(orc.zero_masked(model, masks), x)
+    np.testing.assert_allclose(pruned, ref, rtol=1e-10, atol=1e-10 * np.abs(ref).max())
+
+
+@pytest.mark.parametrize("mi", range(4))
+def test_removed_output_filters_equal_zeroed_filters(mi):
+    """The thin network, whose last convolution adds into the kept channels of the
+    full-width block output, gives bit for bit the zero-masked network's result."""
+    model = stream_models()[mi]
+    x = synth.make_input(94, 2, model["in_shape"])
+    masks = orc.select_masks(model)
+    zeroed = orc.forward(model, x, masks=masks)
+    thin = orc.extract(model, masks)
+    n_stream = 0
+    for (bi, ci), m in masks.items():
+        blk = thin["blocks"][bi]
+        assert blk["convs"][ci]["W"].shape[0] == int(m.sum())
+        if ci + 1 == len(blk["convs"]):
+            assert np.array_equal(blk["stream_keep"], np.flatnonzero(m))
+            n_stream += 1
+    assert n_stream
+    assert np.array_equal(zeroed, orc.forward(thin, x))
+    ref = torch_forward(orc.zero_masked(model, masks), x)
+    np.testing.assert_allclose(zeroed, ref, rtol=1e-10, atol=1e-10 * np.abs(ref).max())
+    inner = {k: v for k, v in masks.items() if k[1] + 1 < len(model["blocks"][k[0]]["convs"])}
+    assert not np.array_equal(zeroed, orc.forward(model, x, masks=inner))
+
+
+def test_output_filters_beside_a_projection_cannot_be_removed():
+    model = synth.make_imagenet_basic_resnet(26, "bf16", (1, 1), 300, widths=(4, 8), size=16, classes=3)
+    blk = model["blocks"][1]
+    assert blk["shortcut"]["kind"] == "projection"
+    mask = np.ones(8, dtype=np.uint8)
+    mask[0] = 0
+    with pytest.raises(ValueError):
+        orc.extract(model, {(1, 1): mask})
+
+
 def test_trace_records_every_conv_site():
     model = small_models()[3]
     x = synth.make_input(95, 1, model["in_shape"])
