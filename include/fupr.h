@@ -17,6 +17,9 @@
  *   fupr_pack            weights -> device layout
  *   fupr_conv_fused      convolution operator k x c x r x s (Sec. III, Sec. IV-B-1)
  *                        with bias, element-wise addition and ReLU in its epilogue
+ *   fupr_conv_scatter_fused             a block's last convolution after its output filters were
+ *                        pruned: the kept filters add into their channels of the block's
+ *                        full-width output (Alg. 1 applied to every non-fused operator, Sec. V-A)
  *   fupr_maxpool, fupr_global_avgpool   the "Others" of Table II / Table VI
  *   fupr_conv_conv1x1_fused             two consecutive 1 x 1 convolutions (a bottleneck block's last,
  *                        the next block's first), the second from the first one's registers
@@ -75,8 +78,9 @@ typedef struct {
   int32_t K, C, R, S, stride, pad;
 } fupr_conv_shape;
 
-/* What fupr_fold merges / what the kernel epilogue applies. */
-enum { FUPR_FUSE_BN = 1, FUPR_FUSE_RELU = 2, FUPR_FUSE_ADD = 4 };
+/* What fupr_fold merges / what the kernel epilogue applies.  FUPR_FUSE_SCATTER is
+ * accepted in fupr_op_desc.epilogue only (see there). */
+enum { FUPR_FUSE_BN = 1, FUPR_FUSE_RELU = 2, FUPR_FUSE_ADD = 4, FUPR_FUSE_SCATTER = 8 };
 
 /* ------------------------------------------------------------------ host -- */
 
@@ -242,6 +246,28 @@ fupr_status fupr_conv_fused(const fupr_conv_shape* shape, const fupr_tensor* x, 
                             const fupr_residual* res, uint32_t epilogue_flags, const fupr_tensor* y,
                             void* stream);
 
+/*
+ * The last convolution of a building block whose OUTPUT filters were pruned
+ * (Alg. 1 removes the lowest-norm filters of every non-fused operator, Sec. V-A;
+ * fupr_prune with no consumer gives the kept filters and keep_idx).  The block's
+ * output keeps its full width, because the shortcut still feeds every channel
+ * (Table II "add"); the shape->K kept filters add into their own channels:
+ *     y[n,p,q,keep_idx[j]] = act( b_j + conv_j(x)[n,p,q] + y[n,p,q,keep_idx[j]] ),  j < shape->K,
+ * in place: on entry y holds the shortcut tensor (identity shortcut: the block's
+ * input), every channel not listed is left as it is.  That equals the zero-masked
+ * block (removed filters and their batch norm set to zero) whenever act leaves the
+ * unlisted channels unchanged, i.e. for a shortcut that is the output of a ReLU.
+ * One rounding per updated element; fp32 accumulation as in fupr_conv_fused.
+ * keep_idx is [dev], shape->K int32 entries, distinct (equal entries race);
+ * an entry outside 0 .. y->C - 1 is skipped.  y has the convolution's output
+ * extent and y->C >= shape->K channels; x and y are 16-bit tensors of one type
+ * and do not overlap.  epilogue_flags: FUPR_FUSE_RELU or 0.
+ * Errors: NULL, SHAPE, DTYPE (fp32 tensors), ALIGN, ARG, LIMIT, LAUNCH.
+ */
+fupr_status fupr_conv_scatter_fused(const fupr_conv_shape* shape, const fupr_tensor* x,
+                                    const void* packed, const int32_t* keep_idx,
+                                    uint32_t epilogue_flags, const fupr_tensor* y, void* stream);
+
 /* Max over the taps of a k x k window that fall inside the image (Table II, ImageNet stem). */
 fupr_status fupr_maxpool(const fupr_tensor* x, int32_t k, int32_t stride, int32_t pad,
                          const fupr_tensor* y, void* stream);
@@ -298,8 +324,15 @@ typedef struct {
   int32_t res;           /* tensor added in the epilogue, -1 = none (conv only) */
   fupr_conv_shape conv;  /* conv: its shape.  maxpool: R = S = window, stride, pad */
   const void* packed;    /* [dev] conv only: blob from fupr_pack; must outlive the model */
-  uint32_t epilogue;     /* conv only: FUPR_FUSE_RELU | FUPR_FUSE_ADD */
+  uint32_t epilogue;     /* conv only: FUPR_FUSE_RELU | FUPR_FUSE_ADD | FUPR_FUSE_SCATTER */
   int32_t res_spatial_stride, res_c_offset; /* see fupr_residual */
+  /* With FUPR_FUSE_SCATTER (which needs FUPR_FUSE_ADD, 16-bit types, spatial stride 1 and
+   * channel offset 0): the operator is fupr_conv_scatter_fused on tensor `res`, updated in
+   * place; conv.K filters, keep_idx [dev] as described there, must outlive the model.  The
+   * operator's output tensor IS tensor `res` afterwards (same memory, res's width), so `res`
+   * must be an intermediate tensor (not 0) that no later operator reads under its old
+   * number, and the operator must not be the network's last.  NULL otherwise. */
+  const int32_t* keep_idx;
 } fupr_op_desc;
 
 typedef struct {

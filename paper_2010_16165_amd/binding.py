@@ -29,7 +29,7 @@ FUPR_OK = 0
 ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_MASK_EMPTY, ERR_BN_VAR = -1, -2, -3, -4, -5
 ERR_WORKSPACE, ERR_ALIGN, ERR_LAUNCH, ERR_ARG, ERR_LIMIT, ERR_BN_SCALE = -6, -7, -8, -9, -10, -11
 F32, BF16, F16 = 0, 1, 2
-FUSE_BN, FUSE_RELU, FUSE_ADD = 1, 2, 4
+FUSE_BN, FUSE_RELU, FUSE_ADD, FUSE_SCATTER = 1, 2, 4, 8
 OP_CONV, OP_MAXPOOL, OP_AVGPOOL = 0, 1, 2
 SHORTCUT_IDENTITY, SHORTCUT_SUBSAMPLE_PAD, SHORTCUT_PROJECTION = 0, 1, 2
 SCHEDULE_AUTO, SCHEDULE_PER_LAYER = 0, 1
@@ -60,7 +60,8 @@ class Residual(C.Structure):
 class OpDesc(C.Structure):
     _fields_ = [("kind", C.c_int32), ("in_", C.c_int32), ("res", C.c_int32), ("conv", ConvShape),
                 ("packed", C.c_void_p), ("epilogue", C.c_uint32),
-                ("res_spatial_stride", C.c_int32), ("res_c_offset", C.c_int32)]
+                ("res_spatial_stride", C.c_int32), ("res_c_offset", C.c_int32),
+                ("keep_idx", C.c_void_p)]
 
 
 class GraphDesc(C.Structure):
@@ -105,6 +106,8 @@ SIGNATURES = {
     "fupr_pack": (C.c_int32, [_SH, _F, _F, C.c_int, C.c_void_p]),
     "fupr_conv_fused": (C.c_int32, [_SH, _T, C.c_void_p, C.POINTER(Residual), C.c_uint32, _T,
                                     C.c_void_p]),
+    "fupr_conv_scatter_fused": (C.c_int32, [_SH, _T, C.c_void_p, C.c_void_p, C.c_uint32, _T,
+                                            C.c_void_p]),
     "fupr_maxpool": (C.c_int32, [_T, C.c_int32, C.c_int32, C.c_int32, _T, C.c_void_p]),
     "fupr_global_avgpool": (C.c_int32, [_T, _T, C.c_void_p]),
     "fupr_conv_conv1x1_fused": (C.c_int32, [_SH, _T, C.c_void_p, C.POINTER(Residual), C.c_uint32, _T,
@@ -354,6 +357,16 @@ def fupr_conv_fused(shape, x, packed, res, epilogue_flags, y, stream=None):
                               None if r is None else C.byref(r), int(epilogue_flags), C.byref(ys),
                               stream if stream is not None else current_stream())
     _check(st, "fupr_conv_fused")
+
+
+def fupr_conv_scatter_fused(shape, x, packed, keep_idx, epilogue_flags, y, stream=None):
+    """packed: torch uint8 CUDA tensor; keep_idx: torch int32 CUDA tensor of shape.K entries;
+    y is updated in place."""
+    xs, ys = x.struct, y.struct
+    st = _lib.fupr_conv_scatter_fused(C.byref(shape), C.byref(xs), C.c_void_p(packed.data_ptr()),
+                                      C.c_void_p(keep_idx.data_ptr()), int(epilogue_flags),
+                                      C.byref(ys), stream if stream is not None else current_stream())
+    _check(st, "fupr_conv_scatter_fused")
 
 
 def fupr_maxpool(x, k, stride, pad, y, stream=None):

@@ -19,6 +19,13 @@ struct Conv16Params {
   int rH, rW, rcs, rss, roff;
   int relu;
   uint32_t x_bytes, w_bytes;   // extents of x and w, for range-checked buffer loads
+  // A block's last convolution after its output filters were pruned (Alg. 1):
+  // filter j adds into channel keep[j] of y, which already holds the shortcut,
+  // and every other channel of y stays as it is.  keep = nullptr otherwise.
+  // keep has keep_n entries in device memory; entries outside 0 .. yC - 1 are
+  // skipped.  Only conv_tiled.hip and conv_patch.hip read these fields.
+  const int32_t* keep;
+  int keep_n, yC;
 };
 
 // conv_tiled.hip: LDS-staged filters, register-blocked tiles.  M = N*P*Q.

@@ -67,6 +67,8 @@ struct PatchParams {
   int Kp, cpt, n_stages;
   int rH, rW, rcs, rss, roff;
   int relu;
+  const int32_t* keep;   // pruned output filters of a block: filter j adds into channel
+  int keep_n, yC;        // keep[j] of y (keep_n entries, channels 0 .. yC - 1); else nullptr
   int PR, Wh, Whh;       // patch rows; slots per patch row (W + 2); even columns per row
   int plane_bytes;       // PR * Wh * 32
   int patch_slots;       // 2 planes * PR * Wh * 2 halves
@@ -121,7 +123,10 @@ constexpr int kLoaderWaves = 4;
 // reads and MFMAs in the main loop (a wave that waits for room in the vector
 // memory queue cannot issue its MFMAs); the loading waves move the next unit's
 // weights and patch global -> LDS meanwhile.  One barrier per unit joins them.
-template <bool BF, int WM, int WN, int MT, int NT>
+//
+// IX: the indexed epilogue of a block's last convolution whose output filters
+// were pruned (p.keep); without it p.keep is not read.
+template <bool BF, int WM, int WN, int MT, int NT, bool IX>
 __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kernel(
     const PatchParams p) {
   constexpr int NWC = WM * WN;
@@ -261,6 +266,7 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
   constexpr int NP = NT / 2;
   u32x4 rvw[MT][NP > 0 ? NP : 1];   // shortcut values, fetched during the last stage
   u32x2 rvo[MT];
+  int cidx[IX ? NT : 1][4];         // IX: the channels of y this lane's filters add into
   auto setup_compute = [&](int tile) {
     const int strip = div_by(tile, p.divF);
     c_f0 = (tile - strip * p.fgroups) * NF;
@@ -301,7 +307,7 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
     const int buf = u & 1;
     if (c_stage == 0) setup_compute(c_tile);
     const bool last = c_stage == p.n_stages - 1;
-    if (last && p.res) {
+    if (!IX && last && p.res) {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -317,6 +323,18 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
           const uint32_t off = (rc >= 0 && rc < p.rcs) ? roff[mt] + (uint32_t)rc * 2u : kOutside;
           rvo[mt] = __builtin_amdgcn_raw_buffer_load_b64(rrsrc, off, 0, 0);
         }
+      }
+    }
+    if constexpr (IX) {
+      if (last) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int kk = c_f0 + k_lane + t * 16 + i;
+            const int c = p.keep[min(kk, p.keep_n - 1)];
+            cidx[t][i] = kk < p.keep_n ? c : -1;
+          }
       }
     }
     const char* wts = lds + (p.w_resident ? c_stage * kWeightBytes : buf * p.buf_stride);
@@ -351,7 +369,47 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
       // (measured 3 - 8 % slower; the 7 x 4 tile is the exception and stays free)
       if constexpr (MT * NT <= 16) __builtin_amdgcn_sched_barrier(0);
     }
-    if (last) {
+    if (IX && last) {
+      // y holds the shortcut: 2-byte read, add, ReLU, one rounding, 2-byte write per
+      // kept filter; the reads of kGroup pixel tiles are in flight together
+      if constexpr (IX) {
+        constexpr int kGroup = (8 / NT) < 1 ? 1 : ((8 / NT) < MT ? (8 / NT) : MT);
+        auto offset_of = [&](int mt, int c) {
+          return (unsigned)c < (unsigned)p.yC ? yoff[mt] + (uint32_t)c * 2u : kOutside;
+        };
+#pragma unroll
+        for (int m0 = 0; m0 < MT; m0 += kGroup) {
+          uint16_t old[kGroup][NT][4];
+#pragma unroll
+          for (int dm = 0; dm < kGroup; ++dm)
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                const int mt = m0 + dm;
+                old[dm][t][i] = mt < MT ? __builtin_amdgcn_raw_buffer_load_b16(
+                                              yrsrc, offset_of(mt, cidx[t][i]), 0, 0)
+                                        : (uint16_t)0;
+              }
+#pragma unroll
+          for (int dm = 0; dm < kGroup; ++dm)
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                const int mt = m0 + dm;
+                if (mt < MT) {
+                  float v = acc[mt][t][i] + bias4[t][i] + to_float<BF>(old[dm][t][i]);
+                  if (p.relu) v = fmaxf(v, 0.f);
+                  __builtin_amdgcn_raw_buffer_store_b16(from_float<BF>(v), yrsrc,
+                                                        offset_of(mt, cidx[t][i]), 0, 0);
+                }
+              }
+        }
+      }
+      c_stage = 0;
+      ++c_tile;
+    } else if (last) {
       // bias, shortcut, ReLU, one rounding
       auto finish = [&](const f32x4& av, const f32x4& bv, uint32_t r0, uint32_t r1) {
         float v[4] = {av[0] + bv[0], av[1] + bv[1], av[2] + bv[2], av[3] + bv[3]};
@@ -468,6 +526,7 @@ bool plan_patch(const Conv16Params& c, int N, const PatchTile& tile, PatchPlan* 
   p.Kp = c.Kp; p.cpt = c.cpt; p.n_stages = (c.cpt + 3) / 4;
   p.rH = c.rH; p.rW = c.rW; p.rcs = c.rcs; p.rss = c.rss; p.roff = c.roff;
   p.relu = c.relu;
+  p.keep = c.keep; p.keep_n = c.keep_n; p.yC = c.yC;
   // virtual output rows a tile can touch
   const int rows_out = BM % c.Q == 0 ? BM / c.Q : (BM - 1 + c.Q - 1) / c.Q + 1;
   p.PR = (rows_out - 1) * c.stride + 3;
@@ -526,19 +585,25 @@ bool plan_patch(const Conv16Params& c, int N, const PatchTile& tile, PatchPlan* 
   return true;
 }
 
-template <bool BF, int WM, int WN, int MT, int NT>
-fupr_status launch_patch(const PatchPlan& plan, hipStream_t st) {
+template <bool BF, int WM, int WN, int MT, int NT, bool IX>
+fupr_status launch_patch_as(const PatchPlan& plan, hipStream_t st) {
   static std::once_flag once;
   static hipError_t status = hipSuccess;
   std::call_once(once, [] {
-    status =
-        hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_patch_kernel<BF, WM, WN, MT, NT>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPatchLdsLimit);
+    status = hipFuncSetAttribute(
+        reinterpret_cast<const void*>(&conv_patch_kernel<BF, WM, WN, MT, NT, IX>),
+        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPatchLdsLimit);
   });
   if (status != hipSuccess) return FUPR_ERR_LAUNCH;
-  hipLaunchKernelGGL((conv_patch_kernel<BF, WM, WN, MT, NT>), dim3((unsigned)plan.grid),
+  hipLaunchKernelGGL((conv_patch_kernel<BF, WM, WN, MT, NT, IX>), dim3((unsigned)plan.grid),
                      dim3((WM * WN + kLoaderWaves) * 64), plan.lds_bytes, st, plan.p);
   return launch_status("conv_patch_kernel");
+}
+
+template <bool BF, int WM, int WN, int MT, int NT>
+fupr_status launch_patch(const PatchPlan& plan, hipStream_t st) {
+  return plan.p.keep ? launch_patch_as<BF, WM, WN, MT, NT, true>(plan, st)
+                     : launch_patch_as<BF, WM, WN, MT, NT, false>(plan, st);
 }
 
 template <bool BF>

@@ -192,6 +192,29 @@ __global__ __launch_bounds__(256) void conv16_tiled_kernel(const Conv16Params p,
       rp = p.res + (((int64_t)n * p.rH + pp * p.rss) * p.rW + qq * p.rss) * p.rcs;
     }
     uint16_t* yp = p.y + (int64_t)m * p.ycs;
+    if (p.keep) {
+      // pruned output filters of a block: filter k adds into channel keep[k] of y,
+      // which holds the shortcut; one rounding, 2-byte accesses
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        const int ftile = fgi * (WN * NT) + wn * NT + t;
+        const int k0 = ftile * 16 + g * 4;
+        if (ftile >= p.FT) continue;
+        const float4 b4 = *reinterpret_cast<const float4*>(p.bias + k0);
+        const float b[4] = {b4.x, b4.y, b4.z, b4.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          if (k0 + i >= p.keep_n) continue;
+          const int c = p.keep[k0 + i];
+          if ((unsigned)c >= (unsigned)p.yC) continue;
+          float v = acc[mt][t][i] + b[i];
+          v += to_float<BF>(yp[c]);
+          if (p.relu) v = fmaxf(v, 0.f);
+          yp[c] = from_float<BF>(v);
+        }
+      }
+      continue;
+    }
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
       const int ftile = fgi * (WN * NT) + wn * NT + t;

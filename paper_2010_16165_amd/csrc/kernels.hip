@@ -264,6 +264,7 @@ Conv16Params params16(const ConvArgs& a) {
   p.relu = a.relu;
   p.x_bytes = (uint32_t)((int64_t)a.N * a.H * a.W * a.xcs * 2);
   p.w_bytes = (uint32_t)((size_t)L.nchunk_pad * L.Kp * 16);
+  p.keep = a.keep; p.keep_n = a.K; p.yC = a.yC;
   return p;
 }
 
@@ -276,10 +277,12 @@ bool prefer_pipe(const Conv16Params& g) {
 
 }  // namespace
 
-const char* conv_kernel_name(const fupr_conv_shape& s, fupr_dtype dt, int N, int H, int W) {
+const char* conv_kernel_name(const fupr_conv_shape& s, fupr_dtype dt, int N, int H, int W,
+                             bool indexed) {
   if (dt == FUPR_F32) return "conv32_direct";
   const Conv16Params g = geometry16(s, dt, N, H, W);
   if (s.R == 3 && conv_patch_applies(g, N)) return conv_patch_name(g, N);
+  if (indexed) return conv16_tiled_name(g.FT, g.nsteps, g.M);
   if (s.R == 1 && prefer_pipe(g)) return conv1x1_pipe_name(g);
   if (s.R == 1 && conv1x1_stream_applies(g)) return conv1x1_stream_name(g);
   if (s.R == 1 && conv1x1_pipe_applies(g)) return conv1x1_pipe_name(g);
@@ -311,6 +314,8 @@ fupr_status launch_conv(const ConvArgs& a, void* stream) {
   }
   const Conv16Params p = params16(a);
   if (a.R == 3 && conv_patch_applies(p, a.N)) return launch_conv_patch(p, a.N, a.dt == FUPR_BF16, stream);
+  // the indexed epilogue exists in the 3 x 3 kernel above and in the general one
+  if (a.keep) return launch_conv16_tiled(p, a.dt == FUPR_BF16, stream);
   if (a.R == 1 && prefer_pipe(p)) return launch_conv1x1_pipe(p, a.N, a.dt == FUPR_BF16, stream);
   if (a.R == 1 && conv1x1_stream_applies(p)) return launch_conv1x1_stream(p, a.N, a.dt == FUPR_BF16, stream);
   if (a.R == 1 && conv1x1_pipe_applies(p)) return launch_conv1x1_pipe(p, a.N, a.dt == FUPR_BF16, stream);
@@ -345,7 +350,7 @@ namespace {
 // Validates one fused convolution call and fills the launcher's arguments.
 fupr_status check_conv(const fupr_conv_shape* shape, const fupr_tensor* x, const void* packed,
                        const fupr_residual* res, uint32_t epilogue_flags, const fupr_tensor* y,
-                       ConvArgs* out) {
+                       ConvArgs* out, bool wider_y = false) {
   if (!shape || !x || !y || !packed) return FUPR_ERR_NULL;
   if (!shape_ok(shape)) return FUPR_ERR_SHAPE;
   if (epilogue_flags & ~uint32_t(FUPR_FUSE_RELU | FUPR_FUSE_ADD)) return FUPR_ERR_ARG;
@@ -364,7 +369,7 @@ fupr_status check_conv(const fupr_conv_shape* shape, const fupr_tensor* x, const
   if (x->C != shape->C || y->C != shape->K || y->N != x->N || y->H != P || y->W != Q)
     return FUPR_ERR_SHAPE;
   const PackedLayout L = packed_layout(*shape, x->dt);
-  if (y->c_stride > L.Kp) return FUPR_ERR_ALIGN;
+  if (!wider_y && y->c_stride > L.Kp) return FUPR_ERR_ALIGN;
   if (x->ptr == y->ptr) return FUPR_ERR_ARG;
 
   ConvArgs a{};
@@ -406,6 +411,27 @@ extern "C" fupr_status fupr_conv_fused(const fupr_conv_shape* shape, const fupr_
   ConvArgs a;
   const fupr_status st = check_conv(shape, x, packed, res, epilogue_flags, y, &a);
   return st != FUPR_OK ? st : launch_conv(a, stream);
+}
+
+extern "C" fupr_status fupr_conv_scatter_fused(const fupr_conv_shape* shape, const fupr_tensor* x,
+                                               const void* packed, const int32_t* keep_idx,
+                                               uint32_t epilogue_flags, const fupr_tensor* y,
+                                               void* stream) {
+  if (!shape || !x || !y || !packed || !keep_idx) return FUPR_ERR_NULL;
+  if (epilogue_flags & ~uint32_t(FUPR_FUSE_RELU)) return FUPR_ERR_ARG;
+  if ((reinterpret_cast<uintptr_t>(keep_idx) & 3u) != 0) return FUPR_ERR_ALIGN;
+  // the convolution's own output has shape->K channels; y is wider
+  fupr_tensor own = *y;
+  own.C = shape->K;
+  if (shape_ok(shape) && shape->K > y->C) return FUPR_ERR_SHAPE;
+  ConvArgs a;
+  const fupr_status st = check_conv(shape, x, packed, nullptr, epilogue_flags, &own, &a, true);
+  if (st != FUPR_OK) return st;
+  if (y->C <= 0 || y->c_stride < y->C) return FUPR_ERR_SHAPE;
+  if (a.dt == FUPR_F32) return FUPR_ERR_DTYPE;
+  a.keep = keep_idx;
+  a.yC = y->C;
+  return launch_conv(a, stream);
 }
 
 extern "C" fupr_status fupr_conv_conv1x1_fused(const fupr_conv_shape* shape1, const fupr_tensor* x,

@@ -62,9 +62,13 @@ struct ConvArgs {
   int rH, rW, rC, rcs, rss, roff;  // residual tensor geometry
   int relu;
   fupr_dtype dt;
+  const int32_t* keep;   // device, K entries: filter j adds into channel keep[j] of y; else nullptr
+  int yC;                // with keep: channels of y
 };
 fupr_status launch_conv(const ConvArgs& a, void* stream);
-const char* conv_kernel_name(const fupr_conv_shape& s, fupr_dtype dt, int N, int H, int W);
+// indexed: the convolution adds into listed channels of a wider tensor (ConvArgs::keep)
+const char* conv_kernel_name(const fupr_conv_shape& s, fupr_dtype dt, int N, int H, int W,
+                             bool indexed = false);
 // Shapes only: can convolution s1 on an N x H x W input and convolution s2 on its
 // output run as one launch (fupr_conv_conv1x1_fused)?
 bool conv_pair_fusable(const fupr_conv_shape& s1, const fupr_conv_shape& s2, fupr_dtype dt, int N,

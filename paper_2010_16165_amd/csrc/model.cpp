@@ -206,6 +206,7 @@ void plan_resident(fupr_model* m) {
   // every LDS tensor larger than 1 x 1 gets a ring of hp zero pixels
   int hp = 0;
   for (const fupr_op_desc& op : m->ops) {
+    if (op.kind == FUPR_OP_CONV && (op.epilogue & FUPR_FUSE_SCATTER)) return;   // per-operator kernels only
     if (op.kind == FUPR_OP_CONV) hp = std::max(hp, op.conv.pad);
     else if (op.kind != FUPR_OP_AVGPOOL) return;   // max-pool networks: images too large for LDS
   }
@@ -584,7 +585,11 @@ extern "C" fupr_status fupr_model_create(const fupr_graph_desc* g, fupr_model** 
       if (s.C != tin.C || tin.H + 2 * s.pad < s.R || tin.W + 2 * s.pad < s.S) {
         err = FUPR_ERR_SHAPE; break;
       }
-      if (op.epilogue & ~uint32_t(FUPR_FUSE_RELU | FUPR_FUSE_ADD)) { err = FUPR_ERR_ARG; break; }
+      if (op.epilogue & ~uint32_t(FUPR_FUSE_RELU | FUPR_FUSE_ADD | FUPR_FUSE_SCATTER)) {
+        err = FUPR_ERR_ARG; break;
+      }
+      const bool scatter = (op.epilogue & FUPR_FUSE_SCATTER) != 0;
+      if (scatter != (op.keep_idx != nullptr)) { err = scatter ? FUPR_ERR_NULL : FUPR_ERR_ARG; break; }
       t.C = s.K;
       t.H = out_extent(tin.H, s.R, s.stride, s.pad);
       t.W = out_extent(tin.W, s.S, s.stride, s.pad);
@@ -596,10 +601,22 @@ extern "C" fupr_status fupr_model_create(const fupr_graph_desc* g, fupr_model** 
         if (op.res_spatial_stride < 1 || op.res_c_offset < 0 || op.res_c_offset % 4 != 0) {
           err = FUPR_ERR_ARG; break;
         }
-        if (op.res_c_offset + tr.C > s.K || (int64_t)(t.H - 1) * op.res_spatial_stride >= tr.H ||
-            (int64_t)(t.W - 1) * op.res_spatial_stride >= tr.W) {
+        if (scatter) {
+          // the kept output filters add into tensor res in place; the output is that tensor
+          if (g->dt == FUPR_F32) { err = FUPR_ERR_DTYPE; break; }
+          if (op.res == 0 || i + 1 == g->n_ops || op.res_spatial_stride != 1 || op.res_c_offset != 0 ||
+              op.res == op.in) {
+            err = FUPR_ERR_ARG; break;
+          }
+          if (s.K > tr.C || tr.H != t.H || tr.W != t.W) { err = FUPR_ERR_SHAPE; break; }
+          t.C = tr.C;
+        } else if (op.res_c_offset + tr.C > s.K ||
+                   (int64_t)(t.H - 1) * op.res_spatial_stride >= tr.H ||
+                   (int64_t)(t.W - 1) * op.res_spatial_stride >= tr.W) {
           err = FUPR_ERR_SHAPE; break;
         }
+      } else if (scatter) {
+        err = FUPR_ERR_ARG; break;
       }
     } else if (op.kind == FUPR_OP_MAXPOOL) {
       const int k = op.conv.R;
@@ -633,6 +650,14 @@ extern "C" fupr_status fupr_model_create(const fupr_graph_desc* g, fupr_model** 
     m->tensors[m->ops[i].in].last_use = i;
     if (m->ops[i].res >= 0) m->tensors[m->ops[i].res].last_use = i;
   }
+  // a tensor updated in place must have no reader after the update
+  for (int i = 0; i < n; ++i) {
+    if (!(m->ops[i].epilogue & FUPR_FUSE_SCATTER) || m->ops[i].kind != FUPR_OP_CONV) continue;
+    if (m->tensors[m->ops[i].res].last_use != i) {
+      delete m;
+      return FUPR_ERR_ARG;
+    }
+  }
   // two convolutions that may run as one kernel: what the first reads must
   // outlive the second, whose output is written while the first still reads
   for (int i = 0; i + 1 < n; ++i) {
@@ -650,6 +675,10 @@ extern "C" fupr_status fupr_model_create(const fupr_graph_desc* g, fupr_model** 
     TensorInfo& t = m->tensors[tid];
     if (tid == n) {
       t.buffer = -2;
+    } else if (m->ops[i].kind == FUPR_OP_CONV && (m->ops[i].epilogue & FUPR_FUSE_SCATTER)) {
+      // the operator's output is the tensor it updated: same buffer, new holder
+      t.buffer = m->tensors[m->ops[i].res].buffer;
+      holder[t.buffer] = tid;
     } else {
       const size_t need = (size_t)t.H * t.W * t.cs;
       int pick = -1;
@@ -764,6 +793,7 @@ bool conv_conv_pair(const fupr_model* m, size_t i) {
   const fupr_op_desc& a = m->ops[i];
   const fupr_op_desc& b = m->ops[i + 1];
   if (a.kind != FUPR_OP_CONV || b.kind != FUPR_OP_CONV) return false;
+  if ((a.epilogue | b.epilogue) & FUPR_FUSE_SCATTER) return false;
   if (b.in != (int)i + 1 || b.res >= 0) return false;
   const TensorInfo& tin = m->tensors[a.in];
   return conv_pair_fusable(a.conv, b.conv, m->dt, 1, tin.H, tin.W);
@@ -899,6 +929,9 @@ fupr_status run(const fupr_model* m, const fupr_tensor* input, const fupr_tensor
         const fupr_op_desc& pool = m->ops[i + 1];
         st = fupr_conv_maxpool_fused(&op.conv, &x, op.packed, pool.conv.R, pool.conv.stride,
                                      pool.conv.pad, &y, on);
+      } else if (op.kind == FUPR_OP_CONV && (op.epilogue & FUPR_FUSE_SCATTER)) {
+        st = fupr_conv_scatter_fused(&op.conv, &x, op.packed, op.keep_idx,
+                                     op.epilogue & FUPR_FUSE_RELU, &y, on);
       } else if (op.kind == FUPR_OP_CONV) {
         fupr_residual r;
         const bool add = op.res >= 0;
@@ -998,7 +1031,11 @@ extern "C" fupr_status fupr_model_op_stats(const fupr_model* m, int32_t batch, i
     double res_b = 0.0;
     if (d.res >= 0) res_b = es * (double)s.M * m->tensors[d.res].C;
     s.bytes = in_b + out_b + res_b + es * crs * d.conv.K + 4.0 * d.conv.K;
-    s.kernel = conv_kernel_name(d.conv, m->dt, batch, ti.H, ti.W);
+    const bool scatter = (d.epilogue & FUPR_FUSE_SCATTER) != 0;
+    if (scatter)   // conv.K channels of the updated tensor read and written, and the index list
+      s.bytes = in_b + 2.0 * es * (double)s.M * d.conv.K + es * crs * d.conv.K + 8.0 * d.conv.K;
+    if (scatter) s.K = d.conv.K;
+    s.kernel = conv_kernel_name(d.conv, m->dt, batch, ti.H, ti.W, scatter);
   } else {
     s.R = s.S = d.kind == FUPR_OP_MAXPOOL ? d.conv.R : ti.H;
     s.stride = d.kind == FUPR_OP_MAXPOOL ? d.conv.stride : 1;

@@ -16,8 +16,9 @@ from . import binding as B
 class Layer:
     """One convolution site of the optimised network (host side)."""
 
-    def __init__(self, site, W, bias, stride, pad, relu, add=False):
+    def __init__(self, site, W, bias, stride, pad, relu, add=False, keep=None):
         self.site = site
+        self.keep = keep        # int32 channels of the block output the kept filters add into
         self.W = W              # folded, compacted, float32 K x C x R x S
         self.bias = bias        # float32 K
         self.stride = stride
@@ -83,12 +84,19 @@ def optimise(model, norm=1, aggressive=False, prune_fused=True):
             n_prune = counts[ci] if counts else B.fupr_prune_count(sh_raw.K, pm)
             mask = B.fupr_select_filters(sh_raw, raw, norm, n_prune)
             Wp, bp = folded[ci]
-            Wn = folded[ci + 1][0]
             prod = B.shape_of(Wp, convs[ci]["stride"], convs[ci]["pad"])
-            cons = B.shape_of(Wn, convs[ci + 1]["stride"], convs[ci + 1]["pad"])
-            keep, Wp_c, bp_c, (Wn_c,) = B.fupr_prune(prod, Wp, bp, mask, [cons], [Wn])
+            if ci + 1 < len(convs):
+                Wn = folded[ci + 1][0]
+                cons = B.shape_of(Wn, convs[ci + 1]["stride"], convs[ci + 1]["pad"])
+                keep, Wp_c, bp_c, (Wn_c,) = B.fupr_prune(prod, Wp, bp, mask, [cons], [Wn])
+                folded[ci + 1][0] = Wn_c
+            else:
+                # the block's output filters: nothing downstream shrinks, the kept filters
+                # add into their channels of the full-width output
+                if blk["shortcut"]["kind"] != "identity":
+                    raise ValueError("output filters are pruned only beside an identity shortcut")
+                keep, Wp_c, bp_c, _ = B.fupr_prune(prod, Wp, bp, mask, [], [])
             folded[ci] = [Wp_c, bp_c]
-            folded[ci + 1][0] = Wn_c
             masks[(bi, ci)] = mask
             keeps[(bi, ci)] = keep
         sc = blk["shortcut"]
@@ -101,7 +109,8 @@ def optimise(model, norm=1, aggressive=False, prune_fused=True):
         for ci, (Wf, bf) in enumerate(folded):
             last = ci == len(folded) - 1
             layers.append(Layer(f"b{bi}.conv{ci + 1}", Wf, bf, convs[ci]["stride"], convs[ci]["pad"],
-                                True, add=last and sc["kind"] != "none"))
+                                True, add=last and sc["kind"] != "none",
+                                keep=keeps.get((bi, ci)) if last else None))
         wiring.append(("block", (proj_layer, first, len(folded)), sc))
     head = model["head"]
     if head is not None:
@@ -125,9 +134,17 @@ def build(plan, device="cuda:0"):
         offsets.append(total)
         blobs.append(blob)
         total += (len(blob) + 255) // 256 * 256
+    keep_offsets = {}
+    for li, L in enumerate(plan["layers"]):
+        if L.keep is not None:
+            keep_offsets[li] = total
+            total += (4 * len(L.keep) + 255) // 256 * 256
     host = np.zeros(total, dtype=np.uint8)
     for off, blob in zip(offsets, blobs):
         host[off:off + len(blob)] = blob
+    for li, off in keep_offsets.items():
+        idx = np.ascontiguousarray(plan["layers"][li].keep, dtype=np.int32)
+        host[off:off + 4 * len(idx)] = idx.view(np.uint8)
     dev = B.upload_blob(host, device)
     base = dev.data_ptr()
 
@@ -136,7 +153,12 @@ def build(plan, device="cuda:0"):
     def conv_op(li, tin, res=-1, rss=1, roff=0):
         L = plan["layers"][li]
         epi = (B.FUSE_RELU if L.relu else 0) | (B.FUSE_ADD if res >= 0 else 0)
-        ops.append(B.OpDesc(B.OP_CONV, tin, res, L.shape, base + offsets[li], epi, rss, roff))
+        keep_ptr = None
+        if L.keep is not None:
+            epi |= B.FUSE_SCATTER
+            keep_ptr = base + keep_offsets[li]
+        ops.append(B.OpDesc(B.OP_CONV, tin, res, L.shape, base + offsets[li], epi, rss, roff,
+                            keep_ptr))
         sites.append(L.site)
         return len(ops)
 

@@ -698,6 +698,186 @@ def test_sub_batches_on_forked_streams_give_identical_results(fx):
             os.environ["FUPR_SPLIT"] = old
 
 
+# ---- a block's pruned output filters: indexed update of the full-width stream --------------
+
+SCATTER_CASES = [
+    # name, N, C, H, W, kept filters, channels of y, R, relu
+    ("3x3 C45 keep 45 of 64 56x56", 1, 45, 56, 56, 45, 64, 3, True),
+    ("3x3 C90 keep 90 of 128 28x28 x3", 3, 90, 28, 28, 90, 128, 3, True),
+    ("3x3 C180 keep 179 of 256 14x14", 2, 180, 14, 14, 179, 256, 3, True),
+    ("3x3 C24 keep 5 of 24 ragged", 2, 24, 13, 11, 5, 24, 3, True),
+    ("3x3 C16 keep 12 of 16 no relu", 2, 16, 32, 32, 12, 16, 3, False),
+    ("3x3 C64 keep 100 of 100 7x7 x5", 5, 64, 7, 7, 100, 100, 3, True),
+    ("3x3 C8 keep 3 of 10 general kernel", 1, 8, 9, 9, 3, 10, 3, True),
+    ("1x1 C32 keep 180 of 256", 2, 32, 14, 14, 180, 256, 1, True),
+    ("1x1 C64 keep 100 of 520 ragged", 3, 64, 7, 9, 100, 520, 1, True),
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("case", SCATTER_CASES, ids=[c[0] for c in SCATTER_CASES])
+def test_conv_scatter_site(fx, case, dtype):
+    """The kept filters add into their channels of y in place; every other channel
+    of y keeps its bits."""
+    B, network, torch = fx
+    name, n, c, h, w, k, width, r, relu = case
+    rng = np.random.default_rng(zlib.crc32(name.encode()))
+    print(f"case={name} dtype={dtype}", flush=True)
+    pad = r // 2
+    x = rng.standard_normal((n, c, h, w)).astype(np.float32)
+    wt = (rng.standard_normal((k, c, r, r)) * np.sqrt(2.0 / (c * r * r))).astype(np.float32)
+    bn = {"gamma": rng.uniform(0.5, 1.5, k).astype(np.float32),
+          "beta": (rng.standard_normal(k) * 0.1).astype(np.float32),
+          "mean": (rng.standard_normal(k) * 0.1).astype(np.float32),
+          "var": rng.uniform(0.5, 1.5, k).astype(np.float32), "eps": 1e-5}
+    keep = np.sort(rng.choice(width, size=k, replace=False)).astype(np.int32)
+    y0 = rng.standard_normal((n, width, h, w)).astype(np.float32)
+    dt = B.DTYPES[dtype]
+
+    y0r = round_to(y0, dtype, torch)
+    upd = orc.add(orc.batchnorm(orc.conv2d(round_to(x, dtype, torch), wt, 1, pad), bn),
+                  np.ascontiguousarray(y0r[:, keep]))
+    if relu:
+        upd = orc.relu(upd)
+
+    sh = B.shape_of(wt, 1, pad)
+    Wf, bf = B.fupr_fold(sh, wt, None, bn["gamma"], bn["beta"], bn["mean"], bn["var"], bn["eps"],
+                         B.FUSE_BN)
+    packed = B.upload_blob(B.fupr_pack(sh, Wf, bf, dt))
+    keep_d = torch.from_numpy(keep).cuda()
+    xd = B.DeviceTensor.from_nchw(x, dt)
+    yd = B.DeviceTensor.from_nchw(y0, dt)
+    B.fupr_conv_scatter_fused(sh, xd, packed, keep_d, B.FUSE_RELU if relu else 0, yd)
+    torch.cuda.synchronize()
+    got = yd.to_nchw()
+    assert yd.padding_is_zero()
+    rest = np.setdiff1d(np.arange(width), keep)
+    assert np.array_equal(got[:, rest], y0r[:, rest])
+    err = rel_err(got[:, keep], upd)
+    print(f"  max-norm rel err {err:.3e}", flush=True)
+    assert err <= TOL[dtype], (name, dtype, err)
+
+
+def test_conv_scatter_skips_entries_outside_the_tensor_and_rejects_bad_calls(fx):
+    B, network, torch = fx
+    rng = np.random.default_rng(17)
+    n, c, h, w, k, width = 2, 16, 12, 12, 6, 16
+    x = rng.standard_normal((n, c, h, w)).astype(np.float32)
+    wt = (rng.standard_normal((k, c, 3, 3)) * 0.1).astype(np.float32)
+    bias = rng.standard_normal(k).astype(np.float32)
+    y0 = rng.standard_normal((n, width, h, w)).astype(np.float32)
+    keep = np.array([1, -1, 5, 16, 9, 1 << 20], dtype=np.int32)
+    valid = np.array([0, 2, 4])
+    sh = B.shape_of(wt, 1, 1)
+    for dtype in ("bf16", "f16"):
+        dt = B.DTYPES[dtype]
+        packed = B.upload_blob(B.fupr_pack(sh, wt, bias, dt))
+        keep_d = torch.from_numpy(keep).cuda()
+        xd = B.DeviceTensor.from_nchw(x, dt)
+        yd = B.DeviceTensor.from_nchw(y0, dt)
+        B.fupr_conv_scatter_fused(sh, xd, packed, keep_d, 0, yd)
+        torch.cuda.synchronize()
+        got, y0r = yd.to_nchw(), round_to(y0, dtype, torch)
+        conv = orc.conv2d(round_to(x, dtype, torch), round_to(wt, dtype, torch), 1, 1)
+        ref = y0r.copy()
+        ref[:, keep[valid]] += conv[:, valid] + bias[valid].astype(np.float64)[None, :, None, None]
+        rest = np.setdiff1d(np.arange(width), keep[valid])
+        assert np.array_equal(got[:, rest], y0r[:, rest]) and yd.padding_is_zero()
+        assert rel_err(got[:, keep[valid]], ref[:, keep[valid]]) <= TOL[dtype]
+
+    dt = B.BF16
+    packed = B.upload_blob(B.fupr_pack(sh, wt, bias, dt))
+    keep_d = torch.from_numpy(keep).cuda()
+    xd = B.DeviceTensor.from_nchw(x, dt)
+    yd = B.DeviceTensor.from_nchw(y0, dt)
+    before = yd.data.clone()
+
+    def expect(code, fn):
+        with pytest.raises(B.FuprError) as e:
+            fn()
+        assert e.value.status == code
+        torch.cuda.synchronize()
+        assert torch.equal(yd.data, before)
+
+    narrow = B.DeviceTensor.from_nchw(y0[:, :4], dt)
+    expect(B.ERR_SHAPE, lambda: B.fupr_conv_scatter_fused(sh, xd, packed, keep_d, 0, narrow))
+    other = B.DeviceTensor.from_nchw(y0[:, :, :5], dt)
+    expect(B.ERR_SHAPE, lambda: B.fupr_conv_scatter_fused(sh, xd, packed, keep_d, 0, other))
+    expect(B.ERR_ARG, lambda: B.fupr_conv_scatter_fused(sh, xd, packed, keep_d, B.FUSE_ADD, yd))
+    x32 = B.DeviceTensor.from_nchw(x, B.F32)
+    y32 = B.DeviceTensor.from_nchw(y0, B.F32)
+    p32 = B.upload_blob(B.fupr_pack(sh, wt, bias, B.F32))
+    expect(B.ERR_DTYPE, lambda: B.fupr_conv_scatter_fused(sh, x32, p32, keep_d, 0, y32))
+    xs, ys = xd.struct, yd.struct
+    st = B._lib.fupr_conv_scatter_fused(B.C.byref(sh), B.C.byref(xs), B.C.c_void_p(packed.data_ptr()),
+                                        None, 0, B.C.byref(ys), None)
+    assert st == B.ERR_NULL
+
+
+def stream_models():
+    return [
+        synth.make_cifar_resnet(42, "bf16", 2, 400, widths=(8, 16, 24), size=16, classes=5,
+                                out_permille=300),
+        synth.make_imagenet_basic_resnet(43, "f16", (2, 1, 2, 1), 300, widths=(8, 16, 16, 24), size=32,
+                                         classes=7, out_permille=500),
+        synth.make_imagenet_bottleneck_resnet(44, "bf16", (2, 2, 1, 1), 500, widths=(4, 4, 8, 8),
+                                              size=32, classes=5, out_permille=300),
+        synth.make_cifar_resnet(45, "bf16", 3, 300, out_permille=300),
+    ]
+
+
+@pytest.mark.parametrize("mi", range(4))
+def test_network_with_pruned_output_filters(fx, mi):
+    """Every block with an identity shortcut also loses output filters (the paper
+    prunes all non-fused convolutions, Sec. V-A): against the zero-masked oracle."""
+    B, network, torch = fx
+    model = stream_models()[mi]
+    x = synth.make_input(81, 3, model["in_shape"])
+    masks = orc.select_masks(model)
+    ref = orc.forward(model, round_to(x, model["dtype"], torch), masks=masks)
+    plan, m, y = run_network(B, network, torch, model, x)
+    assert set(plan["masks"]) == set(masks)
+    n_stream = 0
+    for key in masks:
+        assert np.array_equal(plan["masks"][key], masks[key])
+        assert np.array_equal(plan["keep_idx"][key], np.flatnonzero(masks[key]))
+        n_stream += key[1] + 1 == len(model["blocks"][key[0]]["convs"])
+    assert n_stream >= 2
+    assert m.num_launches >= m.num_ops - 1     # one kernel per operator, not the one-kernel schedule
+    err = rel_err(y, ref)
+    print(f"model {mi} {model['name']} end-to-end rel err {err:.3e}", flush=True)
+    assert err <= TOL[model["dtype"]]
+    # the graph replays to the same bits (the updates are in place, the stream is rebuilt each pass)
+    dt = B.DTYPES[model["dtype"]]
+    xd = B.DeviceTensor.from_nchw(x, dt)
+    out, ws = m.alloc(x.shape[0])
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        g = m.fupr_graph_create(xd, out, ws, B.C.c_void_p(stream.cuda_stream))
+        for _ in range(3):
+            out.data.zero_()
+            stream.synchronize()
+            m.fupr_graph_launch(g, B.C.c_void_p(stream.cuda_stream))
+            stream.synchronize()
+            assert np.array_equal(out.to_nchw()[:, :, 0, 0], y)
+
+
+@pytest.mark.parametrize("name", ["resnet18", "resnet34"])
+def test_paper_workload_with_pruned_output_filters(fx, name):
+    B, network, torch = fx
+    model = synth.make_paper_workload(name, 300, out_permille=300)
+    x = synth.make_input(82, 2, model["in_shape"])
+    masks = orc.select_masks(model)
+    ref = orc.forward(model, round_to(x, model["dtype"], torch), masks=masks)
+    plan, m, y = run_network(B, network, torch, model, x)
+    kernels = [m.op_stats(2, i)["kernel"] for i, L in enumerate(m.sites) if L and L.endswith("conv2")]
+    assert all(k.startswith("conv3x3p_") for k in kernels)
+    err = rel_err(y, ref)
+    print(f"{model['name']}: rel err {err:.3e}", flush=True)
+    assert err <= TOL[model["dtype"]]
+
+
 def test_timed_forward_and_stats(fx):
     B, network, torch = fx
     model = synth.make_cifar_resnet(22, "bf16", 2, 400)

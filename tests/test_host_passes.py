@@ -425,6 +425,94 @@ def test_baseline_config_graphs_have_expected_launch_counts():
         assert len(plan["layers"]) == n
 
 
+# ---- a block's pruned output filters (Alg. 1 on every non-fused operator, Sec. V-A) ---------
+
+def scatter_ops(keep=0x2000, **change):
+    """stem, conv1, conv2 whose 11 kept filters add into the stem's 16 channels, head."""
+    specs = [
+        (B.OP_CONV, 0, -1, 16, 3, 3, 1, 1, B.FUSE_RELU, 1),                          # t1 16 x 32 x 32
+        (B.OP_CONV, 1, -1, 10, 16, 3, 1, 1, B.FUSE_RELU, 1),                         # t2
+        (B.OP_CONV, 2, 1, 11, 10, 3, 1, 1, B.FUSE_RELU | B.FUSE_ADD | B.FUSE_SCATTER, 1),  # t3 = t1 updated
+        (B.OP_AVGPOOL, 3, -1, 1, 1, 1, 1, 0, 0, 1),
+        (B.OP_CONV, 4, -1, 10, 16, 1, 1, 0, 0, 1),
+    ]
+    for i, spec in change.get("specs", {}).items():
+        specs[i] = spec
+    ops = fake_ops(specs)
+    ops[2].keep_idx = keep
+    return ops
+
+
+def test_model_plan_updates_the_stream_in_place():
+    m = B.Model(B.BF16, (3, 32, 32), scatter_ops(), None)
+    # t1 and t2 only: the update needs no buffer of its own
+    assert m.workspace_bytes(1) == 2 * 32 * 32 * 16 * 2
+    s = m.op_stats(2, 2)
+    assert s["K"] == 11 and s["C"] == 10
+    assert s["flops"] == 2.0 * 10 * 9 * 11 * 2 * 1024
+    # input once, 11 channels of the stream read and written, parameters, index list
+    assert s["bytes"] == 2 * (2 * 1024 * 10 + 2 * 2 * 1024 * 11 + 11 * 10 * 9) + 8 * 11
+    assert s["kernel"].startswith("conv3x3p_") or s["kernel"].startswith("conv16t_")
+    t = m.output_shape(3)
+    assert (t.C, t.c_stride) == (10, 16)
+    # no one-kernel schedule with such an operator
+    assert m.num_launches == m.num_ops
+
+
+def test_model_create_errors_of_in_place_updates():
+    S = B.FUSE_RELU | B.FUSE_ADD | B.FUSE_SCATTER
+    expect(B.ERR_NULL, lambda: B.Model(B.BF16, (3, 32, 32), scatter_ops(keep=None), None))
+    cases = [
+        ({2: (B.OP_CONV, 2, -1, 11, 10, 3, 1, 1, B.FUSE_RELU | B.FUSE_SCATTER, 1)}, B.ERR_ARG),  # no tensor
+        ({2: (B.OP_CONV, 2, 1, 17, 10, 3, 1, 1, S, 1)}, B.ERR_SHAPE),          # more filters than channels
+        ({2: (B.OP_CONV, 2, 1, 11, 10, 3, 2, 1, S, 1)}, B.ERR_SHAPE),          # other extent
+        ({2: (B.OP_CONV, 2, 1, 11, 10, 3, 1, 1, S, 2)}, B.ERR_ARG),            # strided shortcut
+        ({1: (B.OP_CONV, 0, -1, 10, 3, 3, 1, 1, B.FUSE_RELU, 1),
+          2: (B.OP_CONV, 2, 0, 3, 10, 3, 1, 1, S, 1)}, B.ERR_ARG),             # the network input
+        ({3: (B.OP_CONV, 1, -1, 10, 16, 1, 1, 0, 0, 1),
+          4: (B.OP_CONV, 3, -1, 10, 16, 1, 1, 0, 0, 1)}, B.ERR_ARG),           # old number read later
+    ]
+    for change, code in cases:
+        expect(code, lambda: B.Model(B.BF16, (3, 32, 32), scatter_ops(specs=change), None))
+    expect(B.ERR_DTYPE, lambda: B.Model(B.F32, (3, 32, 32), scatter_ops(), None))
+    last = scatter_ops()[:3]
+    expect(B.ERR_ARG, lambda: B.Model(B.BF16, (3, 32, 32), last, None))       # the network's last operator
+    plain = fake_ops([(B.OP_CONV, 0, -1, 16, 3, 3, 1, 1, B.FUSE_RELU, 1)])
+    plain[0].keep_idx = 0x2000
+    expect(B.ERR_ARG, lambda: B.Model(B.BF16, (3, 32, 32), plain, None))      # index list without the flag
+
+
+def test_output_filter_plan_matches_oracle():
+    """Masks and kept-filter lists of the blocks' last convolutions are the oracle's,
+    the compacted weights are its extraction, and only identity blocks take part."""
+    model = synth.make_imagenet_basic_resnet(23, "bf16", (2, 1, 2, 1), 300, widths=(4, 8, 8, 12),
+                                             size=32, classes=7, out_permille=500)
+    plan = network.optimise(model)
+    masks = orc.select_masks(model)
+    assert set(plan["masks"]) == set(masks)
+    thin = orc.extract(model, masks)
+    by_site = {L.site: L for L in plan["layers"]}
+    n_stream = 0
+    for bi, blk in enumerate(thin["blocks"]):
+        L = by_site[f"b{bi}.conv2"]
+        if "stream_keep" in blk:
+            assert blk["shortcut"]["kind"] == "identity"
+            assert np.array_equal(L.keep, blk["stream_keep"]) and L.keep.dtype == np.int32
+            assert np.array_equal(plan["masks"][(bi, 1)], masks[(bi, 1)])
+            n_stream += 1
+        else:
+            assert L.keep is None
+        wo, bo = orc.fold(blk["convs"][1]["W"], blk["bns"][1])
+        assert L.W.shape == wo.shape
+        np.testing.assert_allclose(L.W, wo, rtol=2 ** -23)
+        np.testing.assert_allclose(L.bias, bo, rtol=2 ** -22, atol=1e-9)
+    assert n_stream == 3
+    proj = synth.make_imagenet_basic_resnet(26, "bf16", (1, 1), 300, widths=(4, 8), size=16, classes=3)
+    proj["blocks"][1]["prune_permille"][1] = 300
+    with pytest.raises(ValueError):
+        network.optimise(proj)
+
+
 # ---- aggressive fusion (Sec. IV-B) -------------------------------------------------
 
 def fusible_blocks():
