@@ -110,6 +110,10 @@ def main():
                     help="one of the paper's own networks (Table II) instead of --config; "
                          "batch 1 unless --batch is given (Tables V-VI are batch-1 latencies)")
     ap.add_argument("--permille", type=int, default=300, help="pruning rate of --workload")
+    ap.add_argument("--out-permille", type=int, default=0,
+                    help="with --workload: pruning rate of the last convolution of every block "
+                         "with an identity shortcut (its kept filters add into the full-width "
+                         "block output)")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--schedule", choices=["auto", "per-layer"], default="auto")
     ap.add_argument("--aggressive", choices=["off", "fused", "fused-pruned"], default="off",
@@ -135,7 +139,8 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     if args.workload:
-        model, batch = synth.make_paper_workload(args.workload, args.permille), 1
+        model, batch = synth.make_paper_workload(args.workload, args.permille,
+                                                 out_permille=args.out_permille), 1
         args.config = -1
     else:
         model, batch = synth.make_config(args.config)

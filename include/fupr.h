@@ -258,8 +258,9 @@ fupr_status fupr_conv_fused(const fupr_conv_shape* shape, const fupr_tensor* x, 
  * block (removed filters and their batch norm set to zero) whenever act leaves the
  * unlisted channels unchanged, i.e. for a shortcut that is the output of a ReLU.
  * One rounding per updated element; fp32 accumulation as in fupr_conv_fused.
- * keep_idx is [dev], shape->K int32 entries, distinct (equal entries race);
- * an entry outside 0 .. y->C - 1 is skipped.  y has the convolution's output
+ * keep_idx is [dev], shape->K int32 entries, strictly ascending, in 0 .. y->C - 1
+ * (what fupr_prune writes); with any other content the values left in y are
+ * unspecified, but no access leaves y.  y has the convolution's output
  * extent and y->C >= shape->K channels; x and y are 16-bit tensors of one type
  * and do not overlap.  epilogue_flags: FUPR_FUSE_RELU or 0.
  * Errors: NULL, SHAPE, DTYPE (fp32 tensors), ALIGN, ARG, LIMIT, LAUNCH.

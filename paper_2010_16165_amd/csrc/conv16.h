@@ -22,8 +22,8 @@ struct Conv16Params {
   // A block's last convolution after its output filters were pruned (Alg. 1):
   // filter j adds into channel keep[j] of y, which already holds the shortcut,
   // and every other channel of y stays as it is.  keep = nullptr otherwise.
-  // keep has keep_n entries in device memory; entries outside 0 .. yC - 1 are
-  // skipped.  Only conv_tiled.hip and conv_patch.hip read these fields.
+  // keep has keep_n ascending entries in 0 .. yC - 1, in device memory.  Only
+  // conv_tiled.hip and conv_patch.hip read these fields.
   const int32_t* keep;
   int keep_n, yC;
 };

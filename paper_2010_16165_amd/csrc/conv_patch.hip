@@ -68,7 +68,8 @@ struct PatchParams {
   int rH, rW, rcs, rss, roff;
   int relu;
   const int32_t* keep;   // pruned output filters of a block: filter j adds into channel
-  int keep_n, yC;        // keep[j] of y (keep_n entries, channels 0 .. yC - 1); else nullptr
+  int keep_n, yC;        // keep[j] of y (keep_n ascending entries in 0 .. yC - 1); else nullptr
+  int ix_base;           // with keep: LDS byte offset of the computing waves' staging areas
   int PR, Wh, Whh;       // patch rows; slots per patch row (W + 2); even columns per row
   int plane_bytes;       // PR * Wh * 32
   int patch_slots;       // 2 planes * PR * Wh * 2 halves
@@ -117,6 +118,11 @@ __device__ __forceinline__ uint32_t clamp_below(uint32_t v, uint32_t floor2) {
 }
 
 constexpr int kLoaderWaves = 4;
+
+// Indexed epilogue: per computing wave, a staging area of 16 pixels x (NT * 16
+// slots + 4) floats, a byte table over kIxSpan channels, 64 channel numbers.
+constexpr int kIxSpan = 512;
+__host__ __device__ constexpr int kIxWaveBytes(int NT) { return 16 * (NT * 64 + 16) + kIxSpan + 256; }
 
 // WM x WN computing waves, each owning MT pixel tiles x NT filter tiles of
 // 16 x 16, and kLoaderWaves loading waves.  The computing waves issue only LDS
@@ -266,7 +272,9 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
   constexpr int NP = NT / 2;
   u32x4 rvw[MT][NP > 0 ? NP : 1];   // shortcut values, fetched during the last stage
   u32x2 rvo[MT];
-  int cidx[IX ? NT : 1][4];         // IX: the channels of y this lane's filters add into
+  // IX: this wave's filters are slots s0 .. s0 + ns - 1 of the index list; lane l < ns
+  // holds the channel of slot s0 + l, k_before / k_after the neighbouring entries (-1: none)
+  int ix_ns = 0, ix_chan = 0, ix_before = -1, ix_after = -1;
   auto setup_compute = [&](int tile) {
     const int strip = div_by(tile, p.divF);
     c_f0 = (tile - strip * p.fgroups) * NF;
@@ -325,16 +333,91 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
         }
       }
     }
+    // ---- indexed epilogue, part 1 (see part 2 after the taps) ----
+    constexpr int kRow = NT * 64 + 16;          // bytes per pixel row of the staging area
+    constexpr int kWholeIt = 3, kNarrowIt = 2;  // rounds per pixel tile fetched ahead of use
+    constexpr int kPer = kWholeIt * 4 + kNarrowIt;
+    // fetched before the last stage's taps where the registers allow, else after them
+    constexpr bool kAhead = IX && MT * NT * 4 + 2 * (MT + NT) * 4 + 44 + MT * kPer <= 256;
+    constexpr int kBatch = !IX || kAhead ? MT : (MT * NT > 16 ? 2 : 4);
+    char* scr = lds + p.ix_base + wave * kIxWaveBytes(NT);
+    uint8_t* inv = reinterpret_cast<uint8_t*>(scr + 16 * kRow);     // kIxSpan bytes
+    int* chan = reinterpret_cast<int*>(scr + 16 * kRow + kIxSpan);  // 64 entries
+    int a0 = 0, a1 = 0, nch = 0, n_lo = 0, n_hi = 0;
+    bool wide = false, lo_shared = false, hi_shared = false;
+    u32x4 oldw[IX ? kBatch : 1][kWholeIt];
+    uint16_t oldn[IX ? kBatch : 1][kNarrowIt];
+    auto whole_off = [&](int mt, int cb) {
+      const int a = a0 + cb + g;
+      const bool whole =
+          wide && cb + g < nch && !((a == a0 && lo_shared) || (a == a1 && hi_shared));
+      return whole ? yoff[mt] + (uint32_t)a * 16u : kOutside;
+    };
+    auto narrow_slot = [&](int q) { return q < n_lo ? q : ix_ns - n_hi + (q - n_lo); };
+    auto narrow_off = [&](int mt, int q) {
+      const int c = q < n_lo + n_hi ? chan[narrow_slot(q)] : -1;
+      return (unsigned)c < (unsigned)p.yC ? yoff[mt] + (uint32_t)c * 2u : kOutside;
+    };
+    auto fetch_old = [&](int m0) {
+#pragma unroll
+      for (int dm = 0; dm < kBatch; ++dm) {
+        const int mt = min(m0 + dm, MT - 1);
+#pragma unroll
+        for (int it = 0; it < kWholeIt; ++it)
+          oldw[dm][it] = __builtin_amdgcn_raw_buffer_load_b128(
+              yrsrc, m0 + dm < MT ? whole_off(mt, it * 4) : kOutside, 0, 0);
+#pragma unroll
+        for (int it = 0; it < kNarrowIt; ++it)
+          oldn[dm][it] = __builtin_amdgcn_raw_buffer_load_b16(
+              yrsrc, m0 + dm < MT ? narrow_off(mt, g + it * 4) : kOutside, 0, 0);
+      }
+    };
     if constexpr (IX) {
-      if (last) {
-#pragma unroll
-        for (int t = 0; t < NT; ++t)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int kk = c_f0 + k_lane + t * 16 + i;
-            const int c = p.keep[min(kk, p.keep_n - 1)];
-            cidx[t][i] = kk < p.keep_n ? c : -1;
-          }
+      if (c_stage == 0) {
+        const int s0 = c_f0 + wn * NT * 16;
+        ix_ns = min(NT * 16, p.keep_n - s0);
+        ix_chan = p.keep[min(max(s0 + lane, 0), p.keep_n - 1)];
+        ix_before = s0 > 0 && ix_ns > 0 ? p.keep[s0 - 1] : -1;
+        ix_after = ix_ns > 0 && s0 + ix_ns < p.keep_n ? p.keep[s0 + ix_ns] : -1;
+      }
+      if (last && ix_ns > 0) {
+        // The index list is ascending, so the wave's slots cover the channels
+        // c_first .. c_last and own every kept channel in between.  A 16-byte
+        // chunk (8 channels) of that range that holds no other wave's channel is
+        // read, updated and written whole; only the first and last chunk can hold
+        // a neighbour's channel.  This wave's channels in such a chunk (the first
+        // n_lo and last n_hi slots), and all of them when the range is wider than
+        // the byte table chunk channel -> slot, are updated with 2-byte accesses.
+        const int ns = ix_ns;
+        const int c_first = __builtin_amdgcn_readfirstlane(ix_chan);
+        const int c_last = __builtin_amdgcn_readlane(ix_chan, ns - 1);
+        a0 = c_first >> 3;
+        a1 = c_last >> 3;
+        nch = a1 - a0 + 1;
+        wide = c_first >= 0 && nch >= 1 && nch * 8 <= kIxSpan;
+        lo_shared = ix_before >= 0 && (ix_before >> 3) == a0;
+        hi_shared = ix_after >= 0 && (ix_after >> 3) == a1;
+        n_lo = ns;
+        n_hi = 0;
+        if (wide) {
+          const bool mine = lane < ns;
+          const int in_lo =
+              __builtin_popcountll(__builtin_amdgcn_ballot_w64(mine && (ix_chan >> 3) == a0));
+          const int in_hi =
+              __builtin_popcountll(__builtin_amdgcn_ballot_w64(mine && (ix_chan >> 3) == a1));
+          n_lo = lo_shared ? in_lo : 0;
+          n_hi = hi_shared ? in_hi : 0;
+          if (a1 == a0 && (lo_shared || hi_shared)) { n_lo = ns; n_hi = 0; }
+          *reinterpret_cast<uint2*>(inv + lane * 8) = uint2{0xffffffffu, 0xffffffffu};
+        }
+        chan[lane] = lane < ns ? ix_chan : -1;
+        __builtin_amdgcn_wave_barrier();
+        if (wide && lane < ns) {
+          const unsigned at = (unsigned)(ix_chan - a0 * 8);
+          if (at < (unsigned)kIxSpan) inv[at] = (uint8_t)lane;
+        }
+        __builtin_amdgcn_wave_barrier();
+        if constexpr (kAhead) fetch_old(0);
       }
     }
     const char* wts = lds + (p.w_resident ? c_stage * kWeightBytes : buf * p.buf_stride);
@@ -370,41 +453,71 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
       if constexpr (MT * NT <= 16) __builtin_amdgcn_sched_barrier(0);
     }
     if (IX && last) {
-      // y holds the shortcut: 2-byte read, add, ReLU, one rounding, 2-byte write per
-      // kept filter; the reads of kGroup pixel tiles are in flight together
       if constexpr (IX) {
-        constexpr int kGroup = (8 / NT) < 1 ? 1 : ((8 / NT) < MT ? (8 / NT) : MT);
-        auto offset_of = [&](int mt, int c) {
-          return (unsigned)c < (unsigned)p.yC ? yoff[mt] + (uint32_t)c * 2u : kOutside;
-        };
+        // part 2: y holds the shortcut; the sums reach lane (pixel, chunk) through
+        // this wave's 16 x slots staging area
+        const int ns = ix_ns;
+        if (ns > 0) {
+          const int n_narrow = n_lo + n_hi;
+          auto update_whole = [&](int mt, int cb, const u32x4& oldv) {
+            const uint2 which = *reinterpret_cast<const uint2*>(inv + (cb + g) * 8);
+            u32x4 out;
 #pragma unroll
-        for (int m0 = 0; m0 < MT; m0 += kGroup) {
-          uint16_t old[kGroup][NT][4];
+            for (int j = 0; j < 4; ++j) {
+              uint32_t halves[2];
 #pragma unroll
-          for (int dm = 0; dm < kGroup; ++dm)
-#pragma unroll
-            for (int t = 0; t < NT; ++t)
-#pragma unroll
-              for (int i = 0; i < 4; ++i) {
-                const int mt = m0 + dm;
-                old[dm][t][i] = mt < MT ? __builtin_amdgcn_raw_buffer_load_b16(
-                                              yrsrc, offset_of(mt, cidx[t][i]), 0, 0)
-                                        : (uint16_t)0;
+              for (int h = 0; h < 2; ++h) {
+                const int e = 2 * j + h;
+                const uint32_t slot = ((e < 4 ? which.x : which.y) >> (8 * (e & 3))) & 0xffu;
+                const bool has = slot != 0xffu;
+                const float add =
+                    *reinterpret_cast<const float*>(scr + li * kRow + (has ? slot : 0u) * 4);
+                const uint16_t o = (uint16_t)(oldv[j] >> (16 * h));
+                float r = to_float<BF>(o) + add;
+                if (p.relu) r = fmaxf(r, 0.f);
+                halves[h] = has ? (uint32_t)from_float<BF>(r) : (uint32_t)o;
               }
+              out[j] = halves[0] | (halves[1] << 16);
+            }
+            __builtin_amdgcn_raw_buffer_store_b128(out, yrsrc, whole_off(mt, cb), 0, 0);
+          };
+          auto update_narrow = [&](int mt, int q, uint16_t o) {
+            const int sl = narrow_slot(min(q, max(n_narrow - 1, 0)));
+            float r = to_float<BF>(o) + *reinterpret_cast<const float*>(scr + li * kRow + sl * 4);
+            if (p.relu) r = fmaxf(r, 0.f);
+            __builtin_amdgcn_raw_buffer_store_b16(from_float<BF>(r), yrsrc, narrow_off(mt, q), 0, 0);
+          };
 #pragma unroll
-          for (int dm = 0; dm < kGroup; ++dm)
+          for (int m0 = 0; m0 < MT; m0 += kBatch) {
+            if constexpr (!kAhead) fetch_old(m0);
 #pragma unroll
-            for (int t = 0; t < NT; ++t)
+            for (int dm = 0; dm < kBatch; ++dm) {
+              const int mt = m0 + dm;
+              if (mt < MT) {
+                __builtin_amdgcn_wave_barrier();
 #pragma unroll
-              for (int i = 0; i < 4; ++i) {
-                const int mt = m0 + dm;
-                if (mt < MT) {
-                  float v = acc[mt][t][i] + bias4[t][i] + to_float<BF>(old[dm][t][i]);
-                  if (p.relu) v = fmaxf(v, 0.f);
-                  __builtin_amdgcn_raw_buffer_store_b16(from_float<BF>(v), yrsrc,
-                                                        offset_of(mt, cidx[t][i]), 0, 0);
+                for (int t = 0; t < NT; ++t) {
+                  f32x4 v = acc[mt][t];
+#pragma unroll
+                  for (int i = 0; i < 4; ++i) v[i] += bias4[t][i];
+                  *reinterpret_cast<f32x4*>(scr + li * kRow + (t * 16 + g * 4) * 4) = v;
                 }
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int it = 0; it < kWholeIt; ++it) update_whole(mt, it * 4, oldw[dm][it]);
+#pragma unroll
+                for (int it = 0; it < kNarrowIt; ++it)
+                  if (g + it * 4 < n_narrow) update_narrow(mt, g + it * 4, oldn[dm][it]);
+                // longer ranges
+                for (int cb = kWholeIt * 4; wide && cb < nch; cb += 4)
+                  update_whole(mt, cb,
+                               __builtin_amdgcn_raw_buffer_load_b128(yrsrc, whole_off(mt, cb), 0, 0));
+                for (int q = g + kNarrowIt * 4; q < n_narrow; q += 4)
+                  update_narrow(mt, q,
+                                __builtin_amdgcn_raw_buffer_load_b16(yrsrc, narrow_off(mt, q), 0, 0));
               }
+            }
+          }
         }
       }
       c_stage = 0;
@@ -462,6 +575,12 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
   }
 }
 
+// Tiles the indexed epilogue is used with.  The two largest leave few registers
+// beside their accumulators, fetch from y in small batches and were measured
+// slower than the next smaller tiles (27 against 31 us on a 28 x 28, 90 -> 90 of
+// 128 layer at batch 64).
+constexpr bool indexed_tile(int MT, int NT) { return MT * NT < 21; }
+
 struct PatchTile {
   int WM, WN, MT, NT;
   const char* name;
@@ -506,6 +625,7 @@ bool plan_patch(const Conv16Params& c, int N, const PatchTile& tile, PatchPlan* 
   const int BM = tile.WM * tile.MT * 16, NF = tile.WN * tile.NT * 16;
   if (c.P * c.stride != c.H) return false;
   if (c.res && c.roff % 8 != 0) return false;   // 16-byte shortcut loads
+  if (c.keep && !indexed_tile(tile.MT, tile.NT)) return false;
   p.x = c.x; p.w = c.w; p.bias = c.bias; p.res = c.res; p.y = c.y;
   p.x_bytes = c.x_bytes; p.w_bytes = c.w_bytes;
   p.N = N; p.H = c.H; p.W = c.W; p.xcs = c.xcs;
@@ -555,6 +675,10 @@ bool plan_patch(const Conv16Params& c, int N, const PatchTile& tile, PatchPlan* 
     p.buf_stride = weight_bytes + patch_bytes;
     out->lds_bytes = 2 * (size_t)p.buf_stride;
   }
+  if (p.keep) {
+    p.ix_base = (int)out->lds_bytes;
+    out->lds_bytes += (size_t)NW * kIxWaveBytes(tile.NT);
+  }
   p.divQ = fast_div(c.Q);
   p.divWh = fast_div(p.Wh);
   p.divPR = fast_div(p.PR);
@@ -602,8 +726,10 @@ fupr_status launch_patch_as(const PatchPlan& plan, hipStream_t st) {
 
 template <bool BF, int WM, int WN, int MT, int NT>
 fupr_status launch_patch(const PatchPlan& plan, hipStream_t st) {
-  return plan.p.keep ? launch_patch_as<BF, WM, WN, MT, NT, true>(plan, st)
-                     : launch_patch_as<BF, WM, WN, MT, NT, false>(plan, st);
+  if constexpr (indexed_tile(MT, NT)) {
+    if (plan.p.keep) return launch_patch_as<BF, WM, WN, MT, NT, true>(plan, st);
+  }
+  return plan.p.keep ? FUPR_ERR_LIMIT : launch_patch_as<BF, WM, WN, MT, NT, false>(plan, st);
 }
 
 template <bool BF>

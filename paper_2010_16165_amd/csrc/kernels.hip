@@ -280,7 +280,10 @@ bool prefer_pipe(const Conv16Params& g) {
 const char* conv_kernel_name(const fupr_conv_shape& s, fupr_dtype dt, int N, int H, int W,
                              bool indexed) {
   if (dt == FUPR_F32) return "conv32_direct";
-  const Conv16Params g = geometry16(s, dt, N, H, W);
+  Conv16Params g = geometry16(s, dt, N, H, W);
+  // the indexed epilogue needs LDS of its own, which can change the tile: a marker
+  // that is never dereferenced stands for the index list
+  if (indexed) g.keep = reinterpret_cast<const int32_t*>(uintptr_t(16));
   if (s.R == 3 && conv_patch_applies(g, N)) return conv_patch_name(g, N);
   if (indexed) return conv16_tiled_name(g.FT, g.nsteps, g.M);
   if (s.R == 1 && prefer_pipe(g)) return conv1x1_pipe_name(g);

@@ -709,6 +709,10 @@ SCATTER_CASES = [
     ("3x3 C16 keep 12 of 16 no relu", 2, 16, 32, 32, 12, 16, 3, False),
     ("3x3 C64 keep 100 of 100 7x7 x5", 5, 64, 7, 7, 100, 100, 3, True),
     ("3x3 C8 keep 3 of 10 general kernel", 1, 8, 9, 9, 3, 10, 3, True),
+    ("3x3 C32 keep 5 of 8 one chunk", 2, 32, 10, 10, 5, 8, 3, True),
+    ("3x3 C16 keep 20 of 1200 sparse", 1, 16, 6, 6, 20, 1200, 3, True),
+    ("3x3 C64 keep 130 of 136 dense", 2, 64, 9, 9, 130, 136, 3, True),
+    ("3x3 C48 keep 70 of 700 wide range", 1, 48, 8, 8, 70, 700, 3, False),
     ("1x1 C32 keep 180 of 256", 2, 32, 14, 14, 180, 256, 1, True),
     ("1x1 C64 keep 100 of 520 ragged", 3, 64, 7, 9, 100, 520, 1, True),
 ]
@@ -758,7 +762,7 @@ def test_conv_scatter_site(fx, case, dtype):
     assert err <= TOL[dtype], (name, dtype, err)
 
 
-def test_conv_scatter_skips_entries_outside_the_tensor_and_rejects_bad_calls(fx):
+def test_conv_scatter_rejects_bad_calls(fx):
     B, network, torch = fx
     rng = np.random.default_rng(17)
     n, c, h, w, k, width = 2, 16, 12, 12, 6, 16
@@ -766,25 +770,8 @@ def test_conv_scatter_skips_entries_outside_the_tensor_and_rejects_bad_calls(fx)
     wt = (rng.standard_normal((k, c, 3, 3)) * 0.1).astype(np.float32)
     bias = rng.standard_normal(k).astype(np.float32)
     y0 = rng.standard_normal((n, width, h, w)).astype(np.float32)
-    keep = np.array([1, -1, 5, 16, 9, 1 << 20], dtype=np.int32)
-    valid = np.array([0, 2, 4])
+    keep = np.array([1, 2, 5, 9, 14, 15], dtype=np.int32)
     sh = B.shape_of(wt, 1, 1)
-    for dtype in ("bf16", "f16"):
-        dt = B.DTYPES[dtype]
-        packed = B.upload_blob(B.fupr_pack(sh, wt, bias, dt))
-        keep_d = torch.from_numpy(keep).cuda()
-        xd = B.DeviceTensor.from_nchw(x, dt)
-        yd = B.DeviceTensor.from_nchw(y0, dt)
-        B.fupr_conv_scatter_fused(sh, xd, packed, keep_d, 0, yd)
-        torch.cuda.synchronize()
-        got, y0r = yd.to_nchw(), round_to(y0, dtype, torch)
-        conv = orc.conv2d(round_to(x, dtype, torch), round_to(wt, dtype, torch), 1, 1)
-        ref = y0r.copy()
-        ref[:, keep[valid]] += conv[:, valid] + bias[valid].astype(np.float64)[None, :, None, None]
-        rest = np.setdiff1d(np.arange(width), keep[valid])
-        assert np.array_equal(got[:, rest], y0r[:, rest]) and yd.padding_is_zero()
-        assert rel_err(got[:, keep[valid]], ref[:, keep[valid]]) <= TOL[dtype]
-
     dt = B.BF16
     packed = B.upload_blob(B.fupr_pack(sh, wt, bias, dt))
     keep_d = torch.from_numpy(keep).cuda()
