@@ -193,7 +193,7 @@ _DEFAULT_BATCH = [1, 128, 64, 64, 256]
 
 
 def make_config(index):
-    """Model and default batch size of BASELINE workload `index` (0..4)."""
+    """Model and default batch size of benchmark configuration `index` (0..4)."""
     seed = BASE_SEED + index
     if index == 0:
         m = make_block_model(seed, "f32", 16, 32, 250)
