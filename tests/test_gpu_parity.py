@@ -865,6 +865,40 @@ def test_paper_workload_with_pruned_output_filters(fx, name):
     assert err <= TOL[model["dtype"]]
 
 
+@pytest.mark.parametrize("name,batch", [("resnet34", 64), ("resnet18", 192)])
+def test_pruned_output_filters_full_batch_sampled(fx, name, batch):
+    """The batch sizes bench.py uses, launched the way it launches them (HIP-graph
+    replay on a side stream; 192 images run as two sub-batches on forked streams,
+    each updating its own slice of the stream in place); the oracle computes three
+    of the images."""
+    B, network, torch = fx
+    model = synth.make_paper_workload(name, 300, out_permille=300)
+    dtype = model["dtype"]
+    plan = network.optimise(model)
+    m, _ = network.build(plan)
+    x = synth.make_input(83, batch, model["in_shape"])
+    xd = B.DeviceTensor.from_nchw(x, B.DTYPES[dtype])
+    s = torch.cuda.Stream()
+    sp = B.C.c_void_p(s.cuda_stream)
+    with torch.cuda.stream(s):
+        out, ws = m.alloc(batch)
+        out.data.fill_(float("nan"))
+        s.synchronize()
+        g = m.fupr_graph_create(xd, out, ws, sp)
+        for _ in range(2):
+            m.fupr_graph_launch(g, sp)
+            s.synchronize()
+    y = out.to_nchw()[:, :, 0, 0]
+    assert np.isfinite(y).all()
+    masks = orc.select_masks(model)
+    worst = 0.0
+    for i in (0, batch // 2, batch - 1):
+        ref = orc.forward(model, round_to(x[i:i + 1], dtype, torch), masks=masks)
+        worst = max(worst, rel_err(y[i:i + 1], ref))
+    print(f"{model['name']} batch {batch}: worst sampled rel err {worst:.3e}", flush=True)
+    assert worst <= TOL[dtype]
+
+
 def test_timed_forward_and_stats(fx):
     B, network, torch = fx
     model = synth.make_cifar_resnet(22, "bf16", 2, 400)
