@@ -99,6 +99,36 @@ def measured_traffic(kernel, args):
     return entry["bytes_per_launch"] if entry else None
 
 
+def measured_peaks(B, torch, dt):
+    """What two kernels of known work and nothing else reach on this GPU (beside the
+    published peaks the roofline entry is priced against): MFMAs on registers only,
+    and a 1 GiB device-to-device copy (bytes read + bytes written per second)."""
+    out = torch.empty(2048 * 256, dtype=torch.float32, device="cuda")
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    mfma_dt = dt if dt in (B.BF16, B.F16) else B.BF16
+    best_mfma = 0.0
+    B.fupr_measure_mfma(mfma_dt, 100, 2048, out)
+    for _ in range(3):
+        start.record()
+        flops = B.fupr_measure_mfma(mfma_dt, 20000, 2048, out)
+        stop.record()
+        stop.synchronize()
+        best_mfma = max(best_mfma, flops / (start.elapsed_time(stop) * 1e-3))
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    best_copy = 0.0
+    B.fupr_measure_copy(src, dst, n)
+    for _ in range(5):
+        start.record()
+        B.fupr_measure_copy(src, dst, n)
+        stop.record()
+        stop.synchronize()
+        best_copy = max(best_copy, 2.0 * n / (start.elapsed_time(stop) * 1e-3))
+    return {"mfma_tflops": best_mfma / 1e12, "mfma_dtype": "bf16" if mfma_dt == B.BF16 else "f16",
+            "copy_gbs": best_copy / 1e9}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -121,6 +151,8 @@ def main():
                          "convolutions, no additions; fused-pruned = then the n - m prune-back of Alg. 1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-op", action="store_true", help="print a per-operator table to stderr")
+    ap.add_argument("--no-measured-peaks", action="store_true",
+                    help="skip the two measuring kernels (MFMA rate, 1 GiB copy)")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="skip the short runs of the ImageNet-size configurations")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -263,11 +295,21 @@ def main():
     }
     default_run = (args.config == 1 and not args.batch and args.schedule == "auto"
                    and args.aggressive == "off" and not args.workload)
+    if not args.no_measured_peaks:
+        mp = measured_peaks(B, torch, dt)
+        line["measured_peaks"] = mp
+        measured = mp["mfma_tflops"] if roof["unit"] == "TFLOP/s" and dt != B.F32 else mp["copy_gbs"]
+        if roof["unit"] == "TFLOP/s" and dt == B.F32:
+            measured = None      # the fp32 path is plain vector arithmetic, not priced against MFMAs
+        roof["frac_of_measured_peak"] = roof["achieved"] / measured if measured else None
     if default_run and not args.no_other_workloads:
         # the larger configurations of the same path, a few replays each
         del xd, out, ws
         torch.cuda.empty_cache()
         line["other_workloads"] = [quick_measure(c) for c in (2, 3, 4)]
+        if "measured_peaks" in line:
+            for w in line["other_workloads"]:
+                w["mfma_frac_of_measured_peak"] = w["tflops"] / line["measured_peaks"]["mfma_tflops"]
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(model, batch, args.aggressive)
     print(json.dumps(line))

@@ -430,6 +430,24 @@ fupr_status fupr_graph_create(const fupr_model* m, const fupr_tensor* input,
 fupr_status fupr_graph_launch(const fupr_graph* g, void* stream);
 void fupr_graph_destroy(fupr_graph* g);
 
+/* ------------------------------------------------------- measuring aids -- */
+
+/*
+ * Kernels of known work and nothing else, for the roofline figures reported
+ * beside the published peaks (they are not part of the method).
+ * fupr_measure_mfma: `workgroups` workgroups of 4 waves, each wave issuing
+ * iters * 8 MFMAs 16 x 16 x 32 of type dt (FUPR_BF16 / FUPR_F16) on registers only;
+ * out [dev] receives workgroups * 256 floats (so that the work cannot be dropped);
+ * *flops [host] receives the number of floating-point operations enqueued.
+ * fupr_measure_copy: dst[0..bytes) = src[0..bytes), 16 bytes per lane; bytes a
+ * multiple of 16, both pointers [dev] 16-byte aligned, not overlapping.
+ * Asynchronous on `stream`; the caller times them.  Errors: NULL, DTYPE, ARG, SHAPE,
+ * ALIGN, LAUNCH.
+ */
+fupr_status fupr_measure_mfma(int32_t dt, int32_t iters, int32_t workgroups, void* out,
+                              double* flops, void* stream);
+fupr_status fupr_measure_copy(const void* src, void* dst, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -129,6 +129,9 @@ SIGNATURES = {
                                       C.POINTER(C.c_void_p)]),
     "fupr_graph_launch": (C.c_int32, [C.c_void_p, C.c_void_p]),
     "fupr_graph_destroy": (None, [C.c_void_p]),
+    "fupr_measure_mfma": (C.c_int32, [C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                      C.POINTER(C.c_double), C.c_void_p]),
+    "fupr_measure_copy": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
 }
 for _name, (_res, _args) in SIGNATURES.items():
     _fn = getattr(_lib, _name)
@@ -402,6 +405,22 @@ def fupr_global_avgpool(x, y, stream=None):
     st = _lib.fupr_global_avgpool(C.byref(xs), C.byref(ys),
                                   stream if stream is not None else current_stream())
     _check(st, "fupr_global_avgpool")
+
+
+def fupr_measure_mfma(dt, iters, workgroups, out, stream=None):
+    """out: torch float32 CUDA tensor of workgroups * 256 elements.  Returns the flops enqueued."""
+    flops = C.c_double(0.0)
+    st = _lib.fupr_measure_mfma(int(dt), int(iters), int(workgroups), C.c_void_p(out.data_ptr()),
+                                C.byref(flops), stream if stream is not None else current_stream())
+    _check(st, "fupr_measure_mfma")
+    return flops.value
+
+
+def fupr_measure_copy(src, dst, nbytes, stream=None):
+    """src, dst: torch CUDA tensors of at least nbytes bytes."""
+    st = _lib.fupr_measure_copy(C.c_void_p(src.data_ptr()), C.c_void_p(dst.data_ptr()), int(nbytes),
+                                stream if stream is not None else current_stream())
+    _check(st, "fupr_measure_copy")
 
 
 # ---- model ----------------------------------------------------------------------

@@ -7,7 +7,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfupr.so")
 SOURCES = ["host_passes.cpp", "kernels.hip", "conv_tiled.hip", "conv_patch.hip", "stem_pool.hip", "conv1x1.hip", "conv1x1_pipe.hip", "resident.hip",
-           "model.cpp"]
+           "peaks.hip", "model.cpp"]
 HEADERS = [os.path.join(ROOT, "include", "fupr.h"), os.path.join(CSRC, "layout.h"),
            os.path.join(CSRC, "device_utils.h"), os.path.join(CSRC, "conv16.h"), os.path.join(CSRC, "stem_pool.h")]
 

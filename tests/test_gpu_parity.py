@@ -899,6 +899,29 @@ def test_pruned_output_filters_full_batch_sampled(fx, name, batch):
     assert worst <= TOL[dtype]
 
 
+def test_measuring_kernels(fx):
+    """The copy copies; the MFMA loop reports its work and multiplies what it says
+    (ones times ones, summed over 32 channels, iters times)."""
+    B, network, torch = fx
+    src = torch.randint(0, 255, (1 << 20,), dtype=torch.uint8, device="cuda")
+    dst = torch.zeros_like(src)
+    B.fupr_measure_copy(src, dst, src.numel())
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    with pytest.raises(B.FuprError) as e:
+        B.fupr_measure_copy(src, dst, 24)
+    assert e.value.status == B.ERR_SHAPE
+    out = torch.zeros(4 * 256, dtype=torch.float32, device="cuda")
+    for dt in (B.BF16, B.F16):
+        flops = B.fupr_measure_mfma(dt, 3, 4, out)
+        torch.cuda.synchronize()
+        assert flops == 4 * 4 * 3 * 8 * 2 * 16 * 16 * 32
+        assert torch.isfinite(out).all() and float(out.abs().max()) > 0
+    with pytest.raises(B.FuprError) as e:
+        B.fupr_measure_mfma(B.F32, 3, 4, out)
+    assert e.value.status == B.ERR_DTYPE
+
+
 def test_timed_forward_and_stats(fx):
     B, network, torch = fx
     model = synth.make_cifar_resnet(22, "bf16", 2, 400)
