@@ -267,13 +267,20 @@ def main():
     roof["algorithmic_flops_per_launch"] = dom["flops"] / dom["launches"]
 
     if args.per_op:
+        # per launch: time, algorithmic work, rates, their share of the published MFMA (or
+        # fp32 vector) and HBM peaks, and which of the two the operator's arithmetic
+        # intensity puts it under
         print(f"{'op':>3} {'site':<18} {'kernel':<21} {'M':>9} {'C':>5} {'K':>5} RxS/s "
-              f"{'us':>8} {'GFLOP':>8} {'MB':>8} {'TF/s':>7} {'GB/s':>7}", file=sys.stderr)
+              f"{'us':>8} {'GFLOP':>8} {'MB':>8} {'TF/s':>7} {'GB/s':>7} {'%flop':>6} {'%hbm':>6} bound",
+              file=sys.stderr)
         for i, (s, ms) in enumerate(zip(stats, op_ms)):
+            sec = ms * 1e-3
+            bound = "flop" if s["bytes"] and s["flops"] / s["bytes"] >= ridge else "hbm"
             print(f"{i:>3} {str(sites[i]):<18} {s['kernel']:<21} {s['M']:>9} {s['C']:>5} {s['K']:>5} "
                   f"{s['R']}x{s['S']}/{s['stride']} {ms * 1e3:>8.1f} {s['flops'] / 1e9:>8.3f} "
-                  f"{s['bytes'] / 1e6:>8.2f} {s['flops'] / ms / 1e9:>7.1f} {s['bytes'] / ms / 1e6:>7.0f}",
-                  file=sys.stderr)
+                  f"{s['bytes'] / 1e6:>8.2f} {s['flops'] / ms / 1e9:>7.1f} {s['bytes'] / ms / 1e6:>7.0f} "
+                  f"{100 * s['flops'] / sec / peak_flops:>6.1f} {100 * s['bytes'] / sec / PEAK_HBM:>6.1f} "
+                  f"{bound}", file=sys.stderr)
         print(f"sum of per-op event times {op_ms.sum() * 1e3:.1f} us; graph step {ms_per_step * 1e3:.1f} us",
               file=sys.stderr)
 
