@@ -762,6 +762,55 @@ def test_conv_scatter_site(fx, case, dtype):
     assert err <= TOL[dtype], (name, dtype, err)
 
 
+def test_conv_scatter_random_shapes(fx):
+    """Seeded random shapes and index lists (clustered and spread, few and many
+    filter groups, ragged pixel counts): the chunk ownership of the 3 x 3 kernel's
+    indexed epilogue must hold for every way the kept channels fall into chunks."""
+    B, network, torch = fx
+    rng = np.random.default_rng(20101616)
+    worst = 0.0
+    for case in range(24):
+        r = 3 if case % 4 else 1
+        width = int(rng.choice([16, 24, 40, 64, 72, 128, 200, 256, 520]))
+        frac = float(rng.choice([0.15, 0.5, 0.7, 0.9, 1.0]))
+        k = max(1, int(width * frac))
+        c = int(rng.choice([16, 24, 32, 45, 64, 90]))
+        h, w = int(rng.integers(5, 20)), int(rng.integers(5, 20))
+        n = int(rng.integers(1, 4))
+        dtype = "bf16" if case % 2 else "f16"
+        if case % 3 == 0:      # clustered: a contiguous run of channels, then the rest spread
+            start = int(rng.integers(0, width - k + 1))
+            keep = np.arange(start, start + k)
+        else:
+            keep = np.sort(rng.choice(width, size=k, replace=False))
+        keep = keep.astype(np.int32)
+        print(f"case {case}: {r}x{r} C{c} keep {k} of {width}, {n}x{h}x{w} {dtype}", flush=True)
+        pad = r // 2
+        x = rng.standard_normal((n, c, h, w)).astype(np.float32)
+        wt = (rng.standard_normal((k, c, r, r)) * np.sqrt(2.0 / (c * r * r))).astype(np.float32)
+        bias = (rng.standard_normal(k) * 0.1).astype(np.float32)
+        y0 = rng.standard_normal((n, width, h, w)).astype(np.float32)
+        dt = B.DTYPES[dtype]
+        y0r = round_to(y0, dtype, torch)
+        conv = orc.conv2d(round_to(x, dtype, torch), round_to(wt, dtype, torch), 1, pad)
+        upd = orc.relu(conv + bias.astype(np.float64)[None, :, None, None] + y0r[:, keep])
+        sh = B.shape_of(wt, 1, pad)
+        packed = B.upload_blob(B.fupr_pack(sh, wt, bias, dt))
+        keep_d = torch.from_numpy(keep).cuda()
+        xd = B.DeviceTensor.from_nchw(x, dt)
+        yd = B.DeviceTensor.from_nchw(y0, dt)
+        B.fupr_conv_scatter_fused(sh, xd, packed, keep_d, B.FUSE_RELU, yd)
+        torch.cuda.synchronize()
+        got = yd.to_nchw()
+        rest = np.setdiff1d(np.arange(width), keep)
+        assert np.array_equal(got[:, rest], y0r[:, rest]), case
+        assert yd.padding_is_zero()
+        err = rel_err(got[:, keep], upd)
+        worst = max(worst, err)
+        assert err <= TOL[dtype], (case, err)
+    print(f"worst rel err {worst:.3e}", flush=True)
+
+
 def test_conv_scatter_rejects_bad_calls(fx):
     B, network, torch = fx
     rng = np.random.default_rng(17)
