@@ -26,7 +26,9 @@
 //     of the next unit while the computing waves multiply the current one, so
 //     that a computing wave never waits for room in the vector memory queue
 //     with its MFMAs behind it.  Units (tile, stage) are double buffered; one
-//     barrier per unit joins the two kinds of waves.
+//     barrier per unit joins the two kinds of waves.  The smallest tiles, whose
+//     units are shorter than the latency of their loads, keep a ring of up to
+//     four buffers and load up to three units ahead.
 //   * A workgroup is persistent: it walks a contiguous range of tiles, and the
 //     sequence (tile, stage) is one pipeline, so that the first loads of the
 //     next tile fly during the last stage and the epilogue of the current one.
@@ -77,7 +79,8 @@ struct PatchParams {
   int tap1, tap2;        // byte offsets of the second and third tap of a row
   int w_resident;        // all stages' weights stay in LDS (one filter group only)
   int patch_base;        // LDS byte offset of patch buffer 0
-  int buf_stride;        // bytes from buffer 0 to buffer 1
+  int buf_stride;        // bytes from one buffer of the ring to the next
+  int depth;             // buffers in the ring: units loaded ahead of the one multiplied, plus one
   int fgroups, tiles;
   int tiles_q, tiles_r;  // tiles / grid, tiles % grid
   FastDiv divQ, divWh, divPR, divHv, divPv, divF;   // by Q, Wh, PR, Hv, Pv, fgroups
@@ -117,6 +120,25 @@ __device__ __forceinline__ uint32_t clamp_below(uint32_t v, uint32_t floor2) {
   return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(a, f));
 }
 
+// s_waitcnt vmcnt(n) for a wave-uniform n known only at run time: wait until at
+// most n of this wave's vector-memory loads are outstanding (they complete in
+// order).  The counter has 6 bits; a smaller allowance than asked is always safe.
+__device__ __forceinline__ void wait_vmcnt(int n) {
+#define FUPR_VMCNT(k) case k: asm volatile("s_waitcnt vmcnt(" #k ")" ::: "memory"); break;
+  switch (__builtin_amdgcn_readfirstlane(n)) {
+    FUPR_VMCNT(0) FUPR_VMCNT(1) FUPR_VMCNT(2) FUPR_VMCNT(3) FUPR_VMCNT(4) FUPR_VMCNT(5) FUPR_VMCNT(6)
+    FUPR_VMCNT(7) FUPR_VMCNT(8) FUPR_VMCNT(9) FUPR_VMCNT(10) FUPR_VMCNT(11) FUPR_VMCNT(12)
+    FUPR_VMCNT(13) FUPR_VMCNT(14) FUPR_VMCNT(15) FUPR_VMCNT(16) FUPR_VMCNT(17) FUPR_VMCNT(18)
+    FUPR_VMCNT(19) FUPR_VMCNT(20) FUPR_VMCNT(21) FUPR_VMCNT(22) FUPR_VMCNT(23) FUPR_VMCNT(24)
+    FUPR_VMCNT(25) FUPR_VMCNT(26) FUPR_VMCNT(27) FUPR_VMCNT(28) FUPR_VMCNT(29) FUPR_VMCNT(30)
+    FUPR_VMCNT(31) FUPR_VMCNT(32) FUPR_VMCNT(33) FUPR_VMCNT(34) FUPR_VMCNT(35) FUPR_VMCNT(36)
+    FUPR_VMCNT(37) FUPR_VMCNT(38) FUPR_VMCNT(39) FUPR_VMCNT(40) FUPR_VMCNT(41) FUPR_VMCNT(42)
+    FUPR_VMCNT(43) FUPR_VMCNT(44) FUPR_VMCNT(45) FUPR_VMCNT(46) FUPR_VMCNT(47) FUPR_VMCNT(48)
+    default: asm volatile("s_waitcnt vmcnt(48)" ::: "memory"); break;
+  }
+#undef FUPR_VMCNT
+}
+
 constexpr int kLoaderWaves = 4;
 
 // Indexed epilogue: per computing wave, a staging area of 16 pixels x (NT * 16
@@ -132,7 +154,11 @@ __host__ __device__ constexpr int kIxWaveBytes(int NT) { return 16 * (NT * 64 + 
 //
 // IX: the indexed epilogue of a block's last convolution whose output filters
 // were pruned (p.keep); without it p.keep is not read.
-template <bool BF, int WM, int WN, int MT, int NT, bool IX>
+//
+// RING: the small tiles, whose units are shorter than the time their loads take
+// to arrive, keep a ring of p.depth buffers and load up to depth - 1 units ahead;
+// the others use two buffers.
+template <bool BF, int WM, int WN, int MT, int NT, bool IX, bool RING>
 __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kernel(
     const PatchParams p) {
   constexpr int NWC = WM * WN;
@@ -238,17 +264,41 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
     setup_load(l_tile);
     load_patch(0, lds_base + p.patch_base);
     if (++l_stage == p.n_stages) { l_stage = 0; ++l_tile; }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if constexpr (!RING) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      for (int u = 0; u < n_units; ++u) {
+        __syncthreads();   // unit u is in LDS; the computing waves have finished unit u - 1
+        if (u + 1 < n_units) {
+          if (l_stage == 0) setup_load(l_tile);
+          const uint32_t nb = (uint32_t)((u + 1) & 1) * (uint32_t)p.buf_stride;
+          if (!p.w_resident) load_weights(l_stage, lds_base + nb);
+          load_patch(l_stage, lds_base + p.patch_base + nb);
+          if (++l_stage == p.n_stages) { l_stage = 0; ++l_tile; }
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+      }
+      return;
+    }
+    // A ring of p.depth buffers: units u + 1 .. u + depth - 1 are on their way while
+    // unit u is multiplied.  Loads complete in order, so "unit u + 1 has landed" is
+    // "at most the loads of the units after it are outstanding".
+    const int per_unit = (p.w_resident ? 0 : kWeightLoads) + p.n_loads;   // loads per thread
+    int ring = 1 % p.depth;    // buffer of the next unit to issue
+    auto issue = [&]() {
+      if (l_stage == 0) setup_load(l_tile);
+      const uint32_t nb = (uint32_t)ring * (uint32_t)p.buf_stride;
+      if (!p.w_resident) load_weights(l_stage, lds_base + nb);
+      load_patch(l_stage, lds_base + p.patch_base + nb);
+      if (++l_stage == p.n_stages) { l_stage = 0; ++l_tile; }
+      if (++ring == p.depth) ring = 0;
+    };
+    int issued = 1;
+    while (issued < p.depth - 1 && issued < n_units) { issue(); ++issued; }
+    wait_vmcnt((issued - 1) * per_unit);
     for (int u = 0; u < n_units; ++u) {
       __syncthreads();   // unit u is in LDS; the computing waves have finished unit u - 1
-      if (u + 1 < n_units) {
-        if (l_stage == 0) setup_load(l_tile);
-        const uint32_t nb = (uint32_t)((u + 1) & 1) * (uint32_t)p.buf_stride;
-        if (!p.w_resident) load_weights(l_stage, lds_base + nb);
-        load_patch(l_stage, lds_base + p.patch_base + nb);
-        if (++l_stage == p.n_stages) { l_stage = 0; ++l_tile; }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      }
+      if (issued < n_units) { issue(); ++issued; }
+      if (u + 1 < n_units) wait_vmcnt((issued - (u + 2)) * per_unit);
     }
     return;
   }
@@ -310,9 +360,14 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
   const uint32_t floor2 = p.relu ? 0u : 0x80008000u;
 
   int c_tile = t_begin, c_stage = 0;
+  int ring = 0;   // buffer of the unit being multiplied
   for (int u = 0; u < n_units; ++u) {
     __syncthreads();   // unit u is in LDS
-    const int buf = u & 1;
+    int buf = u & 1;
+    if constexpr (RING) {
+      buf = ring;
+      if (++ring == p.depth) ring = 0;
+    }
     if (c_stage == 0) setup_compute(c_tile);
     const bool last = c_stage == p.n_stages - 1;
     if (!IX && last && p.res) {
@@ -585,6 +640,8 @@ struct PatchTile {
   int WM, WN, MT, NT;
   const char* name;
 };
+// Tiles small enough that a unit's arithmetic is shorter than the latency of its loads.
+constexpr bool ring_tile(int NW, int MT, int NT) { return NW * MT * NT <= 16; }
 // pixels x filters per workgroup
 constexpr PatchTile kTiles[] = {
     {4, 1, 4, 4, "conv3x3p_256x64"}, {4, 1, 4, 3, "conv3x3p_256x48"},
@@ -593,8 +650,12 @@ constexpr PatchTile kTiles[] = {
     {2, 2, 7, 2, "conv3x3p_224x64"}, {2, 2, 7, 1, "conv3x3p_224x32"},
     {4, 1, 7, 4, "conv3x3p_448x64"}, {4, 1, 2, 4, "conv3x3p_128x64w"},
     {4, 1, 7, 2, "conv3x3p_448x32"}, {4, 1, 7, 3, "conv3x3p_448x48"},
+    {2, 2, 2, 1, "conv3x3p_64x32"},
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
+// Clocks from issuing a unit's loads to their arrival in LDS (measured on one-image
+// layers, whose 16 dependent units of a 64 x 64 tile take 2250 clocks each).
+constexpr double kLoadLatency = 2250.0;
 
 int num_compute_units() {
   static int cus = [] {
@@ -666,18 +727,29 @@ bool plan_patch(const Conv16Params& c, int N, const PatchTile& tile, PatchPlan* 
   // they fit beside the two patch buffers
   p.w_resident = p.fgroups == 1 &&
                  (size_t)p.n_stages * weight_bytes + 2 * (size_t)patch_bytes <= kPatchLdsLimit;
+  const size_t ix_bytes = p.keep ? (size_t)NW * kIxWaveBytes(tile.NT) : 0;
+  // Estimated clocks of a unit's arithmetic (see below); a unit shorter than the
+  // time its loads take to arrive is worth loading further ahead, LDS permitting.
+  const double mfma = 9.0 * tile.MT * tile.NT * 16.0 * NW / 4.0;
+  const double ldsr = 9.0 * (tile.MT + tile.NT) * NW * 5.4;
+  const int want = !ring_tile(NW, tile.MT, tile.NT) || mfma + ldsr >= kLoadLatency
+                       ? 2 : (mfma + ldsr >= kLoadLatency / 2 ? 3 : 4);
   if (p.w_resident) {
     p.patch_base = p.n_stages * weight_bytes;
     p.buf_stride = patch_bytes;
-    out->lds_bytes = (size_t)p.patch_base + 2 * (size_t)patch_bytes;
+    const int64_t room = (int64_t)kPatchLdsLimit - (int64_t)ix_bytes - p.patch_base;
+    p.depth = (int)std::max<int64_t>(2, std::min<int64_t>(want, room / patch_bytes));
+    out->lds_bytes = (size_t)p.patch_base + (size_t)p.depth * (size_t)patch_bytes;
   } else {
     p.patch_base = weight_bytes;
     p.buf_stride = weight_bytes + patch_bytes;
-    out->lds_bytes = 2 * (size_t)p.buf_stride;
+    const int64_t room = (int64_t)kPatchLdsLimit - (int64_t)ix_bytes;
+    p.depth = (int)std::max<int64_t>(2, std::min<int64_t>(want, room / p.buf_stride));
+    out->lds_bytes = (size_t)p.depth * (size_t)p.buf_stride;
   }
   if (p.keep) {
     p.ix_base = (int)out->lds_bytes;
-    out->lds_bytes += (size_t)NW * kIxWaveBytes(tile.NT);
+    out->lds_bytes += ix_bytes;
   }
   p.divQ = fast_div(c.Q);
   p.divWh = fast_div(p.Wh);
@@ -698,10 +770,8 @@ bool plan_patch(const Conv16Params& c, int N, const PatchTile& tile, PatchPlan* 
   // MFMAs slow both), a 16-byte-per-lane LDS read costs about 5.4 clocks of the
   // LDS port, the loading waves move about 40 bytes per clock, and the
   // epilogue's 8-byte accesses about 16.
-  const double mfma = 9.0 * tile.MT * tile.NT * 16.0 * NW / 4.0;
-  const double ldsr = 9.0 * (tile.MT + tile.NT) * NW * 5.4;
   const double load = (patch_bytes + (p.w_resident ? 0 : weight_bytes)) / 40.0;
-  const double unit = std::max(mfma + ldsr, load) + 150.0;
+  const double unit = std::max({mfma + ldsr, load, kLoadLatency / (p.depth - 1)}) + 150.0;
   const double epi = 500.0 + (double)BM * NF * (c.res ? 4.0 : 2.0) / 16.0;
   const double per_tile = p.n_stages * unit + epi;
   out->cost = 6000.0 + (double)((tiles + out->grid - 1) / out->grid) * per_tile;
@@ -711,15 +781,16 @@ bool plan_patch(const Conv16Params& c, int N, const PatchTile& tile, PatchPlan* 
 
 template <bool BF, int WM, int WN, int MT, int NT, bool IX>
 fupr_status launch_patch_as(const PatchPlan& plan, hipStream_t st) {
+  constexpr bool RING = ring_tile(WM * WN, MT, NT);
   static std::once_flag once;
   static hipError_t status = hipSuccess;
   std::call_once(once, [] {
     status = hipFuncSetAttribute(
-        reinterpret_cast<const void*>(&conv_patch_kernel<BF, WM, WN, MT, NT, IX>),
+        reinterpret_cast<const void*>(&conv_patch_kernel<BF, WM, WN, MT, NT, IX, RING>),
         hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPatchLdsLimit);
   });
   if (status != hipSuccess) return FUPR_ERR_LAUNCH;
-  hipLaunchKernelGGL((conv_patch_kernel<BF, WM, WN, MT, NT, IX>), dim3((unsigned)plan.grid),
+  hipLaunchKernelGGL((conv_patch_kernel<BF, WM, WN, MT, NT, IX, RING>), dim3((unsigned)plan.grid),
                      dim3((WM * WN + kLoaderWaves) * 64), plan.lds_bytes, st, plan.p);
   return launch_status("conv_patch_kernel");
 }
@@ -746,7 +817,8 @@ fupr_status dispatch_patch(int tile, const PatchPlan& plan, hipStream_t st) {
     case 8: return launch_patch<BF, 4, 1, 7, 4>(plan, st);
     case 9: return launch_patch<BF, 4, 1, 2, 4>(plan, st);
     case 10: return launch_patch<BF, 4, 1, 7, 2>(plan, st);
-    default: return launch_patch<BF, 4, 1, 7, 3>(plan, st);
+    case 11: return launch_patch<BF, 4, 1, 7, 3>(plan, st);
+    default: return launch_patch<BF, 2, 2, 2, 1>(plan, st);
   }
 }
 
@@ -787,10 +859,12 @@ bool conv_patch_applies(const Conv16Params& c, int N) {
   const int t = pick_patch(c, N, &plan);
   if (t < 0) return false;
   // Stride 2 needs four input pixels per output pixel in LDS; where that leaves
-  // only tiles under 128 x 64 (56 x 56 inputs), the general kernel, which reads
-  // pixel fragments straight from global memory, was measured faster.
+  // only tiles under 128 x 64 (56 x 56 inputs) and the tiles come in rounds, the
+  // general kernel, which reads pixel fragments straight from global memory, was
+  // measured faster.  A layer of at most one tile per workgroup (one image) is a
+  // chain of dependent units, which this kernel loads further ahead.
   const int area = kTiles[t].WM * kTiles[t].MT * 16 * kTiles[t].WN * kTiles[t].NT * 16;
-  if (c.stride == 2 && area < 128 * 64) return false;
+  if (c.stride == 2 && area < 128 * 64 && plan.p.tiles > plan.grid) return false;
   return true;
 }
 
