@@ -127,6 +127,47 @@ def test_conv_site(fx, case, dtype):
     assert err <= TOL[dtype], (name, dtype, err)
 
 
+@pytest.mark.parametrize("tile", [4, 5, 12], ids=["128x32", "64x64", "64x32"])
+def test_small_tiles_with_several_units_in_flight(fx, tile):
+    """The small tiles of the 3 x 3 kernel load up to three units ahead through a ring
+    of LDS buffers.  The planner picks them for small layers only (one tile per
+    workgroup); forced onto layers with more tiles than compute units, every
+    workgroup walks several tiles and the ring wraps across tile boundaries."""
+    import os
+    B, network, torch = fx
+    cases = [(6, 45, 56, 56, 64, 1, "identity"), (5, 40, 30, 26, 72, 2, None), (7, 100, 28, 28, 33, 1, None)]
+    os.environ["FUPR_PATCH_TILE"] = str(tile)
+    try:
+        for n, c, h, w, k, stride, rkind in cases:
+            rng = np.random.default_rng(1000 * tile + c)
+            x = rng.standard_normal((n, c, h, w)).astype(np.float32)
+            wt = (rng.standard_normal((k, c, 3, 3)) * np.sqrt(2.0 / (c * 9))).astype(np.float32)
+            bias = (rng.standard_normal(k) * 0.1).astype(np.float32)
+            p, q = (h + 2 - 3) // stride + 1, (w + 2 - 3) // stride + 1
+            for dtype in ("bf16", "f16"):
+                dt = B.DTYPES[dtype]
+                ref = orc.conv2d(round_to(x, dtype, torch), round_to(wt, dtype, torch), stride, 1)
+                ref = ref + bias.astype(np.float64)[None, :, None, None]
+                res_arg = None
+                if rkind:
+                    rs = rng.standard_normal((n, k, p, q)).astype(np.float32)
+                    ref = ref + round_to(rs, dtype, torch)
+                    res_arg = (B.DeviceTensor.from_nchw(rs, dt), 1, 0)
+                ref = orc.relu(ref)
+                sh = B.shape_of(wt, stride, 1)
+                packed = B.upload_blob(B.fupr_pack(sh, wt, bias, dt))
+                xd = B.DeviceTensor.from_nchw(x, dt)
+                yd = B.DeviceTensor.empty(n, p, q, k, dt)
+                yd.data.fill_(3.0)
+                B.fupr_conv_fused(sh, xd, packed, res_arg, B.FUSE_RELU | (B.FUSE_ADD if res_arg else 0), yd)
+                torch.cuda.synchronize()
+                err = rel_err(yd.to_nchw(), ref)
+                print(f"tile {tile} C{c} K{k} s{stride} {dtype}: rel err {err:.3e}", flush=True)
+                assert yd.padding_is_zero() and err <= TOL[dtype]
+    finally:
+        del os.environ["FUPR_PATCH_TILE"]
+
+
 def test_identity_weights_copy_input(fx):
     """x = xconv(x, W~) (Sec. IV-B-1): bit-exact on the device, every dtype."""
     B, network, torch = fx
