@@ -558,8 +558,10 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
                   *reinterpret_cast<f32x4*>(scr + li * kRow + (t * 16 + g * 4) * 4) = v;
                 }
                 __builtin_amdgcn_wave_barrier();
+                if (wide) {
 #pragma unroll
-                for (int it = 0; it < kWholeIt; ++it) update_whole(mt, it * 4, oldw[dm][it]);
+                  for (int it = 0; it < kWholeIt; ++it) update_whole(mt, it * 4, oldw[dm][it]);
+                }
 #pragma unroll
                 for (int it = 0; it < kNarrowIt; ++it)
                   if (g + it * 4 < n_narrow) update_narrow(mt, g + it * 4, oldn[dm][it]);
