@@ -180,6 +180,46 @@ __global__ __launch_bounds__(256) void conv16_tiled_kernel(const Conv16Params p,
     __syncthreads();
   }
 
+  if (p.keep) {
+    // Pruned output filters of a block: filter k adds into channel keep[k] of y,
+    // which holds the shortcut; one rounding, 2-byte accesses.  No branch stands
+    // between the loads: a filter that does not exist or points outside y reads
+    // channel 0 and stores nothing.
+    int ch[NT][4];
+    float bs[NT][4];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const int ftile = fgi * (WN * NT) + wn * NT + t;
+      const int k0 = ftile * 16 + g * 4;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const bool exists = ftile < p.FT && k0 + i < p.keep_n;
+        const int c = p.keep[exists ? k0 + i : 0];
+        ch[t][i] = exists && (unsigned)c < (unsigned)p.yC ? c : -1;
+        bs[t][i] = p.bias[exists ? k0 + i : 0];
+      }
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = pb * BMPX + (wm * MT + mt) * 16 + li;
+      uint16_t* yp = p.y + (int64_t)min(m, p.M - 1) * p.ycs;
+      uint16_t old[NT][4];
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) old[t][i] = yp[max(ch[t][i], 0)];
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float v = acc[mt][t][i] + bs[t][i] + to_float<BF>(old[t][i]);
+          if (p.relu) v = fmaxf(v, 0.f);
+          if (m < p.M && ch[t][i] >= 0) yp[ch[t][i]] = from_float<BF>(v);
+        }
+    }
+    return;
+  }
+
   // Epilogue: bias, shortcut, ReLU, one rounding, 8-byte NHWC store.
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
@@ -192,29 +232,6 @@ __global__ __launch_bounds__(256) void conv16_tiled_kernel(const Conv16Params p,
       rp = p.res + (((int64_t)n * p.rH + pp * p.rss) * p.rW + qq * p.rss) * p.rcs;
     }
     uint16_t* yp = p.y + (int64_t)m * p.ycs;
-    if (p.keep) {
-      // pruned output filters of a block: filter k adds into channel keep[k] of y,
-      // which holds the shortcut; one rounding, 2-byte accesses
-#pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        const int ftile = fgi * (WN * NT) + wn * NT + t;
-        const int k0 = ftile * 16 + g * 4;
-        if (ftile >= p.FT) continue;
-        const float4 b4 = *reinterpret_cast<const float4*>(p.bias + k0);
-        const float b[4] = {b4.x, b4.y, b4.z, b4.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          if (k0 + i >= p.keep_n) continue;
-          const int c = p.keep[k0 + i];
-          if ((unsigned)c >= (unsigned)p.yC) continue;
-          float v = acc[mt][t][i] + b[i];
-          v += to_float<BF>(yp[c]);
-          if (p.relu) v = fmaxf(v, 0.f);
-          yp[c] = from_float<BF>(v);
-        }
-      }
-      continue;
-    }
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
       const int ftile = fgi * (WN * NT) + wn * NT + t;
