@@ -108,9 +108,20 @@ def optimise(model, norm=1, aggressive=False, prune_fused=True):
         first = len(layers)
         for ci, (Wf, bf) in enumerate(folded):
             last = ci == len(folded) - 1
+            keep = keeps.get((bi, ci)) if last else None
+            if keep is not None and Wf.shape[2] == 1 and Wf.shape[3] == 1:
+                # A 1 x 1 last convolution is bound by writing the block's full-width output,
+                # which removing filters does not shrink: its removed filters go back in as
+                # zero rows (exact copies of the kept ones, zeros elsewhere), and the layer
+                # runs as an ordinary convolution with the shortcut in its epilogue.
+                k_full = convs[ci]["W"].shape[0]
+                W_full = np.zeros((k_full,) + Wf.shape[1:], dtype=np.float32)
+                b_full = np.zeros(k_full, dtype=np.float32)
+                W_full[keep] = Wf
+                b_full[keep] = bf
+                Wf, bf, keep = W_full, b_full, None
             layers.append(Layer(f"b{bi}.conv{ci + 1}", Wf, bf, convs[ci]["stride"], convs[ci]["pad"],
-                                True, add=last and sc["kind"] != "none",
-                                keep=keeps.get((bi, ci)) if last else None))
+                                True, add=last and sc["kind"] != "none", keep=keep))
         wiring.append(("block", (proj_layer, first, len(folded)), sc))
     head = model["head"]
     if head is not None:
