@@ -590,3 +590,14 @@ def test_xconv_fuse_errors():
     with pytest.raises(B.FuprError) as e:
         B.fupr_xconv_fuse(even, b1, even, b2, B.SHORTCUT_IDENTITY)
     assert e.value.status == B.ERR_SHAPE
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU; asking for more must end with a message, not a run."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr
