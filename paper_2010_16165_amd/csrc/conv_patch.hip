@@ -842,7 +842,10 @@ int pick_patch(const Conv16Params& c, int N, PatchPlan* best) {
       *best = plan;
       return i;
     }
-    if (which < 0 || plan.cost < best->cost) {
+    // equal estimates at stride 2 go to the later tile: there 64 x 64 beats 128 x 32 and the
+    // 4 x 1 arrangement of 128 x 64 beats the 2 x 2 one (measured on the stride-2 layers of the
+    // ResNet-18 / ResNet-50 workloads: 15.4 against 21.0 us, 14.4 against 16.0 us)
+    if (which < 0 || plan.cost < best->cost || (c.stride == 2 && plan.cost <= best->cost)) {
       *best = plan;
       which = i;
     }
@@ -860,13 +863,14 @@ bool conv_patch_applies(const Conv16Params& c, int N) {
   PatchPlan plan;
   const int t = pick_patch(c, N, &plan);
   if (t < 0) return false;
-  // Stride 2 needs four input pixels per output pixel in LDS; where that leaves
-  // only tiles under 128 x 64 (56 x 56 inputs) and the tiles come in rounds, the
-  // general kernel, which reads pixel fragments straight from global memory, was
-  // measured faster.  A layer of at most one tile per workgroup (one image) is a
-  // chain of dependent units, which this kernel loads further ahead.
-  const int area = kTiles[t].WM * kTiles[t].MT * 16 * kTiles[t].WN * kTiles[t].NT * 16;
-  if (c.stride == 2 && area < 128 * 64 && plan.p.tiles > plan.grid) return false;
+  // Stride 2 needs four input pixels per output pixel in LDS, once per filter group, which
+  // leaves small tiles.  Where those come in rounds, the general kernel, which reads pixel
+  // fragments straight from global memory, was measured equal or faster (128 -> 180 channels at
+  // 28 x 28, batch 64: 19.0 against 24.8 us; 256 -> 359 at 14 x 14, batch 256: 50 against 59 us;
+  // at most 4 % slower where the filter count is a multiple of 64).  A single round of tiles
+  // stays here (256 -> 359 at 14 x 14, batch 64: 22 against 31 us), and so does a layer of one
+  // image, a chain of dependent units that this kernel loads further ahead.
+  if (c.stride == 2 && plan.p.tiles > plan.grid) return false;
   return true;
 }
 
