@@ -6,7 +6,7 @@ bench.py reports for its dominant kernel.
 FETCH_DIR / WRITE_DIR hold the CSV output of
 
     rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d FETCH_DIR -o r -- \
-        python3 bench.py --steps 5 --warmup 2 --no-cpu-baseline --copy-calibration 1024
+        python3 bench.py --steps 5 --warmup 2 --no-cpu-baseline --no-measured-peaks --copy-calibration 1024
     rocprofv3 --pmc WRITE_SIZE ... (the same command)
 
 Both counters are in KiB per dispatch.  Each is scaled by what the same counter
