@@ -26,13 +26,19 @@
  *   fupr_conv_maxpool_fused             Table II's ImageNet stem (7 x 7 convolution, stride 2, then
  *                        3 x 3 max pool, stride 2) in one kernel
  *   fupr_model_*, fupr_forward          a whole network (Table II) on one stream
+ *   fupr_block_fused                    a whole bottleneck building block (Table II) in one kernel
  *
  * Conventions
  *   - Host calls (fold, select, prune, pack, model create) take HOST pointers.
  *     Device calls take DEVICE pointers, marked [dev] below.  The library never
- *     allocates or frees device memory and never synchronises a stream unless
- *     a call says so; device work is enqueued on the caller's stream
- *     (a hipStream_t passed as void*, NULL = the default stream).
+ *     allocates, frees or copies device memory, creates no stream, and never
+ *     synchronises a stream unless a call says so; device work is enqueued on
+ *     the caller's stream (a hipStream_t passed as void*, NULL = the default
+ *     stream) and, for fupr_forward only, on streams the caller has lent with
+ *     fupr_model_set_side_streams.  Every device buffer is the caller's: packed
+ *     parameters, the one-kernel schedule's table (fupr_model_table_*), the
+ *     workspace.  The one exception is said where it is declared:
+ *     fupr_forward_static works in a fixed device array inside the library.
  *   - Every call returns FUPR_OK (0) or a negative fupr_status.  On error no
  *     output buffer has been written and nothing has been launched.
  *   - Activations are NHWC.  A tensor of C channels has a channel stride
@@ -42,7 +48,13 @@
  *     that way).  Base pointers are 16-byte aligned.
  *   - Convolutions are cross-correlations with zero padding, square stride and
  *     padding; weights on the host are float32 in K x C x R x S order.
- *   - Calls are re-entrant and thread-safe; they share no mutable state.
+ *   - Calls are re-entrant and thread-safe.  Mutable state they share: (1) the
+ *     tuning switches of fupr_tuning_set, process-wide, read at every launch;
+ *     (2) a model's schedule, table and side streams, set by the
+ *     fupr_model_set_* calls, which must not run concurrently with a forward
+ *     pass of the same model; forward passes of one model that use its side
+ *     streams are serialised with each other while they enqueue (they share the
+ *     fork / join events); (3) the array fupr_forward_static works in.
  */
 #ifndef FUPR_H
 #define FUPR_H
@@ -233,7 +245,8 @@ typedef struct {
 /*
  * y[n,p,q,k] = act( b_k + sum_{r,s,c} x[n, p*stride+r-pad, q*stride+s-pad, c] W[k,c,r,s] (+ res) )
  * (Sec. III; Sec. IV-B-1), accumulated in fp32; the residual is converted to
- * fp32 and added after the bias; act is ReLU with FUPR_FUSE_RELU, else the
+ * fp32 and added after the bias (this call; the one-kernel schedule of
+ * fupr_forward orders the sum differently, see fupr_model_set_schedule); act is ReLU with FUPR_FUSE_RELU, else the
  * identity; one rounding to y's type at the end.  FUPR_FUSE_ADD requires res.
  * packed is [dev] the blob written by fupr_pack for the same shape and dtype.
  * x, y (and res) share one dtype; y->ptr is written, including its zero
@@ -356,13 +369,59 @@ void fupr_model_destroy(fupr_model* m);
 /*
  * How fupr_forward schedules the network.  AUTO (default): if every activation
  * tensor of one image fits in the compute unit's LDS (CIFAR-size networks of
- * Table II), the whole network runs as ONE kernel, one workgroup per image,
- * activations never leaving LDS; otherwise one kernel per operator.
- * PER_LAYER: always one kernel per operator.  Both schedules compute the same
- * arithmetic in the same order and give bit-identical results.
+ * Table II) and the caller has provided the table below, the whole network runs
+ * as ONE kernel, one workgroup per image, activations never leaving LDS;
+ * otherwise one kernel per launch group (an operator, or operators that have a
+ * kernel together: stem convolution + max-pool, two 1 x 1 convolutions, a
+ * bottleneck block).  PER_LAYER: always one kernel per operator.
+ * The schedules compute the same operators but round differently: the
+ * one-kernel schedule starts the fp32 accumulator from the bias and adds the
+ * shortcut as one more MFMA step (before, not after, the last products), and the
+ * fused launch groups sum inside a 32-channel step in another order.  Results
+ * agree within the rounding of the storage type, not bit for bit.  The
+ * one-kernel schedule also assumes FINITE activations: a shortcut value of
+ * +-Inf turns all 16 filters of its tile at that pixel into NaN (0 x Inf), where
+ * the per-operator kernels keep the other filters finite.
+ * The one-kernel schedule is taken only when input->c_stride is the minimal one
+ * (C rounded up to 8) and output->c_stride is at most the last operator's padded
+ * width; other strides run one kernel per operator.
  */
 enum { FUPR_SCHEDULE_AUTO = 0, FUPR_SCHEDULE_PER_LAYER = 1 };
 fupr_status fupr_model_set_schedule(fupr_model* m, int32_t schedule);
+
+/*
+ * The table the one-kernel schedule walks (per layer: LDS offsets, strides, work
+ * item shape, tap offsets).  It lives in device memory that the CALLER provides,
+ * like packed parameters:
+ *   fupr_model_table_bytes  its size; 0 when the network does not qualify for the
+ *                           one-kernel schedule (or m is NULL).
+ *   fupr_model_table_write  writes its image to host_out (that many bytes) as it
+ *                           must appear at the 256-byte aligned [dev] address
+ *                           dev_table (the image holds addresses inside itself and
+ *                           the operators' `packed` addresses); the caller copies
+ *                           it there.
+ *   fupr_model_set_table    tells the model where the copy is; it must stay
+ *                           valid and unchanged while the model is used.  NULL
+ *                           takes it away again.  Without a table AUTO runs one
+ *                           kernel per launch group.
+ * Errors: NULL, ALIGN, ARG (the network has no such table).
+ */
+size_t fupr_model_table_bytes(const fupr_model* m);
+fupr_status fupr_model_table_write(const fupr_model* m, const void* dev_table, void* host_out);
+fupr_status fupr_model_set_table(fupr_model* m, const void* dev_table);
+
+/*
+ * Streams the per-operator schedule may use beside the caller's stream: batches
+ * of 192 images or more then run as two sub-batches side by side (images are
+ * independent; each sub-batch owns its slice of every workspace buffer), forked
+ * from and joined to the stream passed to fupr_forward by events, so that the
+ * call stays asynchronous, ordered on that stream, and capturable.  n = 0 .. 3
+ * non-NULL hipStream_t of default priority, owned by the caller, alive until the
+ * model is destroyed or the streams are replaced; n = 0 (the default) keeps
+ * every launch on the caller's stream.  The library creates events here, never
+ * streams.  Errors: NULL, ARG (n out of range), LAUNCH.
+ */
+fupr_status fupr_model_set_side_streams(fupr_model* m, int32_t n, void* const* streams);
 
 /* Bytes of [dev] workspace fupr_forward needs for a batch (0 if m is NULL or batch <= 0). */
 size_t fupr_model_workspace_bytes(const fupr_model* m, int32_t batch);
@@ -374,7 +433,11 @@ fupr_status fupr_model_output_shape(const fupr_model* m, int32_t batch, fupr_ten
  * Runs the network on input (batch = input->N) and writes the last operator's
  * result into output->ptr.  workspace is [dev], 256-byte aligned, at least
  * fupr_model_workspace_bytes(m, batch) bytes, and is only used until the
- * enqueued work completes.  Asynchronous; safe to capture in a HIP graph.
+ * enqueued work completes.  Asynchronous; creates nothing and allocates nothing,
+ * so it is safe to capture in a HIP graph (with side streams: capture mode
+ * thread-local or relaxed, and `stream` not the default stream).  If a launch
+ * fails after sub-batches were forked, the side streams are still joined to
+ * `stream` before the error is returned.
  * Errors: NULL, SHAPE, DTYPE, ALIGN, WORKSPACE, LIMIT, LAUNCH.
  */
 fupr_status fupr_forward(const fupr_model* m, const fupr_tensor* input, const fupr_tensor* output,
@@ -430,23 +493,25 @@ fupr_status fupr_graph_create(const fupr_model* m, const fupr_tensor* input,
 fupr_status fupr_graph_launch(const fupr_graph* g, void* stream);
 void fupr_graph_destroy(fupr_graph* g);
 
-/* ------------------------------------------------------- measuring aids -- */
+/* --------------------------------------------------------------- tuning -- */
 
 /*
- * Kernels of known work and nothing else, for the roofline figures reported
- * beside the published peaks (they are not part of the method).
- * fupr_measure_mfma: `workgroups` workgroups of 4 waves, each wave issuing
- * iters * 8 MFMAs 16 x 16 x 32 of type dt (FUPR_BF16 / FUPR_F16) on registers only;
- * out [dev] receives workgroups * 256 floats (so that the work cannot be dropped);
- * *flops [host] receives the number of floating-point operations enqueued.
- * fupr_measure_copy: dst[0..bytes) = src[0..bytes), 16 bytes per lane; bytes a
- * multiple of 16, both pointers [dev] 16-byte aligned, not overlapping.
- * Asynchronous on `stream`; the caller times them.  Errors: NULL, DTYPE, ARG, SHAPE,
- * ALIGN, LAUNCH.
+ * Process-wide switches that select among kernel instantiations or schedules
+ * computing the same operators (for tests and sweeps; normal use needs none).
+ * Each starts from the environment variable FUPR_<NAME IN CAPITALS>, read once
+ * when the first switch is looked up, and changes only through this call; value
+ * NULL or "" returns a switch to automatic.  Launchers read them at every launch.
+ *   patch_tile, pipe_tile, stream_tile, block_tile = <index>
+ *                                                 force a tile of that kernel family (where it fits)
+ *   conv_tile = <tile name>                       force a tile of the general kernel
+ *   conv_patch, conv1x1_stream, conv1x1_pipe, conv1x1_fuse, block_fuse = 0
+ *                                                 leave that kernel family out
+ *   split = 1..4                                  sub-batches of the per-operator schedule
+ *   res_item = "M/FT/nsteps:MTxNT,..."            work-item shapes of the one-kernel schedule
+ *   debug = 1                                     planner decisions and HIP error text on stderr
+ * Errors: NULL, ARG (unknown name, value of 128 characters or more).
  */
-fupr_status fupr_measure_mfma(int32_t dt, int32_t iters, int32_t workgroups, void* out,
-                              double* flops, void* stream);
-fupr_status fupr_measure_copy(const void* src, void* dst, size_t bytes, void* stream);
+fupr_status fupr_tuning_set(const char* name, const char* value);
 
 #ifdef __cplusplus
 }

@@ -354,10 +354,14 @@ def aggressive_fuse_block(blk):
             "shortcut": {"kind": "none"}}
 
 
-def aggressive_fuse(model):
-    """The model with every basic block rewritten by aggressive_fuse_block."""
+def aggressive_fuse(model, stages=None):
+    """The model with its basic blocks rewritten by aggressive_fuse_block.
+
+    stages: the fusion option x of "x/n" (Sec. V, optimization setting): only the
+    blocks of the first x stages are fused, in order; None fuses every stage."""
     out = dict(model)
-    out["blocks"] = [aggressive_fuse_block(b) if b["kind"] == "basic" else b
+    out["blocks"] = [aggressive_fuse_block(b)
+                     if b["kind"] == "basic" and (stages is None or b.get("stage", 0) < stages) else b
                      for b in model["blocks"]]
     return out
 

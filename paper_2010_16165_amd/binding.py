@@ -125,13 +125,15 @@ SIGNATURES = {
     "fupr_model_num_launches": (C.c_int32, [C.c_void_p]),
     "fupr_model_launch_stats": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(OpStats)]),
     "fupr_model_set_schedule": (C.c_int32, [C.c_void_p, C.c_int32]),
+    "fupr_model_table_bytes": (C.c_size_t, [C.c_void_p]),
+    "fupr_model_table_write": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_void_p]),
+    "fupr_model_set_table": (C.c_int32, [C.c_void_p, C.c_void_p]),
+    "fupr_model_set_side_streams": (C.c_int32, [C.c_void_p, C.c_int32, C.POINTER(C.c_void_p)]),
     "fupr_graph_create": (C.c_int32, [C.c_void_p, _T, _T, C.c_void_p, C.c_size_t, C.c_void_p,
                                       C.POINTER(C.c_void_p)]),
     "fupr_graph_launch": (C.c_int32, [C.c_void_p, C.c_void_p]),
     "fupr_graph_destroy": (None, [C.c_void_p]),
-    "fupr_measure_mfma": (C.c_int32, [C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
-                                      C.POINTER(C.c_double), C.c_void_p]),
-    "fupr_measure_copy": (C.c_int32, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "fupr_tuning_set": (C.c_int32, [C.c_char_p, C.c_char_p]),
 }
 for _name, (_res, _args) in SIGNATURES.items():
     _fn = getattr(_lib, _name)
@@ -407,20 +409,10 @@ def fupr_global_avgpool(x, y, stream=None):
     _check(st, "fupr_global_avgpool")
 
 
-def fupr_measure_mfma(dt, iters, workgroups, out, stream=None):
-    """out: torch float32 CUDA tensor of workgroups * 256 elements.  Returns the flops enqueued."""
-    flops = C.c_double(0.0)
-    st = _lib.fupr_measure_mfma(int(dt), int(iters), int(workgroups), C.c_void_p(out.data_ptr()),
-                                C.byref(flops), stream if stream is not None else current_stream())
-    _check(st, "fupr_measure_mfma")
-    return flops.value
-
-
-def fupr_measure_copy(src, dst, nbytes, stream=None):
-    """src, dst: torch CUDA tensors of at least nbytes bytes."""
-    st = _lib.fupr_measure_copy(C.c_void_p(src.data_ptr()), C.c_void_p(dst.data_ptr()), int(nbytes),
-                                stream if stream is not None else current_stream())
-    _check(st, "fupr_measure_copy")
+def fupr_tuning_set(name, value):
+    """value: None (back to automatic), or anything str() turns into the switch's text."""
+    v = None if value is None else str(value).encode()
+    _check(_lib.fupr_tuning_set(name.encode(), v), "fupr_tuning_set")
 
 
 # ---- model ----------------------------------------------------------------------
@@ -428,7 +420,7 @@ def fupr_measure_copy(src, dst, nbytes, stream=None):
 class Model:
     """Owns a fupr_model and the device blobs its operators point into."""
 
-    def __init__(self, dt, in_shape, ops, keepalive):
+    def __init__(self, dt, in_shape, ops, keepalive, device="cuda:0", side_streams=3):
         self.dt = int(dt)
         self.in_shape = tuple(in_shape)
         self._keepalive = keepalive
@@ -439,6 +431,25 @@ class Model:
         _check(st, "fupr_model_create")
         self._h = h
         self._graphs = []
+        # device buffers and streams are the caller's: the one-kernel schedule's table
+        # is uploaded here, and the per-operator schedule is lent side streams
+        nbytes = int(_lib.fupr_model_table_bytes(self._h))
+        torch = _torch()
+        if nbytes and torch.cuda.is_available():
+            dev = torch.empty(nbytes, dtype=torch.uint8, device=device)
+            assert dev.data_ptr() % 256 == 0
+            host = np.empty(nbytes, dtype=np.uint8)
+            _check(_lib.fupr_model_table_write(self._h, C.c_void_p(dev.data_ptr()),
+                                               host.ctypes.data_as(C.c_void_p)),
+                   "fupr_model_table_write")
+            dev.copy_(torch.from_numpy(host))
+            torch.cuda.synchronize()
+            _check(_lib.fupr_model_set_table(self._h, C.c_void_p(dev.data_ptr())),
+                   "fupr_model_set_table")
+            self._keepalive = list(self._keepalive) + [dev]
+        self._side = []
+        if side_streams and torch.cuda.is_available():
+            self.set_side_streams([torch.cuda.Stream(device=device) for _ in range(side_streams)])
 
     def __del__(self):
         try:
@@ -465,6 +476,13 @@ class Model:
     @property
     def num_launches(self):
         return int(_lib.fupr_model_num_launches(self._h))
+
+    def set_side_streams(self, streams):
+        """torch.cuda.Stream objects the per-operator schedule may fork sub-batches onto."""
+        arr = (C.c_void_p * max(len(streams), 1))(*[s.cuda_stream for s in streams])
+        _check(_lib.fupr_model_set_side_streams(self._h, len(streams), arr),
+               "fupr_model_set_side_streams")
+        self._side = list(streams)
 
     def set_schedule(self, schedule):
         _check(_lib.fupr_model_set_schedule(self._h, int(schedule)), "fupr_model_set_schedule")

@@ -27,6 +27,7 @@
 #include "device_utils.h"
 #include "fupr.h"
 #include "layout.h"
+#include "tuning.h"
 
 namespace fupr {
 namespace {
@@ -334,16 +335,17 @@ size_t stream_lds_bytes(const StreamTile& t, int ksteps) {
 
 // The widest filter group whose filters fit; -1: the layer is not for this kernel.
 int pick_stream(const Conv16Params& c) {
-  if (const char* e = std::getenv("FUPR_CONV1X1_STREAM"))
-    if (e[0] == '0') return -1;
+  if (tuning_off("conv1x1_stream")) return -1;
   if (c.S != 1 || c.nchunk != c.cpt || c.pad != 0 || (c.stride != 1 && c.stride != 2)) return -1;
   if (c.roff % 8 != 0) return -1;   // 16-byte shortcut loads
   const int ksteps = (c.cpt + 3) / 4;
+  const int forced = tuning_int("stream_tile", -1);   // taken if the layer fits it
   int best = -1;
   double best_cost = 1e30;
   for (int i = 0; i < kNumStreamTiles; ++i) {
     const StreamTile& t = kStreamTiles[i];
     if (ksteps > t.KMAX || stream_lds_bytes(t, ksteps) > (size_t)kStreamLdsLimit) continue;
+    if (i == forced) return i;
     // padded filter tiles, and the input is read once per group
     const int groups = (c.FT + t.NT - 1) / t.NT;
     const double cost = (double)groups * t.NT * 32.0 + (double)groups * c.cpt * 16.0 +
@@ -418,8 +420,7 @@ bool fill_stream_params(const Conv16Params& c, int N, StreamParams* out) {
 // Which 16-tile variant (2 or 4 steps) and how many second-layer filter tiles a
 // fused pair needs; false if the pair is not for the fused kernel.
 bool plan_fused(const Conv16Params& c1, const Conv16Params& c2, int* kmax, int* nt2, size_t* lds) {
-  if (const char* e = std::getenv("FUPR_CONV1X1_FUSE"))
-    if (e[0] == '0') return false;
+  if (tuning_off("conv1x1_fuse")) return false;
   const int t = pick_stream(c1);
   if (t < 0 || kStreamTiles[t].NT != 16 || c1.FT > 16 || c1.stride != 1) return false;
   if (c2.S != 1 || c2.nchunk != c2.cpt || c2.pad != 0 || c2.stride != 1 || c2.res) return false;

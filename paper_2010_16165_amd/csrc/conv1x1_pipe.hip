@@ -25,6 +25,7 @@
 #include "device_utils.h"
 #include "fupr.h"
 #include "layout.h"
+#include "tuning.h"
 
 namespace fupr {
 namespace {
@@ -365,15 +366,13 @@ struct PipePlan {
   int grid;
 };
 
-// The tile with the least estimated time; FUPR_PIPE_TILE=<index> forces one.
+// The tile with the least estimated time; the tuning switch pipe_tile=<index> forces one.
 bool plan_pipe(const Conv16Params& c, PipePlan* out) {
-  if (const char* e = std::getenv("FUPR_CONV1X1_PIPE"))
-    if (e[0] == '0') return false;
+  if (tuning_off("conv1x1_pipe")) return false;
   if (c.S != 1 || c.nchunk != c.cpt || c.pad != 0 || (c.stride != 1 && c.stride != 2)) return false;
   if (c.roff % 8 != 0) return false;
   if (c.cpt < 16) return false;   // fewer than 128 channels: one unit, nothing to pipeline
-  int forced = -1;
-  if (const char* e = std::getenv("FUPR_PIPE_TILE")) forced = std::atoi(e);
+  const int forced = tuning_int("pipe_tile", -1);
   const int cus = pipe_compute_units();
   double best = 1e30;
   bool found = false;

@@ -47,6 +47,7 @@
 #include "device_utils.h"
 #include "fupr.h"
 #include "layout.h"
+#include "tuning.h"
 
 namespace fupr {
 namespace {
@@ -825,15 +826,13 @@ fupr_status dispatch_patch(int tile, const PatchPlan& plan, hipStream_t st) {
 }
 
 bool patch_disabled() {
-  const char* e = std::getenv("FUPR_CONV_PATCH");
-  return e && e[0] == '0';
+  return tuning_off("conv_patch");
 }
 
-// The tile with the least estimated time; FUPR_PATCH_TILE=<index> forces one
+// The tile with the least estimated time; the tuning switch patch_tile=<index> forces one
 // (tuning aid).  -1: none fits.
 int pick_patch(const Conv16Params& c, int N, PatchPlan* best) {
-  int forced = -1;
-  if (const char* e = std::getenv("FUPR_PATCH_TILE")) forced = std::atoi(e);
+  const int forced = tuning_int("patch_tile", -1);
   int which = -1;
   for (int i = 0; i < kNumTiles; ++i) {
     PatchPlan plan;

@@ -29,6 +29,7 @@
 #include "conv16.h"
 #include "device_utils.h"
 #include "layout.h"
+#include "tuning.h"
 
 namespace fupr {
 namespace {
@@ -279,11 +280,11 @@ constexpr TileCfg kTiles[] = {
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 constexpr int kStageSteps = 4;
 
-// FUPR_CONV_TILE=<tile name> in the environment forces one tile for every layer
-// (read at each launch; a tuning aid for sweeps, not needed in normal use).
+// The tuning switch conv_tile=<tile name> forces one tile for every layer (an
+// aid for tests and sweeps, not needed in normal use).
 int forced_tile() {
-  const char* e = getenv("FUPR_CONV_TILE");
-  if (!e) return -1;
+  char e[64];
+  if (!tuning_text("conv_tile", e, sizeof(e))) return -1;
   for (int i = 0; i < kNumTiles; ++i)
     if (strcmp(e, kTiles[i].name) == 0) return i;
   return -1;

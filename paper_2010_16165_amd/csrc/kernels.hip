@@ -9,6 +9,7 @@
 
 #include "fupr.h"
 #include "layout.h"
+#include "tuning.h"
 #include "stem_pool.h"
 #include "device_utils.h"
 #include "conv16.h"
@@ -224,7 +225,7 @@ __global__ __launch_bounds__(256) void avgpool_kernel(const PoolParams p) {
 fupr_status launch_status(const char* what) {
   const hipError_t e = hipGetLastError();
   if (e == hipSuccess) return FUPR_OK;
-  if (getenv("FUPR_DEBUG")) fprintf(stderr, "fupr: %s: %s\n", what, hipGetErrorString(e));
+  if (tuning_int("debug", 0)) fprintf(stderr, "fupr: %s: %s\n", what, hipGetErrorString(e));
   return FUPR_ERR_LAUNCH;
 }
 

@@ -14,6 +14,7 @@
 #include "fupr.h"
 #include "layout.h"
 #include "stem_pool.h"
+#include "tuning.h"
 
 using namespace fupr;
 
@@ -40,15 +41,15 @@ struct fupr_model {
   std::vector<ResLayer> res_layers;       // host copy of the layer table
   std::vector<int32_t> res_tables;        // tap tables of all layers, back to back
   std::vector<size_t> res_table_at;       // first entry of each layer's table
-  void* res_dev = nullptr;                // device copy: layer table, then tap tables
-  std::mutex res_mutex;
-  // Per-operator schedule: the batch runs as kSplit sub-batches on streams of
-  // their own that fork from and join the caller's stream, so that one
-  // sub-batch's launch gaps, prologues and tails are filled by the other's work.
-  bool side_ready = false;
+  const void* res_dev = nullptr;          // the caller's device copy of the table (fupr_model_set_table)
+  // Per-operator schedule: the batch runs as sub-batches on streams the caller
+  // lends (fupr_model_set_side_streams) that fork from and join the caller's
+  // stream, so that one sub-batch's launch gaps, prologues and tails are filled
+  // by the other's work.
+  int n_side = 0;
   hipStream_t side_stream[kMaxSplit - 1] = {};
   hipEvent_t fork_event = nullptr, join_event[kMaxSplit - 1] = {};
-  std::mutex side_mutex;                  // one forked enqueue at a time
+  std::mutex side_mutex;                  // one forked enqueue at a time: the events are shared
 };
 
 struct fupr_graph {
@@ -66,11 +67,12 @@ namespace {
 // accumulator and every MFMA waits for the one before), and vector
 // instructions beside them (about 2.7 clocks each).  Items go round robin
 // over 16 waves, hence over the 4 SIMDs.
-// FUPR_RES_ITEM="M/FT/nsteps:MTxNT,..." overrides the choice per layer class
-// (a tuning aid).
+// The tuning switch res_item="M/FT/nsteps:MTxNT,..." overrides the choice per
+// layer class (an aid for sweeps).
 void resident_item_shape(int M, int FT, int nsteps, bool has_res, int* MT_out, int* NT_out) {
   static const int shapes[5][2] = {{4, 1}, {2, 2}, {2, 1}, {1, 2}, {1, 1}};
-  if (const char* env = std::getenv("FUPR_RES_ITEM")) {
+  char env[128];
+  if (tuning_text("res_item", env, sizeof(env))) {
     const char* c = env;
     while (*c) {
       int em = 0, ef = 0, es = 0, mt = 0, nt = 0, used = 0;
@@ -316,7 +318,7 @@ void plan_resident(fupr_model* m) {
     }
     if (!ok) return;
     const size_t extent = assign_offsets(blocks);
-    if (std::getenv("FUPR_DEBUG")) {
+    if (tuning_int("debug", 0)) {
       std::fprintf(stderr, "resident candidate: strides");
       for (int c = 0; c < k; ++c)
         std::fprintf(stderr, " %dx%d:%d", classes[c].H, classes[c].W,
@@ -492,14 +494,14 @@ void plan_resident(fupr_model* m) {
         mark(blocks[n + 2 + i].offset, blocks[n + 2 + i].units, 0);
       m->res_layers.push_back(L);
       m->res_table_at.push_back(table_at);
-      if (std::getenv("FUPR_DEBUG"))
+      if (tuning_int("debug", 0))
         std::fprintf(stderr, "resident layer %d: M %d FT %d steps %d item %dx%d items %d ps2 in %d out %d "
                      "zero_halo %d res %d\n", i, L.M, L.FT, L.nsteps, L.MT, L.NT, L.n_items, ps2[op.in],
                      ps2[i + 1], (L.flags & kResZeroHalo) != 0, L.res_org >= 0);
     }
     if (m->res_layers.size() > (size_t)kResMaxLayers) return;
     R.n_layers = (int)m->res_layers.size();
-    if (std::getenv("FUPR_DEBUG"))
+    if (tuning_int("debug", 0))
       std::fprintf(stderr, "resident plan: %d bytes of LDS, %d table entries for %d layers\n",
                    R.lds_bytes, R.n_layers, n);
     m->resident_ok = true;
@@ -511,49 +513,12 @@ void plan_resident(fupr_model* m) {
 void release_side(fupr_model* m);   // below, with the forked schedule
 bool conv_conv_pair(const fupr_model* m, size_t i);   // below, with the launch list
 
-void release_resident(fupr_model* m) {
-  if (m->res_dev) (void)hipFree(m->res_dev);
-  m->res_dev = nullptr;
+// Sizes of the one-kernel schedule's table: the layer entries, then the tap tables.
+size_t resident_layer_bytes(const fupr_model* m) {
+  return round_up_sz(m->res_layers.size() * sizeof(ResLayer), 256);
 }
-
-// Copies the layer table and the tap tables to the device (once).  Returns
-// false when there is no device to copy to.
-bool upload_resident(const fupr_model* cm) {
-  fupr_model* m = const_cast<fupr_model*>(cm);
-  std::lock_guard<std::mutex> lock(m->res_mutex);
-  if (m->res_dev) return true;
-  const size_t n = m->res_layers.size();
-  const size_t layer_bytes = round_up_sz(n * sizeof(ResLayer), 256);
-  const size_t table_bytes = round_up_sz(m->res_tables.size() * sizeof(int32_t), 256) + 256;
-  void* dev = nullptr;
-  if (hipMalloc(&dev, layer_bytes + table_bytes) != hipSuccess) {
-    (void)hipGetLastError();
-    return false;
-  }
-  char* base = reinterpret_cast<char*>(dev);
-  std::vector<ResLayer> layers = m->res_layers;
-  for (size_t i = 0; i < n; ++i)
-    layers[i].table = base + layer_bytes + m->res_table_at[i] * sizeof(int32_t);
-  for (size_t i = 0; i + 1 < n; ++i) {
-    layers[i].next_packed = layers[i + 1].packed;
-    layers[i].next_table = layers[i + 1].table;
-    layers[i].next_blob_units = layers[i + 1].blob_units;
-    layers[i].next_tab_units = layers[i + 1].tab_units;
-    layers[i].next_w_off = layers[i + 1].w_off;
-    layers[i].next_tab_off = layers[i + 1].tab_off;
-  }
-  bool ok = hipMemcpy(base, layers.data(), n * sizeof(ResLayer), hipMemcpyHostToDevice) == hipSuccess;
-  if (ok && !m->res_tables.empty())
-    ok = hipMemcpy(base + layer_bytes, m->res_tables.data(), m->res_tables.size() * sizeof(int32_t),
-                   hipMemcpyHostToDevice) == hipSuccess;
-  if (!ok) {
-    (void)hipGetLastError();
-    (void)hipFree(dev);
-    return false;
-  }
-  m->res_dev = dev;
-  m->resident.layers = reinterpret_cast<const ResLayer*>(dev);
-  return true;
+size_t resident_table_bytes(const fupr_model* m) {
+  return round_up_sz(m->res_tables.size() * sizeof(int32_t), 256) + 256;
 }
 
 }  // namespace
@@ -709,7 +674,6 @@ extern "C" fupr_status fupr_model_create(const fupr_graph_desc* g, fupr_model** 
     }
   }
   plan_resident(m);
-  if (m->resident_ok) (void)upload_resident(m);   // retried at the first forward pass if no device yet
   *out = m;
   return FUPR_OK;
 }
@@ -721,9 +685,71 @@ extern "C" fupr_status fupr_model_set_schedule(fupr_model* m, int32_t schedule) 
   return FUPR_OK;
 }
 
+extern "C" size_t fupr_model_table_bytes(const fupr_model* m) {
+  if (!m || !m->resident_ok) return 0;
+  return resident_layer_bytes(m) + resident_table_bytes(m);
+}
+
+extern "C" fupr_status fupr_model_table_write(const fupr_model* m, const void* dev_table,
+                                              void* host_out) {
+  if (!m || !dev_table || !host_out) return FUPR_ERR_NULL;
+  if (!m->resident_ok) return FUPR_ERR_ARG;
+  if ((reinterpret_cast<uintptr_t>(dev_table) & 255u) != 0) return FUPR_ERR_ALIGN;
+  const size_t n = m->res_layers.size();
+  const size_t layer_bytes = resident_layer_bytes(m);
+  const char* base = reinterpret_cast<const char*>(dev_table);
+  std::vector<ResLayer> layers = m->res_layers;
+  for (size_t i = 0; i < n; ++i)
+    layers[i].table = base + layer_bytes + m->res_table_at[i] * sizeof(int32_t);
+  for (size_t i = 0; i + 1 < n; ++i) {
+    layers[i].next_packed = layers[i + 1].packed;
+    layers[i].next_table = layers[i + 1].table;
+    layers[i].next_blob_units = layers[i + 1].blob_units;
+    layers[i].next_tab_units = layers[i + 1].tab_units;
+    layers[i].next_w_off = layers[i + 1].w_off;
+    layers[i].next_tab_off = layers[i + 1].tab_off;
+  }
+  char* out = reinterpret_cast<char*>(host_out);
+  std::fill(out, out + layer_bytes + resident_table_bytes(m), 0);
+  std::copy(reinterpret_cast<const char*>(layers.data()),
+            reinterpret_cast<const char*>(layers.data()) + n * sizeof(ResLayer), out);
+  std::copy(reinterpret_cast<const char*>(m->res_tables.data()),
+            reinterpret_cast<const char*>(m->res_tables.data()) + m->res_tables.size() * sizeof(int32_t),
+            out + layer_bytes);
+  return FUPR_OK;
+}
+
+extern "C" fupr_status fupr_model_set_table(fupr_model* m, const void* dev_table) {
+  if (!m) return FUPR_ERR_NULL;
+  if (dev_table && !m->resident_ok) return FUPR_ERR_ARG;
+  if ((reinterpret_cast<uintptr_t>(dev_table) & 255u) != 0) return FUPR_ERR_ALIGN;
+  m->res_dev = dev_table;
+  return FUPR_OK;
+}
+
+extern "C" fupr_status fupr_model_set_side_streams(fupr_model* m, int32_t n, void* const* streams) {
+  if (!m || (n > 0 && !streams)) return FUPR_ERR_NULL;
+  if (n < 0 || n > kMaxSplit - 1) return FUPR_ERR_ARG;
+  for (int k = 0; k < n; ++k)
+    if (!streams[k]) return FUPR_ERR_NULL;   // the default stream cannot be forked into a capture
+  std::lock_guard<std::mutex> lock(m->side_mutex);
+  release_side(m);
+  if (n == 0) return FUPR_OK;
+  bool ok = hipEventCreateWithFlags(&m->fork_event, hipEventDisableTiming) == hipSuccess;
+  for (int k = 0; ok && k < n; ++k)
+    ok = hipEventCreateWithFlags(&m->join_event[k], hipEventDisableTiming) == hipSuccess;
+  if (!ok) {
+    (void)hipGetLastError();
+    release_side(m);
+    return FUPR_ERR_LAUNCH;
+  }
+  for (int k = 0; k < n; ++k) m->side_stream[k] = reinterpret_cast<hipStream_t>(streams[k]);
+  m->n_side = n;
+  return FUPR_OK;
+}
+
 extern "C" void fupr_model_destroy(fupr_model* m) {
   if (!m) return;
-  release_resident(m);
   release_side(m);
   delete m;
 }
@@ -758,7 +784,7 @@ namespace {
 // asked for per-layer kernels, and the caller's tensors have the strides the
 // plan assumed.
 bool use_resident(const fupr_model* m, const fupr_tensor* input, const fupr_tensor* output) {
-  if (!m->resident_ok || m->schedule != FUPR_SCHEDULE_AUTO) return false;
+  if (!m->resident_ok || !m->res_dev || m->schedule != FUPR_SCHEDULE_AUTO) return false;
   if (input->c_stride != m->tensors.front().cs) return false;
   const fupr_op_desc& last = m->ops.back();
   const int limit = last.kind == FUPR_OP_CONV ? round_up(last.conv.K, 16) : m->tensors[last.in].cs;
@@ -812,38 +838,23 @@ std::vector<Launch> launches_of(const fupr_model* m) {
 // Sub-batches of the per-operator schedule.  Measured on the ImageNet-size
 // workloads: two sub-batches of 128 images gain 6 %, sub-batches of 32 lose 11 %
 // (their kernels no longer fill the compute units), more than two never pay;
-// so two from 192 images on, else one.  FUPR_SPLIT=<1..4> forces a count.
-int split_count(int N) {
-  const char* e = getenv("FUPR_SPLIT");   // read at every call: a tuning and testing aid
-  const int forced = e ? std::min(std::max(atoi(e), 1), kMaxSplit) : 0;
-  if (forced) return std::min(forced, std::max(N / 8, 1));
-  return N >= 192 ? 2 : 1;
-}
-
-// Streams and events of the forked schedule; created outside any stream capture.
-bool ensure_side(const fupr_model* cm) {
-  fupr_model* m = const_cast<fupr_model*>(cm);
-  std::lock_guard<std::mutex> lock(m->res_mutex);
-  if (m->side_ready) return true;
-  bool ok = hipEventCreateWithFlags(&m->fork_event, hipEventDisableTiming) == hipSuccess;
-  for (int k = 0; ok && k < kMaxSplit - 1; ++k) {
-    ok = hipStreamCreateWithFlags(&m->side_stream[k], hipStreamNonBlocking) == hipSuccess &&
-         hipEventCreateWithFlags(&m->join_event[k], hipEventDisableTiming) == hipSuccess;
-  }
-  if (!ok) {
-    (void)hipGetLastError();
-    return false;
-  }
-  m->side_ready = true;
-  return true;
+// so two from 192 images on, else one, and never more than the caller has lent
+// streams for.  The tuning switch split=<1..4> forces a count.
+int split_count(const fupr_model* m, int N) {
+  const int forced = std::min(std::max(tuning_int("split", 0), 0), kMaxSplit);
+  const int want = forced ? std::min(forced, std::max(N / 8, 1)) : (N >= 192 ? 2 : 1);
+  return std::min(want, m->n_side + 1);
 }
 
 void release_side(fupr_model* m) {
   if (m->fork_event) (void)hipEventDestroy(m->fork_event);
+  m->fork_event = nullptr;
   for (int k = 0; k < kMaxSplit - 1; ++k) {
     if (m->join_event[k]) (void)hipEventDestroy(m->join_event[k]);
-    if (m->side_stream[k]) (void)hipStreamDestroy(m->side_stream[k]);
+    m->join_event[k] = nullptr;
+    m->side_stream[k] = nullptr;
   }
+  m->n_side = 0;
 }
 
 fupr_status run(const fupr_model* m, const fupr_tensor* input, const fupr_tensor* output,
@@ -895,8 +906,8 @@ fupr_status run(const fupr_model* m, const fupr_tensor* input, const fupr_tensor
   hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
   if (events && hipEventRecord(events[0], hs) != hipSuccess) return FUPR_ERR_LAUNCH;
   if (use_resident(m, input, output)) {
-    if (!upload_resident(m)) return FUPR_ERR_LAUNCH;
     ResParams R = m->resident;
+    R.layers = reinterpret_cast<const ResLayer*>(m->res_dev);
     R.x = input->ptr;
     R.y = output->ptr;
     R.y_cs = output->c_stride;
@@ -953,25 +964,25 @@ fupr_status run(const fupr_model* m, const fupr_tensor* input, const fupr_tensor
   };
   // Timed runs and small batches stay on the caller's stream; otherwise the
   // batch is cut into sub-batches that run side by side (images are independent).
-  const int split = events ? 1 : split_count(N);
-  if (split <= 1 || m->schedule != FUPR_SCHEDULE_AUTO || !ensure_side(m))
-    return enqueue(0, N, stream, events != nullptr);
+  const int split = events || m->schedule != FUPR_SCHEDULE_AUTO ? 1 : split_count(m, N);
+  if (split <= 1) return enqueue(0, N, stream, events != nullptr);
   std::lock_guard<std::mutex> lock(const_cast<fupr_model*>(m)->side_mutex);
   if (hipEventRecord(m->fork_event, hs) != hipSuccess) return FUPR_ERR_LAUNCH;
-  for (int k = 1; k < split; ++k)
-    if (hipStreamWaitEvent(m->side_stream[k - 1], m->fork_event, 0) != hipSuccess)
-      return FUPR_ERR_LAUNCH;
   fupr_status result = FUPR_OK;
-  for (int k = 0; k < split; ++k) {
-    const int n0 = (int)((int64_t)N * k / split), n1 = (int)((int64_t)N * (k + 1) / split);
-    const fupr_status st = enqueue(n0, n1 - n0, k == 0 ? stream : (void*)m->side_stream[k - 1], false);
-    if (st != FUPR_OK && result == FUPR_OK) result = st;
+  int forked = 0;   // side streams that wait on the caller's stream and must be joined to it again
+  for (int k = 1; k < split && result == FUPR_OK; ++k) {
+    if (hipStreamWaitEvent(m->side_stream[k - 1], m->fork_event, 0) != hipSuccess) result = FUPR_ERR_LAUNCH;
+    else ++forked;
   }
-  // always join, so that the caller's stream (or capture) is whole again
-  for (int k = 1; k < split; ++k) {
+  for (int k = 0; k < split && result == FUPR_OK; ++k) {
+    const int n0 = (int)((int64_t)N * k / split), n1 = (int)((int64_t)N * (k + 1) / split);
+    result = enqueue(n0, n1 - n0, k == 0 ? stream : (void*)m->side_stream[k - 1], false);
+  }
+  // always join what was forked, so that the caller's stream (or capture) is whole again
+  for (int k = 1; k <= forked; ++k) {
     if (hipEventRecord(m->join_event[k - 1], m->side_stream[k - 1]) != hipSuccess ||
         hipStreamWaitEvent(hs, m->join_event[k - 1], 0) != hipSuccess)
-      return FUPR_ERR_LAUNCH;
+      result = FUPR_ERR_LAUNCH;
   }
   return result;
 }
@@ -1047,16 +1058,23 @@ extern "C" fupr_status fupr_model_op_stats(const fupr_model* m, int32_t batch, i
   return FUPR_OK;
 }
 
+namespace {
+// The one-kernel schedule will run (given tensors of the planned strides).
+bool one_kernel(const fupr_model* m) {
+  return m->resident_ok && m->res_dev && m->schedule == FUPR_SCHEDULE_AUTO;
+}
+}  // namespace
+
 extern "C" int32_t fupr_model_num_launches(const fupr_model* m) {
   if (!m) return 0;
-  return m->resident_ok && m->schedule == FUPR_SCHEDULE_AUTO ? 1 : (int32_t)launches_of(m).size();
+  return one_kernel(m) ? 1 : (int32_t)launches_of(m).size();
 }
 
 extern "C" fupr_status fupr_model_launch_stats(const fupr_model* m, int32_t batch, int32_t launch,
                                                fupr_op_stats* out) {
   if (!m || !out) return FUPR_ERR_NULL;
   if (batch <= 0 || launch < 0 || launch >= fupr_model_num_launches(m)) return FUPR_ERR_ARG;
-  if (!(m->resident_ok && m->schedule == FUPR_SCHEDULE_AUTO)) {
+  if (!one_kernel(m)) {
     const Launch l = launches_of(m)[launch];
     fupr_status st = fupr_model_op_stats(m, batch, l.first, out);
     if (st != FUPR_OK || l.count == 1) return st;
@@ -1118,8 +1136,6 @@ extern "C" fupr_status fupr_graph_create(const fupr_model* m, const fupr_tensor*
                                          size_t workspace_bytes, void* stream, fupr_graph** out) {
   if (!out) return FUPR_ERR_NULL;
   if (!stream) return FUPR_ERR_ARG;
-  if (m && m->resident_ok) (void)upload_resident(m);   // no allocation inside the capture
-  if (m) (void)ensure_side(m);                          // nor stream / event creation
   hipStream_t hs = reinterpret_cast<hipStream_t>(stream);
   fupr_graph* g = new (std::nothrow) fupr_graph;
   if (!g) return FUPR_ERR_ARG;

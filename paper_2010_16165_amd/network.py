@@ -50,12 +50,14 @@ def _aggressive(blk):
             "prune_counts": [c1["W"].shape[0] - k1, 0], "shortcut": {"kind": "none"}}
 
 
-def optimise(model, norm=1, aggressive=False, prune_fused=True):
+def optimise(model, norm=1, aggressive=False, prune_fused=True, fuse_stages=None):
     """Masks from the raw weights, batch norm merged, masked filters removed.
 
     aggressive: basic blocks are first rewritten by aggressive fusion; with
     prune_fused their dilated first operator then loses its n - m lowest-norm
     filters (Alg. 1), without it the fused model is run as it is.
+    fuse_stages: the fusion option x of "x/n" (Sec. V, optimization setting): only
+    the blocks of the first x stages are fused; None fuses every stage.
 
     Returns {"layers": [Layer...], "masks": {(block, conv): uint8 mask},
              "keep_idx": {(block, conv): int32 indices}, "wiring": [...]}
@@ -69,7 +71,8 @@ def optimise(model, norm=1, aggressive=False, prune_fused=True):
         if stem["maxpool"] is not None:
             wiring.append(("maxpool", stem["maxpool"], None))
     for bi, blk in enumerate(model["blocks"]):
-        if aggressive and blk["kind"] == "basic":
+        if aggressive and blk["kind"] == "basic" and (fuse_stages is None
+                                                      or blk.get("stage", 0) < fuse_stages):
             blk = _aggressive(blk)
             if not prune_fused:
                 blk["prune_counts"] = [0, 0]
@@ -133,8 +136,11 @@ def optimise(model, norm=1, aggressive=False, prune_fused=True):
             "dt": B.DTYPES[model["dtype"]], "in_shape": model["in_shape"]}
 
 
-def build(plan, device="cuda:0"):
+def build(plan, device="cuda:0", base_address=None):
     """Pack every layer, upload one blob, create the fupr model.
+
+    base_address: plan on the host only - nothing is uploaded, the operators point
+    at that (never dereferenced) address, and the model can be queried but not run.
 
     Returns (Model, sites) where sites[i] is the convolution site name of
     operator i (None for pools)."""
@@ -156,8 +162,8 @@ def build(plan, device="cuda:0"):
     for li, off in keep_offsets.items():
         idx = np.ascontiguousarray(plan["layers"][li].keep, dtype=np.int32)
         host[off:off + 4 * len(idx)] = idx.view(np.uint8)
-    dev = B.upload_blob(host, device)
-    base = dev.data_ptr()
+    dev = None if base_address is not None else B.upload_blob(host, device)
+    base = base_address if dev is None else dev.data_ptr()
 
     ops, sites = [], []
 
@@ -207,7 +213,7 @@ def build(plan, device="cuda:0"):
                 if i == 0 and late:
                     res = conv_op(proj, x)
             cur = conv_op(first + n - 1, h, res, rss, 0)
-    model = B.Model(dt, plan["in_shape"], ops, keepalive=[dev])
+    model = B.Model(dt, plan["in_shape"], ops, keepalive=[dev], device=device)
     model.sites = sites
     model.plan = plan
     return model, sites

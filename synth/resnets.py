@@ -19,6 +19,7 @@ Layout of a model (all arrays numpy float32, C-contiguous):
     conv  = {"W": (K, C, R, S), "stride": int, "pad": int}
     bn    = {"gamma", "beta", "mean", "var": (K,), "eps": float}
     block = {"kind": "basic" | "bottleneck",
+             "stage": int,                   # which stage of Table II the block belongs to
              "convs": [conv, ...], "bns": [bn, ...],
              "prune_permille": [int, ...],   # one per conv, 0 = not pruned; a nonzero
                                              # rate on the LAST conv prunes the block's
@@ -115,6 +116,7 @@ def make_block_model(seed, dtype="f32", channels=16, size=32, permille=250, out_
     """One CIFAR-style basic block with identity shortcut (config 0)."""
     rng = np.random.default_rng([seed, 1])
     blk = _basic_block(rng, channels, channels, 1, "identity", permille, out_permille)
+    blk["stage"] = 0
     return {"name": "basic-block", "dtype": dtype, "in_shape": (channels, size, size),
             "stem": None, "blocks": [blk], "head": None}
 
@@ -133,6 +135,7 @@ def make_cifar_resnet(seed, dtype="bf16", blocks_per_stage=9, permille=400,
             blocks.append(_basic_block(rng, c_in, k, 2 if down else 1,
                                        "optionA" if down else "identity", permille,
                                        out_permille))
+            blocks[-1]["stage"] = si
             c_in = k
     return {"name": f"cifar-resnet{6 * blocks_per_stage + 2}", "dtype": dtype,
             "in_shape": (3, size, size),
@@ -155,6 +158,7 @@ def make_imagenet_basic_resnet(seed, dtype="bf16", stage_blocks=(2, 2, 2, 2), pe
             blocks.append(_basic_block(rng, c_in, k, 2 if down else 1,
                                        "projection" if down else "identity", permille,
                                        out_permille))
+            blocks[-1]["stage"] = si
             c_in = k
     return {"name": f"imagenet-resnet{2 * sum(stage_blocks) + 2}", "dtype": dtype,
             "in_shape": (3, size, size),
@@ -182,6 +186,7 @@ def make_imagenet_bottleneck_resnet(seed, dtype="bf16", stage_blocks=(3, 4, 6, 3
                 lo, hi = permille_range
                 pm = tuple(int(np.floor(prng.uniform(lo, hi))) for _ in range(2))
             blocks.append(_bottleneck_block(rng, c_in, w, stride, bi == 0, pm, out_permille))
+            blocks[-1]["stage"] = si
             c_in = 4 * w
     return {"name": f"imagenet-resnet{3 * sum(stage_blocks) + 2}", "dtype": dtype,
             "in_shape": (3, size, size),

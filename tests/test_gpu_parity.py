@@ -1,9 +1,11 @@
 """GPU parity: the HIP path, called through the C ABI, against the CPU oracle
 on the same seeded inputs.
 
-Tolerances (max-norm relative error, max|gpu - ref| / max|ref|, per tensor):
-2e-2 for bf16 / fp16 storage, 1e-3 for the fp32 path.  Masks and kept-filter
-indices must be identical.
+Tolerances: max-norm relative error max|gpu - ref| / max|ref| per tensor of at
+most 2e-2 for bf16 / fp16 storage and 1e-3 for the fp32 path, and at least 99.9 %
+of a tensor's elements within |gpu - ref| <= atol + rtol |ref| with rtol the same
+tolerance and atol = rtol x the tensor's root mean square.  Masks and
+kept-filter indices must be identical.
 """
 import zlib
 
@@ -26,8 +28,32 @@ def fx():
     return B, network, torch
 
 
+PASS_RATE = 0.999
+
+
 def rel_err(got, ref):
     return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+def pass_rate(got, ref, tol):
+    """Share of elements with |got - ref| <= atol + rtol |ref|, rtol = tol and
+    atol = tol x the tensor's root mean square (the scale below which an element
+    is the remainder of cancelled terms and a relative bound says nothing)."""
+    rms = float(np.sqrt(np.mean(np.square(ref)))) if ref.size else 0.0
+    return float(np.mean(np.abs(got - ref) <= tol * rms + tol * np.abs(ref))) if ref.size else 1.0
+
+
+def parity(got, ref, dtype, quiet=False):
+    """Both readings of the error bound: max-norm relative error within the
+    tolerance of the storage type, and at least PASS_RATE of the elements within
+    atol + rtol |ref|.  Returns the max-norm relative error."""
+    tol = TOL[dtype]
+    err, rate = rel_err(got, ref), pass_rate(got, ref, tol)
+    if not quiet:
+        print(f"  max-norm rel err {err:.3e}, element-wise pass rate {rate:.5f}", flush=True)
+    assert err <= tol, (err, tol)
+    assert rate >= PASS_RATE, (rate, err)
+    return err
 
 
 def round_to(x, dtype, torch):
@@ -77,10 +103,17 @@ CONV_CASES = [
 @pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
 @pytest.mark.parametrize("case", CONV_CASES, ids=[c[0] for c in CONV_CASES])
 def test_conv_site(fx, case, dtype):
-    B, network, torch = fx
     name, n, c, h, w, k, r, stride, pad, rkind, relu = case
     if dtype == "f32" and c * k * r * r > 200000:
         pytest.skip("fp32 path is exercised on the small shapes")
+    conv_site(fx, case, dtype)
+
+
+def conv_site(fx, case, dtype):
+    """One convolution with merged batch norm, shortcut and ReLU through
+    fupr_conv_fused against the oracle's conv, BN, add, ReLU."""
+    B, network, torch = fx
+    name, n, c, h, w, k, r, stride, pad, rkind, relu = case
     rng = np.random.default_rng(zlib.crc32(name.encode()))
     print(f"case={name} dtype={dtype}", flush=True)
     x = rng.standard_normal((n, c, h, w)).astype(np.float32)
@@ -122,9 +155,123 @@ def test_conv_site(fx, case, dtype):
     torch.cuda.synchronize()
     got = yd.to_nchw()
     assert yd.padding_is_zero()
-    err = rel_err(got, ref)
-    print(f"  max-norm rel err {err:.3e}", flush=True)
-    assert err <= TOL[dtype], (name, dtype, err)
+    return parity(got, ref, dtype)
+
+
+def kernel_of(B, dtype, case):
+    """Name of the kernel fupr_conv_fused launches for a case under the current tuning
+    switches, from a one-operator model on the host (its parameter address is never read)."""
+    name, n, c, h, w, k, r, stride, pad, rkind, relu = case
+    op = B.OpDesc(B.OP_CONV, 0, -1, B.conv_shape(k, c, r, r, stride, pad), 0x1000, 0, 1, 0)
+    return B.Model(B.DTYPES[dtype], (c, h, w), [op], None).op_stats(n, 0)["kernel"]
+
+
+# Every instantiation of the per-layer kernel families, forced through the tuning
+# switches onto shapes with ragged channel / filter counts, both strides, with and
+# without a shortcut, several tiles per workgroup (bench.py at another batch size
+# may pick any of them).
+PATCH_TILES = ["256x64", "256x48", "256x32", "128x64", "128x32", "64x64", "224x64", "224x32",
+               "448x64", "128x64w", "448x32", "448x48", "64x32"]
+FORCED_3X3 = [
+    ("forced 3x3 C45 K72 +id 28x28 x9", 9, 45, 28, 28, 72, 3, 1, 1, "identity", True),
+    ("forced 3x3 C40 K100 s2 26x30 x4", 4, 40, 26, 30, 100, 3, 2, 1, None, True),
+    ("forced 3x3 C136 K39 14x14 x20 norelu", 20, 136, 14, 14, 39, 3, 1, 1, None, False),
+]
+
+
+@pytest.mark.parametrize("tile", range(13), ids=PATCH_TILES)
+def test_every_3x3_tile_forced(fx, tile):
+    B, network, torch = fx
+    B.fupr_tuning_set("patch_tile", tile)
+    try:
+        ran = 0
+        for case in FORCED_3X3:
+            for dtype in ("bf16", "f16"):
+                kernel = kernel_of(B, dtype, case)
+                if kernel != "conv3x3p_" + PATCH_TILES[tile]:
+                    print(f"  {case[0]}: tile does not fit ({kernel} runs)", flush=True)
+                    continue
+                conv_site(fx, case, dtype)
+                ran += 1
+        assert ran >= 2, "the forced tile ran on too few shapes"
+    finally:
+        B.fupr_tuning_set("patch_tile", None)
+
+
+PIPE_TILES = ["128x128", "128x64", "64x64"]
+STREAM_TILES = ["256f", "256f_c128", "128f", "64f", "64f_c512", "32f"]
+FORCED_1X1 = [
+    ("forced 1x1 C520 K100 +id 14x14 x11", 11, 520, 14, 14, 100, 1, 1, 0, "identity", True),
+    ("forced 1x1 C136 K300 s2 24x20 x5", 5, 136, 24, 20, 300, 1, 2, 0, None, False),
+    ("forced 1x1 C1024 K72 7x7 x30", 30, 1024, 7, 7, 72, 1, 1, 0, None, True),
+    ("forced 1x1 C45 K256 +id 20x20 x6 norelu", 6, 45, 20, 20, 256, 1, 1, 0, "identity", False),
+    ("forced 1x1 C64 K41 28x28 x5", 5, 64, 28, 28, 41, 1, 1, 0, None, True),
+    ("forced 1x1 C256 K90 s2 12x12 x7", 7, 256, 12, 12, 90, 1, 2, 0, None, True),
+]
+
+
+@pytest.mark.parametrize("tile", range(3), ids=PIPE_TILES)
+def test_every_pipelined_1x1_tile_forced(fx, tile):
+    B, network, torch = fx
+    B.fupr_tuning_set("pipe_tile", tile)
+    B.fupr_tuning_set("conv1x1_stream", 0)
+    try:
+        ran = 0
+        for case in FORCED_1X1:
+            for dtype in ("bf16", "f16"):
+                if kernel_of(B, dtype, case) != "conv1x1p_" + PIPE_TILES[tile]:
+                    continue
+                conv_site(fx, case, dtype)
+                ran += 1
+        assert ran >= 4, "the forced tile ran on too few shapes"
+    finally:
+        B.fupr_tuning_set("pipe_tile", None)
+        B.fupr_tuning_set("conv1x1_stream", None)
+
+
+@pytest.mark.parametrize("tile", range(6), ids=STREAM_TILES)
+def test_every_streaming_1x1_tile_forced(fx, tile):
+    B, network, torch = fx
+    B.fupr_tuning_set("stream_tile", tile)
+    B.fupr_tuning_set("conv1x1_pipe", 0)
+    try:
+        ran = 0
+        for case in FORCED_1X1:
+            for dtype in ("bf16", "f16"):
+                if kernel_of(B, dtype, case) != "conv1x1s_" + STREAM_TILES[tile]:
+                    continue
+                conv_site(fx, case, dtype)
+                ran += 1
+        assert ran >= 2, "the forced tile ran on too few shapes"
+    finally:
+        B.fupr_tuning_set("stream_tile", None)
+        B.fupr_tuning_set("conv1x1_pipe", None)
+
+
+GENERAL_TILES = ["64x16", "128x16", "64x32", "128x32", "64x48", "128x48", "64x64", "128x64",
+                 "64x96", "128x96", "64x128", "128x128"]
+FORCED_GENERAL = [
+    ("forced general 3x3 C40 K100 s2 26x30 x4", 4, 40, 26, 30, 100, 3, 2, 1, None, True),
+    ("forced general 3x3 C6 K20 +id 17x13 x3", 3, 6, 17, 13, 20, 3, 1, 1, "identity", True),
+    ("forced general 1x1 C72 K200 +id 9x11 x5 norelu", 5, 72, 9, 11, 200, 1, 1, 0, "identity", False),
+    ("forced general 5x5 C12 K33 s2 21x21 x2", 2, 12, 21, 21, 33, 5, 2, 2, None, True),
+]
+
+
+@pytest.mark.parametrize("tile", GENERAL_TILES)
+def test_every_general_tile_forced(fx, tile):
+    B, network, torch = fx
+    B.fupr_tuning_set("conv_tile", "conv16t_" + tile)
+    for family in ("conv_patch", "conv1x1_stream", "conv1x1_pipe"):
+        B.fupr_tuning_set(family, 0)
+    try:
+        for case in FORCED_GENERAL:
+            for dtype in ("bf16", "f16"):
+                assert kernel_of(B, dtype, case) == "conv16t_" + tile
+                conv_site(fx, case, dtype)
+    finally:
+        for family in ("conv_tile", "conv_patch", "conv1x1_stream", "conv1x1_pipe"):
+            B.fupr_tuning_set(family, None)
 
 
 @pytest.mark.parametrize("tile", [4, 5, 12], ids=["128x32", "64x64", "64x32"])
@@ -133,10 +280,9 @@ def test_small_tiles_with_several_units_in_flight(fx, tile):
     of LDS buffers.  The planner picks them for small layers only (one tile per
     workgroup); forced onto layers with more tiles than compute units, every
     workgroup walks several tiles and the ring wraps across tile boundaries."""
-    import os
     B, network, torch = fx
     cases = [(6, 45, 56, 56, 64, 1, "identity"), (5, 40, 30, 26, 72, 2, None), (7, 100, 28, 28, 33, 1, None)]
-    os.environ["FUPR_PATCH_TILE"] = str(tile)
+    B.fupr_tuning_set("patch_tile", tile)
     try:
         for n, c, h, w, k, stride, rkind in cases:
             rng = np.random.default_rng(1000 * tile + c)
@@ -161,11 +307,11 @@ def test_small_tiles_with_several_units_in_flight(fx, tile):
                 yd.data.fill_(3.0)
                 B.fupr_conv_fused(sh, xd, packed, res_arg, B.FUSE_RELU | (B.FUSE_ADD if res_arg else 0), yd)
                 torch.cuda.synchronize()
-                err = rel_err(yd.to_nchw(), ref)
+                err = parity(yd.to_nchw(), ref, dtype)
                 print(f"tile {tile} C{c} K{k} s{stride} {dtype}: rel err {err:.3e}", flush=True)
                 assert yd.padding_is_zero() and err <= TOL[dtype]
     finally:
-        del os.environ["FUPR_PATCH_TILE"]
+        B.fupr_tuning_set("patch_tile", None)
 
 
 def test_identity_weights_copy_input(fx):
@@ -276,7 +422,7 @@ def test_stem_maxpool_fused(fx, size, dtype):
     B.fupr_conv_maxpool_fused(sh, xd, packed, 3, 2, 1, yd)
     torch.cuda.synchronize()
     got = yd.to_nchw()
-    err = rel_err(got, ref)
+    err = parity(got, ref, dtype)
     print(f"  max-norm rel err {err:.3e}", flush=True)
     assert err <= TOL[dtype], (size, dtype, err)
     # the two-kernel path: same accumulation order, one rounding each, max of rounded values
@@ -328,10 +474,10 @@ def test_two_1x1_convolutions_in_one_kernel(fx, case, dtype):
     torch.cuda.synchronize()
     y = yd.to_nchw()
     assert yd.padding_is_zero() and hd.padding_is_zero()
-    err_y = rel_err(y, y_ref)
+    err_y = parity(y, y_ref, dtype)
     # the second convolution reads what the device holds of y
     h_ref = orc.relu(orc.conv2d(y, w2, 1, 0) + b2.astype(np.float64)[None, :, None, None])
-    err_h = rel_err(hd.to_nchw(), h_ref)
+    err_h = parity(hd.to_nchw(), h_ref, dtype)
     print(f"  max-norm rel err y {err_y:.3e}, h {err_h:.3e}", flush=True)
     assert err_y <= TOL[dtype] and err_h <= TOL[dtype]
     # the two separate kernels
@@ -431,7 +577,7 @@ def test_small_network(fx, mi):
     for key in masks:
         assert np.array_equal(plan["masks"][key], masks[key])
         assert np.array_equal(plan["keep_idx"][key], np.flatnonzero(masks[key]))
-    err = rel_err(y, ref)
+    err = parity(y, ref, model["dtype"])
     print(f"model {mi} {model['name']} end-to-end rel err {err:.3e}", flush=True)
     assert err <= TOL[model["dtype"]]
 
@@ -460,19 +606,41 @@ def test_aggressively_fused_network(fx, mi):
     ref_original = orc.forward(model, xr)
     plan, m, y = run_network(B, network, torch, model, x, aggressive=True, prune_fused=False)
     assert not plan["masks"] and not any(L.add for L in plan["layers"])
-    err = rel_err(y, ref_fused)
+    err = parity(y, ref_fused, model["dtype"])
     print(f"fused model {mi}: rel err {err:.3e} (vs original {rel_err(y, ref_original):.3e})", flush=True)
     assert err <= TOL[model["dtype"]]
-    assert rel_err(y, ref_original) <= TOL[model["dtype"]]
+    parity(y, ref_original, model["dtype"])
     masks = orc.select_masks(fused)
     ref_pruned = orc.forward(fused, xr, masks=masks)
     plan, m, y = run_network(B, network, torch, model, x, aggressive=True)
     assert set(plan["masks"]) == set(masks)
     for key in masks:
         assert np.array_equal(plan["masks"][key], masks[key])
-    err = rel_err(y, ref_pruned)
+    err = parity(y, ref_pruned, model["dtype"])
     print(f"fused + pruned-back model {mi}: rel err {err:.3e}", flush=True)
     assert err <= TOL[model["dtype"]]
+
+
+@pytest.mark.parametrize("name,stages", [("resnet20", 1), ("resnet20", 2), ("resnet18", 2)])
+def test_fusion_option_x_of_n(fx, name, stages):
+    """The paper's fusion option x/n (Sec. V, optimization setting; the axis of
+    Tables V, VI, VIII): the first x stages aggressively fused and pruned back
+    (n - m), the other stages pruned at p with their addition in the epilogue."""
+    B, network, torch = fx
+    model = synth.make_paper_workload(name)
+    x = synth.make_input(84, 2, model["in_shape"])
+    xr = round_to(x, model["dtype"], torch)
+    part = orc.aggressive_fuse(model, stages=stages)
+    masks = orc.select_masks(part)
+    ref = orc.forward(part, xr, masks=masks)
+    plan, m, y = run_network(B, network, torch, model, x, aggressive=True, fuse_stages=stages)
+    assert set(plan["masks"]) == set(masks)
+    for key in masks:
+        assert np.array_equal(plan["masks"][key], masks[key])
+    fused_blocks = sum(b["stage"] < stages for b in model["blocks"])
+    assert sum(L.add for L in plan["layers"]) == len(model["blocks"]) - fused_blocks
+    err = parity(y, ref, model["dtype"])
+    print(f"{name} fused {stages} stages: rel err {err:.3e}", flush=True)
 
 
 @pytest.mark.parametrize("name", synth.PAPER_WORKLOADS)
@@ -487,7 +655,7 @@ def test_paper_workload_at_batch_one(fx, name):
     plan, m, y = run_network(B, network, torch, model, x)
     # CIFAR networks: one kernel; ImageNet networks: one per operator, stem + pool as one
     assert m.num_launches == (1 if name in ("resnet20", "resnet32") else m.num_ops - 1)
-    err = rel_err(y, ref)
+    err = parity(y, ref, model["dtype"])
     print(f"{model['name']}: rel err {err:.3e}", flush=True)
     assert err <= TOL[model["dtype"]]
 
@@ -502,7 +670,7 @@ def test_unpruned_cifar_network_stays_in_one_kernel(fx):
     ref = orc.forward(model, round_to(x, model["dtype"], torch))
     plan, m, y = run_network(B, network, torch, model, x)
     assert m.num_launches == 1
-    err = rel_err(y, ref)
+    err = parity(y, ref, model["dtype"])
     print(f"{model['name']}: rel err {err:.3e}", flush=True)
     assert err <= TOL[model["dtype"]]
 
@@ -526,7 +694,7 @@ def test_baseline_config_end_to_end(fx, idx):
         assert np.array_equal(plan["masks"][key], masks[key])
         assert np.array_equal(plan["keep_idx"][key], np.flatnonzero(masks[key]))
     assert np.isfinite(y).all()
-    err = rel_err(y, ref)
+    err = parity(y, ref, model["dtype"])
     print(f"config {idx} {model['name']} end-to-end rel err {err:.3e}", flush=True)
     assert err <= TOL[model["dtype"]]
 
@@ -571,7 +739,7 @@ def test_baseline_config_teacher_forced(fx, idx):
         flags = (B.FUSE_RELU if L.relu else 0) | (B.FUSE_ADD if res_arg else 0)
         B.fupr_conv_fused(L.shape, xd, packed, res_arg, flags, yd)
         torch.cuda.synchronize()
-        err = rel_err(yd.to_nchw(), yref)
+        err = parity(yd.to_nchw(), yref, dtype, quiet=True)
         worst = max(worst, err)
         assert err <= TOL[dtype], (L.site, err)
     print(f"config {idx}: worst site rel err {worst:.3e} over {len(plan['layers'])} sites", flush=True)
@@ -618,7 +786,7 @@ def test_one_kernel_schedule_equals_per_layer_schedule(fx, mi):
     y = out_a.to_nchw()
     if model["head"] is not None:
         y = y[:, :, 0, 0]
-    err = rel_err(y, ref)
+    err = parity(y, ref, model["dtype"])
     print(f"resident model {mi}: rel err {err:.3e}", flush=True)
     assert err <= TOL[model["dtype"]]
 
@@ -632,10 +800,13 @@ def test_imagenet_models_use_per_layer_schedule(fx):
 
 
 @pytest.mark.parametrize("idx", range(5))
-def test_baseline_config_full_batch_sampled(fx, idx):
+def test_baseline_config_full_batch(fx, idx):
     """The workload at its full batch size, launched the way bench.py launches it
-    (HIP-graph replay on a side stream); the oracle computes a sample of the
-    images (first, second, middle, last) one by one."""
+    (HIP-graph replay on a side stream).  Configurations 0 - 3: the oracle computes
+    EVERY image of the batch (tiles run across image boundaries and persistent
+    workgroups walk ranges of tiles, so no image may go unchecked).  Configuration 4
+    (256 images of the largest network): the oracle computes four images here, and
+    test_config4_layer_shapes_at_full_batch covers every layer at the full batch."""
     B, network, torch = fx
     model, batch = synth.make_config(idx)
     dtype = model["dtype"]
@@ -658,14 +829,112 @@ def test_baseline_config_full_batch_sampled(fx, idx):
         y = y[:, :, 0, 0]
     assert np.isfinite(y).all()
     masks = orc.select_masks(model)
-    sample = sorted({0, min(1, batch - 1), batch // 2, batch - 1})
-    print(f"config {idx}: batch {batch}, oracle on images {sample}", flush=True)
+    sample = list(range(batch)) if idx < 4 else sorted({0, 1, batch // 2, batch - 1})
+    print(f"config {idx}: batch {batch}, oracle on {len(sample)} images", flush=True)
+    xr = round_to(x[sample], dtype, torch)
     worst = 0.0
-    for i in sample:
-        ref = orc.forward(model, round_to(x[i:i + 1], dtype, torch), masks=masks)
-        worst = max(worst, rel_err(y[i:i + 1], ref))
-    print(f"config {idx}: worst sampled rel err {worst:.3e}", flush=True)
-    assert worst <= TOL[dtype]
+    for at in range(0, len(sample), 16):       # 16 images per oracle pass bounds its memory
+        ref = orc.forward(model, xr[at:at + 16], masks=masks)
+        for j in range(ref.shape[0]):          # every image against its own maximum
+            worst = max(worst, parity(y[sample[at + j]:sample[at + j] + 1], ref[j:j + 1], dtype,
+                                      quiet=True))
+    print(f"config {idx}: worst rel err over {len(sample)} images {worst:.3e}", flush=True)
+
+
+def raw_layers(model):
+    """site name -> (raw convolution, its batch norm, (block, conv) key or None)."""
+    sites = {}
+    if model["stem"] is not None:
+        sites["stem"] = (model["stem"]["conv"], model["stem"]["bn"], None)
+    for bi, blk in enumerate(model["blocks"]):
+        for ci, (conv, bn) in enumerate(zip(blk["convs"], blk["bns"])):
+            sites[f"b{bi}.conv{ci + 1}"] = (conv, bn, (bi, ci))
+        if blk["shortcut"]["kind"] == "projection":
+            sites[f"b{bi}.proj"] = (blk["shortcut"]["conv"], blk["shortcut"]["bn"], None)
+    return sites
+
+
+def test_config4_layer_shapes_at_full_batch(fx):
+    """Every convolution of the largest workload (irregular channel counts, fp16)
+    at its full batch of 256 images, each alone on seeded synthetic activations of
+    its input shape: the device computes the whole layer, the oracle (raw weights,
+    literal batch norm, removed filters and removed input channels as zeros) a
+    sample of output pixels one by one - the corners of the first and last image,
+    pixels either side of image boundaries, and seeded random ones."""
+    B, network, torch = fx
+    model, batch = synth.make_config(4)
+    dtype = model["dtype"]
+    dt = B.DTYPES[dtype]
+    masks = orc.select_masks(model)
+    plan = network.optimise(model)
+    raw = raw_layers(model)
+    rng = np.random.default_rng(synth.BASE_SEED + 4004)
+    worst, done = 0.0, 0
+    for L in plan["layers"]:
+        if L.site == "fc":
+            continue                      # a 1 x 1 image: covered at full batch by the network test
+        conv, bn, key = raw[L.site]
+        k_full, c_full, r, _ = conv["W"].shape
+        stride, pad = conv["stride"], conv["pad"]
+        in_keep = np.arange(c_full)
+        if key is not None and (key[0], key[1] - 1) in masks:
+            in_keep = np.flatnonzero(masks[(key[0], key[1] - 1)])
+        out_keep = np.flatnonzero(masks[key]) if key in masks else np.arange(k_full)
+        assert L.W.shape == (len(out_keep), len(in_keep), r, r), L.site
+        # input extent from the site's place in the network
+        h = {"stem": 224}.get(L.site)
+        if h is None:
+            bi = int(L.site[1:].split(".")[0])
+            stage = 0 if bi < 3 else 1 if bi < 7 else 2 if bi < 13 else 3
+            first = bi in (0, 3, 7, 13)
+            out_h = 56 >> stage
+            if L.site.endswith("conv3"):
+                h = out_h
+            elif L.site.endswith("conv2"):
+                h = out_h * stride
+            else:                          # conv1 and the projection read the block input
+                h = out_h * (2 if first and stage > 0 else 1)
+        p = (h + 2 * pad - r) // stride + 1
+        c = len(in_keep)
+        x = np.maximum(rng.standard_normal((batch, c, h, h), dtype=np.float32), 0.0)
+        if L.site == "stem":
+            x = rng.standard_normal((batch, c, h, h), dtype=np.float32)
+        xd = B.DeviceTensor.from_nchw(x, dt)
+        xr = round_to(x, dtype, torch) if x.size < (1 << 26) else None
+        res_d = None
+        if L.add:
+            rs = np.maximum(rng.standard_normal((batch, len(out_keep), p, p), dtype=np.float32), 0.0)
+            res_d = B.DeviceTensor.from_nchw(rs, dt)
+        packed = B.upload_blob(B.fupr_pack(L.shape, L.W, L.bias, dt))
+        yd = B.DeviceTensor.empty(batch, p, p, len(out_keep), dt)
+        flags = (B.FUSE_RELU if L.relu else 0) | (B.FUSE_ADD if L.add else 0)
+        print(f"{L.site}: {c} -> {len(out_keep)} {r}x{r}/{stride} on {batch}x{h}x{h}", flush=True)
+        B.fupr_conv_fused(L.shape, xd, packed, (res_d, 1, 0) if L.add else None, flags, yd)
+        torch.cuda.synchronize()
+        # sampled output pixels (n, p, q)
+        pts = [(0, 0, 0), (0, 0, p - 1), (0, p - 1, p - 1), (1, 0, 0), (batch // 2 - 1, p - 1, p - 1),
+               (batch // 2, 0, 0), (batch - 1, p - 1, 0), (batch - 1, p - 1, p - 1)]
+        pts += [(int(rng.integers(batch)), int(rng.integers(p)), int(rng.integers(p))) for _ in range(40)]
+        crops = np.zeros((len(pts), c_full, r, r), dtype=np.float64)
+        for j, (n, pp, qq) in enumerate(pts):
+            for dr in range(r):
+                for ds in range(r):
+                    ih, iw = pp * stride + dr - pad, qq * stride + ds - pad
+                    if 0 <= ih < h and 0 <= iw < h:
+                        v = x[n, :, ih, iw] if xr is None else xr[n, :, ih, iw]
+                        crops[j, in_keep, dr, ds] = round_to(v, dtype, torch) if xr is None else v
+        ref = orc.batchnorm(orc.conv2d(crops, conv["W"], 1, 0), bn)[:, out_keep, 0, 0]
+        got = np.stack([yd.data[n, pp, qq, :len(out_keep)].double().cpu().numpy() for n, pp, qq in pts])
+        if L.add:
+            ref = ref + np.stack([res_d.data[n, pp, qq, :len(out_keep)].double().cpu().numpy()
+                                  for n, pp, qq in pts])
+        if L.relu:
+            ref = orc.relu(ref)
+        worst = max(worst, parity(got, ref, dtype, quiet=True))
+        done += 1
+        del xd, yd, res_d, packed, x, xr
+    print(f"config 4: {done} layers at batch {batch}, worst sampled rel err {worst:.3e}", flush=True)
+    assert done == 53
 
 
 def test_forward_is_deterministic_and_graph_replays(fx):
@@ -699,7 +968,6 @@ def test_sub_batches_on_forked_streams_give_identical_results(fx):
     """Large batches run as sub-batches on streams that fork from and join the
     caller's stream; images are independent, so the result must not change by a
     bit, eagerly and from a replayed graph."""
-    import os
     B, network, torch = fx
     model = synth.make_imagenet_basic_resnet(31, "bf16", (1, 1, 1, 1), 300, widths=(64, 16, 24, 40),
                                              size=64, classes=9)
@@ -708,14 +976,13 @@ def test_sub_batches_on_forked_streams_give_identical_results(fx):
     m, _ = network.build(network.optimise(model))
     xd = B.DeviceTensor.from_nchw(x, B.BF16)
     out, ws = m.alloc(n)
-    old = os.environ.get("FUPR_SPLIT")
     try:
-        os.environ["FUPR_SPLIT"] = "1"
+        B.fupr_tuning_set("split", 1)
         m.fupr_forward(xd, out, ws)
         torch.cuda.synchronize()
         whole = out.data.clone()
         for parts in (2, 3):
-            os.environ["FUPR_SPLIT"] = str(parts)
+            B.fupr_tuning_set("split", parts)
             print(f"sub-batches: {parts}", flush=True)
             out.data.zero_()
             m.fupr_forward(xd, out, ws)
@@ -733,10 +1000,7 @@ def test_sub_batches_on_forked_streams_give_identical_results(fx):
                     s.synchronize()
                     assert torch.equal(whole, out2.data)
     finally:
-        if old is None:
-            os.environ.pop("FUPR_SPLIT", None)
-        else:
-            os.environ["FUPR_SPLIT"] = old
+        B.fupr_tuning_set("split", None)
 
 
 # ---- a block's pruned output filters: indexed update of the full-width stream --------------
@@ -798,7 +1062,7 @@ def test_conv_scatter_site(fx, case, dtype):
     assert yd.padding_is_zero()
     rest = np.setdiff1d(np.arange(width), keep)
     assert np.array_equal(got[:, rest], y0r[:, rest])
-    err = rel_err(got[:, keep], upd)
+    err = parity(got[:, keep], upd, dtype)
     print(f"  max-norm rel err {err:.3e}", flush=True)
     assert err <= TOL[dtype], (name, dtype, err)
 
@@ -846,7 +1110,7 @@ def test_conv_scatter_random_shapes(fx):
         rest = np.setdiff1d(np.arange(width), keep)
         assert np.array_equal(got[:, rest], y0r[:, rest]), case
         assert yd.padding_is_zero()
-        err = rel_err(got[:, keep], upd)
+        err = parity(got[:, keep], upd, dtype, quiet=True)
         worst = max(worst, err)
         assert err <= TOL[dtype], (case, err)
     print(f"worst rel err {worst:.3e}", flush=True)
@@ -925,7 +1189,7 @@ def test_network_with_pruned_output_filters(fx, mi):
     # 3 x 3 last convolutions run thin and add into their channels; 1 x 1 ones get zero rows back
     assert all(L.W.shape[2] == 3 for L in thin)
     assert bool(thin) == (model["blocks"][0]["kind"] == "basic")
-    err = rel_err(y, ref)
+    err = parity(y, ref, model["dtype"])
     print(f"model {mi} {model['name']} end-to-end rel err {err:.3e}", flush=True)
     assert err <= TOL[model["dtype"]]
     # the graph replays to the same bits (the updates are in place, the stream is rebuilt each pass)
@@ -954,7 +1218,7 @@ def test_paper_workload_with_pruned_output_filters(fx, name):
     plan, m, y = run_network(B, network, torch, model, x)
     kernels = [m.op_stats(2, i)["kernel"] for i, L in enumerate(m.sites) if L and L.endswith("conv2")]
     assert all(k.startswith("conv3x3p_") for k in kernels)
-    err = rel_err(y, ref)
+    err = parity(y, ref, model["dtype"])
     print(f"{model['name']}: rel err {err:.3e}", flush=True)
     assert err <= TOL[model["dtype"]]
 
@@ -988,7 +1252,7 @@ def test_pruned_output_filters_full_batch_sampled(fx, name, batch):
     worst = 0.0
     for i in (0, batch // 2, batch - 1):
         ref = orc.forward(model, round_to(x[i:i + 1], dtype, torch), masks=masks)
-        worst = max(worst, rel_err(y[i:i + 1], ref))
+        worst = max(worst, parity(y[i:i + 1], ref, dtype, quiet=True))
     print(f"{model['name']} batch {batch}: worst sampled rel err {worst:.3e}", flush=True)
     assert worst <= TOL[dtype]
 
@@ -997,23 +1261,25 @@ def test_measuring_kernels(fx):
     """The copy copies; the MFMA loop reports its work and multiplies what it says
     (ones times ones, summed over 32 channels, iters times)."""
     B, network, torch = fx
+    from paper_2010_16165_amd import measure as M
     src = torch.randint(0, 255, (1 << 20,), dtype=torch.uint8, device="cuda")
     dst = torch.zeros_like(src)
-    B.fupr_measure_copy(src, dst, src.numel())
+    M.fupr_measure_copy(src, dst, src.numel())
     torch.cuda.synchronize()
     assert torch.equal(src, dst)
-    with pytest.raises(B.FuprError) as e:
-        B.fupr_measure_copy(src, dst, 24)
-    assert e.value.status == B.ERR_SHAPE
+    with pytest.raises(RuntimeError):
+        M.fupr_measure_copy(src, dst, 24)
     out = torch.zeros(4 * 256, dtype=torch.float32, device="cuda")
     for dt in (B.BF16, B.F16):
-        flops = B.fupr_measure_mfma(dt, 3, 4, out)
-        torch.cuda.synchronize()
-        assert flops == 4 * 4 * 3 * 8 * 2 * 16 * 16 * 32
-        assert torch.isfinite(out).all() and float(out.abs().max()) > 0
-    with pytest.raises(B.FuprError) as e:
-        B.fupr_measure_mfma(B.F32, 3, 4, out)
-    assert e.value.status == B.ERR_DTYPE
+        for shape, per_mfma in ((16, 2 * 16 * 16 * 32), (32, 2 * 32 * 32 * 16)):
+            flops = M.fupr_measure_mfma(dt, shape, 3, 4, out)
+            torch.cuda.synchronize()
+            assert flops == 4 * 4 * 3 * 8 * per_mfma
+            assert torch.isfinite(out).all() and float(out.abs().max()) > 0
+    with pytest.raises(RuntimeError):
+        M.fupr_measure_mfma(B.F32, 16, 3, 4, out)
+    with pytest.raises(RuntimeError):
+        M.fupr_measure_mfma(B.BF16, 8, 3, 4, out)
 
 
 def test_timed_forward_and_stats(fx):

@@ -24,15 +24,105 @@ def rand_bn(k):
 
 # ---- C ABI surface ------------------------------------------------------------
 
-def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "fupr.h")).read()
+def declared_in(header_name):
+    header = open(os.path.join(ROOT, "include", header_name)).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(fupr_[a-z_0-9]+)\s*\(", header))
+    return set(re.findall(r"\b(fupr_[a-z_0-9]+)\s*\(", header))
+
+
+def test_library_exports_every_declared_symbol():
+    declared = declared_in("fupr.h")
     assert len(declared) >= 20
     lib = C.CDLL(B.LIB_PATH)
     for name in declared:
         assert hasattr(lib, name), name
     assert declared == set(B.SIGNATURES), declared ^ set(B.SIGNATURES)
+
+
+def test_measuring_library_exports_every_declared_symbol():
+    """The measuring kernels live in a library of their own, apart from the product's."""
+    from paper_2010_16165_amd import measure as M
+    declared = declared_in("fupr_measure.h")
+    assert declared == set(M.SIGNATURES) == {"fupr_measure_mfma", "fupr_measure_copy"}
+    lib = C.CDLL(M.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    product = C.CDLL(B.LIB_PATH)
+    assert not any(hasattr(product, name) for name in declared)
+
+
+def test_library_owns_no_device_memory_or_stream():
+    """Every device buffer and stream is the caller's: the product sources call no
+    allocating, copying or stream-creating runtime routine."""
+    csrc = os.path.join(ROOT, "paper_2010_16165_amd", "csrc")
+    banned = re.compile(r"\bhip(Malloc\w*|Free\w*|Memcpy\w*|Memset\w*|StreamCreate\w*|HostMalloc|ExtMalloc\w*)\s*\(")
+    for name in sorted(os.listdir(csrc)):
+        text = open(os.path.join(csrc, name)).read()
+        text = re.sub(r"//.*", "", text)
+        hits = banned.findall(text)
+        assert not hits, (name, hits)
+
+
+def build_host_model(plan, base):
+    return network.build(plan, base_address=base)
+
+
+def test_tuning_switches():
+    B.fupr_tuning_set("patch_tile", 4)
+    B.fupr_tuning_set("patch_tile", None)
+    B.fupr_tuning_set("conv_tile", "conv16t_64x16")
+    B.fupr_tuning_set("conv_tile", "")
+    with pytest.raises(B.FuprError) as e:
+        B.fupr_tuning_set("no_such_switch", 1)
+    assert e.value.status == B.ERR_ARG
+    with pytest.raises(B.FuprError) as e:
+        B.fupr_tuning_set("split", "9" * 200)
+    assert e.value.status == B.ERR_ARG
+    assert B._lib.fupr_tuning_set(None, None) == B.ERR_NULL
+
+
+def test_one_kernel_table_is_the_callers():
+    """The one-kernel schedule's table is written on the host for a device address
+    the caller names; without one the model runs a kernel per operator."""
+    model = synth.make_cifar_resnet(5, "bf16", 2, 400)
+    plan = network.optimise(model)
+    # host-only: made-up 256-byte aligned "device" addresses, nothing is dereferenced here
+    base = 1 << 20
+    m, _ = build_host_model(plan, base)
+    nbytes = B._lib.fupr_model_table_bytes(m._h)
+    assert nbytes > 0 and nbytes % 256 == 0
+    assert m.num_launches == m.num_ops            # no table yet: per operator
+    img_a = np.zeros(nbytes, np.uint8)
+    img_b = np.zeros(nbytes, np.uint8)
+    st = B._lib.fupr_model_table_write(m._h, C.c_void_p(1 << 30), img_a.ctypes.data_as(C.c_void_p))
+    assert st == B.FUPR_OK
+    st = B._lib.fupr_model_table_write(m._h, C.c_void_p((1 << 30) + 4096), img_b.ctypes.data_as(C.c_void_p))
+    assert st == B.FUPR_OK
+    assert not np.array_equal(img_a, img_b)       # the image holds addresses inside itself
+    assert B._lib.fupr_model_table_write(m._h, C.c_void_p((1 << 30) + 8), img_a.ctypes.data_as(C.c_void_p)) == B.ERR_ALIGN
+    assert B._lib.fupr_model_table_write(m._h, None, img_a.ctypes.data_as(C.c_void_p)) == B.ERR_NULL
+    assert B._lib.fupr_model_set_table(m._h, C.c_void_p(1 << 30)) == B.FUPR_OK
+    assert m.num_launches == 1
+    assert B._lib.fupr_model_set_table(m._h, None) == B.FUPR_OK
+    assert m.num_launches == m.num_ops
+    # a network with a max-pool has no such table
+    big = synth.make_imagenet_basic_resnet(13, "bf16", (1, 1, 1, 1), 300, widths=(4, 8, 8, 12), size=32, classes=7)
+    mb, _ = build_host_model(network.optimise(big), base)
+    assert B._lib.fupr_model_table_bytes(mb._h) == 0
+    assert B._lib.fupr_model_set_table(mb._h, C.c_void_p(1 << 30)) == B.ERR_ARG
+    assert B._lib.fupr_model_table_bytes(None) == 0
+
+
+def test_side_streams_argument_checks():
+    model = synth.make_cifar_resnet(5, "bf16", 1, 400)
+    m, _ = build_host_model(network.optimise(model), 1 << 20)
+    arr = (C.c_void_p * 4)(None, None, None, None)
+    assert B._lib.fupr_model_set_side_streams(m._h, 0, None) == B.FUPR_OK
+    assert B._lib.fupr_model_set_side_streams(m._h, 1, None) == B.ERR_NULL
+    assert B._lib.fupr_model_set_side_streams(m._h, 1, arr) == B.ERR_NULL      # NULL stream
+    assert B._lib.fupr_model_set_side_streams(m._h, 4, arr) == B.ERR_ARG
+    assert B._lib.fupr_model_set_side_streams(m._h, -1, arr) == B.ERR_ARG
+    assert B._lib.fupr_model_set_side_streams(None, 0, None) == B.ERR_NULL
 
 
 def test_status_strings():
@@ -555,6 +645,21 @@ def test_aggressive_plan_selects_the_oracles_filters():
     by_site = {L.site: L for L in unpruned["layers"]}
     assert by_site["b0.conv1"].W.shape == (k + c, c, 3, 3)
     assert by_site["b0.conv2"].W.shape == (k, k + c, 3, 3)
+
+
+def test_partially_fused_plan_selects_the_oracles_filters():
+    """Fusion option x/n: the blocks of the first x stages go through fupr_xconv_fuse
+    and lose n - m filters, the rest are pruned at their rate; masks equal the oracle's."""
+    model = synth.make_imagenet_basic_resnet(23, "bf16", (1, 2, 1, 1), 300, widths=(4, 8, 8, 12),
+                                             size=32, classes=7)
+    for stages in (0, 1, 3, 4):
+        plan = network.optimise(model, aggressive=True, fuse_stages=stages)
+        masks = orc.select_masks(orc.aggressive_fuse(model, stages=stages))
+        assert set(plan["masks"]) == set(masks)
+        for key in masks:
+            assert np.array_equal(plan["masks"][key], masks[key])
+        fused = sum(b["stage"] < stages for b in model["blocks"])
+        assert sum(L.add for L in plan["layers"]) == len(model["blocks"]) - fused
 
 
 def test_xconv_fuse_errors():

@@ -516,6 +516,37 @@ def test_aggressive_fusion_is_an_equivalence(mi):
         assert blk["shortcut"]["kind"] == "none"
 
 
+@pytest.mark.parametrize("mi,stages", [(0, 0), (0, 1), (0, 2), (1, 1), (1, 2), (1, 3)])
+def test_fusion_option_x_of_n_is_an_equivalence(mi, stages):
+    """The fusion option x/n (Sec. V, optimization setting): the blocks of the
+    first x stages are fused, the others keep their addition; whichever x, the
+    network computes what the original computes, and exactly the blocks of
+    those stages lose their addition."""
+    model = fusible_models()[mi]
+    x = synth.make_input(98, 2, model["in_shape"])
+    part = orc.aggressive_fuse(model, stages=stages)
+    a = orc.forward(model, x)
+    b = orc.forward(part, x)
+    np.testing.assert_allclose(a, b, rtol=1e-10, atol=1e-10 * np.abs(a).max())
+    for blk_o, blk_f in zip(model["blocks"], part["blocks"]):
+        fused = blk_f["shortcut"]["kind"] == "none"
+        assert fused == (blk_o["stage"] < stages)
+        if not fused:
+            assert blk_f is blk_o
+    n_stages = 1 + max(b["stage"] for b in model["blocks"])
+    whole = orc.aggressive_fuse(model, stages=n_stages)
+    assert all(b["shortcut"]["kind"] == "none" for b in whole["blocks"])
+    # pruning the partially fused model: fused operators lose n - m, the others p * n (Alg. 1)
+    masks = orc.select_masks(part)
+    for bi, blk in enumerate(part["blocks"]):
+        n = blk["convs"][0]["W"].shape[0]
+        lost = int((masks[(bi, 0)] == 0).sum()) if (bi, 0) in masks else 0
+        if blk["shortcut"]["kind"] == "none":
+            assert lost == n - blk["original_filters"][0]
+        else:
+            assert lost == orc.prune_count(n, blk["prune_permille"][0])
+
+
 def test_aggressive_fusion_shapes_and_auxiliary_values():
     """conv1' is (k + c) x c x 3 x 3 and conv2' is k x (k + c) x 3 x 3
     (Sec. IV-B-1); the channel-wise auxiliary filters are identities with an
