@@ -446,7 +446,7 @@ class Model:
             torch.cuda.synchronize()
             _check(_lib.fupr_model_set_table(self._h, C.c_void_p(dev.data_ptr())),
                    "fupr_model_set_table")
-            self._keepalive = list(self._keepalive) + [dev]
+            self._keepalive = list(self._keepalive or []) + [dev]
         self._side = []
         if side_streams and torch.cuda.is_available():
             self.set_side_streams([torch.cuda.Stream(device=device) for _ in range(side_streams)])
