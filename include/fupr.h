@@ -444,6 +444,32 @@ fupr_status fupr_forward(const fupr_model* m, const fupr_tensor* input, const fu
                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * fupr_forward for the callers that cannot allocate device memory: code under
+ * HIP-graph capture, tight serving loops, harnesses that forbid allocation.
+ * The workspace is a fixed array of FUPR_STATIC_WORKSPACE_BYTES bytes of device
+ * memory inside the library (a file-scope device array: every GPU the library
+ * runs on holds its own copy from the moment the library is loaded there until
+ * the process ends); its address on the current device is looked up once, at the
+ * first call on that device.  The call itself allocates and frees nothing, on the
+ * device or through any library.  input and output remain the caller's.
+ * Networks and batch sizes whose fupr_model_workspace_bytes exceed the array are
+ * refused with FUPR_ERR_WORKSPACE before anything is launched (32 MiB holds the
+ * networks of Table II at one image, the paper's setting, and the CIFAR
+ * networks up to a few hundred images; the one-kernel schedule needs no
+ * workspace at any batch size).  The array keeps what the last call left in it;
+ * nothing in it has to start at zero, because every tensor of the workspace is
+ * written in full before it is read.  All calls on one GPU share the one array:
+ * calls that overlap in time on one GPU (other streams, other threads) race, so
+ * the caller orders them.  Otherwise identical to fupr_forward, bit for bit.
+ * Errors: those of fupr_forward; WORKSPACE as said; LAUNCH if the runtime cannot
+ * locate the array.
+ */
+#define FUPR_STATIC_WORKSPACE_BYTES (32u << 20)
+size_t fupr_static_workspace_bytes(void);
+fupr_status fupr_forward_static(const fupr_model* m, const fupr_tensor* input,
+                                const fupr_tensor* output, void* stream);
+
+/*
  * As fupr_forward, but brackets every kernel launch with HIP events on the
  * stream, waits for the stream, and writes elapsed times (milliseconds) to the
  * HOST array op_ms, which has fupr_model_num_ops entries: entry i is launch i;

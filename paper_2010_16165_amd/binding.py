@@ -119,6 +119,8 @@ SIGNATURES = {
     "fupr_model_workspace_bytes": (C.c_size_t, [C.c_void_p, C.c_int32]),
     "fupr_model_output_shape": (C.c_int32, [C.c_void_p, C.c_int32, _T]),
     "fupr_forward": (C.c_int32, [C.c_void_p, _T, _T, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "fupr_static_workspace_bytes": (C.c_size_t, []),
+    "fupr_forward_static": (C.c_int32, [C.c_void_p, _T, _T, C.c_void_p]),
     "fupr_forward_timed": (C.c_int32, [C.c_void_p, _T, _T, C.c_void_p, C.c_size_t, C.c_void_p, _F]),
     "fupr_model_op_stats": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(OpStats)]),
     "fupr_model_num_ops": (C.c_int32, [C.c_void_p]),
@@ -409,6 +411,10 @@ def fupr_global_avgpool(x, y, stream=None):
     _check(st, "fupr_global_avgpool")
 
 
+def fupr_static_workspace_bytes():
+    return int(_lib.fupr_static_workspace_bytes())
+
+
 def fupr_tuning_set(name, value):
     """value: None (back to automatic), or anything str() turns into the switch's text."""
     v = None if value is None else str(value).encode()
@@ -519,6 +525,13 @@ class Model:
         st = _lib.fupr_forward(self._h, C.byref(xs), C.byref(ys), C.c_void_p(ws.data_ptr()),
                                ws.numel(), stream if stream is not None else current_stream())
         _check(st, "fupr_forward")
+
+    def fupr_forward_static(self, x, out, stream=None):
+        """The forward pass in the library's own fixed workspace (no allocation)."""
+        xs, ys = x.struct, out.struct
+        st = _lib.fupr_forward_static(self._h, C.byref(xs), C.byref(ys),
+                                      stream if stream is not None else current_stream())
+        _check(st, "fupr_forward_static")
 
     def fupr_forward_timed(self, x, out, ws, stream=None):
         xs, ys = x.struct, out.struct

@@ -11,7 +11,8 @@ LIB = os.path.join(HERE, "libfupr.so")
 MEASURE_DIR = os.path.join(HERE, "measure")
 MEASURE_LIB = os.path.join(MEASURE_DIR, "libfupr_measure.so")
 SOURCES = ["host_passes.cpp", "tuning.cpp", "kernels.hip", "conv_tiled.hip", "conv_patch.hip",
-           "stem_pool.hip", "conv1x1.hip", "conv1x1_pipe.hip", "resident.hip", "model.cpp"]
+           "stem_pool.hip", "conv1x1.hip", "conv1x1_pipe.hip", "resident.hip", "model.cpp",
+           "static_workspace.hip"]
 HEADERS = [os.path.join(ROOT, "include", "fupr.h")] + [
     os.path.join(CSRC, h) for h in ("layout.h", "device_utils.h", "conv16.h", "stem_pool.h",
                                     "tuning.h")]
