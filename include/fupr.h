@@ -17,6 +17,8 @@
  *   fupr_pack            weights -> device layout
  *   fupr_conv_fused      convolution operator k x c x r x s (Sec. III, Sec. IV-B-1)
  *                        with bias, element-wise addition and ReLU in its epilogue
+ *   fupr_proj_concat, fupr_conv_cat_fused   a projection shortcut accumulated in the accumulators of
+ *                        its block's last convolution (Sec. IV-B-1, projection-shortcut recipe)
  *   fupr_conv_scatter_fused             a block's last convolution after its output filters were
  *                        pruned: the kept filters add into their channels of the block's
  *                        full-width output (Alg. 1 applied to every non-fused operator, Sec. V-A)
@@ -26,7 +28,6 @@
  *   fupr_conv_maxpool_fused             Table II's ImageNet stem (7 x 7 convolution, stride 2, then
  *                        3 x 3 max pool, stride 2) in one kernel
  *   fupr_model_*, fupr_forward          a whole network (Table II) on one stream
- *   fupr_block_fused                    a whole bottleneck building block (Table II) in one kernel
  *
  * Conventions
  *   - Host calls (fold, select, prune, pack, model create) take HOST pointers.
@@ -90,9 +91,9 @@ typedef struct {
   int32_t K, C, R, S, stride, pad;
 } fupr_conv_shape;
 
-/* What fupr_fold merges / what the kernel epilogue applies.  FUPR_FUSE_SCATTER is
- * accepted in fupr_op_desc.epilogue only (see there). */
-enum { FUPR_FUSE_BN = 1, FUPR_FUSE_RELU = 2, FUPR_FUSE_ADD = 4, FUPR_FUSE_SCATTER = 8 };
+/* What fupr_fold merges / what the kernel epilogue applies.  FUPR_FUSE_SCATTER and
+ * FUPR_FUSE_CAT are accepted in fupr_op_desc.epilogue only (see there). */
+enum { FUPR_FUSE_BN = 1, FUPR_FUSE_RELU = 2, FUPR_FUSE_ADD = 4, FUPR_FUSE_SCATTER = 8, FUPR_FUSE_CAT = 16 };
 
 /* ------------------------------------------------------------------ host -- */
 
@@ -168,6 +169,29 @@ fupr_status fupr_xconv_fuse(const fupr_conv_shape* conv1, const float* W1, const
                             int32_t shortcut, const fupr_conv_shape* proj, const float* Wp,
                             const fupr_bn* bnp, float* W1_out, const fupr_bn_out* bn1_out,
                             float* W2_out, float* beta2_out);
+
+/*
+ * A projection shortcut accumulated in the accumulators of its block's last
+ * convolution (Sec. IV-B-1, the projection-shortcut recipe, fused along the C
+ * dimension): for a block that ends in a 1 x 1 convolution of h with weights W
+ * and whose shortcut is a 1 x 1 convolution of the block input x with weights Wp,
+ *     conv(h, W) + conv_p(x, Wp) = conv([h ; x], [W | Wp]),
+ * so the addition disappears into one convolution over the concatenated
+ * channels.  (The paper pads the 1 x 1 shortcut to the 3 x 3 of a basic block's
+ * last convolution; a bottleneck block's last convolution is 1 x 1 already.)
+ * Both batch norms have been merged beforehand (fupr_fold).  Writes
+ *     W_out   K x (C1p + C2) x 1 x 1: W's C1 channels, zeros up to C1p = C1 rounded
+ *             up to 32 (one MFMA step), then Wp's C2 channels;
+ *     b_out   K: b + bp (one fp32 addition each; NULL inputs count as zeros);
+ *     *out    the shape of the concatenated operator: K, C1p + C2, 1 x 1, stride 1, pad 0.
+ * The device never builds [h ; x]: fupr_conv_cat_fused reads the first C1p
+ * channels from h and the others from x at the shortcut's stride.
+ * last, proj: 1 x 1, pad 0, equal K; last->stride = 1.  Outputs are
+ * caller-allocated and must not alias inputs.  Errors: NULL, SHAPE.
+ */
+fupr_status fupr_proj_concat(const fupr_conv_shape* last, const float* W, const float* b,
+                             const fupr_conv_shape* proj, const float* Wp, const float* bp,
+                             fupr_conv_shape* out, float* W_out, float* b_out);
 
 /*
  * Number of filters a non-fused operator with n filters loses at pruning rate
@@ -260,6 +284,23 @@ fupr_status fupr_conv_fused(const fupr_conv_shape* shape, const fupr_tensor* x, 
                             void* stream);
 
 /*
+ * fupr_conv_fused over the channel-wise concatenation of two tensors that is
+ * never built (the operator fupr_proj_concat constructs; Sec. IV-B-1): input
+ * channel c < split is channel c of x1 at the output pixel (zero from x1->C on),
+ * input channel c >= split is channel c - split of x2 at
+ * (n, p * x2_spatial_stride, q * x2_spatial_stride), where split = x1->C rounded
+ * up to 32.  shape: 1 x 1, stride 1, pad 0, C = split + x2->C.  x1 has the
+ * output's extent; x2 has at least (P - 1) * x2_spatial_stride + 1 rows and
+ * likewise columns; x2_spatial_stride is 1 or 2; 16-bit types only; everything
+ * else (packed, res, flags, y, rounding) as in fupr_conv_fused.
+ * Errors: as fupr_conv_fused; DTYPE for fp32 tensors.
+ */
+fupr_status fupr_conv_cat_fused(const fupr_conv_shape* shape, const fupr_tensor* x1,
+                                const fupr_tensor* x2, int32_t x2_spatial_stride, const void* packed,
+                                const fupr_residual* res, uint32_t epilogue_flags,
+                                const fupr_tensor* y, void* stream);
+
+/*
  * The last convolution of a building block whose OUTPUT filters were pruned
  * (Alg. 1 removes the lowest-norm filters of every non-fused operator, Sec. V-A;
  * fupr_prune with no consumer gives the kept filters and keep_idx).  The block's
@@ -338,7 +379,7 @@ typedef struct {
   int32_t res;           /* tensor added in the epilogue, -1 = none (conv only) */
   fupr_conv_shape conv;  /* conv: its shape.  maxpool: R = S = window, stride, pad */
   const void* packed;    /* [dev] conv only: blob from fupr_pack; must outlive the model */
-  uint32_t epilogue;     /* conv only: FUPR_FUSE_RELU | FUPR_FUSE_ADD | FUPR_FUSE_SCATTER */
+  uint32_t epilogue;     /* conv only: FUPR_FUSE_RELU | FUPR_FUSE_ADD | FUPR_FUSE_SCATTER | FUPR_FUSE_CAT */
   int32_t res_spatial_stride, res_c_offset; /* see fupr_residual */
   /* With FUPR_FUSE_SCATTER (which needs FUPR_FUSE_ADD, 16-bit types, spatial stride 1 and
    * channel offset 0): the operator is fupr_conv_scatter_fused on tensor `res`, updated in
@@ -347,6 +388,10 @@ typedef struct {
    * must be an intermediate tensor (not 0) that no later operator reads under its old
    * number, and the operator must not be the network's last.  NULL otherwise. */
   const int32_t* keep_idx;
+  /* With FUPR_FUSE_CAT (16-bit types): the operator is fupr_conv_cat_fused over tensor
+   * `in` and tensor `in2` (an earlier tensor) read at spatial stride in2_spatial_stride;
+   * conv.C = (channels of `in` rounded up to 32) + channels of `in2`.  Ignored otherwise. */
+  int32_t in2, in2_spatial_stride;
 } fupr_op_desc;
 
 typedef struct {

@@ -29,7 +29,7 @@ FUPR_OK = 0
 ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_MASK_EMPTY, ERR_BN_VAR = -1, -2, -3, -4, -5
 ERR_WORKSPACE, ERR_ALIGN, ERR_LAUNCH, ERR_ARG, ERR_LIMIT, ERR_BN_SCALE = -6, -7, -8, -9, -10, -11
 F32, BF16, F16 = 0, 1, 2
-FUSE_BN, FUSE_RELU, FUSE_ADD, FUSE_SCATTER = 1, 2, 4, 8
+FUSE_BN, FUSE_RELU, FUSE_ADD, FUSE_SCATTER, FUSE_CAT = 1, 2, 4, 8, 16
 OP_CONV, OP_MAXPOOL, OP_AVGPOOL = 0, 1, 2
 SHORTCUT_IDENTITY, SHORTCUT_SUBSAMPLE_PAD, SHORTCUT_PROJECTION = 0, 1, 2
 SCHEDULE_AUTO, SCHEDULE_PER_LAYER = 0, 1
@@ -61,7 +61,7 @@ class OpDesc(C.Structure):
     _fields_ = [("kind", C.c_int32), ("in_", C.c_int32), ("res", C.c_int32), ("conv", ConvShape),
                 ("packed", C.c_void_p), ("epilogue", C.c_uint32),
                 ("res_spatial_stride", C.c_int32), ("res_c_offset", C.c_int32),
-                ("keep_idx", C.c_void_p)]
+                ("keep_idx", C.c_void_p), ("in2", C.c_int32), ("in2_spatial_stride", C.c_int32)]
 
 
 class GraphDesc(C.Structure):
@@ -98,6 +98,7 @@ SIGNATURES = {
     "fupr_fold": (C.c_int32, [_SH, _F, _F, _F, _F, _F, _F, C.c_float, C.c_uint32, _F, _F]),
     "fupr_xconv_fuse": (C.c_int32, [_SH, _F, C.POINTER(Bn), _SH, _F, C.POINTER(Bn), C.c_int32, _SH, _F,
                                     C.POINTER(Bn), _F, C.POINTER(BnOut), _F, _F]),
+    "fupr_proj_concat": (C.c_int32, [_SH, _F, _F, _SH, _F, _F, _SH, _F, _F]),
     "fupr_prune_count": (C.c_int32, [C.c_int32, C.c_int32]),
     "fupr_select_filters": (C.c_int32, [_SH, _F, C.c_int32, C.c_int32, _U8]),
     "fupr_prune": (C.c_int32, [_SH, _F, _F, _U8, C.c_int32, _SH, C.POINTER(_F), _I32, _I32, _F, _F,
@@ -106,6 +107,8 @@ SIGNATURES = {
     "fupr_pack": (C.c_int32, [_SH, _F, _F, C.c_int, C.c_void_p]),
     "fupr_conv_fused": (C.c_int32, [_SH, _T, C.c_void_p, C.POINTER(Residual), C.c_uint32, _T,
                                     C.c_void_p]),
+    "fupr_conv_cat_fused": (C.c_int32, [_SH, _T, _T, C.c_int32, C.c_void_p, C.POINTER(Residual),
+                                        C.c_uint32, _T, C.c_void_p]),
     "fupr_conv_scatter_fused": (C.c_int32, [_SH, _T, C.c_void_p, C.c_void_p, C.c_uint32, _T,
                                             C.c_void_p]),
     "fupr_maxpool": (C.c_int32, [_T, C.c_int32, C.c_int32, C.c_int32, _T, C.c_void_p]),
@@ -218,6 +221,22 @@ def fupr_xconv_fuse(conv1, bn1, conv2, bn2, shortcut, proj=None, bnp=None):
     bn2f["beta"] = beta2
     return ({"W": W1_out, "stride": conv1["stride"], "pad": conv1["pad"]}, bn1f,
             {"W": W2_out, "stride": conv2["stride"], "pad": conv2["pad"]}, bn2f)
+
+
+def fupr_proj_concat(last, W, b, proj, Wp, bp):
+    """Returns (shape, W_cat, b_cat) of the last convolution with the projection
+    shortcut concatenated along the channels."""
+    W, Wp = _f32(W), _f32(Wp)
+    b = None if b is None else _f32(b)
+    bp = None if bp is None else _f32(bp)
+    c1p = (last.C + 31) // 32 * 32
+    W_out = np.empty((last.K, c1p + proj.C, 1, 1), dtype=np.float32)
+    b_out = np.empty(last.K, dtype=np.float32)
+    out = ConvShape()
+    st = _lib.fupr_proj_concat(C.byref(last), _fp(W), _fp(b), C.byref(proj), _fp(Wp), _fp(bp),
+                               C.byref(out), _fp(W_out), _fp(b_out))
+    _check(st, "fupr_proj_concat")
+    return out, W_out, b_out
 
 
 def fupr_prune_count(n, permille):
@@ -364,6 +383,20 @@ def fupr_conv_fused(shape, x, packed, res, epilogue_flags, y, stream=None):
                               None if r is None else C.byref(r), int(epilogue_flags), C.byref(ys),
                               stream if stream is not None else current_stream())
     _check(st, "fupr_conv_fused")
+
+
+def fupr_conv_cat_fused(shape, x1, x2, x2_stride, packed, res, epilogue_flags, y, stream=None):
+    """The convolution over [x1 ; x2] (x2 read at spatial stride x2_stride); other
+    arguments as in fupr_conv_fused."""
+    x1s, x2s, ys = x1.struct, x2.struct, y.struct
+    r = None
+    if res is not None:
+        r = Residual(res[0].struct, int(res[1]), int(res[2]))
+    st = _lib.fupr_conv_cat_fused(C.byref(shape), C.byref(x1s), C.byref(x2s), int(x2_stride),
+                                  C.c_void_p(packed.data_ptr()), None if r is None else C.byref(r),
+                                  int(epilogue_flags), C.byref(ys),
+                                  stream if stream is not None else current_stream())
+    _check(st, "fupr_conv_cat_fused")
 
 
 def fupr_conv_scatter_fused(shape, x, packed, keep_idx, epilogue_flags, y, stream=None):

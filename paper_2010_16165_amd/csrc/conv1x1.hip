@@ -58,6 +58,11 @@ struct StreamParams {
   int Kp2, cpt2, hcs, relu2;
   int w_lds_bytes;       // LDS bytes of the first convolution's filters
   int n_tiles;           // 16-pixel tiles
+  // second input tensor: chunks from `split` on come from x2 at spatial stride
+  // stride2 (split is a multiple of 4; 1 << 30 when there is no second tensor)
+  const uint16_t* x2;
+  uint32_t x2_bytes;
+  int split, H2, W2, xcs2, stride2;
 };
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -78,8 +83,12 @@ __device__ __forceinline__ uint32_t clamp_below2(uint32_t v, uint32_t floor2) {
 // wave's finished 16-pixel tile, rounded as it is stored, is at once the pixel
 // operand of the second convolution, whose output is stored as well; the
 // second layer never reads the first one's output from memory.
-template <bool BF, int NT, int KMAX, int NT2>
-__global__ __launch_bounds__(256) void conv1x1_stream_kernel(const StreamParams p) {
+// THREADS: 256, two workgroups to a compute unit; or 512, one workgroup whose
+// eight waves share one copy of the filters, for the pairs whose two filter sets
+// do not fit LDS twice.
+template <bool BF, int NT, int KMAX, int NT2, int THREADS = 256>
+__global__ __launch_bounds__(THREADS) void conv1x1_stream_kernel(const StreamParams p) {
+  constexpr int kWaves = THREADS / 64;
   constexpr int NF = NT * 16;
   constexpr int NF2 = NT2 * 16;
   extern __shared__ uint4 lds4[];
@@ -97,6 +106,8 @@ __global__ __launch_bounds__(256) void conv1x1_stream_kernel(const StreamParams 
 
   const __amdgpu_buffer_rsrc_t xrsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.x), 0, p.x_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t x2rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.x2), 0, p.x2_bytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t wrsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.w), 0, p.w_bytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t yrsrc =
@@ -118,7 +129,7 @@ __global__ __launch_bounds__(256) void conv1x1_stream_kernel(const StreamParams 
     wr[3] = 0x00020000;
     const uint32_t wts_lds = (uint32_t)(uintptr_t)(LdsPtr)wts;
     const int n_slots = p.ksteps * 4 * NF;
-    for (int base = wave * 64; base < n_slots; base += 256) {
+    for (int base = wave * 64; base < n_slots; base += THREADS) {
       const int e = base + lane;
       const int chunk = e / NF, f = e - chunk * NF;
       const bool ok = e < n_slots && chunk < p.cpt && f0 + f < p.Kp;
@@ -132,7 +143,7 @@ __global__ __launch_bounds__(256) void conv1x1_stream_kernel(const StreamParams 
           : "memory", "m0");
     }
   }
-  for (int e = tid; e < NF; e += 256) bias_lds[e] = f0 + e < p.Kp ? p.bias[f0 + e] : 0.f;
+  for (int e = tid; e < NF; e += THREADS) bias_lds[e] = f0 + e < p.Kp ? p.bias[f0 + e] : 0.f;
   if constexpr (NT2 > 0) {
     const uint64_t wa = reinterpret_cast<uint64_t>(p.w2);
     i32x4 wr;
@@ -142,7 +153,7 @@ __global__ __launch_bounds__(256) void conv1x1_stream_kernel(const StreamParams 
     wr[3] = 0x00020000;
     const uint32_t wts2_lds = (uint32_t)(uintptr_t)(LdsPtr)wts2;
     constexpr int n_slots2 = (NT / 2) * 4 * NF2;
-    for (int base = wave * 64; base < n_slots2; base += 256) {
+    for (int base = wave * 64; base < n_slots2; base += THREADS) {
       const int e = base + lane;
       const int chunk = e / NF2, f = e - chunk * NF2;
       const bool ok = e < n_slots2 && chunk < p.cpt2 && f < p.Kp2;
@@ -155,12 +166,12 @@ __global__ __launch_bounds__(256) void conv1x1_stream_kernel(const StreamParams 
           : "s"(wts2_lds + base * 16), "v"(off), "s"(wr)
           : "memory", "m0");
     }
-    for (int e = tid; e < NF2; e += 256) bias2_lds[e] = e < p.Kp2 ? p.bias2[e] : 0.f;
+    for (int e = tid; e < NF2; e += THREADS) bias2_lds[e] = e < p.Kp2 ? p.bias2[e] : 0.f;
   }
 
   // ---- this wave's tiles -------------------------------------------------------------
-  const int n_waves = gridDim.x * 4;
-  int tile = blockIdx.x * 4 + wave;
+  const int n_waves = gridDim.x * kWaves;
+  int tile = blockIdx.x * kWaves + wave;
   uint4 bn[KMAX] = {};
   static_assert(NT % 2 == 0, "filter tiles are handled in pairs");
   constexpr int NP = NT / 2;
@@ -169,7 +180,7 @@ __global__ __launch_bounds__(256) void conv1x1_stream_kernel(const StreamParams 
   uint32_t yoff_n = kOutside, hoff_n = kOutside;
   auto fetch = [&](int t) {
     const int m = t * 16 + li;
-    uint32_t xo = kOutside, ro = kOutside;
+    uint32_t xo = kOutside, ro = kOutside, xo2 = kOutside;
     yoff_n = kOutside;
     hoff_n = kOutside;
     if (m < p.M) {
@@ -178,19 +189,29 @@ __global__ __launch_bounds__(256) void conv1x1_stream_kernel(const StreamParams 
       if (p.plain) {
         xo = (uint32_t)m * (uint32_t)(p.xcs * 2);
         ro = (uint32_t)m * (uint32_t)(p.rcs * 2);
-      } else {
+      }
+      if (!p.plain || p.x2) {
         const int n = m / p.PQ, rem = m - n * p.PQ;
         const int pp = rem / p.Q, qq = rem - pp * p.Q;
-        xo = (uint32_t)(((n * p.H + pp * p.stride) * p.W + qq * p.stride) * p.xcs) * 2u;
-        ro = (uint32_t)(((n * p.rH + pp * p.rss) * p.rW + qq * p.rss) * p.rcs) * 2u;
+        if (!p.plain) {
+          xo = (uint32_t)(((n * p.H + pp * p.stride) * p.W + qq * p.stride) * p.xcs) * 2u;
+          ro = (uint32_t)(((n * p.rH + pp * p.rss) * p.rW + qq * p.rss) * p.rcs) * 2u;
+        }
+        xo2 = (uint32_t)(((n * p.H2 + pp * p.stride2) * p.W2 + qq * p.stride2) * p.xcs2) * 2u;
       }
     }
 #pragma unroll
     for (int k = 0; k < KMAX; ++k) {
       if (k < p.ksteps) {
         const int chunk = k * 4 + g;
-        const uint32_t off = chunk * 8 < p.xcs ? xo + (uint32_t)chunk * 16u : kOutside;
-        bn[k] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, off, 0, 0));
+        if (k * 4 < p.split) {   // a whole step comes from one tensor
+          const uint32_t off = chunk * 8 < p.xcs ? xo + (uint32_t)chunk * 16u : kOutside;
+          bn[k] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, off, 0, 0));
+        } else {
+          const int c2 = chunk - p.split;
+          const uint32_t off = c2 * 8 < p.xcs2 ? xo2 + (uint32_t)c2 * 16u : kOutside;
+          bn[k] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(x2rsrc, off, 0, 0));
+        }
       }
     }
     if (p.res) {
@@ -358,17 +379,18 @@ int pick_stream(const Conv16Params& c) {
   return best;
 }
 
-template <bool BF, int NT, int KMAX, int NT2 = 0>
+template <bool BF, int NT, int KMAX, int NT2 = 0, int THREADS = 256>
 fupr_status launch_stream(const StreamParams& p, dim3 grid, size_t lds, hipStream_t st) {
   static std::once_flag once;
   static hipError_t status = hipSuccess;
   std::call_once(once, [] {
     status = hipFuncSetAttribute(
-        reinterpret_cast<const void*>(&conv1x1_stream_kernel<BF, NT, KMAX, NT2>),
-        hipFuncAttributeMaxDynamicSharedMemorySize, kStreamFusedLdsLimit);
+        reinterpret_cast<const void*>(&conv1x1_stream_kernel<BF, NT, KMAX, NT2, THREADS>),
+        hipFuncAttributeMaxDynamicSharedMemorySize,
+        THREADS == 256 ? kStreamFusedLdsLimit : 2 * kStreamFusedLdsLimit);
   });
   if (status != hipSuccess) return FUPR_ERR_LAUNCH;
-  hipLaunchKernelGGL((conv1x1_stream_kernel<BF, NT, KMAX, NT2>), grid, dim3(256), lds, st, p);
+  hipLaunchKernelGGL((conv1x1_stream_kernel<BF, NT, KMAX, NT2, THREADS>), grid, dim3(THREADS), lds, st, p);
   return launch_status("conv1x1_stream_kernel");
 }
 
@@ -402,7 +424,9 @@ bool fill_stream_params(const Conv16Params& c, int N, StreamParams* out) {
   p.x = c.x; p.w = c.w; p.bias = c.bias; p.res = c.res; p.y = c.y;
   const uint64_t y_bytes = (uint64_t)c.M * c.ycs * 2;
   const uint64_t res_bytes = c.res ? (uint64_t)N * c.rH * c.rW * c.rcs * 2 : 0;
-  if ((uint64_t)c.x_bytes >= kOutside || y_bytes >= kOutside || res_bytes >= kOutside) return false;
+  if ((uint64_t)c.x_bytes >= kOutside || y_bytes >= kOutside || res_bytes >= kOutside ||
+      (uint64_t)c.x2_bytes >= kOutside)
+    return false;
   p.x_bytes = c.x_bytes; p.w_bytes = c.w_bytes;
   p.y_bytes = (uint32_t)y_bytes; p.res_bytes = (uint32_t)res_bytes;
   p.H = c.H; p.W = c.W; p.xcs = c.xcs;
@@ -412,13 +436,17 @@ bool fill_stream_params(const Conv16Params& c, int N, StreamParams* out) {
   p.rH = c.rH; p.rW = c.rW; p.rcs = c.rcs; p.rss = c.rss; p.roff = c.roff;
   p.relu = c.relu;
   p.plain = c.stride == 1 && (!c.res || (c.rss == 1 && c.rH == c.P && c.rW == c.Q));
+  p.x2 = c.x2; p.x2_bytes = c.x2_bytes;
+  p.split = c.x2 ? c.split : (1 << 30);
+  p.H2 = c.H2; p.W2 = c.W2; p.xcs2 = c.xcs2; p.stride2 = c.stride2;
   p.n_tiles = (c.M + 15) / 16;
   *out = p;
   return true;
 }
 
 // Which 16-tile variant (2 or 4 steps) and how many second-layer filter tiles a
-// fused pair needs; false if the pair is not for the fused kernel.
+// fused pair needs; false if the pair is not for the fused kernel.  A pair whose
+// filters fit LDS only once runs as one workgroup of eight waves per compute unit.
 bool plan_fused(const Conv16Params& c1, const Conv16Params& c2, int* kmax, int* nt2, size_t* lds) {
   if (tuning_off("conv1x1_fuse")) return false;
   const int t = pick_stream(c1);
@@ -431,7 +459,7 @@ bool plan_fused(const Conv16Params& c1, const Conv16Params& c2, int* kmax, int* 
   const int ksteps = (c1.cpt + 3) / 4;
   *lds = stream_lds_bytes(kStreamTiles[t], ksteps) + (size_t)*nt2 * 16 * 4 +
          (size_t)8 * 4 * *nt2 * 16 * 16;
-  return *lds <= (size_t)kStreamFusedLdsLimit;
+  return *lds <= (size_t)kStreamFusedLdsLimit || (*kmax == 4 && *lds <= 2 * (size_t)kStreamFusedLdsLimit);
 }
 
 }  // namespace
@@ -472,10 +500,12 @@ fupr_status launch_conv1x1_fused_pair(const Conv16Params& c1, const Conv16Params
   p.w2_bytes = c2.w_bytes; p.h_bytes = (uint32_t)h_bytes;
   p.Kp2 = c2.Kp; p.cpt2 = c2.cpt; p.hcs = c2.ycs; p.relu2 = c2.relu;
   p.w_lds_bytes = (int)round_up_sz((size_t)p.ksteps * 4 * 16 * 16 * 16, 1024);
-  const int gx = std::min((p.n_tiles + 3) / 4, 2 * stream_compute_units());
+  const bool wide = lds > (size_t)kStreamFusedLdsLimit;   // eight waves share the filters
+  const int gx = wide ? std::min((p.n_tiles + 7) / 8, stream_compute_units())
+                      : std::min((p.n_tiles + 3) / 4, 2 * stream_compute_units());
   const dim3 grid((unsigned)gx, 1u);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-  const int key = (bf16 ? 100 : 0) + kmax * 10 + nt2;
+  const int key = (bf16 ? 100 : 0) + kmax * 10 + nt2 + (wide ? 1000 : 0);
   switch (key) {
     case 122: return launch_stream<true, 16, 2, 2>(p, grid, lds, st);
     case 124: return launch_stream<true, 16, 2, 4>(p, grid, lds, st);
@@ -484,7 +514,12 @@ fupr_status launch_conv1x1_fused_pair(const Conv16Params& c1, const Conv16Params
     case 22: return launch_stream<false, 16, 2, 2>(p, grid, lds, st);
     case 24: return launch_stream<false, 16, 2, 4>(p, grid, lds, st);
     case 42: return launch_stream<false, 16, 4, 2>(p, grid, lds, st);
-    default: return launch_stream<false, 16, 4, 4>(p, grid, lds, st);
+    case 44: return launch_stream<false, 16, 4, 4>(p, grid, lds, st);
+    case 1142: return launch_stream<true, 16, 4, 2, 512>(p, grid, lds, st);
+    case 1144: return launch_stream<true, 16, 4, 4, 512>(p, grid, lds, st);
+    case 1042: return launch_stream<false, 16, 4, 2, 512>(p, grid, lds, st);
+    case 1044: return launch_stream<false, 16, 4, 4, 512>(p, grid, lds, st);
+    default: return FUPR_ERR_LIMIT;
   }
 }
 

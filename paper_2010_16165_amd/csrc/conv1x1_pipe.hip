@@ -51,6 +51,11 @@ struct PipeParams {
   int fgroups, tiles;
   int tiles_q, tiles_r;  // tiles / grid, tiles % grid
   FastDiv divPQ, divQ, divF;
+  // second input tensor: chunks from `split` on come from x2 at spatial stride
+  // stride2 (split is a multiple of 4; 1 << 30 when there is no second tensor)
+  const uint16_t* x2;
+  uint32_t x2_bytes;
+  int split, H2, W2, xcs2, stride2;
 };
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
@@ -132,8 +137,10 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv1x1_pipe_ke
     // ================================ loading waves ================================
     const int lw = wave - NWC;
     const i32x4 xrsrc = pipe_rsrc(p.x, p.x_bytes), wrsrc = pipe_rsrc(p.w, p.w_bytes);
+    const i32x4 x2rsrc = pipe_rsrc(p.x2, p.x2_bytes);
     // pixel slot s = ((step * 2 + plane) * BM + pixel) * 2 + half
     uint32_t poff[kPixelLoads];    // byte offset in x of the slot's pixel; kOutside: none
+    uint32_t poff2[kPixelLoads];   // likewise in x2
     int l_f0 = 0;
     auto setup_load = [&](int tile) {
       const int strip = div_by(tile, p.divF);
@@ -143,17 +150,19 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv1x1_pipe_ke
       for (int i = 0; i < kPixelLoads; ++i) {
         const int s = (i * kLoaderWaves + lw) * 64 + lane;
         const int m = m0 + ((s >> 1) % BM);
-        uint32_t off = kOutside;
+        uint32_t off = kOutside, off2 = kOutside;
         if (m < p.M) {
-          if (p.plain) {
-            off = (uint32_t)m * (uint32_t)(p.xcs * 2);
-          } else {
+          if (p.plain) off = (uint32_t)m * (uint32_t)(p.xcs * 2);
+          if (!p.plain || p.x2) {
             const int n = div_by(m, p.divPQ), rem = m - n * p.PQ;
             const int pp = div_by(rem, p.divQ), qq = rem - pp * p.Q;
-            off = (uint32_t)(((n * p.H + pp * p.stride) * p.W + qq * p.stride) * p.xcs) * 2u;
+            if (!p.plain)
+              off = (uint32_t)(((n * p.H + pp * p.stride) * p.W + qq * p.stride) * p.xcs) * 2u;
+            off2 = (uint32_t)(((n * p.H2 + pp * p.stride2) * p.W2 + qq * p.stride2) * p.xcs2) * 2u;
           }
         }
         poff[i] = off;
+        poff2[i] = off2;
       }
     };
     auto issue = [&](int unit, uint32_t dst) {
@@ -171,8 +180,17 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv1x1_pipe_ke
         const int sbase = (i * kLoaderWaves + lw) * 64, s = sbase + lane;
         const int half = s & 1, sp = (s >> 1) / BM;        // sp = step * 2 + plane
         const int chunk = unit * (kSteps * 4) + sp * 2 + half;
-        const uint32_t off = chunk * 8 < p.xcs ? poff[i] + (uint32_t)chunk * 16u : kOutside;
-        pipe_load_to_lds(xrsrc, off, dst + kWeightBytes + sbase * 16);
+        // the 64 slots of one load lie in one plane of 16 channels, and the second
+        // tensor starts at a multiple of 32 channels: one tensor per load
+        const int first = __builtin_amdgcn_readfirstlane(unit * (kSteps * 4) + (sbase >> 1) / BM * 2);
+        if (first < p.split) {
+          const uint32_t off = chunk * 8 < p.xcs ? poff[i] + (uint32_t)chunk * 16u : kOutside;
+          pipe_load_to_lds(xrsrc, off, dst + kWeightBytes + sbase * 16);
+        } else {
+          const int c2 = chunk - p.split;
+          const uint32_t off = c2 * 8 < p.xcs2 ? poff2[i] + (uint32_t)c2 * 16u : kOutside;
+          pipe_load_to_lds(x2rsrc, off, dst + kWeightBytes + sbase * 16);
+        }
       }
     };
 
@@ -451,7 +469,8 @@ fupr_status launch_conv1x1_pipe(const Conv16Params& c, int N, bool bf16, void* s
   p.x = c.x; p.w = c.w; p.bias = c.bias; p.res = c.res; p.y = c.y;
   const uint64_t y_bytes = (uint64_t)c.M * c.ycs * 2;
   const uint64_t res_bytes = c.res ? (uint64_t)N * c.rH * c.rW * c.rcs * 2 : 0;
-  if ((uint64_t)c.x_bytes >= kOutside || y_bytes >= kOutside || res_bytes >= kOutside)
+  if ((uint64_t)c.x_bytes >= kOutside || y_bytes >= kOutside || res_bytes >= kOutside ||
+      (uint64_t)c.x2_bytes >= kOutside)
     return FUPR_ERR_LIMIT;
   p.x_bytes = c.x_bytes; p.w_bytes = c.w_bytes;
   p.y_bytes = (uint32_t)y_bytes; p.res_bytes = (uint32_t)res_bytes;
@@ -470,6 +489,9 @@ fupr_status launch_conv1x1_pipe(const Conv16Params& c, int N, bool bf16, void* s
   p.divPQ = fast_div(c.PQ);
   p.divQ = fast_div(c.Q);
   p.divF = fast_div(plan.fgroups);
+  p.x2 = c.x2; p.x2_bytes = c.x2_bytes;
+  p.split = c.x2 ? c.split : (1 << 30);
+  p.H2 = c.H2; p.W2 = c.W2; p.xcs2 = c.xcs2; p.stride2 = c.stride2;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   return bf16 ? dispatch_pipe<true>(p, plan, st) : dispatch_pipe<false>(p, plan, st);
 }

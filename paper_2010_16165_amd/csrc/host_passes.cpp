@@ -170,6 +170,32 @@ extern "C" fupr_status fupr_xconv_fuse(const fupr_conv_shape* conv1, const float
 }
 
 // Alg. 1: a non-fused operator loses p_phi * n filters.
+// Sec. IV-B-1, projection-shortcut recipe: the shortcut's 1 x 1 convolution
+// concatenated to the block's last 1 x 1 convolution along the channels.
+extern "C" fupr_status fupr_proj_concat(const fupr_conv_shape* last, const float* W, const float* b,
+                                        const fupr_conv_shape* proj, const float* Wp,
+                                        const float* bp, fupr_conv_shape* out, float* W_out,
+                                        float* b_out) {
+  if (!last || !W || !proj || !Wp || !out || !W_out || !b_out) return FUPR_ERR_NULL;
+  if (!shape_ok(last) || !shape_ok(proj)) return FUPR_ERR_SHAPE;
+  if (last->R != 1 || last->S != 1 || proj->R != 1 || proj->S != 1 || last->pad != 0 ||
+      proj->pad != 0 || last->stride != 1 || last->K != proj->K)
+    return FUPR_ERR_SHAPE;
+  const int K = last->K, C1 = last->C, C2 = proj->C;
+  const int C1p = fupr::round_up(C1, 32);
+  if ((int64_t)K * (C1p + C2) >= (int64_t(1) << 31)) return FUPR_ERR_SHAPE;
+  const size_t C = (size_t)C1p + C2;
+  for (int k = 0; k < K; ++k) {
+    float* row = W_out + (size_t)k * C;
+    std::copy(W + (size_t)k * C1, W + (size_t)(k + 1) * C1, row);
+    std::fill(row + C1, row + C1p, 0.0f);
+    std::copy(Wp + (size_t)k * C2, Wp + (size_t)(k + 1) * C2, row + C1p);
+    b_out[k] = (b ? b[k] : 0.0f) + (bp ? bp[k] : 0.0f);
+  }
+  *out = fupr_conv_shape{K, C1p + C2, 1, 1, 1, 0};
+  return FUPR_OK;
+}
+
 extern "C" int32_t fupr_prune_count(int32_t n, int32_t permille) {
   if (n <= 0 || permille < 0 || permille > 1000) return FUPR_ERR_ARG;
   const int64_t cut = ((int64_t)n * permille) / 1000;

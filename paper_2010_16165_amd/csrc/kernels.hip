@@ -266,6 +266,12 @@ Conv16Params params16(const ConvArgs& a) {
   p.x_bytes = (uint32_t)((int64_t)a.N * a.H * a.W * a.xcs * 2);
   p.w_bytes = (uint32_t)((size_t)L.nchunk_pad * L.Kp * 16);
   p.keep = a.keep; p.keep_n = a.K; p.yC = a.yC;
+  p.x2 = (const uint16_t*)a.x2;
+  if (a.x2) {
+    p.x2_bytes = (uint32_t)((int64_t)a.N * a.H2 * a.W2 * a.xcs2 * 2);
+    p.split = a.split_c / 8;
+    p.H2 = a.H2; p.W2 = a.W2; p.xcs2 = a.xcs2; p.stride2 = a.stride2;
+  }
   return p;
 }
 
@@ -274,7 +280,10 @@ Conv16Params params16(const ConvArgs& a) {
 // the last stages; the streaming kernel wins where pixels are many and filters few.
 bool prefer_pipe(const Conv16Params& g) {
   // (a stride-2 projection from 256 channels: 32.1 against 35.5 us at 56 x 56, batch 64)
-  return conv1x1_pipe_applies(g) && (g.cpt >= 64 || g.M <= 16384 || (g.stride == 2 && g.cpt >= 32));
+  // (two input tensors, the second a strided block input, from 256 channels on: the streaming
+  // kernel would re-read both tensors once per group of 64 filters)
+  return conv1x1_pipe_applies(g) &&
+         (g.cpt >= 64 || g.M <= 16384 || ((g.stride == 2 || g.x2) && g.cpt >= 32));
 }
 
 }  // namespace
@@ -318,6 +327,12 @@ fupr_status launch_conv(const ConvArgs& a, void* stream) {
     return launch_status(__func__);
   }
   const Conv16Params p = params16(a);
+  if (a.x2) {   // two input tensors: the two 1 x 1 kernels read them
+    if (prefer_pipe(p)) return launch_conv1x1_pipe(p, a.N, a.dt == FUPR_BF16, stream);
+    if (conv1x1_stream_applies(p)) return launch_conv1x1_stream(p, a.N, a.dt == FUPR_BF16, stream);
+    if (conv1x1_pipe_applies(p)) return launch_conv1x1_pipe(p, a.N, a.dt == FUPR_BF16, stream);
+    return FUPR_ERR_LIMIT;
+  }
   if (a.R == 3 && conv_patch_applies(p, a.N)) return launch_conv_patch(p, a.N, a.dt == FUPR_BF16, stream);
   // the indexed epilogue exists in the 3 x 3 kernel above and in the general one
   if (a.keep) return launch_conv16_tiled(p, a.dt == FUPR_BF16, stream);
@@ -418,6 +433,52 @@ extern "C" fupr_status fupr_conv_fused(const fupr_conv_shape* shape, const fupr_
   return st != FUPR_OK ? st : launch_conv(a, stream);
 }
 
+namespace {
+
+// Validates a convolution over two concatenated tensors: x1 as an ordinary 1 x 1
+// convolution of its own channels, then x2 and the split.
+fupr_status check_conv_cat(const fupr_conv_shape* shape, const fupr_tensor* x1, const fupr_tensor* x2,
+                           int32_t x2_stride, const void* packed, const fupr_residual* res,
+                           uint32_t epilogue_flags, const fupr_tensor* y, ConvArgs* out) {
+  if (!shape || !x1 || !x2) return FUPR_ERR_NULL;
+  if (!shape_ok(shape)) return FUPR_ERR_SHAPE;
+  if (shape->R != 1 || shape->S != 1 || shape->stride != 1 || shape->pad != 0) return FUPR_ERR_SHAPE;
+  if (x2_stride != 1 && x2_stride != 2) return FUPR_ERR_ARG;
+  fupr_conv_shape own = *shape;   // the part that reads x1
+  own.C = x1->C;
+  ConvArgs a;
+  fupr_status st = check_conv(&own, x1, packed, res, epilogue_flags, y, &a);
+  if (st != FUPR_OK) return st;
+  st = check_tensor(x2);
+  if (st != FUPR_OK) return st;
+  if (x1->dt == FUPR_F32) return FUPR_ERR_DTYPE;
+  if (x2->dt != x1->dt) return FUPR_ERR_DTYPE;
+  const int split = round_up(x1->C, 32);
+  if (shape->C != split + x2->C || x2->N != x1->N) return FUPR_ERR_SHAPE;
+  if ((int64_t)(a.P - 1) * x2_stride >= x2->H || (int64_t)(a.Q - 1) * x2_stride >= x2->W)
+    return FUPR_ERR_SHAPE;
+  if (x2->ptr == y->ptr) return FUPR_ERR_ARG;
+  a.C = shape->C;
+  a.x2 = x2->ptr;
+  a.H2 = x2->H; a.W2 = x2->W; a.xcs2 = x2->c_stride; a.stride2 = x2_stride;
+  a.split_c = split;
+  *out = a;
+  return FUPR_OK;
+}
+
+}  // namespace
+
+extern "C" fupr_status fupr_conv_cat_fused(const fupr_conv_shape* shape, const fupr_tensor* x1,
+                                           const fupr_tensor* x2, int32_t x2_spatial_stride,
+                                           const void* packed, const fupr_residual* res,
+                                           uint32_t epilogue_flags, const fupr_tensor* y,
+                                           void* stream) {
+  ConvArgs a;
+  const fupr_status st =
+      check_conv_cat(shape, x1, x2, x2_spatial_stride, packed, res, epilogue_flags, y, &a);
+  return st != FUPR_OK ? st : launch_conv(a, stream);
+}
+
 extern "C" fupr_status fupr_conv_scatter_fused(const fupr_conv_shape* shape, const fupr_tensor* x,
                                                const void* packed, const int32_t* keep_idx,
                                                uint32_t epilogue_flags, const fupr_tensor* y,
@@ -452,6 +513,22 @@ extern "C" fupr_status fupr_conv_conv1x1_fused(const fupr_conv_shape* shape1, co
   if (st != FUPR_OK) return st;
   if (h->ptr == x->ptr || (res && h->ptr == res->t.ptr)) return FUPR_ERR_ARG;
   if (a.dt == FUPR_F32) return FUPR_ERR_LIMIT;
+  const Conv16Params p1 = params16(a), p2 = params16(b);
+  if (!conv1x1_fused_pair_applies(p1, p2)) return FUPR_ERR_LIMIT;
+  return launch_conv1x1_fused_pair(p1, p2, a.N, a.dt == FUPR_BF16, stream);
+}
+
+fupr_status fupr::conv_cat_conv1x1_fused(const fupr_conv_shape* shape1, const fupr_tensor* x1,
+                                         const fupr_tensor* x2, int32_t x2_stride,
+                                         const void* packed1, uint32_t flags1, const fupr_tensor* y,
+                                         const fupr_conv_shape* shape2, const void* packed2,
+                                         uint32_t flags2, const fupr_tensor* h, void* stream) {
+  ConvArgs a, b;
+  fupr_status st = check_conv_cat(shape1, x1, x2, x2_stride, packed1, nullptr, flags1, y, &a);
+  if (st != FUPR_OK) return st;
+  st = check_conv(shape2, y, packed2, nullptr, flags2, h, &b);
+  if (st != FUPR_OK) return st;
+  if (h->ptr == x1->ptr || h->ptr == x2->ptr) return FUPR_ERR_ARG;
   const Conv16Params p1 = params16(a), p2 = params16(b);
   if (!conv1x1_fused_pair_applies(p1, p2)) return FUPR_ERR_LIMIT;
   return launch_conv1x1_fused_pair(p1, p2, a.N, a.dt == FUPR_BF16, stream);

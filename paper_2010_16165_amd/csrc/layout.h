@@ -64,11 +64,22 @@ struct ConvArgs {
   fupr_dtype dt;
   const int32_t* keep;   // device, K entries: filter j adds into channel keep[j] of y; else nullptr
   int yC;                // with keep: channels of y
+  // second input of a convolution over two concatenated tensors; x2 = nullptr otherwise
+  const void* x2;
+  int H2, W2, xcs2, stride2;
+  int split_c;           // input channels taken from x (a multiple of 32); the others come from x2
 };
 fupr_status launch_conv(const ConvArgs& a, void* stream);
 // indexed: the convolution adds into listed channels of a wider tensor (ConvArgs::keep)
 const char* conv_kernel_name(const fupr_conv_shape& s, fupr_dtype dt, int N, int H, int W,
                              bool indexed = false);
+// fupr_conv_cat_fused followed by a 1 x 1 convolution of its output, in one launch
+// (what fupr_conv_conv1x1_fused is to fupr_conv_fused); for the model executor.
+fupr_status conv_cat_conv1x1_fused(const fupr_conv_shape* shape1, const fupr_tensor* x1,
+                                   const fupr_tensor* x2, int32_t x2_stride, const void* packed1,
+                                   uint32_t flags1, const fupr_tensor* y,
+                                   const fupr_conv_shape* shape2, const void* packed2,
+                                   uint32_t flags2, const fupr_tensor* h, void* stream);
 // Shapes only: can convolution s1 on an N x H x W input and convolution s2 on its
 // output run as one launch (fupr_conv_conv1x1_fused)?
 bool conv_pair_fusable(const fupr_conv_shape& s1, const fupr_conv_shape& s2, fupr_dtype dt, int N,

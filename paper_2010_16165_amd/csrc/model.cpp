@@ -208,7 +208,7 @@ void plan_resident(fupr_model* m) {
   // every LDS tensor larger than 1 x 1 gets a ring of hp zero pixels
   int hp = 0;
   for (const fupr_op_desc& op : m->ops) {
-    if (op.kind == FUPR_OP_CONV && (op.epilogue & FUPR_FUSE_SCATTER)) return;   // per-operator kernels only
+    if (op.kind == FUPR_OP_CONV && (op.epilogue & (FUPR_FUSE_SCATTER | FUPR_FUSE_CAT))) return;   // per-operator kernels only
     if (op.kind == FUPR_OP_CONV) hp = std::max(hp, op.conv.pad);
     else if (op.kind != FUPR_OP_AVGPOOL) return;   // max-pool networks: images too large for LDS
   }
@@ -547,11 +547,28 @@ extern "C" fupr_status fupr_model_create(const fupr_graph_desc* g, fupr_model** 
       const fupr_conv_shape& s = op.conv;
       if (!shape_ok(&s)) { err = FUPR_ERR_SHAPE; break; }
       if (!op.packed) { err = FUPR_ERR_NULL; break; }
-      if (s.C != tin.C || tin.H + 2 * s.pad < s.R || tin.W + 2 * s.pad < s.S) {
-        err = FUPR_ERR_SHAPE; break;
-      }
-      if (op.epilogue & ~uint32_t(FUPR_FUSE_RELU | FUPR_FUSE_ADD | FUPR_FUSE_SCATTER)) {
+      if (op.epilogue & ~uint32_t(FUPR_FUSE_RELU | FUPR_FUSE_ADD | FUPR_FUSE_SCATTER | FUPR_FUSE_CAT)) {
         err = FUPR_ERR_ARG; break;
+      }
+      const bool cat = (op.epilogue & FUPR_FUSE_CAT) != 0;
+      int c_in = tin.C;
+      if (cat) {
+        // a 1 x 1 convolution over tensor `in` and tensor `in2` concatenated along the channels
+        if (g->dt == FUPR_F32) { err = FUPR_ERR_DTYPE; break; }
+        if (op.in2 < 0 || op.in2 > i || (op.in2_spatial_stride != 1 && op.in2_spatial_stride != 2) ||
+            (op.epilogue & FUPR_FUSE_SCATTER)) {
+          err = FUPR_ERR_ARG; break;
+        }
+        const TensorInfo& t2 = m->tensors[op.in2];
+        if (s.R != 1 || s.S != 1 || s.stride != 1 || s.pad != 0 ||
+            (int64_t)(tin.H - 1) * op.in2_spatial_stride >= t2.H ||
+            (int64_t)(tin.W - 1) * op.in2_spatial_stride >= t2.W) {
+          err = FUPR_ERR_SHAPE; break;
+        }
+        c_in = round_up(tin.C, 32) + t2.C;
+      }
+      if (s.C != c_in || tin.H + 2 * s.pad < s.R || tin.W + 2 * s.pad < s.S) {
+        err = FUPR_ERR_SHAPE; break;
       }
       const bool scatter = (op.epilogue & FUPR_FUSE_SCATTER) != 0;
       if (scatter != (op.keep_idx != nullptr)) { err = scatter ? FUPR_ERR_NULL : FUPR_ERR_ARG; break; }
@@ -614,6 +631,8 @@ extern "C" fupr_status fupr_model_create(const fupr_graph_desc* g, fupr_model** 
   for (int i = 0; i < n; ++i) {
     m->tensors[m->ops[i].in].last_use = i;
     if (m->ops[i].res >= 0) m->tensors[m->ops[i].res].last_use = i;
+    if (m->ops[i].kind == FUPR_OP_CONV && (m->ops[i].epilogue & FUPR_FUSE_CAT))
+      m->tensors[m->ops[i].in2].last_use = i;
   }
   // a tensor updated in place must have no reader after the update
   for (int i = 0; i < n; ++i) {
@@ -632,6 +651,10 @@ extern "C" fupr_status fupr_model_create(const fupr_graph_desc* g, fupr_model** 
     if (m->ops[i].res >= 0) {
       TensorInfo& tr = m->tensors[m->ops[i].res];
       tr.last_use = std::max(tr.last_use, i + 1);
+    }
+    if (m->ops[i].epilogue & FUPR_FUSE_CAT) {
+      TensorInfo& t2 = m->tensors[m->ops[i].in2];
+      t2.last_use = std::max(t2.last_use, i + 1);
     }
   }
   std::vector<int> holder;  // buffer -> tensor id it holds, -1 = free
@@ -820,6 +843,8 @@ bool conv_conv_pair(const fupr_model* m, size_t i) {
   const fupr_op_desc& b = m->ops[i + 1];
   if (a.kind != FUPR_OP_CONV || b.kind != FUPR_OP_CONV) return false;
   if ((a.epilogue | b.epilogue) & FUPR_FUSE_SCATTER) return false;
+  if (b.epilogue & FUPR_FUSE_CAT) return false;
+  if ((a.epilogue & FUPR_FUSE_CAT) && a.res >= 0) return false;
   if (b.in != (int)i + 1 || b.res >= 0) return false;
   const TensorInfo& tin = m->tensors[a.in];
   return conv_pair_fusable(a.conv, b.conv, m->dt, 1, tin.H, tin.W);
@@ -934,8 +959,15 @@ fupr_status run(const fupr_model* m, const fupr_tensor* input, const fupr_tensor
           r.spatial_stride = op.res_spatial_stride;
           r.c_offset = op.res_c_offset;
         }
-        st = fupr_conv_conv1x1_fused(&op.conv, &x, op.packed, add ? &r : nullptr, op.epilogue, &mid,
-                                     &second.conv, second.packed, second.epilogue, &y, on);
+        if (op.epilogue & FUPR_FUSE_CAT) {
+          const fupr_tensor x2 = view(op.in2, n0, count);
+          st = conv_cat_conv1x1_fused(&op.conv, &x, &x2, op.in2_spatial_stride, op.packed,
+                                      op.epilogue & ~uint32_t(FUPR_FUSE_CAT), &mid, &second.conv,
+                                      second.packed, second.epilogue, &y, on);
+        } else {
+          st = fupr_conv_conv1x1_fused(&op.conv, &x, op.packed, add ? &r : nullptr, op.epilogue, &mid,
+                                       &second.conv, second.packed, second.epilogue, &y, on);
+        }
       } else if (launches[l].count == 2) {
         const fupr_op_desc& pool = m->ops[i + 1];
         st = fupr_conv_maxpool_fused(&op.conv, &x, op.packed, pool.conv.R, pool.conv.stride,
@@ -951,7 +983,13 @@ fupr_status run(const fupr_model* m, const fupr_tensor* input, const fupr_tensor
           r.spatial_stride = op.res_spatial_stride;
           r.c_offset = op.res_c_offset;
         }
-        st = fupr_conv_fused(&op.conv, &x, op.packed, add ? &r : nullptr, op.epilogue, &y, on);
+        if (op.epilogue & FUPR_FUSE_CAT) {
+          const fupr_tensor x2 = view(op.in2, n0, count);
+          st = fupr_conv_cat_fused(&op.conv, &x, &x2, op.in2_spatial_stride, op.packed,
+                                   add ? &r : nullptr, op.epilogue & ~uint32_t(FUPR_FUSE_CAT), &y, on);
+        } else {
+          st = fupr_conv_fused(&op.conv, &x, op.packed, add ? &r : nullptr, op.epilogue, &y, on);
+        }
       } else if (op.kind == FUPR_OP_MAXPOOL) {
         st = fupr_maxpool(&x, op.conv.R, op.conv.stride, op.conv.pad, &y, on);
       } else {
@@ -1042,6 +1080,14 @@ extern "C" fupr_status fupr_model_op_stats(const fupr_model* m, int32_t batch, i
     double res_b = 0.0;
     if (d.res >= 0) res_b = es * (double)s.M * m->tensors[d.res].C;
     s.bytes = in_b + out_b + res_b + es * crs * d.conv.K + 4.0 * d.conv.K;
+    if (d.epilogue & FUPR_FUSE_CAT) {
+      // the second tensor's pixels that are read (one per output pixel); the zero
+      // channels between the two tensors are neither read nor multiplied
+      const double c2 = (double)m->tensors[d.in2].C;
+      s.bytes += es * (double)s.M * c2 - es * ((double)d.conv.C - ti.C - c2) * d.conv.K;
+      s.flops = 2.0 * (ti.C + c2) * d.conv.K * (double)s.M;
+      s.C = ti.C + (int)c2;
+    }
     const bool scatter = (d.epilogue & FUPR_FUSE_SCATTER) != 0;
     if (scatter)   // conv.K channels of the updated tensor read and written, and the index list
       s.bytes = in_b + 2.0 * es * (double)s.M * d.conv.K + es * crs * d.conv.K + 8.0 * d.conv.K;

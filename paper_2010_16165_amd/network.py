@@ -16,8 +16,10 @@ from . import binding as B
 class Layer:
     """One convolution site of the optimised network (host side)."""
 
-    def __init__(self, site, W, bias, stride, pad, relu, add=False, keep=None):
+    def __init__(self, site, W, bias, stride, pad, relu, add=False, keep=None, cat_stride=0):
         self.site = site
+        self.cat_stride = cat_stride   # > 0: the last convolution with the block's projection
+                                       # shortcut concatenated; the block input is read at this stride
         self.keep = keep        # int32 channels of the block output the kept filters add into
         self.W = W              # folded, compacted, float32 K x C x R x S
         self.bias = bias        # float32 K
@@ -50,7 +52,8 @@ def _aggressive(blk):
             "prune_counts": [c1["W"].shape[0] - k1, 0], "shortcut": {"kind": "none"}}
 
 
-def optimise(model, norm=1, aggressive=False, prune_fused=True, fuse_stages=None):
+def optimise(model, norm=1, aggressive=False, prune_fused=True, fuse_stages=None,
+             concat_projection=True):
     """Masks from the raw weights, batch norm merged, masked filters removed.
 
     aggressive: basic blocks are first rewritten by aggressive fusion; with
@@ -58,6 +61,10 @@ def optimise(model, norm=1, aggressive=False, prune_fused=True, fuse_stages=None
     filters (Alg. 1), without it the fused model is run as it is.
     fuse_stages: the fusion option x of "x/n" (Sec. V, optimization setting): only
     the blocks of the first x stages are fused; None fuses every stage.
+    concat_projection: a bottleneck block's projection shortcut is concatenated to
+    its last 1 x 1 convolution (fupr_proj_concat, Sec. IV-B-1) and accumulates in
+    that convolution's accumulators instead of running as an operator of its own
+    (16-bit types).
 
     Returns {"layers": [Layer...], "masks": {(block, conv): uint8 mask},
              "keep_idx": {(block, conv): int32 indices}, "wiring": [...]}
@@ -104,14 +111,26 @@ def optimise(model, norm=1, aggressive=False, prune_fused=True, fuse_stages=None
             keeps[(bi, ci)] = keep
         sc = blk["shortcut"]
         proj_layer = None
+        cat = None
         if sc["kind"] == "projection":
             Wf, bf = _fold(sc["conv"], sc["bn"])
-            layers.append(Layer(f"b{bi}.proj", Wf, bf, sc["conv"]["stride"], sc["conv"]["pad"], False))
-            proj_layer = len(layers) - 1
+            Wl = folded[-1][0]
+            if (concat_projection and model["dtype"] != "f32" and Wl.shape[2:] == (1, 1)
+                    and convs[-1]["stride"] == 1 and (bi, len(folded) - 1) not in keeps):
+                cat = (B.shape_of(Wf, sc["conv"]["stride"], sc["conv"]["pad"]), Wf, bf)
+            else:
+                layers.append(Layer(f"b{bi}.proj", Wf, bf, sc["conv"]["stride"], sc["conv"]["pad"], False))
+                proj_layer = len(layers) - 1
         first = len(layers)
         for ci, (Wf, bf) in enumerate(folded):
             last = ci == len(folded) - 1
             keep = keeps.get((bi, ci)) if last else None
+            if last and cat is not None:
+                sh_last = B.shape_of(Wf, convs[ci]["stride"], convs[ci]["pad"])
+                _, Wc, bc = B.fupr_proj_concat(sh_last, Wf, bf, cat[0], cat[1], cat[2])
+                layers.append(Layer(f"b{bi}.conv{ci + 1}+proj", Wc, bc, 1, 0, True,
+                                    cat_stride=cat[0].stride))
+                continue
             if keep is not None and Wf.shape[2] == 1 and Wf.shape[3] == 1:
                 # A 1 x 1 last convolution is bound by writing the block's full-width output,
                 # which removing filters does not shrink: its removed filters go back in as
@@ -167,15 +186,17 @@ def build(plan, device="cuda:0", base_address=None):
 
     ops, sites = [], []
 
-    def conv_op(li, tin, res=-1, rss=1, roff=0):
+    def conv_op(li, tin, res=-1, rss=1, roff=0, tin2=-1):
         L = plan["layers"][li]
         epi = (B.FUSE_RELU if L.relu else 0) | (B.FUSE_ADD if res >= 0 else 0)
         keep_ptr = None
         if L.keep is not None:
             epi |= B.FUSE_SCATTER
             keep_ptr = base + keep_offsets[li]
+        if L.cat_stride:
+            epi |= B.FUSE_CAT
         ops.append(B.OpDesc(B.OP_CONV, tin, res, L.shape, base + offsets[li], epi, rss, roff,
-                            keep_ptr))
+                            keep_ptr, tin2, max(L.cat_stride, 0)))
         sites.append(L.site)
         return len(ops)
 
@@ -204,15 +225,19 @@ def build(plan, device="cuda:0", base_address=None):
             # block's last 1 x 1 convolution and the next block's first one as one kernel
             # when they are adjacent, so a bottleneck block's projection follows its first
             # convolution; a basic block's comes first.
-            late = sc["kind"] == "projection" and n >= 3
-            if sc["kind"] == "projection" and not late:
+            late = proj is not None and n >= 3
+            if proj is not None and not late:
                 res = conv_op(proj, x)
             h = x
             for i in range(n - 1):
                 h = conv_op(first + i, h)
                 if i == 0 and late:
                     res = conv_op(proj, x)
-            cur = conv_op(first + n - 1, h, res, rss, 0)
+            if plan["layers"][first + n - 1].cat_stride:
+                # the projection shortcut is part of the last convolution: it reads the block input
+                cur = conv_op(first + n - 1, h, tin2=x)
+            else:
+                cur = conv_op(first + n - 1, h, res, rss, 0)
     model = B.Model(dt, plan["in_shape"], ops, keepalive=[dev], device=device)
     model.sites = sites
     model.plan = plan

@@ -496,6 +496,167 @@ def test_two_1x1_convolutions_in_one_kernel(fx, case, dtype):
     assert rel_err(hd.to_nchw(), h2.to_nchw()) <= TOL[dtype] / 4
 
 
+CAT_CASES = [
+    # name, N, C1 (last conv's input), C2 (block input), K, P, Q, shortcut stride, then-second-conv K2 or 0
+    ("cat 38+64 -> 256 s1 (streaming kernel)", 3, 38, 64, 256, 14, 14, 1, 0),
+    ("cat 38+64 -> 256 s1 then 1x1 -> 30 (pair)", 3, 38, 64, 256, 12, 14, 1, 30),
+    ("cat 64+256 -> 512 s2 (pipelined kernel)", 2, 64, 256, 512, 14, 14, 2, 0),
+    ("cat 207+512 -> 300 s2 ragged", 2, 207, 512, 300, 7, 9, 2, 0),
+    ("cat 12+40 -> 72 s2 odd extent", 3, 12, 40, 72, 9, 7, 2, 0),
+    ("cat 96+24 -> 64 s1", 2, 96, 24, 64, 10, 10, 1, 0),
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("case", CAT_CASES, ids=[c[0] for c in CAT_CASES])
+def test_conv_cat_site(fx, case, dtype):
+    """A projection shortcut accumulated in the accumulators of the block's last
+    1 x 1 convolution (Sec. IV-B-1): the device runs ONE convolution over the two
+    tensors, the oracle the original graph - two convolutions with their batch
+    norms, the addition, the ReLU."""
+    B, network, torch = fx
+    name, n, c1, c2, k, p, q, stride, k2 = case
+    rng = np.random.default_rng(zlib.crc32(name.encode()))
+    print(f"case={name} dtype={dtype}", flush=True)
+    dt = B.DTYPES[dtype]
+
+    def bn_of(kk):
+        return {"gamma": rng.uniform(0.5, 1.5, kk).astype(np.float32),
+                "beta": (rng.standard_normal(kk) * 0.1).astype(np.float32),
+                "mean": (rng.standard_normal(kk) * 0.1).astype(np.float32),
+                "var": rng.uniform(0.5, 1.5, kk).astype(np.float32), "eps": 1e-5}
+
+    h = np.maximum(rng.standard_normal((n, c1, p, q)), 0).astype(np.float32)
+    hx, wx = (p - 1) * stride + 1 + (stride - 1), (q - 1) * stride + 1 + (stride - 1)
+    x = np.maximum(rng.standard_normal((n, c2, hx, wx)), 0).astype(np.float32)
+    w3 = (rng.standard_normal((k, c1, 1, 1)) * np.sqrt(2.0 / c1)).astype(np.float32)
+    wp = (rng.standard_normal((k, c2, 1, 1)) * np.sqrt(2.0 / c2)).astype(np.float32)
+    bn3, bnp = bn_of(k), bn_of(k)
+    ref = orc.relu(orc.add(orc.batchnorm(orc.conv2d(round_to(h, dtype, torch), w3, 1, 0), bn3),
+                           orc.batchnorm(orc.conv2d(round_to(x, dtype, torch), wp, stride, 0), bnp)))
+    sh3, shp = B.shape_of(w3, 1, 0), B.shape_of(wp, stride, 0)
+    f3 = B.fupr_fold(sh3, w3, None, bn3["gamma"], bn3["beta"], bn3["mean"], bn3["var"], 1e-5, B.FUSE_BN)
+    fp = B.fupr_fold(shp, wp, None, bnp["gamma"], bnp["beta"], bnp["mean"], bnp["var"], 1e-5, B.FUSE_BN)
+    shc, wc, bc = B.fupr_proj_concat(sh3, f3[0], f3[1], shp, fp[0], fp[1])
+    packed = B.upload_blob(B.fupr_pack(shc, wc, bc, dt))
+    hd, xd = B.DeviceTensor.from_nchw(h, dt), B.DeviceTensor.from_nchw(x, dt)
+    yd = B.DeviceTensor.empty(n, p, q, k, dt)
+    yd.data.fill_(7.0)
+    if not k2:
+        B.fupr_conv_cat_fused(shc, hd, xd, stride, packed, None, B.FUSE_RELU, yd)
+        torch.cuda.synchronize()
+        assert yd.padding_is_zero()
+        parity(yd.to_nchw(), ref, dtype)
+        return
+    # followed by the next block's first convolution in the same launch: through the model
+    w1 = (rng.standard_normal((k2, k, 1, 1)) * np.sqrt(2.0 / k)).astype(np.float32)
+    b1 = (rng.standard_normal(k2) * 0.1).astype(np.float32)
+    sh1 = B.shape_of(w1, 1, 0)
+    p1 = B.upload_blob(B.fupr_pack(sh1, w1, b1, dt))
+    # tensors: 0 = block input x; 1 = h (a stand-in 1 x 1 convolution of x at the stride); 2 = y; 3 = h'
+    w0 = (rng.standard_normal((c1, c2, 1, 1)) * np.sqrt(2.0 / c2)).astype(np.float32)
+    sh0 = B.shape_of(w0, stride, 0)
+    p0 = B.upload_blob(B.fupr_pack(sh0, w0, None, dt))
+    ops = [B.OpDesc(B.OP_CONV, 0, -1, sh0, p0.data_ptr(), B.FUSE_RELU, 1, 0),
+           B.OpDesc(B.OP_CONV, 1, -1, shc, packed.data_ptr(), B.FUSE_RELU | B.FUSE_CAT, 1, 0, None, 0, stride),
+           B.OpDesc(B.OP_CONV, 2, -1, sh1, p1.data_ptr(), B.FUSE_RELU, 1, 0)]
+    m = B.Model(dt, (c2, hx, wx), ops, [p0, p1, packed])
+    assert m.num_launches == 2 and m.launch_stats(n, 1)["kernel"] == "conv1x1s_256f+conv1x1"
+    out, ws = m.alloc(n)
+    m.fupr_forward(xd, out, ws)
+    torch.cuda.synchronize()
+    xr = round_to(x, dtype, torch)
+    h_dev = round_to(orc.relu(orc.conv2d(xr, round_to(w0, dtype, torch), stride, 0)), dtype, torch)
+    y_ref = orc.relu(orc.add(orc.batchnorm(orc.conv2d(h_dev, w3, 1, 0), bn3),
+                             orc.batchnorm(orc.conv2d(xr, wp, stride, 0), bnp)))
+    h2_ref = orc.relu(orc.conv2d(round_to(y_ref, dtype, torch), w1, 1, 0) + b1.astype(np.float64)[None, :, None, None])
+    parity(out.to_nchw(), h2_ref, dtype)
+    m.set_schedule(B.SCHEDULE_PER_LAYER)
+    assert m.num_launches == 3
+    out2, ws2 = m.alloc(n)
+    m.fupr_forward(xd, out2, ws2)
+    torch.cuda.synchronize()
+    assert rel_err(out.to_nchw(), out2.to_nchw()) <= TOL[dtype] / 4
+
+
+def test_conv_cat_rejects_bad_calls(fx):
+    B, network, torch = fx
+    dt = B.BF16
+    w = np.zeros((16, 32 + 8, 1, 1), np.float32)
+    sh = B.shape_of(w, 1, 0)
+    packed = B.upload_blob(B.fupr_pack(sh, w, None, dt))
+    h = B.DeviceTensor.empty(1, 4, 4, 20, dt)
+    x = B.DeviceTensor.empty(1, 8, 8, 8, dt)
+    y = B.DeviceTensor.empty(1, 4, 4, 16, dt)
+
+    def expect(code, fn):
+        with pytest.raises(B.FuprError) as e:
+            fn()
+        assert e.value.status == code
+
+    B.fupr_conv_cat_fused(sh, h, x, 2, packed, None, 0, y)
+    expect(B.ERR_ARG, lambda: B.fupr_conv_cat_fused(sh, h, x, 3, packed, None, 0, y))
+    small = B.DeviceTensor.empty(1, 4, 4, 8, dt)
+    expect(B.ERR_SHAPE, lambda: B.fupr_conv_cat_fused(sh, h, small, 2, packed, None, 0, y))
+    wide = B.DeviceTensor.empty(1, 8, 8, 9, dt)
+    expect(B.ERR_SHAPE, lambda: B.fupr_conv_cat_fused(sh, h, wide, 2, packed, None, 0, y))
+    w3 = np.zeros((16, 40, 3, 3), np.float32)
+    expect(B.ERR_SHAPE, lambda: B.fupr_conv_cat_fused(B.shape_of(w3, 1, 1), h, x, 2, packed, None, 0, y))
+    h32, x32, y32 = (B.DeviceTensor.empty(1, 4, 4, 20, B.F32), B.DeviceTensor.empty(1, 8, 8, 8, B.F32),
+                     B.DeviceTensor.empty(1, 4, 4, 16, B.F32))
+    expect(B.ERR_DTYPE, lambda: B.fupr_conv_cat_fused(sh, h32, x32, 2, packed, None, 0, y32))
+    torch.cuda.synchronize()
+
+
+def test_config4_projection_blocks_at_full_batch(fx):
+    """The four blocks of the largest workload whose projection shortcut runs inside
+    their last convolution, each alone at the full batch of 256 images on seeded
+    synthetic activations; the oracle (both raw convolutions, both literal batch
+    norms, removed input channels as zeros, the addition, the ReLU) computes a sample
+    of output pixels one by one."""
+    B, network, torch = fx
+    model, batch = synth.make_config(4)
+    dtype = model["dtype"]
+    dt = B.DTYPES[dtype]
+    masks = orc.select_masks(model)
+    plan = network.optimise(model)
+    rng = np.random.default_rng(synth.BASE_SEED + 4005)
+    cats = [L for L in plan["layers"] if L.cat_stride]
+    assert len(cats) == 4
+    for L in cats:
+        bi = int(L.site[1:].split(".")[0])
+        blk = model["blocks"][bi]
+        conv3, bn3 = blk["convs"][2], blk["bns"][2]
+        convp, bnp = blk["shortcut"]["conv"], blk["shortcut"]["bn"]
+        stride = convp["stride"]
+        keep2 = np.flatnonzero(masks[(bi, 1)])
+        c1, c2, k = len(keep2), convp["W"].shape[1], conv3["W"].shape[0]
+        stage = blk["stage"]
+        p = 56 >> stage
+        hx = p * stride
+        h = np.maximum(rng.standard_normal((batch, c1, p, p), dtype=np.float32), 0.0)
+        x = np.maximum(rng.standard_normal((batch, c2, hx, hx), dtype=np.float32), 0.0)
+        print(f"{L.site}: [{c1} ; {c2} at stride {stride}] -> {k} on {batch}x{p}x{p}", flush=True)
+        hd, xd = B.DeviceTensor.from_nchw(h, dt), B.DeviceTensor.from_nchw(x, dt)
+        packed = B.upload_blob(B.fupr_pack(L.shape, L.W, L.bias, dt))
+        yd = B.DeviceTensor.empty(batch, p, p, k, dt)
+        B.fupr_conv_cat_fused(L.shape, hd, xd, stride, packed, None, B.FUSE_RELU, yd)
+        torch.cuda.synchronize()
+        pts = [(0, 0, 0), (0, p - 1, p - 1), (1, 0, 0), (batch // 2, 0, p - 1), (batch - 1, p - 1, 0),
+               (batch - 1, p - 1, p - 1)]
+        pts += [(int(rng.integers(batch)), int(rng.integers(p)), int(rng.integers(p))) for _ in range(40)]
+        hc = np.zeros((len(pts), conv3["W"].shape[1], 1, 1))
+        xc = np.zeros((len(pts), c2, 1, 1))
+        for j, (n, pp, qq) in enumerate(pts):
+            hc[j, keep2, 0, 0] = round_to(h[n, :, pp, qq], dtype, torch)
+            xc[j, :, 0, 0] = round_to(x[n, :, pp * stride, qq * stride], dtype, torch)
+        ref = orc.relu(orc.add(orc.batchnorm(orc.conv2d(hc, conv3["W"], 1, 0), bn3),
+                               orc.batchnorm(orc.conv2d(xc, convp["W"], 1, 0), bnp)))[:, :, 0, 0]
+        got = np.stack([yd.data[n, pp, qq, :k].double().cpu().numpy() for n, pp, qq in pts])
+        parity(got, ref, dtype)
+        del hd, xd, yd, packed, h, x
+
+
 def test_two_1x1_convolutions_rejected_when_not_a_pair(fx):
     B, network, torch = fx
     w1 = np.zeros((512, 64, 1, 1), np.float32)   # 512 filters: two filter groups
@@ -719,7 +880,7 @@ def test_baseline_config_teacher_forced(fx, idx):
     trace = []
     orc.forward(model, round_to(x, dtype, torch), masks=masks, trace=trace)
     by_site = {t["site"]: t for t in trace}
-    plan = network.optimise(model)
+    plan = network.optimise(model, concat_projection=False)   # one operator per convolution site
     # which (block, conv) feeds / is each site, to drop removed channels
     worst = 0.0
     for L in plan["layers"]:
@@ -872,7 +1033,7 @@ def test_config4_layer_shapes_at_full_batch(fx):
     dtype = model["dtype"]
     dt = B.DTYPES[dtype]
     masks = orc.select_masks(model)
-    plan = network.optimise(model)
+    plan = network.optimise(model, concat_projection=False)   # one operator per convolution site
     raw = raw_layers(model)
     rng = np.random.default_rng(synth.BASE_SEED + 4004)
     worst, done = 0.0, 0

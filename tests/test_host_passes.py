@@ -330,7 +330,7 @@ def test_library_compaction_equals_oracle_extraction():
     merged weights, filter for filter."""
     model = synth.make_imagenet_bottleneck_resnet(14, "bf16", (2, 1, 1, 1), 500, widths=(4, 4, 8, 8),
                                                   size=32, classes=5)
-    plan = network.optimise(model)
+    plan = network.optimise(model, concat_projection=False)
     thin = orc.extract(model, orc.select_masks(model))
     by_site = {L.site: L for L in plan["layers"]}
     for bi, blk in enumerate(thin["blocks"]):
@@ -511,8 +511,12 @@ def test_baseline_config_graphs_have_expected_launch_counts():
     want = {0: 2, 1: 56, 2: 21, 3: 54, 4: 54}
     for idx, n in want.items():
         model, _ = synth.make_config(idx)
-        plan = network.optimise(model)
+        plan = network.optimise(model, concat_projection=False)
         assert len(plan["layers"]) == n
+        # a bottleneck block's projection shortcut is part of its last convolution by default
+        plan = network.optimise(model)
+        assert len(plan["layers"]) == n - (4 if idx >= 3 else 0)
+        assert sum(L.cat_stride > 0 for L in plan["layers"]) == (4 if idx >= 3 else 0)
 
 
 # ---- a block's pruned output filters (Alg. 1 on every non-fused operator, Sec. V-A) ---------
@@ -660,6 +664,58 @@ def test_partially_fused_plan_selects_the_oracles_filters():
             assert np.array_equal(plan["masks"][key], masks[key])
         fused = sum(b["stage"] < stages for b in model["blocks"])
         assert sum(L.add for L in plan["layers"]) == len(model["blocks"]) - fused
+
+
+def test_proj_concat_is_the_filterwise_concatenation():
+    """conv(h, W) + conv_p(x, Wp) = conv([h ; x], [W | Wp]) (Sec. IV-B-1): exact copies of
+    both weight sets with zeros between them up to a multiple of 32 channels, biases added;
+    the oracle's two convolutions and addition equal its one convolution of the concatenation."""
+    rng = np.random.default_rng(12)
+    k, c1, c2 = 20, 38, 24
+    W = rng.standard_normal((k, c1, 1, 1)).astype(np.float32)
+    Wp = rng.standard_normal((k, c2, 1, 1)).astype(np.float32)
+    b, bp = rng.standard_normal(k).astype(np.float32), rng.standard_normal(k).astype(np.float32)
+    sh, shp = B.shape_of(W, 1, 0), B.shape_of(Wp, 2, 0)
+    out, Wc, bc = B.fupr_proj_concat(sh, W, b, shp, Wp, bp)
+    assert (out.K, out.C, out.R, out.S, out.stride, out.pad) == (k, 64 + c2, 1, 1, 1, 0)
+    assert np.array_equal(Wc[:, :c1], W) and not Wc[:, c1:64].any() and np.array_equal(Wc[:, 64:], Wp)
+    assert np.array_equal(bc, b + bp)
+    h = rng.standard_normal((2, c1, 5, 6))
+    x = rng.standard_normal((2, c2, 10, 12))
+    two = orc.add(orc.conv2d(h, W, 1, 0), orc.conv2d(x, Wp, 2, 0))
+    cat = np.concatenate([h, np.zeros((2, 64 - c1, 5, 6)), x[:, :, ::2, ::2]], axis=1)
+    one = orc.conv2d(cat, Wc, 1, 0)
+    np.testing.assert_allclose(one, two, rtol=1e-12, atol=1e-12)
+    # errors: a 3 x 3 last convolution, different filter counts, a strided last convolution
+    W3 = np.zeros((k, c1, 3, 3), np.float32)
+    for bad_last, bad_proj in ((B.shape_of(W3, 1, 1), shp), (sh, B.conv_shape(k + 1, c2, 1, 1, 2, 0)),
+                               (B.conv_shape(k, c1, 1, 1, 2, 0), shp)):
+        with pytest.raises(B.FuprError) as e:
+            B.fupr_proj_concat(bad_last, W3 if bad_last.R == 3 else W, b, bad_proj,
+                               np.zeros((bad_proj.K, c2, 1, 1), np.float32), None)
+        assert e.value.status == B.ERR_SHAPE
+
+
+def test_model_accepts_a_two_input_convolution():
+    def ops(in2=1, stride=2, c=32 + 16, epi=B.FUSE_RELU | B.FUSE_CAT):
+        o = fake_ops([
+            (B.OP_CONV, 0, -1, 16, 3, 3, 1, 1, B.FUSE_RELU, 1),      # t1 16 x 32 x 32
+            (B.OP_CONV, 1, -1, 12, 16, 3, 2, 1, B.FUSE_RELU, 1),     # t2 12 x 16 x 16
+            (B.OP_CONV, 2, -1, 40, c, 1, 1, 0, epi, 1),              # t3 = conv([t2 ; t1 at stride 2])
+        ])
+        o[2].in2, o[2].in2_spatial_stride = in2, stride
+        return o
+    m = B.Model(B.BF16, (3, 32, 32), ops(), None)
+    s = m.op_stats(2, 2)
+    assert s["flops"] == 2.0 * (12 + 16) * 40 * 2 * 256 and s["C"] == 28
+    # t1 stays alive until the last operator: three buffers... t1 and t2 only (t3 is the output)
+    assert m.workspace_bytes(1) == (32 * 32 * 16 + 16 * 16 * 16) * 2
+    expect(B.ERR_SHAPE, lambda: B.Model(B.BF16, (3, 32, 32), ops(c=12 + 16), None))   # split not at 32
+    expect(B.ERR_ARG, lambda: B.Model(B.BF16, (3, 32, 32), ops(in2=3), None))
+    expect(B.ERR_ARG, lambda: B.Model(B.BF16, (3, 32, 32), ops(stride=3), None))
+    B.Model(B.BF16, (3, 32, 32), ops(in2=0, c=32 + 3, stride=1), None)      # any earlier tensor large enough
+    expect(B.ERR_SHAPE, lambda: B.Model(B.BF16, (3, 32, 32), ops(in2=2, c=32 + 12, stride=2), None))  # too small
+    expect(B.ERR_DTYPE, lambda: B.Model(B.F32, (3, 32, 32), ops(), None))
 
 
 def test_xconv_fuse_errors():
