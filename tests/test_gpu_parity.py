@@ -176,8 +176,11 @@ def kernel_of(B, dtype, case):
 # switches onto shapes with ragged channel / filter counts, both strides, with and
 # without a shortcut, several tiles per workgroup (bench.py at another batch size
 # may pick any of them).
-PATCH_TILES = ["256x64", "256x48", "256x32", "128x64", "128x32", "64x64", "224x64", "224x32",
-               "448x64", "128x64w", "448x32", "448x48", "64x32"]
+PATCH_TILES = ["p_256x64", "p_256x48", "p_256x32", "p_128x64", "p_128x32", "p_64x64", "p_224x64",
+               "p_224x32", "p_448x64", "p_128x64w", "p_448x32", "p_448x48", "p_64x32",
+               # the same kernel on the 32 x 32 x 16 MFMA
+               "q_448x64", "q_256x64", "q_256x32", "q_128x64", "q_64x64", "q_128x64w", "q_512x32",
+               "q_384x64"]
 FORCED_3X3 = [
     ("forced 3x3 C45 K72 +id 28x28 x9", 9, 45, 28, 28, 72, 3, 1, 1, "identity", True),
     ("forced 3x3 C40 K100 s2 26x30 x4", 4, 40, 26, 30, 100, 3, 2, 1, None, True),
@@ -185,7 +188,7 @@ FORCED_3X3 = [
 ]
 
 
-@pytest.mark.parametrize("tile", range(13), ids=PATCH_TILES)
+@pytest.mark.parametrize("tile", range(len(PATCH_TILES)), ids=PATCH_TILES)
 def test_every_3x3_tile_forced(fx, tile):
     B, network, torch = fx
     B.fupr_tuning_set("patch_tile", tile)
@@ -194,7 +197,7 @@ def test_every_3x3_tile_forced(fx, tile):
         for case in FORCED_3X3:
             for dtype in ("bf16", "f16"):
                 kernel = kernel_of(B, dtype, case)
-                if kernel != "conv3x3p_" + PATCH_TILES[tile]:
+                if kernel != "conv3x3" + PATCH_TILES[tile]:
                     print(f"  {case[0]}: tile does not fit ({kernel} runs)", flush=True)
                     continue
                 conv_site(fx, case, dtype)
