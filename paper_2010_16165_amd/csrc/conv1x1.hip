@@ -178,14 +178,23 @@ __global__ __launch_bounds__(THREADS) void conv1x1_stream_kernel(const StreamPar
   u32x4 rvn[NP] = {};
   const int k_pair = (g & 1) * 16 + (g >> 1) * 8;   // channel of this lane's 16 bytes in a tile pair
   uint32_t yoff_n = kOutside, hoff_n = kOutside;
-  auto fetch = [&](int t) {
+  // The eight-wave variant keeps the pixel fragments of TWO tiles in flight per wave (the pairs
+  // it serves read few bytes per pixel, and one tile per wave in flight leaves the memory
+  // system short of requests: 2.7 TB/s measured).  It has no shortcut (its launcher refuses
+  // one): the registers that would hold shortcut values hold the second tile.
+  constexpr bool kDeep = THREADS == 512;
+  const bool has_res = !kDeep && p.res != nullptr;
+  uint4 bn2[kDeep ? KMAX : 1] = {};
+  uint32_t yoff_n2 = kOutside, hoff_n2 = kOutside;
+  auto fetch_pixels = [&](int t, uint4* bdst, uint32_t& yo, uint32_t& ho, uint32_t& ro) {
     const int m = t * 16 + li;
-    uint32_t xo = kOutside, ro = kOutside, xo2 = kOutside;
-    yoff_n = kOutside;
-    hoff_n = kOutside;
+    uint32_t xo = kOutside, xo2 = kOutside;
+    ro = kOutside;
+    yo = kOutside;
+    ho = kOutside;
     if (m < p.M) {
-      yoff_n = (uint32_t)m * (uint32_t)(p.ycs * 2);
-      hoff_n = (uint32_t)m * (uint32_t)(p.hcs * 2);
+      yo = (uint32_t)m * (uint32_t)(p.ycs * 2);
+      ho = (uint32_t)m * (uint32_t)(p.hcs * 2);
       if (p.plain) {
         xo = (uint32_t)m * (uint32_t)(p.xcs * 2);
         ro = (uint32_t)m * (uint32_t)(p.rcs * 2);
@@ -206,15 +215,17 @@ __global__ __launch_bounds__(THREADS) void conv1x1_stream_kernel(const StreamPar
         const int chunk = k * 4 + g;
         if (k * 4 < p.split) {   // a whole step comes from one tensor
           const uint32_t off = chunk * 8 < p.xcs ? xo + (uint32_t)chunk * 16u : kOutside;
-          bn[k] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, off, 0, 0));
+          bdst[k] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, off, 0, 0));
         } else {
           const int c2 = chunk - p.split;
           const uint32_t off = c2 * 8 < p.xcs2 ? xo2 + (uint32_t)c2 * 16u : kOutside;
-          bn[k] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(x2rsrc, off, 0, 0));
+          bdst[k] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(x2rsrc, off, 0, 0));
         }
       }
     }
-    if (p.res) {
+  };
+  auto fetch_shortcut = [&](uint32_t ro) {
+    if (has_res) {
 #pragma unroll
       for (int pr = 0; pr < NP; ++pr) {
         const int rc = f0 + pr * 32 + k_pair - p.roff;
@@ -223,20 +234,38 @@ __global__ __launch_bounds__(THREADS) void conv1x1_stream_kernel(const StreamPar
       }
     }
   };
-  if (tile < p.n_tiles) fetch(tile);   // in flight while the filters arrive
+  uint32_t ro_n = kOutside, ro_n2 = kOutside;
+  if (tile < p.n_tiles) {   // in flight while the filters arrive
+    fetch_pixels(tile, bn, yoff_n, hoff_n, ro_n);
+    fetch_shortcut(ro_n);
+    if constexpr (kDeep)
+      if (tile + n_waves < p.n_tiles) fetch_pixels(tile + n_waves, bn2, yoff_n2, hoff_n2, ro_n2);
+  }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();   // filters and bias are in LDS
   const uint32_t floor2 = p.relu ? 0u : 0x80008000u;
   const char* a_lane = wts + (g * NF + li) * 16;
-  for (; tile < p.n_tiles; tile += n_waves) {
+  // One tile: `cur` holds its pixel fragments (asked for one or two tiles ago), rvn its
+  // shortcut values.  kDeep: the other register set holds the next tile's fragments, already
+  // on their way; this set is refilled with the tile after that.  Otherwise this set is
+  // refilled with the next tile.
+  auto process = [&](uint4* cur, uint32_t& yo_cur, uint32_t& ho_cur, uint32_t& ro_cur, uint32_t ro_other) {
     uint4 b[KMAX];
     u32x4 rv[NP];
 #pragma unroll
-    for (int k = 0; k < KMAX; ++k) b[k] = bn[k];
+    for (int k = 0; k < KMAX; ++k) b[k] = cur[k];
 #pragma unroll
     for (int pr = 0; pr < NP; ++pr) rv[pr] = rvn[pr];
-    const uint32_t yoff = yoff_n, hoff = hoff_n;
-    if (tile + n_waves < p.n_tiles) fetch(tile + n_waves);
+    const uint32_t yoff = yo_cur, hoff = ho_cur;
+    if constexpr (kDeep) {
+      if (tile + n_waves < p.n_tiles) fetch_shortcut(ro_other);
+      if (tile + 2 * n_waves < p.n_tiles) fetch_pixels(tile + 2 * n_waves, cur, yo_cur, ho_cur, ro_cur);
+    } else {
+      if (tile + n_waves < p.n_tiles) {
+        fetch_pixels(tile + n_waves, cur, yo_cur, ho_cur, ro_cur);
+        fetch_shortcut(ro_cur);
+      }
+    }
 
     uint4 yb[NT2 > 0 ? NP : 1];   // the finished tile as pixel fragments of the second convolution
     f32x4 acc[NT];
@@ -257,7 +286,7 @@ __global__ __launch_bounds__(THREADS) void conv1x1_stream_kernel(const StreamPar
     // every access is 16 bytes and a pixel's 64 bytes come from four lanes.
     auto finish = [&](const f32x4& av, uint32_t r0, uint32_t r1) {
       float v[4] = {av[0], av[1], av[2], av[3]};
-      if (p.res) {
+      if (has_res) {
         v[0] += to_float<BF>((uint16_t)(r0 & 0xffffu));
         v[1] += to_float<BF>((uint16_t)(r0 >> 16));
         v[2] += to_float<BF>((uint16_t)(r1 & 0xffffu));
@@ -272,7 +301,7 @@ __global__ __launch_bounds__(THREADS) void conv1x1_stream_kernel(const StreamPar
     for (int pr = 0; pr < NP; ++pr) {
       const int t = 2 * pr;
       uint32_t ra0 = 0, ra1 = 0, rb0 = 0, rb1 = 0;
-      if (p.res) {
+      if (has_res) {
         const auto s0 = __builtin_amdgcn_permlane16_swap(rv[pr][0], rv[pr][2], false, false);
         const auto s1 = __builtin_amdgcn_permlane16_swap(rv[pr][1], rv[pr][3], false, false);
         ra0 = s0[0]; ra1 = s1[0];
@@ -322,6 +351,17 @@ __global__ __launch_bounds__(THREADS) void conv1x1_stream_kernel(const StreamPar
         __builtin_amdgcn_raw_buffer_store_b128(o4, hrsrc, off, 0, 0);
       }
     }
+  };
+  if constexpr (kDeep) {
+    while (tile < p.n_tiles) {
+      process(bn, yoff_n, hoff_n, ro_n, ro_n2);
+      tile += n_waves;
+      if (tile >= p.n_tiles) break;
+      process(bn2, yoff_n2, hoff_n2, ro_n2, ro_n);
+      tile += n_waves;
+    }
+  } else {
+    for (; tile < p.n_tiles; tile += n_waves) process(bn, yoff_n, hoff_n, ro_n, ro_n);
   }
 }
 
@@ -459,7 +499,9 @@ bool plan_fused(const Conv16Params& c1, const Conv16Params& c2, int* kmax, int* 
   const int ksteps = (c1.cpt + 3) / 4;
   *lds = stream_lds_bytes(kStreamTiles[t], ksteps) + (size_t)*nt2 * 16 * 4 +
          (size_t)8 * 4 * *nt2 * 16 * 16;
-  return *lds <= (size_t)kStreamFusedLdsLimit || (*kmax == 4 && *lds <= 2 * (size_t)kStreamFusedLdsLimit);
+  // (the eight-wave variant has no shortcut in its epilogue)
+  return *lds <= (size_t)kStreamFusedLdsLimit ||
+         (*kmax == 4 && !c1.res && *lds <= 2 * (size_t)kStreamFusedLdsLimit);
 }
 
 }  // namespace
@@ -500,7 +542,9 @@ fupr_status launch_conv1x1_fused_pair(const Conv16Params& c1, const Conv16Params
   p.w2_bytes = c2.w_bytes; p.h_bytes = (uint32_t)h_bytes;
   p.Kp2 = c2.Kp; p.cpt2 = c2.cpt; p.hcs = c2.ycs; p.relu2 = c2.relu;
   p.w_lds_bytes = (int)round_up_sz((size_t)p.ksteps * 4 * 16 * 16 * 16, 1024);
-  const bool wide = lds > (size_t)kStreamFusedLdsLimit;   // eight waves share the filters
+  // eight waves share the filters and keep two tiles in flight each: needed when the filters
+  // fit LDS once only, and faster whenever there is no shortcut to read (few bytes per pixel)
+  const bool wide = lds > (size_t)kStreamFusedLdsLimit || (kmax == 4 && !c1.res);
   const int gx = wide ? std::min((p.n_tiles + 7) / 8, stream_compute_units())
                       : std::min((p.n_tiles + 3) / 4, 2 * stream_compute_units());
   const dim3 grid((unsigned)gx, 1u);

@@ -289,9 +289,15 @@ bool prefer_pipe(const Conv16Params& g) {
 }  // namespace
 
 const char* conv_kernel_name(const fupr_conv_shape& s, fupr_dtype dt, int N, int H, int W,
-                             bool indexed) {
+                             bool indexed, bool two_inputs) {
   if (dt == FUPR_F32) return "conv32_direct";
   Conv16Params g = geometry16(s, dt, N, H, W);
+  if (two_inputs) {   // a marker that is never dereferenced stands for the second tensor
+    g.x2 = reinterpret_cast<const uint16_t*>(uintptr_t(16));
+    if (prefer_pipe(g)) return conv1x1_pipe_name(g);
+    if (conv1x1_stream_applies(g)) return conv1x1_stream_name(g);
+    return conv1x1_pipe_applies(g) ? conv1x1_pipe_name(g) : "none";
+  }
   // the indexed epilogue needs LDS of its own, which can change the tile: a marker
   // that is never dereferenced stands for the index list
   if (indexed) g.keep = reinterpret_cast<const int32_t*>(uintptr_t(16));

@@ -72,7 +72,7 @@ struct ConvArgs {
 fupr_status launch_conv(const ConvArgs& a, void* stream);
 // indexed: the convolution adds into listed channels of a wider tensor (ConvArgs::keep)
 const char* conv_kernel_name(const fupr_conv_shape& s, fupr_dtype dt, int N, int H, int W,
-                             bool indexed = false);
+                             bool indexed = false, bool two_inputs = false);
 // fupr_conv_cat_fused followed by a 1 x 1 convolution of its output, in one launch
 // (what fupr_conv_conv1x1_fused is to fupr_conv_fused); for the model executor.
 fupr_status conv_cat_conv1x1_fused(const fupr_conv_shape* shape1, const fupr_tensor* x1,

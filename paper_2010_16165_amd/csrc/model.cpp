@@ -1092,7 +1092,8 @@ extern "C" fupr_status fupr_model_op_stats(const fupr_model* m, int32_t batch, i
     if (scatter)   // conv.K channels of the updated tensor read and written, and the index list
       s.bytes = in_b + 2.0 * es * (double)s.M * d.conv.K + es * crs * d.conv.K + 8.0 * d.conv.K;
     if (scatter) s.K = d.conv.K;
-    s.kernel = conv_kernel_name(d.conv, m->dt, batch, ti.H, ti.W, scatter);
+    s.kernel = conv_kernel_name(d.conv, m->dt, batch, ti.H, ti.W, scatter,
+                                (d.epilogue & FUPR_FUSE_CAT) != 0);
   } else {
     s.R = s.S = d.kind == FUPR_OP_MAXPOOL ? d.conv.R : ti.H;
     s.stride = d.kind == FUPR_OP_MAXPOOL ? d.conv.stride : 1;
