@@ -392,6 +392,37 @@ def print_per_op(w, stats, op_ms, ms_per_step):
           file=sys.stderr)
 
 
+def filter_tail_point(reps=50):
+    """The paper's remark that a layer with 64 filters is often faster than one with
+    63 (Sec. VI-B), as one data point of the tail handling here: a 3 x 3 and a 1 x 1
+    layer of ResNet-18 / ResNet-50 shape at 64 images with 60 .. 66 filters, microseconds
+    per launch by HIP events."""
+    import numpy as np
+    import torch
+    from paper_2010_16165_amd import binding as B
+    out = {}
+    for name, c, h, r in (("3x3 64->K 56x56 x64", 64, 56, 3), ("1x1 256->K 56x56 x64", 256, 56, 1)):
+        row = {}
+        xd = B.DeviceTensor.empty(64, h, h, c, B.BF16)
+        xd.data.normal_()
+        for k in (60, 62, 63, 64, 65, 66):
+            w = (np.random.default_rng(k).standard_normal((k, c, r, r)) * 0.05).astype(np.float32)
+            sh = B.shape_of(w, 1, r // 2)
+            packed = B.upload_blob(B.fupr_pack(sh, w, None, B.BF16))
+            yd = B.DeviceTensor.empty(64, h, h, k, B.BF16)
+            for _ in range(5):
+                B.fupr_conv_fused(sh, xd, packed, None, B.FUSE_RELU, yd)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                B.fupr_conv_fused(sh, xd, packed, None, B.FUSE_RELU, yd)
+            b.record()
+            b.synchronize()
+            row[str(k)] = a.elapsed_time(b) / reps * 1e3
+        out[name] = row
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -428,6 +459,9 @@ def main():
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="also run a plain device-to-device copy of MIB mebibytes (a kernel of "
                          "known traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE by)")
+    ap.add_argument("--filter-tail-point", action="store_true",
+                    help="instead of a workload: time one 3 x 3 and one 1 x 1 layer with 60 .. 66 "
+                         "filters (the paper's 63-against-64-filters remark, Sec. VI-B)")
     ap.add_argument("--record-traffic", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"),
                     help="no GPU run: turn two rocprofv3 counter outputs into the traffic table")
     args = ap.parse_args()
@@ -444,6 +478,9 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
+    if args.filter_tail_point:
+        print(json.dumps({"filter_tail_us": filter_tail_point()}))
+        return
     if args.split:
         B.fupr_tuning_set("split", args.split)
     if args.workload:

@@ -860,14 +860,28 @@ std::vector<Launch> launches_of(const fupr_model* m) {
   return v;
 }
 
-// Sub-batches of the per-operator schedule.  Measured on the ImageNet-size
-// workloads: two sub-batches of 128 images gain 6 %, sub-batches of 32 lose 11 %
-// (their kernels no longer fill the compute units), more than two never pay;
-// so two from 192 images on, else one, and never more than the caller has lent
-// streams for.  The tuning switch split=<1..4> forces a count.
+// Sub-batches of the per-operator schedule.  Two sub-batches side by side let one's
+// memory-bound kernels run beside the other's arithmetic and fill launch gaps and tails.
+// Measured on the ImageNet-size workloads (one / two / three / four sub-batches): the
+// bottleneck network, whose 1 x 1 convolutions move 75 - 100 flops per byte, 3261 / 2988 /
+// 3220 / 3320 us at 256 images and 922 / 888 / 960 / 1058 us at 64; the basic-block network
+// (258 flops per byte, kernels that fill the compute units only at full batch) 417 / 448 us
+// at 64.  So: two sub-batches from 192 images on, and from 64 images on for networks under
+// 150 flops per byte; else one; never more than the caller has lent streams for.  The
+// tuning switch split=<1..4> forces a count.
 int split_count(const fupr_model* m, int N) {
   const int forced = std::min(std::max(tuning_int("split", 0), 0), kMaxSplit);
-  const int want = forced ? std::min(forced, std::max(N / 8, 1)) : (N >= 192 ? 2 : 1);
+  int want = forced ? std::min(forced, std::max(N / 8, 1)) : (N >= 192 ? 2 : 1);
+  if (!forced && want == 1 && N >= 64 && m->n_side > 0) {
+    double flops = 0.0, bytes = 0.0;
+    for (int32_t i = 0; i < (int32_t)m->ops.size(); ++i) {
+      fupr_op_stats s;
+      if (fupr_model_op_stats(m, N, i, &s) != FUPR_OK) return 1;
+      flops += s.flops;
+      bytes += s.bytes;
+    }
+    if (bytes > 0.0 && flops / bytes < 150.0) want = 2;
+  }
   return std::min(want, m->n_side + 1);
 }
 
