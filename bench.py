@@ -88,6 +88,20 @@ def counter_rows(directory, counter):
     return rows
 
 
+TRAFFIC_HEADER = """\
+# HBM bytes per launch of every kernel group, per configuration N, from two counter runs
+# (on the GPU box, from the repository root, after cd /tmp && export TMPDIR=/tmp && cd back):
+#   rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d gpurun_out/pmc_fetch_cN -o r -- \\
+#       python3 bench.py --config N --steps 3 --warmup 1 --split 1 --only-headline \\
+#       --no-cpu-baseline --no-measured-peaks --copy-calibration 1024
+#   rocprofv3 --pmc WRITE_SIZE ... -d gpurun_out/pmc_write_cN ... (the same command)
+# folded into this file by
+#   python3 bench.py --record-traffic gpurun_out/pmc_fetch_cN gpurun_out/pmc_write_cN --config N
+# fetch_bytes / write_bytes: mean counter value per dispatch (KiB) x 1024 x the factor that makes the
+# same counter read 1 GiB for the 1 GiB device copy of that run.  sources: hash of the kernel sources.
+"""
+
+
 def record_traffic(fetch_dir, write_dir, config):
     """FETCH_DIR / WRITE_DIR hold the CSV output of
 
@@ -120,7 +134,8 @@ def record_traffic(fetch_dir, write_dir, config):
     lines = []
     if os.path.exists(TRAFFIC_TABLE):
         with open(TRAFFIC_TABLE) as f:
-            lines = [ln.rstrip("\n") for ln in f if ln.strip() and not ln.startswith(f"config={config} ")]
+            lines = [ln.rstrip("\n") for ln in f if ln.strip() and not ln.startswith("#")
+                     and not ln.startswith(f"config={config} ")]
     for g, e in sorted(per.items()):
         if not e["fetch"] or not e["write"]:
             continue
@@ -129,7 +144,7 @@ def record_traffic(fetch_dir, write_dir, config):
                      f"write_bytes={wb:.0f} bytes_per_launch={fb + wb:.0f} fetch_factor={f_factor:.4f} "
                      f"write_factor={w_factor:.4f} sources={sources_hash()}")
     with open(TRAFFIC_TABLE, "w") as f:
-        f.write("\n".join(lines) + "\n")
+        f.write(TRAFFIC_HEADER + "\n".join(lines) + "\n")
     print("\n".join(ln for ln in lines if ln.startswith(f"config={config} ")))
 
 
