@@ -95,6 +95,11 @@ typedef struct {
  * FUPR_FUSE_CAT are accepted in fupr_op_desc.epilogue only (see there). */
 enum { FUPR_FUSE_BN = 1, FUPR_FUSE_RELU = 2, FUPR_FUSE_ADD = 4, FUPR_FUSE_SCATTER = 8, FUPR_FUSE_CAT = 16 };
 
+/* In a channel-wise concatenation of two tensors (fupr_proj_concat, fupr_conv_cat_fused) the
+ * second tensor's channels start at a multiple of this many channels: the kernels fetch
+ * 64 channels of one pixel (one 128-byte line of a 16-bit tensor) per load and tensor. */
+#define FUPR_CAT_ALIGN 64
+
 /* ------------------------------------------------------------------ host -- */
 
 /*
@@ -181,7 +186,7 @@ fupr_status fupr_xconv_fuse(const fupr_conv_shape* conv1, const float* W1, const
  * last convolution; a bottleneck block's last convolution is 1 x 1 already.)
  * Both batch norms have been merged beforehand (fupr_fold).  Writes
  *     W_out   K x (C1p + C2) x 1 x 1: W's C1 channels, zeros up to C1p = C1 rounded
- *             up to 32 (one MFMA step), then Wp's C2 channels;
+ *             up to FUPR_CAT_ALIGN, then Wp's C2 channels;
  *     b_out   K: b + bp (one fp32 addition each; NULL inputs count as zeros);
  *     *out    the shape of the concatenated operator: K, C1p + C2, 1 x 1, stride 1, pad 0.
  * The device never builds [h ; x]: fupr_conv_cat_fused reads the first C1p
@@ -289,7 +294,7 @@ fupr_status fupr_conv_fused(const fupr_conv_shape* shape, const fupr_tensor* x, 
  * channel c < split is channel c of x1 at the output pixel (zero from x1->C on),
  * input channel c >= split is channel c - split of x2 at
  * (n, p * x2_spatial_stride, q * x2_spatial_stride), where split = x1->C rounded
- * up to 32.  shape: 1 x 1, stride 1, pad 0, C = split + x2->C.  x1 has the
+ * up to FUPR_CAT_ALIGN.  shape: 1 x 1, stride 1, pad 0, C = split + x2->C.  x1 has the
  * output's extent; x2 has at least (P - 1) * x2_spatial_stride + 1 rows and
  * likewise columns; x2_spatial_stride is 1 or 2; 16-bit types only; everything
  * else (packed, res, flags, y, rounding) as in fupr_conv_fused.
@@ -390,7 +395,8 @@ typedef struct {
   const int32_t* keep_idx;
   /* With FUPR_FUSE_CAT (16-bit types): the operator is fupr_conv_cat_fused over tensor
    * `in` and tensor `in2` (an earlier tensor) read at spatial stride in2_spatial_stride;
-   * conv.C = (channels of `in` rounded up to 32) + channels of `in2`.  Ignored otherwise. */
+   * conv.C = (channels of `in` rounded up to FUPR_CAT_ALIGN) + channels of `in2`.  Ignored
+   * otherwise. */
   int32_t in2, in2_spatial_stride;
 } fupr_op_desc;
 
@@ -577,6 +583,8 @@ void fupr_graph_destroy(fupr_graph* g);
  *   conv_tile = <tile name>                       force a tile of the general kernel
  *   conv_patch, conv1x1_stream, conv1x1_pipe, conv1x1_fuse, block_fuse = 0
  *                                                 leave that kernel family out
+ *   pipe_order = 0                                tiles of the pipelined 1 x 1 kernel as one contiguous
+ *                                                 range per workgroup, not consecutive tiles per XCD
  *   split = 1..4                                  sub-batches of the per-operator schedule
  *   res_item = "M/FT/nsteps:MTxNT,..."            work-item shapes of the one-kernel schedule
  *   debug = 1                                     planner decisions and HIP error text on stderr

@@ -30,6 +30,7 @@ ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_MASK_EMPTY, ERR_BN_VAR = -1, -2, -3, -4, -5
 ERR_WORKSPACE, ERR_ALIGN, ERR_LAUNCH, ERR_ARG, ERR_LIMIT, ERR_BN_SCALE = -6, -7, -8, -9, -10, -11
 F32, BF16, F16 = 0, 1, 2
 FUSE_BN, FUSE_RELU, FUSE_ADD, FUSE_SCATTER, FUSE_CAT = 1, 2, 4, 8, 16
+CAT_ALIGN = 64   # FUPR_CAT_ALIGN
 OP_CONV, OP_MAXPOOL, OP_AVGPOOL = 0, 1, 2
 SHORTCUT_IDENTITY, SHORTCUT_SUBSAMPLE_PAD, SHORTCUT_PROJECTION = 0, 1, 2
 SCHEDULE_AUTO, SCHEDULE_PER_LAYER = 0, 1
@@ -229,7 +230,7 @@ def fupr_proj_concat(last, W, b, proj, Wp, bp):
     W, Wp = _f32(W), _f32(Wp)
     b = None if b is None else _f32(b)
     bp = None if bp is None else _f32(bp)
-    c1p = (last.C + 31) // 32 * 32
+    c1p = (last.C + CAT_ALIGN - 1) // CAT_ALIGN * CAT_ALIGN
     W_out = np.empty((last.K, c1p + proj.C, 1, 1), dtype=np.float32)
     b_out = np.empty(last.K, dtype=np.float32)
     out = ConvShape()

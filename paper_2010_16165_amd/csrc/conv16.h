@@ -29,7 +29,7 @@ struct Conv16Params {
   // A second input tensor (fupr_conv_cat_fused, 1 x 1 convolutions only): the
   // 8-channel chunks from `split` on come from x2, read at spatial stride
   // stride2; the chunks before it from x.  x2 = nullptr otherwise.  split is a
-  // multiple of 4 (one MFMA step).  Only conv1x1.hip and conv1x1_pipe.hip read these.
+  // multiple of 8 (FUPR_CAT_ALIGN channels).  Only conv1x1.hip and conv1x1_pipe.hip read these.
   const uint16_t* x2;
   uint32_t x2_bytes;
   int split, H2, W2, xcs2, stride2;

@@ -59,7 +59,7 @@ struct StreamParams {
   int w_lds_bytes;       // LDS bytes of the first convolution's filters
   int n_tiles;           // 16-pixel tiles
   // second input tensor: chunks from `split` on come from x2 at spatial stride
-  // stride2 (split is a multiple of 4; 1 << 30 when there is no second tensor)
+  // stride2 (split is a multiple of 8; 1 << 30 when there is no second tensor)
   const uint16_t* x2;
   uint32_t x2_bytes;
   int split, H2, W2, xcs2, stride2;

@@ -10,8 +10,11 @@
 // computing waves multiply the current unit; a ring of 3 - 4 buffers keeps 2 - 3
 // units in flight (these layers multiply little per byte: memory latency times
 // the bytes in flight bounds them); one barrier per unit; workgroups are
-// persistent over a contiguous range of tiles, so the loads of the next tile
-// fly during the last units of the current one.
+// persistent, so the loads of the next tile fly during the last units of the
+// current one.  Tiles are numbered strip of pixels first, group of filters
+// second, and the workgroups of one XCD take consecutive tiles at the same
+// time: the filter groups of a strip read its pixels from that XCD's L2 while
+// they are there, not once per group from memory.
 // Epilogue: bias, shortcut, ReLU, one rounding, 16-byte accesses (pairs of
 // filter tiles exchanged between 16-lane rows).
 #include <hip/hip_runtime.h>
@@ -49,10 +52,11 @@ struct PipeParams {
   int relu;
   int plain;             // output pixel m is input pixel m and shortcut pixel m
   int fgroups, tiles;
+  int xcd_order;         // 1: workgroups of one XCD take consecutive tiles; 0: a range of tiles each
   int tiles_q, tiles_r;  // tiles / grid, tiles % grid
   FastDiv divPQ, divQ, divF;
   // second input tensor: chunks from `split` on come from x2 at spatial stride
-  // stride2 (split is a multiple of 4; 1 << 30 when there is no second tensor)
+  // stride2 (split is a multiple of 8; 1 << 30 when there is no second tensor)
   const uint16_t* x2;
   uint32_t x2_bytes;
   int split, H2, W2, xcs2, stride2;
@@ -97,127 +101,169 @@ __device__ __forceinline__ void wait_loads() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-// WM x WN computing waves of MT x NT 16 x 16 tiles, plus the loading waves.
-// A unit is kSteps MFMA steps of 32 channels; D buffers form a ring, so D - 1
+// What the two kernels below share.  A tile is BM output pixels x NF filters; a
+// unit is kSteps steps of 32 channels of it; D buffers form a ring, so D - 1
 // units are in flight (the layers this kernel serves multiply little per byte:
 // what bounds them is memory latency times the bytes LDS can hold in flight).
 // LDS per buffer: weights [kSteps * 4 chunks][NF][16 bytes], then pixels
-// [kSteps][2 planes of 16 channels][BM][32 bytes].
+// [kSteps / 2][BM][128 bytes]: 64 channels of a pixel side by side, so that one
+// load instruction fetches whole 128-byte lines of 8 pixels; the eight 16-byte
+// pieces of a row are stored at piece ^ ((pixel >> 1) & 7), which keeps the
+// operand reads of 16 or 32 lanes (pixels 128 bytes apart) off each other's banks.
+template <int BM_, int NF_, int kSteps_, int D_>
+struct PipeGeom {
+  static constexpr int BM = BM_, NF = NF_, kSteps = kSteps_, D = D_;
+  static constexpr int NL = kLoaderWaves * 64;
+  static constexpr int kWeightSlots = kSteps * 4 * NF;
+  static constexpr int kWeightLoads = (kWeightSlots + NL - 1) / NL;
+  static constexpr int kWeightBytes = kWeightLoads * NL * 16;
+  static constexpr int kPixelSlots = kSteps * 2 * BM * 2;
+  static constexpr int kPixelLoads = kPixelSlots / NL;
+  static_assert(kPixelSlots % NL == 0, "whole waves of pixel loads");
+  static constexpr int kBufBytes = kWeightBytes + kPixelSlots * 16;
+  static_assert(kSteps % 2 == 0, "pixels are stored 64 channels at a time");
+  static constexpr int kWStep = 4 * NF * 16;   // bytes of weights per 32-channel step
+  static constexpr int kPHalf = BM * 128;      // bytes of pixels per 64 channels
+};
+
+// The tiles of a workgroup: t_begin, t_begin + t_step, ... (t_count of them).
+// Workgroups go to the XCDs in turn, so with a grid of 8 n workgroups those
+// numbered x, x + 8, ... share XCD x and take n consecutive tiles per round.
+struct PipeTiles {
+  int t_begin, t_step, t_count;
+};
+__device__ __forceinline__ PipeTiles pipe_tiles_of_workgroup(const PipeParams& p) {
+  const int wg = blockIdx.x, grid = gridDim.x;
+  PipeTiles t;
+  if (p.xcd_order) {
+    t.t_begin = (grid & 7) == 0 ? (wg & 7) * (grid >> 3) + (wg >> 3) : wg;
+    t.t_step = grid;
+    t.t_count = p.tiles_q + (t.t_begin < p.tiles_r ? 1 : 0);
+  } else {
+    t.t_begin = wg * p.tiles_q + min(wg, p.tiles_r);
+    t.t_step = 1;
+    t.t_count = p.tiles_q + (wg < p.tiles_r ? 1 : 0);
+  }
+  return t;
+}
+
+// A loading wave (number lw of kLoaderWaves): all units of the workgroup's tiles,
+// global -> LDS, one barrier per unit with the computing waves.
+template <typename G>
+__device__ __forceinline__ void pipe_loader(const PipeParams& p, uint32_t lds_base, int lw, int lane,
+                                            int t_begin, int t_step, int n_units) {
+  constexpr int BM = G::BM, NF = G::NF, kSteps = G::kSteps, D = G::D;
+  constexpr int kWeightSlots = G::kWeightSlots, kWeightLoads = G::kWeightLoads;
+  constexpr int kWeightBytes = G::kWeightBytes, kPixelLoads = G::kPixelLoads, kBufBytes = G::kBufBytes;
+  const i32x4 xrsrc = pipe_rsrc(p.x, p.x_bytes), wrsrc = pipe_rsrc(p.w, p.w_bytes);
+  const i32x4 x2rsrc = pipe_rsrc(p.x2, p.x2_bytes);
+  // pixel slot s = ((64-channel block * BM) + pixel) * 8 + stored piece
+  uint32_t poff[kPixelLoads];    // byte offset in x of the slot's pixel; kOutside: none
+  uint32_t poff2[kPixelLoads];   // likewise in x2
+  int l_f0 = 0;
+  auto setup_load = [&](int tile) {
+    const int strip = div_by(tile, p.divF);
+    l_f0 = (tile - strip * p.fgroups) * NF;
+    const int m0 = strip * BM;
+#pragma unroll
+    for (int i = 0; i < kPixelLoads; ++i) {
+      const int s = (i * kLoaderWaves + lw) * 64 + lane;
+      const int m = m0 + ((s >> 3) % BM);
+      uint32_t off = kOutside, off2 = kOutside;
+      if (m < p.M) {
+        if (p.plain) off = (uint32_t)m * (uint32_t)(p.xcs * 2);
+        if (!p.plain || p.x2) {
+          const int n = div_by(m, p.divPQ), rem = m - n * p.PQ;
+          const int pp = div_by(rem, p.divQ), qq = rem - pp * p.Q;
+          if (!p.plain)
+            off = (uint32_t)(((n * p.H + pp * p.stride) * p.W + qq * p.stride) * p.xcs) * 2u;
+          off2 = (uint32_t)(((n * p.H2 + pp * p.stride2) * p.W2 + qq * p.stride2) * p.xcs2) * 2u;
+        }
+      }
+      poff[i] = off;
+      poff2[i] = off2;
+    }
+  };
+  auto issue = [&](int unit, uint32_t dst) {
+#pragma unroll
+    for (int i = 0; i < kWeightLoads; ++i) {
+      const int sbase = (i * kLoaderWaves + lw) * 64, s = sbase + lane;
+      const int row = s / NF, f = s - row * NF;          // row = step * 4 + chunk of the step
+      const int cc = unit * (kSteps * 4) + row;
+      const bool ok = s < kWeightSlots && cc < p.cpt && l_f0 + f < p.Kp;
+      const uint32_t off = ok ? (uint32_t)(cc * p.Kp + l_f0 + f) * 16u : kOutside;
+      pipe_load_to_lds(wrsrc, off, dst + sbase * 16);
+    }
+#pragma unroll
+    for (int i = 0; i < kPixelLoads; ++i) {
+      const int sbase = (i * kLoaderWaves + lw) * 64, s = sbase + lane;
+      const int pixel = (s >> 3) % BM;
+      const int piece = (s & 7) ^ ((pixel >> 1) & 7);
+      // the 64 slots of one load are 64 channels of 8 pixels, and the second tensor
+      // starts at a multiple of 64 channels: one tensor per load
+      const int first = __builtin_amdgcn_readfirstlane(unit * (kSteps * 4) + (sbase >> 3) / BM * 8);
+      const int chunk = first + piece;
+      if (first < p.split) {
+        const uint32_t off = chunk * 8 < p.xcs ? poff[i] + (uint32_t)chunk * 16u : kOutside;
+        pipe_load_to_lds(xrsrc, off, dst + kWeightBytes + sbase * 16);
+      } else {
+        const int c2 = chunk - p.split;
+        const uint32_t off = c2 * 8 < p.xcs2 ? poff2[i] + (uint32_t)c2 * 16u : kOutside;
+        pipe_load_to_lds(x2rsrc, off, dst + kWeightBytes + sbase * 16);
+      }
+    }
+  };
+
+  constexpr int L = kWeightLoads + kPixelLoads;   // loads per thread and unit
+  static_assert((D - 2) * L <= 63, "the load counter holds 63");
+  int l_tile = t_begin, l_unit = 0;
+  int issued = 0;
+  auto issue_next = [&]() {   // unit number `issued` of this workgroup into its ring slot
+    if (l_unit == 0) setup_load(l_tile);
+    issue(l_unit, lds_base + (uint32_t)(issued % D) * (uint32_t)kBufBytes);
+    if (++l_unit == p.n_units) { l_unit = 0; l_tile += t_step; }
+    ++issued;
+  };
+  // before barrier u: unit u has landed, up to D - 2 younger units may be in flight
+  auto wait_for = [&](int u) {
+    const int younger = issued - 1 - u;
+    if (D >= 4 && younger >= 2) wait_loads<(D >= 4 ? 2 : 0) * L>();
+    else if (D >= 3 && younger >= 1) wait_loads<(D >= 3 ? 1 : 0) * L>();
+    else wait_loads<0>();
+  };
+  for (int k = 0; k < D - 1 && issued < n_units; ++k) issue_next();
+  wait_for(0);
+  for (int u = 0; u < n_units; ++u) {
+    __syncthreads();   // unit u is in LDS; the computing waves have finished unit u - 1
+    if (issued < n_units) issue_next();   // into the slot unit u - 1 has left
+    if (u + 1 < n_units) wait_for(u + 1);
+  }
+}
+
+// WM x WN computing waves of MT x NT tiles of 16 x 16 (MFMA 16 x 16 x 32), plus the
+// loading waves.
 template <bool BF, int WM, int WN, int MT, int NT, int kSteps, int D>
 __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv1x1_pipe_kernel(
     const PipeParams p) {
   static_assert(NT % 2 == 0, "filter tiles are stored in pairs");
+  using G = PipeGeom<WM * MT * 16, WN * NT * 16, kSteps, D>;
   constexpr int NWC = WM * WN;
-  constexpr int NL = kLoaderWaves * 64;
-  constexpr int NF = WN * NT * 16;
-  constexpr int BM = WM * MT * 16;
-  constexpr int kWeightSlots = kSteps * 4 * NF;
-  constexpr int kWeightLoads = (kWeightSlots + NL - 1) / NL;
-  constexpr int kWeightBytes = kWeightLoads * NL * 16;
-  constexpr int kPixelSlots = kSteps * 2 * BM * 2;
-  constexpr int kPixelLoads = kPixelSlots / NL;
-  static_assert(kPixelSlots % NL == 0, "whole waves of pixel loads");
-  constexpr int kBufBytes = kWeightBytes + kPixelSlots * 16;
-  constexpr int kWStep = 4 * NF * 16;          // bytes of weights per 32-channel step
-  constexpr int kPStep = 2 * BM * 32;          // bytes of pixels per 32-channel step
+  constexpr int NF = G::NF, BM = G::BM;
+  constexpr int kWeightBytes = G::kWeightBytes, kBufBytes = G::kBufBytes;
+  constexpr int kWStep = G::kWStep, kPHalf = G::kPHalf;
   extern __shared__ uint4 lds4[];
   char* lds = reinterpret_cast<char*>(lds4);
   const uint32_t lds_base = (uint32_t)(uintptr_t)(LdsPtr)lds;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-
-  const int wg = blockIdx.x;
-  const int t_begin = wg * p.tiles_q + min(wg, p.tiles_r);
-  const int t_end = t_begin + p.tiles_q + (wg < p.tiles_r ? 1 : 0);
-  const int n_units = (t_end - t_begin) * p.n_units;
+  const PipeTiles tl = pipe_tiles_of_workgroup(p);
+  const int t_begin = tl.t_begin, t_step = tl.t_step;
+  const int n_units = tl.t_count * p.n_units;
   if (n_units <= 0) return;
 
   if (wave >= NWC) {
-    // ================================ loading waves ================================
-    const int lw = wave - NWC;
-    const i32x4 xrsrc = pipe_rsrc(p.x, p.x_bytes), wrsrc = pipe_rsrc(p.w, p.w_bytes);
-    const i32x4 x2rsrc = pipe_rsrc(p.x2, p.x2_bytes);
-    // pixel slot s = ((step * 2 + plane) * BM + pixel) * 2 + half
-    uint32_t poff[kPixelLoads];    // byte offset in x of the slot's pixel; kOutside: none
-    uint32_t poff2[kPixelLoads];   // likewise in x2
-    int l_f0 = 0;
-    auto setup_load = [&](int tile) {
-      const int strip = div_by(tile, p.divF);
-      l_f0 = (tile - strip * p.fgroups) * NF;
-      const int m0 = strip * BM;
-#pragma unroll
-      for (int i = 0; i < kPixelLoads; ++i) {
-        const int s = (i * kLoaderWaves + lw) * 64 + lane;
-        const int m = m0 + ((s >> 1) % BM);
-        uint32_t off = kOutside, off2 = kOutside;
-        if (m < p.M) {
-          if (p.plain) off = (uint32_t)m * (uint32_t)(p.xcs * 2);
-          if (!p.plain || p.x2) {
-            const int n = div_by(m, p.divPQ), rem = m - n * p.PQ;
-            const int pp = div_by(rem, p.divQ), qq = rem - pp * p.Q;
-            if (!p.plain)
-              off = (uint32_t)(((n * p.H + pp * p.stride) * p.W + qq * p.stride) * p.xcs) * 2u;
-            off2 = (uint32_t)(((n * p.H2 + pp * p.stride2) * p.W2 + qq * p.stride2) * p.xcs2) * 2u;
-          }
-        }
-        poff[i] = off;
-        poff2[i] = off2;
-      }
-    };
-    auto issue = [&](int unit, uint32_t dst) {
-#pragma unroll
-      for (int i = 0; i < kWeightLoads; ++i) {
-        const int sbase = (i * kLoaderWaves + lw) * 64, s = sbase + lane;
-        const int row = s / NF, f = s - row * NF;          // row = step * 4 + chunk of the step
-        const int cc = unit * (kSteps * 4) + row;
-        const bool ok = s < kWeightSlots && cc < p.cpt && l_f0 + f < p.Kp;
-        const uint32_t off = ok ? (uint32_t)(cc * p.Kp + l_f0 + f) * 16u : kOutside;
-        pipe_load_to_lds(wrsrc, off, dst + sbase * 16);
-      }
-#pragma unroll
-      for (int i = 0; i < kPixelLoads; ++i) {
-        const int sbase = (i * kLoaderWaves + lw) * 64, s = sbase + lane;
-        const int half = s & 1, sp = (s >> 1) / BM;        // sp = step * 2 + plane
-        const int chunk = unit * (kSteps * 4) + sp * 2 + half;
-        // the 64 slots of one load lie in one plane of 16 channels, and the second
-        // tensor starts at a multiple of 32 channels: one tensor per load
-        const int first = __builtin_amdgcn_readfirstlane(unit * (kSteps * 4) + (sbase >> 1) / BM * 2);
-        if (first < p.split) {
-          const uint32_t off = chunk * 8 < p.xcs ? poff[i] + (uint32_t)chunk * 16u : kOutside;
-          pipe_load_to_lds(xrsrc, off, dst + kWeightBytes + sbase * 16);
-        } else {
-          const int c2 = chunk - p.split;
-          const uint32_t off = c2 * 8 < p.xcs2 ? poff2[i] + (uint32_t)c2 * 16u : kOutside;
-          pipe_load_to_lds(x2rsrc, off, dst + kWeightBytes + sbase * 16);
-        }
-      }
-    };
-
-    constexpr int L = kWeightLoads + kPixelLoads;   // loads per thread and unit
-    static_assert((D - 2) * L <= 63, "the load counter holds 63");
-    int l_tile = t_begin, l_unit = 0;
-    int issued = 0;
-    auto issue_next = [&]() {   // unit number `issued` of this workgroup into its ring slot
-      if (l_unit == 0) setup_load(l_tile);
-      issue(l_unit, lds_base + (uint32_t)(issued % D) * (uint32_t)kBufBytes);
-      if (++l_unit == p.n_units) { l_unit = 0; ++l_tile; }
-      ++issued;
-    };
-    // before barrier u: unit u has landed, up to D - 2 younger units may be in flight
-    auto wait_for = [&](int u) {
-      const int younger = issued - 1 - u;
-      if (D >= 4 && younger >= 2) wait_loads<(D >= 4 ? 2 : 0) * L>();
-      else if (D >= 3 && younger >= 1) wait_loads<(D >= 3 ? 1 : 0) * L>();
-      else wait_loads<0>();
-    };
-    for (int k = 0; k < D - 1 && issued < n_units; ++k) issue_next();
-    wait_for(0);
-    for (int u = 0; u < n_units; ++u) {
-      __syncthreads();   // unit u is in LDS; the computing waves have finished unit u - 1
-      if (issued < n_units) issue_next();   // into the slot unit u - 1 has left
-      if (u + 1 < n_units) wait_for(u + 1);
-    }
+    pipe_loader<G>(p, lds_base, wave - NWC, lane, t_begin, t_step, n_units);
     return;
   }
 
@@ -236,7 +282,8 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv1x1_pipe_ke
   int rin[MT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
-    rin[mt] = ((wm * MT + mt) * 16 + li) * 32 + (g >> 1) * (BM * 32) + (g & 1) * 16;
+    rin[mt] = ((wm * MT + mt) * 16 + li) * 128 + ((g ^ ((li >> 1) & 7)) * 16);   // even steps; odd: ^ 64
+  // the tile's pixel offsets; its accumulators start at zero
   auto setup_compute = [&](int tile) {
     const int strip = div_by(tile, p.divF);
     c_f0 = (tile - strip * p.fgroups) * NF;
@@ -258,47 +305,61 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv1x1_pipe_ke
       }
     }
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      const int k0 = min(c_f0 + (wn * NT + t) * 16, p.Kp - 16) + g * 4;
-      bias4[t] = *reinterpret_cast<const f32x4*>(p.bias + k0);
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
   };
   const int a_lane = g * (NF * 16) + (wn * NT * 16 + li) * 16;
   const int k_pair = wn * NT * 16 + (g & 1) * 16 + (g >> 1) * 8;
   const uint32_t floor2 = p.relu ? 0u : 0x80008000u;
 
+  // The steps of all units form one stream: the operands of a step are read from
+  // LDS while the step before it multiplies, also across units.  The barrier that
+  // says unit u + 1 has landed therefore stands before the last step of unit u
+  // multiplies (that step's operands are in registers by then, so the loading
+  // waves may overwrite unit u from this barrier on, as before).
+  uint4 a[2][NT], b[2][MT];
+  auto operands = [&](const char* wts, int step, uint4* av, uint4* bv) {
+    const char* pix = wts + kWeightBytes;
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+      av[t] = *reinterpret_cast<const uint4*>(wts + a_lane + step * kWStep + t * 256);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+      bv[mt] = *reinterpret_cast<const uint4*>(pix + (rin[mt] ^ ((step & 1) * 64)) + (step >> 1) * kPHalf);
+  };
   int c_tile = t_begin, c_unit = 0;
+  __syncthreads();   // unit 0 is in LDS
+  setup_compute(c_tile);
+  operands(lds, 0, a[0], b[0]);
   for (int u = 0; u < n_units; ++u) {
-    __syncthreads();   // unit u is in LDS
-    if (c_unit == 0) setup_compute(c_tile);
     const bool last = c_unit == p.n_units - 1;
-    if (last && p.res) {
+    if (last) {   // what the epilogue adds, fetched while the last unit multiplies
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
+      for (int t = 0; t < NT; ++t) {
+        const int k0 = min(c_f0 + (wn * NT + t) * 16, p.Kp - 16) + g * 4;
+        bias4[t] = *reinterpret_cast<const f32x4*>(p.bias + k0);
+      }
+      if (p.res) {
 #pragma unroll
-        for (int pr = 0; pr < NP; ++pr) {
-          const int rc = c_f0 + k_pair + pr * 32 - p.roff;
-          const uint32_t off = (rc >= 0 && rc < p.rcs) ? roff[mt] + (uint32_t)rc * 2u : kOutside;
-          rvw[mt][pr] = __builtin_amdgcn_raw_buffer_load_b128(rrsrc, off, 0, 0);
-        }
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int pr = 0; pr < NP; ++pr) {
+            const int rc = c_f0 + k_pair + pr * 32 - p.roff;
+            const uint32_t off = (rc >= 0 && rc < p.rcs) ? roff[mt] + (uint32_t)rc * 2u : kOutside;
+            rvw[mt][pr] = __builtin_amdgcn_raw_buffer_load_b128(rrsrc, off, 0, 0);
+          }
+      }
     }
     const char* wts = lds + (u % D) * kBufBytes;
-    const char* pix = wts + kWeightBytes;
-    uint4 a[2][NT], b[2][MT];
-    auto operands = [&](int step, uint4* av, uint4* bv) {
-#pragma unroll
-      for (int t = 0; t < NT; ++t)
-        av[t] = *reinterpret_cast<const uint4*>(wts + a_lane + step * kWStep + t * 256);
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-        bv[mt] = *reinterpret_cast<const uint4*>(pix + rin[mt] + step * kPStep);
-    };
-    operands(0, a[0], b[0]);
 #pragma unroll
     for (int step = 0; step < kSteps; ++step) {
-      if (step + 1 < kSteps) operands(step + 1, a[(step + 1) & 1], b[(step + 1) & 1]);
+      if (step + 1 < kSteps) {
+        operands(wts, step + 1, a[(step + 1) & 1], b[(step + 1) & 1]);
+      } else if (u + 1 < n_units) {
+        __syncthreads();   // unit u + 1 is in LDS
+        operands(lds + ((u + 1) % D) * kBufBytes, 0, a[0], b[0]);
+      }
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -343,21 +404,225 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv1x1_pipe_ke
         }
       }
       c_unit = 0;
-      ++c_tile;
+      c_tile += t_step;
+      if (u + 1 < n_units) setup_compute(c_tile);
     } else {
       ++c_unit;
     }
   }
 }
 
+// The same pipeline on the 32 x 32 x 16 MFMA, which sustains the matrix cores' full
+// rate on gfx950 where 16 x 16 x 32 sustains 57 % of it: WM x WN computing waves, each
+// owning MT pixel tiles x NT filter tiles of 32 x 32 (16 accumulator registers each).
+// LDS layout and loading waves are shared with conv1x1_pipe_kernel.  A step is 16
+// channels here: lane (index j = lane % 32, half h = lane / 32) reads chunk 2 * step + h
+// of filter j and piece 2 * step + h of pixel j.  The operands of a step are read PD
+// steps ahead of its MFMAs (2 or 4 register sets in turn), also across units: the barrier
+// that says unit u + 1 has landed stands PD steps before the end of unit u, and every
+// read of unit u has been issued before it.  The layer's biases are staged in LDS once
+// (behind the ring of buffers) and a tile's accumulators start from them, so the
+// epilogue holds no bias registers.  A finished tile holds, per lane, channels
+// 8 b + 4 h .. + 3 (b = 0 .. 3) of pixel j; the two lanes of a pixel exchange halves
+// (v_permlane32_swap) so that each stores 16 bytes: channels 16 pr + 8 h .. + 7.
+constexpr int kPipeBiasBytes = 8192;   // up to 2048 filters per layer in the 32 x 32 kernel
+template <bool BF, int WM, int WN, int MT, int NT, int kSteps, int D, int PD>
+__global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv1x1_pipe32_kernel(
+    const PipeParams p) {
+  using G = PipeGeom<WM * MT * 32, WN * NT * 32, kSteps, D>;
+  constexpr int NWC = WM * WN;
+  constexpr int NF = G::NF;
+  constexpr int kWeightBytes = G::kWeightBytes, kBufBytes = G::kBufBytes, kPHalf = G::kPHalf;
+  constexpr int S = 2 * kSteps;                // steps of 16 channels per unit
+  constexpr int SETS = PD == 1 ? 2 : 4;        // operand register sets
+  static_assert((PD == 1 || PD == 2) && S % SETS == 0, "operand register sets in turn");
+  constexpr int kWHalf = 2 * NF * 16;          // bytes of weights per 16-channel step
+  extern __shared__ uint4 lds4[];
+  char* lds = reinterpret_cast<char*>(lds4);
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(LdsPtr)lds;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const PipeTiles tl = pipe_tiles_of_workgroup(p);
+  const int t_begin = tl.t_begin, t_step = tl.t_step;
+  const int n_units = tl.t_count * p.n_units;
+  if (n_units <= 0) return;
+
+  if (wave >= NWC) {
+    pipe_loader<G>(p, lds_base, wave - NWC, lane, t_begin, t_step, n_units);
+    return;
+  }
+
+  // ================================ computing waves ================================
+  const int j = lane & 31, h = lane >> 5;
+  const int wm = wave % WM, wn = wave / WM;
+  const __amdgpu_buffer_rsrc_t yrsrc =
+      __builtin_amdgcn_make_buffer_rsrc(p.y, 0, p.y_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rrsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.res), 0, p.res_bytes, 0x00020000);
+  uint32_t yoff[MT], roff[MT];
+  int c_f0 = 0;
+  f32x16 acc[MT][NT];
+  u32x4 rvw[MT][NT][2];   // shortcut values, fetched during the last unit of a tile
+  const float* lds_bias = reinterpret_cast<const float*>(lds + D * kBufBytes);
+  int rin[MT];            // step 0 of a 64-channel block; step s of it: ^ (s * 32)
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+    rin[mt] = ((wm * MT + mt) * 32 + j) * 128 + ((h ^ ((j >> 1) & 7)) * 16);
+  auto setup_compute = [&](int tile) {
+    const int strip = div_by(tile, p.divF);
+    c_f0 = (tile - strip * p.fgroups) * NF;
+    const int m0 = strip * G::BM;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = m0 + (wm * MT + mt) * 32 + j;
+      yoff[mt] = kOutside;
+      roff[mt] = kOutside;
+      if (m < p.M) {
+        yoff[mt] = (uint32_t)m * (uint32_t)(p.ycs * 2);
+        if (p.plain) {
+          roff[mt] = (uint32_t)m * (uint32_t)(p.rcs * 2);
+        } else if (p.res) {
+          const int n = div_by(m, p.divPQ), rem = m - n * p.PQ;
+          const int pp = div_by(rem, p.divQ), qq = rem - pp * p.Q;
+          roff[mt] = (uint32_t)(((n * p.rH + pp * p.rss) * p.rW + qq * p.rss) * p.rcs) * 2u;
+        }
+      }
+    }
+    // the accumulators start from the biases of their filters
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const int kt = c_f0 + (wn * NT + t) * 32;   // first filter of this 32-row tile
+#pragma unroll
+      for (int bb = 0; bb < 4; ++bb) {
+        const f32x4 b4 = *reinterpret_cast<const f32x4*>(lds_bias + min(kt + 8 * bb + 4 * h, p.Kp - 4));
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) acc[mt][t][4 * bb + i] = b4[i];
+      }
+    }
+  };
+  const int a_lane = h * (NF * 16) + (wn * NT * 32 + j) * 16;
+  const int k_lane = wn * NT * 32 + h * 8;   // first channel of this lane's 16 bytes, pair 0 of tile 0
+  const uint32_t floor2 = p.relu ? 0u : 0x80008000u;
+
+  uint4 a[SETS][NT], b[SETS][MT];
+  auto operands = [&](const char* wts, int step, uint4* av, uint4* bv) {
+    const char* pix = wts + kWeightBytes + (step >> 2) * kPHalf;
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+      av[t] = *reinterpret_cast<const uint4*>(wts + a_lane + step * kWHalf + t * 512);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+      bv[mt] = *reinterpret_cast<const uint4*>(pix + (rin[mt] ^ ((step & 3) * 32)));
+  };
+  int c_tile = t_begin, c_unit = 0;
+  // the computing waves stage the biases while the first unit is on its way
+  for (int i = wave * 64 + lane; i < p.Kp; i += NWC * 64)
+    reinterpret_cast<float*>(lds + D * kBufBytes)[i] = p.bias[i];
+  __syncthreads();   // unit 0 and the biases are in LDS
+  setup_compute(c_tile);
+#pragma unroll
+  for (int s0 = 0; s0 < PD; ++s0) operands(lds, s0, a[s0], b[s0]);
+  for (int u = 0; u < n_units; ++u) {
+    const bool last = c_unit == p.n_units - 1;
+    if (last) {   // what the epilogue adds, fetched while the last unit multiplies
+      if (p.res) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int pr = 0; pr < 2; ++pr) {
+              const int rc = c_f0 + k_lane + t * 32 + pr * 16 - p.roff;
+              const uint32_t off = (rc >= 0 && rc < p.rcs) ? roff[mt] + (uint32_t)rc * 2u : kOutside;
+              rvw[mt][t][pr] = __builtin_amdgcn_raw_buffer_load_b128(rrsrc, off, 0, 0);
+            }
+      }
+    }
+    const char* wts = lds + (u % D) * kBufBytes;
+    const char* next = lds + ((u + 1) % D) * kBufBytes;
+#pragma unroll
+    for (int step = 0; step < S; ++step) {
+      const int ns = step + PD;   // the step whose operands are read now
+      if (ns < S) {
+        operands(wts, ns, a[ns % SETS], b[ns % SETS]);
+      } else if (u + 1 < n_units) {
+        if (ns == S) __syncthreads();   // unit u + 1 is in LDS
+        operands(next, ns - S, a[ns % SETS], b[ns % SETS]);
+      }
+      // the reads stay in front of this step's MFMAs: left alone, the scheduler sinks
+      // every read to just before its use and each MFMA waits out an LDS round trip
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+          acc[mt][t] = mfma_32x32x16<BF>(a[step % SETS][t], b[step % SETS][mt], acc[mt][t]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (!last) {
+      ++c_unit;
+      continue;
+    }
+    // ---- epilogue: bias, shortcut, ReLU, one rounding, 16-byte stores ----
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int pr = 0; pr < 2; ++pr) {
+          // shortcut values into the accumulators' layout: the lanes of a pixel exchange halves
+          uint32_t ra[2] = {0u, 0u}, rb[2] = {0u, 0u};
+          if (p.res) {
+            const u32x4 r4 = rvw[mt][t][pr];
+            const auto s0 = __builtin_amdgcn_permlane32_swap(r4[0], r4[2], false, false);
+            const auto s1 = __builtin_amdgcn_permlane32_swap(r4[1], r4[3], false, false);
+            ra[0] = s0[0]; ra[1] = s1[0];   // group 2 pr
+            rb[0] = s0[1]; rb[1] = s1[1];   // group 2 pr + 1
+          }
+          auto finish = [&](int bb, const uint32_t* r) {
+            float v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = acc[mt][t][4 * bb + i];
+            if (p.res) {
+              v[0] += to_float<BF>((uint16_t)(r[0] & 0xffffu));
+              v[1] += to_float<BF>((uint16_t)(r[0] >> 16));
+              v[2] += to_float<BF>((uint16_t)(r[1] & 0xffffu));
+              v[3] += to_float<BF>((uint16_t)(r[1] >> 16));
+            }
+            u32x2 o;
+            o[0] = pipe_clamp(pack2<BF>(v[0], v[1]), floor2);
+            o[1] = pipe_clamp(pack2<BF>(v[2], v[3]), floor2);
+            return o;
+          };
+          const u32x2 oa = finish(2 * pr, ra), ob = finish(2 * pr + 1, rb);
+          const auto w0 = __builtin_amdgcn_permlane32_swap(oa[0], ob[0], false, false);
+          const auto w1 = __builtin_amdgcn_permlane32_swap(oa[1], ob[1], false, false);
+          const u32x4 o4 = {w0[0], w1[0], w0[1], w1[1]};
+          const int k0 = c_f0 + k_lane + t * 32 + pr * 16;
+          const uint32_t off = k0 < p.ycs ? yoff[mt] + (uint32_t)k0 * 2u : kOutside;
+          __builtin_amdgcn_raw_buffer_store_b128(o4, yrsrc, off, 0, 0);
+        }
+    c_unit = 0;
+    c_tile += t_step;
+    if (u + 1 < n_units) setup_compute(c_tile);
+  }
+}
+
 struct PipeTile {
   int WM, WN, MT, NT, steps, depth;
   const char* name;
+  bool wide;   // MFMA tiles of 32 x 32 (conv1x1_pipe32_kernel), else 16 x 16
 };
 constexpr PipeTile kPipeTiles[] = {
-    {2, 2, 4, 4, 2, 4, "conv1x1p_128x128"},
-    {4, 1, 2, 4, 4, 3, "conv1x1p_128x64"},
-    {2, 2, 2, 2, 4, 4, "conv1x1p_64x64"},
+    {2, 2, 4, 4, 2, 4, "conv1x1p_128x128", false},
+    {4, 1, 2, 4, 4, 3, "conv1x1p_128x64", false},
+    {2, 2, 2, 2, 4, 4, "conv1x1p_64x64", false},
+    {2, 2, 2, 2, 2, 4, "conv1x1q_128x128", true},
+    {2, 4, 2, 2, 2, 3, "conv1x1q_128x256", true},   // before 256 x 128: it wins a tie
+    {4, 2, 2, 2, 2, 3, "conv1x1q_256x128", true},
 };
 constexpr int kNumPipeTiles = sizeof(kPipeTiles) / sizeof(kPipeTiles[0]);
 
@@ -389,6 +654,7 @@ bool plan_pipe(const Conv16Params& c, PipePlan* out) {
   if (tuning_off("conv1x1_pipe")) return false;
   if (c.S != 1 || c.nchunk != c.cpt || c.pad != 0 || (c.stride != 1 && c.stride != 2)) return false;
   if (c.roff % 8 != 0) return false;
+  if (c.x2 && c.split % 8 != 0) return false;   // a load fetches 64 channels of one tensor
   if (c.cpt < 16) return false;   // fewer than 128 channels: one unit, nothing to pipeline
   const int forced = tuning_int("pipe_tile", -1);
   const int cus = pipe_compute_units();
@@ -396,29 +662,40 @@ bool plan_pipe(const Conv16Params& c, PipePlan* out) {
   bool found = false;
   for (int i = 0; i < kNumPipeTiles; ++i) {
     const PipeTile& t = kPipeTiles[i];
-    const int BM = t.WM * t.MT * 16, NF = t.WN * t.NT * 16;
+    const int edge = t.wide ? 32 : 16;
+    const int BM = t.WM * t.MT * edge, NF = t.WN * t.NT * edge;
     const int NL = kLoaderWaves * 64;
+    // (four waves of 64 x 64 on the 32 x 32 MFMA: measured equal to tile 0 on every layer)
+    if (t.wide && t.WM * t.WN == 4 && i != forced) continue;
     const int units = (c.cpt + 4 * t.steps - 1) / (4 * t.steps);
     const size_t wbytes = (size_t)((t.steps * 4 * NF + NL - 1) / NL) * NL * 16;
     const size_t buf = wbytes + (size_t)t.steps * 2 * BM * 2 * 16;
-    if (t.depth * buf > kPipeLdsLimit) continue;
+    const size_t lds_need = t.depth * buf + (t.wide ? kPipeBiasBytes : 0);
+    if (lds_need > kPipeLdsLimit) continue;
+    if (t.wide && c.Kp * 4 > kPipeBiasBytes) continue;
     const int fgroups = (c.Kp + NF - 1) / NF;
     const int64_t tiles = ((int64_t)c.M + BM - 1) / BM * fgroups;
     if (tiles >= (int64_t(1) << 30)) continue;
     const int grid = (int)std::min<int64_t>(tiles, cus);
     // clocks per unit: loads (bounded by the bytes in flight over the memory
-    // latency, about 4000 clocks, and by 40 bytes per clock) against MFMA + LDS reads
+    // latency, about 4000 clocks, and by 40 bytes per clock) against the MFMAs of
+    // the waves that share a SIMD (measured in this kernel: 28 clocks per
+    // 16 x 16 x 32, 40 per 32 x 32 x 16); per tile an epilogue of BM x NF / 8 clocks.
+    // A strip's pixels are read once per group of filters: a small preference for
+    // fewer groups (measured: 116 against 134 us for 320 -> 512 channels at 56 x 56 x 256).
     const double load = std::max((double)buf / 40.0, 4000.0 / (t.depth - 1));
-    const double mfma = t.steps * t.MT * t.NT * 16.0 + t.steps * (t.MT + t.NT) * 4 * 5.4;
-    const double per_tile = units * (std::max(load, mfma) + 150.0) + 400.0 + BM * NF / 16.0;
-    const double cost = 6000.0 + (double)((tiles + grid - 1) / grid) * per_tile;
+    const double per_wave = t.wide ? 2.0 * t.steps * t.MT * t.NT * 40.0 : t.steps * t.MT * t.NT * 28.0;
+    const double mfma = per_wave * (t.WM * t.WN / 4.0);
+    const double per_tile = units * (std::max(load, mfma) + 150.0) + 600.0 + BM * NF / 8.0;
+    const double cost = (6000.0 + (double)((tiles + grid - 1) / grid) * per_tile) *
+                        (1.0 + 0.02 * std::min(fgroups - 1, 3));
     if (i == forced || cost < best) {
       best = i == forced ? -1.0 : cost;
       out->tile = i;
       out->units = units;
       out->fgroups = fgroups;
       out->tiles = tiles;
-      out->lds_bytes = t.depth * buf;
+      out->lds_bytes = lds_need;
       out->grid = grid;
       found = true;
     }
@@ -441,9 +718,27 @@ fupr_status launch_pipe(const PipeParams& p, const PipePlan& plan, hipStream_t s
   return launch_status("conv1x1_pipe_kernel");
 }
 
+template <bool BF, int WM, int WN, int MT, int NT, int KS, int D, int PD>
+fupr_status launch_pipe32(const PipeParams& p, const PipePlan& plan, hipStream_t st) {
+  static std::once_flag once;
+  static hipError_t status = hipSuccess;
+  std::call_once(once, [] {
+    status =
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&conv1x1_pipe32_kernel<BF, WM, WN, MT, NT, KS, D, PD>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPipeLdsLimit);
+  });
+  if (status != hipSuccess) return FUPR_ERR_LAUNCH;
+  hipLaunchKernelGGL((conv1x1_pipe32_kernel<BF, WM, WN, MT, NT, KS, D, PD>), dim3((unsigned)plan.grid),
+                     dim3((WM * WN + kLoaderWaves) * 64), plan.lds_bytes, st, p);
+  return launch_status("conv1x1_pipe32_kernel");
+}
+
 template <bool BF>
 fupr_status dispatch_pipe(const PipeParams& p, const PipePlan& plan, hipStream_t st) {
   switch (plan.tile) {
+    case 3: return launch_pipe32<BF, 2, 2, 2, 2, 2, 4, 2>(p, plan, st);
+    case 4: return launch_pipe32<BF, 2, 4, 2, 2, 2, 3, 1>(p, plan, st);
+    case 5: return launch_pipe32<BF, 4, 2, 2, 2, 2, 3, 1>(p, plan, st);
     case 0: return launch_pipe<BF, 2, 2, 4, 4, 2, 4>(p, plan, st);
     case 1: return launch_pipe<BF, 4, 1, 2, 4, 4, 3>(p, plan, st);
     default: return launch_pipe<BF, 2, 2, 2, 2, 4, 4>(p, plan, st);
@@ -484,6 +779,7 @@ fupr_status launch_conv1x1_pipe(const Conv16Params& c, int N, bool bf16, void* s
   p.plain = c.stride == 1 && (!c.res || (c.rss == 1 && c.rH == c.P && c.rW == c.Q));
   p.fgroups = plan.fgroups;
   p.tiles = (int)plan.tiles;
+  p.xcd_order = tuning_int("pipe_order", 1) != 0;
   p.tiles_q = p.tiles / plan.grid;
   p.tiles_r = p.tiles % plan.grid;
   p.divPQ = fast_div(c.PQ);

@@ -182,7 +182,7 @@ extern "C" fupr_status fupr_proj_concat(const fupr_conv_shape* last, const float
       proj->pad != 0 || last->stride != 1 || last->K != proj->K)
     return FUPR_ERR_SHAPE;
   const int K = last->K, C1 = last->C, C2 = proj->C;
-  const int C1p = fupr::round_up(C1, 32);
+  const int C1p = fupr::round_up(C1, FUPR_CAT_ALIGN);
   if ((int64_t)K * (C1p + C2) >= (int64_t(1) << 31)) return FUPR_ERR_SHAPE;
   const size_t C = (size_t)C1p + C2;
   for (int k = 0; k < K; ++k) {

@@ -459,7 +459,7 @@ fupr_status check_conv_cat(const fupr_conv_shape* shape, const fupr_tensor* x1, 
   if (st != FUPR_OK) return st;
   if (x1->dt == FUPR_F32) return FUPR_ERR_DTYPE;
   if (x2->dt != x1->dt) return FUPR_ERR_DTYPE;
-  const int split = round_up(x1->C, 32);
+  const int split = round_up(x1->C, FUPR_CAT_ALIGN);
   if (shape->C != split + x2->C || x2->N != x1->N) return FUPR_ERR_SHAPE;
   if ((int64_t)(a.P - 1) * x2_stride >= x2->H || (int64_t)(a.Q - 1) * x2_stride >= x2->W)
     return FUPR_ERR_SHAPE;

@@ -565,7 +565,7 @@ extern "C" fupr_status fupr_model_create(const fupr_graph_desc* g, fupr_model** 
             (int64_t)(tin.W - 1) * op.in2_spatial_stride >= t2.W) {
           err = FUPR_ERR_SHAPE; break;
         }
-        c_in = round_up(tin.C, 32) + t2.C;
+        c_in = round_up(tin.C, FUPR_CAT_ALIGN) + t2.C;
       }
       if (s.C != c_in || tin.H + 2 * s.pad < s.R || tin.W + 2 * s.pad < s.S) {
         err = FUPR_ERR_SHAPE; break;

@@ -207,7 +207,8 @@ def test_every_3x3_tile_forced(fx, tile):
         B.fupr_tuning_set("patch_tile", None)
 
 
-PIPE_TILES = ["128x128", "128x64", "64x64"]
+PIPE_TILES = ["conv1x1p_128x128", "conv1x1p_128x64", "conv1x1p_64x64", "conv1x1q_128x128",
+              "conv1x1q_128x256", "conv1x1q_256x128"]
 STREAM_TILES = ["256f", "256f_c128", "128f", "64f", "64f_c512", "32f"]
 FORCED_1X1 = [
     ("forced 1x1 C520 K100 +id 14x14 x11", 11, 520, 14, 14, 100, 1, 1, 0, "identity", True),
@@ -219,7 +220,7 @@ FORCED_1X1 = [
 ]
 
 
-@pytest.mark.parametrize("tile", range(3), ids=PIPE_TILES)
+@pytest.mark.parametrize("tile", range(len(PIPE_TILES)), ids=PIPE_TILES)
 def test_every_pipelined_1x1_tile_forced(fx, tile):
     B, network, torch = fx
     B.fupr_tuning_set("pipe_tile", tile)
@@ -228,11 +229,14 @@ def test_every_pipelined_1x1_tile_forced(fx, tile):
         ran = 0
         for case in FORCED_1X1:
             for dtype in ("bf16", "f16"):
-                if kernel_of(B, dtype, case) != "conv1x1p_" + PIPE_TILES[tile]:
+                if kernel_of(B, dtype, case) != PIPE_TILES[tile]:
                     continue
                 conv_site(fx, case, dtype)
                 ran += 1
         assert ran >= 4, "the forced tile ran on too few shapes"
+        # two input tensors (the second at stride 2, ragged channel counts) through the same tile
+        for case in CAT_CASES[2:4]:
+            test_conv_cat_site(fx, case, "f16" if tile % 2 else "bf16")
     finally:
         B.fupr_tuning_set("pipe_tile", None)
         B.fupr_tuning_set("conv1x1_stream", None)
@@ -585,7 +589,7 @@ def test_conv_cat_site(fx, case, dtype):
 def test_conv_cat_rejects_bad_calls(fx):
     B, network, torch = fx
     dt = B.BF16
-    w = np.zeros((16, 32 + 8, 1, 1), np.float32)
+    w = np.zeros((16, B.CAT_ALIGN + 8, 1, 1), np.float32)
     sh = B.shape_of(w, 1, 0)
     packed = B.upload_blob(B.fupr_pack(sh, w, None, dt))
     h = B.DeviceTensor.empty(1, 4, 4, 20, dt)
@@ -603,7 +607,7 @@ def test_conv_cat_rejects_bad_calls(fx):
     expect(B.ERR_SHAPE, lambda: B.fupr_conv_cat_fused(sh, h, small, 2, packed, None, 0, y))
     wide = B.DeviceTensor.empty(1, 8, 8, 9, dt)
     expect(B.ERR_SHAPE, lambda: B.fupr_conv_cat_fused(sh, h, wide, 2, packed, None, 0, y))
-    w3 = np.zeros((16, 40, 3, 3), np.float32)
+    w3 = np.zeros((16, B.CAT_ALIGN + 8, 3, 3), np.float32)
     expect(B.ERR_SHAPE, lambda: B.fupr_conv_cat_fused(B.shape_of(w3, 1, 1), h, x, 2, packed, None, 0, y))
     h32, x32, y32 = (B.DeviceTensor.empty(1, 4, 4, 20, B.F32), B.DeviceTensor.empty(1, 8, 8, 8, B.F32),
                      B.DeviceTensor.empty(1, 4, 4, 16, B.F32))

@@ -668,10 +668,11 @@ def test_partially_fused_plan_selects_the_oracles_filters():
 
 def test_proj_concat_is_the_filterwise_concatenation():
     """conv(h, W) + conv_p(x, Wp) = conv([h ; x], [W | Wp]) (Sec. IV-B-1): exact copies of
-    both weight sets with zeros between them up to a multiple of 32 channels, biases added;
+    both weight sets with zeros between them up to a multiple of 64 channels, biases added;
     the oracle's two convolutions and addition equal its one convolution of the concatenation."""
     rng = np.random.default_rng(12)
-    k, c1, c2 = 20, 38, 24
+    k, c1, c2 = 20, 20, 24
+    assert B.CAT_ALIGN == 64
     W = rng.standard_normal((k, c1, 1, 1)).astype(np.float32)
     Wp = rng.standard_normal((k, c2, 1, 1)).astype(np.float32)
     b, bp = rng.standard_normal(k).astype(np.float32), rng.standard_normal(k).astype(np.float32)
@@ -697,7 +698,7 @@ def test_proj_concat_is_the_filterwise_concatenation():
 
 
 def test_model_accepts_a_two_input_convolution():
-    def ops(in2=1, stride=2, c=32 + 16, epi=B.FUSE_RELU | B.FUSE_CAT):
+    def ops(in2=1, stride=2, c=64 + 16, epi=B.FUSE_RELU | B.FUSE_CAT):
         o = fake_ops([
             (B.OP_CONV, 0, -1, 16, 3, 3, 1, 1, B.FUSE_RELU, 1),      # t1 16 x 32 x 32
             (B.OP_CONV, 1, -1, 12, 16, 3, 2, 1, B.FUSE_RELU, 1),     # t2 12 x 16 x 16
@@ -710,11 +711,11 @@ def test_model_accepts_a_two_input_convolution():
     assert s["flops"] == 2.0 * (12 + 16) * 40 * 2 * 256 and s["C"] == 28
     # t1 stays alive until the last operator: three buffers... t1 and t2 only (t3 is the output)
     assert m.workspace_bytes(1) == (32 * 32 * 16 + 16 * 16 * 16) * 2
-    expect(B.ERR_SHAPE, lambda: B.Model(B.BF16, (3, 32, 32), ops(c=12 + 16), None))   # split not at 32
+    expect(B.ERR_SHAPE, lambda: B.Model(B.BF16, (3, 32, 32), ops(c=32 + 16), None))   # split not at 64
     expect(B.ERR_ARG, lambda: B.Model(B.BF16, (3, 32, 32), ops(in2=3), None))
     expect(B.ERR_ARG, lambda: B.Model(B.BF16, (3, 32, 32), ops(stride=3), None))
-    B.Model(B.BF16, (3, 32, 32), ops(in2=0, c=32 + 3, stride=1), None)      # any earlier tensor large enough
-    expect(B.ERR_SHAPE, lambda: B.Model(B.BF16, (3, 32, 32), ops(in2=2, c=32 + 12, stride=2), None))  # too small
+    B.Model(B.BF16, (3, 32, 32), ops(in2=0, c=64 + 3, stride=1), None)      # any earlier tensor large enough
+    expect(B.ERR_SHAPE, lambda: B.Model(B.BF16, (3, 32, 32), ops(in2=2, c=64 + 12, stride=2), None))  # too small
     expect(B.ERR_DTYPE, lambda: B.Model(B.F32, (3, 32, 32), ops(), None))
 
 
