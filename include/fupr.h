@@ -583,8 +583,8 @@ void fupr_graph_destroy(fupr_graph* g);
  *   conv_tile = <tile name>                       force a tile of the general kernel
  *   conv_patch, conv1x1_stream, conv1x1_pipe, conv1x1_fuse, block_fuse = 0
  *                                                 leave that kernel family out
- *   pipe_order = 0                                tiles of the pipelined 1 x 1 kernel as one contiguous
- *                                                 range per workgroup, not consecutive tiles per XCD
+ *   pipe_order = 0 | 1                            tiles of the pipelined 1 x 1 kernel as one contiguous
+ *                                                 range per workgroup | consecutive tiles per XCD
  *   split = 1..4                                  sub-batches of the per-operator schedule
  *   res_item = "M/FT/nsteps:MTxNT,..."            work-item shapes of the one-kernel schedule
  *   debug = 1                                     planner decisions and HIP error text on stderr

@@ -24,7 +24,7 @@ struct Switch {
 Switch g_switches[] = {
     {"patch_tile", false, {0}},      // index of the 3 x 3 patch kernel's tile
     {"pipe_tile", false, {0}},       // index of the pipelined 1 x 1 kernel's tile
-    {"pipe_order", false, {0}},      // 0: each workgroup of that kernel takes a contiguous range of tiles
+    {"pipe_order", false, {0}},      // that kernel's tiles: 0 a contiguous range per workgroup, 1 per XCD
     {"stream_tile", false, {0}},     // index of the streaming 1 x 1 kernel's tile
     {"conv_tile", false, {0}},       // name of the general kernel's tile
     {"conv_patch", false, {0}},      // 0: 3 x 3 layers skip the patch kernel

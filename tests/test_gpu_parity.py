@@ -242,6 +242,23 @@ def test_every_pipelined_1x1_tile_forced(fx, tile):
         B.fupr_tuning_set("conv1x1_stream", None)
 
 
+@pytest.mark.parametrize("order", [0, 1])
+def test_pipelined_1x1_tile_orders(fx, order):
+    """Both ways of handing tiles to workgroups (a contiguous range each; consecutive tiles
+    per XCD), on layers with one and with several groups of filters."""
+    B, network, torch = fx
+    B.fupr_tuning_set("pipe_order", order)
+    B.fupr_tuning_set("conv1x1_stream", 0)
+    try:
+        for case in (FORCED_1X1[0], FORCED_1X1[1], FORCED_1X1[2]):
+            assert kernel_of(B, "bf16", case).startswith("conv1x1")
+            conv_site(fx, case, "bf16")
+        test_conv_cat_site(fx, CAT_CASES[3], "f16")
+    finally:
+        B.fupr_tuning_set("pipe_order", None)
+        B.fupr_tuning_set("conv1x1_stream", None)
+
+
 @pytest.mark.parametrize("tile", range(6), ids=STREAM_TILES)
 def test_every_streaming_1x1_tile_forced(fx, tile):
     B, network, torch = fx
