@@ -427,7 +427,7 @@ fupr_status launch_stream(const StreamParams& p, dim3 grid, size_t lds, hipStrea
     status = hipFuncSetAttribute(
         reinterpret_cast<const void*>(&conv1x1_stream_kernel<BF, NT, KMAX, NT2, THREADS>),
         hipFuncAttributeMaxDynamicSharedMemorySize,
-        THREADS == 256 ? kStreamFusedLdsLimit : 2 * kStreamFusedLdsLimit);
+        THREADS == 256 && NT2 <= 4 ? kStreamFusedLdsLimit : 2 * kStreamFusedLdsLimit);
   });
   if (status != hipSuccess) return FUPR_ERR_LAUNCH;
   hipLaunchKernelGGL((conv1x1_stream_kernel<BF, NT, KMAX, NT2, THREADS>), grid, dim3(THREADS), lds, st, p);
@@ -492,13 +492,18 @@ bool plan_fused(const Conv16Params& c1, const Conv16Params& c2, int* kmax, int* 
   const int t = pick_stream(c1);
   if (t < 0 || kStreamTiles[t].NT != 16 || c1.FT > 16 || c1.stride != 1) return false;
   if (c2.S != 1 || c2.nchunk != c2.cpt || c2.pad != 0 || c2.stride != 1 || c2.res) return false;
-  if (c2.cpt * 8 != c1.ycs || c2.cpt > 32 || c2.FT > 4) return false;   // reads all of y's channels
+  if (c2.cpt * 8 != c1.ycs || c2.cpt > 32 || c2.FT > 8) return false;   // reads all of y's channels
+  if (c2.FT * 16 > tuning_int("pair_filters", 128)) return false;
   if (c2.H != c1.P || c2.W != c1.Q) return false;
   *kmax = kStreamTiles[t].KMAX;
-  *nt2 = c2.FT <= 2 ? 2 : 4;
+  *nt2 = 2 * ((std::max(c2.FT, 1) + 1) / 2);
   const int ksteps = (c1.cpt + 3) / 4;
   *lds = stream_lds_bytes(kStreamTiles[t], ksteps) + (size_t)*nt2 * 16 * 4 +
          (size_t)8 * 4 * *nt2 * 16 * 16;
+  // 65 - 128 second filters: four waves, one workgroup per compute unit (the
+  // sixteen-tile variants take more than half of a SIMD's registers per wave
+  // anyway), all of LDS
+  if (*nt2 > 4) return *lds <= 2 * (size_t)kStreamFusedLdsLimit;
   // (the eight-wave variant has no shortcut in its epilogue)
   return *lds <= (size_t)kStreamFusedLdsLimit ||
          (*kmax == 4 && !c1.res && *lds <= 2 * (size_t)kStreamFusedLdsLimit);
@@ -544,9 +549,10 @@ fupr_status launch_conv1x1_fused_pair(const Conv16Params& c1, const Conv16Params
   p.w_lds_bytes = (int)round_up_sz((size_t)p.ksteps * 4 * 16 * 16 * 16, 1024);
   // eight waves share the filters and keep two tiles in flight each: needed when the filters
   // fit LDS once only, and faster whenever there is no shortcut to read (few bytes per pixel)
-  const bool wide = lds > (size_t)kStreamFusedLdsLimit || (kmax == 4 && !c1.res);
+  const bool wide = nt2 <= 4 && (lds > (size_t)kStreamFusedLdsLimit || (kmax == 4 && !c1.res));
   const int gx = wide ? std::min((p.n_tiles + 7) / 8, stream_compute_units())
-                      : std::min((p.n_tiles + 3) / 4, 2 * stream_compute_units());
+                      : std::min((p.n_tiles + 3) / 4,
+                                 (lds > (size_t)kStreamFusedLdsLimit ? 1 : 2) * stream_compute_units());
   const dim3 grid((unsigned)gx, 1u);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   const int key = (bf16 ? 100 : 0) + kmax * 10 + nt2 + (wide ? 1000 : 0);
@@ -555,6 +561,14 @@ fupr_status launch_conv1x1_fused_pair(const Conv16Params& c1, const Conv16Params
     case 124: return launch_stream<true, 16, 2, 4>(p, grid, lds, st);
     case 142: return launch_stream<true, 16, 4, 2>(p, grid, lds, st);
     case 144: return launch_stream<true, 16, 4, 4>(p, grid, lds, st);
+    case 126: return launch_stream<true, 16, 2, 6>(p, grid, lds, st);
+    case 128: return launch_stream<true, 16, 2, 8>(p, grid, lds, st);
+    case 146: return launch_stream<true, 16, 4, 6>(p, grid, lds, st);
+    case 148: return launch_stream<true, 16, 4, 8>(p, grid, lds, st);
+    case 26: return launch_stream<false, 16, 2, 6>(p, grid, lds, st);
+    case 28: return launch_stream<false, 16, 2, 8>(p, grid, lds, st);
+    case 46: return launch_stream<false, 16, 4, 6>(p, grid, lds, st);
+    case 48: return launch_stream<false, 16, 4, 8>(p, grid, lds, st);
     case 22: return launch_stream<false, 16, 2, 2>(p, grid, lds, st);
     case 24: return launch_stream<false, 16, 2, 4>(p, grid, lds, st);
     case 42: return launch_stream<false, 16, 4, 2>(p, grid, lds, st);

@@ -467,8 +467,10 @@ def test_stem_maxpool_fused(fx, size, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
-@pytest.mark.parametrize("case", [(32, 256, 32, True), (64, 200, 64, True), (58, 256, 45, False)],
-                         ids=["32-256-32+res", "64-200-64+res", "58-256-45"])
+@pytest.mark.parametrize("case", [(32, 256, 32, True), (64, 200, 64, True), (58, 256, 45, False),
+                                  (45, 256, 90, True), (100, 240, 128, True), (64, 256, 70, False)],
+                         ids=["32-256-32+res", "64-200-64+res", "58-256-45", "45-256-90+res",
+                              "100-240-128+res", "64-256-70"])
 def test_two_1x1_convolutions_in_one_kernel(fx, case, dtype):
     """A block's last 1 x 1 convolution and the next block's first one as one
     launch: both outputs against the oracle (the second from the first one's
