@@ -412,8 +412,9 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv1x1_pipe_ke
   }
 }
 
-// The same pipeline on the 32 x 32 x 16 MFMA, which sustains the matrix cores' full
-// rate on gfx950 where 16 x 16 x 32 sustains 57 % of it: WM x WN computing waves, each
+// The same pipeline on the 32 x 32 x 16 MFMA (half as many MFMA instructions and
+// accumulator reads per flop), with eight computing waves in the tiles that are
+// selected: WM x WN computing waves, each
 // owning MT pixel tiles x NT filter tiles of 32 x 32 (16 accumulator registers each).
 // LDS layout and loading waves are shared with conv1x1_pipe_kernel.  A step is 16
 // channels here: lane (index j = lane % 32, half h = lane / 32) reads chunk 2 * step + h

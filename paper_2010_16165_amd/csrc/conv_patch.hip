@@ -651,8 +651,8 @@ __global__ __launch_bounds__((WM * WN + kLoaderWaves) * 64) void conv_patch_kern
   }
 }
 
-// The same kernel on the 32 x 32 x 16 MFMA, which sustains the matrix cores' full rate
-// on gfx950 where 16 x 16 x 32 sustains 57 % of it: WM x WN computing waves, each owning
+// The same kernel on the 32 x 32 x 16 MFMA (half as many MFMA instructions per flop;
+// parity-tested, selected only when forced): WM x WN computing waves, each owning
 // MT pixel tiles x NT filter tiles of 32 x 32 (16 accumulator registers each).  LDS
 // layout, loading waves and pipeline are those of conv_patch_kernel; what differs
 // is how a computing wave's lanes address the operands and the results:

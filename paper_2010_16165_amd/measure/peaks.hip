@@ -15,54 +15,64 @@ typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-constexpr int kChains = 8;   // independent accumulators per wave
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// Independent accumulators per wave: 16 of 16 x 16 (64 registers), 8 of 32 x 32 (128).
+constexpr int kChains16 = 16, kChains32 = 8;
+
+// The instruction stream is written out, so that it is the one measured: chain c
+// multiplies operand registers a[c % 4] and b[c / 4 % 4] (a kernel's MFMAs take
+// their operands from different registers; a stream that names the same two
+// registers in every MFMA was measured at 57 % of this one's rate for 16 x 16 x 32).
 template <bool BF, bool WIDE>
 __global__ __launch_bounds__(256) void mfma_rate_kernel(int iters, float* out) {
   const int lane = threadIdx.x & 63;
   // operands that no compiler can fold: they depend on the lane
   const uint32_t bits = BF ? 0x3f803f80u : 0x3c003c00u;   // two ones
-  const uint4 a = {bits, bits ^ (uint32_t)(lane & 1), bits, bits};
-  const uint4 b = {bits, bits, bits ^ (uint32_t)(lane & 2), bits};
+  u32x4 a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    a[i] = u32x4{bits, bits ^ (uint32_t)(lane & 1), bits, bits ^ (uint32_t)(i << 16)};
+    b[i] = u32x4{bits, bits, bits ^ (uint32_t)(lane & 2), bits ^ (uint32_t)i};
+  }
   float s = 0.f;
   if constexpr (WIDE) {
-    f32x16 acc[kChains];
+    f32x16 acc[kChains32];
 #pragma unroll
-    for (int c = 0; c < kChains; ++c)
+    for (int c = 0; c < kChains32; ++c)
 #pragma unroll
       for (int j = 0; j < 16; ++j) acc[c][j] = 0.f;
     for (int i = 0; i < iters; ++i) {
 #pragma unroll
-      for (int c = 0; c < kChains; ++c) {
+      for (int c = 0; c < kChains32; ++c) {
         if constexpr (BF)
-          acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
-                                                           __builtin_bit_cast(bf16x8, b), acc[c], 0, 0, 0);
+          asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc[c]) : "v"(a[c & 3]), "v"(b[(c >> 2) & 3]));
         else
-          acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
-                                                          __builtin_bit_cast(f16x8, b), acc[c], 0, 0, 0);
+          asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(acc[c]) : "v"(a[c & 3]), "v"(b[(c >> 2) & 3]));
       }
     }
+    // the results are read by ordinary instructions: let the last MFMAs finish first
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
 #pragma unroll
-    for (int c = 0; c < kChains; ++c)
+    for (int c = 0; c < kChains32; ++c)
 #pragma unroll
       for (int j = 0; j < 16; ++j) s += acc[c][j];
   } else {
-    f32x4 acc[kChains];
+    f32x4 acc[kChains16];
 #pragma unroll
-    for (int c = 0; c < kChains; ++c) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < kChains16; ++c) acc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
     for (int i = 0; i < iters; ++i) {
 #pragma unroll
-      for (int c = 0; c < kChains; ++c) {
+      for (int c = 0; c < kChains16; ++c) {
         if constexpr (BF)
-          acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
-                                                           __builtin_bit_cast(bf16x8, b), acc[c], 0, 0, 0);
+          asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc[c]) : "v"(a[c & 3]), "v"(b[(c >> 2) & 3]));
         else
-          acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a),
-                                                          __builtin_bit_cast(f16x8, b), acc[c], 0, 0, 0);
+          asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+v"(acc[c]) : "v"(a[c & 3]), "v"(b[(c >> 2) & 3]));
       }
     }
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
 #pragma unroll
-    for (int c = 0; c < kChains; ++c) s += acc[c][0] + acc[c][1] + acc[c][2] + acc[c][3];
+    for (int c = 0; c < kChains16; ++c) s += acc[c][0] + acc[c][1] + acc[c][2] + acc[c][3];
   }
   out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
@@ -88,8 +98,8 @@ extern "C" int32_t fupr_measure_mfma(int32_t dt, int32_t shape, int32_t iters, i
   else if (dt == 1) hipLaunchKernelGGL((mfma_rate_kernel<true, true>), grid, block, 0, st, iters, o);
   else if (shape == 16) hipLaunchKernelGGL((mfma_rate_kernel<false, false>), grid, block, 0, st, iters, o);
   else hipLaunchKernelGGL((mfma_rate_kernel<false, true>), grid, block, 0, st, iters, o);
-  // 4 waves per workgroup, kChains MFMAs per iteration of 2 * 16 * 16 * 32 or 2 * 32 * 32 * 16 flops
-  *flops = (double)workgroups * 4.0 * iters * kChains * (shape == 16 ? 16384.0 : 32768.0);
+  // 4 waves per workgroup; per iteration 16 MFMAs of 2 * 16 * 16 * 32 flops or 8 of 2 * 32 * 32 * 16
+  *flops = (double)workgroups * 4.0 * iters * (shape == 16 ? kChains16 * 16384.0 : kChains32 * 32768.0);
   return launched();
 }
 

@@ -1464,10 +1464,10 @@ def test_measuring_kernels(fx):
         M.fupr_measure_copy(src, dst, 24)
     out = torch.zeros(4 * 256, dtype=torch.float32, device="cuda")
     for dt in (B.BF16, B.F16):
-        for shape, per_mfma in ((16, 2 * 16 * 16 * 32), (32, 2 * 32 * 32 * 16)):
+        for shape, chains, per_mfma in ((16, 16, 2 * 16 * 16 * 32), (32, 8, 2 * 32 * 32 * 16)):
             flops = M.fupr_measure_mfma(dt, shape, 3, 4, out)
             torch.cuda.synchronize()
-            assert flops == 4 * 4 * 3 * 8 * per_mfma
+            assert flops == 4 * 4 * 3 * chains * per_mfma   # workgroups, waves, iterations, chains
             assert torch.isfinite(out).all() and float(out.abs().max()) > 0
     with pytest.raises(RuntimeError):
         M.fupr_measure_mfma(B.F32, 16, 3, 4, out)
