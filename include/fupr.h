@@ -585,6 +585,8 @@ void fupr_graph_destroy(fupr_graph* g);
  *                                                 leave that kernel family out
  *   pipe_order = 0 | 1                            tiles of the pipelined 1 x 1 kernel as one contiguous
  *                                                 range per workgroup | consecutive tiles per XCD
+ *   stream_blocks = 1 | 2                         the streaming 1 x 1 kernel built for one or two
+ *                                                 workgroups per compute unit
  *   pair_filters = 16..128                        most filters of the second convolution of a pair of
  *                                                 1 x 1 convolutions in one launch
  *   split = 1..4                                  sub-batches of the per-operator schedule

@@ -86,8 +86,8 @@ __device__ __forceinline__ uint32_t clamp_below2(uint32_t v, uint32_t floor2) {
 // THREADS: 256, two workgroups to a compute unit; or 512, one workgroup whose
 // eight waves share one copy of the filters, for the pairs whose two filter sets
 // do not fit LDS twice.
-template <bool BF, int NT, int KMAX, int NT2, int THREADS = 256>
-__global__ __launch_bounds__(THREADS) void conv1x1_stream_kernel(const StreamParams p) {
+template <bool BF, int NT, int KMAX, int NT2, int THREADS = 256, int MINB = 1>
+__global__ __launch_bounds__(THREADS, MINB) void conv1x1_stream_kernel(const StreamParams p) {
   constexpr int kWaves = THREADS / 64;
   constexpr int NF = NT * 16;
   constexpr int NF2 = NT2 * 16;
@@ -419,24 +419,39 @@ int pick_stream(const Conv16Params& c) {
   return best;
 }
 
-template <bool BF, int NT, int KMAX, int NT2 = 0, int THREADS = 256>
+template <bool BF, int NT, int KMAX, int NT2 = 0, int THREADS = 256, int MINB = 1>
 fupr_status launch_stream(const StreamParams& p, dim3 grid, size_t lds, hipStream_t st) {
   static std::once_flag once;
   static hipError_t status = hipSuccess;
   std::call_once(once, [] {
     status = hipFuncSetAttribute(
-        reinterpret_cast<const void*>(&conv1x1_stream_kernel<BF, NT, KMAX, NT2, THREADS>),
+        reinterpret_cast<const void*>(&conv1x1_stream_kernel<BF, NT, KMAX, NT2, THREADS, MINB>),
         hipFuncAttributeMaxDynamicSharedMemorySize,
         THREADS == 256 && NT2 <= 4 ? kStreamFusedLdsLimit : 2 * kStreamFusedLdsLimit);
   });
   if (status != hipSuccess) return FUPR_ERR_LAUNCH;
-  hipLaunchKernelGGL((conv1x1_stream_kernel<BF, NT, KMAX, NT2, THREADS>), grid, dim3(THREADS), lds, st, p);
+  hipLaunchKernelGGL((conv1x1_stream_kernel<BF, NT, KMAX, NT2, THREADS, MINB>), grid, dim3(THREADS), lds, st, p);
   return launch_status("conv1x1_stream_kernel");
 }
 
 template <bool BF>
 fupr_status dispatch_stream(int tile, const StreamParams& p, dim3 grid, size_t lds,
                             hipStream_t st) {
+  // Compiled for two workgroups per compute unit (at most 256 registers): the MFMAs keep
+  // their accumulators in ordinary registers, without the copies to and from the
+  // accumulation registers that the one-workgroup build spends per tile, and eight waves
+  // keep loads in flight (config 4: 2800 -> 2736 us; the pairs of convolutions, which
+  // would spill, stay as they are: 2807 -> 2988 us when forced).
+  if (tuning_int("stream_blocks", 2) >= 2) {
+    switch (tile) {
+      case 0: return launch_stream<BF, 16, 2, 0, 256, 2>(p, grid, lds, st);
+      case 1: return launch_stream<BF, 16, 4, 0, 256, 2>(p, grid, lds, st);
+      case 2: return launch_stream<BF, 8, 8, 0, 256, 2>(p, grid, lds, st);
+      case 3: return launch_stream<BF, 4, 8, 0, 256, 2>(p, grid, lds, st);
+      case 4: return launch_stream<BF, 4, 16, 0, 256, 2>(p, grid, lds, st);
+      default: return launch_stream<BF, 2, 8, 0, 256, 2>(p, grid, lds, st);
+    }
+  }
   switch (tile) {
     case 0: return launch_stream<BF, 16, 2>(p, grid, lds, st);
     case 1: return launch_stream<BF, 16, 4>(p, grid, lds, st);

@@ -26,6 +26,7 @@ Switch g_switches[] = {
     {"pipe_tile", false, {0}},       // index of the pipelined 1 x 1 kernel's tile
     {"pipe_order", false, {0}},      // that kernel's tiles: 0 a contiguous range per workgroup, 1 per XCD
     {"stream_tile", false, {0}},     // index of the streaming 1 x 1 kernel's tile
+    {"stream_blocks", false, {0}},   // workgroups per compute unit that kernel is compiled for (1, 2)
     {"conv_tile", false, {0}},       // name of the general kernel's tile
     {"conv_patch", false, {0}},      // 0: 3 x 3 layers skip the patch kernel
     {"conv1x1_stream", false, {0}},  // 0: 1 x 1 layers skip the streaming kernel
