@@ -183,6 +183,9 @@ __global__ __launch_bounds__(THREADS, MINB) void conv1x1_stream_kernel(const Str
   // system short of requests: 2.7 TB/s measured).  It has no shortcut (its launcher refuses
   // one): the registers that would hold shortcut values hold the second tile.
   constexpr bool kDeep = THREADS == 512;
+  // A pair built for two workgroups per compute unit has no registers for the next tile's
+  // shortcut: it asks for a tile's shortcut when it starts the tile (eight waves hide the wait).
+  constexpr bool kLateRes = MINB == 2 && NT2 > 0 && !kDeep;
   const bool has_res = !kDeep && p.res != nullptr;
   uint4 bn2[kDeep ? KMAX : 1] = {};
   uint32_t yoff_n2 = kOutside, hoff_n2 = kOutside;
@@ -237,7 +240,7 @@ __global__ __launch_bounds__(THREADS, MINB) void conv1x1_stream_kernel(const Str
   uint32_t ro_n = kOutside, ro_n2 = kOutside;
   if (tile < p.n_tiles) {   // in flight while the filters arrive
     fetch_pixels(tile, bn, yoff_n, hoff_n, ro_n);
-    fetch_shortcut(ro_n);
+    if constexpr (!kLateRes) fetch_shortcut(ro_n);
     if constexpr (kDeep)
       if (tile + n_waves < p.n_tiles) fetch_pixels(tile + n_waves, bn2, yoff_n2, hoff_n2, ro_n2);
   }
@@ -254,6 +257,9 @@ __global__ __launch_bounds__(THREADS, MINB) void conv1x1_stream_kernel(const Str
     u32x4 rv[NP];
 #pragma unroll
     for (int k = 0; k < KMAX; ++k) b[k] = cur[k];
+    if constexpr (kLateRes) {
+      fetch_shortcut(ro_cur);
+    }
 #pragma unroll
     for (int pr = 0; pr < NP; ++pr) rv[pr] = rvn[pr];
     const uint32_t yoff = yo_cur, hoff = ho_cur;
@@ -263,7 +269,7 @@ __global__ __launch_bounds__(THREADS, MINB) void conv1x1_stream_kernel(const Str
     } else {
       if (tile + n_waves < p.n_tiles) {
         fetch_pixels(tile + n_waves, cur, yo_cur, ho_cur, ro_cur);
-        fetch_shortcut(ro_cur);
+        if constexpr (!kLateRes) fetch_shortcut(ro_cur);
       }
     }
 
@@ -440,8 +446,7 @@ fupr_status dispatch_stream(int tile, const StreamParams& p, dim3 grid, size_t l
   // Compiled for two workgroups per compute unit (at most 256 registers): the MFMAs keep
   // their accumulators in ordinary registers, without the copies to and from the
   // accumulation registers that the one-workgroup build spends per tile, and eight waves
-  // keep loads in flight (config 4: 2800 -> 2736 us; the pairs of convolutions, which
-  // would spill, stay as they are: 2807 -> 2988 us when forced).
+  // keep loads in flight (config 4: 2800 -> 2736 us).
   if (tuning_int("stream_blocks", 2) >= 2) {
     switch (tile) {
       case 0: return launch_stream<BF, 16, 2, 0, 256, 2>(p, grid, lds, st);
@@ -571,6 +576,21 @@ fupr_status launch_conv1x1_fused_pair(const Conv16Params& c1, const Conv16Params
   const dim3 grid((unsigned)gx, 1u);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   const int key = (bf16 ? 100 : 0) + kmax * 10 + nt2 + (wide ? 1000 : 0);
+  // The pairs with up to 64 second filters whose filters fit LDS twice are built for two
+  // workgroups per compute unit as well (config 3: 884 -> 864 us; config 4 unchanged).
+  if (!wide && tuning_int("stream_blocks", 2) >= 2 && lds <= (size_t)kStreamFusedLdsLimit) {
+    switch (key) {
+      case 122: return launch_stream<true, 16, 2, 2, 256, 2>(p, grid, lds, st);
+      case 124: return launch_stream<true, 16, 2, 4, 256, 2>(p, grid, lds, st);
+      case 142: return launch_stream<true, 16, 4, 2, 256, 2>(p, grid, lds, st);
+      case 144: return launch_stream<true, 16, 4, 4, 256, 2>(p, grid, lds, st);
+      case 22: return launch_stream<false, 16, 2, 2, 256, 2>(p, grid, lds, st);
+      case 24: return launch_stream<false, 16, 2, 4, 256, 2>(p, grid, lds, st);
+      case 42: return launch_stream<false, 16, 4, 2, 256, 2>(p, grid, lds, st);
+      case 44: return launch_stream<false, 16, 4, 4, 256, 2>(p, grid, lds, st);
+      default: break;
+    }
+  }
   switch (key) {
     case 122: return launch_stream<true, 16, 2, 2>(p, grid, lds, st);
     case 124: return launch_stream<true, 16, 2, 4>(p, grid, lds, st);
