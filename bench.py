@@ -60,6 +60,10 @@ def group_of_device_kernel(name):
     num = lambda i: int(args[i])
     if fn == "conv1x1_pipe_kernel":
         return f"conv1x1p_{num(1) * num(3) * 16}x{num(2) * num(4) * 16}"
+    if fn == "conv1x1_pipe32_kernel":
+        return f"conv1x1q_{num(1) * num(3) * 32}x{num(2) * num(4) * 32}"
+    if fn == "conv_patch32_kernel":
+        return None   # (selected only when forced)
     if fn == "conv_patch_kernel":
         wide = "w" if (num(1), num(2), num(3), num(4)) == (4, 1, 2, 4) else ""
         return f"conv3x3p_{num(1) * num(3) * 16}x{num(2) * num(4) * 16}{wide}"
