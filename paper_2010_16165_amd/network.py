@@ -2,8 +2,13 @@
 model + fusion options + pruning rates -> optimised model).
 
 Orchestration only: every number is produced by the library calls
-(fupr_select_filters, fupr_fold, fupr_prune, fupr_pack); this module decides
-which call sees which layer and lays the packed blobs out in one buffer.
+(fupr_select_filters, fupr_fold, fupr_prune, fupr_xconv_fuse, fupr_proj_concat,
+fupr_pack); this module decides which call sees which layer, wires the blocks
+(which tensor is a shortcut, where a projection sits), lays the packed blobs
+out in one buffer, and in one place moves numbers without computing any: the
+removed output filters of a 1 x 1 last convolution go back in as zero rows
+(exact copies of the kept rows, zeros elsewhere).  A C caller of
+fupr_model_create does the same wiring itself from the operator descriptions.
 The model description is the plain-data format of synth.resnets.
 """
 from __future__ import annotations
