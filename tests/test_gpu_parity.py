@@ -998,7 +998,7 @@ def test_baseline_config_full_batch(fx, idx):
     (HIP-graph replay on a side stream).  Configurations 0 - 3: the oracle computes
     EVERY image of the batch (tiles run across image boundaries and persistent
     workgroups walk ranges of tiles, so no image may go unchecked).  Configuration 4
-    (256 images of the largest network): the oracle computes four images here, and
+    (256 images of the largest network): the oracle computes about fifteen images here, and
     test_config4_layer_shapes_at_full_batch covers every layer at the full batch."""
     B, network, torch = fx
     model, batch = synth.make_config(idx)
@@ -1022,7 +1022,12 @@ def test_baseline_config_full_batch(fx, idx):
         y = y[:, :, 0, 0]
     assert np.isfinite(y).all()
     masks = orc.select_masks(model)
-    sample = list(range(batch)) if idx < 4 else sorted({0, 1, batch // 2, batch - 1})
+    # (configuration 4: the first and last images, both sides of the boundary between the two
+    # sub-batches and of each quarter, and a seeded handful in between)
+    extra = [int(v) for v in np.random.default_rng(seed).integers(0, batch, 4)]
+    sample = list(range(batch)) if idx < 4 else sorted(
+        {0, 1, batch // 4 - 1, batch // 4, batch // 2 - 1, batch // 2, batch // 2 + 1, 3 * batch // 4 - 1,
+         3 * batch // 4, batch - 2, batch - 1, *extra})
     print(f"config {idx}: batch {batch}, oracle on {len(sample)} images", flush=True)
     xr = round_to(x[sample], dtype, torch)
     worst = 0.0
