@@ -75,8 +75,6 @@ def group_of_device_kernel(name):
                     (num(1), num(2)))
     if fn == "conv16_tiled_kernel":
         return f"conv16t_{num(1) * 64}x{num(2) * 16}"
-    if fn == "block_kernel":
-        return "bottleneck_block"
     return {"stem_pool_kernel": "stem7x7_maxpool", "resident_kernel": "resident_network",
             "maxpool_kernel": "maxpool", "avgpool_kernel": "global_avgpool",
             "conv32_kernel": "conv32_direct"}.get(fn)

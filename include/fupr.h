@@ -578,10 +578,10 @@ void fupr_graph_destroy(fupr_graph* g);
  * Each starts from the environment variable FUPR_<NAME IN CAPITALS>, read once
  * when the first switch is looked up, and changes only through this call; value
  * NULL or "" returns a switch to automatic.  Launchers read them at every launch.
- *   patch_tile, pipe_tile, stream_tile, block_tile = <index>
+ *   patch_tile, pipe_tile, stream_tile = <index>
  *                                                 force a tile of that kernel family (where it fits)
  *   conv_tile = <tile name>                       force a tile of the general kernel
- *   conv_patch, conv1x1_stream, conv1x1_pipe, conv1x1_fuse, block_fuse = 0
+ *   conv_patch, conv1x1_stream, conv1x1_pipe, conv1x1_fuse = 0
  *                                                 leave that kernel family out
  *   pipe_order = 0 | 1                            tiles of the pipelined 1 x 1 kernel as one contiguous
  *                                                 range per workgroup | consecutive tiles per XCD

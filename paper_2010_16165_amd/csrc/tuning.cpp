@@ -33,8 +33,6 @@ Switch g_switches[] = {
     {"conv1x1_pipe", false, {0}},    // 0: 1 x 1 layers skip the pipelined kernel
     {"conv1x1_fuse", false, {0}},    // 0: no pairs of 1 x 1 convolutions in one launch
     {"pair_filters", false, {0}},    // most filters of such a pair's second convolution (up to 128)
-    {"block_fuse", false, {0}},      // 0: no bottleneck-block launches
-    {"block_tile", false, {0}},      // index of the bottleneck-block kernel's tile
     {"split", false, {0}},           // sub-batches of the per-operator schedule
     {"res_item", false, {0}},        // work-item shapes of the one-kernel schedule
     {"debug", false, {0}},           // non-empty: planner and HIP error text on stderr

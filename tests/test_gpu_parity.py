@@ -217,6 +217,9 @@ FORCED_1X1 = [
     ("forced 1x1 C45 K256 +id 20x20 x6 norelu", 6, 45, 20, 20, 256, 1, 1, 0, "identity", False),
     ("forced 1x1 C64 K41 28x28 x5", 5, 64, 28, 28, 41, 1, 1, 0, None, True),
     ("forced 1x1 C256 K90 s2 12x12 x7", 7, 256, 12, 12, 90, 1, 2, 0, None, True),
+    ("forced 1x1 C260 K257 +id 9x9 x9", 9, 260, 9, 9, 257, 1, 1, 0, "identity", True),   # one filter past a group of 256
+    ("forced 1x1 C2048 K40 1x1 x3", 3, 2048, 1, 1, 40, 1, 1, 0, None, False),            # three pixels in all
+    ("forced 1x1 C264 K136 s2 15x13 x3 +optionA", 3, 264, 15, 13, 136, 1, 2, 0, "optionA", True),
 ]
 
 
