@@ -92,13 +92,13 @@ def counter_rows(directory, counter):
 
 TRAFFIC_HEADER = """\
 # HBM bytes per launch of every kernel group, per configuration N, from two counter runs
-# (on the GPU box, from the repository root, after cd /tmp && export TMPDIR=/tmp && cd back):
-#   rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d gpurun_out/pmc_fetch_cN -o r -- \\
+# (from the repository root, with TMPDIR=/tmp; OUT is any directory for the profiler's output):
+#   rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d OUT/pmc_fetch_cN -o r -- \\
 #       python3 bench.py --config N --steps 3 --warmup 1 --split 1 --only-headline \\
 #       --no-cpu-baseline --no-measured-peaks --copy-calibration 1024
-#   rocprofv3 --pmc WRITE_SIZE ... -d gpurun_out/pmc_write_cN ... (the same command)
+#   rocprofv3 --pmc WRITE_SIZE ... -d OUT/pmc_write_cN ... (the same command)
 # folded into this file by
-#   python3 bench.py --record-traffic gpurun_out/pmc_fetch_cN gpurun_out/pmc_write_cN --config N
+#   python3 bench.py --record-traffic OUT/pmc_fetch_cN OUT/pmc_write_cN --config N
 # fetch_bytes / write_bytes: mean counter value per dispatch (KiB) x 1024 x the factor that makes the
 # same counter read 1 GiB for the 1 GiB device copy of that run.  sources: hash of the kernel sources.
 """
