@@ -72,6 +72,13 @@ def test_tuning_switches():
     B.fupr_tuning_set("patch_tile", None)
     B.fupr_tuning_set("conv_tile", "conv16t_64x16")
     B.fupr_tuning_set("conv_tile", "")
+    for name in ("pipe_tile", "pipe_order", "stream_tile", "stream_blocks", "pair_filters", "split",
+                 "conv_patch", "conv1x1_stream", "conv1x1_pipe", "conv1x1_fuse", "res_item", "debug"):
+        B.fupr_tuning_set(name, 1)
+        B.fupr_tuning_set(name, None)
+    for gone in ("block_fuse", "block_tile"):      # switches of a kernel that was never built
+        with pytest.raises(B.FuprError):
+            B.fupr_tuning_set(gone, 1)
     with pytest.raises(B.FuprError) as e:
         B.fupr_tuning_set("no_such_switch", 1)
     assert e.value.status == B.ERR_ARG
