@@ -526,6 +526,24 @@ def test_baseline_config_graphs_have_expected_launch_counts():
         assert sum(L.cat_stride > 0 for L in plan["layers"]) == (4 if idx >= 3 else 0)
 
 
+def test_largest_workload_pairs_its_first_stage_output_with_the_next_convolution():
+    """The launch list of the largest workload: stem + pool, three pairs of 1 x 1 convolutions in
+    the first stage (the third with the 90-filter first convolution of the next stage), 48
+    launches for 52 operators; with pairs limited to 64 second filters it has one more."""
+    model, batch = synth.make_config(4)
+    plan = network.optimise(model)
+    m, _ = build_host_model(plan, 1 << 20)
+    assert (m.num_ops, m.num_launches) == (52, 48)
+    kernels = [m.launch_stats(batch, i)["kernel"] for i in range(m.num_launches)]
+    assert kernels.count("conv1x1s_256f+conv1x1") == 3 and kernels[0] == "stem7x7_maxpool"
+    B.fupr_tuning_set("pair_filters", 64)
+    try:
+        m2, _ = build_host_model(plan, 1 << 20)
+        assert m2.num_launches == 49
+    finally:
+        B.fupr_tuning_set("pair_filters", None)
+
+
 # ---- a block's pruned output filters (Alg. 1 on every non-fused operator, Sec. V-A) ---------
 
 def scatter_ops(keep=0x2000, **change):
